@@ -1,0 +1,421 @@
+"""Pins of the fp64 oracle against what the paper and the mathematics fix.
+
+The paper (arxiv 2406.13035) prints no worked numeric example of the method's state, so
+there are no paper values to store; the pins are closed forms, invariants stated in the
+text, reductions to library routines, and brute force on tiny inputs (tests/brute.py)."""
+import math
+from fractions import Fraction
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import d2o_ref as ref
+from tests import brute
+
+rng = np.random.default_rng(7)
+
+
+def _rand(n, d, seed):
+    g = np.random.default_rng(seed)
+    return g.standard_normal((n, d))
+
+
+# ------------------------------------------------------------------ attention (Eq. 3, Eq. 4)
+
+def test_attention_equals_library_sdpa():
+    q, k, v = _rand(97, 16, 1) * 2, _rand(97, 16, 2), _rand(97, 16, 3)
+    o, s = ref.prefill_attention_head(q, k, v, causal=True, row_block=32)
+    want = torch.nn.functional.scaled_dot_product_attention(
+        torch.from_numpy(q)[None], torch.from_numpy(k)[None], torch.from_numpy(v)[None],
+        is_causal=True)[0].numpy()
+    np.testing.assert_allclose(o, want, rtol=1e-12, atol=1e-13)
+    assert abs(s.sum() - 97) < 1e-10          # every row of A sums to 1
+
+
+def test_attention_row_block_invariance():
+    q, k, v = _rand(70, 8, 4), _rand(70, 8, 5), _rand(70, 8, 6)
+    o1, s1 = ref.prefill_attention_head(q, k, v, row_block=7)
+    o2, s2 = ref.prefill_attention_head(q, k, v, row_block=1000)
+    np.testing.assert_allclose(o1, o2, rtol=0, atol=1e-14)
+    np.testing.assert_allclose(s1, s2, rtol=0, atol=1e-13)
+
+
+def test_zero_query_causal_gives_harmonic_column_sums():
+    # Q = 0: A[i, j] = 1/(i+1) for j <= i, so s[j] = H_N - H_j (0-based j) exactly.
+    n = 40
+    k, v = _rand(n, 4, 8), _rand(n, 4, 9)
+    o, s = ref.prefill_attention_head(np.zeros((n, 4)), k, v)
+    H = [Fraction(0)]
+    for i in range(1, n + 1):
+        H.append(H[-1] + Fraction(1, i))
+    want = [H[n] - H[j] for j in range(n)]
+    np.testing.assert_allclose(s, [float(x) for x in want], rtol=1e-13)
+    mu = sum(want) / n
+    var = sum((x - mu) ** 2 for x in want) / n
+    assert abs(ref.head_variance(s) - float(var)) < 1e-13
+    # row i of O is the mean of v[0..i]
+    np.testing.assert_allclose(o[9], v[:10].mean(axis=0), rtol=1e-12)
+
+
+def test_zero_query_noncausal_is_uniform():
+    n = 33
+    o, s = ref.prefill_attention_head(np.zeros((n, 4)), _rand(n, 4, 1), _rand(n, 4, 2),
+                                      causal=False)
+    np.testing.assert_allclose(s, np.ones(n), rtol=1e-13)
+    assert ref.head_variance(s) < 1e-26
+    assert ref.layer_density([s, s]) < 1e-26
+
+
+def test_constant_values_give_constant_output():
+    v = np.tile(np.array([[1.5, -2.0, 0.25]]), (20, 1))
+    o, _ = ref.prefill_attention_head(_rand(20, 3, 3) * 3, _rand(20, 3, 4), v)
+    np.testing.assert_allclose(o, v, rtol=1e-13)
+
+
+def test_attention_matches_brute_force_matrix():
+    n, d = 24, 5
+    q, k, v = _rand(n, d, 10) * 2, _rand(n, d, 11), _rand(n, d, 12)
+    o, s = ref.prefill_attention_head(q, k, v, row_block=5)
+    A = brute.attention_matrix(q.tolist(), k.tolist())
+    np.testing.assert_allclose(s, brute.column_sums(A), rtol=1e-12)
+    np.testing.assert_allclose(o, brute.attend(A, v.tolist()), rtol=1e-11, atol=1e-13)
+    assert abs(ref.head_variance(s) - brute.variance(brute.column_sums(A))) < 1e-13
+    assert abs(ref.head_variance(s) - np.var(s)) < 1e-13
+    # a transposed operand or a missing mask would break these two:
+    assert A[0][1] == 0.0 and abs(s[n - 1] - A[n - 1][n - 1]) < 1e-15
+
+
+# ------------------------------------------------------------------ allocation (Eq. 5, App. A.2)
+
+def test_allocation_uniform_when_densities_equal():
+    S = ref.allocate_budgets(np.full(32, 3.7), 4096, round(0.2 * 4096 * 32), 64)
+    assert S.sum() == round(0.2 * 4096 * 32)
+    assert S.max() - S.min() <= 1                      # uniform alpha_l = rho
+    S = ref.allocate_budgets(np.full(8, 0.1), 1000, 1600, 10)
+    assert list(S) == [200] * 8
+
+
+def test_allocation_two_layer_closed_form():
+    F = np.array([0.3, 1.1])
+    tot = 1000
+    S = ref.allocate_budgets(F, 10_000, tot, 1)
+    p0 = 1.0 / (1.0 + math.exp(F[0] - F[1]))           # softmax(-F)[0]
+    assert S.sum() == tot and abs(S[0] - p0 * tot) <= 1.0
+    assert S[0] > S[1]                                 # lower variance => larger cache
+
+
+def test_allocation_matches_library_softmax_before_clamping():
+    from scipy.special import softmax
+    F = rng.uniform(0.0, 2.0, size=16)
+    tot = 16 * 300
+    S = ref.allocate_budgets(F, 4000, tot, 1)
+    want = softmax(-F) * tot
+    assert S.sum() == tot
+    assert np.all(np.abs(S - want) < 1.0)
+    order = np.argsort(F)
+    assert np.all(np.diff(S[order]) <= 0)              # F_a < F_b  =>  S_a >= S_b
+
+
+def test_allocation_clamps_and_conserves():
+    F = np.array([0.0, 5.0, 500.0, 2000.0, 1e6, 3.0])  # exp(-F) underflows for some layers
+    tot = 6 * 200
+    S = ref.allocate_budgets(F, 512, tot, 64)
+    assert S.sum() == tot and S.min() >= 64 and S.max() <= 512
+    assert S[0] == 512                                 # the densest layer saturates at seq_len
+    assert list(S[2:5]) == [64, 64, 64]
+    with pytest.raises(ValueError):
+        ref.allocate_budgets(F, 512, 6 * 64 - 1, 64)
+    with pytest.raises(ValueError):
+        ref.allocate_budgets(F, 512, 6 * 512 + 1, 64)
+
+
+def test_allocation_integer_remainder_goes_to_largest_fractions():
+    # equal densities, 3 layers, 10 units: shares 3.33.. each, the extra unit to layer 0
+    assert list(ref.allocate_budgets(np.zeros(3), 100, 10, 0)) == [4, 3, 3]
+    assert list(ref.allocate_budgets(np.zeros(3), 100, 11, 0)) == [4, 4, 3]
+
+
+# ------------------------------------------------------------------ selection (Eq. 7-8)
+
+@pytest.mark.parametrize("n,budget,recent,sink", [(30, 12, 3, 0), (30, 12, 4, 2), (17, 6, 6, 0),
+                                                  (25, 9, 0, 1), (12, 12, 3, 0), (12, 40, 3, 1)])
+def test_selection_matches_repeated_removal(n, budget, recent, sink):
+    g = np.random.default_rng(n * 100 + budget)
+    for trial in range(20):
+        score = g.integers(0, 6, size=n).astype(float) if trial % 2 else g.random(n)
+        ret, evi = ref.select(score, budget, recent, sink)
+        alive, dropped = brute.choose_retained(score.tolist(), budget, recent, sink)
+        assert list(ret) == alive and list(evi) == dropped
+        assert len(ret) == min(budget, n)
+        assert sorted(list(ret) + list(evi)) == list(range(n))
+
+
+def test_selection_without_heavy_hitters_is_sink_plus_window():
+    ret, evi = ref.select(rng.random(50), 10, 7, 3)
+    assert list(ret) == [0, 1, 2] + list(range(43, 50))
+    with pytest.raises(ValueError):
+        ref.select(rng.random(50), 5, 4, 2)
+
+
+def test_selection_tie_keeps_lower_index():
+    score = np.array([9.0, 1.0, 1.0, 1.0, 1.0, 9.0])
+    ret, evi = ref.select(score, 3, 1, 0)              # window = {5}; top-2 of [0..4]
+    assert list(ret) == [0, 1, 5] and list(evi) == [2, 3, 4]
+
+
+# ------------------------------------------------------------------ matching (Eq. 9)
+
+def test_cosine_properties_and_library_value():
+    from scipy.spatial.distance import cosine as cosine_distance
+    Ke, Kc = _rand(9, 6, 20), _rand(7, 6, 21)
+    U = ref.cosine_matrix(Ke, Kc)
+    assert np.all(U <= 1 + 1e-15) and np.all(U >= -1 - 1e-15)
+    for i in range(9):
+        for j in range(7):
+            assert abs(U[i, j] - (1.0 - cosine_distance(Ke[i], Kc[j]))) < 1e-14
+            assert abs(U[i, j] - brute.cosine(Ke[i].tolist(), Kc[j].tolist())) < 1e-14
+    np.testing.assert_allclose(np.diag(ref.cosine_matrix(Kc, Kc)), 1.0, rtol=1e-15)
+    U2 = ref.cosine_matrix(Ke * 3.5, Kc * 0.01)        # scale invariance
+    np.testing.assert_allclose(U2, U, rtol=1e-13, atol=1e-15)
+    assert np.all(ref.cosine_matrix(np.zeros((2, 6)), Kc) == 0.0)
+
+
+def test_matching_finds_planted_twins_and_first_maximum():
+    Kc = _rand(10, 8, 30)
+    Kc[7] = Kc[2]                                       # duplicate retained keys
+    Ke = np.vstack([Kc[4] * 2.0, Kc[2], _rand(1, 8, 31)])
+    u, t = ref.match(Ke, Kc)
+    assert t[0] == 4 and abs(u[0] - 1) < 1e-15
+    assert t[1] == 2 and abs(u[1] - 1) < 1e-15          # first maximum, not index 7
+    bu, bj = brute.nearest(np.vstack([Kc, Ke]).tolist(), list(range(10)), [10, 11, 12])
+    assert bj == list(t)
+    np.testing.assert_allclose(u, bu, rtol=1e-14)
+
+
+# ------------------------------------------------------------------ threshold (Eq. 10)
+
+def test_threshold_prefill_and_ema_closed_form():
+    u = rng.random(25)
+    tau, passed = ref.prefill_threshold(u)
+    assert u.min() <= tau <= u.max() and abs(tau - math.fsum(u) / 25) < 1e-15
+    assert list(passed) == [x >= tau for x in u]
+    assert math.isnan(ref.prefill_threshold(np.zeros(0))[0])
+    beta, tau0 = 0.7, 0.4
+    us = rng.random(12)
+    t = tau0
+    for x in us:
+        t = ref.ema_threshold(t, x, beta)
+    T = len(us)
+    closed = (1 - beta) ** T * tau0 + beta * sum((1 - beta) ** (T - 1 - k) * us[k]
+                                                 for k in range(T))
+    assert abs(t - closed) < 1e-14
+    assert ref.ema_threshold(0.83, 0.83, 0.6) == pytest.approx(0.83, abs=1e-16)
+    assert ref.ema_threshold(float("nan"), 0.31, 0.6) == 0.31
+
+
+# ------------------------------------------------------------------ merge (Eq. 11-12)
+
+def test_merge_two_token_hand_example():
+    # kept k=[1,0], evicted k=[0,1], u=0: weights e/(e+1) and 1/(e+1)
+    Kc, Vc = np.array([[1.0, 0.0]]), np.array([[2.0, 4.0]])
+    Ke, Ve = np.array([[0.0, 1.0]]), np.array([[-1.0, 1.0]])
+    K2, V2, n = ref.merge(Kc, Vc, Ke, Ve, np.array([0.0]), np.array([0]), np.array([True]))
+    wc, we = math.e / (math.e + 1), 1 / (math.e + 1)
+    np.testing.assert_allclose(K2[0], [wc, we], rtol=1e-15)
+    np.testing.assert_allclose(V2[0], [2 * wc - we, 4 * wc + we], rtol=1e-15)
+    assert n[0] == 1 and wc > we                        # the kept token has the largest weight
+
+
+def test_merge_copies_of_twin_average_the_values():
+    m = 5
+    Kc, Vc = _rand(3, 4, 40), _rand(3, 4, 41)
+    Ke = np.tile(Kc[1], (m, 1))
+    Ve = _rand(m, 4, 42)
+    K2, V2, n = ref.merge(Kc, Vc, Ke, Ve, np.ones(m), np.full(m, 1), np.ones(m, bool))
+    np.testing.assert_allclose(K2[1], Kc[1], rtol=1e-14)                 # weights sum to 1
+    np.testing.assert_allclose(V2[1], (Vc[1] + Ve.sum(0)) / (m + 1), rtol=1e-14)
+    assert np.array_equal(K2[[0, 2]], Kc[[0, 2]]) and list(n) == [0, m, 0]
+
+
+def test_merge_convex_hull_mask_and_brute_force():
+    Kc, Vc, Ke, Ve = _rand(6, 5, 50), _rand(6, 5, 51), _rand(14, 5, 52), _rand(14, 5, 53)
+    u, t = ref.match(Ke, Kc)
+    tau, passed = ref.prefill_threshold(u)
+    K2, V2, n = ref.merge(Kc, Vc, Ke, Ve, u, t, passed)
+    assert n.sum() == passed.sum()
+    for j in range(6):
+        src = [i for i in range(14) if passed[i] and t[i] == j]
+        grpK = np.vstack([Kc[j:j + 1], Ke[src]])
+        grpV = np.vstack([Vc[j:j + 1], Ve[src]])
+        assert np.all(K2[j] <= grpK.max(0) + 1e-15) and np.all(K2[j] >= grpK.min(0) - 1e-15)
+        assert np.all(V2[j] <= grpV.max(0) + 1e-15) and np.all(V2[j] >= grpV.min(0) - 1e-15)
+    allK, allV = np.vstack([Kc, Ke]).tolist(), np.vstack([Vc, Ve]).tolist()
+    bK, bV = brute.merged_rows(allK, allV, list(range(6)), list(range(6, 20)), list(u),
+                               list(t), list(passed))
+    np.testing.assert_allclose(K2, [bK[j] for j in range(6)], rtol=1e-13, atol=1e-15)
+    np.testing.assert_allclose(V2, [bV[j] for j in range(6)], rtol=1e-13, atol=1e-15)
+    # failed tokens are discarded: with nothing passing the cache rows are bit copies
+    K3, V3, n3 = ref.merge(Kc, Vc, Ke, Ve, u, t, np.zeros(14, bool))
+    assert np.array_equal(K3, Kc) and np.array_equal(V3, Vc) and n3.sum() == 0
+
+
+def test_round_storage_bf16_matches_torch_and_is_idempotent():
+    x = np.concatenate([rng.standard_normal(4000) * 10, [0.0, 1.0, -1.0, 1.00390625, 3.0e-3]])
+    got = ref.round_storage(x, "bf16")
+    # torch rounds fp32 -> bf16 to nearest even; feed it values exactly representable in fp32
+    x32 = x.astype(np.float32).astype(np.float64)
+    want = torch.from_numpy(x32.astype(np.float32)).to(torch.bfloat16).to(torch.float64).numpy()
+    np.testing.assert_array_equal(ref.round_storage(x32, "bf16"), want)
+    np.testing.assert_array_equal(ref.round_storage(got, "bf16"), got)
+    assert np.all(np.abs(got - x) <= np.abs(x) * 2.0 ** -8)
+    # a tie: 1 + 2^-8 lies midway between 1 and 1 + 2^-7 and must go to the even mantissa
+    assert ref.round_storage(np.array([1.0 + 2.0 ** -8]), "bf16")[0] == 1.0
+    assert ref.round_storage(np.array([1.0 + 3 * 2.0 ** -8]), "bf16")[0] == 1.0 + 2.0 ** -6
+
+
+# ------------------------------------------------------------------ whole method, brute force
+
+@pytest.mark.parametrize("n,d,G,budget,recent,sink,steps", [
+    (40, 6, 1, 12, 3, 0, 6), (33, 4, 2, 10, 4, 1, 5), (48, 8, 1, 16, 8, 2, 4),
+    (20, 4, 1, 7, 0, 0, 4), (20, 4, 3, 6, 6, 0, 3), (16, 4, 1, 40, 5, 0, 3)])
+def test_whole_method_matches_brute_force(n, d, G, budget, recent, sink, steps):
+    g = np.random.default_rng(n + 17 * d + budget)
+    cen = g.standard_normal((3, d)) * 2
+    K = cen[g.integers(0, 3, n)] + 0.3 * g.standard_normal((n, d))
+    V = g.standard_normal((n, d))
+    Q = cen[g.integers(0, 3, (G, n))] + 0.5 * g.standard_normal((G, n, d))
+    O, score, var = ref.prefill_kv_head(Q, K, V)
+    A = [brute.attention_matrix(Q[h].tolist(), K.tolist()) for h in range(G)]
+    bscore = [math.fsum(brute.column_sums(A[h])[j] for h in range(G)) for j in range(n)]
+    np.testing.assert_allclose(score, bscore, rtol=1e-12)
+    np.testing.assert_allclose(var, [brute.variance(brute.column_sums(a)) for a in A],
+                               rtol=1e-10, atol=1e-14)
+    cache, ev = ref.compress_head(K, V, score, budget, recent, sink)
+    st, bev = brute.compress(K.tolist(), V.tolist(), bscore, budget, recent, sink)
+    assert list(ev.retained) == bev["ret"] and list(ev.evicted) == bev["evi"]
+    assert list(ev.target) == bev["t"] and list(ev.passed) == bev["passed"]
+    np.testing.assert_allclose(ev.u_star, bev["u"], rtol=1e-13)
+    np.testing.assert_allclose(cache.K, st["K"], rtol=1e-12, atol=1e-14)
+    np.testing.assert_allclose(cache.V, st["V"], rtol=1e-12, atol=1e-14)
+    assert len(ev.retained) + ev.passed.sum() + (~ev.passed).sum() == n
+    for t in range(steps):
+        q = cen[g.integers(0, 3, G)] + 0.5 * g.standard_normal((G, d))
+        kn = cen[g.integers(0, 3)] + 0.3 * g.standard_normal(d)
+        vn = g.standard_normal(d)
+        out, e = ref.decode_step_head(cache, q, kn, vn, n + t, budget, recent, sink, 0.6)
+        bout, be = brute.decode_step(st, q.tolist(), kn.tolist(), vn.tolist(), n + t, budget,
+                                     recent, sink, 0.6)
+        np.testing.assert_allclose(out, bout, rtol=1e-11, atol=1e-13)
+        assert (e.evicted_pos, e.target_pos) == (be[0], be[1])
+        assert list(cache.pos) == st["pos"]
+        np.testing.assert_allclose(cache.K, st["K"], rtol=1e-11, atol=1e-13)
+        np.testing.assert_allclose(cache.score, st["score"], rtol=1e-12)
+        if not math.isnan(cache.tau):
+            assert abs(cache.tau - st["tau"]) < 1e-13
+
+
+# ------------------------------------------------------------------ reductions and decode invariants
+
+def _small_case(seed=3, n=64, d=8, G=2):
+    g = np.random.default_rng(seed)
+    cen = g.standard_normal((4, d)) * 2
+    K = cen[g.integers(0, 4, n)] + 0.3 * g.standard_normal((n, d))
+    V = g.standard_normal((n, d))
+    Q = cen[g.integers(0, 4, (G, n))] + 0.5 * g.standard_normal((G, n, d))
+    return g, cen, Q, K, V
+
+
+def test_budget_at_least_prompt_length_is_full_attention():
+    g, cen, Q, K, V = _small_case()
+    n, d = K.shape
+    _, score, _ = ref.prefill_kv_head(Q, K, V)
+    cache, ev = ref.compress_head(K, V, score, n + 10, 4, 0)
+    assert len(ev.evicted) == 0 and math.isnan(cache.tau) and np.array_equal(cache.K, K)
+    Ks, Vs = K.copy(), V.copy()
+    for t in range(5):
+        q, kn, vn = g.standard_normal((2, d)), g.standard_normal(d), g.standard_normal(d)
+        out, e = ref.decode_step_head(cache, q, kn, vn, n + t, n + 10, 4, 0, 0.7)
+        Ks, Vs = np.vstack([Ks, kn]), np.vstack([Vs, vn])
+        want = torch.nn.functional.scaled_dot_product_attention(
+            torch.from_numpy(q)[:, None, :], torch.from_numpy(Ks)[None].expand(2, -1, -1),
+            torch.from_numpy(Vs)[None].expand(2, -1, -1))[:, 0].numpy()
+        np.testing.assert_allclose(out, want, rtol=1e-12, atol=1e-14)
+        assert e.evicted_pos == -1
+        assert abs(cache.score.sum() - 2 * (n + t + 1)) < 1e-9   # +G per step, nothing lost
+
+
+def test_never_merging_is_pure_heavy_hitter_eviction():
+    g, cen, Q, K, V = _small_case(5)
+    _, score, _ = ref.prefill_kv_head(Q, K, V)
+    cache, ev = ref.compress_head(K, V, score, 20, 5, 1, tau_force=float("inf"))
+    assert not ev.passed.any()
+    assert np.array_equal(cache.K, K[ev.retained]) and np.array_equal(cache.V, V[ev.retained])
+    cache2, ev2 = ref.compress_head(K, V, score, 20, 5, 1, tau_force=float("-inf"))
+    assert ev2.passed.all() and np.array_equal(ev2.retained, ev.retained)
+    for t in range(4):
+        out, e = ref.decode_step_head(cache, g.standard_normal((2, 8)), g.standard_normal(8),
+                                      g.standard_normal(8), 64 + t, 20, 5, 1, 0.7,
+                                      tau_force=float("inf"))
+        assert e.target_pos == -1 and e.evicted_pos >= 0
+
+
+def test_decode_zero_query_uniform_scores_and_window():
+    g, cen, Q, K, V = _small_case(9)
+    n, d, G = 64, 8, 2
+    _, score, _ = ref.prefill_kv_head(Q, K, V)
+    budget, recent = 16, 4
+    cache, _ = ref.compress_head(K, V, score, budget, recent, 0)
+    for t in range(8):
+        before = cache.score.copy()
+        pos_before = cache.pos.copy()
+        vn = g.standard_normal(d)
+        want_out = np.vstack([cache.V, vn]).mean(axis=0)
+        out, e = ref.decode_step_head(cache, np.zeros((G, d)), g.standard_normal(d), vn,
+                                      n + t, budget, recent, 0, 0.7)
+        # uniform p = 1/(c+1): every surviving old slot gained G/(c+1)
+        keep = np.isin(pos_before, cache.pos)
+        np.testing.assert_allclose(cache.score[:-1] - before[keep], G / (budget + 1), rtol=1e-12)
+        assert cache.pos.size == budget and cache.pos[-1] == n + t
+        assert e.evicted_pos >= 0 and e.evicted_pos <= n + t - recent   # window is protected
+        assert set(range(n + t - recent + 1, n + t + 1)) <= set(cache.pos.tolist())
+        np.testing.assert_allclose(out[0], want_out, rtol=1e-12, atol=1e-14)
+
+
+def test_decode_merge_is_two_term_weighted_mean():
+    d = 4
+    K = np.array([[1.0, 0, 0, 0], [0, 1.0, 0, 0], [0.9, 0.1, 0, 0], [0, 0, 1.0, 0]])
+    V = np.arange(16, dtype=float).reshape(4, 4)
+    cache = ref.HeadCache(K.copy(), V.copy(), np.array([5.0, 4.0, 0.1, 3.0]),
+                          np.arange(4), 0.2, "f64")
+    q = np.zeros((1, d))
+    out, e = ref.decode_step_head(cache, q, np.array([0, 0, 0, 1.0]), np.ones(4), 4, 4, 1, 0, 0.5)
+    assert e.evicted_pos == 2 and e.target_pos == 0      # nearest to [0.9, 0.1] is [1, 0]
+    u = 0.9 / math.sqrt(0.82)
+    assert abs(e.u_star - u) < 1e-15 and abs(e.tau - (0.5 * u + 0.5 * 0.2)) < 1e-15
+    w = math.exp(u)
+    np.testing.assert_allclose(cache.K[0], (math.e * K[0] + w * K[2]) / (math.e + w), rtol=1e-15)
+    np.testing.assert_allclose(cache.V[0], (math.e * V[0] + w * V[2]) / (math.e + w), rtol=1e-15)
+    assert list(cache.pos) == [0, 1, 3, 4]
+
+
+def test_allocation_is_the_clipped_proportional_solution():
+    # Independent check by bisection on lambda: S_l = clip(lambda * exp(-F_l), lo, hi).
+    g = np.random.default_rng(11)
+    for trial in range(30):
+        L = int(g.integers(2, 12))
+        F = g.uniform(0, 12, size=L) * g.choice([0.1, 1.0, 30.0])
+        lo, hi = 8, 300
+        tot = int(g.integers(L * lo, L * hi + 1))
+        S = ref.allocate_budgets(F, hi, tot, lo)
+        w = np.exp(-(F - F.min()))
+        a, b = 0.0, 1e300
+        for _ in range(2000):
+            mid = 0.5 * (a + b) if b < 1e299 else max(1.0, a * 2)
+            if np.clip(mid * w, lo, hi).sum() < tot:
+                a = mid
+            else:
+                b = mid
+        want = np.clip(b * w, lo, hi)
+        assert S.sum() == tot and S.min() >= lo and S.max() <= hi
+        assert np.all(np.abs(S - want) <= 1.0 + 1e-6), (F, tot, S, want)
