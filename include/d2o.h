@@ -1,0 +1,191 @@
+/*
+ * d2o.h - C ABI of the MI355X (gfx950) implementation of the D2O KV-cache compression
+ * hot path (Dynamic Discriminative Operations, arxiv 2406.13035).
+ *
+ * The library never allocates device memory: the caller supplies two device workspaces
+ * whose sizes d2o_workspace_bytes() reports.  All device work is enqueued on the stream
+ * the caller passes (a hipStream_t, typed void* here so the header needs no HIP include;
+ * NULL = the default stream).  Unless stated otherwise a call returns without
+ * synchronising.  Every function returns 0 on success or a negative d2o_status;
+ * d2o_last_error() gives the message of the last failure on a context.
+ *
+ * Pointer kinds: "device" = device memory, "host" = ordinary host memory.
+ * Token identity across the ABI is the ORIGINAL TOKEN POSITION (prompt tokens 0..n-1,
+ * generated tokens n, n+1, ...), never a physical cache slot.
+ *
+ * Notation (paper, Sec. 3-4): B batch, L layers, Hq query heads, Hkv KV heads, G = Hq/Hkv,
+ * d head dimension, N prompt length, S_l cache budget of layer l (slots per KV head),
+ * T attention-sink tokens, M recent window, beta EMA constant, tau EMA threshold.
+ */
+#ifndef D2O_H
+#define D2O_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct d2o_ctx d2o_ctx;
+
+typedef enum { D2O_F32 = 0, D2O_BF16 = 1 } d2o_dtype;
+
+typedef enum {
+  D2O_OK = 0,
+  D2O_ERR_INVALID_ARG = -1, /* null pointer, index out of range, inconsistent sizes        */
+  D2O_ERR_UNSUPPORTED = -2, /* head_dim / dtype combination without a kernel               */
+  D2O_ERR_CAPACITY = -3,    /* cache slots or a workspace too small                        */
+  D2O_ERR_STATE = -4,       /* call order violated (compress before attend, ...)           */
+  D2O_ERR_HIP = -5          /* a HIP runtime call failed                                   */
+} d2o_status;
+
+/* Immutable after d2o_create. */
+typedef struct {
+  int32_t batch;          /* B                                                             */
+  int32_t n_layers;       /* L                                                             */
+  int32_t n_q_heads;      /* Hq, a multiple of n_kv_heads                                  */
+  int32_t n_kv_heads;     /* Hkv                                                           */
+  int32_t head_dim;       /* d: 64 or 128 for D2O_F32, 128 for D2O_BF16                    */
+  int32_t max_prompt_len; /* largest n any prefill call will pass                          */
+  int64_t slots_per_seq;  /* cache capacity per (sequence, KV head) over all layers:       */
+                          /* must hold sum_l (min(S_l, n) + 1)                             */
+  int32_t dtype;          /* d2o_dtype of Q, K, V, O and of the cache                      */
+  int32_t n_sink;         /* T of Eq. 7: the first T prompt tokens are always kept         */
+  double beta;            /* Eq. 10 smoothing constant, 0 <= beta < 1                      */
+  double tau_force;       /* NaN: threshold of Eq. 10.  +inf: never merge (pure eviction). */
+                          /* -inf: merge every evicted token.                              */
+} d2o_config;
+
+/* A strided tensor whose last dimension (d) is contiguous.  Strides are in elements.
+ * Prefill tensors are [b][head][token][d]; decode tensors are [layer][b][head][d] and use
+ * stride_n as the stride between consecutive layers. */
+typedef struct {
+  void* ptr;        /* device */
+  int64_t stride_b;
+  int64_t stride_h;
+  int64_t stride_n;
+} d2o_view;
+
+/* Sizes in bytes of the two device workspaces a context needs: `persistent` holds the
+ * compressed cache, per-key scores and statistics for the context's life; `scratch` holds
+ * per-call temporaries (contents are undefined between calls, except that the prefill
+ * events of the most recent d2o_compress_layer call stay readable until the next prefill
+ * call).  Errors: INVALID_ARG, UNSUPPORTED. */
+int d2o_workspace_bytes(const d2o_config* cfg, size_t* persistent, size_t* scratch);
+
+/* Creates a context over caller-owned device workspaces (256-byte aligned, at least the
+ * sizes reported above; the caller keeps them alive and untouched until d2o_destroy).
+ * The persistent workspace is cleared on `stream`.  Errors: INVALID_ARG, UNSUPPORTED,
+ * CAPACITY (workspace too small), HIP. */
+int d2o_create(const d2o_config* cfg, void* persistent_dev, size_t persistent_bytes,
+               void* scratch_dev, size_t scratch_bytes, void* stream, d2o_ctx** out);
+
+/* Frees the host-side context only. */
+void d2o_destroy(d2o_ctx* ctx);
+
+/* Message of the last error on this context ("" if none); valid until the next call. */
+const char* d2o_last_error(const d2o_ctx* ctx);
+
+/* Forgets all layers' caches, scores and thresholds (the workspaces are reused). */
+int d2o_reset(d2o_ctx* ctx, void* stream);
+
+/* Prompt encoding, attention part (Sec. 4.1 Eq. 4; Sec. 4.2.1 Eq. 6, prompt case).
+ * For one layer computes, per query head, O = softmax(Q K^T / sqrt(d)) V with a causal
+ * mask; per KV head the cumulative attention score of every key (column sums of the
+ * attention matrix, added over the G query heads of the group) and, per query head, the
+ * population variance of its column sums, whose mean over heads is the layer's density
+ * statistic F.  Scores and statistics are kept in the context.
+ * Q, O: [B][Hq][n][d]; K, V: [B][Hkv][n][d]; n <= max_prompt_len.  O.ptr may be NULL to skip
+ * the output write.  Errors: INVALID_ARG, STATE (layer already compressed), HIP. */
+int d2o_prefill_attend(d2o_ctx* ctx, int32_t layer, d2o_view Q, d2o_view K, d2o_view V,
+                       int32_t n, d2o_view O, void* stream);
+
+/* Copies the density statistics to the host and waits for them (synchronises `stream`).
+ * F_layers: host [B][L] (layers not yet attended read as NaN); F_heads: host
+ * [B][L][Hq] per-query-head variances, may be NULL.  Errors: INVALID_ARG, HIP. */
+int d2o_get_density(d2o_ctx* ctx, double* F_layers, double* F_heads, void* stream);
+
+/* Dynamic layer budgets (Sec. 4.1 Eq. 5, App. A.2): S_l proportional to exp(-F_l) with
+ * sum_l S_l = total_budget, every S_l clipped to [min_budget, seq_len] (the unique clipped
+ * proportional split), shares floored and the leftover units given to the largest
+ * fractional parts (ties: lower layer).  Pure host function on host arrays, fp64.
+ * Errors: INVALID_ARG (also when n_layers*min_budget <= total_budget <= n_layers*seq_len
+ * fails or an F is not finite). */
+int d2o_allocate_budgets(const double* F, int32_t n_layers, int32_t seq_len,
+                         int64_t total_budget, int32_t min_budget, int32_t* S_out);
+
+/* Replaces a layer's per-key scores by host values ([B][Hkv][n] floats) as if
+ * d2o_prefill_attend had produced them (used to drive the token-level stages from given
+ * scores).  Synchronises `stream`.  Errors: INVALID_ARG, STATE, HIP. */
+int d2o_scores_import(d2o_ctx* ctx, int32_t layer, const float* scores, int32_t n, void* stream);
+
+/* Copies a layer's per-key scores to the host ([B][Hkv][n] floats); synchronises. */
+int d2o_scores_export(d2o_ctx* ctx, int32_t layer, float* scores, int32_t n, void* stream);
+
+/* Prompt encoding, token-level operation for one layer (Sec. 4.2): eviction by cumulative
+ * score (Eq. 7-8: keep T sinks, the top S-T-M scores of the middle, the last M tokens; equal
+ * scores: the lower position is kept), nearest-neighbour matching of evicted keys to
+ * retained keys by cosine similarity (Eq. 9, first maximum in ascending position), the
+ * initial threshold tau_0 = mean of the best similarities (Eq. 10) and the similarity-
+ * weighted merge of passing tokens into their matches (Eq. 11-12, weights
+ * e/Z and exp(u)/Z with Z = e + sum exp(u)).  Requires the layer's scores
+ * (d2o_prefill_attend or d2o_scores_import) and the same K, V.
+ * budget, recent: host [B], the layer's S_l and M per sequence; budget >= n keeps
+ * everything.  Errors: INVALID_ARG (budget < T + M, ...), STATE, CAPACITY, HIP. */
+int d2o_compress_layer(d2o_ctx* ctx, int32_t layer, d2o_view K, d2o_view V, int32_t n,
+                       const int32_t* budget, const int32_t* recent, void* stream);
+
+/* d2o_prefill_attend followed by d2o_compress_layer with caller-chosen budgets. */
+int d2o_prefill_compress(d2o_ctx* ctx, int32_t layer, d2o_view Q, d2o_view K, d2o_view V,
+                         int32_t n, d2o_view O, const int32_t* budget, const int32_t* recent,
+                         void* stream);
+
+/* One generation step on layers [layer, layer + n_layers_in_call) (Sec. 3 Eq. 2-3; Sec. 4.2
+ * Eq. 6-12): append (k_new, v_new), attend over the cache, add the softmax rows of the G
+ * query heads to the scores, and, when a cache exceeds its budget, evict one token by
+ * Eq. 7-8 (equal scores: the later position is evicted), match it (Eq. 9), update the EMA
+ * threshold (Eq. 10, update first, then test) and merge or discard it (Eq. 11-12).
+ * q, out: [layers][B][Hq][d]; k_new, v_new: [layers][B][Hkv][d].
+ * Errors: INVALID_ARG, STATE (a layer not compressed), CAPACITY, HIP. */
+int d2o_decode_step(d2o_ctx* ctx, int32_t layer, int32_t n_layers_in_call, d2o_view q,
+                    d2o_view k_new, d2o_view v_new, d2o_view out, void* stream);
+
+/* Reserves a layer's cache region for the given budgets without running the prefill
+ * stages (so that d2o_cache_import can fill it).  n is the prompt length the positions
+ * refer to.  Errors: INVALID_ARG, STATE (already reserved), CAPACITY. */
+int d2o_layer_reserve(d2o_ctx* ctx, int32_t layer, int32_t n, const int32_t* budget,
+                      const int32_t* recent);
+
+/* Cache of one (layer, sequence, KV head) to host buffers, rows in ascending token position:
+ * K, V [count][d] in the cache dtype, score [count], pos [count]; buffers must hold
+ * budget+1 rows.  Any pointer may be NULL.  Synchronises `stream`. */
+int d2o_cache_export(d2o_ctx* ctx, int32_t layer, int32_t b, int32_t kv_head, void* K, void* V,
+                     double* score, int32_t* pos, int32_t* count, double* tau, void* stream);
+
+/* Host buffers into the cache of one (layer, sequence, KV head) of a reserved layer;
+ * count <= budget, `next_pos` = position the next generated token will get (same for every
+ * head of the layer).  Synchronises `stream`. */
+int d2o_cache_import(d2o_ctx* ctx, int32_t layer, int32_t b, int32_t kv_head, const void* K,
+                     const void* V, const double* score, const int32_t* pos, int32_t count,
+                     double tau, int32_t next_pos, void* stream);
+
+/* What the last decode step did on one layer, host arrays [B][Hkv]: position of the evicted
+ * token (-1 none), position it was merged into (-1 discarded / none), its best similarity
+ * (NaN none).  Synchronises `stream`. */
+int d2o_last_events(d2o_ctx* ctx, int32_t layer, int32_t* evicted_pos, int32_t* target_pos,
+                    double* u_star, void* stream);
+
+/* What the most recent d2o_compress_layer call did on one (sequence, KV head): retained
+ * positions [n_ret] and evicted positions [n_evi] ascending, and per evicted token its
+ * match (position), best similarity and whether it passed the threshold.  Host buffers of n
+ * entries each; any may be NULL.  Synchronises `stream`. */
+int d2o_prefill_events(d2o_ctx* ctx, int32_t layer, int32_t b, int32_t kv_head,
+                       int32_t* retained_pos, int32_t* n_ret, int32_t* evicted_pos,
+                       int32_t* n_evi, int32_t* target_pos, double* u_star, uint8_t* passed,
+                       void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* D2O_H */

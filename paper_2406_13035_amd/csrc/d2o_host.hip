@@ -1,0 +1,554 @@
+// Host side of libd2o: context, workspace layout, argument checks, stage sequencing and the
+// host-only budget allocation.  All device arithmetic lives in the kernel files.
+#include <algorithm>
+#include <cmath>
+#include <cstring>
+#include <limits>
+#include <numeric>
+
+#include "d2o_internal.h"
+
+namespace d2o {
+
+int fail(d2o_ctx* ctx, int code, const std::string& msg) {
+  if (ctx) ctx->err = msg;
+  return code;
+}
+
+namespace {
+
+// Walks the workspace layout; with base == nullptr it only measures.
+struct Carver {
+  char* base;
+  size_t off = 0;
+  template <typename T>
+  void take(T*& field, size_t count) {
+    off = (off + 255) & ~size_t(255);
+    field = base ? reinterpret_cast<T*>(base + off) : nullptr;
+    off += count * sizeof(T);
+  }
+  void take_raw(void*& field, size_t bytes) {
+    off = (off + 255) & ~size_t(255);
+    field = base ? static_cast<void*>(base + off) : nullptr;
+    off += bytes;
+  }
+};
+
+int check_config(const d2o_config* c) {
+  if (!c) return D2O_ERR_INVALID_ARG;
+  if (c->batch < 1 || c->n_layers < 1 || c->n_q_heads < 1 || c->n_kv_heads < 1) return D2O_ERR_INVALID_ARG;
+  if (c->n_q_heads % c->n_kv_heads) return D2O_ERR_INVALID_ARG;
+  if (c->max_prompt_len < 1 || c->slots_per_seq < 2 || c->n_sink < 0) return D2O_ERR_INVALID_ARG;
+  if (!(c->beta >= 0.0 && c->beta < 1.0)) return D2O_ERR_INVALID_ARG;
+  if (c->dtype == D2O_BF16) {
+    if (c->head_dim != 128) return D2O_ERR_UNSUPPORTED;
+  } else if (c->dtype == D2O_F32) {
+    if (c->head_dim != 64 && c->head_dim != 128) return D2O_ERR_UNSUPPORTED;
+  } else {
+    return D2O_ERR_UNSUPPORTED;
+  }
+  if (c->n_q_heads / c->n_kv_heads > 8) return D2O_ERR_UNSUPPORTED;
+  return D2O_OK;
+}
+
+void layout(d2o_ctx* x, char* persistent, char* scratch, size_t* pbytes, size_t* sbytes) {
+  const d2o_config& c = x->cfg;
+  const size_t B = c.batch, L = c.n_layers, Hq = c.n_q_heads, Hkv = c.n_kv_heads, d = c.head_dim;
+  const size_t slots = c.slots_per_seq, es = x->esize, np = x->npad, G = Hq / Hkv;
+  const size_t nch = x->nchunk_cap;
+  Carver p{persistent};
+  p.take(x->score_pre, L * B * Hkv * np);
+  p.take(x->head_var, L * B * Hq);
+  p.take(x->layer_F, L * B);
+  p.take_raw(x->cacheK, B * Hkv * slots * d * es);
+  p.take_raw(x->cacheV, B * Hkv * slots * d * es);
+  p.take(x->cscore, B * Hkv * slots);
+  p.take(x->cpos, B * Hkv * slots);
+  p.take(x->ccount, L * B * Hkv);
+  p.take(x->ctau, L * B * Hkv);
+  p.take(x->meta, L * B * 4);
+  p.take(x->ev_evicted, L * B * Hkv);
+  p.take(x->ev_target, L * B * Hkv);
+  p.take(x->ev_ustar, L * B * Hkv);
+  *pbytes = (p.off + 255) & ~size_t(255);
+
+  Carver s{scratch};
+  s.take(x->lse, B * Hq * np);
+  s.take_raw(x->vt, c.dtype == D2O_BF16 ? B * Hkv * d * np * es : 0);
+  s.take(x->varpart, B * Hq * (np / 128) * 2);
+  const size_t bh = B * Hkv;
+  s.take(x->sel_ret, bh * np);
+  s.take(x->sel_evi, bh * np);
+  s.take(x->sel_cnt, bh * 2);
+  s.take(x->invnorm, bh * np);
+  s.take(x->m_cand, bh * np);
+  s.take(x->m_ustar, bh * np);
+  s.take(x->m_tgt, bh * np);
+  s.take(x->m_pass, bh * np);
+  s.take(x->g_cnt, bh * (np + 1));
+  s.take(x->g_off, bh * (np + 1));
+  s.take(x->g_cur, bh * (np + 1));
+  s.take(x->g_src, bh * np);
+  s.take(x->d_logit, B * Hq * slots);
+  s.take(x->d_pm, bh * nch * G);
+  s.take(x->d_pl, bh * nch * G);
+  s.take(x->d_pacc, bh * nch * G * d);
+  s.take(x->d_eslot, L * bh);
+  s.take(x->d_cu, bh * nch);
+  s.take(x->d_cslot, bh * nch);
+  *sbytes = (s.off + 255) & ~size_t(255);
+}
+
+void init_sizes(d2o_ctx* x) {
+  x->esize = x->cfg.dtype == D2O_BF16 ? 2 : 4;
+  x->npad = (x->cfg.max_prompt_len + 127) / 128 * 128;
+  x->nchunk_cap = x->cfg.slots_per_seq / kChunk + x->cfg.n_layers + 1;
+}
+
+bool view_ok(const d2o_ctx* x, const d2o_view& v) {
+  const int64_t al = 16 / x->esize;  // 16-byte vector loads
+  if (!v.ptr || (reinterpret_cast<uintptr_t>(v.ptr) & 15)) return false;
+  return v.stride_b % al == 0 && v.stride_h % al == 0 && v.stride_n % al == 0 && v.stride_n >= 0;
+}
+
+int reserve_layer(d2o_ctx* x, int32_t layer, int32_t n, const int32_t* budget, const int32_t* recent) {
+  const d2o_config& c = x->cfg;
+  LayerState& st = x->layers[layer];
+  std::vector<LayerMeta> meta(c.batch);
+  for (int b = 0; b < c.batch; ++b) {
+    if (budget[b] < 1 || recent[b] < 0 || budget[b] < c.n_sink + recent[b])
+      return fail(x, D2O_ERR_INVALID_ARG, "budget must be >= 1 and >= n_sink + recent");
+    if (n < c.n_sink) return fail(x, D2O_ERR_INVALID_ARG, "prompt shorter than the sink tokens");
+    const int64_t need = int64_t(budget[b]) + 1;
+    if (x->used_slots[b] + need > c.slots_per_seq)
+      return fail(x, D2O_ERR_CAPACITY, "slots_per_seq too small for the layer budgets");
+    meta[b].base = int32_t(x->used_slots[b]);
+    meta[b].budget = budget[b];
+    meta[b].recent = recent[b];
+    meta[b].chunk_base = int32_t(x->used_chunks[b]);
+  }
+  for (int b = 0; b < c.batch; ++b) {
+    x->used_slots[b] += int64_t(budget[b]) + 1;
+    x->used_chunks[b] += (int64_t(budget[b]) + 1 + kChunk - 1) / kChunk;
+  }
+  st.meta = meta;
+  st.n = n;
+  st.next_pos = n;
+  return D2O_OK;
+}
+
+}  // namespace
+}  // namespace d2o
+
+using namespace d2o;
+
+extern "C" {
+
+int d2o_workspace_bytes(const d2o_config* cfg, size_t* persistent, size_t* scratch) {
+  int rc = check_config(cfg);
+  if (rc) return rc;
+  if (!persistent || !scratch) return D2O_ERR_INVALID_ARG;
+  d2o_ctx tmp;
+  tmp.cfg = *cfg;
+  init_sizes(&tmp);
+  layout(&tmp, nullptr, nullptr, persistent, scratch);
+  return D2O_OK;
+}
+
+int d2o_create(const d2o_config* cfg, void* persistent_dev, size_t persistent_bytes,
+               void* scratch_dev, size_t scratch_bytes, void* stream, d2o_ctx** out) {
+  int rc = check_config(cfg);
+  if (rc) return rc;
+  if (!persistent_dev || !scratch_dev || !out) return D2O_ERR_INVALID_ARG;
+  if ((reinterpret_cast<uintptr_t>(persistent_dev) | reinterpret_cast<uintptr_t>(scratch_dev)) & 255)
+    return D2O_ERR_INVALID_ARG;
+  d2o_ctx* x = new d2o_ctx;
+  x->cfg = *cfg;
+  init_sizes(x);
+  size_t pb = 0, sb = 0;
+  layout(x, static_cast<char*>(persistent_dev), static_cast<char*>(scratch_dev), &pb, &sb);
+  if (pb > persistent_bytes || sb > scratch_bytes) {
+    delete x;
+    return D2O_ERR_CAPACITY;
+  }
+  x->layers.assign(cfg->n_layers, LayerState{});
+  x->used_slots.assign(cfg->batch, 0);
+  x->used_chunks.assign(cfg->batch, 0);
+  rc = d2o_reset(x, stream);
+  if (rc) {
+    delete x;
+    return rc;
+  }
+  *out = x;
+  return D2O_OK;
+}
+
+void d2o_destroy(d2o_ctx* ctx) { delete ctx; }
+
+const char* d2o_last_error(const d2o_ctx* ctx) { return ctx ? ctx->err.c_str() : ""; }
+
+int d2o_reset(d2o_ctx* x, void* stream) {
+  if (!x) return D2O_ERR_INVALID_ARG;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const d2o_config& c = x->cfg;
+  const size_t lbh = size_t(c.n_layers) * c.batch * c.n_kv_heads;
+  // Only the small per-head state needs defined contents; 0xFF bytes read as NaN / -1.
+  D2O_HIP_CHECK(x, hipMemsetAsync(x->layer_F, 0xFF, sizeof(double) * c.n_layers * c.batch, s));
+  D2O_HIP_CHECK(x, hipMemsetAsync(x->head_var, 0xFF, sizeof(double) * c.n_layers * c.batch * c.n_q_heads, s));
+  D2O_HIP_CHECK(x, hipMemsetAsync(x->ccount, 0, sizeof(int32_t) * lbh, s));
+  D2O_HIP_CHECK(x, hipMemsetAsync(x->ctau, 0xFF, sizeof(double) * lbh, s));
+  D2O_HIP_CHECK(x, hipMemsetAsync(x->meta, 0, sizeof(int32_t) * 4 * c.n_layers * c.batch, s));
+  D2O_HIP_CHECK(x, hipMemsetAsync(x->ev_evicted, 0xFF, sizeof(int32_t) * lbh, s));
+  D2O_HIP_CHECK(x, hipMemsetAsync(x->ev_target, 0xFF, sizeof(int32_t) * lbh, s));
+  D2O_HIP_CHECK(x, hipMemsetAsync(x->ev_ustar, 0xFF, sizeof(double) * lbh, s));
+  for (auto& l : x->layers) l = LayerState{};
+  std::fill(x->used_slots.begin(), x->used_slots.end(), 0);
+  std::fill(x->used_chunks.begin(), x->used_chunks.end(), 0);
+  x->last_compress_layer = -1;
+  return D2O_OK;
+}
+
+int d2o_prefill_attend(d2o_ctx* x, int32_t layer, d2o_view Q, d2o_view K, d2o_view V, int32_t n,
+                       d2o_view O, void* stream) {
+  if (!x) return D2O_ERR_INVALID_ARG;
+  const d2o_config& c = x->cfg;
+  if (layer < 0 || layer >= c.n_layers) return fail(x, D2O_ERR_INVALID_ARG, "layer out of range");
+  if (n < 1 || n > c.max_prompt_len) return fail(x, D2O_ERR_INVALID_ARG, "n out of range");
+  if (!view_ok(x, Q) || !view_ok(x, K) || !view_ok(x, V) || (O.ptr && !view_ok(x, O)))
+    return fail(x, D2O_ERR_INVALID_ARG, "null, misaligned or badly strided tensor view");
+  if (Q.stride_n < c.head_dim || K.stride_n < c.head_dim || V.stride_n < c.head_dim ||
+      (O.ptr && O.stride_n < c.head_dim))
+    return fail(x, D2O_ERR_INVALID_ARG, "token stride smaller than head_dim");
+  LayerState& st = x->layers[layer];
+  if (st.phase == kReady) return fail(x, D2O_ERR_STATE, "layer already compressed");
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  hipError_t e = c.dtype == D2O_BF16
+                     ? launch_prefill_bf16(x, layer, to_view(Q), to_view(K), to_view(V), to_view(O), n, s)
+                     : launch_prefill_f32(x, layer, to_view(Q), to_view(K), to_view(V), to_view(O), n, s);
+  if (e != hipSuccess) return fail(x, D2O_ERR_HIP, std::string("prefill attention: ") + hipGetErrorString(e));
+  e = launch_density(x, layer, n, s);
+  if (e != hipSuccess) return fail(x, D2O_ERR_HIP, std::string("density: ") + hipGetErrorString(e));
+  st.phase = kAttended;
+  st.n = n;
+  return D2O_OK;
+}
+
+int d2o_get_density(d2o_ctx* x, double* F_layers, double* F_heads, void* stream) {
+  if (!x || !F_layers) return D2O_ERR_INVALID_ARG;
+  const d2o_config& c = x->cfg;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  std::vector<double> lf(size_t(c.n_layers) * c.batch), hv(size_t(c.n_layers) * c.batch * c.n_q_heads);
+  D2O_HIP_CHECK(x, hipMemcpyAsync(lf.data(), x->layer_F, lf.size() * sizeof(double), hipMemcpyDeviceToHost, s));
+  D2O_HIP_CHECK(x, hipMemcpyAsync(hv.data(), x->head_var, hv.size() * sizeof(double), hipMemcpyDeviceToHost, s));
+  D2O_HIP_CHECK(x, hipStreamSynchronize(s));
+  for (int b = 0; b < c.batch; ++b)
+    for (int l = 0; l < c.n_layers; ++l) {
+      F_layers[size_t(b) * c.n_layers + l] = lf[size_t(l) * c.batch + b];
+      if (F_heads)
+        for (int h = 0; h < c.n_q_heads; ++h)
+          F_heads[(size_t(b) * c.n_layers + l) * c.n_q_heads + h] = hv[(size_t(l) * c.batch + b) * c.n_q_heads + h];
+    }
+  return D2O_OK;
+}
+
+// Sec. 4.1 Eq. 5 with the clipping and integer rules stated in d2o.h.
+int d2o_allocate_budgets(const double* F, int32_t L, int32_t seq_len, int64_t total, int32_t min_budget,
+                         int32_t* S_out) {
+  if (!F || !S_out || L < 1 || seq_len < 1 || min_budget < 0) return D2O_ERR_INVALID_ARG;
+  if (total < int64_t(L) * min_budget || total > int64_t(L) * seq_len) return D2O_ERR_INVALID_ARG;
+  for (int l = 0; l < L; ++l)
+    if (!std::isfinite(F[l])) return D2O_ERR_INVALID_ARG;
+  std::vector<char> pinned(L, 0);
+  std::vector<double> share(L, 0.0), w(L, 0.0);
+  int64_t remaining = total;
+  const double hi = double(seq_len), lo = double(min_budget);
+  for (;;) {
+    double fmin = std::numeric_limits<double>::infinity();
+    int nfree = 0;
+    for (int l = 0; l < L; ++l)
+      if (!pinned[l]) {
+        fmin = std::min(fmin, F[l]);
+        ++nfree;
+      }
+    if (!nfree) break;
+    double wsum = 0.0;
+    for (int l = 0; l < L; ++l)
+      if (!pinned[l]) {
+        w[l] = std::exp(-(F[l] - fmin));
+        wsum += w[l];
+      }
+    double excess = 0.0, deficit = 0.0;
+    int nover = 0, nunder = 0;
+    for (int l = 0; l < L; ++l)
+      if (!pinned[l]) {
+        share[l] = double(remaining) * (w[l] / wsum);
+        if (share[l] > hi) {
+          excess += share[l] - hi;
+          ++nover;
+        }
+      }
+    for (int l = 0; l < L; ++l)
+      if (!pinned[l] && share[l] < lo) {
+        deficit += lo - share[l];
+        ++nunder;
+      }
+    if (!nover && !nunder) break;
+    if (nover && excess >= deficit) {
+      for (int l = 0; l < L; ++l)
+        if (!pinned[l] && share[l] > hi) {
+          pinned[l] = 1;
+          S_out[l] = seq_len;
+          remaining -= seq_len;
+        }
+    } else {
+      for (int l = 0; l < L; ++l)
+        if (!pinned[l] && share[l] < lo) {
+          pinned[l] = 1;
+          S_out[l] = min_budget;
+          remaining -= min_budget;
+        }
+    }
+  }
+  std::vector<int> free_layers;
+  int64_t given = 0;
+  for (int l = 0; l < L; ++l)
+    if (!pinned[l]) {
+      S_out[l] = int32_t(std::floor(share[l]));
+      given += S_out[l];
+      free_layers.push_back(l);
+    }
+  int64_t left = remaining - given;
+  std::stable_sort(free_layers.begin(), free_layers.end(), [&](int a, int b) {
+    return (share[a] - std::floor(share[a])) > (share[b] - std::floor(share[b]));
+  });
+  for (size_t t = 0; left > 0 && !free_layers.empty(); ++t) {
+    int l = free_layers[t % free_layers.size()];
+    if (S_out[l] < seq_len) {
+      ++S_out[l];
+      --left;
+    }
+  }
+  return D2O_OK;
+}
+
+int d2o_scores_import(d2o_ctx* x, int32_t layer, const float* scores, int32_t n, void* stream) {
+  if (!x || !scores) return D2O_ERR_INVALID_ARG;
+  const d2o_config& c = x->cfg;
+  if (layer < 0 || layer >= c.n_layers || n < 1 || n > c.max_prompt_len)
+    return fail(x, D2O_ERR_INVALID_ARG, "layer or n out of range");
+  LayerState& st = x->layers[layer];
+  if (st.phase == kReady) return fail(x, D2O_ERR_STATE, "layer already compressed");
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const size_t bh = size_t(c.batch) * c.n_kv_heads;
+  float* dst = x->score_pre + size_t(layer) * bh * x->npad;
+  D2O_HIP_CHECK(x, hipMemcpy2DAsync(dst, sizeof(float) * x->npad, scores, sizeof(float) * n,
+                                    sizeof(float) * n, bh, hipMemcpyHostToDevice, s));
+  D2O_HIP_CHECK(x, hipStreamSynchronize(s));
+  st.phase = kAttended;
+  st.n = n;
+  return D2O_OK;
+}
+
+int d2o_scores_export(d2o_ctx* x, int32_t layer, float* scores, int32_t n, void* stream) {
+  if (!x || !scores) return D2O_ERR_INVALID_ARG;
+  const d2o_config& c = x->cfg;
+  if (layer < 0 || layer >= c.n_layers || n < 1 || n > c.max_prompt_len)
+    return fail(x, D2O_ERR_INVALID_ARG, "layer or n out of range");
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const size_t bh = size_t(c.batch) * c.n_kv_heads;
+  const float* src = x->score_pre + size_t(layer) * bh * x->npad;
+  D2O_HIP_CHECK(x, hipMemcpy2DAsync(scores, sizeof(float) * n, src, sizeof(float) * x->npad,
+                                    sizeof(float) * n, bh, hipMemcpyDeviceToHost, s));
+  D2O_HIP_CHECK(x, hipStreamSynchronize(s));
+  return D2O_OK;
+}
+
+int d2o_layer_reserve(d2o_ctx* x, int32_t layer, int32_t n, const int32_t* budget, const int32_t* recent) {
+  if (!x || !budget || !recent) return D2O_ERR_INVALID_ARG;
+  const d2o_config& c = x->cfg;
+  if (layer < 0 || layer >= c.n_layers || n < 1) return fail(x, D2O_ERR_INVALID_ARG, "layer or n out of range");
+  LayerState& st = x->layers[layer];
+  if (st.phase == kReady) return fail(x, D2O_ERR_STATE, "layer already reserved");
+  int rc = reserve_layer(x, layer, n, budget, recent);
+  if (rc) return rc;
+  // Metadata is tiny; a blocking copy keeps the host vector's lifetime simple.
+  hipError_t e = hipMemcpy(x->meta + size_t(layer) * c.batch * 4, st.meta.data(),
+                           sizeof(LayerMeta) * c.batch, hipMemcpyHostToDevice);
+  if (e != hipSuccess) return fail(x, D2O_ERR_HIP, hipGetErrorString(e));
+  st.phase = kReady;
+  return D2O_OK;
+}
+
+int d2o_compress_layer(d2o_ctx* x, int32_t layer, d2o_view K, d2o_view V, int32_t n,
+                       const int32_t* budget, const int32_t* recent, void* stream) {
+  if (!x || !budget || !recent) return D2O_ERR_INVALID_ARG;
+  const d2o_config& c = x->cfg;
+  if (layer < 0 || layer >= c.n_layers) return fail(x, D2O_ERR_INVALID_ARG, "layer out of range");
+  LayerState& st = x->layers[layer];
+  if (st.phase == kEmpty) return fail(x, D2O_ERR_STATE, "layer has no scores: call d2o_prefill_attend first");
+  if (st.phase == kReady) return fail(x, D2O_ERR_STATE, "layer already compressed");
+  if (n != st.n) return fail(x, D2O_ERR_INVALID_ARG, "n differs from the attention call");
+  if (!view_ok(x, K) || !view_ok(x, V) || K.stride_n < c.head_dim || V.stride_n < c.head_dim)
+    return fail(x, D2O_ERR_INVALID_ARG, "null, misaligned or badly strided tensor view");
+  int rc = reserve_layer(x, layer, n, budget, recent);
+  if (rc) return rc;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  D2O_HIP_CHECK(x, hipMemcpyAsync(x->meta + size_t(layer) * c.batch * 4, st.meta.data(),
+                                  sizeof(LayerMeta) * c.batch, hipMemcpyHostToDevice, s));
+  D2O_HIP_CHECK(x, hipStreamSynchronize(s));  // st.meta may be reallocated later; keep it simple
+  st.phase = kReady;
+  x->last_compress_layer = layer;
+  hipError_t e;
+  if ((e = launch_select(x, layer, n, s)) != hipSuccess) return fail(x, D2O_ERR_HIP, std::string("select: ") + hipGetErrorString(e));
+  if ((e = launch_gather(x, layer, to_view(K), to_view(V), n, s)) != hipSuccess) return fail(x, D2O_ERR_HIP, std::string("gather: ") + hipGetErrorString(e));
+  if ((e = launch_match(x, layer, to_view(K), n, s)) != hipSuccess) return fail(x, D2O_ERR_HIP, std::string("match: ") + hipGetErrorString(e));
+  if ((e = launch_threshold_group(x, layer, n, s)) != hipSuccess) return fail(x, D2O_ERR_HIP, std::string("threshold: ") + hipGetErrorString(e));
+  if ((e = launch_merge(x, layer, to_view(K), to_view(V), n, s)) != hipSuccess) return fail(x, D2O_ERR_HIP, std::string("merge: ") + hipGetErrorString(e));
+  return D2O_OK;
+}
+
+int d2o_prefill_compress(d2o_ctx* x, int32_t layer, d2o_view Q, d2o_view K, d2o_view V, int32_t n,
+                         d2o_view O, const int32_t* budget, const int32_t* recent, void* stream) {
+  int rc = d2o_prefill_attend(x, layer, Q, K, V, n, O, stream);
+  if (rc) return rc;
+  return d2o_compress_layer(x, layer, K, V, n, budget, recent, stream);
+}
+
+int d2o_decode_step(d2o_ctx* x, int32_t layer, int32_t nl, d2o_view q, d2o_view k_new, d2o_view v_new,
+                    d2o_view out, void* stream) {
+  if (!x) return D2O_ERR_INVALID_ARG;
+  const d2o_config& c = x->cfg;
+  if (layer < 0 || nl < 1 || layer + nl > c.n_layers) return fail(x, D2O_ERR_INVALID_ARG, "layer range");
+  if (!view_ok(x, q) || !view_ok(x, k_new) || !view_ok(x, v_new) || !view_ok(x, out))
+    return fail(x, D2O_ERR_INVALID_ARG, "null, misaligned or badly strided tensor view");
+  const int32_t new_pos = x->layers[layer].next_pos;
+  for (int l = layer; l < layer + nl; ++l) {
+    if (x->layers[l].phase != kReady) return fail(x, D2O_ERR_STATE, "layer not compressed");
+    if (x->layers[l].next_pos != new_pos)
+      return fail(x, D2O_ERR_STATE, "layers of one call must be at the same token position");
+  }
+  hipError_t e = launch_decode(x, layer, nl, to_view(q), to_view(k_new), to_view(v_new), to_view(out),
+                               new_pos, static_cast<hipStream_t>(stream));
+  if (e != hipSuccess) return fail(x, D2O_ERR_HIP, std::string("decode: ") + hipGetErrorString(e));
+  for (int l = layer; l < layer + nl; ++l) ++x->layers[l].next_pos;
+  return D2O_OK;
+}
+
+static int head_args_ok(d2o_ctx* x, int32_t layer, int32_t b, int32_t h) {
+  const d2o_config& c = x->cfg;
+  if (layer < 0 || layer >= c.n_layers || b < 0 || b >= c.batch || h < 0 || h >= c.n_kv_heads)
+    return fail(x, D2O_ERR_INVALID_ARG, "layer, sequence or head out of range");
+  return D2O_OK;
+}
+
+int d2o_cache_export(d2o_ctx* x, int32_t layer, int32_t b, int32_t h, void* K, void* V, double* score,
+                     int32_t* pos, int32_t* count, double* tau, void* stream) {
+  if (!x) return D2O_ERR_INVALID_ARG;
+  int rc = head_args_ok(x, layer, b, h);
+  if (rc) return rc;
+  const d2o_config& c = x->cfg;
+  LayerState& st = x->layers[layer];
+  if (st.phase != kReady) return fail(x, D2O_ERR_STATE, "layer not compressed");
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const size_t lbh = (size_t(layer) * c.batch + b) * c.n_kv_heads + h;
+  int32_t cnt = 0;
+  double t = 0;
+  D2O_HIP_CHECK(x, hipMemcpyAsync(&cnt, x->ccount + lbh, sizeof(int32_t), hipMemcpyDeviceToHost, s));
+  D2O_HIP_CHECK(x, hipMemcpyAsync(&t, x->ctau + lbh, sizeof(double), hipMemcpyDeviceToHost, s));
+  D2O_HIP_CHECK(x, hipStreamSynchronize(s));
+  if (count) *count = cnt;
+  if (tau) *tau = t;
+  if (cnt <= 0) return D2O_OK;
+  const size_t slot0 = (size_t(b) * c.n_kv_heads + h) * c.slots_per_seq + st.meta[b].base;
+  const size_t row = size_t(c.head_dim) * x->esize;
+  std::vector<char> k(cnt * row), v(cnt * row);
+  std::vector<double> sc(cnt);
+  std::vector<int32_t> ps(cnt);
+  D2O_HIP_CHECK(x, hipMemcpyAsync(k.data(), static_cast<char*>(x->cacheK) + slot0 * row, cnt * row, hipMemcpyDeviceToHost, s));
+  D2O_HIP_CHECK(x, hipMemcpyAsync(v.data(), static_cast<char*>(x->cacheV) + slot0 * row, cnt * row, hipMemcpyDeviceToHost, s));
+  D2O_HIP_CHECK(x, hipMemcpyAsync(sc.data(), x->cscore + slot0, cnt * sizeof(double), hipMemcpyDeviceToHost, s));
+  D2O_HIP_CHECK(x, hipMemcpyAsync(ps.data(), x->cpos + slot0, cnt * sizeof(int32_t), hipMemcpyDeviceToHost, s));
+  D2O_HIP_CHECK(x, hipStreamSynchronize(s));
+  std::vector<int32_t> order(cnt);
+  std::iota(order.begin(), order.end(), 0);
+  std::sort(order.begin(), order.end(), [&](int a, int bb) { return ps[a] < ps[bb]; });
+  for (int i = 0; i < cnt; ++i) {
+    const int src = order[i];
+    if (K) std::memcpy(static_cast<char*>(K) + i * row, k.data() + src * row, row);
+    if (V) std::memcpy(static_cast<char*>(V) + i * row, v.data() + src * row, row);
+    if (score) score[i] = sc[src];
+    if (pos) pos[i] = ps[src];
+  }
+  return D2O_OK;
+}
+
+int d2o_cache_import(d2o_ctx* x, int32_t layer, int32_t b, int32_t h, const void* K, const void* V,
+                     const double* score, const int32_t* pos, int32_t count, double tau, int32_t next_pos,
+                     void* stream) {
+  if (!x || !K || !V || !score || !pos) return D2O_ERR_INVALID_ARG;
+  int rc = head_args_ok(x, layer, b, h);
+  if (rc) return rc;
+  const d2o_config& c = x->cfg;
+  LayerState& st = x->layers[layer];
+  if (st.phase != kReady) return fail(x, D2O_ERR_STATE, "layer not reserved");
+  if (count < 0 || count > st.meta[b].budget) return fail(x, D2O_ERR_INVALID_ARG, "count exceeds the budget");
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const size_t lbh = (size_t(layer) * c.batch + b) * c.n_kv_heads + h;
+  const size_t slot0 = (size_t(b) * c.n_kv_heads + h) * c.slots_per_seq + st.meta[b].base;
+  const size_t row = size_t(c.head_dim) * x->esize;
+  D2O_HIP_CHECK(x, hipMemcpyAsync(static_cast<char*>(x->cacheK) + slot0 * row, K, count * row, hipMemcpyHostToDevice, s));
+  D2O_HIP_CHECK(x, hipMemcpyAsync(static_cast<char*>(x->cacheV) + slot0 * row, V, count * row, hipMemcpyHostToDevice, s));
+  D2O_HIP_CHECK(x, hipMemcpyAsync(x->cscore + slot0, score, count * sizeof(double), hipMemcpyHostToDevice, s));
+  D2O_HIP_CHECK(x, hipMemcpyAsync(x->cpos + slot0, pos, count * sizeof(int32_t), hipMemcpyHostToDevice, s));
+  D2O_HIP_CHECK(x, hipMemcpyAsync(x->ccount + lbh, &count, sizeof(int32_t), hipMemcpyHostToDevice, s));
+  D2O_HIP_CHECK(x, hipMemcpyAsync(x->ctau + lbh, &tau, sizeof(double), hipMemcpyHostToDevice, s));
+  D2O_HIP_CHECK(x, hipStreamSynchronize(s));
+  st.next_pos = next_pos;
+  return D2O_OK;
+}
+
+int d2o_last_events(d2o_ctx* x, int32_t layer, int32_t* evicted_pos, int32_t* target_pos, double* u_star,
+                    void* stream) {
+  if (!x) return D2O_ERR_INVALID_ARG;
+  const d2o_config& c = x->cfg;
+  if (layer < 0 || layer >= c.n_layers) return fail(x, D2O_ERR_INVALID_ARG, "layer out of range");
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const size_t bh = size_t(c.batch) * c.n_kv_heads, off = size_t(layer) * bh;
+  if (evicted_pos) D2O_HIP_CHECK(x, hipMemcpyAsync(evicted_pos, x->ev_evicted + off, bh * sizeof(int32_t), hipMemcpyDeviceToHost, s));
+  if (target_pos) D2O_HIP_CHECK(x, hipMemcpyAsync(target_pos, x->ev_target + off, bh * sizeof(int32_t), hipMemcpyDeviceToHost, s));
+  if (u_star) D2O_HIP_CHECK(x, hipMemcpyAsync(u_star, x->ev_ustar + off, bh * sizeof(double), hipMemcpyDeviceToHost, s));
+  D2O_HIP_CHECK(x, hipStreamSynchronize(s));
+  return D2O_OK;
+}
+
+int d2o_prefill_events(d2o_ctx* x, int32_t layer, int32_t b, int32_t h, int32_t* retained_pos, int32_t* n_ret,
+                       int32_t* evicted_pos, int32_t* n_evi, int32_t* target_pos, double* u_star,
+                       uint8_t* passed, void* stream) {
+  if (!x) return D2O_ERR_INVALID_ARG;
+  int rc = head_args_ok(x, layer, b, h);
+  if (rc) return rc;
+  if (layer != x->last_compress_layer)
+    return fail(x, D2O_ERR_STATE, "prefill events are kept for the most recently compressed layer only");
+  const d2o_config& c = x->cfg;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const size_t bh = size_t(b) * c.n_kv_heads + h;
+  int32_t cnt[2] = {0, 0};
+  D2O_HIP_CHECK(x, hipMemcpyAsync(cnt, x->sel_cnt + bh * 2, 2 * sizeof(int32_t), hipMemcpyDeviceToHost, s));
+  D2O_HIP_CHECK(x, hipStreamSynchronize(s));
+  if (n_ret) *n_ret = cnt[0];
+  if (n_evi) *n_evi = cnt[1];
+  const size_t o = bh * x->npad;
+  std::vector<int32_t> ret(cnt[0]), tgt(cnt[1]);
+  D2O_HIP_CHECK(x, hipMemcpyAsync(ret.data(), x->sel_ret + o, cnt[0] * sizeof(int32_t), hipMemcpyDeviceToHost, s));
+  if (evicted_pos && cnt[1]) D2O_HIP_CHECK(x, hipMemcpyAsync(evicted_pos, x->sel_evi + o, cnt[1] * sizeof(int32_t), hipMemcpyDeviceToHost, s));
+  if (cnt[1]) D2O_HIP_CHECK(x, hipMemcpyAsync(tgt.data(), x->m_tgt + o, cnt[1] * sizeof(int32_t), hipMemcpyDeviceToHost, s));
+  if (u_star && cnt[1]) D2O_HIP_CHECK(x, hipMemcpyAsync(u_star, x->m_ustar + o, cnt[1] * sizeof(double), hipMemcpyDeviceToHost, s));
+  if (passed && cnt[1]) D2O_HIP_CHECK(x, hipMemcpyAsync(passed, x->m_pass + o, cnt[1], hipMemcpyDeviceToHost, s));
+  D2O_HIP_CHECK(x, hipStreamSynchronize(s));
+  if (retained_pos) std::memcpy(retained_pos, ret.data(), cnt[0] * sizeof(int32_t));
+  if (target_pos)
+    for (int i = 0; i < cnt[1]; ++i) target_pos[i] = ret[tgt[i]];
+  return D2O_OK;
+}
+
+}  // extern "C"

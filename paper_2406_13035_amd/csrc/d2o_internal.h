@@ -1,0 +1,124 @@
+// Internal declarations shared by the HIP sources of libd2o (not part of the C ABI).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <string>
+#include <vector>
+
+#include "d2o.h"
+
+namespace d2o {
+
+constexpr int kChunk = 256;        // cache slots handled by one workgroup in the decode kernels
+constexpr int kPrefillBM = 128;    // query rows per workgroup, prefill attention (bf16)
+constexpr int kColBN = 128;        // keys per workgroup, column-sum pass (bf16)
+
+// A strided [b][head][token][d] (or [layer][b][head][d]) tensor, strides in elements.
+struct View {
+  void* ptr;
+  int64_t sb, sh, sn;
+};
+
+inline View to_view(const d2o_view& v) { return View{v.ptr, v.stride_b, v.stride_h, v.stride_n}; }
+
+// Per-(layer, sequence) cache geometry, mirrored on the device as int32[4].
+struct LayerMeta {
+  int32_t base;        // first slot of this layer's region inside a (sequence, KV head) cache
+  int32_t budget;      // S_l
+  int32_t recent;      // M
+  int32_t chunk_base;  // first chunk index of this layer in the decode partial buffers
+};
+
+enum LayerPhase { kEmpty = 0, kAttended = 1, kReady = 2 };
+
+struct LayerState {
+  int phase = kEmpty;
+  int32_t n = 0;          // prompt length seen by the prefill calls
+  int32_t next_pos = 0;   // position of the next generated token
+  std::vector<LayerMeta> meta;  // [B]
+};
+
+}  // namespace d2o
+
+struct d2o_ctx {
+  d2o_config cfg;
+  std::string err;
+  std::vector<d2o::LayerState> layers;
+  std::vector<int64_t> used_slots;   // [B]
+  std::vector<int64_t> used_chunks;  // [B]
+  int32_t last_compress_layer = -1;
+  int32_t esize = 2;                 // bytes per element of Q/K/V/cache
+  int32_t npad = 0;                  // max_prompt_len rounded up to 128
+  int64_t nchunk_cap = 0;            // chunk slots per (sequence, KV head) in decode partials
+
+  // ---- persistent workspace (device) ----
+  float* score_pre = nullptr;    // [L][B][Hkv][npad]   cumulative prompt scores per key
+  double* head_var = nullptr;    // [L][B][Hq]          per-query-head variance of column sums
+  double* layer_F = nullptr;     // [L][B]              density statistic
+  void* cacheK = nullptr;        // [B][Hkv][slots][d]
+  void* cacheV = nullptr;        // [B][Hkv][slots][d]
+  double* cscore = nullptr;      // [B][Hkv][slots]
+  int32_t* cpos = nullptr;       // [B][Hkv][slots]
+  int32_t* ccount = nullptr;     // [L][B][Hkv]
+  double* ctau = nullptr;        // [L][B][Hkv]
+  int32_t* meta = nullptr;       // [L][B][4]
+  int32_t* ev_evicted = nullptr; // [L][B][Hkv]
+  int32_t* ev_target = nullptr;  // [L][B][Hkv]
+  double* ev_ustar = nullptr;    // [L][B][Hkv]
+
+  // ---- scratch workspace (device) ----
+  // prefill attention
+  float* lse = nullptr;          // [B][Hq][npad]   row log-sum-exp (natural log, scaled logits)
+  void* vt = nullptr;            // [B][Hkv][d][npad] transposed values (bf16 path)
+  double* varpart = nullptr;     // [B][Hq][npad/128][2] partial sums of s and s^2
+  // token-level prefill stages, all [B][Hkv][npad] unless noted
+  int32_t* sel_ret = nullptr;    // retained positions, ascending
+  int32_t* sel_evi = nullptr;    // evicted positions, ascending
+  int32_t* sel_cnt = nullptr;    // [B][Hkv][2]  n_ret, n_evi
+  float* invnorm = nullptr;      // 1/|k_j| of every prompt key (fp32, filter only)
+  int32_t* m_cand = nullptr;     // filter's best retained rank per evicted row; bit 31 = ambiguous
+  double* m_ustar = nullptr;     // exact best similarity per evicted row
+  int32_t* m_tgt = nullptr;      // exact match (retained rank)
+  uint8_t* m_pass = nullptr;     // threshold test
+  int32_t* g_cnt = nullptr;      // [..][npad+1] sources per retained slot
+  int32_t* g_off = nullptr;      // [..][npad+1] exclusive prefix of g_cnt
+  int32_t* g_cur = nullptr;      // [..][npad+1] fill cursors
+  int32_t* g_src = nullptr;      // evicted ranks grouped by target (unordered inside a group)
+  // decode
+  double* d_logit = nullptr;     // [B][Hq][slots]
+  double* d_pm = nullptr;        // [B][Hkv][nchunk][G]   chunk maxima
+  float* d_pl = nullptr;         // [B][Hkv][nchunk][G]   chunk exp-sums (relative to chunk max)
+  float* d_pacc = nullptr;       // [B][Hkv][nchunk][G][d] chunk partial outputs
+  int32_t* d_eslot = nullptr;    // [L][B][Hkv] slot chosen for eviction (-1 none)
+  double* d_cu = nullptr;        // [B][Hkv][nchunk] chunk best cosine
+  int32_t* d_cslot = nullptr;    // [B][Hkv][nchunk] its slot
+};
+
+namespace d2o {
+
+int fail(d2o_ctx* ctx, int code, const std::string& msg);
+
+#define D2O_HIP_CHECK(ctx, expr)                                                        \
+  do {                                                                                  \
+    hipError_t e_ = (expr);                                                             \
+    if (e_ != hipSuccess)                                                               \
+      return d2o::fail(ctx, D2O_ERR_HIP, std::string(#expr) + ": " + hipGetErrorString(e_)); \
+  } while (0)
+
+// ---- kernel launchers (one per stage), defined in the .hip files ----
+hipError_t launch_prefill_f32(d2o_ctx* c, int layer, View Q, View K, View V, View O, int n,
+                              hipStream_t s);
+hipError_t launch_prefill_bf16(d2o_ctx* c, int layer, View Q, View K, View V, View O, int n,
+                               hipStream_t s);
+hipError_t launch_density(d2o_ctx* c, int layer, int n, hipStream_t s);
+hipError_t launch_select(d2o_ctx* c, int layer, int n, hipStream_t s);
+hipError_t launch_gather(d2o_ctx* c, int layer, View K, View V, int n, hipStream_t s);
+hipError_t launch_match(d2o_ctx* c, int layer, View K, int n, hipStream_t s);
+hipError_t launch_threshold_group(d2o_ctx* c, int layer, int n, hipStream_t s);
+hipError_t launch_merge(d2o_ctx* c, int layer, View K, View V, int n, hipStream_t s);
+hipError_t launch_decode(d2o_ctx* c, int layer0, int nl, View q, View k, View v, View out,
+                         int new_pos, hipStream_t s);
+
+}  // namespace d2o

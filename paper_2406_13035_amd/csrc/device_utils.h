@@ -1,0 +1,85 @@
+// Small device helpers shared by the kernel files.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace d2o {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+
+// Storage element traits: float and bf16 (held as uint16_t).
+template <typename T>
+struct Elem;
+template <>
+struct Elem<float> {
+  static __device__ __forceinline__ double to_f64(float x) { return double(x); }
+  static __device__ __forceinline__ float to_f32(float x) { return x; }
+  static __device__ __forceinline__ float from_f64(double x) { return float(x); }
+  static __device__ __forceinline__ float from_f32(float x) { return x; }
+};
+template <>
+struct Elem<uint16_t> {
+  static __device__ __forceinline__ float to_f32(uint16_t x) { return __uint_as_float(uint32_t(x) << 16); }
+  static __device__ __forceinline__ double to_f64(uint16_t x) { return double(to_f32(x)); }
+  // fp64 -> bf16, round to nearest even, in one rounding (no detour through fp32 rounding):
+  // bf16 keeps 7 of the 52 fraction bits; values are far from bf16's exponent limits.
+  static __device__ __forceinline__ uint16_t from_f64(double x) {
+    unsigned long long b = (unsigned long long)__double_as_longlong(x);
+    const unsigned long long lsb = (b >> 45) & 1ull;
+    b = (b + ((1ull << 44) - 1ull) + lsb) & ~((1ull << 45) - 1ull);
+    const float f = float(__longlong_as_double((long long)b));  // exact: 8 significant bits
+    return uint16_t(__float_as_uint(f) >> 16);
+  }
+  static __device__ __forceinline__ uint16_t from_f32(float x) {
+    uint32_t b = __float_as_uint(x);
+    b += 0x7FFFu + ((b >> 16) & 1u);
+    return uint16_t(b >> 16);
+  }
+};
+
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+  return v;
+}
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+__device__ __forceinline__ double wave_sum(double v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+__device__ __forceinline__ double wave_max(double v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmax(v, __shfl_xor(v, o, 64));
+  return v;
+}
+__device__ __forceinline__ int wave_min(int v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = min(v, __shfl_xor(v, o, 64));
+  return v;
+}
+
+// Deterministic block-wide sum (fixed tree): every thread gets the total.
+// `buf` holds one double per wave; blockDim.x must be a multiple of 64 and <= 1024.
+__device__ __forceinline__ double block_sum(double v, double* buf) {
+  v = wave_sum(v);
+  const int w = threadIdx.x >> 6, nw = blockDim.x >> 6;
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) buf[w] = v;
+  __syncthreads();
+  double t = 0.0;
+  for (int i = 0; i < nw; ++i) t += buf[i];
+  return t;
+}
+
+}  // namespace d2o

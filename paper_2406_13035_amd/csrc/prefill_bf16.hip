@@ -1,0 +1,300 @@
+// Prompt-phase attention for bf16 tensors on the CDNA4 matrix cores (head_dim 128).
+//
+// Pass 1, attn_fwd_bf16 (Sec. 4.1 Eq. 4; Sec. 3 Eq. 3): row-stationary flash attention.  A
+//   workgroup owns 128 query rows (4 wavefronts x 32), streams 64-key tiles of K and of the
+//   pre-transposed V through LDS and keeps S^T = K Q^T in the MFMA accumulator layout, where
+//   one lane owns one query column: row maxima and sums are then in-register reductions.
+//   Emits O and the row log-sum-exp (base 2, of the scaled logits).
+// Pass 2, colsum_bf16 ("sum the elements of each column", Sec. 4.1; Eq. 6 prompt case):
+//   key-stationary.  A workgroup owns 128 keys, streams query tiles, recomputes S^T with the
+//   keys as the stationary MFMA operand, and accumulates P = exp2(S - lse) per key in
+//   registers; the column sums come out without atomics, the G query heads of a KV group are
+//   added in ascending order, and per-query-head partial sums of the column sums and their
+//   squares feed the variance of Eq. 4.
+// The column sums need every row's final normaliser, so they cannot come out of the single
+// online-softmax pass; the second QK^T product is implementation overhead.
+//
+// v_mfma_f32_32x32x16_bf16 operand layout (lane l, m = l % 32, h = l / 32):
+//   A[m][8h .. 8h+7], B[8h .. 8h+7][m], D[(r/4)*8 + 4h + r%4][m] for r = 0..15.
+#include "d2o_internal.h"
+#include "device_utils.h"
+
+namespace d2o {
+namespace {
+
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr int kD = 128;
+constexpr int kLdK = kD + 8;   // LDS row pitch (elements) of [token][d] tiles
+constexpr int kLdV = 64 + 8;   // LDS row pitch of the [d][key] tile
+
+// V [b][h][n][d] -> VT [b][h][d][npad], zero for keys >= n.
+__global__ __launch_bounds__(256) void transpose_v(const uint16_t* __restrict__ V, View vv, uint16_t* __restrict__ VT,
+                                                   int n, int npad) {
+  __shared__ uint16_t t[64][kD + 2];
+  const int k0 = blockIdx.x * 64, h = blockIdx.y, b = blockIdx.z, Hkv = gridDim.y;
+  const uint16_t* src = V + b * vv.sb + h * vv.sh;
+  for (int c = threadIdx.x; c < 64 * 16; c += 256) {
+    const int row = c >> 4, col = (c & 15) * 8;
+    u32x4 v = {0, 0, 0, 0};
+    if (k0 + row < n) v = *reinterpret_cast<const u32x4*>(src + int64_t(k0 + row) * vv.sn + col);
+    uint32_t* d = reinterpret_cast<uint32_t*>(&t[row][col]);
+    d[0] = v[0]; d[1] = v[1]; d[2] = v[2]; d[3] = v[3];
+  }
+  __syncthreads();
+  uint16_t* dst = VT + (int64_t(b) * Hkv + h) * kD * npad;
+  for (int c = threadIdx.x; c < kD * 8; c += 256) {
+    const int dd = c >> 3, kc = (c & 7) * 8;
+    uint16_t o[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) o[i] = t[kc + i][dd];
+    u32x4 v;
+    v[0] = o[0] | (uint32_t(o[1]) << 16); v[1] = o[2] | (uint32_t(o[3]) << 16);
+    v[2] = o[4] | (uint32_t(o[5]) << 16); v[3] = o[6] | (uint32_t(o[7]) << 16);
+    *reinterpret_cast<u32x4*>(dst + int64_t(dd) * npad + k0 + kc) = v;
+  }
+}
+
+// MFMA row m -> key offset inside a 32-key sub-tile, chosen so that accumulator registers
+// 8*kb .. 8*kb+7 of lane-half h hold the 8 consecutive keys 16*kb + 8*h .. +7: exactly the
+// B-operand slice the P V product needs, with no cross-lane movement.
+__device__ __forceinline__ int perm_key(int m) { return (m & ~0xC) | ((m & 4) << 1) | ((m & 8) >> 1); }
+
+__global__ __launch_bounds__(256) void attn_fwd_bf16(const uint16_t* __restrict__ Q, View qv,
+                                                     const uint16_t* __restrict__ K, View kv,
+                                                     const uint16_t* __restrict__ VT, uint16_t* __restrict__ O, View ov,
+                                                     float* __restrict__ lse2, int n, int npad, int G) {
+  __shared__ __attribute__((aligned(16))) uint16_t Ks[64 * kLdK];
+  __shared__ __attribute__((aligned(16))) uint16_t Vs[kD * kLdV];
+  const int nblk = gridDim.x;
+  const int rb = (nblk - 1 - blockIdx.x) * kPrefillBM;  // longest rows first
+  const int hq = blockIdx.y, b = blockIdx.z, Hq = gridDim.y, hk = hq / G, Hkv = Hq / G;
+  const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, m = lane & 31, h = lane >> 5;
+  const int q_row = rb + w * 32 + m;
+  const int wave_row_max = rb + w * 32 + 31;
+  const float scale2 = kLog2e / sqrtf(float(kD));
+
+  const uint16_t* qp = Q + b * qv.sb + hq * qv.sh + int64_t(min(q_row, n - 1)) * qv.sn;
+  bf16x8 bq[8];
+#pragma unroll
+  for (int ks = 0; ks < 8; ++ks) bq[ks] = *reinterpret_cast<const bf16x8*>(qp + ks * 16 + h * 8);
+
+  const uint16_t* kbase = K + b * kv.sb + hk * kv.sh;
+  const uint16_t* vtbase = VT + (int64_t(b) * Hkv + hk) * kD * npad;
+
+  f32x16 o[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) o[i][r] = 0.f;
+  float mrun = -INFINITY, lsum = 0.f;
+
+  const int last_key = min(rb + kPrefillBM - 1, n - 1);
+  const int ntile = last_key / 64 + 1;
+  const int krow = perm_key(m);
+  for (int t = 0; t < ntile; ++t) {
+    const int k0 = t * 64;
+    __syncthreads();
+    for (int c = tid; c < 64 * 16; c += 256) {
+      const int row = c >> 4, col = (c & 15) * 8;
+      const u32x4 v = *reinterpret_cast<const u32x4*>(kbase + int64_t(min(k0 + row, n - 1)) * kv.sn + col);
+      *reinterpret_cast<u32x4*>(&Ks[row * kLdK + col]) = v;
+    }
+    for (int c = tid; c < kD * 8; c += 256) {
+      const int dd = c >> 3, kc = (c & 7) * 8;
+      const u32x4 v = *reinterpret_cast<const u32x4*>(vtbase + int64_t(dd) * npad + k0 + kc);
+      *reinterpret_cast<u32x4*>(&Vs[dd * kLdV + kc]) = v;
+    }
+    __syncthreads();
+    if (k0 > wave_row_max) continue;  // whole tile is above this wavefront's diagonal
+
+    f32x16 s[2];
+#pragma unroll
+    for (int st = 0; st < 2; ++st) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) s[st][r] = 0.f;
+#pragma unroll
+      for (int ks = 0; ks < 8; ++ks) {
+        const bf16x8 a = *reinterpret_cast<const bf16x8*>(&Ks[(st * 32 + krow) * kLdK + ks * 16 + h * 8]);
+        s[st] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bq[ks], s[st], 0, 0, 0);
+      }
+    }
+    // register r of sub-tile st holds key k0 + 32*st + 16*(r/8) + 8*h + r%8 for query q_row
+    if (k0 + 63 > rb + w * 32) {  // tile touches the diagonal of this wavefront
+#pragma unroll
+      for (int st = 0; st < 2; ++st)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int key = k0 + st * 32 + (r >> 3) * 16 + h * 8 + (r & 7);
+          if (key > q_row) s[st][r] = -INFINITY;
+        }
+    }
+    float mx = s[0][0];
+#pragma unroll
+    for (int st = 0; st < 2; ++st)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[st][r]);
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    const float mnew = fmaxf(mrun, mx * scale2);
+    const float alpha = exp2f(mrun - mnew);
+    mrun = mnew;
+    float psum = 0.f;
+    bf16x8 pb[2][2];
+#pragma unroll
+    for (int st = 0; st < 2; ++st)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const float p = exp2f(fmaf(s[st][r], scale2, -mnew));
+        psum += p;
+        pb[st][r >> 3][r & 7] = (__bf16)p;
+      }
+    lsum = fmaf(lsum, alpha, psum);
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) o[i][r] *= alpha;
+#pragma unroll
+    for (int st = 0; st < 2; ++st)
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int dc = 0; dc < 4; ++dc) {
+          const bf16x8 a = *reinterpret_cast<const bf16x8*>(&Vs[(dc * 32 + m) * kLdV + st * 32 + kb * 16 + h * 8]);
+          o[dc] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb[st][kb], o[dc], 0, 0, 0);
+        }
+  }
+  const float ltot = lsum + __shfl_xor(lsum, 32, 64);
+  if (q_row < n) {
+    if (h == 0) lse2[(int64_t(b) * Hq + hq) * npad + q_row] = mrun + log2f(ltot);
+    if (O) {
+      const float inv = 1.f / ltot;
+      uint16_t* orow = O + b * ov.sb + hq * ov.sh + int64_t(q_row) * ov.sn;
+#pragma unroll
+      for (int dc = 0; dc < 4; ++dc)
+#pragma unroll
+        for (int rg = 0; rg < 4; ++rg) {
+          // registers 4*rg .. 4*rg+3 hold d = 32*dc + 8*rg + 4*h + 0..3
+          u32x2 v;
+          v[0] = Elem<uint16_t>::from_f32(o[dc][4 * rg + 0] * inv) |
+                 (uint32_t(Elem<uint16_t>::from_f32(o[dc][4 * rg + 1] * inv)) << 16);
+          v[1] = Elem<uint16_t>::from_f32(o[dc][4 * rg + 2] * inv) |
+                 (uint32_t(Elem<uint16_t>::from_f32(o[dc][4 * rg + 3] * inv)) << 16);
+          *reinterpret_cast<u32x2*>(orow + dc * 32 + rg * 8 + h * 4) = v;
+        }
+    }
+  }
+}
+
+__global__ __launch_bounds__(256) void colsum_bf16(const uint16_t* __restrict__ Q, View qv,
+                                                   const uint16_t* __restrict__ K, View kv,
+                                                   const float* __restrict__ lse2, float* __restrict__ score,
+                                                   double* __restrict__ varpart, int n, int npad, int G, int Hq) {
+  __shared__ __attribute__((aligned(16))) uint16_t Qs[64 * kLdK];
+  __shared__ float ls[64];
+  __shared__ float cs[128];
+  __shared__ double red[4];
+  const int tile = blockIdx.x, hk = blockIdx.y, b = blockIdx.z, Hkv = gridDim.y;
+  const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, m = lane & 31, h = lane >> 5;
+  const int kb0 = tile * kColBN, kw0 = kb0 + w * 32;  // first key of the workgroup / wavefront
+  const float scale2 = kLog2e / sqrtf(float(kD));
+
+  const uint16_t* kp = K + b * kv.sb + hk * kv.sh + int64_t(min(kw0 + m, n - 1)) * kv.sn;
+  bf16x8 ak[8];
+#pragma unroll
+  for (int ks = 0; ks < 8; ++ks) ak[ks] = *reinterpret_cast<const bf16x8*>(kp + ks * 16 + h * 8);
+
+  float total = 0.f;  // thread t < 128 owns key kb0 + t
+  for (int g = 0; g < G; ++g) {
+    const int hq = hk * G + g;
+    const uint16_t* qb = Q + b * qv.sb + hq * qv.sh;
+    const float* lrow = lse2 + (int64_t(b) * Hq + hq) * npad;
+    float acc[16];
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+    for (int q0 = kb0 & ~63; q0 < n; q0 += 64) {
+      __syncthreads();
+      for (int c = tid; c < 64 * 16; c += 256) {
+        const int row = c >> 4, col = (c & 15) * 8;
+        const u32x4 v = *reinterpret_cast<const u32x4*>(qb + int64_t(min(q0 + row, n - 1)) * qv.sn + col);
+        *reinterpret_cast<u32x4*>(&Qs[row * kLdK + col]) = v;
+      }
+      if (tid < 64) ls[tid] = (q0 + tid < n) ? lrow[q0 + tid] : INFINITY;  // +inf => p = 0
+      __syncthreads();
+#pragma unroll
+      for (int qt = 0; qt < 2; ++qt) {
+        const int qbase = q0 + qt * 32;
+        if (qbase + 31 < kw0) continue;  // every query precedes every key of this wavefront
+        f32x16 s;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) s[r] = 0.f;
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) {
+          const bf16x8 bqv = *reinterpret_cast<const bf16x8*>(&Qs[(qt * 32 + m) * kLdK + ks * 16 + h * 8]);
+          s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ak[ks], bqv, s, 0, 0, 0);
+        }
+        // register r: key kw0 + (r/4)*8 + 4h + r%4, query qbase + m
+        const float lq = ls[qt * 32 + m];
+        const int query = qbase + m;
+        if (qbase < kw0 + 31) {  // diagonal tile: mask query < key
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const int key = kw0 + (r >> 2) * 8 + h * 4 + (r & 3);
+            const float p = exp2f(fmaf(s[r], scale2, -lq));
+            acc[r] += (query >= key) ? p : 0.f;
+          }
+        } else {
+#pragma unroll
+          for (int r = 0; r < 16; ++r) acc[r] += exp2f(fmaf(s[r], scale2, -lq));
+        }
+      }
+    }
+    // add the 32 query columns held by the lanes of each half
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      float v = acc[r];
+#pragma unroll
+      for (int o = 16; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+      acc[r] = v;
+    }
+    __syncthreads();
+    if (m == 0) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) cs[w * 32 + (r >> 2) * 8 + h * 4 + (r & 3)] = acc[r];
+    }
+    __syncthreads();
+    double s1 = 0.0, s2 = 0.0;
+    if (tid < 128 && kb0 + tid < n) {
+      const float c = cs[tid];
+      total += c;
+      s1 = double(c);
+      s2 = double(c) * double(c);
+    }
+    s1 = block_sum(s1, red);
+    s2 = block_sum(s2, red);
+    if (tid == 0) {
+      double* vp = varpart + ((int64_t(b) * Hq + hq) * (npad / 128) + tile) * 2;
+      vp[0] = s1;
+      vp[1] = s2;
+    }
+  }
+  if (tid < 128 && kb0 + tid < n) score[(int64_t(b) * Hkv + hk) * npad + kb0 + tid] = total;
+}
+
+}  // namespace
+
+hipError_t launch_prefill_bf16(d2o_ctx* c, int layer, View Q, View K, View V, View O, int n, hipStream_t s) {
+  const d2o_config& cf = c->cfg;
+  const int G = cf.n_q_heads / cf.n_kv_heads;
+  float* score = c->score_pre + size_t(layer) * cf.batch * cf.n_kv_heads * c->npad;
+  const int nblk = (n + 127) / 128;
+  transpose_v<<<dim3(c->npad / 64, cf.n_kv_heads, cf.batch), 256, 0, s>>>((const uint16_t*)V.ptr, V,
+                                                                         (uint16_t*)c->vt, n, c->npad);
+  attn_fwd_bf16<<<dim3(nblk, cf.n_q_heads, cf.batch), 256, 0, s>>>((const uint16_t*)Q.ptr, Q, (const uint16_t*)K.ptr, K,
+                                                                  (const uint16_t*)c->vt, (uint16_t*)O.ptr, O, c->lse,
+                                                                  n, c->npad, G);
+  colsum_bf16<<<dim3(nblk, cf.n_kv_heads, cf.batch), 256, 0, s>>>((const uint16_t*)Q.ptr, Q, (const uint16_t*)K.ptr, K,
+                                                                 c->lse, score, c->varpart, n, c->npad, G,
+                                                                 cf.n_q_heads);
+  return hipGetLastError();
+}
+
+}  // namespace d2o

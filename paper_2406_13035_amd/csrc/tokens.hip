@@ -1,0 +1,614 @@
+// Token-level operation after prompt encoding (Sec. 4.2): selection (Eq. 7-8), compaction into
+// the cache, nearest-neighbour matching (Eq. 9), the initial threshold (Eq. 10, t = 0) and the
+// similarity-weighted merge (Eq. 11-12).
+//
+// Every decision (top-N membership, arg-max of the cosine, threshold test) is taken on exact
+// integer keys or in fp64 with the operation order of the defining formulas, so that index
+// outputs do not depend on reduction shapes; the bf16 matrix-core product in match_filter_bf16
+// only pre-selects candidates and flags rows whose two best candidates are too close for fp32.
+#include "d2o_internal.h"
+#include "device_utils.h"
+
+namespace d2o {
+namespace {
+
+// ------------------------------------------------------------------------------------------
+// Selection.  One workgroup per (sequence, KV head).  Radix-select of the N_hh-th largest
+// score among positions [T, n-M) on order-preserving 32-bit keys, then an ordered compaction
+// that keeps, among keys equal to the threshold, the lowest positions first.
+
+__device__ __forceinline__ uint32_t order_key(float x) {
+  if (x == 0.f) x = 0.f;  // -0 and +0 compare equal
+  const uint32_t b = __float_as_uint(x);
+  return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
+}
+
+// Exclusive prefix sums of two 0/1 flags over the block, in thread order.  Returns the
+// exclusive counts and adds the block totals to *tot_a / *tot_b (read by all threads).
+__device__ __forceinline__ void block_scan2(bool fa, bool fb, int& ex_a, int& ex_b, int& tot_a, int& tot_b,
+                                            int* wa, int* wb) {
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, nw = blockDim.x >> 6;
+  const unsigned long long ma = __ballot(fa), mb = __ballot(fb);
+  const unsigned long long below = (lane == 0) ? 0ull : (~0ull >> (64 - lane));
+  const int pa = __popcll(ma & below), pb = __popcll(mb & below);
+  __syncthreads();
+  if (lane == 0) {
+    wa[w] = __popcll(ma);
+    wb[w] = __popcll(mb);
+  }
+  __syncthreads();
+  int oa = 0, ob = 0, ta = 0, tb = 0;
+  for (int i = 0; i < nw; ++i) {
+    if (i < w) {
+      oa += wa[i];
+      ob += wb[i];
+    }
+    ta += wa[i];
+    tb += wb[i];
+  }
+  ex_a = oa + pa;
+  ex_b = ob + pb;
+  tot_a = ta;
+  tot_b = tb;
+}
+
+__global__ __launch_bounds__(1024) void select_kernel(const float* __restrict__ score, const int32_t* __restrict__ meta,
+                                                      int32_t* __restrict__ ret, int32_t* __restrict__ evi,
+                                                      int32_t* __restrict__ cnt, int n, int npad, int n_sink) {
+  __shared__ int hist[256];
+  __shared__ int wa[16], wb[16];
+  __shared__ uint32_t sh_prefix;
+  __shared__ int sh_need;
+  const int hk = blockIdx.x, b = blockIdx.y, Hkv = gridDim.x;
+  const int64_t bh = int64_t(b) * Hkv + hk;
+  const float* sc = score + bh * npad;
+  int32_t* r = ret + bh * npad;
+  int32_t* e = evi + bh * npad;
+  const int budget = meta[b * 4 + 1], recent = meta[b * 4 + 2];
+  const int tid = threadIdx.x;
+  if (budget >= n) {
+    for (int j = tid; j < n; j += blockDim.x) r[j] = j;
+    if (tid == 0) {
+      cnt[bh * 2] = n;
+      cnt[bh * 2 + 1] = 0;
+    }
+    return;
+  }
+  const int lo = n_sink, hi = n - recent;   // middle range [lo, hi)
+  const int nhh = budget - n_sink - recent;  // heavy hitters to keep, 0 <= nhh < hi - lo
+  // ---- radix select: find the key value of the nhh-th largest and how many equal keys to take
+  uint32_t prefix = 0, mask = 0;
+  int need = nhh;
+  if (nhh > 0) {
+    for (int shift = 24; shift >= 0; shift -= 8) {
+      for (int i = tid; i < 256; i += blockDim.x) hist[i] = 0;
+      __syncthreads();
+      for (int j = lo + tid; j < hi; j += blockDim.x) {
+        const uint32_t k = order_key(sc[j]);
+        if ((k & mask) == prefix) atomicAdd(&hist[(k >> shift) & 255], 1);
+      }
+      __syncthreads();
+      if (tid == 0) {
+        int rem = need, bin = 255;
+        for (; bin > 0; --bin) {
+          if (hist[bin] >= rem) break;
+          rem -= hist[bin];
+        }
+        sh_prefix = prefix | (uint32_t(bin) << shift);
+        sh_need = rem;
+      }
+      __syncthreads();
+      prefix = sh_prefix;
+      need = sh_need;
+      mask |= 0xFFu << shift;
+      __syncthreads();
+    }
+  }
+  // prefix = threshold key; `need` of the keys equal to it are kept, lowest positions first
+  int base_keep = 0, base_eq = 0;
+  for (int j0 = 0; j0 < n; j0 += blockDim.x) {
+    const int j = j0 + tid;
+    bool keep = false, eq = false;
+    if (j < n) {
+      if (j < lo || j >= hi) {
+        keep = true;
+      } else if (nhh > 0) {
+        const uint32_t k = order_key(sc[j]);
+        keep = k > prefix;
+        eq = k == prefix;
+      }
+    }
+    int ex_eq, ex_dummy, tot_eq, tot_dummy;
+    block_scan2(eq, false, ex_eq, ex_dummy, tot_eq, tot_dummy, wa, wb);
+    if (eq && base_eq + ex_eq < need) keep = true;
+    int ex_keep, tot_keep;
+    block_scan2(keep, false, ex_keep, ex_dummy, tot_keep, tot_dummy, wa, wb);
+    if (j < n) {
+      if (keep)
+        r[base_keep + ex_keep] = j;
+      else
+        e[j - (base_keep + ex_keep)] = j;
+    }
+    base_keep += tot_keep;
+    base_eq += tot_eq;
+  }
+  if (tid == 0) {
+    cnt[bh * 2] = base_keep;
+    cnt[bh * 2 + 1] = n - base_keep;
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// Compaction: retained rows of K, V into the layer's cache region; scores widen to fp64.
+template <typename T>
+__global__ __launch_bounds__(256) void gather_kernel(const T* __restrict__ K, View kv, const T* __restrict__ V, View vv,
+                                                     const float* __restrict__ score, const int32_t* __restrict__ ret,
+                                                     const int32_t* __restrict__ cnt, const int32_t* __restrict__ meta,
+                                                     T* __restrict__ cK, T* __restrict__ cV, double* __restrict__ cscore,
+                                                     int32_t* __restrict__ cpos, int32_t* __restrict__ ccount,
+                                                     int npad, int d, int64_t slots) {
+  const int hk = blockIdx.y, b = blockIdx.z, Hkv = gridDim.y;
+  const int64_t bh = int64_t(b) * Hkv + hk;
+  const int nret = cnt[bh * 2];
+  constexpr int kVec = 16 / sizeof(T);
+  const int tpr = d / kVec;                 // threads per row
+  const int rows_per_blk = 256 / tpr;
+  const int slot = blockIdx.x * rows_per_blk + threadIdx.x / tpr;
+  if (blockIdx.x == 0 && threadIdx.x == 0) ccount[bh] = nret;
+  if (slot >= nret) return;
+  const int c = (threadIdx.x % tpr) * kVec;
+  const int pos = ret[bh * npad + slot];
+  const int64_t dst = (bh * slots + meta[b * 4 + 0] + slot);
+  *reinterpret_cast<u32x4*>(cK + dst * d + c) =
+      *reinterpret_cast<const u32x4*>(K + b * kv.sb + hk * kv.sh + int64_t(pos) * kv.sn + c);
+  *reinterpret_cast<u32x4*>(cV + dst * d + c) =
+      *reinterpret_cast<const u32x4*>(V + b * vv.sb + hk * vv.sh + int64_t(pos) * vv.sn + c);
+  if (c == 0) {
+    cscore[dst] = double(score[bh * npad + pos]);
+    cpos[dst] = pos;
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// Matching.
+
+// 1/|k_j| in fp32 for every prompt key (used by the bf16 candidate filter only).
+__global__ __launch_bounds__(256) void invnorm_bf16(const uint16_t* __restrict__ K, View kv, float* __restrict__ invn,
+                                                    int n, int npad) {
+  const int hk = blockIdx.y, b = blockIdx.z, Hkv = gridDim.y;
+  const int row = blockIdx.x * 16 + threadIdx.x / 16, c = (threadIdx.x % 16) * 8;
+  float s = 0.f;
+  if (row < n) {
+    const u32x4 v = *reinterpret_cast<const u32x4*>(K + b * kv.sb + hk * kv.sh + int64_t(row) * kv.sn + c);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const float lo = __uint_as_float(v[i] << 16), hi = __uint_as_float(v[i] & 0xFFFF0000u);
+      s = fmaf(lo, lo, s);
+      s = fmaf(hi, hi, s);
+    }
+  }
+#pragma unroll
+  for (int o = 8; o > 0; o >>= 1) s += __shfl_xor(s, o, 64);
+  if (row < n && (threadIdx.x % 16) == 0)
+    invn[(int64_t(b) * Hkv + hk) * npad + row] = s > 0.f ? 1.0f / sqrtf(s) : 0.f;
+}
+
+// Candidate filter on the matrix cores.  A workgroup owns 128 evicted rows (4 wavefronts x 32,
+// the stationary B operand) and streams the retained keys in tiles of 128 through LDS (the A
+// operand), so each lane owns one evicted row and sees 16 retained keys per MFMA tile.
+// Per row it tracks the best and second-best fp32 cosine and the best's retained rank; a row
+// whose two best values differ by less than kAmbiguous is flagged for the exact search.
+constexpr float kAmbiguous = 1.0e-4f;  // > 2 * (128 * 2^-23 + fp32 norm error): see match_refine
+constexpr int kLdM = 128 + 8;
+
+__global__ __launch_bounds__(256) void match_filter_bf16(const uint16_t* __restrict__ K, View kv,
+                                                         const float* __restrict__ invn,
+                                                         const int32_t* __restrict__ ret,
+                                                         const int32_t* __restrict__ evi,
+                                                         const int32_t* __restrict__ cnt, int32_t* __restrict__ cand,
+                                                         int npad) {
+  __shared__ __attribute__((aligned(16))) uint16_t Rs[128 * kLdM];
+  __shared__ float rin[128];   // 1/|k| of the staged retained keys
+  __shared__ float rbias[128];  // 0, or -inf for padding rows
+  const int hk = blockIdx.y, b = blockIdx.z, Hkv = gridDim.y;
+  const int64_t bh = int64_t(b) * Hkv + hk;
+  const int nret = cnt[bh * 2], nevi = cnt[bh * 2 + 1];
+  const int e0 = blockIdx.x * 128;
+  if (e0 >= nevi) return;
+  const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, m = lane & 31, h = lane >> 5;
+  const uint16_t* kb = K + b * kv.sb + hk * kv.sh;
+  const int32_t* rl = ret + bh * npad;
+  const int32_t* el = evi + bh * npad;
+  const float* inl = invn + bh * npad;
+  const int erank = e0 + w * 32 + m;
+  const int epos = el[min(erank, nevi - 1)];
+  bf16x8 be[8];
+#pragma unroll
+  for (int ks = 0; ks < 8; ++ks)
+    be[ks] = *reinterpret_cast<const bf16x8*>(kb + int64_t(epos) * kv.sn + ks * 16 + h * 8);
+  float m1 = -INFINITY, m2 = -INFINITY;
+  int i1 = 0;
+  for (int r0 = 0; r0 < nret; r0 += 128) {
+    __syncthreads();
+    for (int c = tid; c < 128 * 16; c += 256) {
+      const int row = c >> 4, col = (c & 15) * 8;
+      const int pos = rl[min(r0 + row, nret - 1)];
+      *reinterpret_cast<u32x4*>(&Rs[row * kLdM + col]) =
+          *reinterpret_cast<const u32x4*>(kb + int64_t(pos) * kv.sn + col);
+    }
+    if (tid < 128) {
+      const bool ok = r0 + tid < nret;
+      rin[tid] = ok ? inl[rl[r0 + tid]] : 0.f;
+      rbias[tid] = ok ? 0.f : -INFINITY;
+    }
+    __syncthreads();
+    const int nsub = min(4, (nret - r0 + 31) / 32);
+    for (int st = 0; st < nsub; ++st) {
+      f32x16 s;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) s[r] = 0.f;
+#pragma unroll
+      for (int ks = 0; ks < 8; ++ks) {
+        const bf16x8 a = *reinterpret_cast<const bf16x8*>(&Rs[(st * 32 + m) * kLdM + ks * 16 + h * 8]);
+        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, be[ks], s, 0, 0, 0);
+      }
+      // register r: retained row st*32 + (r/4)*8 + 4h + r%4 of this stage, evicted row = lane's
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int rr = st * 32 + (r >> 2) * 8 + h * 4 + (r & 3);
+        const float t = fmaf(s[r], rin[rr], rbias[rr]);
+        const bool gt = t > m1;
+        i1 = gt ? (r0 + rr) : i1;
+        m2 = __builtin_amdgcn_fmed3f(m1, m2, t);
+        m1 = fmaxf(m1, t);
+      }
+    }
+  }
+  // combine the two lane halves that share an evicted row
+  const float om1 = __shfl_xor(m1, 32, 64), om2 = __shfl_xor(m2, 32, 64);
+  const int oi1 = __shfl_xor(i1, 32, 64);
+  const float best = fmaxf(m1, om1);
+  const float second = fmaxf(fminf(m1, om1), fmaxf(m2, om2));
+  const int bi = (om1 > m1) ? oi1 : i1;
+  if (h == 0 && erank < nevi) {
+    const float ie = inl[epos];
+    const bool amb = !((best - second) * ie >= kAmbiguous);  // also true for NaN / equal
+    cand[bh * npad + erank] = bi | (amb ? int(0x80000000u) : 0);
+  }
+}
+
+// Exact similarity in fp64, operation order of Eq. 9 as written: dot / (|k_i| * |k_j|), 0 when
+// a norm is 0.  One wavefront per evicted row.  Unambiguous rows evaluate their candidate only;
+// ambiguous rows (and every row when no filter ran) search all retained keys, first maximum in
+// ascending retained order.  Products of bf16 values are exact in fp64 and their sums stay
+// exact at these magnitudes, so the result does not depend on the summation tree.
+template <typename T>
+__device__ __forceinline__ void load8(const T* p, double* out);
+template <>
+__device__ __forceinline__ void load8<uint16_t>(const uint16_t* p, double* out) {
+  const u32x4 v = *reinterpret_cast<const u32x4*>(p);
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    out[2 * i] = double(__uint_as_float(v[i] << 16));
+    out[2 * i + 1] = double(__uint_as_float(v[i] & 0xFFFF0000u));
+  }
+}
+template <>
+__device__ __forceinline__ void load8<float>(const float* p, double* out) {
+  const float4 a = reinterpret_cast<const float4*>(p)[0], b = reinterpret_cast<const float4*>(p)[1];
+  out[0] = a.x; out[1] = a.y; out[2] = a.z; out[3] = a.w;
+  out[4] = b.x; out[5] = b.y; out[6] = b.z; out[7] = b.w;
+}
+
+template <typename T, int D>
+__global__ __launch_bounds__(256) void match_refine(const T* __restrict__ K, View kv, const int32_t* __restrict__ ret,
+                                                    const int32_t* __restrict__ evi, const int32_t* __restrict__ cnt,
+                                                    const int32_t* __restrict__ cand, double* __restrict__ ustar,
+                                                    int32_t* __restrict__ tgt, int npad, int use_filter) {
+  __shared__ double ke[4][D];
+  const int hk = blockIdx.y, b = blockIdx.z, Hkv = gridDim.y;
+  const int64_t bh = int64_t(b) * Hkv + hk;
+  const int nret = cnt[bh * 2], nevi = cnt[bh * 2 + 1];
+  const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  if (int(blockIdx.x) * 4 >= nevi) return;  // block-uniform
+  const int erank_raw = blockIdx.x * 4 + w;
+  const bool valid = erank_raw < nevi;
+  const int erank = valid ? erank_raw : nevi - 1;
+  const T* kb = K + b * kv.sb + hk * kv.sh;
+  const int32_t* rl = ret + bh * npad;
+  const int epos = evi[bh * npad + erank];
+  const T* er = kb + int64_t(epos) * kv.sn;
+  double ne = 0.0;
+  for (int c = lane; c < D; c += 64) {
+    const double x = Elem<T>::to_f64(er[c]);
+    ke[w][c] = x;
+    ne += x * x;
+  }
+  __syncthreads();
+  ne = wave_sum(ne);
+  const double sne = sqrt(ne);
+  const int cnd = use_filter ? cand[bh * npad + erank] : int(0x80000000u);
+  double best = -2.0;
+  int bj = 0x7FFFFFFF;
+  if (cnd >= 0) {
+    const T* rr = kb + int64_t(rl[cnd]) * kv.sn;
+    double dot = 0.0, nr = 0.0;
+    for (int c = lane; c < D; c += 64) {
+      const double y = Elem<T>::to_f64(rr[c]);
+      dot += ke[w][c] * y;
+      nr += y * y;
+    }
+    dot = wave_sum(dot);
+    nr = wave_sum(nr);
+    const double den = sne * sqrt(nr);
+    best = den > 0.0 ? dot / den : 0.0;
+    bj = cnd;
+  } else {
+    for (int j = lane; j < nret; j += 64) {
+      const T* rr = kb + int64_t(rl[j]) * kv.sn;
+      double dot = 0.0, nr = 0.0;
+      for (int c = 0; c < D; c += 8) {
+        double y[8];
+        load8<T>(rr + c, y);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          dot += ke[w][c + i] * y[i];
+          nr += y[i] * y[i];
+        }
+      }
+      const double den = sne * sqrt(nr);
+      const double u = den > 0.0 ? dot / den : 0.0;
+      if (u > best) {  // j ascends within a lane: strict > keeps the first maximum
+        best = u;
+        bj = j;
+      }
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+      const double ob = __shfl_xor(best, o, 64);
+      const int oj = __shfl_xor(bj, o, 64);
+      if (ob > best || (ob == best && oj < bj)) {
+        best = ob;
+        bj = oj;
+      }
+    }
+  }
+  if (lane == 0 && valid) {
+    ustar[bh * npad + erank] = best;
+    tgt[bh * npad + erank] = bj;
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// Threshold (Eq. 10, t = 0) and grouping of the passing tokens by target.  One workgroup per
+// (sequence, KV head).  Group members are stored unordered; merge_kernel visits them in
+// ascending evicted order.
+__global__ __launch_bounds__(1024) void threshold_group_kernel(const double* __restrict__ ustar,
+                                                               const int32_t* __restrict__ tgt,
+                                                               const int32_t* __restrict__ cnt, uint8_t* __restrict__ pass,
+                                                               int32_t* __restrict__ gcnt, int32_t* __restrict__ goff,
+                                                               int32_t* __restrict__ gcur, int32_t* __restrict__ gsrc,
+                                                               double* __restrict__ tau_out, int npad, double tau_force) {
+  __shared__ double red[16];
+  __shared__ int wa[16], wb[16];
+  const int hk = blockIdx.x, b = blockIdx.y, Hkv = gridDim.x;
+  const int64_t bh = int64_t(b) * Hkv + hk;
+  const int nret = cnt[bh * 2], nevi = cnt[bh * 2 + 1];
+  const int tid = threadIdx.x;
+  const double* us = ustar + bh * npad;
+  const int32_t* tg = tgt + bh * npad;
+  uint8_t* ps = pass + bh * npad;
+  int32_t* gc = gcnt + bh * (npad + 1);
+  int32_t* go = goff + bh * (npad + 1);
+  int32_t* gu = gcur + bh * (npad + 1);
+  int32_t* gs = gsrc + bh * npad;
+  if (nevi == 0) {
+    for (int j = tid; j <= nret; j += blockDim.x) gc[j] = 0;
+    return;  // tau stays unset (NaN)
+  }
+  double part = 0.0;
+  for (int i = tid; i < nevi; i += blockDim.x) part += us[i];
+  const double tau = block_sum(part, red) / double(nevi);
+  if (tid == 0) tau_out[bh] = tau;
+  const double thr = isnan(tau_force) ? tau : tau_force;
+  for (int j = tid; j <= nret; j += blockDim.x) {
+    gc[j] = 0;
+    gu[j] = 0;
+  }
+  __syncthreads();
+  for (int i = tid; i < nevi; i += blockDim.x) {
+    const bool ok = us[i] >= thr;
+    ps[i] = ok ? 1 : 0;
+    if (ok) atomicAdd(&gc[tg[i]], 1);
+  }
+  __syncthreads();
+  // exclusive prefix of gc over [0, nret]
+  int base = 0;
+  for (int j0 = 0; j0 <= nret; j0 += blockDim.x) {
+    const int j = j0 + tid;
+    const int v = (j < nret) ? gc[j] : 0;
+    // inclusive scan within the wavefront
+    int inc = v;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+      const int t = __shfl_up(inc, o, 64);
+      if ((tid & 63) >= o) inc += t;
+    }
+    __syncthreads();
+    if ((tid & 63) == 63) wa[tid >> 6] = inc;
+    __syncthreads();
+    int woff = 0, tot = 0;
+    for (int i = 0; i < int(blockDim.x >> 6); ++i) {
+      if (i < (tid >> 6)) woff += wa[i];
+      tot += wa[i];
+    }
+    if (j <= nret) go[j] = base + woff + inc - v;
+    base += tot;
+  }
+  __syncthreads();
+  for (int i = tid; i < nevi; i += blockDim.x) {
+    if (ps[i]) {
+      const int t = tg[i];
+      const int k = atomicAdd(&gu[t], 1);
+      gs[go[t] + k] = i;
+    }
+  }
+  (void)wb;
+}
+
+// Merge (Eq. 11-12).  One wavefront per retained slot that has sources.  fp64, operation order
+// of the definition: acc = e * k_c; for each source in ascending evicted order: w = exp(u),
+// Z += w, acc += w * k_e; result acc / Z rounded once to the cache dtype.  Products and sums
+// are kept unfused so the sequence is the one written in the formula.
+template <typename T, int D>
+__global__ __launch_bounds__(256) void merge_kernel(const T* __restrict__ K, View kv, const T* __restrict__ V, View vv,
+                                                    const int32_t* __restrict__ evi, const int32_t* __restrict__ cnt,
+                                                    const double* __restrict__ ustar, const int32_t* __restrict__ gcnt,
+                                                    const int32_t* __restrict__ goff, const int32_t* __restrict__ gsrc,
+                                                    const int32_t* __restrict__ meta, T* __restrict__ cK,
+                                                    T* __restrict__ cV, int npad, int64_t slots) {
+  const int hk = blockIdx.y, b = blockIdx.z, Hkv = gridDim.y;
+  const int64_t bh = int64_t(b) * Hkv + hk;
+  const int nret = cnt[bh * 2];
+  const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int slot = blockIdx.x * 4 + w;
+  if (slot >= nret) return;
+  const int ns = gcnt[bh * (npad + 1) + slot];
+  if (ns == 0) return;
+  const int32_t* src = gsrc + bh * npad + goff[bh * (npad + 1) + slot];
+  const int32_t* el = evi + bh * npad;
+  const double* us = ustar + bh * npad;
+  const T* kb = K + b * kv.sb + hk * kv.sh;
+  const T* vb = V + b * vv.sb + hk * vv.sh;
+  constexpr int PER = D / 64;
+  const int64_t dst = (bh * slots + meta[b * 4 + 0] + slot) * D;
+  const double e1 = 2.718281828459045;  // exp(1), the retained token's self-similarity weight
+  double ak[PER], av[PER];
+#pragma unroll
+  for (int p = 0; p < PER; ++p) {
+    ak[p] = __dmul_rn(e1, Elem<T>::to_f64(cK[dst + lane + 64 * p]));
+    av[p] = __dmul_rn(e1, Elem<T>::to_f64(cV[dst + lane + 64 * p]));
+  }
+  double z = e1;
+  int prev = -1;
+  for (int s = 0; s < ns; ++s) {
+    int cur = 0x7FFFFFFF;
+    for (int t = lane; t < ns; t += 64) {
+      const int r = src[t];
+      if (r > prev && r < cur) cur = r;
+    }
+    cur = wave_min(cur);
+    const double wgt = exp(us[cur]);
+    z = __dadd_rn(z, wgt);
+    const int64_t pos = el[cur];
+#pragma unroll
+    for (int p = 0; p < PER; ++p) {
+      ak[p] = __dadd_rn(ak[p], __dmul_rn(wgt, Elem<T>::to_f64(kb[pos * kv.sn + lane + 64 * p])));
+      av[p] = __dadd_rn(av[p], __dmul_rn(wgt, Elem<T>::to_f64(vb[pos * vv.sn + lane + 64 * p])));
+    }
+    prev = cur;
+  }
+#pragma unroll
+  for (int p = 0; p < PER; ++p) {
+    cK[dst + lane + 64 * p] = Elem<T>::from_f64(ak[p] / z);
+    cV[dst + lane + 64 * p] = Elem<T>::from_f64(av[p] / z);
+  }
+}
+
+}  // namespace
+
+// ---------------------------------------------------------------------------------------------
+
+hipError_t launch_select(d2o_ctx* c, int layer, int n, hipStream_t s) {
+  const d2o_config& cf = c->cfg;
+  const float* score = c->score_pre + size_t(layer) * cf.batch * cf.n_kv_heads * c->npad;
+  select_kernel<<<dim3(cf.n_kv_heads, cf.batch), 1024, 0, s>>>(score, c->meta + size_t(layer) * cf.batch * 4,
+                                                               c->sel_ret, c->sel_evi, c->sel_cnt, n, c->npad,
+                                                               cf.n_sink);
+  return hipGetLastError();
+}
+
+hipError_t launch_gather(d2o_ctx* c, int layer, View K, View V, int n, hipStream_t s) {
+  const d2o_config& cf = c->cfg;
+  const float* score = c->score_pre + size_t(layer) * cf.batch * cf.n_kv_heads * c->npad;
+  const int32_t* meta = c->meta + size_t(layer) * cf.batch * 4;
+  int32_t* ccount = c->ccount + size_t(layer) * cf.batch * cf.n_kv_heads;
+  int max_budget = 0;
+  for (const auto& mt : c->layers[layer].meta) max_budget = std::max(max_budget, std::min(mt.budget, n));
+  if (cf.dtype == D2O_BF16) {
+    const int rows = 256 / (cf.head_dim / 8);
+    gather_kernel<uint16_t><<<dim3((max_budget + rows - 1) / rows, cf.n_kv_heads, cf.batch), 256, 0, s>>>(
+        (const uint16_t*)K.ptr, K, (const uint16_t*)V.ptr, V, score, c->sel_ret, c->sel_cnt, meta,
+        (uint16_t*)c->cacheK, (uint16_t*)c->cacheV, c->cscore, c->cpos, ccount, c->npad, cf.head_dim,
+        cf.slots_per_seq);
+  } else {
+    const int rows = 256 / (cf.head_dim / 4);
+    gather_kernel<float><<<dim3((max_budget + rows - 1) / rows, cf.n_kv_heads, cf.batch), 256, 0, s>>>(
+        (const float*)K.ptr, K, (const float*)V.ptr, V, score, c->sel_ret, c->sel_cnt, meta, (float*)c->cacheK,
+        (float*)c->cacheV, c->cscore, c->cpos, ccount, c->npad, cf.head_dim, cf.slots_per_seq);
+  }
+  return hipGetLastError();
+}
+
+static int max_evicted(const d2o_ctx* c, int layer, int n) {
+  int m = 0;
+  for (const auto& mt : c->layers[layer].meta) m = std::max(m, n - std::min(mt.budget, n));
+  return m;
+}
+
+hipError_t launch_match(d2o_ctx* c, int layer, View K, int n, hipStream_t s) {
+  const d2o_config& cf = c->cfg;
+  const int me = max_evicted(c, layer, n);
+  if (me == 0) return hipSuccess;
+  const dim3 gr((me + 3) / 4, cf.n_kv_heads, cf.batch);
+  if (cf.dtype == D2O_BF16) {
+    invnorm_bf16<<<dim3((n + 15) / 16, cf.n_kv_heads, cf.batch), 256, 0, s>>>((const uint16_t*)K.ptr, K, c->invnorm, n,
+                                                                             c->npad);
+    match_filter_bf16<<<dim3((me + 127) / 128, cf.n_kv_heads, cf.batch), 256, 0, s>>>(
+        (const uint16_t*)K.ptr, K, c->invnorm, c->sel_ret, c->sel_evi, c->sel_cnt, c->m_cand, c->npad);
+    match_refine<uint16_t, 128><<<gr, 256, 0, s>>>((const uint16_t*)K.ptr, K, c->sel_ret, c->sel_evi, c->sel_cnt,
+                                                   c->m_cand, c->m_ustar, c->m_tgt, c->npad, 1);
+  } else if (cf.head_dim == 64) {
+    match_refine<float, 64><<<gr, 256, 0, s>>>((const float*)K.ptr, K, c->sel_ret, c->sel_evi, c->sel_cnt, c->m_cand,
+                                               c->m_ustar, c->m_tgt, c->npad, 0);
+  } else {
+    match_refine<float, 128><<<gr, 256, 0, s>>>((const float*)K.ptr, K, c->sel_ret, c->sel_evi, c->sel_cnt, c->m_cand,
+                                                c->m_ustar, c->m_tgt, c->npad, 0);
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_threshold_group(d2o_ctx* c, int layer, int n, hipStream_t s) {
+  const d2o_config& cf = c->cfg;
+  double* tau = c->ctau + size_t(layer) * cf.batch * cf.n_kv_heads;
+  threshold_group_kernel<<<dim3(cf.n_kv_heads, cf.batch), 1024, 0, s>>>(c->m_ustar, c->m_tgt, c->sel_cnt, c->m_pass,
+                                                                        c->g_cnt, c->g_off, c->g_cur, c->g_src, tau,
+                                                                        c->npad, cf.tau_force);
+  return hipGetLastError();
+}
+
+hipError_t launch_merge(d2o_ctx* c, int layer, View K, View V, int n, hipStream_t s) {
+  const d2o_config& cf = c->cfg;
+  if (max_evicted(c, layer, n) == 0) return hipSuccess;
+  int max_budget = 0;
+  for (const auto& mt : c->layers[layer].meta) max_budget = std::max(max_budget, std::min(mt.budget, n));
+  const int32_t* meta = c->meta + size_t(layer) * cf.batch * 4;
+  const dim3 gr((max_budget + 3) / 4, cf.n_kv_heads, cf.batch);
+  if (cf.dtype == D2O_BF16) {
+    merge_kernel<uint16_t, 128><<<gr, 256, 0, s>>>((const uint16_t*)K.ptr, K, (const uint16_t*)V.ptr, V, c->sel_evi,
+                                                   c->sel_cnt, c->m_ustar, c->g_cnt, c->g_off, c->g_src, meta,
+                                                   (uint16_t*)c->cacheK, (uint16_t*)c->cacheV, c->npad,
+                                                   cf.slots_per_seq);
+  } else if (cf.head_dim == 64) {
+    merge_kernel<float, 64><<<gr, 256, 0, s>>>((const float*)K.ptr, K, (const float*)V.ptr, V, c->sel_evi, c->sel_cnt,
+                                               c->m_ustar, c->g_cnt, c->g_off, c->g_src, meta, (float*)c->cacheK,
+                                               (float*)c->cacheV, c->npad, cf.slots_per_seq);
+  } else {
+    merge_kernel<float, 128><<<gr, 256, 0, s>>>((const float*)K.ptr, K, (const float*)V.ptr, V, c->sel_evi, c->sel_cnt,
+                                                c->m_ustar, c->g_cnt, c->g_off, c->g_src, meta, (float*)c->cacheK,
+                                                (float*)c->cacheV, c->npad, cf.slots_per_seq);
+  }
+  return hipGetLastError();
+}
+
+}  // namespace d2o
