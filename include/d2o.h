@@ -49,12 +49,15 @@ typedef struct {
   int32_t head_dim;       /* d: 64 or 128 for D2O_F32, 128 for D2O_BF16                    */
   int32_t max_prompt_len; /* largest n any prefill call will pass                          */
   int64_t slots_per_seq;  /* cache capacity per (sequence, KV head) over all layers:       */
-                          /* must hold sum_l (min(S_l, n) + 1)                             */
+                          /* must hold sum_l (S_l + 1)                                     */
   int32_t dtype;          /* d2o_dtype of Q, K, V, O and of the cache                      */
   int32_t n_sink;         /* T of Eq. 7: the first T prompt tokens are always kept         */
   double beta;            /* Eq. 10 smoothing constant, 0 <= beta < 1                      */
   double tau_force;       /* NaN: threshold of Eq. 10.  +inf: never merge (pure eviction). */
                           /* -inf: merge every evicted token.                              */
+  int32_t out_f32;        /* 0: attention outputs (O, out) in `dtype`; 1: in fp32, which    */
+                          /* keeps the fp32 accumulator's precision (bf16 storage alone     */
+                          /* costs up to 2^-8 relative)                                     */
 } d2o_config;
 
 /* A strided tensor whose last dimension (d) is contiguous.  Strides are in elements.
@@ -97,7 +100,7 @@ int d2o_reset(d2o_ctx* ctx, void* stream);
  * population variance of its column sums, whose mean over heads is the layer's density
  * statistic F.  Scores and statistics are kept in the context.
  * Q, O: [B][Hq][n][d]; K, V: [B][Hkv][n][d]; n <= max_prompt_len.  O.ptr may be NULL to skip
- * the output write.  Errors: INVALID_ARG, STATE (layer already compressed), HIP. */
+ * the output write; O holds fp32 when out_f32 is set (strides in its own elements).  Errors: INVALID_ARG, STATE (layer already compressed), HIP. */
 int d2o_prefill_attend(d2o_ctx* ctx, int32_t layer, d2o_view Q, d2o_view K, d2o_view V,
                        int32_t n, d2o_view O, void* stream);
 

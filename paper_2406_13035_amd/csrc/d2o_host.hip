@@ -47,7 +47,8 @@ int check_config(const d2o_config* c) {
   } else {
     return D2O_ERR_UNSUPPORTED;
   }
-  if (c->n_q_heads / c->n_kv_heads > 8) return D2O_ERR_UNSUPPORTED;
+  if (c->n_q_heads / c->n_kv_heads > 8 || c->n_q_heads > 256) return D2O_ERR_UNSUPPORTED;
+  if (c->out_f32 != 0 && c->out_f32 != 1) return D2O_ERR_INVALID_ARG;
   return D2O_OK;
 }
 
@@ -75,6 +76,8 @@ void layout(d2o_ctx* x, char* persistent, char* scratch, size_t* pbytes, size_t*
   Carver s{scratch};
   s.take(x->lse, B * Hq * np);
   s.take_raw(x->vt, c.dtype == D2O_BF16 ? B * Hkv * d * np * es : 0);
+  s.take(x->vmax_bits, B * Hkv);
+  s.take(x->vt_unscale, B * Hkv);
   s.take(x->varpart, B * Hq * (np / 128) * 2);
   const size_t bh = B * Hkv;
   s.take(x->sel_ret, bh * np);
@@ -105,8 +108,8 @@ void init_sizes(d2o_ctx* x) {
   x->nchunk_cap = x->cfg.slots_per_seq / kChunk + x->cfg.n_layers + 1;
 }
 
-bool view_ok(const d2o_ctx* x, const d2o_view& v) {
-  const int64_t al = 16 / x->esize;  // 16-byte vector loads
+bool view_ok(const d2o_ctx* x, const d2o_view& v, int esize = 0) {
+  const int64_t al = 16 / (esize ? esize : x->esize);  // 16-byte vector loads
   if (!v.ptr || (reinterpret_cast<uintptr_t>(v.ptr) & 15)) return false;
   return v.stride_b % al == 0 && v.stride_h % al == 0 && v.stride_n % al == 0 && v.stride_n >= 0;
 }
@@ -214,7 +217,7 @@ int d2o_prefill_attend(d2o_ctx* x, int32_t layer, d2o_view Q, d2o_view K, d2o_vi
   const d2o_config& c = x->cfg;
   if (layer < 0 || layer >= c.n_layers) return fail(x, D2O_ERR_INVALID_ARG, "layer out of range");
   if (n < 1 || n > c.max_prompt_len) return fail(x, D2O_ERR_INVALID_ARG, "n out of range");
-  if (!view_ok(x, Q) || !view_ok(x, K) || !view_ok(x, V) || (O.ptr && !view_ok(x, O)))
+  if (!view_ok(x, Q) || !view_ok(x, K) || !view_ok(x, V) || (O.ptr && !view_ok(x, O, x->cfg.out_f32 ? 4 : 0)))
     return fail(x, D2O_ERR_INVALID_ARG, "null, misaligned or badly strided tensor view");
   if (Q.stride_n < c.head_dim || K.stride_n < c.head_dim || V.stride_n < c.head_dim ||
       (O.ptr && O.stride_n < c.head_dim))
@@ -419,7 +422,7 @@ int d2o_decode_step(d2o_ctx* x, int32_t layer, int32_t nl, d2o_view q, d2o_view 
   if (!x) return D2O_ERR_INVALID_ARG;
   const d2o_config& c = x->cfg;
   if (layer < 0 || nl < 1 || layer + nl > c.n_layers) return fail(x, D2O_ERR_INVALID_ARG, "layer range");
-  if (!view_ok(x, q) || !view_ok(x, k_new) || !view_ok(x, v_new) || !view_ok(x, out))
+  if (!view_ok(x, q) || !view_ok(x, k_new) || !view_ok(x, v_new) || !view_ok(x, out, c.out_f32 ? 4 : 0))
     return fail(x, D2O_ERR_INVALID_ARG, "null, misaligned or badly strided tensor view");
   const int32_t new_pos = x->layers[layer].next_pos;
   for (int l = layer; l < layer + nl; ++l) {

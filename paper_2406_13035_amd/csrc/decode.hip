@@ -43,7 +43,7 @@ struct DecodeArgs {
   double* ev_ustar;
   int64_t slots;
   int64_t nchunk_cap;
-  int layer0, B, Hkv, G, new_pos, n_sink;
+  int layer0, B, Hkv, G, new_pos, n_sink, out_f32;
   double beta, tau_force;
 };
 
@@ -209,8 +209,8 @@ __global__ __launch_bounds__(256) void decode_attend(DecodeArgs a, const T* __re
   }
 }
 
-template <typename T, int D, int G>
-__global__ __launch_bounds__(256) void decode_update(DecodeArgs a, T* __restrict__ out, View ov) {
+template <typename T, typename OT, int D, int G>
+__global__ __launch_bounds__(256) void decode_update(DecodeArgs a, OT* __restrict__ out, View ov) {
   __shared__ double red[4];
   __shared__ double Msh[G], Lsh[G];
   __shared__ double bscore[4];
@@ -242,7 +242,7 @@ __global__ __launch_bounds__(256) void decode_update(DecodeArgs a, T* __restrict
         den = fmaf(a.pl[pi], f, den);
         num = fmaf(a.pacc[pi * D + tid], f, num);
       }
-      out[li * ov.sn + b * ov.sb + (hk * G + g) * ov.sh + tid] = Elem<T>::from_f32(num / den);
+      out[li * ov.sn + b * ov.sb + (hk * G + g) * ov.sh + tid] = Elem<OT>::from_f32(num / den);
     }
     // exact normaliser: sum_j exp(s_j - max), fp64; the exponentials replace the logits
     double* lg = a.logit + (int64_t(b) * a.Hkv * G + hk * G + g) * a.slots + mt[0];
@@ -480,7 +480,10 @@ hipError_t run_decode(const DecodeArgs& a, int nl, int maxchunks, View q, View k
   const int bh = a.B * a.Hkv;
   decode_append<T, D><<<dim3(bh, nl), 128, 0, s>>>(a, (const T*)k.ptr, k, (const T*)v.ptr, v);
   decode_attend<T, D, G><<<dim3(maxchunks, bh, nl), 256, 0, s>>>(a, (const T*)q.ptr, q);
-  decode_update<T, D, G><<<dim3(bh, nl), 256, 0, s>>>(a, (T*)out.ptr, out);
+  if (a.out_f32)
+    decode_update<T, float, D, G><<<dim3(bh, nl), 256, 0, s>>>(a, (float*)out.ptr, out);
+  else
+    decode_update<T, T, D, G><<<dim3(bh, nl), 256, 0, s>>>(a, (T*)out.ptr, out);
   decode_cosine<T, D><<<dim3(maxchunks, bh, nl), 256, 0, s>>>(a);
   decode_finish<T, D><<<dim3(bh, nl), 128, 0, s>>>(a);
   return hipGetLastError();
@@ -528,6 +531,7 @@ hipError_t launch_decode(d2o_ctx* c, int layer0, int nl, View q, View k, View v,
   a.G = cf.n_q_heads / cf.n_kv_heads;
   a.new_pos = new_pos;
   a.n_sink = cf.n_sink;
+  a.out_f32 = cf.out_f32;
   a.beta = cf.beta;
   a.tau_force = cf.tau_force;
   int maxchunks = 1;

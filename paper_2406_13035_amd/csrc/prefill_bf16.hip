@@ -5,6 +5,11 @@
 //   pre-transposed V through LDS and keeps S^T = K Q^T in the MFMA accumulator layout, where
 //   one lane owns one query column: row maxima and sums are then in-register reductions.
 //   Emits O and the row log-sum-exp (base 2, of the scaled logits).
+//   The P V product runs in fp16, not bf16: probabilities rounded to bf16 (8 significant bits)
+//   alone cost up to 2^-8 relative on O, fp16 (11 bits) keeps it below 2^-11.  V is converted
+//   once, in the transposing pre-pass, with a per-head power-of-two scale that maps max|v| to
+//   2^13 (exact for bf16 inputs inside fp16's exponent range), and P carries a factor 2^12 so
+//   that small probabilities stay in fp16's normal range; both factors cancel in O.
 // Pass 2, colsum_bf16 ("sum the elements of each column", Sec. 4.1; Eq. 6 prompt case):
 //   key-stationary.  A workgroup owns 128 keys, streams query tiles, recomputes S^T with the
 //   keys as the stationary MFMA operand, and accumulates P = exp2(S - lse) per key in
@@ -17,6 +22,8 @@
 // v_mfma_f32_32x32x16_bf16 operand layout (lane l, m = l % 32, h = l / 32):
 //   A[m][8h .. 8h+7], B[8h .. 8h+7][m], D[(r/4)*8 + 4h + r%4][m] for r = 0..15.
 #include "d2o_internal.h"
+#include <algorithm>
+
 #include "device_utils.h"
 
 namespace d2o {
@@ -26,19 +33,64 @@ constexpr float kLog2e = 1.4426950408889634f;
 constexpr int kD = 128;
 constexpr int kLdK = kD + 8;   // LDS row pitch (elements) of [token][d] tiles
 constexpr int kLdV = 64 + 8;   // LDS row pitch of the [d][key] tile
+constexpr float kPShift = 12.f;  // probabilities are formed as 2^12 * p before the fp16 rounding
 
-// V [b][h][n][d] -> VT [b][h][d][npad], zero for keys >= n.
+__global__ void zero_u32(uint32_t* p, int n) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = 0u;
+}
+
+// max |v| per (sequence, KV head), as the bit pattern of the non-negative float.
+__global__ __launch_bounds__(256) void vabsmax_kernel(const uint16_t* __restrict__ V, View vv, uint32_t* __restrict__ vmax,
+                                                      int n) {
+  __shared__ uint32_t red[4];
+  const int h = blockIdx.y, b = blockIdx.z, Hkv = gridDim.y;
+  const uint16_t* src = V + b * vv.sb + h * vv.sh;
+  uint32_t m = 0;
+  for (int c = blockIdx.x * 256 + threadIdx.x; c < n * 16; c += gridDim.x * 256) {
+    const int row = c >> 4, col = (c & 15) * 8;
+    const u32x4 v = *reinterpret_cast<const u32x4*>(src + int64_t(row) * vv.sn + col);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      m = max(m, (v[i] << 16) & 0x7FFFFFFFu);
+      m = max(m, v[i] & 0x7FFF0000u);
+    }
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) m = max(m, (uint32_t)__shfl_xor((int)m, o, 64));
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = m;
+  __syncthreads();
+  if (threadIdx.x == 0) atomicMax(&vmax[b * Hkv + h], max(max(red[0], red[1]), max(red[2], red[3])));
+}
+
+// Power-of-two factor that maps max|v| into [2^13, 2^14) (1 when the head is all zero).
+__device__ __forceinline__ float v_scale_from_max(uint32_t maxbits) {
+  const int e = int((maxbits >> 23) & 0xFF);  // biased exponent of max |v|
+  if (e == 0 || e == 255) return 1.0f;
+  const int k = min(max(e - 127 - 13, -100), 100);
+  return __uint_as_float(uint32_t(127 - k) << 23);  // 2^-k
+}
+
+// V [b][h][n][d] (bf16) -> VT [b][h][d][npad] (fp16, scaled), zero for keys >= n.
 __global__ __launch_bounds__(256) void transpose_v(const uint16_t* __restrict__ V, View vv, uint16_t* __restrict__ VT,
+                                                   const uint32_t* __restrict__ vmax, float* __restrict__ unscale,
                                                    int n, int npad) {
   __shared__ uint16_t t[64][kD + 2];
   const int k0 = blockIdx.x * 64, h = blockIdx.y, b = blockIdx.z, Hkv = gridDim.y;
+  const float mul = v_scale_from_max(vmax[b * Hkv + h]);
+  if (blockIdx.x == 0 && threadIdx.x == 0) unscale[b * Hkv + h] = 1.0f / mul;
   const uint16_t* src = V + b * vv.sb + h * vv.sh;
   for (int c = threadIdx.x; c < 64 * 16; c += 256) {
     const int row = c >> 4, col = (c & 15) * 8;
     u32x4 v = {0, 0, 0, 0};
     if (k0 + row < n) v = *reinterpret_cast<const u32x4*>(src + int64_t(k0 + row) * vv.sn + col);
-    uint32_t* d = reinterpret_cast<uint32_t*>(&t[row][col]);
-    d[0] = v[0]; d[1] = v[1]; d[2] = v[2]; d[3] = v[3];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const _Float16 lo = (_Float16)(__uint_as_float(v[i] << 16) * mul);
+      const _Float16 hi = (_Float16)(__uint_as_float(v[i] & 0xFFFF0000u) * mul);
+      t[row][col + 2 * i] = __builtin_bit_cast(uint16_t, lo);
+      t[row][col + 2 * i + 1] = __builtin_bit_cast(uint16_t, hi);
+    }
   }
   __syncthreads();
   uint16_t* dst = VT + (int64_t(b) * Hkv + h) * kD * npad;
@@ -61,8 +113,8 @@ __device__ __forceinline__ int perm_key(int m) { return (m & ~0xC) | ((m & 4) <<
 
 __global__ __launch_bounds__(256) void attn_fwd_bf16(const uint16_t* __restrict__ Q, View qv,
                                                      const uint16_t* __restrict__ K, View kv,
-                                                     const uint16_t* __restrict__ VT, uint16_t* __restrict__ O, View ov,
-                                                     float* __restrict__ lse2, int n, int npad, int G) {
+                                                     const uint16_t* __restrict__ VT, const float* __restrict__ unscale,
+                                                     void* __restrict__ O, View ov, float* __restrict__ lse2, int n, int npad, int G, int out_f32) {
   __shared__ __attribute__((aligned(16))) uint16_t Ks[64 * kLdK];
   __shared__ __attribute__((aligned(16))) uint16_t Vs[kD * kLdV];
   const int nblk = gridDim.x;
@@ -134,18 +186,18 @@ __global__ __launch_bounds__(256) void attn_fwd_bf16(const uint16_t* __restrict_
 #pragma unroll
       for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[st][r]);
     mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-    const float mnew = fmaxf(mrun, mx * scale2);
+    const float mnew = fmaxf(mrun, fmaf(mx, scale2, -kPShift));  // exponent reference, 2^12 headroom
     const float alpha = exp2f(mrun - mnew);
     mrun = mnew;
     float psum = 0.f;
-    bf16x8 pb[2][2];
+    f16x8 pb[2][2];
 #pragma unroll
     for (int st = 0; st < 2; ++st)
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const float p = exp2f(fmaf(s[st][r], scale2, -mnew));
         psum += p;
-        pb[st][r >> 3][r & 7] = (__bf16)p;
+        pb[st][r >> 3][r & 7] = (_Float16)p;
       }
     lsum = fmaf(lsum, alpha, psum);
 #pragma unroll
@@ -158,27 +210,35 @@ __global__ __launch_bounds__(256) void attn_fwd_bf16(const uint16_t* __restrict_
       for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
         for (int dc = 0; dc < 4; ++dc) {
-          const bf16x8 a = *reinterpret_cast<const bf16x8*>(&Vs[(dc * 32 + m) * kLdV + st * 32 + kb * 16 + h * 8]);
-          o[dc] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pb[st][kb], o[dc], 0, 0, 0);
+          const f16x8 a = *reinterpret_cast<const f16x8*>(&Vs[(dc * 32 + m) * kLdV + st * 32 + kb * 16 + h * 8]);
+          o[dc] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, pb[st][kb], o[dc], 0, 0, 0);
         }
   }
   const float ltot = lsum + __shfl_xor(lsum, 32, 64);
   if (q_row < n) {
     if (h == 0) lse2[(int64_t(b) * Hq + hq) * npad + q_row] = mrun + log2f(ltot);
     if (O) {
-      const float inv = 1.f / ltot;
-      uint16_t* orow = O + b * ov.sb + hq * ov.sh + int64_t(q_row) * ov.sn;
+      const float inv = unscale[b * Hkv + hk] / ltot;
+      const int64_t ooff = b * ov.sb + hq * ov.sh + int64_t(q_row) * ov.sn;
 #pragma unroll
       for (int dc = 0; dc < 4; ++dc)
 #pragma unroll
         for (int rg = 0; rg < 4; ++rg) {
           // registers 4*rg .. 4*rg+3 hold d = 32*dc + 8*rg + 4*h + 0..3
-          u32x2 v;
-          v[0] = Elem<uint16_t>::from_f32(o[dc][4 * rg + 0] * inv) |
-                 (uint32_t(Elem<uint16_t>::from_f32(o[dc][4 * rg + 1] * inv)) << 16);
-          v[1] = Elem<uint16_t>::from_f32(o[dc][4 * rg + 2] * inv) |
-                 (uint32_t(Elem<uint16_t>::from_f32(o[dc][4 * rg + 3] * inv)) << 16);
-          *reinterpret_cast<u32x2*>(orow + dc * 32 + rg * 8 + h * 4) = v;
+          const int dd = dc * 32 + rg * 8 + h * 4;
+          if (out_f32) {
+            f32x4 v;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) v[i] = o[dc][4 * rg + i] * inv;
+            *reinterpret_cast<f32x4*>(static_cast<float*>(O) + ooff + dd) = v;
+          } else {
+            u32x2 v;
+            v[0] = Elem<uint16_t>::from_f32(o[dc][4 * rg + 0] * inv) |
+                   (uint32_t(Elem<uint16_t>::from_f32(o[dc][4 * rg + 1] * inv)) << 16);
+            v[1] = Elem<uint16_t>::from_f32(o[dc][4 * rg + 2] * inv) |
+                   (uint32_t(Elem<uint16_t>::from_f32(o[dc][4 * rg + 3] * inv)) << 16);
+            *reinterpret_cast<u32x2*>(static_cast<uint16_t*>(O) + ooff + dd) = v;
+          }
         }
     }
   }
@@ -286,11 +346,15 @@ hipError_t launch_prefill_bf16(d2o_ctx* c, int layer, View Q, View K, View V, Vi
   const int G = cf.n_q_heads / cf.n_kv_heads;
   float* score = c->score_pre + size_t(layer) * cf.batch * cf.n_kv_heads * c->npad;
   const int nblk = (n + 127) / 128;
-  transpose_v<<<dim3(c->npad / 64, cf.n_kv_heads, cf.batch), 256, 0, s>>>((const uint16_t*)V.ptr, V,
-                                                                         (uint16_t*)c->vt, n, c->npad);
+  const int nbh = cf.batch * cf.n_kv_heads;
+  zero_u32<<<(nbh + 255) / 256, 256, 0, s>>>(c->vmax_bits, nbh);
+  vabsmax_kernel<<<dim3(std::min(64, (n * 16 + 255) / 256), cf.n_kv_heads, cf.batch), 256, 0, s>>>(
+      (const uint16_t*)V.ptr, V, c->vmax_bits, n);
+  transpose_v<<<dim3(c->npad / 64, cf.n_kv_heads, cf.batch), 256, 0, s>>>((const uint16_t*)V.ptr, V, (uint16_t*)c->vt,
+                                                                         c->vmax_bits, c->vt_unscale, n, c->npad);
   attn_fwd_bf16<<<dim3(nblk, cf.n_q_heads, cf.batch), 256, 0, s>>>((const uint16_t*)Q.ptr, Q, (const uint16_t*)K.ptr, K,
-                                                                  (const uint16_t*)c->vt, (uint16_t*)O.ptr, O, c->lse,
-                                                                  n, c->npad, G);
+                                                                  (const uint16_t*)c->vt, c->vt_unscale, O.ptr, O, c->lse,
+                                                                  n, c->npad, G, cf.out_f32);
   colsum_bf16<<<dim3(nblk, cf.n_kv_heads, cf.batch), 256, 0, s>>>((const uint16_t*)Q.ptr, Q, (const uint16_t*)K.ptr, K,
                                                                  c->lse, score, c->varpart, n, c->npad, G,
                                                                  cf.n_q_heads);

@@ -33,15 +33,15 @@ def test_library_exports_every_declared_symbol(lib):
 
 
 def test_workspace_query_and_config_validation(lib):
-    cfg = binding.d2o_config(1, 32, 32, 32, 128, 4096, 30000, binding.D2O_BF16, 0, 0.7, float("nan"))
+    cfg = binding.d2o_config(1, 32, 32, 32, 128, 4096, 30000, binding.D2O_BF16, 0, 0.7, float("nan"), 0)
     p, s = C.c_size_t(), C.c_size_t()
     assert lib.d2o_workspace_bytes(C.byref(cfg), C.byref(p), C.byref(s)) == 0
     assert p.value > 32 * 30000 * 128 * 2 * 2 and s.value > 0
-    bad = binding.d2o_config(1, 32, 32, 5, 128, 4096, 30000, binding.D2O_BF16, 0, 0.7, float("nan"))
+    bad = binding.d2o_config(1, 32, 32, 5, 128, 4096, 30000, binding.D2O_BF16, 0, 0.7, float("nan"), 0)
     assert lib.d2o_workspace_bytes(C.byref(bad), C.byref(p), C.byref(s)) == -1      # Hq % Hkv
-    bad = binding.d2o_config(1, 32, 32, 32, 96, 4096, 30000, binding.D2O_BF16, 0, 0.7, float("nan"))
+    bad = binding.d2o_config(1, 32, 32, 32, 96, 4096, 30000, binding.D2O_BF16, 0, 0.7, float("nan"), 0)
     assert lib.d2o_workspace_bytes(C.byref(bad), C.byref(p), C.byref(s)) == -2      # head_dim
-    bad = binding.d2o_config(1, 32, 32, 32, 128, 4096, 30000, binding.D2O_BF16, 0, 1.0, float("nan"))
+    bad = binding.d2o_config(1, 32, 32, 32, 128, 4096, 30000, binding.D2O_BF16, 0, 1.0, float("nan"), 0)
     assert lib.d2o_workspace_bytes(C.byref(bad), C.byref(p), C.byref(s)) == -1      # beta = 1
 
 

@@ -45,7 +45,7 @@ def test_prefill_attention_scores_density(case):
     print(f"case={case} n={n} B={B}", flush=True)
     Q, K, V = H.make_inputs(w, B, layer, n)
     ctx = H.new_ctx(w, B, 1, n, n + 8)
-    O = torch.empty_like(Q)
+    O = torch.empty(Q.shape, dtype=ctx.out_dtype, device=Q.device)
     ctx.d2o_prefill_attend(0, Q, K, V, O)
     torch.cuda.synchronize()
     wantO, want_score, want_var = H.oracle_prefill_layer(Q, K, V, w.group)
@@ -59,6 +59,26 @@ def test_prefill_attention_scores_density(case):
     np.testing.assert_allclose(F[:, 0], want_var.mean(axis=1), rtol=H.FLOAT_TOL)
     # invariant at any size: every query row sums to 1, so a head's column sums add up to n
     np.testing.assert_allclose(got_score.sum(axis=2), w.group * n, rtol=1e-4)
+    ctx.close()
+
+
+def test_bf16_output_storage_adds_only_its_rounding():
+    """With outputs stored in bf16 (out_f32 = 0) every element must be the fp32-accumulated
+    value rounded once: |got - want| <= 2e-3 * |row|_inf + 2^-8 * |want| (bf16 unit roundoff)."""
+    w, n, B, layer = _small_bf16(True), 777, 1, 9
+    Q, K, V = H.make_inputs(w, B, layer, n)
+    ctx = H.new_ctx(w, B, 1, n, 400, out_f32=False)
+    O = torch.empty_like(Q)
+    ctx.d2o_prefill_compress(0, Q, K, V, 300, 75, O)
+    q, k, v = H.decode_inputs(w, B, [layer], 1)
+    out = torch.empty_like(q[0])
+    ctx.d2o_decode_step(0, 1, q[0], k[0], v[0], out)
+    torch.cuda.synchronize()
+    wantO, _, _ = H.oracle_prefill_layer(Q, K, V, w.group)
+    got = binding.tensor_to_f64(O)
+    bound = H.FLOAT_TOL * np.abs(wantO).max(axis=-1, keepdims=True) + 2.0 ** -8 * np.abs(wantO)
+    assert np.all(np.abs(got - wantO) <= bound)
+    assert torch.isfinite(out.float()).all()
     ctx.close()
 
 
@@ -118,6 +138,9 @@ def test_matching_with_duplicate_keys_takes_first_maximum():
     Q, K, V = H.make_inputs(w, 1, 0, n)
     K = K.clone()
     K[0, :, 100:140] = K[0, :, 300:340]          # twins: evicted rows equal to retained rows
+    V = V.clone()
+    V[0, :, 100:140] = V[0, :, 300:340]          # (equal values too: a mean of two different
+                                                 # bf16 numbers can sit exactly on a rounding tie)
     K[0, :, 400:420] = K[0, :, 300:320]          # and duplicated retained keys
     score32 = np.zeros((1, w.n_kv_heads, n), dtype=np.float32)
     score32[:, :, 300:340] = 5.0
@@ -146,7 +169,7 @@ def _run_decode_parity(w, n, B, layer, budget, recent, sink, steps, tau_force=fl
     _, caches = H.check_compress_against_oracle(ctx, 0, K, V, score32, budget, recent, sink, w.dtype,
                                                 tau_force)
     q, k, v = H.decode_inputs(w, B, [layer], steps)
-    out = torch.empty_like(q[0])
+    out = torch.empty(q[0].shape, dtype=ctx.out_dtype, device=q.device)
     qd, kd, vd = (binding.tensor_to_f64(t) for t in (q, k, v))
     G = w.group
     worst = 0.0
@@ -208,7 +231,7 @@ def test_cfg1_end_to_end_free_running():
     w, n = W1, W1.prompt_len
     Q, K, V = H.make_inputs(w, 1, 0, n)
     ctx = H.new_ctx(w, 1, 1, n, w.fixed_budget + 8)
-    O = torch.empty_like(Q)
+    O = torch.empty(Q.shape, dtype=ctx.out_dtype, device=Q.device)
     ctx.d2o_prefill_compress(0, Q, K, V, w.fixed_budget, w.fixed_recent, O)
     torch.cuda.synchronize()
     wantO, score, var = H.oracle_prefill_layer(Q, K, V, w.group)
@@ -233,7 +256,7 @@ def test_cfg1_end_to_end_free_running():
             assert np.all(np.abs(score[0, h][diff] - kth) <= 1e-4 * abs(kth)), "unexplained selection"
             explained += 1
     print(f"  heads agreeing {len(agree)}/{w.n_kv_heads}, margin-explained {explained}", flush=True)
-    out = torch.empty_like(q[0])
+    out = torch.empty(q[0].shape, dtype=ctx.out_dtype, device=q.device)
     for t in range(w.decode_steps):
         ctx.d2o_decode_step(0, 1, q[t], k[t], v[t], out)
         torch.cuda.synchronize()
@@ -262,7 +285,7 @@ def test_error_paths_return_codes():
     with pytest.raises(binding.D2OError):      # second compress of the same layer
         ctx.d2o_compress_layer(0, K, V, 64, 16)
     q, k, v = H.decode_inputs(w, 1, [0, 1], 1)
-    out = torch.empty_like(q[0])
+    out = torch.empty(q[0].shape, dtype=ctx.out_dtype, device=q.device)
     with pytest.raises(binding.D2OError):      # layer 1 was never compressed
         ctx.d2o_decode_step(0, 2, q[0], k[0], v[0], out)
     ctx.d2o_decode_step(0, 1, q[0][:1], k[0][:1], v[0][:1], out[:1])
