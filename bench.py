@@ -1,0 +1,226 @@
+#!/usr/bin/env python3
+"""Benchmark of the D2O hot path on one MI355X.
+
+One "step" is one pass of the whole path over one batch of synthetic input, with all inputs
+resident in HBM before the timed region: for every layer the prefill attention with per-key
+scores and density (a1-a2), the dynamic budget allocation from the measured densities (a3),
+for every layer selection / compaction / matching / threshold / merge (a4-a8), then
+`decode_steps` generation steps over the compressed caches of all layers (a9-a12).
+
+Prints ONE JSON line.  `value` is the decode throughput in tokens/s (batch * decode steps /
+decode time); the same line carries the prefill-compress time per layer, the roofline of the
+dominant kernel (matrix-core prefill attention) and of the HBM-bound decode kernel, and the
+CPU oracle timed on a bounded sample of the same workload."""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+import torch
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+from paper_2406_13035_amd import binding, synth  # noqa: E402
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16/fp16 matrix-core peak
+PEAK_HBM_GBS = 8000.0       # MI355X HBM3E peak
+MIN_BUDGET = 64
+
+
+def generate(w, device):
+    """All inputs of one benchmark step, resident on the device."""
+    Q, K, V = [], [], []
+    for l in range(w.n_layers):
+        q, k, v = [], [], []
+        for b in range(w.batch):
+            ql, kl, vl = synth.layer_inputs(w, b, l, device)
+            q.append(ql)
+            k.append(kl)
+            v.append(vl)
+        Q.append(torch.stack(q))
+        K.append(torch.stack(k))
+        V.append(torch.stack(v))
+    return Q, K, V
+
+
+def generate_decode(w, steps, device):
+    qs, ks, vs = [], [], []
+    for l in range(w.n_layers):
+        ql, kl, vl = [], [], []
+        for b in range(w.batch):
+            q, k, v = synth.layer_decode_inputs(w, b, l, steps, device)
+            ql.append(q)
+            kl.append(k)
+            vl.append(v)
+        qs.append(torch.stack(ql, 1))
+        ks.append(torch.stack(kl, 1))
+        vs.append(torch.stack(vl, 1))
+    # [steps, L, B, H, d]
+    return (torch.stack(qs, 1).contiguous(), torch.stack(ks, 1).contiguous(),
+            torch.stack(vs, 1).contiguous())
+
+
+def run_step(ctx, w, Q, K, V, O, dq, dk, dv, dout, decode_steps):
+    """One pass of the hot path.  Returns (prefill_ms, decode_ms, budgets [B, L], F [B, L])."""
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+    ctx.d2o_reset()
+    ev[0].record()
+    for l in range(w.n_layers):
+        ctx.d2o_prefill_attend(l, Q[l], K[l], V[l], O)
+    F = ctx.d2o_get_density()
+    n = w.prompt_len
+    budgets = np.stack([binding.d2o_allocate_budgets(F[b], n, w.total_budget(), MIN_BUDGET)
+                        for b in range(w.batch)])
+    for l in range(w.n_layers):
+        bud = budgets[:, l]
+        ctx.d2o_compress_layer(l, K[l], V[l], bud, bud // 4)
+    ev[1].record()
+    for t in range(decode_steps):
+        ctx.d2o_decode_step(0, w.n_layers, dq[t], dk[t], dv[t], dout)
+    ev[2].record()
+    torch.cuda.synchronize()
+    return ev[0].elapsed_time(ev[1]), ev[1].elapsed_time(ev[2]), budgets, F
+
+
+def cpu_baseline(w, decode_steps_sample=8):
+    """The fp64 oracle, as it stands, on a bounded sample of the same workload: one query
+    head of layer 0 (prefill attention + scores), the token-level stages of its KV head at the
+    mean budget, and a few decode steps on that head."""
+    from oracle import d2o_ref as ref
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    n = w.prompt_len
+    Qh, Kh, Vh = synth.kv_head_inputs(w, 0, 0, 0, "cpu")
+    Qd, Kd, Vd = (binding.tensor_to_f64(t) for t in (Qh, Kh, Vh))
+    t0 = time.perf_counter()
+    o, s = ref.prefill_attention_head(Qd[0], Kd, Vd)
+    var = ref.head_variance(s)
+    t1 = time.perf_counter()
+    score = s * w.group
+    budget = w.total_budget() // w.n_layers
+    cache, _ = ref.compress_head(Kd, Vd, score, budget, budget // 4, 0, w.dtype)
+    t2 = time.perf_counter()
+    q, k, v = synth.kv_head_decode_inputs(w, 0, 0, 0, decode_steps_sample, "cpu")
+    qd, kd, vd = (binding.tensor_to_f64(t) for t in (q, k, v))
+    for t in range(decode_steps_sample):
+        ref.decode_step_head(cache, qd[t], kd[t], vd[t], n + t, budget, budget // 4, 0, w.beta)
+    t3 = time.perf_counter()
+    attn_s, comp_s, dec_s = t1 - t0, t2 - t1, (t3 - t2) / decode_steps_sample
+    heads_q, heads_kv = w.n_q_heads * w.batch, w.n_kv_heads * w.batch
+    prefill_ms_layer = (attn_s * heads_q + comp_s * heads_kv) * 1e3
+    step_s = dec_s * heads_kv * w.n_layers
+    return {
+        "value": w.batch / step_s, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
+        "prefill_compress_ms_per_layer": prefill_ms_layer,
+        "sample": (f"layer 0: attention+scores of 1 query head ({attn_s:.1f} s), token-level "
+                   f"stages of 1 KV head at budget {budget} ({comp_s:.1f} s), {decode_steps_sample} "
+                   f"decode steps of 1 KV head ({dec_s * 1e3:.1f} ms each); scaled by "
+                   f"{heads_q} query heads / {heads_kv} KV heads per layer and {w.n_layers} layers"),
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=2)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--cfg", type=int, default=3, help="benchmark configuration 1..5")
+    ap.add_argument("--decode-steps", type=int, default=None)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (see DESIGN.md, "
+              "'How the path would shard'); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    if not torch.cuda.is_available():
+        print("no GPU visible: the D2O library has no CPU path", file=sys.stderr)
+        sys.exit(3)
+    w = synth.WORKLOADS[args.cfg]
+    dsteps = args.decode_steps or w.decode_steps
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    print(f"[bench] generating {w.name}: B={w.batch} L={w.n_layers} Hq={w.n_q_heads} "
+          f"Hkv={w.n_kv_heads} d={w.head_dim} N={w.prompt_len}", file=sys.stderr, flush=True)
+    Q, K, V = generate(w, dev)
+    dq, dk, dv = generate_decode(w, dsteps, dev)
+    slots = w.total_budget() + w.n_layers + 8
+    ctx = binding.D2O(w.batch, w.n_layers, w.n_q_heads, w.n_kv_heads, w.head_dim, w.prompt_len,
+                      slots, dtype=w.dtype, n_sink=0, beta=w.beta)
+    O = torch.empty_like(Q[0])
+    dout = torch.empty_like(dq[0])
+    torch.cuda.synchronize()
+    print("[bench] inputs resident; warm-up", file=sys.stderr, flush=True)
+    for _ in range(args.warmup):
+        run_step(ctx, w, Q, K, V, O, dq, dk, dv, dout, dsteps)
+    ctx.d2o_timing_enable(True)
+    for k in binding.KERNEL_IDS:
+        ctx.d2o_timing_read(k)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    pre, dec = [], []
+    for i in range(args.steps):
+        p, d, budgets, F = run_step(ctx, w, Q, K, V, O, dq, dk, dv, dout, dsteps)
+        pre.append(p)
+        dec.append(d)
+        print(f"[bench] step {i}: prefill+compress {p:.1f} ms, decode {d:.1f} ms", file=sys.stderr,
+              flush=True)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    kt = {k: ctx.d2o_timing_read(k) for k in binding.KERNEL_IDS}
+    ctx.d2o_timing_enable(False)
+
+    n, d, L = w.prompt_len, w.head_dim, w.n_layers
+    decode_ms = float(np.mean(dec))
+    prefill_ms = float(np.mean(pre))
+    tokens_per_s = w.batch * dsteps / (decode_ms * 1e-3)
+    # dominant kernel: prefill attention pass 1.  Algorithmic work = causal QK^T + PV:
+    # 2 * N^2 * d FLOP per (sequence, query head), per launch B * Hq heads.
+    attn_ms, attn_n = kt["attn_fwd"]
+    flop_per_launch = 2.0 * n * n * d * w.n_q_heads * w.batch
+    attn_tflops = flop_per_launch / (attn_ms / attn_n * 1e-3) / 1e12 if attn_n else 0.0
+    # decode attention: K and V rows read once (2 * d * esize bytes per slot) + fp64 logits
+    # written, per KV head; slots = budget (+1) per layer.
+    es = 2 if w.dtype == "bf16" else 4
+    slots_b = budgets.sum(axis=1) + L
+    bytes_per_launch = float(sum(int(s) for s in slots_b) * w.n_kv_heads * (2 * d * es + 8))
+    da_ms, da_n = kt["decode_attend"]
+    dec_gbs = bytes_per_launch / (da_ms / da_n * 1e-3) / 1e9 if da_n else 0.0
+    step_bytes = bytes_per_launch  # whole decode step, algorithmic (K second touch not counted)
+    out = {
+        "metric": "compressed-KV decode tokens/s (+ prefill-compress ms/layer at N=32k)",
+        "value": tokens_per_s, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": wall * 1e3 / args.steps, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": f"config {w.cfg}: {w.name}", "batch": w.batch, "layers": L,
+                   "q_heads": w.n_q_heads, "kv_heads": w.n_kv_heads, "head_dim": d, "prompt_len": n,
+                   "decode_steps": dsteps, "total_budget": w.total_budget(),
+                   "layer_budgets_seq0": [int(x) for x in budgets[0]],
+                   "density_F_seq0_min_max": [float(F[0].min()), float(F[0].max())]},
+        "prefill_compress_ms_per_layer": prefill_ms / L,
+        "decode_ms_per_step": decode_ms / dsteps,
+        "decode_step_hbm_frac": step_bytes / (decode_ms / dsteps * 1e-3) / 1e9 / PEAK_HBM_GBS,
+        "roofline": {"kernel": "attn_fwd (prefill attention pass 1)", "bound": "mfma",
+                     "achieved": attn_tflops, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                     "frac": attn_tflops / PEAK_BF16_TFLOPS, "traffic": None,
+                     "avg_launch_ms": attn_ms / attn_n if attn_n else None},
+        "roofline_decode": {"kernel": "decode_attend", "bound": "hbm", "achieved": dec_gbs,
+                            "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": dec_gbs / PEAK_HBM_GBS,
+                            "traffic": None, "avg_launch_ms": da_ms / da_n if da_n else None},
+        "kernel_ms_per_launch": {k: (v[0] / v[1] if v[1] else None) for k, v in kt.items()},
+    }
+    if not args.no_cpu_baseline:
+        print("[bench] timing the CPU oracle on a bounded sample", file=sys.stderr, flush=True)
+        out["cpu_baseline"] = cpu_baseline(w)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

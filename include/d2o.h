@@ -188,6 +188,27 @@ int d2o_prefill_events(d2o_ctx* ctx, int32_t layer, int32_t b, int32_t kv_head,
                        int32_t* n_evi, int32_t* target_pos, double* u_star, uint8_t* passed,
                        void* stream);
 
+/* Kernel timing aid for benchmarks (not part of the method).  While enabled, every launch
+ * of the kernels below is bracketed by two HIP events recorded on the launch stream.
+ * d2o_timing_read synchronises `stream`, returns the summed duration in milliseconds and the
+ * number of launches of one kernel since the last read of that kernel, and forgets them. */
+typedef enum {
+  D2O_K_ATTN_FWD = 0,      /* prefill attention, pass 1 (O and row log-sum-exp)            */
+  D2O_K_COLSUM = 1,        /* prefill attention, pass 2 (per-key column sums)              */
+  D2O_K_SELECT = 2,
+  D2O_K_MATCH_FILTER = 3,  /* matrix-core cosine candidate filter                          */
+  D2O_K_MATCH_REFINE = 4,  /* exact fp64 cosine / arg-max                                  */
+  D2O_K_MERGE = 5,
+  D2O_K_DECODE_ATTEND = 6,
+  D2O_K_DECODE_UPDATE = 7,
+  D2O_K_DECODE_COSINE = 8,
+  D2O_K_DECODE_FINISH = 9,
+  D2O_K_COUNT = 10
+} d2o_kernel_id;
+int d2o_timing_enable(d2o_ctx* ctx, int32_t on);
+int d2o_timing_read(d2o_ctx* ctx, int32_t kernel_id, double* total_ms, int64_t* launches,
+                    void* stream);
+
 #ifdef __cplusplus
 }
 #endif

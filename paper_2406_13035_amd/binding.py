@@ -21,7 +21,7 @@ EXPORTS = [
     "d2o_prefill_attend", "d2o_get_density", "d2o_allocate_budgets", "d2o_scores_import",
     "d2o_scores_export", "d2o_compress_layer", "d2o_prefill_compress", "d2o_decode_step",
     "d2o_layer_reserve", "d2o_cache_export", "d2o_cache_import", "d2o_last_events",
-    "d2o_prefill_events",
+    "d2o_prefill_events", "d2o_timing_enable", "d2o_timing_read",
 ]
 
 
@@ -76,6 +76,8 @@ def load_library() -> C.CDLL:
     lib.d2o_cache_import.argtypes = [vp, i32, i32, i32, vp, vp, vp, vp, i32, C.c_double, i32, vp]
     lib.d2o_last_events.argtypes = [vp, i32, vp, vp, vp, vp]
     lib.d2o_prefill_events.argtypes = [vp, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp]
+    lib.d2o_timing_enable.argtypes = [vp, i32]
+    lib.d2o_timing_read.argtypes = [vp, i32, P(C.c_double), P(C.c_int64), vp]
     for name in EXPORTS:
         if name not in ("d2o_destroy", "d2o_last_error"):
             getattr(lib, name).restype = C.c_int
@@ -221,6 +223,16 @@ class D2O:
                                              view_decode(k_new), view_decode(v_new),
                                              view_decode(out), _stream_ptr()), "d2o_decode_step")
 
+    def d2o_timing_enable(self, on: bool):
+        self._check(self.lib.d2o_timing_enable(self.ctx, 1 if on else 0), "d2o_timing_enable")
+
+    def d2o_timing_read(self, kernel: str):
+        """(total milliseconds, launches) of one kernel since its last read."""
+        ms, cnt = C.c_double(), C.c_int64()
+        self._check(self.lib.d2o_timing_read(self.ctx, KERNEL_IDS[kernel], C.byref(ms),
+                                             C.byref(cnt), _stream_ptr()), "d2o_timing_read")
+        return ms.value, cnt.value
+
     def d2o_layer_reserve(self, layer, n, budget, recent):
         b, r = self._budget_arrays(budget, recent)
         self._check(self.lib.d2o_layer_reserve(self.ctx, layer, n, _np_ptr(b), _np_ptr(r)),
@@ -273,6 +285,11 @@ class D2O:
                     "d2o_prefill_events")
         r, e = nr.value, ne.value
         return ret[:r], evi[:e], tgt[:e], us[:e], ps[:e].astype(bool)
+
+
+KERNEL_IDS = {"attn_fwd": 0, "colsum": 1, "select": 2, "match_filter": 3, "match_refine": 4,
+              "merge": 5, "decode_attend": 6, "decode_update": 7, "decode_cosine": 8,
+              "decode_finish": 9}
 
 
 # ---- element conversions for host-side export / import (bit moves, no arithmetic) ----------

@@ -186,7 +186,14 @@ int d2o_create(const d2o_config* cfg, void* persistent_dev, size_t persistent_by
   return D2O_OK;
 }
 
-void d2o_destroy(d2o_ctx* ctx) { delete ctx; }
+void d2o_destroy(d2o_ctx* ctx) {
+  if (!ctx) return;
+  for (auto& t : ctx->timed) {
+    (void)hipEventDestroy(t.start);
+    (void)hipEventDestroy(t.stop);
+  }
+  delete ctx;
+}
 
 const char* d2o_last_error(const d2o_ctx* ctx) { return ctx ? ctx->err.c_str() : ""; }
 
@@ -551,6 +558,37 @@ int d2o_prefill_events(d2o_ctx* x, int32_t layer, int32_t b, int32_t h, int32_t*
   if (retained_pos) std::memcpy(retained_pos, ret.data(), cnt[0] * sizeof(int32_t));
   if (target_pos)
     for (int i = 0; i < cnt[1]; ++i) target_pos[i] = ret[tgt[i]];
+  return D2O_OK;
+}
+
+int d2o_timing_enable(d2o_ctx* x, int32_t on) {
+  if (!x) return D2O_ERR_INVALID_ARG;
+  x->timing = on != 0;
+  return D2O_OK;
+}
+
+int d2o_timing_read(d2o_ctx* x, int32_t kernel_id, double* total_ms, int64_t* launches, void* stream) {
+  if (!x || !total_ms || !launches || kernel_id < 0 || kernel_id >= D2O_K_COUNT) return D2O_ERR_INVALID_ARG;
+  D2O_HIP_CHECK(x, hipStreamSynchronize(static_cast<hipStream_t>(stream)));
+  double ms = 0.0;
+  int64_t cnt = 0;
+  std::vector<d2o_timed_launch> keep;
+  for (auto& t : x->timed) {
+    if (t.id != kernel_id) {
+      keep.push_back(t);
+      continue;
+    }
+    float f = 0.f;
+    D2O_HIP_CHECK(x, hipEventSynchronize(t.stop));
+    D2O_HIP_CHECK(x, hipEventElapsedTime(&f, t.start, t.stop));
+    ms += f;
+    ++cnt;
+    (void)hipEventDestroy(t.start);
+    (void)hipEventDestroy(t.stop);
+  }
+  x->timed.swap(keep);
+  *total_ms = ms;
+  *launches = cnt;
   return D2O_OK;
 }
 

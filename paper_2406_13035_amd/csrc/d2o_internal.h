@@ -42,9 +42,16 @@ struct LayerState {
 
 }  // namespace d2o
 
+struct d2o_timed_launch {
+  int id;
+  hipEvent_t start, stop;
+};
+
 struct d2o_ctx {
   d2o_config cfg;
   std::string err;
+  bool timing = false;
+  std::vector<d2o_timed_launch> timed;
   std::vector<d2o::LayerState> layers;
   std::vector<int64_t> used_slots;   // [B]
   std::vector<int64_t> used_chunks;  // [B]
@@ -108,6 +115,28 @@ int fail(d2o_ctx* ctx, int code, const std::string& msg);
     if (e_ != hipSuccess)                                                               \
       return d2o::fail(ctx, D2O_ERR_HIP, std::string(#expr) + ": " + hipGetErrorString(e_)); \
   } while (0)
+
+// Brackets the launches made during its lifetime with two events when timing is enabled.
+struct KernelTimer {
+  d2o_ctx* c;
+  hipStream_t s;
+  bool on;
+  d2o_timed_launch t;
+  KernelTimer(d2o_ctx* ctx, int id, hipStream_t stream) : c(ctx), s(stream), on(ctx->timing) {
+    if (!on) return;
+    t.id = id;
+    if (hipEventCreate(&t.start) != hipSuccess || hipEventCreate(&t.stop) != hipSuccess) {
+      on = false;
+      return;
+    }
+    (void)hipEventRecord(t.start, s);
+  }
+  ~KernelTimer() {
+    if (!on) return;
+    (void)hipEventRecord(t.stop, s);
+    c->timed.push_back(t);
+  }
+};
 
 // ---- kernel launchers (one per stage), defined in the .hip files ----
 hipError_t launch_prefill_f32(d2o_ctx* c, int layer, View Q, View K, View V, View O, int n,

@@ -476,26 +476,36 @@ __global__ __launch_bounds__(128) void decode_finish(DecodeArgs a) {
 }
 
 template <typename T, int D, int G>
-hipError_t run_decode(const DecodeArgs& a, int nl, int maxchunks, View q, View k, View v, View out, hipStream_t s) {
+hipError_t run_decode(d2o_ctx* c, const DecodeArgs& a, int nl, int maxchunks, View q, View k, View v, View out, hipStream_t s) {
   const int bh = a.B * a.Hkv;
   decode_append<T, D><<<dim3(bh, nl), 128, 0, s>>>(a, (const T*)k.ptr, k, (const T*)v.ptr, v);
-  decode_attend<T, D, G><<<dim3(maxchunks, bh, nl), 256, 0, s>>>(a, (const T*)q.ptr, q);
+  {
+    KernelTimer kt(c, D2O_K_DECODE_ATTEND, s);
+    decode_attend<T, D, G><<<dim3(maxchunks, bh, nl), 256, 0, s>>>(a, (const T*)q.ptr, q);
+  }
+  {
+  KernelTimer kt(c, D2O_K_DECODE_UPDATE, s);
   if (a.out_f32)
     decode_update<T, float, D, G><<<dim3(bh, nl), 256, 0, s>>>(a, (float*)out.ptr, out);
   else
     decode_update<T, T, D, G><<<dim3(bh, nl), 256, 0, s>>>(a, (T*)out.ptr, out);
-  decode_cosine<T, D><<<dim3(maxchunks, bh, nl), 256, 0, s>>>(a);
+  }
+  {
+    KernelTimer kt(c, D2O_K_DECODE_COSINE, s);
+    decode_cosine<T, D><<<dim3(maxchunks, bh, nl), 256, 0, s>>>(a);
+  }
+  KernelTimer kt(c, D2O_K_DECODE_FINISH, s);
   decode_finish<T, D><<<dim3(bh, nl), 128, 0, s>>>(a);
   return hipGetLastError();
 }
 
 template <typename T, int D>
-hipError_t run_decode_g(const DecodeArgs& a, int nl, int mc, View q, View k, View v, View out, hipStream_t s) {
+hipError_t run_decode_g(d2o_ctx* c, const DecodeArgs& a, int nl, int mc, View q, View k, View v, View out, hipStream_t s) {
   switch (a.G) {
-    case 1: return run_decode<T, D, 1>(a, nl, mc, q, k, v, out, s);
-    case 2: return run_decode<T, D, 2>(a, nl, mc, q, k, v, out, s);
-    case 4: return run_decode<T, D, 4>(a, nl, mc, q, k, v, out, s);
-    case 8: return run_decode<T, D, 8>(a, nl, mc, q, k, v, out, s);
+    case 1: return run_decode<T, D, 1>(c, a, nl, mc, q, k, v, out, s);
+    case 2: return run_decode<T, D, 2>(c, a, nl, mc, q, k, v, out, s);
+    case 4: return run_decode<T, D, 4>(c, a, nl, mc, q, k, v, out, s);
+    case 8: return run_decode<T, D, 8>(c, a, nl, mc, q, k, v, out, s);
     default: return hipErrorInvalidValue;
   }
 }
@@ -537,9 +547,9 @@ hipError_t launch_decode(d2o_ctx* c, int layer0, int nl, View q, View k, View v,
   int maxchunks = 1;
   for (int l = layer0; l < layer0 + nl; ++l)
     for (const auto& mt : c->layers[l].meta) maxchunks = std::max(maxchunks, (mt.budget + 1 + kChunk - 1) / kChunk);
-  if (cf.dtype == D2O_BF16) return run_decode_g<uint16_t, 128>(a, nl, maxchunks, q, k, v, out, s);
-  if (cf.head_dim == 64) return run_decode_g<float, 64>(a, nl, maxchunks, q, k, v, out, s);
-  return run_decode_g<float, 128>(a, nl, maxchunks, q, k, v, out, s);
+  if (cf.dtype == D2O_BF16) return run_decode_g<uint16_t, 128>(c, a, nl, maxchunks, q, k, v, out, s);
+  if (cf.head_dim == 64) return run_decode_g<float, 64>(c, a, nl, maxchunks, q, k, v, out, s);
+  return run_decode_g<float, 128>(c, a, nl, maxchunks, q, k, v, out, s);
 }
 
 }  // namespace d2o

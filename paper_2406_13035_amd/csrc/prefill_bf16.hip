@@ -352,9 +352,13 @@ hipError_t launch_prefill_bf16(d2o_ctx* c, int layer, View Q, View K, View V, Vi
       (const uint16_t*)V.ptr, V, c->vmax_bits, n);
   transpose_v<<<dim3(c->npad / 64, cf.n_kv_heads, cf.batch), 256, 0, s>>>((const uint16_t*)V.ptr, V, (uint16_t*)c->vt,
                                                                          c->vmax_bits, c->vt_unscale, n, c->npad);
+  {
+  KernelTimer kt(c, D2O_K_ATTN_FWD, s);
   attn_fwd_bf16<<<dim3(nblk, cf.n_q_heads, cf.batch), 256, 0, s>>>((const uint16_t*)Q.ptr, Q, (const uint16_t*)K.ptr, K,
                                                                   (const uint16_t*)c->vt, c->vt_unscale, O.ptr, O, c->lse,
                                                                   n, c->npad, G, cf.out_f32);
+  }
+  KernelTimer kt(c, D2O_K_COLSUM, s);
   colsum_bf16<<<dim3(nblk, cf.n_kv_heads, cf.batch), 256, 0, s>>>((const uint16_t*)Q.ptr, Q, (const uint16_t*)K.ptr, K,
                                                                  c->lse, score, c->varpart, n, c->npad, G,
                                                                  cf.n_q_heads);

@@ -172,13 +172,17 @@ hipError_t launch_prefill_f32(d2o_ctx* c, int layer, View Q, View K, View V, Vie
   float* score = c->score_pre + size_t(layer) * cf.batch * cf.n_kv_heads * c->npad;
   dim3 g1((n + 3) / 4, cf.n_q_heads, cf.batch), g2((n + 127) / 128, cf.n_kv_heads, cf.batch);
   if (cf.head_dim == 64) {
+    { KernelTimer kt(c, D2O_K_ATTN_FWD, s);
     attn_rows_f32<64><<<g1, 256, 0, s>>>((const float*)Q.ptr, Q, (const float*)K.ptr, K, (const float*)V.ptr, V,
-                                         (float*)O.ptr, O, c->lse, n, c->npad, G);
+                                         (float*)O.ptr, O, c->lse, n, c->npad, G); }
+    KernelTimer kt(c, D2O_K_COLSUM, s);
     colsum_f32<64><<<g2, 256, 0, s>>>((const float*)Q.ptr, Q, (const float*)K.ptr, K, c->lse, score, c->varpart, n,
                                       c->npad, G, cf.n_q_heads);
   } else {
+    { KernelTimer kt(c, D2O_K_ATTN_FWD, s);
     attn_rows_f32<128><<<g1, 256, 0, s>>>((const float*)Q.ptr, Q, (const float*)K.ptr, K, (const float*)V.ptr, V,
-                                          (float*)O.ptr, O, c->lse, n, c->npad, G);
+                                          (float*)O.ptr, O, c->lse, n, c->npad, G); }
+    KernelTimer kt(c, D2O_K_COLSUM, s);
     colsum_f32<128><<<g2, 256, 0, s>>>((const float*)Q.ptr, Q, (const float*)K.ptr, K, c->lse, score, c->varpart, n,
                                        c->npad, G, cf.n_q_heads);
   }

@@ -522,6 +522,7 @@ __global__ __launch_bounds__(256) void merge_kernel(const T* __restrict__ K, Vie
 hipError_t launch_select(d2o_ctx* c, int layer, int n, hipStream_t s) {
   const d2o_config& cf = c->cfg;
   const float* score = c->score_pre + size_t(layer) * cf.batch * cf.n_kv_heads * c->npad;
+  KernelTimer kt(c, D2O_K_SELECT, s);
   select_kernel<<<dim3(cf.n_kv_heads, cf.batch), 1024, 0, s>>>(score, c->meta + size_t(layer) * cf.batch * 4,
                                                                c->sel_ret, c->sel_evi, c->sel_cnt, n, c->npad,
                                                                cf.n_sink);
@@ -564,8 +565,12 @@ hipError_t launch_match(d2o_ctx* c, int layer, View K, int n, hipStream_t s) {
   if (cf.dtype == D2O_BF16) {
     invnorm_bf16<<<dim3((n + 15) / 16, cf.n_kv_heads, cf.batch), 256, 0, s>>>((const uint16_t*)K.ptr, K, c->invnorm, n,
                                                                              c->npad);
-    match_filter_bf16<<<dim3((me + 127) / 128, cf.n_kv_heads, cf.batch), 256, 0, s>>>(
-        (const uint16_t*)K.ptr, K, c->invnorm, c->sel_ret, c->sel_evi, c->sel_cnt, c->m_cand, c->npad);
+    {
+      KernelTimer kt(c, D2O_K_MATCH_FILTER, s);
+      match_filter_bf16<<<dim3((me + 127) / 128, cf.n_kv_heads, cf.batch), 256, 0, s>>>(
+          (const uint16_t*)K.ptr, K, c->invnorm, c->sel_ret, c->sel_evi, c->sel_cnt, c->m_cand, c->npad);
+    }
+    KernelTimer kt(c, D2O_K_MATCH_REFINE, s);
     match_refine<uint16_t, 128><<<gr, 256, 0, s>>>((const uint16_t*)K.ptr, K, c->sel_ret, c->sel_evi, c->sel_cnt,
                                                    c->m_cand, c->m_ustar, c->m_tgt, c->npad, 1);
   } else if (cf.head_dim == 64) {
@@ -594,6 +599,7 @@ hipError_t launch_merge(d2o_ctx* c, int layer, View K, View V, int n, hipStream_
   for (const auto& mt : c->layers[layer].meta) max_budget = std::max(max_budget, std::min(mt.budget, n));
   const int32_t* meta = c->meta + size_t(layer) * cf.batch * 4;
   const dim3 gr((max_budget + 3) / 4, cf.n_kv_heads, cf.batch);
+  KernelTimer kt(c, D2O_K_MERGE, s);
   if (cf.dtype == D2O_BF16) {
     merge_kernel<uint16_t, 128><<<gr, 256, 0, s>>>((const uint16_t*)K.ptr, K, (const uint16_t*)V.ptr, V, c->sel_evi,
                                                    c->sel_cnt, c->m_ustar, c->g_cnt, c->g_off, c->g_src, meta,
