@@ -85,6 +85,11 @@ void layout(d2o_ctx* x, char* persistent, char* scratch, size_t* pbytes, size_t*
   s.take(x->sel_cnt, bh * 2);
   s.take(x->invnorm, bh * np);
   s.take(x->m_cand, bh * np);
+  s.take(x->m_thr, bh * np);
+  s.take(x->amb_list, bh * np);
+  s.take(x->amb_cnt, bh);
+  s.take(x->m_ncand, bh * np);
+  s.take(x->m_clist, bh * np * 8);
   s.take(x->m_ustar, bh * np);
   s.take(x->m_tgt, bh * np);
   s.take(x->m_pass, bh * np);

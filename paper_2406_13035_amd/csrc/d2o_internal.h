@@ -88,6 +88,11 @@ struct d2o_ctx {
   int32_t* sel_cnt = nullptr;    // [B][Hkv][2]  n_ret, n_evi
   float* invnorm = nullptr;      // 1/|k_j| of every prompt key (fp32, filter only)
   int32_t* m_cand = nullptr;     // filter's best retained rank per evicted row; bit 31 = ambiguous
+  float* m_thr = nullptr;        // filter's acceptance threshold of a flagged row
+  int32_t* amb_list = nullptr;   // flagged evicted ranks, ascending
+  int32_t* amb_cnt = nullptr;    // [B][Hkv]
+  int32_t* m_ncand = nullptr;    // candidates collected for a flagged row
+  int32_t* m_clist = nullptr;    // [..][npad][8] their retained ranks
   double* m_ustar = nullptr;     // exact best similarity per evicted row
   int32_t* m_tgt = nullptr;      // exact match (retained rank)
   uint8_t* m_pass = nullptr;     // threshold test

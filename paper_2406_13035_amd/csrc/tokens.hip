@@ -196,16 +196,28 @@ __global__ __launch_bounds__(256) void invnorm_bf16(const uint16_t* __restrict__
 // Candidate filter on the matrix cores.  A workgroup owns 128 evicted rows (4 wavefronts x 32,
 // the stationary B operand) and streams the retained keys in tiles of 128 through LDS (the A
 // operand), so each lane owns one evicted row and sees 16 retained keys per MFMA tile.
-// Per row it tracks the best and second-best fp32 cosine and the best's retained rank; a row
-// whose two best values differ by less than kAmbiguous is flagged for the exact search.
-constexpr float kAmbiguous = 1.0e-4f;  // > 2 * (128 * 2^-23 + fp32 norm error): see match_refine
+//   COLLECT = false: per row, track the best and second-best fp32 cosine and the best's
+//     retained rank.  A row whose two best values differ by less than kAmbiguous is flagged and
+//     its acceptance threshold (best - kAmbiguous, in the un-normalised domain) is stored.
+//   COLLECT = true: second sweep over the flagged rows only (compacted list): every retained
+//     key whose fp32 cosine reaches the row's threshold is appended to the row's candidate
+//     list (up to kMaxCand; more than that falls back to the exhaustive search).  The sweep
+//     repeats the first one's arithmetic exactly, so the best value is found again.
+// kAmbiguous bounds twice the fp32 error of one cosine: at most one rounding per accumulated
+// product (128 * 2^-24 of |k_i||k_j|) plus the two fp32 inverse norms, 1.6e-5 in total.
+constexpr float kAmbiguous = 2.0e-5f;
+constexpr int kMaxCand = 8;
 constexpr int kLdM = 128 + 8;
 
+template <bool COLLECT>
 __global__ __launch_bounds__(256) void match_filter_bf16(const uint16_t* __restrict__ K, View kv,
                                                          const float* __restrict__ invn,
                                                          const int32_t* __restrict__ ret,
                                                          const int32_t* __restrict__ evi,
                                                          const int32_t* __restrict__ cnt, int32_t* __restrict__ cand,
+                                                         float* __restrict__ thr, const int32_t* __restrict__ amb_list,
+                                                         const int32_t* __restrict__ amb_cnt,
+                                                         int32_t* __restrict__ ncand, int32_t* __restrict__ clist,
                                                          int npad) {
   __shared__ __attribute__((aligned(16))) uint16_t Rs[128 * kLdM];
   __shared__ float rin[128];   // 1/|k| of the staged retained keys
@@ -213,27 +225,31 @@ __global__ __launch_bounds__(256) void match_filter_bf16(const uint16_t* __restr
   const int hk = blockIdx.y, b = blockIdx.z, Hkv = gridDim.y;
   const int64_t bh = int64_t(b) * Hkv + hk;
   const int nret = cnt[bh * 2], nevi = cnt[bh * 2 + 1];
+  const int nrows = COLLECT ? amb_cnt[bh] : nevi;
   const int e0 = blockIdx.x * 128;
-  if (e0 >= nevi) return;
+  if (e0 >= nrows) return;
   const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, m = lane & 31, h = lane >> 5;
   const uint16_t* kb = K + b * kv.sb + hk * kv.sh;
   const int32_t* rl = ret + bh * npad;
   const int32_t* el = evi + bh * npad;
   const float* inl = invn + bh * npad;
-  const int erank = e0 + w * 32 + m;
-  const int epos = el[min(erank, nevi - 1)];
+  const int row = e0 + w * 32 + m;
+  const bool live = row < nrows;
+  const int erank = COLLECT ? amb_list[bh * npad + min(row, nrows - 1)] : min(row, nrows - 1);
+  const int epos = el[erank];
   bf16x8 be[8];
 #pragma unroll
   for (int ks = 0; ks < 8; ++ks)
     be[ks] = *reinterpret_cast<const bf16x8*>(kb + int64_t(epos) * kv.sn + ks * 16 + h * 8);
   float m1 = -INFINITY, m2 = -INFINITY;
   int i1 = 0;
+  const float mythr = COLLECT ? thr[bh * npad + erank] : 0.f;
   for (int r0 = 0; r0 < nret; r0 += 128) {
     __syncthreads();
     for (int c = tid; c < 128 * 16; c += 256) {
-      const int row = c >> 4, col = (c & 15) * 8;
-      const int pos = rl[min(r0 + row, nret - 1)];
-      *reinterpret_cast<u32x4*>(&Rs[row * kLdM + col]) =
+      const int rrow = c >> 4, col = (c & 15) * 8;
+      const int pos = rl[min(r0 + rrow, nret - 1)];
+      *reinterpret_cast<u32x4*>(&Rs[rrow * kLdM + col]) =
           *reinterpret_cast<const u32x4*>(kb + int64_t(pos) * kv.sn + col);
     }
     if (tid < 128) {
@@ -257,24 +273,55 @@ __global__ __launch_bounds__(256) void match_filter_bf16(const uint16_t* __restr
       for (int r = 0; r < 16; ++r) {
         const int rr = st * 32 + (r >> 2) * 8 + h * 4 + (r & 3);
         const float t = fmaf(s[r], rin[rr], rbias[rr]);
-        const bool gt = t > m1;
-        i1 = gt ? (r0 + rr) : i1;
-        m2 = __builtin_amdgcn_fmed3f(m1, m2, t);
-        m1 = fmaxf(m1, t);
+        if (COLLECT) {
+          if (live && t >= mythr) {
+            const int k = atomicAdd(&ncand[bh * npad + erank], 1);
+            if (k < kMaxCand) clist[(bh * npad + erank) * kMaxCand + k] = r0 + rr;
+          }
+        } else {
+          const bool gt = t > m1;
+          i1 = gt ? (r0 + rr) : i1;
+          m2 = __builtin_amdgcn_fmed3f(m1, m2, t);
+          m1 = fmaxf(m1, t);
+        }
       }
     }
   }
+  if (COLLECT) return;
   // combine the two lane halves that share an evicted row
   const float om1 = __shfl_xor(m1, 32, 64), om2 = __shfl_xor(m2, 32, 64);
   const int oi1 = __shfl_xor(i1, 32, 64);
   const float best = fmaxf(m1, om1);
   const float second = fmaxf(fminf(m1, om1), fmaxf(m2, om2));
   const int bi = (om1 > m1) ? oi1 : i1;
-  if (h == 0 && erank < nevi) {
+  if (h == 0 && live) {
     const float ie = inl[epos];
-    const bool amb = !((best - second) * ie >= kAmbiguous);  // also true for NaN / equal
+    const float margin = ie > 0.f ? kAmbiguous / ie : INFINITY;  // threshold in the un-normalised domain
+    const bool amb = !(best - second >= margin);                // also true for NaN / equal / zero norm
     cand[bh * npad + erank] = bi | (amb ? int(0x80000000u) : 0);
+    thr[bh * npad + erank] = best - margin;
   }
+}
+
+// Ordered list of the flagged rows of one (sequence, KV head), and cleared candidate counters.
+__global__ __launch_bounds__(1024) void amb_compact_kernel(const int32_t* __restrict__ cand, const int32_t* __restrict__ cnt,
+                                                           int32_t* __restrict__ amb_list, int32_t* __restrict__ amb_cnt,
+                                                           int32_t* __restrict__ ncand, int npad) {
+  __shared__ int wa[16], wb[16];
+  const int hk = blockIdx.x, b = blockIdx.y, Hkv = gridDim.x;
+  const int64_t bh = int64_t(b) * Hkv + hk;
+  const int nevi = cnt[bh * 2 + 1];
+  int base = 0;
+  for (int i0 = 0; i0 < nevi; i0 += blockDim.x) {
+    const int i = i0 + threadIdx.x;
+    const bool amb = i < nevi && cand[bh * npad + i] < 0;
+    if (i < nevi) ncand[bh * npad + i] = 0;
+    int ex, exd, tot, totd;
+    block_scan2(amb, false, ex, exd, tot, totd, wa, wb);
+    if (amb) amb_list[bh * npad + base + ex] = i;
+    base += tot;
+  }
+  if (threadIdx.x == 0) amb_cnt[bh] = base;
 }
 
 // Exact similarity in fp64, operation order of Eq. 9 as written: dot / (|k_i| * |k_j|), 0 when
@@ -303,7 +350,8 @@ __device__ __forceinline__ void load8<float>(const float* p, double* out) {
 template <typename T, int D>
 __global__ __launch_bounds__(256) void match_refine(const T* __restrict__ K, View kv, const int32_t* __restrict__ ret,
                                                     const int32_t* __restrict__ evi, const int32_t* __restrict__ cnt,
-                                                    const int32_t* __restrict__ cand, double* __restrict__ ustar,
+                                                    const int32_t* __restrict__ cand, const int32_t* __restrict__ ncand,
+                                                    const int32_t* __restrict__ clist, double* __restrict__ ustar,
                                                     int32_t* __restrict__ tgt, int npad, int use_filter) {
   __shared__ double ke[4][D];
   const int hk = blockIdx.y, b = blockIdx.z, Hkv = gridDim.y;
@@ -327,22 +375,44 @@ __global__ __launch_bounds__(256) void match_refine(const T* __restrict__ K, Vie
   __syncthreads();
   ne = wave_sum(ne);
   const double sne = sqrt(ne);
-  const int cnd = use_filter ? cand[bh * npad + erank] : int(0x80000000u);
+  // candidates: one (unambiguous), a short list (ambiguous), or every retained key
+  int ncd = 0;
+  const int32_t* cl = nullptr;
+  int single = -1;
+  if (use_filter) {
+    const int cnd = cand[bh * npad + erank];
+    if (cnd >= 0) {
+      single = cnd;
+      ncd = 1;
+    } else {
+      ncd = ncand[bh * npad + erank];
+      cl = clist + (bh * npad + erank) * kMaxCand;
+      if (ncd > kMaxCand || ncd == 0) ncd = -1;  // overflow (or zero-norm row): exhaustive search
+    }
+  } else {
+    ncd = -1;
+  }
   double best = -2.0;
   int bj = 0x7FFFFFFF;
-  if (cnd >= 0) {
-    const T* rr = kb + int64_t(rl[cnd]) * kv.sn;
-    double dot = 0.0, nr = 0.0;
-    for (int c = lane; c < D; c += 64) {
-      const double y = Elem<T>::to_f64(rr[c]);
-      dot += ke[w][c] * y;
-      nr += y * y;
+  if (ncd >= 0) {
+    for (int q = 0; q < ncd; ++q) {
+      const int j = single >= 0 ? single : cl[q];
+      const T* rr = kb + int64_t(rl[j]) * kv.sn;
+      double dot = 0.0, nr = 0.0;
+      for (int c = lane; c < D; c += 64) {
+        const double y = Elem<T>::to_f64(rr[c]);
+        dot += ke[w][c] * y;
+        nr += y * y;
+      }
+      dot = wave_sum(dot);
+      nr = wave_sum(nr);
+      const double den = sne * sqrt(nr);
+      const double u = den > 0.0 ? dot / den : 0.0;
+      if (u > best || (u == best && j < bj)) {
+        best = u;
+        bj = j;
+      }
     }
-    dot = wave_sum(dot);
-    nr = wave_sum(nr);
-    const double den = sne * sqrt(nr);
-    best = den > 0.0 ? dot / den : 0.0;
-    bj = cnd;
   } else {
     for (int j = lane; j < nret; j += 64) {
       const T* rr = kb + int64_t(rl[j]) * kv.sn;
@@ -563,22 +633,31 @@ hipError_t launch_match(d2o_ctx* c, int layer, View K, int n, hipStream_t s) {
   if (me == 0) return hipSuccess;
   const dim3 gr((me + 3) / 4, cf.n_kv_heads, cf.batch);
   if (cf.dtype == D2O_BF16) {
+    const dim3 gf((me + 127) / 128, cf.n_kv_heads, cf.batch);
     invnorm_bf16<<<dim3((n + 15) / 16, cf.n_kv_heads, cf.batch), 256, 0, s>>>((const uint16_t*)K.ptr, K, c->invnorm, n,
                                                                              c->npad);
     {
       KernelTimer kt(c, D2O_K_MATCH_FILTER, s);
-      match_filter_bf16<<<dim3((me + 127) / 128, cf.n_kv_heads, cf.batch), 256, 0, s>>>(
-          (const uint16_t*)K.ptr, K, c->invnorm, c->sel_ret, c->sel_evi, c->sel_cnt, c->m_cand, c->npad);
+      match_filter_bf16<false><<<gf, 256, 0, s>>>((const uint16_t*)K.ptr, K, c->invnorm, c->sel_ret, c->sel_evi,
+                                                  c->sel_cnt, c->m_cand, c->m_thr, c->amb_list, c->amb_cnt,
+                                                  c->m_ncand, c->m_clist, c->npad);
+      amb_compact_kernel<<<dim3(cf.n_kv_heads, cf.batch), 1024, 0, s>>>(c->m_cand, c->sel_cnt, c->amb_list,
+                                                                        c->amb_cnt, c->m_ncand, c->npad);
+      match_filter_bf16<true><<<gf, 256, 0, s>>>((const uint16_t*)K.ptr, K, c->invnorm, c->sel_ret, c->sel_evi,
+                                                 c->sel_cnt, c->m_cand, c->m_thr, c->amb_list, c->amb_cnt,
+                                                 c->m_ncand, c->m_clist, c->npad);
     }
     KernelTimer kt(c, D2O_K_MATCH_REFINE, s);
     match_refine<uint16_t, 128><<<gr, 256, 0, s>>>((const uint16_t*)K.ptr, K, c->sel_ret, c->sel_evi, c->sel_cnt,
-                                                   c->m_cand, c->m_ustar, c->m_tgt, c->npad, 1);
+                                                   c->m_cand, c->m_ncand, c->m_clist, c->m_ustar, c->m_tgt, c->npad, 1);
   } else if (cf.head_dim == 64) {
+    KernelTimer kt(c, D2O_K_MATCH_REFINE, s);
     match_refine<float, 64><<<gr, 256, 0, s>>>((const float*)K.ptr, K, c->sel_ret, c->sel_evi, c->sel_cnt, c->m_cand,
-                                               c->m_ustar, c->m_tgt, c->npad, 0);
+                                               c->m_ncand, c->m_clist, c->m_ustar, c->m_tgt, c->npad, 0);
   } else {
+    KernelTimer kt(c, D2O_K_MATCH_REFINE, s);
     match_refine<float, 128><<<gr, 256, 0, s>>>((const float*)K.ptr, K, c->sel_ret, c->sel_evi, c->sel_cnt, c->m_cand,
-                                                c->m_ustar, c->m_tgt, c->npad, 0);
+                                                c->m_ncand, c->m_clist, c->m_ustar, c->m_tgt, c->npad, 0);
   }
   return hipGetLastError();
 }
