@@ -111,135 +111,190 @@ __global__ __launch_bounds__(256) void transpose_v(const uint16_t* __restrict__ 
 // B-operand slice the P V product needs, with no cross-lane movement.
 __device__ __forceinline__ int perm_key(int m) { return (m & ~0xC) | ((m & 4) << 1) | ((m & 8) >> 1); }
 
+constexpr int kKsElems = 64 * kLdK;   // one K tile in LDS
+constexpr int kVsElems = kD * kLdV;   // one V^T tile in LDS
+constexpr int kAttnSmemBytes = 2 * (kKsElems + kVsElems) * 2;
+
+// 256 query rows per workgroup: 4 wavefronts x 64 rows (two 32-row MFMA column blocks that
+// share every K / V^T operand read from LDS, which halves LDS traffic per MFMA).  K and V^T
+// tiles of 64 keys are double-buffered in LDS; the next tile's global loads are issued before
+// the current tile's MFMAs and written to the other buffer after them (one barrier per tile).
 __global__ __launch_bounds__(256) void attn_fwd_bf16(const uint16_t* __restrict__ Q, View qv,
                                                      const uint16_t* __restrict__ K, View kv,
                                                      const uint16_t* __restrict__ VT, const float* __restrict__ unscale,
-                                                     void* __restrict__ O, View ov, float* __restrict__ lse2, int n, int npad, int G, int out_f32) {
-  __shared__ __attribute__((aligned(16))) uint16_t Ks[64 * kLdK];
-  __shared__ __attribute__((aligned(16))) uint16_t Vs[kD * kLdV];
+                                                     void* __restrict__ O, View ov, float* __restrict__ lse2, int n,
+                                                     int npad, int G, int out_f32) {
+  extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
+  uint16_t* Ks = smem;                 // [2][kKsElems]
+  uint16_t* Vs = smem + 2 * kKsElems;  // [2][kVsElems]
   const int nblk = gridDim.x;
   const int rb = (nblk - 1 - blockIdx.x) * kPrefillBM;  // longest rows first
   const int hq = blockIdx.y, b = blockIdx.z, Hq = gridDim.y, hk = hq / G, Hkv = Hq / G;
   const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, m = lane & 31, h = lane >> 5;
-  const int q_row = rb + w * 32 + m;
-  const int wave_row_max = rb + w * 32 + 31;
+  const int wr0 = rb + w * 64;  // first row of this wavefront
   const float scale2 = kLog2e / sqrtf(float(kD));
 
-  const uint16_t* qp = Q + b * qv.sb + hq * qv.sh + int64_t(min(q_row, n - 1)) * qv.sn;
-  bf16x8 bq[8];
+  bf16x8 bq[2][8];
 #pragma unroll
-  for (int ks = 0; ks < 8; ++ks) bq[ks] = *reinterpret_cast<const bf16x8*>(qp + ks * 16 + h * 8);
-
+  for (int j = 0; j < 2; ++j) {
+    const uint16_t* qp = Q + b * qv.sb + hq * qv.sh + int64_t(min(wr0 + j * 32 + m, n - 1)) * qv.sn;
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) bq[j][ks] = *reinterpret_cast<const bf16x8*>(qp + ks * 16 + h * 8);
+  }
   const uint16_t* kbase = K + b * kv.sb + hk * kv.sh;
   const uint16_t* vtbase = VT + (int64_t(b) * Hkv + hk) * kD * npad;
 
-  f32x16 o[4];
+  f32x16 o[2][4];
 #pragma unroll
-  for (int i = 0; i < 4; ++i)
-#pragma unroll
-    for (int r = 0; r < 16; ++r) o[i][r] = 0.f;
-  float mrun = -INFINITY, lsum = 0.f;
-
-  const int last_key = min(rb + kPrefillBM - 1, n - 1);
-  const int ntile = last_key / 64 + 1;
-  const int krow = perm_key(m);
-  for (int t = 0; t < ntile; ++t) {
-    const int k0 = t * 64;
-    __syncthreads();
-    for (int c = tid; c < 64 * 16; c += 256) {
-      const int row = c >> 4, col = (c & 15) * 8;
-      const u32x4 v = *reinterpret_cast<const u32x4*>(kbase + int64_t(min(k0 + row, n - 1)) * kv.sn + col);
-      *reinterpret_cast<u32x4*>(&Ks[row * kLdK + col]) = v;
-    }
-    for (int c = tid; c < kD * 8; c += 256) {
-      const int dd = c >> 3, kc = (c & 7) * 8;
-      const u32x4 v = *reinterpret_cast<const u32x4*>(vtbase + int64_t(dd) * npad + k0 + kc);
-      *reinterpret_cast<u32x4*>(&Vs[dd * kLdV + kc]) = v;
-    }
-    __syncthreads();
-    if (k0 > wave_row_max) continue;  // whole tile is above this wavefront's diagonal
-
-    f32x16 s[2];
-#pragma unroll
-    for (int st = 0; st < 2; ++st) {
-#pragma unroll
-      for (int r = 0; r < 16; ++r) s[st][r] = 0.f;
-#pragma unroll
-      for (int ks = 0; ks < 8; ++ks) {
-        const bf16x8 a = *reinterpret_cast<const bf16x8*>(&Ks[(st * 32 + krow) * kLdK + ks * 16 + h * 8]);
-        s[st] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bq[ks], s[st], 0, 0, 0);
-      }
-    }
-    // register r of sub-tile st holds key k0 + 32*st + 16*(r/8) + 8*h + r%8 for query q_row
-    if (k0 + 63 > rb + w * 32) {  // tile touches the diagonal of this wavefront
-#pragma unroll
-      for (int st = 0; st < 2; ++st)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int key = k0 + st * 32 + (r >> 3) * 16 + h * 8 + (r & 7);
-          if (key > q_row) s[st][r] = -INFINITY;
-        }
-    }
-    float mx = s[0][0];
-#pragma unroll
-    for (int st = 0; st < 2; ++st)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[st][r]);
-    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-    const float mnew = fmaxf(mrun, fmaf(mx, scale2, -kPShift));  // exponent reference, 2^12 headroom
-    const float alpha = exp2f(mrun - mnew);
-    mrun = mnew;
-    float psum = 0.f;
-    f16x8 pb[2][2];
-#pragma unroll
-    for (int st = 0; st < 2; ++st)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const float p = exp2f(fmaf(s[st][r], scale2, -mnew));
-        psum += p;
-        pb[st][r >> 3][r & 7] = (_Float16)p;
-      }
-    lsum = fmaf(lsum, alpha, psum);
+  for (int j = 0; j < 2; ++j)
 #pragma unroll
     for (int i = 0; i < 4; ++i)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) o[i][r] *= alpha;
+      for (int r = 0; r < 16; ++r) o[j][i][r] = 0.f;
+  float mrun[2] = {-INFINITY, -INFINITY}, lsum[2] = {0.f, 0.f};
+
+  const int last_key = min(rb + kPrefillBM - 1, n - 1);
+  const int ntile = last_key / 64 + 1;
+
+  // staging: each thread moves 4 16-byte chunks of K and 4 of V^T per tile
+  u32x4 kr[4], vr[4];
+  auto issue = [&](int t) {
+    const int k0 = t * 64;
 #pragma unroll
-    for (int st = 0; st < 2; ++st)
+    for (int i = 0; i < 4; ++i) {
+      const int c = tid + 256 * i;
+      const int row = c >> 4, col = (c & 15) * 8;
+      kr[i] = *reinterpret_cast<const u32x4*>(kbase + int64_t(min(k0 + row, n - 1)) * kv.sn + col);
+      const int dd = c >> 3, kc = (c & 7) * 8;
+      vr[i] = *reinterpret_cast<const u32x4*>(vtbase + int64_t(dd) * npad + k0 + kc);
+    }
+  };
+  auto stage = [&](int buf) {
 #pragma unroll
-      for (int kb = 0; kb < 2; ++kb)
+    for (int i = 0; i < 4; ++i) {
+      const int c = tid + 256 * i;
+      const int row = c >> 4, col = (c & 15) * 8;
+      // key r of a 32-key sub-tile is stored at LDS row perm_key(r) (an involution), so that
+      // MFMA row m, which must see key perm_key(m), reads LDS row m: consecutive rows, no
+      // bank conflicts
+      const int lrow = (row & 32) | perm_key(row & 31);
+      *reinterpret_cast<u32x4*>(&Ks[buf * kKsElems + lrow * kLdK + col]) = kr[i];
+      const int dd = c >> 3, kc = (c & 7) * 8;
+      *reinterpret_cast<u32x4*>(&Vs[buf * kVsElems + dd * kLdV + kc]) = vr[i];
+    }
+  };
+  issue(0);
+  stage(0);
+  __syncthreads();
+
+  for (int t = 0; t < ntile; ++t) {
+    const int k0 = t * 64, buf = t & 1;
+    const bool more = t + 1 < ntile;
+    if (more) issue(t + 1);
+    if (k0 <= wr0 + 63) {  // otherwise the whole tile is above this wavefront's diagonal
+      const uint16_t* ksb = Ks + buf * kKsElems;
+      const uint16_t* vsb = Vs + buf * kVsElems;
+      f32x16 s[2][2];
 #pragma unroll
-        for (int dc = 0; dc < 4; ++dc) {
-          const f16x8 a = *reinterpret_cast<const f16x8*>(&Vs[(dc * 32 + m) * kLdV + st * 32 + kb * 16 + h * 8]);
-          o[dc] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, pb[st][kb], o[dc], 0, 0, 0);
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int st = 0; st < 2; ++st)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) s[j][st][r] = 0.f;
+#pragma unroll
+      for (int st = 0; st < 2; ++st)
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) {
+          const bf16x8 a = *reinterpret_cast<const bf16x8*>(&ksb[(st * 32 + m) * kLdK + ks * 16 + h * 8]);
+          s[0][st] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bq[0][ks], s[0][st], 0, 0, 0);
+          s[1][st] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bq[1][ks], s[1][st], 0, 0, 0);
         }
-  }
-  const float ltot = lsum + __shfl_xor(lsum, 32, 64);
-  if (q_row < n) {
-    if (h == 0) lse2[(int64_t(b) * Hq + hq) * npad + q_row] = mrun + log2f(ltot);
-    if (O) {
-      const float inv = unscale[b * Hkv + hk] / ltot;
-      const int64_t ooff = b * ov.sb + hq * ov.sh + int64_t(q_row) * ov.sn;
+      // register r of sub-tile st holds key k0 + 32*st + 16*(r/8) + 8*h + r%8
+      f16x8 pb[2][2][2];
+      const bool diag = k0 + 63 > wr0;
 #pragma unroll
-      for (int dc = 0; dc < 4; ++dc)
+      for (int j = 0; j < 2; ++j) {
+        const int q_row = wr0 + j * 32 + m;
+        if (diag) {
 #pragma unroll
-        for (int rg = 0; rg < 4; ++rg) {
-          // registers 4*rg .. 4*rg+3 hold d = 32*dc + 8*rg + 4*h + 0..3
-          const int dd = dc * 32 + rg * 8 + h * 4;
-          if (out_f32) {
-            f32x4 v;
+          for (int st = 0; st < 2; ++st)
 #pragma unroll
-            for (int i = 0; i < 4; ++i) v[i] = o[dc][4 * rg + i] * inv;
-            *reinterpret_cast<f32x4*>(static_cast<float*>(O) + ooff + dd) = v;
-          } else {
-            u32x2 v;
-            v[0] = Elem<uint16_t>::from_f32(o[dc][4 * rg + 0] * inv) |
-                   (uint32_t(Elem<uint16_t>::from_f32(o[dc][4 * rg + 1] * inv)) << 16);
-            v[1] = Elem<uint16_t>::from_f32(o[dc][4 * rg + 2] * inv) |
-                   (uint32_t(Elem<uint16_t>::from_f32(o[dc][4 * rg + 3] * inv)) << 16);
-            *reinterpret_cast<u32x2*>(static_cast<uint16_t*>(O) + ooff + dd) = v;
+            for (int r = 0; r < 16; ++r) {
+              const int key = k0 + st * 32 + (r >> 3) * 16 + h * 8 + (r & 7);
+              if (key > q_row) s[j][st][r] = -INFINITY;
+            }
+        }
+        float mx = s[j][0][0];
+#pragma unroll
+        for (int st = 0; st < 2; ++st)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[j][st][r]);
+        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+        const float mnew = fmaxf(mrun[j], fmaf(mx, scale2, -kPShift));  // exponent reference, 2^12 headroom
+        const bool grew = mnew > mrun[j];
+        const float alpha = __builtin_amdgcn_exp2f(mrun[j] - mnew);
+        mrun[j] = mnew;
+        float psum = 0.f;
+#pragma unroll
+        for (int st = 0; st < 2; ++st)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const float p = __builtin_amdgcn_exp2f(fmaf(s[j][st][r], scale2, -mnew));
+            psum += p;
+            pb[j][st][r >> 3][r & 7] = (_Float16)p;
           }
+        lsum[j] = fmaf(lsum[j], alpha, psum);
+        if (__any(grew)) {  // wavefront-uniform: skip the rescale when no row's maximum moved
+#pragma unroll
+          for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) o[j][i][r] *= alpha;
         }
+      }
+#pragma unroll
+      for (int st = 0; st < 2; ++st)
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+          for (int dc = 0; dc < 4; ++dc) {
+            const f16x8 a = *reinterpret_cast<const f16x8*>(&vsb[(dc * 32 + m) * kLdV + st * 32 + kb * 16 + h * 8]);
+            o[0][dc] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, pb[0][st][kb], o[0][dc], 0, 0, 0);
+            o[1][dc] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, pb[1][st][kb], o[1][dc], 0, 0, 0);
+          }
+    }
+    if (more) stage(buf ^ 1);
+    __syncthreads();
+  }
+#pragma unroll
+  for (int j = 0; j < 2; ++j) {
+    const int q_row = wr0 + j * 32 + m;
+    const float ltot = lsum[j] + __shfl_xor(lsum[j], 32, 64);
+    if (q_row < n) {
+      if (h == 0) lse2[(int64_t(b) * Hq + hq) * npad + q_row] = mrun[j] + log2f(ltot);
+      if (O) {
+        const float inv = unscale[b * Hkv + hk] / ltot;
+        const int64_t ooff = b * ov.sb + hq * ov.sh + int64_t(q_row) * ov.sn;
+#pragma unroll
+        for (int dc = 0; dc < 4; ++dc)
+#pragma unroll
+          for (int rg = 0; rg < 4; ++rg) {
+            // registers 4*rg .. 4*rg+3 hold d = 32*dc + 8*rg + 4*h + 0..3
+            const int dd = dc * 32 + rg * 8 + h * 4;
+            if (out_f32) {
+              f32x4 v;
+#pragma unroll
+              for (int i = 0; i < 4; ++i) v[i] = o[j][dc][4 * rg + i] * inv;
+              *reinterpret_cast<f32x4*>(static_cast<float*>(O) + ooff + dd) = v;
+            } else {
+              u32x2 v;
+              v[0] = Elem<uint16_t>::from_f32(o[j][dc][4 * rg + 0] * inv) |
+                     (uint32_t(Elem<uint16_t>::from_f32(o[j][dc][4 * rg + 1] * inv)) << 16);
+              v[1] = Elem<uint16_t>::from_f32(o[j][dc][4 * rg + 2] * inv) |
+                     (uint32_t(Elem<uint16_t>::from_f32(o[j][dc][4 * rg + 3] * inv)) << 16);
+              *reinterpret_cast<u32x2*>(static_cast<uint16_t*>(O) + ooff + dd) = v;
+            }
+          }
+      }
     }
   }
 }
@@ -345,7 +400,15 @@ hipError_t launch_prefill_bf16(d2o_ctx* c, int layer, View Q, View K, View V, Vi
   const d2o_config& cf = c->cfg;
   const int G = cf.n_q_heads / cf.n_kv_heads;
   float* score = c->score_pre + size_t(layer) * cf.batch * cf.n_kv_heads * c->npad;
-  const int nblk = (n + 127) / 128;
+  const int nblk = (n + kPrefillBM - 1) / kPrefillBM;
+  const int nblk_col = (n + kColBN - 1) / kColBN;
+  static bool attr_set = false;
+  if (!attr_set) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_fwd_bf16),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, kAttnSmemBytes);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
   const int nbh = cf.batch * cf.n_kv_heads;
   zero_u32<<<(nbh + 255) / 256, 256, 0, s>>>(c->vmax_bits, nbh);
   vabsmax_kernel<<<dim3(std::min(64, (n * 16 + 255) / 256), cf.n_kv_heads, cf.batch), 256, 0, s>>>(
@@ -354,12 +417,12 @@ hipError_t launch_prefill_bf16(d2o_ctx* c, int layer, View Q, View K, View V, Vi
                                                                          c->vmax_bits, c->vt_unscale, n, c->npad);
   {
   KernelTimer kt(c, D2O_K_ATTN_FWD, s);
-  attn_fwd_bf16<<<dim3(nblk, cf.n_q_heads, cf.batch), 256, 0, s>>>((const uint16_t*)Q.ptr, Q, (const uint16_t*)K.ptr, K,
+  attn_fwd_bf16<<<dim3(nblk, cf.n_q_heads, cf.batch), 256, kAttnSmemBytes, s>>>((const uint16_t*)Q.ptr, Q, (const uint16_t*)K.ptr, K,
                                                                   (const uint16_t*)c->vt, c->vt_unscale, O.ptr, O, c->lse,
                                                                   n, c->npad, G, cf.out_f32);
   }
   KernelTimer kt(c, D2O_K_COLSUM, s);
-  colsum_bf16<<<dim3(nblk, cf.n_kv_heads, cf.batch), 256, 0, s>>>((const uint16_t*)Q.ptr, Q, (const uint16_t*)K.ptr, K,
+  colsum_bf16<<<dim3(nblk_col, cf.n_kv_heads, cf.batch), 256, 0, s>>>((const uint16_t*)Q.ptr, Q, (const uint16_t*)K.ptr, K,
                                                                  c->lse, score, c->varpart, n, c->npad, G,
                                                                  cf.n_q_heads);
   return hipGetLastError();
