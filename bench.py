@@ -135,15 +135,19 @@ def main():
     ap.add_argument("--cfg", type=int, default=3, help="benchmark configuration 1..5")
     ap.add_argument("--decode-steps", type=int, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--layers", type=int, default=None,
+                    help="run only this many layers (profiling aid; the metric needs all)")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py measures one GPU: this build has no multi-GPU path (see DESIGN.md, "
-              "'How the path would shard'); run with --gpus 1", file=sys.stderr)
+        print("bench.py measures one GPU: this build has no multi-GPU path (one GPU's share "
+              "of the work is what is measured); run with --gpus 1", file=sys.stderr)
         sys.exit(2)
     if not torch.cuda.is_available():
         print("no GPU visible: the D2O library has no CPU path", file=sys.stderr)
         sys.exit(3)
     w = synth.WORKLOADS[args.cfg]
+    if args.layers:
+        w = w.scaled(n_layers=args.layers)
     dsteps = args.decode_steps or w.decode_steps
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)

@@ -16,7 +16,7 @@ def build(verbose: bool = False) -> str:
     cmd = [hipcc, "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
            "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
            "-I", os.path.join(ROOT, "include"), "-I", os.path.join(HERE, "csrc"),
-           "-Wno-unused-value", "-o", LIB] + [os.path.join(HERE, "csrc", s) for s in SOURCES]
+           "-Wno-unused-value", "-o", LIB] + os.environ.get("D2O_EXTRA_FLAGS", "").split() + [os.path.join(HERE, "csrc", s) for s in SOURCES]
     res = subprocess.run(cmd, capture_output=True, text=True)
     msgs = "\n".join(l for l in (res.stdout + res.stderr).splitlines()
                      if "packed-fp32-ops" not in l)

@@ -12,7 +12,6 @@
 namespace d2o {
 
 constexpr int kChunk = 256;        // cache slots handled by one workgroup in the decode kernels
-constexpr int kPrefillBM = 256;    // query rows per workgroup, prefill attention (bf16)
 constexpr int kColBN = 128;        // keys per workgroup, column-sum pass (bf16)
 
 // A strided [b][head][token][d] (or [layer][b][head][d]) tensor, strides in elements.

@@ -114,12 +114,16 @@ __device__ __forceinline__ int perm_key(int m) { return (m & ~0xC) | ((m & 4) <<
 constexpr int kKsElems = 64 * kLdK;   // one K tile in LDS
 constexpr int kVsElems = kD * kLdV;   // one V^T tile in LDS
 constexpr int kAttnSmemBytes = 2 * (kKsElems + kVsElems) * 2;
+constexpr int kAttnRW = 1;                     // 32-row blocks per wavefront
+constexpr int kAttnNW = 8;                     // wavefronts per workgroup
+constexpr int kAttnBM = 32 * kAttnRW * kAttnNW;
 
 // 256 query rows per workgroup: 4 wavefronts x 64 rows (two 32-row MFMA column blocks that
 // share every K / V^T operand read from LDS, which halves LDS traffic per MFMA).  K and V^T
 // tiles of 64 keys are double-buffered in LDS; the next tile's global loads are issued before
 // the current tile's MFMAs and written to the other buffer after them (one barrier per tile).
-__global__ __launch_bounds__(256) void attn_fwd_bf16(const uint16_t* __restrict__ Q, View qv,
+template <int RW, int NW>
+__global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_fwd_bf16(const uint16_t* __restrict__ Q, View qv,
                                                      const uint16_t* __restrict__ K, View kv,
                                                      const uint16_t* __restrict__ VT, const float* __restrict__ unscale,
                                                      void* __restrict__ O, View ov, float* __restrict__ lse2, int n,
@@ -128,15 +132,19 @@ __global__ __launch_bounds__(256) void attn_fwd_bf16(const uint16_t* __restrict_
   uint16_t* Ks = smem;                 // [2][kKsElems]
   uint16_t* Vs = smem + 2 * kKsElems;  // [2][kVsElems]
   const int nblk = gridDim.x;
-  const int rb = (nblk - 1 - blockIdx.x) * kPrefillBM;  // longest rows first
   const int hq = blockIdx.y, b = blockIdx.z, Hq = gridDim.y, hk = hq / G, Hkv = Hq / G;
   const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, m = lane & 31, h = lane >> 5;
-  const int wr0 = rb + w * 64;  // first row of this wavefront
+  constexpr int kWR = 32 * RW;   // rows per wavefront
+  constexpr int NT = 64 * NW;    // threads
+  constexpr int NCH = 1024 / NT;  // 16-byte chunks of each tile per thread
+  constexpr int BM = NW * kWR;   // query rows per workgroup
+  const int rb = (nblk - 1 - blockIdx.x) * BM;  // longest rows first
+  const int wr0 = rb + w * kWR;  // first row of this wavefront
   const float scale2 = kLog2e / sqrtf(float(kD));
 
-  bf16x8 bq[2][8];
+  bf16x8 bq[RW][8];
 #pragma unroll
-  for (int j = 0; j < 2; ++j) {
+  for (int j = 0; j < RW; ++j) {
     const uint16_t* qp = Q + b * qv.sb + hq * qv.sh + int64_t(min(wr0 + j * 32 + m, n - 1)) * qv.sn;
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) bq[j][ks] = *reinterpret_cast<const bf16x8*>(qp + ks * 16 + h * 8);
@@ -144,25 +152,30 @@ __global__ __launch_bounds__(256) void attn_fwd_bf16(const uint16_t* __restrict_
   const uint16_t* kbase = K + b * kv.sb + hk * kv.sh;
   const uint16_t* vtbase = VT + (int64_t(b) * Hkv + hk) * kD * npad;
 
-  f32x16 o[2][4];
+  f32x16 o[RW][4];
 #pragma unroll
-  for (int j = 0; j < 2; ++j)
+  for (int j = 0; j < RW; ++j)
 #pragma unroll
     for (int i = 0; i < 4; ++i)
 #pragma unroll
       for (int r = 0; r < 16; ++r) o[j][i][r] = 0.f;
-  float mrun[2] = {-INFINITY, -INFINITY}, lsum[2] = {0.f, 0.f};
+  float mrun[RW], lsum[RW];
+#pragma unroll
+  for (int j = 0; j < RW; ++j) {
+    mrun[j] = -INFINITY;
+    lsum[j] = 0.f;
+  }
 
-  const int last_key = min(rb + kPrefillBM - 1, n - 1);
+  const int last_key = min(rb + BM - 1, n - 1);
   const int ntile = last_key / 64 + 1;
 
   // staging: each thread moves 4 16-byte chunks of K and 4 of V^T per tile
-  u32x4 kr[4], vr[4];
+  u32x4 kr[NCH], vr[NCH];
   auto issue = [&](int t) {
     const int k0 = t * 64;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int c = tid + 256 * i;
+    for (int i = 0; i < NCH; ++i) {
+      const int c = tid + NT * i;
       const int row = c >> 4, col = (c & 15) * 8;
       kr[i] = *reinterpret_cast<const u32x4*>(kbase + int64_t(min(k0 + row, n - 1)) * kv.sn + col);
       const int dd = c >> 3, kc = (c & 7) * 8;
@@ -171,8 +184,8 @@ __global__ __launch_bounds__(256) void attn_fwd_bf16(const uint16_t* __restrict_
   };
   auto stage = [&](int buf) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int c = tid + 256 * i;
+    for (int i = 0; i < NCH; ++i) {
+      const int c = tid + NT * i;
       const int row = c >> 4, col = (c & 15) * 8;
       // key r of a 32-key sub-tile is stored at LDS row perm_key(r) (an involution), so that
       // MFMA row m, which must see key perm_key(m), reads LDS row m: consecutive rows, no
@@ -191,12 +204,12 @@ __global__ __launch_bounds__(256) void attn_fwd_bf16(const uint16_t* __restrict_
     const int k0 = t * 64, buf = t & 1;
     const bool more = t + 1 < ntile;
     if (more) issue(t + 1);
-    if (k0 <= wr0 + 63) {  // otherwise the whole tile is above this wavefront's diagonal
+    if (k0 <= wr0 + kWR - 1) {  // otherwise the whole tile is above this wavefront's diagonal
       const uint16_t* ksb = Ks + buf * kKsElems;
       const uint16_t* vsb = Vs + buf * kVsElems;
-      f32x16 s[2][2];
+      f32x16 s[RW][2];
 #pragma unroll
-      for (int j = 0; j < 2; ++j)
+      for (int j = 0; j < RW; ++j)
 #pragma unroll
         for (int st = 0; st < 2; ++st)
 #pragma unroll
@@ -206,14 +219,15 @@ __global__ __launch_bounds__(256) void attn_fwd_bf16(const uint16_t* __restrict_
 #pragma unroll
         for (int ks = 0; ks < 8; ++ks) {
           const bf16x8 a = *reinterpret_cast<const bf16x8*>(&ksb[(st * 32 + m) * kLdK + ks * 16 + h * 8]);
-          s[0][st] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bq[0][ks], s[0][st], 0, 0, 0);
-          s[1][st] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bq[1][ks], s[1][st], 0, 0, 0);
+#pragma unroll
+          for (int j = 0; j < RW; ++j)
+            s[j][st] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bq[j][ks], s[j][st], 0, 0, 0);
         }
       // register r of sub-tile st holds key k0 + 32*st + 16*(r/8) + 8*h + r%8
-      f16x8 pb[2][2][2];
+      f16x8 pb[RW][2][2];
       const bool diag = k0 + 63 > wr0;
 #pragma unroll
-      for (int j = 0; j < 2; ++j) {
+      for (int j = 0; j < RW; ++j) {
         const int q_row = wr0 + j * 32 + m;
         if (diag) {
 #pragma unroll
@@ -258,15 +272,16 @@ __global__ __launch_bounds__(256) void attn_fwd_bf16(const uint16_t* __restrict_
 #pragma unroll
           for (int dc = 0; dc < 4; ++dc) {
             const f16x8 a = *reinterpret_cast<const f16x8*>(&vsb[(dc * 32 + m) * kLdV + st * 32 + kb * 16 + h * 8]);
-            o[0][dc] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, pb[0][st][kb], o[0][dc], 0, 0, 0);
-            o[1][dc] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, pb[1][st][kb], o[1][dc], 0, 0, 0);
+#pragma unroll
+            for (int j = 0; j < RW; ++j)
+              o[j][dc] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, pb[j][st][kb], o[j][dc], 0, 0, 0);
           }
     }
     if (more) stage(buf ^ 1);
     __syncthreads();
   }
 #pragma unroll
-  for (int j = 0; j < 2; ++j) {
+  for (int j = 0; j < RW; ++j) {
     const int q_row = wr0 + j * 32 + m;
     const float ltot = lsum[j] + __shfl_xor(lsum[j], 32, 64);
     if (q_row < n) {
@@ -400,11 +415,11 @@ hipError_t launch_prefill_bf16(d2o_ctx* c, int layer, View Q, View K, View V, Vi
   const d2o_config& cf = c->cfg;
   const int G = cf.n_q_heads / cf.n_kv_heads;
   float* score = c->score_pre + size_t(layer) * cf.batch * cf.n_kv_heads * c->npad;
-  const int nblk = (n + kPrefillBM - 1) / kPrefillBM;
+  const int nblk = (n + kAttnBM - 1) / kAttnBM;
   const int nblk_col = (n + kColBN - 1) / kColBN;
   static bool attr_set = false;
   if (!attr_set) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_fwd_bf16),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(attn_fwd_bf16<kAttnRW, kAttnNW>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, kAttnSmemBytes);
     if (e != hipSuccess) return e;
     attr_set = true;
@@ -417,7 +432,7 @@ hipError_t launch_prefill_bf16(d2o_ctx* c, int layer, View Q, View K, View V, Vi
                                                                          c->vmax_bits, c->vt_unscale, n, c->npad);
   {
   KernelTimer kt(c, D2O_K_ATTN_FWD, s);
-  attn_fwd_bf16<<<dim3(nblk, cf.n_q_heads, cf.batch), 256, kAttnSmemBytes, s>>>((const uint16_t*)Q.ptr, Q, (const uint16_t*)K.ptr, K,
+  attn_fwd_bf16<kAttnRW, kAttnNW><<<dim3(nblk, cf.n_q_heads, cf.batch), 64 * kAttnNW, kAttnSmemBytes, s>>>((const uint16_t*)Q.ptr, Q, (const uint16_t*)K.ptr, K,
                                                                   (const uint16_t*)c->vt, c->vt_unscale, O.ptr, O, c->lse,
                                                                   n, c->npad, G, cf.out_f32);
   }
