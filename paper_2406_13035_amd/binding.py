@@ -13,7 +13,7 @@ import numpy as np
 import torch
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(HERE, "libd2o.so")
+LIB_PATH = os.environ.get("D2O_LIB", os.path.join(HERE, "libd2o.so"))
 
 D2O_F32, D2O_BF16 = 0, 1
 EXPORTS = [

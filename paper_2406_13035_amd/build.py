@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 SOURCES = ["d2o_host.hip", "prefill_f32.hip", "prefill_bf16.hip", "tokens.hip", "decode.hip"]
-LIB = os.path.join(HERE, "libd2o.so")
+LIB = os.environ.get("D2O_LIB", os.path.join(HERE, "libd2o.so"))
 
 
 def build(verbose: bool = False) -> str:

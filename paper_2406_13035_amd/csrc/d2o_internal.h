@@ -12,7 +12,7 @@
 namespace d2o {
 
 constexpr int kChunk = 256;        // cache slots handled by one workgroup in the decode kernels
-constexpr int kColBN = 128;        // keys per workgroup, column-sum pass (bf16)
+constexpr int kColBN = 256;        // keys per workgroup, column-sum pass (bf16)
 
 // A strided [b][head][token][d] (or [layer][b][head][d]) tensor, strides in elements.
 struct View {

@@ -118,8 +118,9 @@ constexpr int kAttnRW = 1;                     // 32-row blocks per wavefront
 constexpr int kAttnNW = 8;                     // wavefronts per workgroup
 constexpr int kAttnBM = 32 * kAttnRW * kAttnNW;
 
-// 256 query rows per workgroup: 4 wavefronts x 64 rows (two 32-row MFMA column blocks that
-// share every K / V^T operand read from LDS, which halves LDS traffic per MFMA).  K and V^T
+// NW wavefronts per workgroup, each owning RW 32-row MFMA column blocks (blocks of one
+// wavefront share every K / V^T operand read from LDS).  Built as 8 x 1: 256 query rows per
+// workgroup, two wavefronts per SIMD, which measured faster than 4 x 2.  K and V^T
 // tiles of 64 keys are double-buffered in LDS; the next tile's global loads are issued before
 // the current tile's MFMAs and written to the other buffer after them (one barrier per tile).
 template <int RW, int NW>
@@ -314,14 +315,22 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, 2)))
   }
 }
 
-__global__ __launch_bounds__(256) void colsum_bf16(const uint16_t* __restrict__ Q, View qv,
-                                                   const uint16_t* __restrict__ K, View kv,
-                                                   const float* __restrict__ lse2, float* __restrict__ score,
-                                                   double* __restrict__ varpart, int n, int npad, int G, int Hq) {
-  __shared__ __attribute__((aligned(16))) uint16_t Qs[64 * kLdK];
-  __shared__ float ls[64];
-  __shared__ float cs[128];
-  __shared__ double red[4];
+// 256 keys per workgroup (8 wavefronts x 32 keys, the stationary A operand).  Query tiles of
+// 64 rows are double-buffered in LDS and visited from the END of the prompt downwards: every
+// workgroup of a head then reads the same query tiles at about the same time (all start at
+// the last tile), so the tiles are served from L2 instead of HBM.
+constexpr int kColNW = 8;
+__global__ __launch_bounds__(64 * kColNW) void colsum_bf16(const uint16_t* __restrict__ Q, View qv,
+                                                           const uint16_t* __restrict__ K, View kv,
+                                                           const float* __restrict__ lse2, float* __restrict__ score,
+                                                           double* __restrict__ varpart, int n, int npad, int G,
+                                                           int Hq) {
+  __shared__ __attribute__((aligned(16))) uint16_t Qs[2][64 * kLdK];
+  __shared__ float ls[2][64];
+  __shared__ float cs[kColBN];
+  __shared__ double red[kColNW];
+  constexpr int NT = 64 * kColNW;
+  constexpr int NCH = 1024 / NT;
   const int tile = blockIdx.x, hk = blockIdx.y, b = blockIdx.z, Hkv = gridDim.y;
   const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, m = lane & 31, h = lane >> 5;
   const int kb0 = tile * kColBN, kw0 = kb0 + w * 32;  // first key of the workgroup / wavefront
@@ -332,7 +341,8 @@ __global__ __launch_bounds__(256) void colsum_bf16(const uint16_t* __restrict__ 
 #pragma unroll
   for (int ks = 0; ks < 8; ++ks) ak[ks] = *reinterpret_cast<const bf16x8*>(kp + ks * 16 + h * 8);
 
-  float total = 0.f;  // thread t < 128 owns key kb0 + t
+  const int nqt = (n - kb0 + 63) / 64;  // query tiles [kb0 + 64 j, kb0 + 64 j + 64), visited j descending
+  float total = 0.f;                    // thread t < 256 owns key kb0 + t
   for (int g = 0; g < G; ++g) {
     const int hq = hk * G + g;
     const uint16_t* qb = Q + b * qv.sb + hq * qv.sh;
@@ -340,42 +350,61 @@ __global__ __launch_bounds__(256) void colsum_bf16(const uint16_t* __restrict__ 
     float acc[16];
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[r] = 0.f;
-    for (int q0 = kb0 & ~63; q0 < n; q0 += 64) {
-      __syncthreads();
-      for (int c = tid; c < 64 * 16; c += 256) {
-        const int row = c >> 4, col = (c & 15) * 8;
-        const u32x4 v = *reinterpret_cast<const u32x4*>(qb + int64_t(min(q0 + row, n - 1)) * qv.sn + col);
-        *reinterpret_cast<u32x4*>(&Qs[row * kLdK + col]) = v;
+    u32x4 qr[NCH];
+    float lr = 0.f;
+    auto issue = [&](int j) {
+      const int q0 = kb0 + 64 * j;
+#pragma unroll
+      for (int i = 0; i < NCH; ++i) {
+        const int c = tid + NT * i, row = c >> 4, col = (c & 15) * 8;
+        qr[i] = *reinterpret_cast<const u32x4*>(qb + int64_t(min(q0 + row, n - 1)) * qv.sn + col);
       }
-      if (tid < 64) ls[tid] = (q0 + tid < n) ? lrow[q0 + tid] : INFINITY;  // +inf => p = 0
-      __syncthreads();
+      if (tid < 64) lr = (q0 + tid < n) ? lrow[q0 + tid] : INFINITY;  // +inf => p = 0
+    };
+    auto stage = [&](int buf) {
+#pragma unroll
+      for (int i = 0; i < NCH; ++i) {
+        const int c = tid + NT * i, row = c >> 4, col = (c & 15) * 8;
+        *reinterpret_cast<u32x4*>(&Qs[buf][row * kLdK + col]) = qr[i];
+      }
+      if (tid < 64) ls[buf][tid] = lr;
+    };
+    __syncthreads();  // previous head's readers are done with both buffers
+    issue(nqt - 1);
+    stage(0);
+    __syncthreads();
+    for (int it = 0; it < nqt; ++it) {
+      const int j = nqt - 1 - it, buf = it & 1, q0 = kb0 + 64 * j;
+      if (j > 0) issue(j - 1);
 #pragma unroll
       for (int qt = 0; qt < 2; ++qt) {
         const int qbase = q0 + qt * 32;
         if (qbase + 31 < kw0) continue;  // every query precedes every key of this wavefront
-        f32x16 s;
+        f32x16 sacc;
 #pragma unroll
-        for (int r = 0; r < 16; ++r) s[r] = 0.f;
+        for (int r = 0; r < 16; ++r) sacc[r] = 0.f;
 #pragma unroll
         for (int ks = 0; ks < 8; ++ks) {
-          const bf16x8 bqv = *reinterpret_cast<const bf16x8*>(&Qs[(qt * 32 + m) * kLdK + ks * 16 + h * 8]);
-          s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ak[ks], bqv, s, 0, 0, 0);
+          const bf16x8 bqv = *reinterpret_cast<const bf16x8*>(&Qs[buf][(qt * 32 + m) * kLdK + ks * 16 + h * 8]);
+          sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ak[ks], bqv, sacc, 0, 0, 0);
         }
         // register r: key kw0 + (r/4)*8 + 4h + r%4, query qbase + m
-        const float lq = ls[qt * 32 + m];
+        const float lq = ls[buf][qt * 32 + m];
         const int query = qbase + m;
         if (qbase < kw0 + 31) {  // diagonal tile: mask query < key
 #pragma unroll
           for (int r = 0; r < 16; ++r) {
             const int key = kw0 + (r >> 2) * 8 + h * 4 + (r & 3);
-            const float p = exp2f(fmaf(s[r], scale2, -lq));
+            const float p = __builtin_amdgcn_exp2f(fmaf(sacc[r], scale2, -lq));
             acc[r] += (query >= key) ? p : 0.f;
           }
         } else {
 #pragma unroll
-          for (int r = 0; r < 16; ++r) acc[r] += exp2f(fmaf(s[r], scale2, -lq));
+          for (int r = 0; r < 16; ++r) acc[r] += __builtin_amdgcn_exp2f(fmaf(sacc[r], scale2, -lq));
         }
       }
+      if (j > 0) stage(buf ^ 1);
+      __syncthreads();
     }
     // add the 32 query columns held by the lanes of each half
 #pragma unroll
@@ -385,28 +414,33 @@ __global__ __launch_bounds__(256) void colsum_bf16(const uint16_t* __restrict__ 
       for (int o = 16; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
       acc[r] = v;
     }
-    __syncthreads();
     if (m == 0) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) cs[w * 32 + (r >> 2) * 8 + h * 4 + (r & 3)] = acc[r];
     }
     __syncthreads();
-    double s1 = 0.0, s2 = 0.0;
-    if (tid < 128 && kb0 + tid < n) {
+    double c1 = 0.0, c2 = 0.0;
+    if (tid < kColBN && kb0 + tid < n) {
       const float c = cs[tid];
       total += c;
-      s1 = double(c);
-      s2 = double(c) * double(c);
+      c1 = double(c);
+      c2 = double(c) * double(c);
     }
-    s1 = block_sum(s1, red);
-    s2 = block_sum(s2, red);
+    // partial sums per 128-key block (the unit the density reduction adds up)
+    const bool lo = tid < 128;
+    const double s1a = block_sum(lo ? c1 : 0.0, red), s2a = block_sum(lo ? c2 : 0.0, red);
+    const double s1b = block_sum(lo ? 0.0 : c1, red), s2b = block_sum(lo ? 0.0 : c2, red);
     if (tid == 0) {
-      double* vp = varpart + ((int64_t(b) * Hq + hq) * (npad / 128) + tile) * 2;
-      vp[0] = s1;
-      vp[1] = s2;
+      double* vp = varpart + ((int64_t(b) * Hq + hq) * (npad / 128) + tile * 2) * 2;
+      vp[0] = s1a;
+      vp[1] = s2a;
+      if (kb0 + 128 < npad) {
+        vp[2] = s1b;
+        vp[3] = s2b;
+      }
     }
   }
-  if (tid < 128 && kb0 + tid < n) score[(int64_t(b) * Hkv + hk) * npad + kb0 + tid] = total;
+  if (tid < kColBN && kb0 + tid < n) score[(int64_t(b) * Hkv + hk) * npad + kb0 + tid] = total;
 }
 
 }  // namespace
@@ -437,7 +471,7 @@ hipError_t launch_prefill_bf16(d2o_ctx* c, int layer, View Q, View K, View V, Vi
                                                                   n, c->npad, G, cf.out_f32);
   }
   KernelTimer kt(c, D2O_K_COLSUM, s);
-  colsum_bf16<<<dim3(nblk_col, cf.n_kv_heads, cf.batch), 256, 0, s>>>((const uint16_t*)Q.ptr, Q, (const uint16_t*)K.ptr, K,
+  colsum_bf16<<<dim3(nblk_col, cf.n_kv_heads, cf.batch), 64 * kColNW, 0, s>>>((const uint16_t*)Q.ptr, Q, (const uint16_t*)K.ptr, K,
                                                                  c->lse, score, c->varpart, n, c->npad, G,
                                                                  cf.n_q_heads);
   return hipGetLastError();
