@@ -53,23 +53,29 @@ def round_storage(x: np.ndarray, dtype: str) -> np.ndarray:
 
 # --------------------------------------------------------------------------- a1: prefill attention
 
-def prefill_attention_head(q, k, v, causal: bool = True, row_block: int = 2048):
+def prefill_attention_head(q, k, v, causal: bool = True, row_block: int = 2048,
+                           row_range: tuple[int, int] | None = None):
     """Attention of one query head over the prompt, Sec. 4.1 Eq. 4 (and Sec. 3 Eq. 3).
 
     A = softmax(Q K^T / sqrt(d)) row-wise (causal: keys j <= i only; the paper's
     models are decoder-only), O = A V, and the column sums s[j] = sum_i A[i, j]
     ("sum the elements of each column", Sec. 4.1), the initial cumulative
     attention score (Eq. 6, prompt case).  d is the head dimension.
-    Returns (O [N, d], s [N])."""
+    Returns (O [N, d], s [N]).
+
+    row_range = (lo, hi) restricts the work to query rows lo <= i < hi (rows are independent
+    of each other): O then holds those rows only ([hi - lo, d]) and s the column sums over
+    those rows only, which is the complete sum for every column j >= lo when hi = N."""
     q = np.asarray(q, dtype=np.float64)
     k = np.asarray(k, dtype=np.float64)
     v = np.asarray(v, dtype=np.float64)
     n, d = q.shape
-    out = np.empty((n, d))
+    lo, hi = (0, n) if row_range is None else row_range
+    out = np.empty((hi - lo, d))
     colsum = np.zeros(n)
     root_d = np.sqrt(float(d))
-    for i0 in range(0, n, row_block):
-        i1 = min(n, i0 + row_block)
+    for i0 in range(lo, hi, row_block):
+        i1 = min(hi, i0 + row_block)
         ncol = i1 if causal else n
         s = (q[i0:i1] @ k[:ncol].T) / root_d
         if causal:
@@ -79,7 +85,7 @@ def prefill_attention_head(q, k, v, causal: bool = True, row_block: int = 2048):
         s = s - s.max(axis=1, keepdims=True)
         p = np.exp(s)
         p = p / p.sum(axis=1, keepdims=True)
-        out[i0:i1] = p @ v[:ncol]
+        out[i0 - lo:i1 - lo] = p @ v[:ncol]
         colsum[:ncol] += p.sum(axis=0)
     return out, colsum
 

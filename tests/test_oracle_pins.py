@@ -41,6 +41,24 @@ def test_attention_row_block_invariance():
     np.testing.assert_allclose(s1, s2, rtol=0, atol=1e-13)
 
 
+def test_attention_row_range_is_a_slice_of_the_full_result():
+    """Rows are independent: a row range gives exactly those rows of O (checked against the
+    library SDPA on the same rows), its column sums are the dense matrix's sums over those
+    rows, and with hi = N they are complete for every column j >= lo."""
+    n, d = 70, 8
+    q, k, v = _rand(n, d, 14), _rand(n, d, 15), _rand(n, d, 16)
+    full_o, full_s = ref.prefill_attention_head(q, k, v)
+    want = torch.nn.functional.scaled_dot_product_attention(
+        torch.from_numpy(q)[None], torch.from_numpy(k)[None], torch.from_numpy(v)[None],
+        is_causal=True)[0].numpy()
+    A = np.array(brute.attention_matrix(q.tolist(), k.tolist()))
+    for lo, hi in [(0, 13), (20, 51), (50, 70)]:
+        o, s = ref.prefill_attention_head(q, k, v, row_block=9, row_range=(lo, hi))
+        np.testing.assert_allclose(o, want[lo:hi], rtol=1e-12, atol=1e-13)
+        np.testing.assert_allclose(s, A[lo:hi].sum(axis=0), rtol=0, atol=1e-13)
+    np.testing.assert_allclose(s[50:], full_s[50:], rtol=0, atol=1e-13)
+
+
 def test_zero_query_causal_gives_harmonic_column_sums():
     # Q = 0: A[i, j] = 1/(i+1) for j <= i, so s[j] = H_N - H_j (0-based j) exactly.
     n = 40
