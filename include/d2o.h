@@ -199,10 +199,10 @@ typedef enum {
   D2O_K_MATCH_FILTER = 3,  /* matrix-core cosine candidate filter                          */
   D2O_K_MATCH_REFINE = 4,  /* exact fp64 cosine / arg-max                                  */
   D2O_K_MERGE = 5,
-  D2O_K_DECODE_ATTEND = 6,
-  D2O_K_DECODE_UPDATE = 7,
-  D2O_K_DECODE_COSINE = 8,
-  D2O_K_DECODE_FINISH = 9,
+  D2O_K_DECODE_ATTEND = 6,  /* attention over the cache + score update + evict/merge         */
+  D2O_K_DECODE_PREPARE = 7, /* append of the new token, operand set-up                      */
+  D2O_K_DECODE_COSINE = 8,  /* fallback similarity pass (exits at once when not needed)     */
+  D2O_K_DECODE_FINISH = 9,  /* fallback evict/merge                                         */
   D2O_K_COUNT = 10
 } d2o_kernel_id;
 int d2o_timing_enable(d2o_ctx* ctx, int32_t on);

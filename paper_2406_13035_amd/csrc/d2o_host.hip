@@ -71,6 +71,9 @@ void layout(d2o_ctx* x, char* persistent, char* scratch, size_t* pbytes, size_t*
   p.take(x->ev_evicted, L * B * Hkv);
   p.take(x->ev_target, L * B * Hkv);
   p.take(x->ev_ustar, L * B * Hkv);
+  const size_t nc = decode_candidates();
+  p.take(x->ccand, L * B * Hkv * nc);
+  p.take(x->cticket, L * B * Hkv);
   *pbytes = (p.off + 255) & ~size_t(255);
 
   Carver s{scratch};
@@ -99,11 +102,14 @@ void layout(d2o_ctx* x, char* persistent, char* scratch, size_t* pbytes, size_t*
   s.take(x->g_src, bh * np);
   s.take(x->d_logit, B * Hq * slots);
   s.take(x->d_pm, bh * nch * G);
+  s.take(x->d_pf, bh * nch * G);
   s.take(x->d_pl, bh * nch * G);
   s.take(x->d_pacc, bh * nch * G * d);
+  s.take(x->d_vecs, L * bh * (G + nc) * d);
+  s.take(x->d_cnorm, L * bh * nc);
   s.take(x->d_eslot, L * bh);
-  s.take(x->d_cu, bh * nch);
-  s.take(x->d_cslot, bh * nch);
+  s.take(x->d_cu, bh * nch * nc);
+  s.take(x->d_cslot, bh * nch * nc);
   *sbytes = (s.off + 255) & ~size_t(255);
 }
 
@@ -216,6 +222,8 @@ int d2o_reset(d2o_ctx* x, void* stream) {
   D2O_HIP_CHECK(x, hipMemsetAsync(x->ev_evicted, 0xFF, sizeof(int32_t) * lbh, s));
   D2O_HIP_CHECK(x, hipMemsetAsync(x->ev_target, 0xFF, sizeof(int32_t) * lbh, s));
   D2O_HIP_CHECK(x, hipMemsetAsync(x->ev_ustar, 0xFF, sizeof(double) * lbh, s));
+  D2O_HIP_CHECK(x, hipMemsetAsync(x->ccand, 0xFF, sizeof(int32_t) * lbh * decode_candidates(), s));
+  D2O_HIP_CHECK(x, hipMemsetAsync(x->cticket, 0, sizeof(uint32_t) * lbh, s));
   for (auto& l : x->layers) l = LayerState{};
   std::fill(x->used_slots.begin(), x->used_slots.end(), 0);
   std::fill(x->used_chunks.begin(), x->used_chunks.end(), 0);
@@ -517,6 +525,9 @@ int d2o_cache_import(d2o_ctx* x, int32_t layer, int32_t b, int32_t h, const void
   D2O_HIP_CHECK(x, hipMemcpyAsync(x->cpos + slot0, pos, count * sizeof(int32_t), hipMemcpyHostToDevice, s));
   D2O_HIP_CHECK(x, hipMemcpyAsync(x->ccount + lbh, &count, sizeof(int32_t), hipMemcpyHostToDevice, s));
   D2O_HIP_CHECK(x, hipMemcpyAsync(x->ctau + lbh, &tau, sizeof(double), hipMemcpyHostToDevice, s));
+  // the imported rows have no known eviction candidates yet
+  D2O_HIP_CHECK(x, hipMemsetAsync(x->ccand + lbh * decode_candidates(), 0xFF,
+                                  sizeof(int32_t) * decode_candidates(), s));
   D2O_HIP_CHECK(x, hipStreamSynchronize(s));
   st.next_pos = next_pos;
   return D2O_OK;

@@ -73,6 +73,8 @@ struct d2o_ctx {
   int32_t* ev_evicted = nullptr; // [L][B][Hkv]
   int32_t* ev_target = nullptr;  // [L][B][Hkv]
   double* ev_ustar = nullptr;    // [L][B][Hkv]
+  int32_t* ccand = nullptr;      // [L][B][Hkv][decode_candidates()] eviction candidates (slots, -1 none)
+  uint32_t* cticket = nullptr;   // [L][B][Hkv] chunk counter of the running decode step (0 between steps)
 
   // ---- scratch workspace (device) ----
   // prefill attention
@@ -100,13 +102,16 @@ struct d2o_ctx {
   int32_t* g_cur = nullptr;      // [..][npad+1] fill cursors
   int32_t* g_src = nullptr;      // evicted ranks grouped by target (unordered inside a group)
   // decode
-  double* d_logit = nullptr;     // [B][Hq][slots]
+  double* d_logit = nullptr;     // [B][Hq][slots]        exp(logit - chunk max)
   double* d_pm = nullptr;        // [B][Hkv][nchunk][G]   chunk maxima
-  float* d_pl = nullptr;         // [B][Hkv][nchunk][G]   chunk exp-sums (relative to chunk max)
+  double* d_pf = nullptr;        // [B][Hkv][nchunk][G]   chunk rescale factors
+  double* d_pl = nullptr;        // [B][Hkv][nchunk][G]   chunk exp-sums (relative to chunk max)
   float* d_pacc = nullptr;       // [B][Hkv][nchunk][G][d] chunk partial outputs
-  int32_t* d_eslot = nullptr;    // [L][B][Hkv] slot chosen for eviction (-1 none)
-  double* d_cu = nullptr;        // [B][Hkv][nchunk] chunk best cosine
-  int32_t* d_cslot = nullptr;    // [B][Hkv][nchunk] its slot
+  double* d_vecs = nullptr;      // [L][B][Hkv][G + candidates][d] queries and candidate keys, fp64
+  double* d_cnorm = nullptr;     // [L][B][Hkv][candidates] norms of the candidate keys
+  int32_t* d_eslot = nullptr;    // [L][B][Hkv] evicted slot awaiting the fallback pass (-1 none)
+  double* d_cu = nullptr;        // [B][Hkv][nchunk][candidates] chunk best cosine
+  int32_t* d_cslot = nullptr;    // [B][Hkv][nchunk][candidates] its slot
 };
 
 namespace d2o {
@@ -155,5 +160,6 @@ hipError_t launch_threshold_group(d2o_ctx* c, int layer, int n, hipStream_t s);
 hipError_t launch_merge(d2o_ctx* c, int layer, View K, View V, int n, hipStream_t s);
 hipError_t launch_decode(d2o_ctx* c, int layer0, int nl, View q, View k, View v, View out,
                          int new_pos, hipStream_t s);
+int decode_candidates();  // eviction candidates tracked per (layer, sequence, KV head)
 
 }  // namespace d2o

@@ -1,27 +1,49 @@
 // One generation step over the compressed cache (Sec. 3 Eq. 2-3; Sec. 4.2 Eq. 6-12), for a
-// range of layers in one set of launches.  The step is bound by HBM traffic (every K and V row
-// of every layer is read once), so all decision-bearing arithmetic - logits, softmax
-// normaliser, score accumulation, eviction arg-min, cosine arg-max, EMA threshold and the
-// merge - is done in fp64 with the operation order of the defining formulas; only the
-// attention output (P V) accumulates in fp32.
+// range of layers in one set of launches.  The step is bound by HBM traffic, so the design
+// reads every K and V row of every layer exactly once per step:
 //
-// Kernels, per (layer, sequence, KV head):
-//   decode_append  writes the new token's k, v into the free slot (score 0, its position).
-//   decode_attend  split over chunks of 256 slots: fp64 logits of the G query heads (kept in
-//                  scratch), chunk-local softmax statistics and partial P V.
-//   decode_update  combines the chunks into the output rows, forms the exact normaliser, adds
-//                  the softmax rows to the scores (Eq. 6, generation case) and picks the token
-//                  to evict (Eq. 7-8: lowest score outside sinks and the recent window; equal
-//                  scores evict the later position).
-//   decode_cosine  split over chunks: cosine of the evicted key against every survivor (Eq. 9).
-//   decode_finish  arg-max (ties: earlier position), EMA threshold (Eq. 10), merge or discard
-//                  (Eq. 11-12 with one source), and moves the last slot into the freed one.
+//   decode_prepare  per (layer, sequence, KV head): writes the new token's k, v into the free
+//                   slot (score 0, its position) and lays out, in fp64, the vectors the
+//                   attention pass multiplies every cache key with: the G queries and the keys
+//                   of kCand eviction candidates chosen at the end of the previous step.
+//   decode_attend   one workgroup per chunk of 256 slots.  K pass: the chunk's keys go through
+//                   LDS so that one lane owns one cache row; the lane forms, in fp64, the G
+//                   logits, the dot products with the candidate keys and the row's squared
+//                   norm (the vectors come in through scalar loads, so there is no cross-lane
+//                   reduction).  Then chunk-local softmax statistics, the candidates' best
+//                   cosine in the chunk (Eq. 9), and the partial P V in fp32.
+//                   The last workgroup of a head to finish (a ticket counter, no waiting)
+//                   combines the chunks: output rows, exact fp64 normaliser, score update
+//                   (Eq. 6, generation case), the token to evict (Eq. 7-8: lowest score
+//                   outside sinks and the recent window; equal scores evict the later
+//                   position) and the candidates of the next step (the lowest scores that
+//                   remain).  When the evicted token is one of this step's candidates, which
+//                   is the normal case, its similarities are already there and the same
+//                   workgroup finishes the step: arg-max (ties: earlier position), EMA
+//                   threshold (Eq. 10, update first, then test), merge or discard (Eq. 11-12
+//                   with one source), and the last slot moves into the freed one.
+//   decode_cosine,  fallback for heads whose evicted token was not among the candidates (the
+//   decode_finish   first step after prompt encoding, or a candidate overtaken by a token
+//                   outside the list): a second pass over the head's keys, then the same
+//                   finishing code.  Both exit at once for every other head.
+//
+// All decision-bearing arithmetic - logits, softmax normaliser, score accumulation, eviction
+// arg-min, cosine arg-max, EMA threshold, merge - is fp64 in the operation order of the
+// defining formulas; only the attention output (P V) accumulates in fp32.
 // Slots are physically unordered; a token's identity is its position.
+#include <algorithm>
+
 #include "d2o_internal.h"
 #include "device_utils.h"
 
 namespace d2o {
 namespace {
+
+constexpr int kCand = 3;                // eviction candidates whose similarities ride along with the attention pass
+constexpr int kMaxLayersPerCall = 64;
+constexpr int kPiece = 128;             // bytes of a cache row staged per LDS round
+constexpr int kPitch = kPiece + 16;     // LDS pitch of a staged row piece: conflict-free b128 reads
+constexpr int kStageBytes = 4 * 64 * kPitch;
 
 struct DecodeArgs {
   int32_t* ccount;
@@ -31,27 +53,33 @@ struct DecodeArgs {
   void* cV;
   double* cscore;
   int32_t* cpos;
-  double* logit;
-  double* pm;
-  float* pl;
-  float* pacc;
-  int32_t* eslot;
-  double* cu;
-  int32_t* cslot;
+  int32_t* cand;      // [L][B][Hkv][kCand] candidate slots for this step, -1 = none
+  uint32_t* ticket;   // [L][B][Hkv] finished chunks of the running step
+  double* elog;       // [B][Hq][slots] exp(logit - chunk max)
+  double* pm;         // [B][Hkv][nchunk][G] chunk maxima
+  double* pf;         // [B][Hkv][nchunk][G] chunk rescale factors exp(chunk max - head max)
+  double* pl;         // [B][Hkv][nchunk][G] chunk exp-sums relative to the chunk maximum
+  float* pacc;        // [B][Hkv][nchunk][G][d] chunk partial outputs
+  double* vecs;       // [L][B][Hkv][G + kCand][d] queries and candidate keys as fp64
+  double* cnorm;      // [L][B][Hkv][kCand] |k| of the candidates
+  double* cu;         // [B][Hkv][nchunk][kCand] chunk best cosine per candidate
+  int32_t* cslot;     // [B][Hkv][nchunk][kCand] its slot (-1 none)
+  int32_t* eslot;     // [L][B][Hkv] slot awaiting the fallback pass (-1 none)
   int32_t* ev_evicted;
   int32_t* ev_target;
   double* ev_ustar;
   int64_t slots;
   int64_t nchunk_cap;
-  int layer0, B, Hkv, G, new_pos, n_sink, out_f32;
+  int layer0, nl, B, Hkv, G, new_pos, n_sink, out_f32;
   double beta, tau_force;
+  int32_t lay_off[kMaxLayersPerCall + 1];  // first flat chunk index of each entry of lay_id
+  int32_t lay_id[kMaxLayersPerCall];       // layers of the call (relative), most chunks first
 };
 
 template <typename T>
-__device__ __forceinline__ void load_chunk(const T* p, double* out);
+__device__ __forceinline__ void cvt16(const u32x4& v, double* out);  // 16 bytes -> 8 or 4 doubles
 template <>
-__device__ __forceinline__ void load_chunk<uint16_t>(const uint16_t* p, double* out) {  // 8 elements
-  const u32x4 v = *reinterpret_cast<const u32x4*>(p);
+__device__ __forceinline__ void cvt16<uint16_t>(const u32x4& v, double* out) {
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
     out[2 * i] = double(__uint_as_float(v[i] << 16));
@@ -59,15 +87,14 @@ __device__ __forceinline__ void load_chunk<uint16_t>(const uint16_t* p, double* 
   }
 }
 template <>
-__device__ __forceinline__ void load_chunk<float>(const float* p, double* out) {  // 4 elements
-  const float4 a = *reinterpret_cast<const float4*>(p);
-  out[0] = a.x; out[1] = a.y; out[2] = a.z; out[3] = a.w;
+__device__ __forceinline__ void cvt16<float>(const u32x4& v, double* out) {
+#pragma unroll
+  for (int i = 0; i < 4; ++i) out[i] = double(__uint_as_float(v[i]));
 }
 template <typename T>
-__device__ __forceinline__ void load_chunk_f32(const T* p, float* out);
+__device__ __forceinline__ void cvt16f(const u32x4& v, float* out);
 template <>
-__device__ __forceinline__ void load_chunk_f32<uint16_t>(const uint16_t* p, float* out) {
-  const u32x4 v = *reinterpret_cast<const u32x4*>(p);
+__device__ __forceinline__ void cvt16f<uint16_t>(const u32x4& v, float* out) {
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
     out[2 * i] = __uint_as_float(v[i] << 16);
@@ -75,242 +102,565 @@ __device__ __forceinline__ void load_chunk_f32<uint16_t>(const uint16_t* p, floa
   }
 }
 template <>
-__device__ __forceinline__ void load_chunk_f32<float>(const float* p, float* out) {
-  const float4 a = *reinterpret_cast<const float4*>(p);
-  out[0] = a.x; out[1] = a.y; out[2] = a.z; out[3] = a.w;
+__device__ __forceinline__ void cvt16f<float>(const u32x4& v, float* out) {
+#pragma unroll
+  for (int i = 0; i < 4; ++i) out[i] = __uint_as_float(v[i]);
 }
 
-template <typename T, int D>
-__global__ __launch_bounds__(128) void decode_append(DecodeArgs a, const T* __restrict__ kn, View kv,
-                                                     const T* __restrict__ vn, View vv) {
-  const int li = blockIdx.y, l = a.layer0 + li, b = blockIdx.x / a.Hkv, hk = blockIdx.x % a.Hkv;
-  const int64_t lbh = (int64_t(l) * a.B + b) * a.Hkv + hk;
-  const int count = a.ccount[lbh];
-  const int64_t slot = (int64_t(b) * a.Hkv + hk) * a.slots + a.meta[(l * a.B + b) * 4 + 0] + count;
-  const int c = threadIdx.x;
-  if (c < D) {
-    static_cast<T*>(a.cK)[slot * D + c] = kn[li * kv.sn + b * kv.sb + hk * kv.sh + c];
-    static_cast<T*>(a.cV)[slot * D + c] = vn[li * vv.sn + b * vv.sb + hk * vv.sh + c];
-  }
-  if (c == 0) {
-    a.cscore[slot] = 0.0;
-    a.cpos[slot] = a.new_pos;
+// N consecutive elements from LDS as doubles (N * sizeof(T) is 8 or 16 bytes).
+template <typename T, int N>
+__device__ __forceinline__ void load_elems(const unsigned char* p, double* out) {
+  if constexpr (N * sizeof(T) == 16) {
+    cvt16<T>(*reinterpret_cast<const u32x4*>(p), out);
+  } else {
+    static_assert(sizeof(T) == 2 && N == 4, "8-byte steps are for 2-byte elements");
+    const u32x2 v = *reinterpret_cast<const u32x2*>(p);
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      out[2 * i] = double(__uint_as_float(v[i] << 16));
+      out[2 * i + 1] = double(__uint_as_float(v[i] & 0xFFFF0000u));
+    }
   }
 }
 
-template <typename T, int D, int G>
-__global__ __launch_bounds__(256) void decode_attend(DecodeArgs a, const T* __restrict__ q, View qv) {
-  constexpr int kVec = 16 / sizeof(T);       // elements per 16-byte load
-  constexpr int TPR = D / kVec;              // threads per row
-  constexpr int RPP = 256 / TPR;             // rows per pass
-  __shared__ double qs[G][D];
-  __shared__ double slog[G][kChunk];
-  __shared__ float ps[G][kChunk];
-  __shared__ float red[RPP][D];
-  __shared__ double redd[4];
-  const int li = blockIdx.z, l = a.layer0 + li, b = blockIdx.y / a.Hkv, hk = blockIdx.y % a.Hkv;
-  const int64_t lbh = (int64_t(l) * a.B + b) * a.Hkv + hk;
-  const int total = a.ccount[lbh] + 1;       // the new token has been appended
-  const int chunk = blockIdx.x;
-  if (chunk * kChunk >= total) return;
-  const int tid = threadIdx.x;
-  const int32_t* mt = a.meta + (l * a.B + b) * 4;
-  const int64_t bh = int64_t(b) * a.Hkv + hk;
-  const int64_t slot0 = bh * a.slots + mt[0];
-  const T* Kc = static_cast<const T*>(a.cK) + slot0 * D;
-  const T* Vc = static_cast<const T*>(a.cV) + slot0 * D;
-  const int rows = min(kChunk, total - chunk * kChunk);
-  for (int i = tid; i < G * D; i += 256) {
-    const int g = i / D, c = i % D;
-    qs[g][c] = Elem<T>::to_f64(q[li * qv.sn + b * qv.sb + (hk * G + g) * qv.sh + c]);
+// Data that one workgroup of decode_attend hands to another (the head's last workgroup) goes
+// through agent-scope stores and loads: they write through / read around the per-XCD L2, so
+// the hand-over needs no L2 write-back (a release fence at agent scope writes the whole L2
+// back, once per workgroup, which costs more than the attention pass itself).
+template <typename U>
+__device__ __forceinline__ void st_agent(U* p, U v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+template <typename U>
+__device__ __forceinline__ U ld_agent(const U* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// Which entry of the call's layer list a flat chunk index belongs to (block-uniform).  The
+// list is sorted by size, so the workgroups dispatched last belong to the smallest caches,
+// whose closing work is the shortest.
+__device__ __forceinline__ int find_entry(const DecodeArgs& a, int x) {
+  int i0 = 0;
+  for (int i = 1; i < a.nl; ++i) i0 = (x >= a.lay_off[i]) ? i : i0;
+  return i0;
+}
+
+// (u larger, then position smaller) wins; slot < 0 means "no entry".
+struct Best {
+  double u;
+  int pos, slot;
+};
+__device__ __forceinline__ bool better_match(double u, int p, int s, const Best& b) {
+  return s >= 0 && (b.slot < 0 || u > b.u || (u == b.u && p < b.pos));
+}
+__device__ __forceinline__ Best wave_best_match(Best b) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    const double ou = __shfl_xor(b.u, o, 64);
+    const int op = __shfl_xor(b.pos, o, 64), os = __shfl_xor(b.slot, o, 64);
+    if (better_match(ou, op, os, b)) b = Best{ou, op, os};
   }
-  __syncthreads();
-  const int tr = tid / TPR, tc = (tid % TPR) * kVec;
-  const double root_d = sqrt(double(D));
-  // ---- logits, fp64
-  for (int r0 = 0; r0 < rows; r0 += RPP) {
-    const int r = r0 + tr;
-    double dot[G];
+  return b;
+}
+// (score smaller, then position larger) wins: the order in which tokens are evicted.
+__device__ __forceinline__ bool evicts_before(double s, int p, int sl, const Best& b) {
+  return sl >= 0 && (b.slot < 0 || s < b.u || (s == b.u && p > b.pos));
+}
+__device__ __forceinline__ Best wave_first_evicted(Best b) {
 #pragma unroll
-    for (int g = 0; g < G; ++g) dot[g] = 0.0;
-    if (r < rows) {
-      double x[kVec];
-      load_chunk<T>(Kc + int64_t(chunk * kChunk + r) * D + tc, x);
-#pragma unroll
-      for (int g = 0; g < G; ++g)
-#pragma unroll
-        for (int e = 0; e < kVec; ++e) dot[g] += x[e] * qs[g][tc + e];
-    }
-#pragma unroll
-    for (int g = 0; g < G; ++g) {
-#pragma unroll
-      for (int o = TPR / 2; o > 0; o >>= 1) dot[g] += __shfl_xor(dot[g], o, 64);
-      if (r < rows && (tid % TPR) == 0) {
-        const double s = dot[g] / root_d;
-        slog[g][r] = s;
-        a.logit[(int64_t(b) * a.Hkv * G + hk * G + g) * a.slots + mt[0] + chunk * kChunk + r] = s;
-      }
-    }
+  for (int o = 32; o > 0; o >>= 1) {
+    const double ou = __shfl_xor(b.u, o, 64);
+    const int op = __shfl_xor(b.pos, o, 64), os = __shfl_xor(b.slot, o, 64);
+    if (evicts_before(ou, op, os, b)) b = Best{ou, op, os};
   }
-  __syncthreads();
-  // ---- chunk-local softmax statistics
-  const int64_t pidx = (bh * a.nchunk_cap + mt[3] + chunk) * G;
-#pragma unroll
-  for (int g = 0; g < G; ++g) {
-    double mx = tid < rows ? slog[g][tid] : -INFINITY;
-    mx = wave_max(mx);
-    __syncthreads();
-    if ((tid & 63) == 0) redd[tid >> 6] = mx;
-    __syncthreads();
-    mx = fmax(fmax(redd[0], redd[1]), fmax(redd[2], redd[3]));
-    const float p = tid < rows ? expf(float(slog[g][tid] - mx)) : 0.f;
-    ps[g][tid] = p;
-    float sm = wave_sum(p);
-    __syncthreads();
-    if ((tid & 63) == 0) redd[tid >> 6] = double(sm);
-    __syncthreads();
-    if (tid == 0) {
-      a.pm[pidx + g] = mx;
-      a.pl[pidx + g] = float(redd[0]) + float(redd[1]) + float(redd[2]) + float(redd[3]);
-    }
-  }
-  __syncthreads();
-  // ---- partial P V, fp32
-  float acc[G][kVec];
-#pragma unroll
-  for (int g = 0; g < G; ++g)
-#pragma unroll
-    for (int e = 0; e < kVec; ++e) acc[g][e] = 0.f;
-  for (int r0 = 0; r0 < rows; r0 += RPP) {
-    const int r = r0 + tr;
-    if (r < rows) {
-      float x[kVec];
-      load_chunk_f32<T>(Vc + int64_t(chunk * kChunk + r) * D + tc, x);
-#pragma unroll
-      for (int g = 0; g < G; ++g) {
-        const float p = ps[g][r];
-#pragma unroll
-        for (int e = 0; e < kVec; ++e) acc[g][e] = fmaf(p, x[e], acc[g][e]);
-      }
-    }
-  }
-#pragma unroll
-  for (int g = 0; g < G; ++g) {
-    __syncthreads();
-#pragma unroll
-    for (int e = 0; e < kVec; ++e) red[tr][tc + e] = acc[g][e];
-    __syncthreads();
-    if (tid < D) {
-      float t = 0.f;
-#pragma unroll
-      for (int i = 0; i < RPP; ++i) t += red[i][tid];
-      a.pacc[(pidx + g) * D + tid] = t;
-    }
-  }
+  return b;
 }
 
 template <typename T, typename OT, int D, int G>
-__global__ __launch_bounds__(256) void decode_update(DecodeArgs a, OT* __restrict__ out, View ov) {
-  __shared__ double red[4];
-  __shared__ double Msh[G], Lsh[G];
-  __shared__ double bscore[4];
-  __shared__ int bpos[4], bslot[4];
+__global__ __launch_bounds__(128) void decode_prepare(DecodeArgs a, const T* __restrict__ q, View qv,
+                                                      const T* __restrict__ kn, View kv, const T* __restrict__ vn,
+                                                      View vv) {
+  __shared__ double red[2];
   const int li = blockIdx.y, l = a.layer0 + li, b = blockIdx.x / a.Hkv, hk = blockIdx.x % a.Hkv;
   const int64_t lbh = (int64_t(l) * a.B + b) * a.Hkv + hk;
-  const int total = a.ccount[lbh] + 1;
-  const int nchunk = (total + kChunk - 1) / kChunk;
-  const int tid = threadIdx.x;
+  const int count = a.ccount[lbh];
+  const int64_t slot0 = (int64_t(b) * a.Hkv + hk) * a.slots + a.meta[(l * a.B + b) * 4 + 0];
+  const int c = threadIdx.x;
+  T* Kc = static_cast<T*>(a.cK) + slot0 * D;
+  T* Vc = static_cast<T*>(a.cV) + slot0 * D;
+  if (c < D) {
+    Kc[int64_t(count) * D + c] = kn[li * kv.sn + b * kv.sb + hk * kv.sh + c];
+    Vc[int64_t(count) * D + c] = vn[li * vv.sn + b * vv.sb + hk * vv.sh + c];
+  }
+  if (c == 0) {
+    a.cscore[slot0 + count] = 0.0;
+    a.cpos[slot0 + count] = a.new_pos;
+  }
+  double* vec = a.vecs + lbh * (G + kCand) * D;
+#pragma unroll
+  for (int g = 0; g < G; ++g)
+    if (c < D) vec[g * D + c] = Elem<T>::to_f64(q[li * qv.sn + b * qv.sb + (hk * G + g) * qv.sh + c]);
+  for (int i = 0; i < kCand; ++i) {
+    const int cs = a.cand[lbh * kCand + i];  // an older slot: never the one just written
+    double x = 0.0;
+    if (cs >= 0 && c < D) x = Elem<T>::to_f64(Kc[int64_t(cs) * D + c]);
+    if (c < D) vec[(G + i) * D + c] = x;
+    const double n2 = block_sum(x * x, red);
+    if (c == 0) a.cnorm[lbh * kCand + i] = sqrt(n2);
+  }
+}
+
+// Eq. 9 arg-max result -> Eq. 10 threshold, Eq. 11-12 merge with one source, slot bookkeeping.
+// Called by every thread of a workgroup (at least D threads) with block-uniform arguments.
+template <typename T, int D>
+__device__ __forceinline__ void finish_head(const DecodeArgs& a, int64_t lbh, int64_t slot0, int es, int total,
+                                            double best, int bp, int bs) {
+  T* Kc = static_cast<T*>(a.cK) + slot0 * D;
+  T* Vc = static_cast<T*>(a.cV) + slot0 * D;
+  const int tid = threadIdx.x, last = total - 1;
+  bool do_merge;
+  if (isnan(a.tau_force)) {
+    const double told = a.ctau[lbh];
+    const double tnew = isnan(told) ? best : __dadd_rn(__dmul_rn(a.beta, best), __dmul_rn(1.0 - a.beta, told));
+    do_merge = best >= tnew;
+    __syncthreads();  // every thread has read the old threshold
+    if (tid == 0) a.ctau[lbh] = tnew;
+  } else {
+    do_merge = best >= a.tau_force;
+  }
+  if (tid == 0) {
+    a.ev_evicted[lbh] = a.cpos[slot0 + es];
+    a.ev_target[lbh] = do_merge ? bp : -1;
+    a.ev_ustar[lbh] = best;
+    a.ccount[lbh] = last;
+  }
+  if (do_merge && tid < D) {
+    const double e1 = 2.718281828459045;  // exp(1), the retained token's self-similarity weight
+    const double w = exp(best);
+    const double z = __dadd_rn(e1, w);
+    const double kk = __dadd_rn(__dmul_rn(e1, Elem<T>::to_f64(Kc[int64_t(bs) * D + tid])),
+                                __dmul_rn(w, Elem<T>::to_f64(Kc[int64_t(es) * D + tid])));
+    const double vv = __dadd_rn(__dmul_rn(e1, Elem<T>::to_f64(Vc[int64_t(bs) * D + tid])),
+                                __dmul_rn(w, Elem<T>::to_f64(Vc[int64_t(es) * D + tid])));
+    Kc[int64_t(bs) * D + tid] = Elem<T>::from_f64(kk / z);
+    Vc[int64_t(bs) * D + tid] = Elem<T>::from_f64(vv / z);
+  }
+  __syncthreads();  // the merge has read the evicted row (and tid 0 its position)
+  if (es != last) {  // the last slot fills the hole
+    if (tid < D) {
+      Kc[int64_t(es) * D + tid] = Kc[int64_t(last) * D + tid];
+      Vc[int64_t(es) * D + tid] = Vc[int64_t(last) * D + tid];
+    }
+    if (tid == 0) {
+      a.cscore[slot0 + es] = a.cscore[slot0 + last];
+      a.cpos[slot0 + es] = a.cpos[slot0 + last];
+    }
+  }
+}
+
+// Work of the last workgroup of a head: combine the chunks, update the scores, choose the
+// evicted token and the next candidates, and finish the step when possible.
+template <typename T, typename OT, int D, int G>
+__device__ __forceinline__ void head_tail(const DecodeArgs& a, OT* __restrict__ out, const View& ov, int li, int b,
+                                          int hk, int64_t lbh, int total, int nchunk, double* sred, int* ired,
+                                          float* fred) {
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const int l = a.layer0 + li;
   const int32_t* mt = a.meta + (l * a.B + b) * 4;
   const int64_t bh = int64_t(b) * a.Hkv + hk;
   const int64_t slot0 = bh * a.slots + mt[0];
   const int64_t pbase = (bh * a.nchunk_cap + mt[3]) * G;
+  // pf and fred live in LDS space the chunk phase no longer needs
+  double Lg[G];
+#pragma unroll
   for (int g = 0; g < G; ++g) {
     double mx = -INFINITY;
-    for (int c = tid; c < nchunk; c += 256) mx = fmax(mx, a.pm[pbase + int64_t(c) * G + g]);
+    for (int c = tid; c < nchunk; c += 256) mx = fmax(mx, ld_agent(&a.pm[pbase + int64_t(c) * G + g]));
     mx = wave_max(mx);
     __syncthreads();
-    if ((tid & 63) == 0) red[tid >> 6] = mx;
+    if (lane == 0) sred[w] = mx;
     __syncthreads();
-    mx = fmax(fmax(red[0], red[1]), fmax(red[2], red[3]));
-    if (tid == 0) Msh[g] = mx;
-    // output row of query head g: chunks combined in ascending order
-    if (tid < D) {
-      float num = 0.f, den = 0.f;
-      for (int c = 0; c < nchunk; ++c) {
-        const int64_t pi = pbase + int64_t(c) * G + g;
-        const float f = expf(float(a.pm[pi] - mx));
-        den = fmaf(a.pl[pi], f, den);
-        num = fmaf(a.pacc[pi * D + tid], f, num);
-      }
-      out[li * ov.sn + b * ov.sb + (hk * G + g) * ov.sh + tid] = Elem<OT>::from_f32(num / den);
-    }
-    // exact normaliser: sum_j exp(s_j - max), fp64; the exponentials replace the logits
-    double* lg = a.logit + (int64_t(b) * a.Hkv * G + hk * G + g) * a.slots + mt[0];
+    mx = fmax(fmax(sred[0], sred[1]), fmax(sred[2], sred[3]));
     double part = 0.0;
-    for (int j = tid; j < total; j += 256) {
-      const double e = exp(lg[j] - mx);
-      lg[j] = e;
-      part += e;
+    for (int c = tid; c < nchunk; c += 256) {
+      const int64_t pi = pbase + int64_t(c) * G + g;
+      const double m = ld_agent(&a.pm[pi]), pl = ld_agent(&a.pl[pi]);
+      const double f = exp(m - mx);
+      a.pf[pi] = f;  // the chunk's rescale factor (read back by this workgroup only)
+      part += pl * f;
     }
-    const double L = block_sum(part, red);
-    if (tid == 0) Lsh[g] = L;
+    Lg[g] = block_sum(part, sred);  // exact normaliser sum_j exp(s_j - max), fixed summation tree
+    // output row of query head g: NPART groups of threads take every NPART-th chunk, four
+    // loads in flight each, and the groups' sums are added in ascending order
+    constexpr int NPART = 256 / D;
+    const int dcol = tid % D, part_id = tid / D;
+    float num = 0.f;
+    for (int c0 = part_id; c0 < nchunk; c0 += 4 * NPART) {
+      float v[4], f[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int c = c0 + u * NPART;
+        const int64_t pi = pbase + int64_t(min(c, nchunk - 1)) * G + g;
+        v[u] = ld_agent(&a.pacc[pi * D + dcol]);
+        f[u] = c < nchunk ? float(a.pf[pi]) : 0.f;
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) num = fmaf(v[u], f[u], num);
+    }
+    __syncthreads();
+    fred[tid] = num;
+    __syncthreads();
+    if (tid < D) {
+      float t = fred[tid];
+#pragma unroll
+      for (int i = 1; i < NPART; ++i) t += fred[i * D + tid];
+      out[li * ov.sn + b * ov.sb + (hk * G + g) * ov.sh + tid] = Elem<OT>::from_f32(float(double(t) / Lg[g]));
+    }
   }
-  __syncthreads();
-  // scores (Eq. 6) and the eviction candidate (Eq. 7-8 on count+1 entries)
+  // ---- scores (Eq. 6), the token to evict (Eq. 7-8 on count+1 entries) and the lowest scores
+  //      among the tokens evictable at the next step
   const bool evict = total > mt[1];
   const int recent = mt[2];
-  double best = INFINITY;
-  int bp = -1, bs = -1;
-  for (int j = tid; j < total; j += 256) {
-    double sc = a.cscore[slot0 + j];
-    for (int g = 0; g < G; ++g) {
-      const double* lg = a.logit + (int64_t(b) * a.Hkv * G + hk * G + g) * a.slots + mt[0];
-      sc += lg[j] / Lsh[g];
-    }
-    a.cscore[slot0 + j] = sc;
-    const int p = a.cpos[slot0 + j];
-    const bool cand = p >= a.n_sink && p <= a.new_pos - recent;
-    if (cand && (sc < best || (sc == best && p > bp))) {
-      best = sc;
-      bp = p;
-      bs = j;
-    }
-  }
+  Best ev{0.0, 0, -1};
+  Best low[kCand + 1];
 #pragma unroll
-  for (int o = 32; o > 0; o >>= 1) {
-    const double ob = __shfl_xor(best, o, 64);
-    const int op = __shfl_xor(bp, o, 64), os = __shfl_xor(bs, o, 64);
-    if (os >= 0 && (bs < 0 || ob < best || (ob == best && op > bp))) {
-      best = ob;
-      bp = op;
-      bs = os;
+  for (int i = 0; i <= kCand; ++i) low[i] = Best{0.0, 0, -1};
+  for (int j0 = tid; j0 < total; j0 += 4 * 256) {
+    double sc[4], e[4][G];
+    int ps[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {  // four slots' loads in flight
+      const int j = min(j0 + u * 256, total - 1);
+      sc[u] = a.cscore[slot0 + j];
+      ps[u] = a.cpos[slot0 + j];
+#pragma unroll
+      for (int g = 0; g < G; ++g)
+        e[u][g] = ld_agent(&a.elog[(int64_t(b) * a.Hkv * G + hk * G + g) * a.slots + mt[0] + j]);
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int j = j0 + u * 256;
+      if (j < total) {
+        double s2 = sc[u];
+#pragma unroll
+        for (int g = 0; g < G; ++g) s2 += e[u][g] * a.pf[pbase + int64_t(j / kChunk) * G + g] / Lg[g];
+        a.cscore[slot0 + j] = s2;
+        const int p = ps[u];
+        if (p >= a.n_sink && p <= a.new_pos - recent && evicts_before(s2, p, j, ev)) ev = Best{s2, p, j};
+        if (p >= a.n_sink && p <= a.new_pos + 1 - recent && evicts_before(s2, p, j, low[kCand])) {
+          low[kCand] = Best{s2, p, j};
+#pragma unroll
+          for (int i = kCand; i > 0; --i)
+            if (evicts_before(low[i].u, low[i].pos, low[i].slot, low[i - 1])) {
+              const Best t = low[i - 1];
+              low[i - 1] = low[i];
+              low[i] = t;
+            }
+        }
+      }
     }
   }
-  if ((tid & 63) == 0) {
-    bscore[tid >> 6] = best;
-    bpos[tid >> 6] = bp;
-    bslot[tid >> 6] = bs;
+  // evicted token: block-wide
+  ev = wave_first_evicted(ev);
+  __syncthreads();
+  if (lane == 0) {
+    sred[w] = ev.u;
+    ired[w] = ev.pos;
+    ired[4 + w] = ev.slot;
   }
   __syncthreads();
-  if (tid == 0) {
+  ev = Best{sred[0], ired[0], ired[4]};
+#pragma unroll
+  for (int i = 1; i < 4; ++i)
+    if (evicts_before(sred[i], ired[i], ired[4 + i], ev)) ev = Best{sred[i], ired[i], ired[4 + i]};
+  const int es = evict ? ev.slot : -1;  // a candidate always exists: total > budget >= T + M
+  // the kCand + 1 lowest of the next step's evictable tokens: repeated block-wide extraction
+  int nxt[kCand + 1];
+#pragma unroll
+  for (int r = 0; r <= kCand; ++r) {
+    Best h = wave_first_evicted(low[0]);
+    __syncthreads();
+    if (lane == 0) {
+      sred[w] = h.u;
+      ired[w] = h.pos;
+      ired[4 + w] = h.slot;
+    }
+    __syncthreads();
+    h = Best{sred[0], ired[0], ired[4]};
+#pragma unroll
     for (int i = 1; i < 4; ++i)
-      if (bslot[i] >= 0 && (bs < 0 || bscore[i] < best || (bscore[i] == best && bpos[i] > bp))) {
-        best = bscore[i];
-        bp = bpos[i];
-        bs = bslot[i];
-      }
-    if (evict) {
-      a.eslot[lbh] = bs;  // a candidate always exists: total > budget >= T + M
-    } else {
+      if (evicts_before(sred[i], ired[i], ired[4 + i], h)) h = Best{sred[i], ired[i], ired[4 + i]};
+    nxt[r] = h.slot;
+    if (h.slot >= 0 && low[0].slot == h.slot) {  // the owner pops its head
+#pragma unroll
+      for (int i = 0; i < kCand; ++i) low[i] = low[i + 1];
+      low[kCand].slot = -1;
+    }
+  }
+  // this step's candidate list, before it is replaced
+  int ci = -1;
+#pragma unroll
+  for (int i = kCand - 1; i >= 0; --i)
+    if (es >= 0 && a.cand[lbh * kCand + i] == es) ci = i;
+  __syncthreads();  // every thread has read the old list
+  if (tid == 0) {
+    const int last = total - 1;
+    int k = 0;
+    for (int r = 0; r <= kCand && k < kCand; ++r) {
+      int s = nxt[r];
+      if (s < 0 || s == es) continue;
+      if (es >= 0 && s == last) s = es;  // the last slot is about to move into the freed one
+      a.cand[lbh * kCand + k++] = s;
+    }
+    for (; k < kCand; ++k) a.cand[lbh * kCand + k] = -1;
+    st_agent(&a.ticket[lbh], 0u);
+  }
+  if (!evict) {
+    if (tid == 0) {
       a.eslot[lbh] = -1;
       a.ccount[lbh] = total;
       a.ev_evicted[lbh] = -1;
       a.ev_target[lbh] = -1;
       a.ev_ustar[lbh] = __longlong_as_double(0x7FF8000000000000ll);
     }
+    return;
   }
+  if (ci < 0) {  // not foreseen: the fallback pass computes its similarities
+    if (tid == 0) a.eslot[lbh] = es;
+    return;
+  }
+  if (tid == 0) a.eslot[lbh] = -1;
+  // Eq. 9 arg-max over the chunks' results for candidate ci (ties: earlier position)
+  Best m{0.0, 0, -1};
+  for (int c = tid; c < nchunk; c += 256) {
+    const int64_t x = (bh * a.nchunk_cap + mt[3] + c) * kCand + ci;
+    const int s = ld_agent(&a.cslot[x]);
+    if (s >= 0) {
+      const double u = ld_agent(&a.cu[x]);
+      const int p = a.cpos[slot0 + s];
+      if (better_match(u, p, s, m)) m = Best{u, p, s};
+    }
+  }
+  m = wave_best_match(m);
+  __syncthreads();
+  if (lane == 0) {
+    sred[w] = m.u;
+    ired[w] = m.pos;
+    ired[4 + w] = m.slot;
+  }
+  __syncthreads();
+  m = Best{sred[0], ired[0], ired[4]};
+#pragma unroll
+  for (int i = 1; i < 4; ++i)
+    if (better_match(sred[i], ired[i], ired[4 + i], m)) m = Best{sred[i], ired[i], ired[4 + i]};
+  __syncthreads();
+  finish_head<T, D>(a, lbh, slot0, es, total, m.u, m.pos, m.slot);
 }
 
+template <typename T, typename OT, int D, int G>
+__global__ __launch_bounds__(256) void decode_attend(DecodeArgs a, OT* __restrict__ out, View ov) {
+  constexpr int kVec = 16 / sizeof(T);          // elements per 16-byte load
+  constexpr int RB = D * sizeof(T);             // bytes of a cache row
+  constexpr int NP = RB / kPiece;               // row pieces staged through LDS
+  constexpr int EP = kPiece / sizeof(T);        // elements of a piece
+  constexpr int TPR = RB / 16;                  // V pass: threads per row
+  constexpr int RPP = 256 / TPR;                // V pass: rows per pass
+  constexpr int NPASS = kChunk / RPP;           // V pass: passes over the chunk
+  constexpr int NV = G + kCand;
+  constexpr int ES = (NV * 2 * kVec > 72) ? 4 : kVec;  // elements per K-pass step
+  __shared__ __attribute__((aligned(16))) unsigned char stage[kStageBytes];
+  __shared__ double sred[4 * (2 * G + kCand)];
+  __shared__ int ired[8 * kCand];
+  __shared__ int sh_last;
+  float* ps = reinterpret_cast<float*>(stage);                 // [G][kChunk], after the K pass
+  float* red = reinterpret_cast<float*>(stage) + G * kChunk;   // [RPP][D], after the K pass
+  static_assert((G * kChunk + RPP * D) * 4 <= kStageBytes, "LDS aliases do not fit");
+
+  const int entry = find_entry(a, blockIdx.y), chunk = blockIdx.y - a.lay_off[entry];
+  const int li = a.lay_id[entry];
+  const int l = a.layer0 + li, b = blockIdx.x / a.Hkv, hk = blockIdx.x % a.Hkv;
+  const int64_t lbh = (int64_t(l) * a.B + b) * a.Hkv + hk;
+  const int total = a.ccount[lbh] + 1;          // the new token has been appended
+  if (chunk * kChunk >= total) return;
+  const int nchunk = (total + kChunk - 1) / kChunk;
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const int32_t* mt = a.meta + (l * a.B + b) * 4;
+  const int64_t bh = int64_t(b) * a.Hkv + hk;
+  const int64_t slot0 = bh * a.slots + mt[0];
+  const unsigned char* Kc = static_cast<const unsigned char*>(a.cK) + (slot0 + int64_t(chunk) * kChunk) * RB;
+  const unsigned char* Vc = static_cast<const unsigned char*>(a.cV) + (slot0 + int64_t(chunk) * kChunk) * RB;
+  const int rows = min(kChunk, total - chunk * kChunk);
+
+  // ---- issue the chunk's K loads: per piece, 8 lanes cover 128 bytes of a row, 8 rows per load
+  u32x4 kreg[NP][8];
+#pragma unroll
+  for (int p = 0; p < NP; ++p)
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int r = w * 64 + i * 8 + (lane >> 3);
+      kreg[p][i] = u32x4{0, 0, 0, 0};
+      if (r < rows) kreg[p][i] = *reinterpret_cast<const u32x4*>(Kc + int64_t(r) * RB + p * kPiece + (lane & 7) * 16);
+    }
+  // first half of the V loads rides behind them
+  const int tr = tid / TPR, tc = tid % TPR;
+  u32x4 vreg[NPASS / 2];
+#pragma unroll
+  for (int i = 0; i < NPASS / 2; ++i) {
+    const int r = i * RPP + tr;
+    vreg[i] = u32x4{0, 0, 0, 0};
+    if (r < rows) vreg[i] = *reinterpret_cast<const u32x4*>(Vc + int64_t(r) * RB + tc * 16);
+  }
+
+  // ---- K pass: lane = row.  The queries and candidate keys arrive through scalar loads.
+  typedef const double __attribute__((address_space(4))) * cptr;
+  cptr S = (cptr)(a.vecs + lbh * NV * D);
+  double acc[NV];
+#pragma unroll
+  for (int v = 0; v < NV; ++v) acc[v] = 0.0;
+  double nr = 0.0;
+  unsigned char* mine = stage + w * 64 * kPitch;
+  u32x4 vreg2[NPASS / 2];
+#pragma unroll
+  for (int p = 0; p < NP; ++p) {
+    // The staging area of a wavefront is private to it and LDS serves a wavefront's requests in
+    // order, so the piece hand-over needs compiler ordering only, no workgroup barrier.
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+      *reinterpret_cast<u32x4*>(mine + (i * 8 + (lane >> 3)) * kPitch + (lane & 7) * 16) = kreg[p][i];
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    if (p == NP - 1) {  // the key registers are free: second half of the V loads
+#pragma unroll
+      for (int i = 0; i < NPASS / 2; ++i) {
+        const int r = (NPASS / 2 + i) * RPP + tr;
+        vreg2[i] = u32x4{0, 0, 0, 0};
+        if (r < rows) vreg2[i] = *reinterpret_cast<const u32x4*>(Vc + int64_t(r) * RB + tc * 16);
+      }
+    }
+    // ES elements per step: few enough that one step's scalar operands fit the scalar registers
+#pragma unroll 1
+    for (int st = 0; st < EP / ES; ++st) {
+      double x[ES];
+      load_elems<T, ES>(mine + lane * kPitch + st * ES * int(sizeof(T)), x);
+#pragma unroll
+      for (int e = 0; e < ES; ++e) nr = fma(x[e], x[e], nr);
+#pragma unroll
+      for (int v = 0; v < NV; ++v)
+#pragma unroll
+        for (int e = 0; e < ES; ++e) acc[v] = fma(x[e], S[v * D + p * EP + st * ES + e], acc[v]);
+    }
+  }
+  // ---- chunk-local softmax statistics; thread tid owns cache row chunk*kChunk + tid
+  const bool valid = tid < rows;
+  const int j = chunk * kChunk + tid;
+  const double root_d = sqrt(double(D));
+  double sg[G];
+#pragma unroll
+  for (int g = 0; g < G; ++g) {
+    sg[g] = acc[g] / root_d;
+    const double mx = wave_max(valid ? sg[g] : -INFINITY);
+    if (lane == 0) sred[w * G + g] = mx;
+  }
+  __syncthreads();  // also: every wavefront is done with the staged keys
+  const int64_t pidx = (bh * a.nchunk_cap + mt[3] + chunk) * G;
+  double mg[G];
+#pragma unroll
+  for (int g = 0; g < G; ++g) {
+    mg[g] = fmax(fmax(sred[g], sred[G + g]), fmax(sred[2 * G + g], sred[3 * G + g]));
+    const double e = valid ? exp(sg[g] - mg[g]) : 0.0;
+    ps[g * kChunk + tid] = float(e);
+    if (valid) st_agent(&a.elog[(int64_t(b) * a.Hkv * G + hk * G + g) * a.slots + mt[0] + j], e);
+    const double sm = wave_sum(e);
+    if (lane == 0) sred[4 * G + w * G + g] = sm;
+  }
+  // candidates: cosine of this row against each candidate key (Eq. 9), chunk arg-max
+  const int pos = valid ? a.cpos[slot0 + j] : 0;
+  const double nrow = sqrt(nr);
+#pragma unroll
+  for (int c = 0; c < kCand; ++c) {
+    const int cs = a.cand[lbh * kCand + c];
+    const double den = a.cnorm[lbh * kCand + c] * nrow;
+    const double u = den > 0.0 ? acc[G + c] / den : 0.0;
+    Best m{u, pos, (valid && cs >= 0 && j != cs) ? j : -1};
+    m = wave_best_match(m);
+    if (lane == 0) {
+      sred[8 * G + w * kCand + c] = m.u;
+      ired[w * kCand + c] = m.pos;
+      ired[4 * kCand + w * kCand + c] = m.slot;
+    }
+  }
+  __syncthreads();
+  if (tid < G) {
+    // all threads hold the same mg[]; pick element tid without dynamic register indexing
+    double mv = 0.0, lv = 0.0;
+#pragma unroll
+    for (int g = 0; g < G; ++g)
+      if (g == tid) {
+        mv = mg[g];
+        lv = ((sred[4 * G + g] + sred[5 * G + g]) + sred[6 * G + g]) + sred[7 * G + g];
+      }
+    st_agent(&a.pm[pidx + tid], mv);
+    st_agent(&a.pl[pidx + tid], lv);
+  }
+  if (tid >= 64 && tid < 64 + kCand) {
+    const int c = tid - 64;
+    Best m{sred[8 * G + c], ired[c], ired[4 * kCand + c]};
+#pragma unroll
+    for (int i = 1; i < 4; ++i)
+      if (better_match(sred[8 * G + i * kCand + c], ired[i * kCand + c], ired[4 * kCand + i * kCand + c], m))
+        m = Best{sred[8 * G + i * kCand + c], ired[i * kCand + c], ired[4 * kCand + i * kCand + c]};
+    const int64_t x = (bh * a.nchunk_cap + mt[3] + chunk) * kCand + c;
+    st_agent(&a.cu[x], m.u);
+    st_agent(&a.cslot[x], m.slot);
+  }
+  // ---- partial P V, fp32
+  float pv[G][kVec];
+#pragma unroll
+  for (int g = 0; g < G; ++g)
+#pragma unroll
+    for (int e = 0; e < kVec; ++e) pv[g][e] = 0.f;
+#pragma unroll
+  for (int i = 0; i < NPASS; ++i) {
+    const int r = i * RPP + tr;
+    float x[kVec];
+    cvt16f<T>(i < NPASS / 2 ? vreg[i % (NPASS / 2)] : vreg2[i % (NPASS / 2)], x);
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+      const float p = ps[g * kChunk + r];  // 0 for rows beyond the chunk's end
+#pragma unroll
+      for (int e = 0; e < kVec; ++e) pv[g][e] = fmaf(p, x[e], pv[g][e]);
+    }
+  }
+#pragma unroll
+  for (int g = 0; g < G; ++g) {
+    __syncthreads();
+#pragma unroll
+    for (int e = 0; e < kVec; ++e) red[tr * D + tc * kVec + e] = pv[g][e];
+    __syncthreads();
+    if (tid < D) {
+      float t = 0.f;
+#pragma unroll
+      for (int i = 0; i < RPP; ++i) t += red[i * D + tid];
+      st_agent(&a.pacc[(pidx + g) * D + tid], t);
+    }
+  }
+  // ---- ticket: the last workgroup of the head to arrive combines the chunks.  Every store
+  //      above that it will read is a write-through store; they have completed once the
+  //      memory counters are zero, before the barrier that precedes the ticket.
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+  __builtin_amdgcn_s_waitcnt(0);
+  __syncthreads();
+  if (tid == 0)
+    sh_last = (__hip_atomic_fetch_add(&a.ticket[lbh], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) ==
+               unsigned(nchunk - 1)) ? 1 : 0;
+  __syncthreads();
+  if (!sh_last) return;
+  head_tail<T, OT, D, G>(a, out, ov, li, b, hk, lbh, total, nchunk, sred, ired, red);
+}
+
+// Fallback pass: cosine of the evicted key against every survivor of its head (Eq. 9).
 template <typename T, int D>
 __global__ __launch_bounds__(256) void decode_cosine(DecodeArgs a) {
   constexpr int kVec = 16 / sizeof(T);
@@ -320,12 +670,13 @@ __global__ __launch_bounds__(256) void decode_cosine(DecodeArgs a) {
   __shared__ double red[4];
   __shared__ double bu[4];
   __shared__ int bpos[4], bslot[4];
-  const int li = blockIdx.z, l = a.layer0 + li, b = blockIdx.y / a.Hkv, hk = blockIdx.y % a.Hkv;
+  const int entry = find_entry(a, blockIdx.y), chunk = blockIdx.y - a.lay_off[entry];
+  const int li = a.lay_id[entry];
+  const int l = a.layer0 + li, b = blockIdx.x / a.Hkv, hk = blockIdx.x % a.Hkv;
   const int64_t lbh = (int64_t(l) * a.B + b) * a.Hkv + hk;
   const int es = a.eslot[lbh];
   if (es < 0) return;
   const int total = a.ccount[lbh] + 1;
-  const int chunk = blockIdx.x;
   if (chunk * kChunk >= total) return;
   const int tid = threadIdx.x;
   const int32_t* mt = a.meta + (l * a.B + b) * 4;
@@ -341,18 +692,17 @@ __global__ __launch_bounds__(256) void decode_cosine(DecodeArgs a) {
   const double sne = sqrt(block_sum(part, red));
   const int rows = min(kChunk, total - chunk * kChunk);
   const int tr = tid / TPR, tc = (tid % TPR) * kVec;
-  double best = -2.0;
-  int bp = 0x7FFFFFFF, bs = -1;
+  Best m{0.0, 0, -1};
   for (int r0 = 0; r0 < rows; r0 += RPP) {
     const int r = r0 + tr, j = chunk * kChunk + r;
     double dot = 0.0, nr = 0.0;
     if (r < rows) {
       double x[kVec];
-      load_chunk<T>(Kc + int64_t(j) * D + tc, x);
+      cvt16<T>(*reinterpret_cast<const u32x4*>(Kc + int64_t(j) * D + tc), x);
 #pragma unroll
       for (int e = 0; e < kVec; ++e) {
-        dot += x[e] * ke[tc + e];
-        nr += x[e] * x[e];
+        dot = fma(x[e], ke[tc + e], dot);
+        nr = fma(x[e], x[e], nr);
       }
     }
 #pragma unroll
@@ -364,155 +714,102 @@ __global__ __launch_bounds__(256) void decode_cosine(DecodeArgs a) {
       const double den = sne * sqrt(nr);
       const double u = den > 0.0 ? dot / den : 0.0;
       const int p = a.cpos[slot0 + j];
-      if (u > best || (u == best && p < bp)) {
-        best = u;
-        bp = p;
-        bs = j;
-      }
+      if (better_match(u, p, j, m)) m = Best{u, p, j};
     }
   }
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) {
-    const double ob = __shfl_xor(best, o, 64);
-    const int op = __shfl_xor(bp, o, 64), os = __shfl_xor(bs, o, 64);
-    if (os >= 0 && (bs < 0 || ob > best || (ob == best && op < bp))) {
-      best = ob;
-      bp = op;
-      bs = os;
-    }
-  }
+  m = wave_best_match(m);
   if ((tid & 63) == 0) {
-    bu[tid >> 6] = best;
-    bpos[tid >> 6] = bp;
-    bslot[tid >> 6] = bs;
+    bu[tid >> 6] = m.u;
+    bpos[tid >> 6] = m.pos;
+    bslot[tid >> 6] = m.slot;
   }
   __syncthreads();
   if (tid == 0) {
     for (int i = 1; i < 4; ++i)
-      if (bslot[i] >= 0 && (bs < 0 || bu[i] > best || (bu[i] == best && bpos[i] < bp))) {
-        best = bu[i];
-        bp = bpos[i];
-        bs = bslot[i];
-      }
-    const int64_t ci = bh * a.nchunk_cap + mt[3] + chunk;
-    a.cu[ci] = best;
-    a.cslot[ci] = bs;  // -1 when the chunk holds only the evicted slot
+      if (better_match(bu[i], bpos[i], bslot[i], m)) m = Best{bu[i], bpos[i], bslot[i]};
+    const int64_t x = (bh * a.nchunk_cap + mt[3] + chunk) * kCand;
+    a.cu[x] = m.u;
+    a.cslot[x] = m.slot;  // -1 when the chunk holds only the evicted slot
   }
 }
 
 template <typename T, int D>
 __global__ __launch_bounds__(128) void decode_finish(DecodeArgs a) {
-  __shared__ int sh_t, sh_merge;
-  __shared__ double sh_u;
+  __shared__ double su;
+  __shared__ int sp, ss;
   const int li = blockIdx.y, l = a.layer0 + li, b = blockIdx.x / a.Hkv, hk = blockIdx.x % a.Hkv;
   const int64_t lbh = (int64_t(l) * a.B + b) * a.Hkv + hk;
   const int es = a.eslot[lbh];
   if (es < 0) return;
-  const int total = a.ccount[lbh] + 1, last = total - 1;
+  const int total = a.ccount[lbh] + 1;
   const int nchunk = (total + kChunk - 1) / kChunk;
-  const int tid = threadIdx.x;
   const int32_t* mt = a.meta + (l * a.B + b) * 4;
   const int64_t bh = int64_t(b) * a.Hkv + hk;
   const int64_t slot0 = bh * a.slots + mt[0];
-  T* Kc = static_cast<T*>(a.cK) + slot0 * D;
-  T* Vc = static_cast<T*>(a.cV) + slot0 * D;
-  if (tid == 0) {
-    double best = -2.0;
-    int bp = 0x7FFFFFFF, bs = -1;
+  if (threadIdx.x == 0) {
+    Best m{0.0, 0, -1};
     for (int c = 0; c < nchunk; ++c) {
-      const int64_t ci = bh * a.nchunk_cap + mt[3] + c;
-      const int s = a.cslot[ci];
+      const int64_t x = (bh * a.nchunk_cap + mt[3] + c) * kCand;
+      const int s = a.cslot[x];
       if (s < 0) continue;
-      const double u = a.cu[ci];
+      const double u = a.cu[x];
       const int p = a.cpos[slot0 + s];
-      if (bs < 0 || u > best || (u == best && p < bp)) {
-        best = u;
-        bp = p;
-        bs = s;
-      }
+      if (better_match(u, p, s, m)) m = Best{u, p, s};
     }
-    bool do_merge;
-    if (isnan(a.tau_force)) {
-      const double told = a.ctau[lbh];
-      const double tnew = isnan(told) ? best
-                                      : __dadd_rn(__dmul_rn(a.beta, best), __dmul_rn(1.0 - a.beta, told));
-      a.ctau[lbh] = tnew;
-      do_merge = best >= tnew;
-    } else {
-      do_merge = best >= a.tau_force;
-    }
-    sh_t = bs;
-    sh_u = best;
-    sh_merge = do_merge ? 1 : 0;
-    a.ev_evicted[lbh] = a.cpos[slot0 + es];
-    a.ev_target[lbh] = do_merge ? bp : -1;
-    a.ev_ustar[lbh] = best;
+    su = m.u;
+    sp = m.pos;
+    ss = m.slot;
   }
   __syncthreads();
-  if (tid == 0) a.ccount[lbh] = last;  // after every thread has read the old count
-  const int ts = sh_t;
-  if (sh_merge && tid < D) {
-    const double e1 = 2.718281828459045;
-    const double w = exp(sh_u);
-    const double z = __dadd_rn(e1, w);
-    const double kk = __dadd_rn(__dmul_rn(e1, Elem<T>::to_f64(Kc[int64_t(ts) * D + tid])),
-                                __dmul_rn(w, Elem<T>::to_f64(Kc[int64_t(es) * D + tid])));
-    const double vv = __dadd_rn(__dmul_rn(e1, Elem<T>::to_f64(Vc[int64_t(ts) * D + tid])),
-                                __dmul_rn(w, Elem<T>::to_f64(Vc[int64_t(es) * D + tid])));
-    Kc[int64_t(ts) * D + tid] = Elem<T>::from_f64(kk / z);
-    Vc[int64_t(ts) * D + tid] = Elem<T>::from_f64(vv / z);
-  }
-  __syncthreads();
-  if (es != last) {  // the last slot fills the hole
-    if (tid < D) {
-      Kc[int64_t(es) * D + tid] = Kc[int64_t(last) * D + tid];
-      Vc[int64_t(es) * D + tid] = Vc[int64_t(last) * D + tid];
-    }
-    if (tid == 0) {
-      a.cscore[slot0 + es] = a.cscore[slot0 + last];
-      a.cpos[slot0 + es] = a.cpos[slot0 + last];
-    }
-  }
+  finish_head<T, D>(a, lbh, slot0, es, total, su, sp, ss);
 }
 
-template <typename T, int D, int G>
-hipError_t run_decode(d2o_ctx* c, const DecodeArgs& a, int nl, int maxchunks, View q, View k, View v, View out, hipStream_t s) {
+template <typename T, typename OT, int D, int G>
+hipError_t run_decode_o(d2o_ctx* c, const DecodeArgs& a, int nl, int flat_chunks, View q, View k, View v, View out,
+                        hipStream_t s) {
   const int bh = a.B * a.Hkv;
-  decode_append<T, D><<<dim3(bh, nl), 128, 0, s>>>(a, (const T*)k.ptr, k, (const T*)v.ptr, v);
   {
-    KernelTimer kt(c, D2O_K_DECODE_ATTEND, s);
-    decode_attend<T, D, G><<<dim3(maxchunks, bh, nl), 256, 0, s>>>(a, (const T*)q.ptr, q);
+    KernelTimer kt(c, D2O_K_DECODE_PREPARE, s);
+    decode_prepare<T, OT, D, G><<<dim3(bh, nl), 128, 0, s>>>(a, (const T*)q.ptr, q, (const T*)k.ptr, k,
+                                                            (const T*)v.ptr, v);
   }
   {
-  KernelTimer kt(c, D2O_K_DECODE_UPDATE, s);
-  if (a.out_f32)
-    decode_update<T, float, D, G><<<dim3(bh, nl), 256, 0, s>>>(a, (float*)out.ptr, out);
-  else
-    decode_update<T, T, D, G><<<dim3(bh, nl), 256, 0, s>>>(a, (T*)out.ptr, out);
+    KernelTimer kt(c, D2O_K_DECODE_ATTEND, s);
+    decode_attend<T, OT, D, G><<<dim3(bh, flat_chunks), 256, 0, s>>>(a, (OT*)out.ptr, out);
   }
   {
     KernelTimer kt(c, D2O_K_DECODE_COSINE, s);
-    decode_cosine<T, D><<<dim3(maxchunks, bh, nl), 256, 0, s>>>(a);
+    decode_cosine<T, D><<<dim3(bh, flat_chunks), 256, 0, s>>>(a);
   }
   KernelTimer kt(c, D2O_K_DECODE_FINISH, s);
   decode_finish<T, D><<<dim3(bh, nl), 128, 0, s>>>(a);
   return hipGetLastError();
 }
 
+template <typename T, int D, int G>
+hipError_t run_decode(d2o_ctx* c, const DecodeArgs& a, int nl, int fc, View q, View k, View v, View out,
+                      hipStream_t s) {
+  if (a.out_f32) return run_decode_o<T, float, D, G>(c, a, nl, fc, q, k, v, out, s);
+  return run_decode_o<T, T, D, G>(c, a, nl, fc, q, k, v, out, s);
+}
+
 template <typename T, int D>
-hipError_t run_decode_g(d2o_ctx* c, const DecodeArgs& a, int nl, int mc, View q, View k, View v, View out, hipStream_t s) {
+hipError_t run_decode_g(d2o_ctx* c, const DecodeArgs& a, int nl, int fc, View q, View k, View v, View out,
+                        hipStream_t s) {
   switch (a.G) {
-    case 1: return run_decode<T, D, 1>(c, a, nl, mc, q, k, v, out, s);
-    case 2: return run_decode<T, D, 2>(c, a, nl, mc, q, k, v, out, s);
-    case 4: return run_decode<T, D, 4>(c, a, nl, mc, q, k, v, out, s);
-    case 8: return run_decode<T, D, 8>(c, a, nl, mc, q, k, v, out, s);
+    case 1: return run_decode<T, D, 1>(c, a, nl, fc, q, k, v, out, s);
+    case 2: return run_decode<T, D, 2>(c, a, nl, fc, q, k, v, out, s);
+    case 4: return run_decode<T, D, 4>(c, a, nl, fc, q, k, v, out, s);
+    case 8: return run_decode<T, D, 8>(c, a, nl, fc, q, k, v, out, s);
     default: return hipErrorInvalidValue;
   }
 }
 
 }  // namespace
 
-hipError_t launch_decode(d2o_ctx* c, int layer0, int nl, View q, View k, View v, View out, int new_pos,
+int decode_candidates() { return kCand; }
+
+hipError_t launch_decode(d2o_ctx* c, int layer0, int nl_all, View q, View k, View v, View out, int new_pos,
                          hipStream_t s) {
   const d2o_config& cf = c->cfg;
   DecodeArgs a;
@@ -523,19 +820,23 @@ hipError_t launch_decode(d2o_ctx* c, int layer0, int nl, View q, View k, View v,
   a.cV = c->cacheV;
   a.cscore = c->cscore;
   a.cpos = c->cpos;
-  a.logit = c->d_logit;
+  a.cand = c->ccand;
+  a.ticket = c->cticket;
+  a.elog = c->d_logit;
   a.pm = c->d_pm;
+  a.pf = c->d_pf;
   a.pl = c->d_pl;
   a.pacc = c->d_pacc;
-  a.eslot = c->d_eslot;
+  a.vecs = c->d_vecs;
+  a.cnorm = c->d_cnorm;
   a.cu = c->d_cu;
   a.cslot = c->d_cslot;
+  a.eslot = c->d_eslot;
   a.ev_evicted = c->ev_evicted;
   a.ev_target = c->ev_target;
   a.ev_ustar = c->ev_ustar;
   a.slots = cf.slots_per_seq;
   a.nchunk_cap = c->nchunk_cap;
-  a.layer0 = layer0;
   a.B = cf.batch;
   a.Hkv = cf.n_kv_heads;
   a.G = cf.n_q_heads / cf.n_kv_heads;
@@ -544,12 +845,40 @@ hipError_t launch_decode(d2o_ctx* c, int layer0, int nl, View q, View k, View v,
   a.out_f32 = cf.out_f32;
   a.beta = cf.beta;
   a.tau_force = cf.tau_force;
-  int maxchunks = 1;
-  for (int l = layer0; l < layer0 + nl; ++l)
-    for (const auto& mt : c->layers[l].meta) maxchunks = std::max(maxchunks, (mt.budget + 1 + kChunk - 1) / kChunk);
-  if (cf.dtype == D2O_BF16) return run_decode_g<uint16_t, 128>(c, a, nl, maxchunks, q, k, v, out, s);
-  if (cf.head_dim == 64) return run_decode_g<float, 64>(c, a, nl, maxchunks, q, k, v, out, s);
-  return run_decode_g<float, 128>(c, a, nl, maxchunks, q, k, v, out, s);
+  // the per-layer tensors of one call are [layer][...]: groups of at most kMaxLayersPerCall
+  for (int g0 = 0; g0 < nl_all; g0 += kMaxLayersPerCall) {
+    const int nl = std::min(kMaxLayersPerCall, nl_all - g0);
+    a.layer0 = layer0 + g0;
+    a.nl = nl;
+    int mc[kMaxLayersPerCall];
+    for (int i = 0; i < nl; ++i) {
+      a.lay_id[i] = i;
+      mc[i] = 1;
+      for (const auto& mt : c->layers[a.layer0 + i].meta) mc[i] = std::max(mc[i], (mt.budget + 1 + kChunk - 1) / kChunk);
+    }
+    std::stable_sort(a.lay_id, a.lay_id + nl, [&](int x, int y) { return mc[x] > mc[y]; });
+    int flat = 0;
+    for (int i = 0; i < nl; ++i) {
+      a.lay_off[i] = flat;
+      flat += mc[a.lay_id[i]];
+    }
+    a.lay_off[nl] = flat;
+    auto shift = [&](View x, int elem_bytes) {  // first layer of this group
+      x.ptr = static_cast<char*>(x.ptr) + size_t(g0) * x.sn * elem_bytes;
+      return x;
+    };
+    const int es = c->esize, os = cf.out_f32 ? 4 : c->esize;
+    const View qg = shift(q, es), kg = shift(k, es), vg = shift(v, es), og = shift(out, os);
+    hipError_t e;
+    if (cf.dtype == D2O_BF16)
+      e = run_decode_g<uint16_t, 128>(c, a, nl, flat, qg, kg, vg, og, s);
+    else if (cf.head_dim == 64)
+      e = run_decode_g<float, 64>(c, a, nl, flat, qg, kg, vg, og, s);
+    else
+      e = run_decode_g<float, 128>(c, a, nl, flat, qg, kg, vg, og, s);
+    if (e != hipSuccess) return e;
+  }
+  return hipSuccess;
 }
 
 }  // namespace d2o
