@@ -6,15 +6,16 @@
 //                   slot (score 0, its position) and lays out, in fp64, the vectors the
 //                   attention pass multiplies every cache key with: the G queries and the keys
 //                   of kCand eviction candidates chosen at the end of the previous step.
-//   decode_attend   one workgroup per chunk of 256 slots.  K pass: the chunk's keys go through
-//                   LDS so that one lane owns one cache row; the lane forms, in fp64, the G
-//                   logits, the dot products with the candidate keys and the row's squared
-//                   norm (the vectors come in through scalar loads, so there is no cross-lane
-//                   reduction).  Then chunk-local softmax statistics, the candidates' best
-//                   cosine in the chunk (Eq. 9), and the partial P V in fp32.
+//   decode_attend   one workgroup per chunk of 256 slots, each of its four wavefronts working
+//                   alone on 64 of them.  K pass: the keys go through LDS so that one lane owns
+//                   one cache row; the lane forms, in fp64, the G logits, the dot products with
+//                   the candidate keys and the row's squared norm (the vectors come in through
+//                   scalar loads, so there is no cross-lane reduction).  Then the softmax
+//                   statistics of the 64 rows, the candidates' best cosine among them (Eq. 9),
+//                   and the partial P V in fp32.
 //                   The last workgroup of a head to finish (a ticket counter, no waiting)
-//                   combines the chunks: output rows, exact fp64 normaliser, score update
-//                   (Eq. 6, generation case), the token to evict (Eq. 7-8: lowest score
+//                   combines the partial results: output rows, exact fp64 normaliser, score
+//                   update (Eq. 6, generation case), the token to evict (Eq. 7-8: lowest score
 //                   outside sinks and the recent window; equal scores evict the later
 //                   position) and the candidates of the next step (the lowest scores that
 //                   remain).  When the evicted token is one of this step's candidates, which
@@ -22,10 +23,11 @@
 //                   workgroup finishes the step: arg-max (ties: earlier position), EMA
 //                   threshold (Eq. 10, update first, then test), merge or discard (Eq. 11-12
 //                   with one source), and the last slot moves into the freed one.
-//   decode_cosine,  fallback for heads whose evicted token was not among the candidates (the
-//   decode_finish   first step after prompt encoding, or a candidate overtaken by a token
-//                   outside the list): a second pass over the head's keys, then the same
-//                   finishing code.  Both exit at once for every other head.
+//   decode_fallback for heads whose evicted token was not among the candidates (the first step
+//                   after prompt encoding, or a candidate overtaken by a token outside the
+//                   list): one workgroup per such head makes a second pass over the head's
+//                   keys and runs the same finishing code.  It exits at once for every other
+//                   head.
 //
 // All decision-bearing arithmetic - logits, softmax normaliser, score accumulation, eviction
 // arg-min, cosine arg-max, EMA threshold, merge - is fp64 in the operation order of the
@@ -44,6 +46,8 @@ constexpr int kMaxLayersPerCall = 64;
 constexpr int kPiece = 128;             // bytes of a cache row staged per LDS round
 constexpr int kPitch = kPiece + 16;     // LDS pitch of a staged row piece: conflict-free b128 reads
 constexpr int kStageBytes = 4 * 64 * kPitch;
+constexpr int kSub = 64;                // rows one wavefront handles at a time (lane = row)
+constexpr int kGroup = 1;               // chunks of 256 slots per workgroup
 
 struct DecodeArgs {
   int32_t* ccount;
@@ -55,24 +59,24 @@ struct DecodeArgs {
   int32_t* cpos;
   int32_t* cand;      // [L][B][Hkv][kCand] candidate slots for this step, -1 = none
   uint32_t* ticket;   // [L][B][Hkv] finished chunks of the running step
-  double* elog;       // [B][Hq][slots] exp(logit - chunk max)
-  double* pm;         // [B][Hkv][nchunk][G] chunk maxima
-  double* pf;         // [B][Hkv][nchunk][G] chunk rescale factors exp(chunk max - head max)
-  double* pl;         // [B][Hkv][nchunk][G] chunk exp-sums relative to the chunk maximum
-  float* pacc;        // [B][Hkv][nchunk][G][d] chunk partial outputs
+  double* elog;       // [B][Hq][slots] exp(logit - sub-chunk max)
+  double* pm;         // [B][Hkv][nsub][G] sub-chunk maxima
+  double* pf;         // [B][Hkv][nsub][G] rescale factors exp(sub-chunk max - head max)
+  double* pl;         // [B][Hkv][nsub][G] exp-sums relative to the sub-chunk maximum
+  float* pacc;        // [B][Hkv][nsub][G][d] partial outputs
   double* vecs;       // [L][B][Hkv][G + kCand][d] queries and candidate keys as fp64
   double* cnorm;      // [L][B][Hkv][kCand] |k| of the candidates
-  double* cu;         // [B][Hkv][nchunk][kCand] chunk best cosine per candidate
+  double* cu;         // [B][Hkv][nsub][kCand] best cosine per candidate
   int32_t* cslot;     // [B][Hkv][nchunk][kCand] its slot (-1 none)
   int32_t* eslot;     // [L][B][Hkv] slot awaiting the fallback pass (-1 none)
   int32_t* ev_evicted;
   int32_t* ev_target;
   double* ev_ustar;
   int64_t slots;
-  int64_t nchunk_cap;
+  int64_t nsub_cap;   // sub-chunk entries per (sequence, KV head) in the partial buffers
   int layer0, nl, B, Hkv, G, new_pos, n_sink, out_f32;
   double beta, tau_force;
-  int32_t lay_off[kMaxLayersPerCall + 1];  // first flat chunk index of each entry of lay_id
+  int32_t lay_off[kMaxLayersPerCall + 1];  // first flat chunk-group index of each entry of lay_id
   int32_t lay_id[kMaxLayersPerCall];       // layers of the call (relative), most chunks first
 };
 
@@ -107,20 +111,32 @@ __device__ __forceinline__ void cvt16f<float>(const u32x4& v, float* out) {
   for (int i = 0; i < 4; ++i) out[i] = __uint_as_float(v[i]);
 }
 
-// N consecutive elements from LDS as doubles (N * sizeof(T) is 8 or 16 bytes).
-template <typename T, int N>
-__device__ __forceinline__ void load_elems(const unsigned char* p, double* out) {
-  if constexpr (N * sizeof(T) == 16) {
-    cvt16<T>(*reinterpret_cast<const u32x4*>(p), out);
-  } else {
-    static_assert(sizeof(T) == 2 && N == 4, "8-byte steps are for 2-byte elements");
-    const u32x2 v = *reinterpret_cast<const u32x2*>(p);
+// N consecutive elements (4, 8 or 16 bytes) held as raw bits, and their conversion to doubles.
+template <int BYTES> struct RawBits;
+template <> struct RawBits<16> { typedef u32x4 type; };
+template <> struct RawBits<8> { typedef u32x2 type; };
+template <> struct RawBits<4> { typedef uint32_t type; };
+__device__ __forceinline__ uint32_t raw_word(const u32x4& r, int i) { return r[i]; }
+__device__ __forceinline__ uint32_t raw_word(const u32x2& r, int i) { return r[i]; }
+__device__ __forceinline__ uint32_t raw_word(const uint32_t& r, int) { return r; }
+template <typename T, int N, typename R>
+__device__ __forceinline__ void raw_to_f64(const R& r, double* out) {
+  if constexpr (sizeof(T) == 2) {
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
-      out[2 * i] = double(__uint_as_float(v[i] << 16));
-      out[2 * i + 1] = double(__uint_as_float(v[i] & 0xFFFF0000u));
+    for (int i = 0; i < N / 2; ++i) {
+      out[2 * i] = double(__uint_as_float(raw_word(r, i) << 16));
+      out[2 * i + 1] = double(__uint_as_float(raw_word(r, i) & 0xFFFF0000u));
     }
+  } else {
+#pragma unroll
+    for (int i = 0; i < N; ++i) out[i] = double(__uint_as_float(raw_word(r, i)));
   }
+}
+
+// Pins the point where a scalar-loaded value must have arrived; nothing is scheduled across it.
+__device__ __forceinline__ void arrived(double v) {
+  asm volatile("" ::"s"(v));
+  __builtin_amdgcn_sched_barrier(0);
 }
 
 // Data that one workgroup of decode_attend hands to another (the head's last workgroup) goes
@@ -140,9 +156,54 @@ __device__ __forceinline__ U ld_agent(const U* p) {
 // list is sorted by size, so the workgroups dispatched last belong to the smallest caches,
 // whose closing work is the shortest.
 __device__ __forceinline__ int find_entry(const DecodeArgs& a, int x) {
-  int i0 = 0;
-  for (int i = 1; i < a.nl; ++i) i0 = (x >= a.lay_off[i]) ? i : i0;
-  return i0;
+  // one lane per list entry (at most 64): the entry is the last one that starts at or before x
+  const int lane = threadIdx.x & 63;
+  const int start = lane < a.nl ? a.lay_off[lane] : 0x7FFFFFFF;
+  return __popcll(__ballot(start <= x)) - 1;
+}
+
+// Wavefront reductions on the data-parallel-primitive path (register-to-register lane
+// permutations, no LDS round trip): four butterfly steps inside each row of 16 lanes, then the
+// four row results are combined through scalar registers.  Every lane gets the result; the
+// combination tree is fixed.
+constexpr int kDppXor1 = 0xB1;         // quad_perm [1,0,3,2]
+constexpr int kDppXor2 = 0x4E;         // quad_perm [2,3,0,1]
+constexpr int kDppHalfMirror = 0x141;  // lane i <-> 7 - i within 8
+constexpr int kDppMirror = 0x140;      // lane i <-> 15 - i within 16
+template <int CTRL>
+__device__ __forceinline__ int dpp_i32(int v) {
+  return __builtin_amdgcn_update_dpp(0, v, CTRL, 0xF, 0xF, true);
+}
+template <int CTRL>
+__device__ __forceinline__ double dpp_f64(double v) {
+  const int lo = dpp_i32<CTRL>(__double2loint(v)), hi = dpp_i32<CTRL>(__double2hiint(v));
+  return __hiloint2double(hi, lo);
+}
+__device__ __forceinline__ double lane_f64(double v, int lane) {
+  return __hiloint2double(__builtin_amdgcn_readlane(__double2hiint(v), lane),
+                          __builtin_amdgcn_readlane(__double2loint(v), lane));
+}
+__device__ __forceinline__ double fast_wave_max(double v) {
+  v = fmax(v, dpp_f64<kDppXor1>(v));
+  v = fmax(v, dpp_f64<kDppXor2>(v));
+  v = fmax(v, dpp_f64<kDppHalfMirror>(v));
+  v = fmax(v, dpp_f64<kDppMirror>(v));
+  return fmax(fmax(lane_f64(v, 0), lane_f64(v, 16)), fmax(lane_f64(v, 32), lane_f64(v, 48)));
+}
+__device__ __forceinline__ double fast_wave_sum(double v) {
+  v += dpp_f64<kDppXor1>(v);
+  v += dpp_f64<kDppXor2>(v);
+  v += dpp_f64<kDppHalfMirror>(v);
+  v += dpp_f64<kDppMirror>(v);
+  return (lane_f64(v, 0) + lane_f64(v, 16)) + (lane_f64(v, 32) + lane_f64(v, 48));
+}
+__device__ __forceinline__ int fast_wave_min(int v) {
+  v = min(v, dpp_i32<kDppXor1>(v));
+  v = min(v, dpp_i32<kDppXor2>(v));
+  v = min(v, dpp_i32<kDppHalfMirror>(v));
+  v = min(v, dpp_i32<kDppMirror>(v));
+  return min(min(__builtin_amdgcn_readlane(v, 0), __builtin_amdgcn_readlane(v, 16)),
+             min(__builtin_amdgcn_readlane(v, 32), __builtin_amdgcn_readlane(v, 48)));
 }
 
 // (u larger, then position smaller) wins; slot < 0 means "no entry".
@@ -161,6 +222,18 @@ __device__ __forceinline__ Best wave_best_match(Best b) {
     if (better_match(ou, op, os, b)) b = Best{ou, op, os};
   }
   return b;
+}
+// The same arg-max for one entry per lane whose positions are all different and whose u is
+// never below -1 (a cosine): largest u, then smallest position, then that lane's slot.
+__device__ __forceinline__ Best fast_wave_best_match(double u, int pos, int slot) {
+  const bool live = slot >= 0;
+  const double umax = fast_wave_max(live ? u : -INFINITY);
+  const bool top = live && u == umax;
+  const int pmin = fast_wave_min(top ? pos : 0x7FFFFFFF);
+  const unsigned long long who = __ballot(top && pos == pmin);
+  if (who == 0ull) return Best{0.0, 0, -1};
+  const int src = __ffsll((long long)who) - 1;
+  return Best{umax, pmin, __builtin_amdgcn_readlane(slot, src)};
 }
 // (score smaller, then position larger) wins: the order in which tokens are evicted.
 __device__ __forceinline__ bool evicts_before(double s, int p, int sl, const Best& b) {
@@ -262,27 +335,27 @@ __device__ __forceinline__ void finish_head(const DecodeArgs& a, int64_t lbh, in
 // evicted token and the next candidates, and finish the step when possible.
 template <typename T, typename OT, int D, int G>
 __device__ __forceinline__ void head_tail(const DecodeArgs& a, OT* __restrict__ out, const View& ov, int li, int b,
-                                          int hk, int64_t lbh, int total, int nchunk, double* sred, int* ired,
+                                          int hk, int64_t lbh, int total, int nsub, double* sred, int* ired,
                                           float* fred) {
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const int l = a.layer0 + li;
   const int32_t* mt = a.meta + (l * a.B + b) * 4;
   const int64_t bh = int64_t(b) * a.Hkv + hk;
   const int64_t slot0 = bh * a.slots + mt[0];
-  const int64_t pbase = (bh * a.nchunk_cap + mt[3]) * G;
+  const int64_t pbase = (bh * a.nsub_cap + int64_t(mt[3]) * (kChunk / kSub)) * G;
   // pf and fred live in LDS space the chunk phase no longer needs
   double Lg[G];
 #pragma unroll
   for (int g = 0; g < G; ++g) {
     double mx = -INFINITY;
-    for (int c = tid; c < nchunk; c += 256) mx = fmax(mx, ld_agent(&a.pm[pbase + int64_t(c) * G + g]));
+    for (int c = tid; c < nsub; c += 256) mx = fmax(mx, ld_agent(&a.pm[pbase + int64_t(c) * G + g]));
     mx = wave_max(mx);
     __syncthreads();
     if (lane == 0) sred[w] = mx;
     __syncthreads();
     mx = fmax(fmax(sred[0], sred[1]), fmax(sred[2], sred[3]));
     double part = 0.0;
-    for (int c = tid; c < nchunk; c += 256) {
+    for (int c = tid; c < nsub; c += 256) {
       const int64_t pi = pbase + int64_t(c) * G + g;
       const double m = ld_agent(&a.pm[pi]), pl = ld_agent(&a.pl[pi]);
       const double f = exp(m - mx);
@@ -295,14 +368,14 @@ __device__ __forceinline__ void head_tail(const DecodeArgs& a, OT* __restrict__ 
     constexpr int NPART = 256 / D;
     const int dcol = tid % D, part_id = tid / D;
     float num = 0.f;
-    for (int c0 = part_id; c0 < nchunk; c0 += 4 * NPART) {
+    for (int c0 = part_id; c0 < nsub; c0 += 4 * NPART) {
       float v[4], f[4];
 #pragma unroll
       for (int u = 0; u < 4; ++u) {
         const int c = c0 + u * NPART;
-        const int64_t pi = pbase + int64_t(min(c, nchunk - 1)) * G + g;
+        const int64_t pi = pbase + int64_t(min(c, nsub - 1)) * G + g;
         v[u] = ld_agent(&a.pacc[pi * D + dcol]);
-        f[u] = c < nchunk ? float(a.pf[pi]) : 0.f;
+        f[u] = c < nsub ? float(a.pf[pi]) : 0.f;
       }
 #pragma unroll
       for (int u = 0; u < 4; ++u) num = fmaf(v[u], f[u], num);
@@ -343,7 +416,7 @@ __device__ __forceinline__ void head_tail(const DecodeArgs& a, OT* __restrict__ 
       if (j < total) {
         double s2 = sc[u];
 #pragma unroll
-        for (int g = 0; g < G; ++g) s2 += e[u][g] * a.pf[pbase + int64_t(j / kChunk) * G + g] / Lg[g];
+        for (int g = 0; g < G; ++g) s2 += e[u][g] * a.pf[pbase + int64_t(j / kSub) * G + g] / Lg[g];
         a.cscore[slot0 + j] = s2;
         const int p = ps[u];
         if (p >= a.n_sink && p <= a.new_pos - recent && evicts_before(s2, p, j, ev)) ev = Best{s2, p, j};
@@ -432,8 +505,8 @@ __device__ __forceinline__ void head_tail(const DecodeArgs& a, OT* __restrict__ 
   if (tid == 0) a.eslot[lbh] = -1;
   // Eq. 9 arg-max over the chunks' results for candidate ci (ties: earlier position)
   Best m{0.0, 0, -1};
-  for (int c = tid; c < nchunk; c += 256) {
-    const int64_t x = (bh * a.nchunk_cap + mt[3] + c) * kCand + ci;
+  for (int c = tid; c < nsub; c += 256) {
+    const int64_t x = (pbase / G + c) * kCand + ci;
     const int s = ld_agent(&a.cslot[x]);
     if (s >= 0) {
       const double u = ld_agent(&a.cu[x]);
@@ -463,190 +536,211 @@ __global__ __launch_bounds__(256) void decode_attend(DecodeArgs a, OT* __restric
   constexpr int RB = D * sizeof(T);             // bytes of a cache row
   constexpr int NP = RB / kPiece;               // row pieces staged through LDS
   constexpr int EP = kPiece / sizeof(T);        // elements of a piece
-  constexpr int TPR = RB / 16;                  // V pass: threads per row
-  constexpr int RPP = 256 / TPR;                // V pass: rows per pass
-  constexpr int NPASS = kChunk / RPP;           // V pass: passes over the chunk
+  constexpr int TPR = RB / 16;                  // V pass: lanes per row
+  constexpr int RPI = 64 / TPR;                 // V pass: rows per load instruction
+  constexpr int NVL = kSub / RPI;               // V pass: loads per lane
   constexpr int NV = G + kCand;
-  constexpr int ES = (NV * 2 * kVec > 72) ? 4 : kVec;  // elements per K-pass step
+  constexpr int ES = NV <= 4 ? 4 : 2;           // elements per K-pass step (scalar register budget)
+  constexpr int NST = EP / ES;                  // steps per piece (even)
+  typedef typename RawBits<ES * sizeof(T)>::type Raw;
   __shared__ __attribute__((aligned(16))) unsigned char stage[kStageBytes];
-  __shared__ double sred[4 * (2 * G + kCand)];
-  __shared__ int ired[8 * kCand];
+  __shared__ float ps[4][G][kSub];
+  __shared__ double sred[4];
+  __shared__ int ired[8];
   __shared__ int sh_last;
-  float* ps = reinterpret_cast<float*>(stage);                 // [G][kChunk], after the K pass
-  float* red = reinterpret_cast<float*>(stage) + G * kChunk;   // [RPP][D], after the K pass
-  static_assert((G * kChunk + RPP * D) * 4 <= kStageBytes, "LDS aliases do not fit");
 
-  const int entry = find_entry(a, blockIdx.y), chunk = blockIdx.y - a.lay_off[entry];
+  const int entry = find_entry(a, blockIdx.y), grp = blockIdx.y - a.lay_off[entry];
   const int li = a.lay_id[entry];
   const int l = a.layer0 + li, b = blockIdx.x / a.Hkv, hk = blockIdx.x % a.Hkv;
   const int64_t lbh = (int64_t(l) * a.B + b) * a.Hkv + hk;
   const int total = a.ccount[lbh] + 1;          // the new token has been appended
-  if (chunk * kChunk >= total) return;
-  const int nchunk = (total + kChunk - 1) / kChunk;
+  if (grp * kGroup * kChunk >= total) return;
+  const int ngroup = (total + kGroup * kChunk - 1) / (kGroup * kChunk);
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const int32_t* mt = a.meta + (l * a.B + b) * 4;
   const int64_t bh = int64_t(b) * a.Hkv + hk;
   const int64_t slot0 = bh * a.slots + mt[0];
-  const unsigned char* Kc = static_cast<const unsigned char*>(a.cK) + (slot0 + int64_t(chunk) * kChunk) * RB;
-  const unsigned char* Vc = static_cast<const unsigned char*>(a.cV) + (slot0 + int64_t(chunk) * kChunk) * RB;
-  const int rows = min(kChunk, total - chunk * kChunk);
-
-  // ---- issue the chunk's K loads: per piece, 8 lanes cover 128 bytes of a row, 8 rows per load
-  u32x4 kreg[NP][8];
-#pragma unroll
-  for (int p = 0; p < NP; ++p)
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      const int r = w * 64 + i * 8 + (lane >> 3);
-      kreg[p][i] = u32x4{0, 0, 0, 0};
-      if (r < rows) kreg[p][i] = *reinterpret_cast<const u32x4*>(Kc + int64_t(r) * RB + p * kPiece + (lane & 7) * 16);
-    }
-  // first half of the V loads rides behind them
-  const int tr = tid / TPR, tc = tid % TPR;
-  u32x4 vreg[NPASS / 2];
-#pragma unroll
-  for (int i = 0; i < NPASS / 2; ++i) {
-    const int r = i * RPP + tr;
-    vreg[i] = u32x4{0, 0, 0, 0};
-    if (r < rows) vreg[i] = *reinterpret_cast<const u32x4*>(Vc + int64_t(r) * RB + tc * 16);
-  }
-
-  // ---- K pass: lane = row.  The queries and candidate keys arrive through scalar loads.
+  const unsigned char* Kh = static_cast<const unsigned char*>(a.cK) + slot0 * RB;
+  const unsigned char* Vh = static_cast<const unsigned char*>(a.cV) + slot0 * RB;
+  // A workgroup owns kGroup consecutive chunks of 256 slots; each wavefront works alone on 64
+  // rows ("sub-chunk") of each of them, in a software pipeline: while it computes on one
+  // sub-chunk, the V rows of that sub-chunk and the K rows of its next one are in flight.
+  // There is no workgroup barrier until the ticket.
   typedef const double __attribute__((address_space(4))) * cptr;
   cptr S = (cptr)(a.vecs + lbh * NV * D);
-  double acc[NV];
-#pragma unroll
-  for (int v = 0; v < NV; ++v) acc[v] = 0.0;
-  double nr = 0.0;
   unsigned char* mine = stage + w * 64 * kPitch;
-  u32x4 vreg2[NPASS / 2];
+  const int tr = lane / TPR, tc = lane % TPR;
+  const double root_d = sqrt(double(D));
+  int cs[kCand];
+  double cn[kCand];
 #pragma unroll
-  for (int p = 0; p < NP; ++p) {
-    // The staging area of a wavefront is private to it and LDS serves a wavefront's requests in
-    // order, so the piece hand-over needs compiler ordering only, no workgroup barrier.
-    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-    __builtin_amdgcn_wave_barrier();
+  for (int c = 0; c < kCand; ++c) {
+    cs[c] = a.cand[lbh * kCand + c];
+    cn[c] = a.cnorm[lbh * kCand + c];
+  }
+  // K loads of a sub-chunk: per piece, 8 lanes cover 128 bytes of a row, 8 rows per load
+  u32x4 kreg[NP][8];
+  auto load_keys = [&](int sub, int rows) {
+    const unsigned char* Kc = Kh + int64_t(sub) * kSub * RB;
 #pragma unroll
-    for (int i = 0; i < 8; ++i)
-      *reinterpret_cast<u32x4*>(mine + (i * 8 + (lane >> 3)) * kPitch + (lane & 7) * 16) = kreg[p][i];
-    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    if (p == NP - 1) {  // the key registers are free: second half of the V loads
+    for (int p = 0; p < NP; ++p)
 #pragma unroll
-      for (int i = 0; i < NPASS / 2; ++i) {
-        const int r = (NPASS / 2 + i) * RPP + tr;
-        vreg2[i] = u32x4{0, 0, 0, 0};
-        if (r < rows) vreg2[i] = *reinterpret_cast<const u32x4*>(Vc + int64_t(r) * RB + tc * 16);
+      for (int i = 0; i < 8; ++i) {
+        const int r = min(i * 8 + (lane >> 3), rows - 1);  // rows past the end repeat the last one
+        kreg[p][i] = *reinterpret_cast<const u32x4*>(Kc + int64_t(r) * RB + p * kPiece + (lane & 7) * 16);
       }
-    }
-    // ES elements per step: few enough that one step's scalar operands fit the scalar registers
+  };
+  const int sub0 = grp * kGroup * (kChunk / kSub) + w;
+  {
+    const int rows0 = min(kSub, total - sub0 * kSub);
+    if (rows0 > 0) load_keys(sub0, rows0);
+  }
 #pragma unroll 1
-    for (int st = 0; st < EP / ES; ++st) {
+  for (int it = 0; it < kGroup; ++it) {
+    const int sub = sub0 + it * (kChunk / kSub);
+    const int rows = min(kSub, total - sub * kSub);  // <= 0: nothing (more) for this wavefront
+    if (rows <= 0) break;
+    const unsigned char* Vc = Vh + int64_t(sub) * kSub * RB;
+    // ---- K pass: lane = row.  The queries and candidate keys arrive through scalar loads.
+    double acc[NV];
+#pragma unroll
+    for (int v = 0; v < NV; ++v) acc[v] = 0.0;
+    double nr = 0.0;
+    Raw rawA, rawB;
+    double sA[NV][ES], sB[NV][ES];
+    auto fetch = [&](int e0, int st, Raw& raw, double (&sv)[NV][ES]) {  // e0: first element of the piece
+      raw = *reinterpret_cast<const Raw*>(mine + lane * kPitch + st * ES * int(sizeof(T)));
+#pragma unroll
+      for (int v = 0; v < NV; ++v)
+#pragma unroll
+        for (int e = 0; e < ES; ++e) sv[v][e] = S[v * D + e0 + st * ES + e];
+    };
+    auto step = [&](const Raw& raw, const double (&sv)[NV][ES]) {
       double x[ES];
-      load_elems<T, ES>(mine + lane * kPitch + st * ES * int(sizeof(T)), x);
+      raw_to_f64<T, ES>(raw, x);
 #pragma unroll
       for (int e = 0; e < ES; ++e) nr = fma(x[e], x[e], nr);
 #pragma unroll
       for (int v = 0; v < NV; ++v)
 #pragma unroll
-        for (int e = 0; e < ES; ++e) acc[v] = fma(x[e], S[v * D + p * EP + st * ES + e], acc[v]);
-    }
-  }
-  // ---- chunk-local softmax statistics; thread tid owns cache row chunk*kChunk + tid
-  const bool valid = tid < rows;
-  const int j = chunk * kChunk + tid;
-  const double root_d = sqrt(double(D));
-  double sg[G];
+        for (int e = 0; e < ES; ++e) acc[v] = fma(x[e], sv[v][e], acc[v]);
+    };
+    u32x4 vreg[NVL];
+    // this lane's score-side loads ride along
+    const bool valid = lane < rows;
+    const int j = sub * kSub + lane;
+    const int pos = valid ? a.cpos[slot0 + j] : 0;
 #pragma unroll
-  for (int g = 0; g < G; ++g) {
-    sg[g] = acc[g] / root_d;
-    const double mx = wave_max(valid ? sg[g] : -INFINITY);
-    if (lane == 0) sred[w * G + g] = mx;
-  }
-  __syncthreads();  // also: every wavefront is done with the staged keys
-  const int64_t pidx = (bh * a.nchunk_cap + mt[3] + chunk) * G;
-  double mg[G];
+    for (int p = 0; p < NP; ++p) {
+      // The staging area is private to the wavefront and LDS serves a wavefront's requests in
+      // order, so the piece hand-over needs compiler ordering only.
+      __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+      __builtin_amdgcn_wave_barrier();
 #pragma unroll
-  for (int g = 0; g < G; ++g) {
-    mg[g] = fmax(fmax(sred[g], sred[G + g]), fmax(sred[2 * G + g], sred[3 * G + g]));
-    const double e = valid ? exp(sg[g] - mg[g]) : 0.0;
-    ps[g * kChunk + tid] = float(e);
-    if (valid) st_agent(&a.elog[(int64_t(b) * a.Hkv * G + hk * G + g) * a.slots + mt[0] + j], e);
-    const double sm = wave_sum(e);
-    if (lane == 0) sred[4 * G + w * G + g] = sm;
-  }
-  // candidates: cosine of this row against each candidate key (Eq. 9), chunk arg-max
-  const int pos = valid ? a.cpos[slot0 + j] : 0;
-  const double nrow = sqrt(nr);
+      for (int i = 0; i < 8; ++i)
+        *reinterpret_cast<u32x4*>(mine + (i * 8 + (lane >> 3)) * kPitch + (lane & 7) * 16) = kreg[p][i];
+      __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+      if (p == NP - 1) {  // the key registers are free: this sub-chunk's V rows and the next one's K rows
 #pragma unroll
-  for (int c = 0; c < kCand; ++c) {
-    const int cs = a.cand[lbh * kCand + c];
-    const double den = a.cnorm[lbh * kCand + c] * nrow;
-    const double u = den > 0.0 ? acc[G + c] / den : 0.0;
-    Best m{u, pos, (valid && cs >= 0 && j != cs) ? j : -1};
-    m = wave_best_match(m);
-    if (lane == 0) {
-      sred[8 * G + w * kCand + c] = m.u;
-      ired[w * kCand + c] = m.pos;
-      ired[4 * kCand + w * kCand + c] = m.slot;
-    }
-  }
-  __syncthreads();
-  if (tid < G) {
-    // all threads hold the same mg[]; pick element tid without dynamic register indexing
-    double mv = 0.0, lv = 0.0;
-#pragma unroll
-    for (int g = 0; g < G; ++g)
-      if (g == tid) {
-        mv = mg[g];
-        lv = ((sred[4 * G + g] + sred[5 * G + g]) + sred[6 * G + g]) + sred[7 * G + g];
+        for (int i = 0; i < NVL; ++i) {
+          const int r = min(i * RPI + tr, rows - 1);  // repeated rows meet a zero probability
+          vreg[i] = *reinterpret_cast<const u32x4*>(Vc + int64_t(r) * RB + tc * 16);
+        }
+        const int nsub = sub + kChunk / kSub, nrows = min(kSub, total - nsub * kSub);
+        if (it + 1 < kGroup && nrows > 0) load_keys(nsub, nrows);
       }
-    st_agent(&a.pm[pidx + tid], mv);
-    st_agent(&a.pl[pidx + tid], lv);
-  }
-  if (tid >= 64 && tid < 64 + kCand) {
-    const int c = tid - 64;
-    Best m{sred[8 * G + c], ired[c], ired[4 * kCand + c]};
-#pragma unroll
-    for (int i = 1; i < 4; ++i)
-      if (better_match(sred[8 * G + i * kCand + c], ired[i * kCand + c], ired[4 * kCand + i * kCand + c], m))
-        m = Best{sred[8 * G + i * kCand + c], ired[i * kCand + c], ired[4 * kCand + i * kCand + c]};
-    const int64_t x = (bh * a.nchunk_cap + mt[3] + chunk) * kCand + c;
-    st_agent(&a.cu[x], m.u);
-    st_agent(&a.cslot[x], m.slot);
-  }
-  // ---- partial P V, fp32
-  float pv[G][kVec];
-#pragma unroll
-  for (int g = 0; g < G; ++g)
-#pragma unroll
-    for (int e = 0; e < kVec; ++e) pv[g][e] = 0.f;
-#pragma unroll
-  for (int i = 0; i < NPASS; ++i) {
-    const int r = i * RPP + tr;
-    float x[kVec];
-    cvt16f<T>(i < NPASS / 2 ? vreg[i % (NPASS / 2)] : vreg2[i % (NPASS / 2)], x);
+      // ES elements per step.  The row's bits and the scalar operands of a step are fetched one
+      // step ahead (two register sets), so their latency hides behind the previous step's FMAs.
+      const int e0 = p * EP;
+      fetch(e0, 0, rawA, sA);
+#pragma unroll 1
+      for (int st = 0; st < NST; st += 2) {
+        // the wait for a set comes before the other set's fetches are issued (scalar loads
+        // return out of order, so a wait after them would cover them too)
+        arrived(sA[0][0]);
+        fetch(e0, st + 1, rawB, sB);
+        step(rawA, sA);
+        arrived(sB[0][0]);
+        fetch(e0, min(st + 2, NST - 1), rawA, sA);
+        step(rawB, sB);
+      }
+    }
+    // ---- softmax statistics of the sub-chunk; the lane owns cache row sub*kSub + lane
+    const int64_t pidx = (bh * a.nsub_cap + int64_t(mt[3]) * (kChunk / kSub) + sub) * G;
 #pragma unroll
     for (int g = 0; g < G; ++g) {
-      const float p = ps[g * kChunk + r];  // 0 for rows beyond the chunk's end
+      const double sg = acc[g] / root_d;
+      const double mx = fast_wave_max(valid ? sg : -INFINITY);
+      const double e = valid ? exp(sg - mx) : 0.0;
+      ps[w][g][lane] = float(e);
+      if (valid) st_agent(&a.elog[(int64_t(b) * a.Hkv * G + hk * G + g) * a.slots + mt[0] + j], e);
+      const double sm = fast_wave_sum(e);
+      if (lane == 0) {
+        st_agent(&a.pm[pidx + g], mx);
+        st_agent(&a.pl[pidx + g], sm);
+      }
+    }
+    // candidates: cosine of this row against each candidate key (Eq. 9), sub-chunk arg-max
+    const double nrow = sqrt(nr);
 #pragma unroll
-      for (int e = 0; e < kVec; ++e) pv[g][e] = fmaf(p, x[e], pv[g][e]);
+    for (int c = 0; c < kCand; ++c) {
+      const double den = cn[c] * nrow;
+      const double u = den > 0.0 ? acc[G + c] / den : 0.0;
+      const Best m = fast_wave_best_match(u, pos, (valid && cs[c] >= 0 && j != cs[c]) ? j : -1);
+      if (lane == 0) {
+        const int64_t x = (pidx / G) * kCand + c;
+        st_agent(&a.cu[x], m.u);
+        st_agent(&a.cslot[x], m.slot);
+      }
+    }
+    // ---- partial P V, fp32: TPR lanes per row, RPI rows per load, then a sum over the row groups
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    float pv[G][kVec];
+#pragma unroll
+    for (int g = 0; g < G; ++g)
+#pragma unroll
+      for (int e = 0; e < kVec; ++e) pv[g][e] = 0.f;
+#pragma unroll
+    for (int i = 0; i < NVL; ++i) {
+      const int r = i * RPI + tr;
+      float x[kVec];
+      cvt16f<T>(vreg[i], x);
+#pragma unroll
+      for (int g = 0; g < G; ++g) {
+        const float p = ps[w][g][r];  // 0 for rows beyond the end
+#pragma unroll
+        for (int e = 0; e < kVec; ++e) pv[g][e] = fmaf(p, x[e], pv[g][e]);
+      }
+    }
+    // sum over the row groups, then one full-width store per query head: lane i writes
+    // columns 2i, 2i+1 (the staging area is free again and serves as the exchange buffer)
+    float* xch = reinterpret_cast<float*>(mine);
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+#pragma unroll
+      for (int e = 0; e < kVec; ++e) {
+        float t = pv[g][e];
+#pragma unroll
+        for (int o = TPR; o < 64; o <<= 1) t += __shfl_xor(t, o, 64);
+        pv[g][e] = t;
+      }
+      __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+      if (tr == 0) {
+#pragma unroll
+        for (int e = 0; e < kVec; ++e) xch[tc * kVec + e] = pv[g][e];
+      }
+      __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+      for (int c = lane * 2; c < D; c += 128) {
+        const uint64_t two = uint64_t(__float_as_uint(xch[c])) | (uint64_t(__float_as_uint(xch[c + 1])) << 32);
+        st_agent(reinterpret_cast<uint64_t*>(a.pacc + (pidx + g) * D + c), two);
+      }
     }
   }
-#pragma unroll
-  for (int g = 0; g < G; ++g) {
-    __syncthreads();
-#pragma unroll
-    for (int e = 0; e < kVec; ++e) red[tr * D + tc * kVec + e] = pv[g][e];
-    __syncthreads();
-    if (tid < D) {
-      float t = 0.f;
-#pragma unroll
-      for (int i = 0; i < RPP; ++i) t += red[i * D + tid];
-      st_agent(&a.pacc[(pidx + g) * D + tid], t);
-    }
-  }
-  // ---- ticket: the last workgroup of the head to arrive combines the chunks.  Every store
+  // ---- ticket: the last workgroup of the head to arrive combines the sub-chunks.  Every store
   //      above that it will read is a write-through store; they have completed once the
   //      memory counters are zero, before the barrier that precedes the ticket.
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
@@ -654,15 +748,17 @@ __global__ __launch_bounds__(256) void decode_attend(DecodeArgs a, OT* __restric
   __syncthreads();
   if (tid == 0)
     sh_last = (__hip_atomic_fetch_add(&a.ticket[lbh], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) ==
-               unsigned(nchunk - 1)) ? 1 : 0;
+               unsigned(ngroup - 1)) ? 1 : 0;
   __syncthreads();
   if (!sh_last) return;
-  head_tail<T, OT, D, G>(a, out, ov, li, b, hk, lbh, total, nchunk, sred, ired, red);
+  head_tail<T, OT, D, G>(a, out, ov, li, b, hk, lbh, total, (total + kSub - 1) / kSub, sred, ired,
+                         reinterpret_cast<float*>(stage));
 }
 
-// Fallback pass: cosine of the evicted key against every survivor of its head (Eq. 9).
+// Fallback for a head whose evicted token was not among the step's candidates: cosine of the
+// evicted key against every survivor (Eq. 9) by one workgroup, then the finishing code.
 template <typename T, int D>
-__global__ __launch_bounds__(256) void decode_cosine(DecodeArgs a) {
+__global__ __launch_bounds__(256) void decode_fallback(DecodeArgs a) {
   constexpr int kVec = 16 / sizeof(T);
   constexpr int TPR = D / kVec;
   constexpr int RPP = 256 / TPR;
@@ -670,14 +766,11 @@ __global__ __launch_bounds__(256) void decode_cosine(DecodeArgs a) {
   __shared__ double red[4];
   __shared__ double bu[4];
   __shared__ int bpos[4], bslot[4];
-  const int entry = find_entry(a, blockIdx.y), chunk = blockIdx.y - a.lay_off[entry];
-  const int li = a.lay_id[entry];
-  const int l = a.layer0 + li, b = blockIdx.x / a.Hkv, hk = blockIdx.x % a.Hkv;
+  const int li = blockIdx.y, l = a.layer0 + li, b = blockIdx.x / a.Hkv, hk = blockIdx.x % a.Hkv;
   const int64_t lbh = (int64_t(l) * a.B + b) * a.Hkv + hk;
   const int es = a.eslot[lbh];
   if (es < 0) return;
   const int total = a.ccount[lbh] + 1;
-  if (chunk * kChunk >= total) return;
   const int tid = threadIdx.x;
   const int32_t* mt = a.meta + (l * a.B + b) * 4;
   const int64_t bh = int64_t(b) * a.Hkv + hk;
@@ -690,13 +783,12 @@ __global__ __launch_bounds__(256) void decode_cosine(DecodeArgs a) {
     part = x * x;
   }
   const double sne = sqrt(block_sum(part, red));
-  const int rows = min(kChunk, total - chunk * kChunk);
   const int tr = tid / TPR, tc = (tid % TPR) * kVec;
   Best m{0.0, 0, -1};
-  for (int r0 = 0; r0 < rows; r0 += RPP) {
-    const int r = r0 + tr, j = chunk * kChunk + r;
+  for (int r0 = 0; r0 < total; r0 += RPP) {
+    const int j = r0 + tr;
     double dot = 0.0, nr = 0.0;
-    if (r < rows) {
+    if (j < total) {
       double x[kVec];
       cvt16<T>(*reinterpret_cast<const u32x4*>(Kc + int64_t(j) * D + tc), x);
 #pragma unroll
@@ -710,7 +802,7 @@ __global__ __launch_bounds__(256) void decode_cosine(DecodeArgs a) {
       dot += __shfl_xor(dot, o, 64);
       nr += __shfl_xor(nr, o, 64);
     }
-    if (r < rows && j != es && (tid % TPR) == 0) {
+    if (j < total && j != es && (tid % TPR) == 0) {
       const double den = sne * sqrt(nr);
       const double u = den > 0.0 ? dot / den : 0.0;
       const int p = a.cpos[slot0 + j];
@@ -724,44 +816,12 @@ __global__ __launch_bounds__(256) void decode_cosine(DecodeArgs a) {
     bslot[tid >> 6] = m.slot;
   }
   __syncthreads();
-  if (tid == 0) {
-    for (int i = 1; i < 4; ++i)
-      if (better_match(bu[i], bpos[i], bslot[i], m)) m = Best{bu[i], bpos[i], bslot[i]};
-    const int64_t x = (bh * a.nchunk_cap + mt[3] + chunk) * kCand;
-    a.cu[x] = m.u;
-    a.cslot[x] = m.slot;  // -1 when the chunk holds only the evicted slot
-  }
-}
-
-template <typename T, int D>
-__global__ __launch_bounds__(128) void decode_finish(DecodeArgs a) {
-  __shared__ double su;
-  __shared__ int sp, ss;
-  const int li = blockIdx.y, l = a.layer0 + li, b = blockIdx.x / a.Hkv, hk = blockIdx.x % a.Hkv;
-  const int64_t lbh = (int64_t(l) * a.B + b) * a.Hkv + hk;
-  const int es = a.eslot[lbh];
-  if (es < 0) return;
-  const int total = a.ccount[lbh] + 1;
-  const int nchunk = (total + kChunk - 1) / kChunk;
-  const int32_t* mt = a.meta + (l * a.B + b) * 4;
-  const int64_t bh = int64_t(b) * a.Hkv + hk;
-  const int64_t slot0 = bh * a.slots + mt[0];
-  if (threadIdx.x == 0) {
-    Best m{0.0, 0, -1};
-    for (int c = 0; c < nchunk; ++c) {
-      const int64_t x = (bh * a.nchunk_cap + mt[3] + c) * kCand;
-      const int s = a.cslot[x];
-      if (s < 0) continue;
-      const double u = a.cu[x];
-      const int p = a.cpos[slot0 + s];
-      if (better_match(u, p, s, m)) m = Best{u, p, s};
-    }
-    su = m.u;
-    sp = m.pos;
-    ss = m.slot;
-  }
+  m = Best{bu[0], bpos[0], bslot[0]};
+#pragma unroll
+  for (int i = 1; i < 4; ++i)
+    if (better_match(bu[i], bpos[i], bslot[i], m)) m = Best{bu[i], bpos[i], bslot[i]};
   __syncthreads();
-  finish_head<T, D>(a, lbh, slot0, es, total, su, sp, ss);
+  finish_head<T, D>(a, lbh, slot0, es, total, m.u, m.pos, m.slot);
 }
 
 template <typename T, typename OT, int D, int G>
@@ -777,12 +837,8 @@ hipError_t run_decode_o(d2o_ctx* c, const DecodeArgs& a, int nl, int flat_chunks
     KernelTimer kt(c, D2O_K_DECODE_ATTEND, s);
     decode_attend<T, OT, D, G><<<dim3(bh, flat_chunks), 256, 0, s>>>(a, (OT*)out.ptr, out);
   }
-  {
-    KernelTimer kt(c, D2O_K_DECODE_COSINE, s);
-    decode_cosine<T, D><<<dim3(bh, flat_chunks), 256, 0, s>>>(a);
-  }
-  KernelTimer kt(c, D2O_K_DECODE_FINISH, s);
-  decode_finish<T, D><<<dim3(bh, nl), 128, 0, s>>>(a);
+  KernelTimer kt(c, D2O_K_DECODE_FALLBACK, s);
+  decode_fallback<T, D><<<dim3(bh, nl), 256, 0, s>>>(a);
   return hipGetLastError();
 }
 
@@ -808,6 +864,7 @@ hipError_t run_decode_g(d2o_ctx* c, const DecodeArgs& a, int nl, int fc, View q,
 }  // namespace
 
 int decode_candidates() { return kCand; }
+
 
 hipError_t launch_decode(d2o_ctx* c, int layer0, int nl_all, View q, View k, View v, View out, int new_pos,
                          hipStream_t s) {
@@ -836,7 +893,7 @@ hipError_t launch_decode(d2o_ctx* c, int layer0, int nl_all, View q, View k, Vie
   a.ev_target = c->ev_target;
   a.ev_ustar = c->ev_ustar;
   a.slots = cf.slots_per_seq;
-  a.nchunk_cap = c->nchunk_cap;
+  a.nsub_cap = c->nchunk_cap * (kChunk / kSub);
   a.B = cf.batch;
   a.Hkv = cf.n_kv_heads;
   a.G = cf.n_q_heads / cf.n_kv_heads;
@@ -854,7 +911,8 @@ hipError_t launch_decode(d2o_ctx* c, int layer0, int nl_all, View q, View k, Vie
     for (int i = 0; i < nl; ++i) {
       a.lay_id[i] = i;
       mc[i] = 1;
-      for (const auto& mt : c->layers[a.layer0 + i].meta) mc[i] = std::max(mc[i], (mt.budget + 1 + kChunk - 1) / kChunk);
+      for (const auto& mt : c->layers[a.layer0 + i].meta)
+        mc[i] = std::max(mc[i], (mt.budget + 1 + kGroup * kChunk - 1) / (kGroup * kChunk));
     }
     std::stable_sort(a.lay_id, a.lay_id + nl, [&](int x, int y) { return mc[x] > mc[y]; });
     int flat = 0;
