@@ -162,50 +162,6 @@ __device__ __forceinline__ int find_entry(const DecodeArgs& a, int x) {
   return __popcll(__ballot(start <= x)) - 1;
 }
 
-// Wavefront reductions on the data-parallel-primitive path (register-to-register lane
-// permutations, no LDS round trip): four butterfly steps inside each row of 16 lanes, then the
-// four row results are combined through scalar registers.  Every lane gets the result; the
-// combination tree is fixed.
-constexpr int kDppXor1 = 0xB1;         // quad_perm [1,0,3,2]
-constexpr int kDppXor2 = 0x4E;         // quad_perm [2,3,0,1]
-constexpr int kDppHalfMirror = 0x141;  // lane i <-> 7 - i within 8
-constexpr int kDppMirror = 0x140;      // lane i <-> 15 - i within 16
-template <int CTRL>
-__device__ __forceinline__ int dpp_i32(int v) {
-  return __builtin_amdgcn_update_dpp(0, v, CTRL, 0xF, 0xF, true);
-}
-template <int CTRL>
-__device__ __forceinline__ double dpp_f64(double v) {
-  const int lo = dpp_i32<CTRL>(__double2loint(v)), hi = dpp_i32<CTRL>(__double2hiint(v));
-  return __hiloint2double(hi, lo);
-}
-__device__ __forceinline__ double lane_f64(double v, int lane) {
-  return __hiloint2double(__builtin_amdgcn_readlane(__double2hiint(v), lane),
-                          __builtin_amdgcn_readlane(__double2loint(v), lane));
-}
-__device__ __forceinline__ double fast_wave_max(double v) {
-  v = fmax(v, dpp_f64<kDppXor1>(v));
-  v = fmax(v, dpp_f64<kDppXor2>(v));
-  v = fmax(v, dpp_f64<kDppHalfMirror>(v));
-  v = fmax(v, dpp_f64<kDppMirror>(v));
-  return fmax(fmax(lane_f64(v, 0), lane_f64(v, 16)), fmax(lane_f64(v, 32), lane_f64(v, 48)));
-}
-__device__ __forceinline__ double fast_wave_sum(double v) {
-  v += dpp_f64<kDppXor1>(v);
-  v += dpp_f64<kDppXor2>(v);
-  v += dpp_f64<kDppHalfMirror>(v);
-  v += dpp_f64<kDppMirror>(v);
-  return (lane_f64(v, 0) + lane_f64(v, 16)) + (lane_f64(v, 32) + lane_f64(v, 48));
-}
-__device__ __forceinline__ int fast_wave_min(int v) {
-  v = min(v, dpp_i32<kDppXor1>(v));
-  v = min(v, dpp_i32<kDppXor2>(v));
-  v = min(v, dpp_i32<kDppHalfMirror>(v));
-  v = min(v, dpp_i32<kDppMirror>(v));
-  return min(min(__builtin_amdgcn_readlane(v, 0), __builtin_amdgcn_readlane(v, 16)),
-             min(__builtin_amdgcn_readlane(v, 32), __builtin_amdgcn_readlane(v, 48)));
-}
-
 // (u larger, then position smaller) wins; slot < 0 means "no entry".
 struct Best {
   double u;

@@ -325,8 +325,10 @@ __global__ __launch_bounds__(1024) void amb_compact_kernel(const int32_t* __rest
 }
 
 // Exact similarity in fp64, operation order of Eq. 9 as written: dot / (|k_i| * |k_j|), 0 when
-// a norm is 0.  One wavefront per evicted row.  Unambiguous rows evaluate their candidate only;
-// ambiguous rows (and every row when no filter ran) search all retained keys, first maximum in
+// a norm is 0.  A group of 16 lanes (one 16-byte slice of the key each) serves one evicted row:
+// unambiguous rows evaluate their single candidate, ambiguous rows their short candidate list;
+// rows without a usable list (and every row when no filter ran) are then searched exhaustively,
+// one at a time, with the wavefront's lanes striding over the retained keys, first maximum in
 // ascending retained order.  Products of bf16 values are exact in fp64 and their sums stay
 // exact at these magnitudes, so the result does not depend on the summation tree.
 template <typename T>
@@ -341,10 +343,17 @@ __device__ __forceinline__ void load8<uint16_t>(const uint16_t* p, double* out) 
   }
 }
 template <>
-__device__ __forceinline__ void load8<float>(const float* p, double* out) {
-  const float4 a = reinterpret_cast<const float4*>(p)[0], b = reinterpret_cast<const float4*>(p)[1];
+__device__ __forceinline__ void load8<float>(const float* p, double* out) {  // 16 bytes: 4 elements
+  const float4 a = reinterpret_cast<const float4*>(p)[0];
   out[0] = a.x; out[1] = a.y; out[2] = a.z; out[3] = a.w;
-  out[4] = b.x; out[5] = b.y; out[6] = b.z; out[7] = b.w;
+}
+
+// Lanes of one row group (TPR lanes: 16, or 32 for 512-byte rows) add their partial sums.
+template <int TPR>
+__device__ __forceinline__ double group_sum(double v) {
+  v = row16_sum(v);
+  if constexpr (TPR == 32) v += __shfl_xor(v, 16, 64);
+  return v;
 }
 
 template <typename T, int D>
@@ -353,32 +362,31 @@ __global__ __launch_bounds__(256) void match_refine(const T* __restrict__ K, Vie
                                                     const int32_t* __restrict__ cand, const int32_t* __restrict__ ncand,
                                                     const int32_t* __restrict__ clist, double* __restrict__ ustar,
                                                     int32_t* __restrict__ tgt, int npad, int use_filter) {
+  constexpr int kVec = 16 / sizeof(T);  // elements per 16-byte load
+  constexpr int TPR = D / kVec;         // lanes that share one evicted row
+  constexpr int RW = 64 / TPR;          // evicted rows per wavefront
   __shared__ double ke[4][D];
   const int hk = blockIdx.y, b = blockIdx.z, Hkv = gridDim.y;
   const int64_t bh = int64_t(b) * Hkv + hk;
   const int nret = cnt[bh * 2], nevi = cnt[bh * 2 + 1];
-  const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  if (int(blockIdx.x) * 4 >= nevi) return;  // block-uniform
-  const int erank_raw = blockIdx.x * 4 + w;
+  const int w = threadIdx.x >> 6, lane = threadIdx.x & 63, grp = lane / TPR, tc = lane % TPR;
+  if (int(blockIdx.x) * 4 * RW >= nevi) return;  // block-uniform
+  const int erank_raw = (blockIdx.x * 4 + w) * RW + grp;
   const bool valid = erank_raw < nevi;
   const int erank = valid ? erank_raw : nevi - 1;
   const T* kb = K + b * kv.sb + hk * kv.sh;
   const int32_t* rl = ret + bh * npad;
   const int epos = evi[bh * npad + erank];
-  const T* er = kb + int64_t(epos) * kv.sn;
+  // this lane's slice of the evicted key
+  double x[kVec];
+  load8<T>(kb + int64_t(epos) * kv.sn + tc * kVec, x);
   double ne = 0.0;
-  for (int c = lane; c < D; c += 64) {
-    const double x = Elem<T>::to_f64(er[c]);
-    ke[w][c] = x;
-    ne += x * x;
-  }
-  __syncthreads();
-  ne = wave_sum(ne);
-  const double sne = sqrt(ne);
-  // candidates: one (unambiguous), a short list (ambiguous), or every retained key
-  int ncd = 0;
-  const int32_t* cl = nullptr;
-  int single = -1;
+#pragma unroll
+  for (int e = 0; e < kVec; ++e) ne = fma(x[e], x[e], ne);
+  const double sne = sqrt(group_sum<TPR>(ne));
+  // candidates: one (unambiguous), a short list (ambiguous), or every retained key (ncd < 0)
+  int ncd = -1, single = -1;
+  const int32_t* cl = clist + (bh * npad + erank) * kMaxCand;
   if (use_filter) {
     const int cnd = cand[bh * npad + erank];
     if (cnd >= 0) {
@@ -386,64 +394,86 @@ __global__ __launch_bounds__(256) void match_refine(const T* __restrict__ K, Vie
       ncd = 1;
     } else {
       ncd = ncand[bh * npad + erank];
-      cl = clist + (bh * npad + erank) * kMaxCand;
       if (ncd > kMaxCand || ncd == 0) ncd = -1;  // overflow (or zero-norm row): exhaustive search
     }
-  } else {
-    ncd = -1;
   }
   double best = -2.0;
   int bj = 0x7FFFFFFF;
-  if (ncd >= 0) {
-    for (int q = 0; q < ncd; ++q) {
-      const int j = single >= 0 ? single : cl[q];
-      const T* rr = kb + int64_t(rl[j]) * kv.sn;
-      double dot = 0.0, nr = 0.0;
-      for (int c = lane; c < D; c += 64) {
-        const double y = Elem<T>::to_f64(rr[c]);
-        dot += ke[w][c] * y;
-        nr += y * y;
-      }
-      dot = wave_sum(dot);
-      nr = wave_sum(nr);
-      const double den = sne * sqrt(nr);
-      const double u = den > 0.0 ? dot / den : 0.0;
-      if (u > best || (u == best && j < bj)) {
-        best = u;
-        bj = j;
-      }
+  // ---- listed candidates: the row group evaluates them one after the other
+  int nloop = max(ncd, 0);
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) nloop = max(nloop, __shfl_xor(nloop, o, 64));
+  for (int q = 0; q < nloop; ++q) {
+    const bool on = q < ncd;
+    const int j = on ? (single >= 0 ? single : cl[q]) : 0;
+    double y[kVec];
+    load8<T>(kb + int64_t(rl[j]) * kv.sn + tc * kVec, y);
+    double dot = 0.0, nr = 0.0;
+#pragma unroll
+    for (int e = 0; e < kVec; ++e) {
+      dot = fma(x[e], y[e], dot);
+      nr = fma(y[e], y[e], nr);
     }
-  } else {
+    dot = group_sum<TPR>(dot);
+    nr = group_sum<TPR>(nr);
+    const double den = sne * sqrt(nr);
+    const double u = den > 0.0 ? dot / den : 0.0;
+    if (on && (u > best || (u == best && j < bj))) {
+      best = u;
+      bj = j;
+    }
+  }
+  // ---- exhaustive search, one row at a time, the wavefront's lanes striding over the retained keys
+  unsigned long long todo = __ballot(valid && ncd < 0 && tc == 0);
+  while (todo) {
+    const int src = __ffsll((long long)todo) - 1;  // first lane of the row group to serve
+    todo &= todo - 1;
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    if (lane / TPR == src / TPR) {
+#pragma unroll
+      for (int e = 0; e < kVec; ++e) ke[w][tc * kVec + e] = x[e];
+    }
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    const double sne_r = __hiloint2double(__builtin_amdgcn_readlane(__double2hiint(sne), src),
+                                          __builtin_amdgcn_readlane(__double2loint(sne), src));
+    double fb = -2.0;
+    int fj = 0x7FFFFFFF;
     for (int j = lane; j < nret; j += 64) {
       const T* rr = kb + int64_t(rl[j]) * kv.sn;
       double dot = 0.0, nr = 0.0;
-      for (int c = 0; c < D; c += 8) {
-        double y[8];
+      for (int c = 0; c < D; c += kVec) {
+        double y[kVec];
         load8<T>(rr + c, y);
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-          dot += ke[w][c + i] * y[i];
-          nr += y[i] * y[i];
+        for (int i = 0; i < kVec; ++i) {
+          dot = fma(ke[w][c + i], y[i], dot);
+          nr = fma(y[i], y[i], nr);
         }
       }
-      const double den = sne * sqrt(nr);
+      const double den = sne_r * sqrt(nr);
       const double u = den > 0.0 ? dot / den : 0.0;
-      if (u > best) {  // j ascends within a lane: strict > keeps the first maximum
-        best = u;
-        bj = j;
+      if (u > fb) {  // j ascends within a lane: strict > keeps the first maximum
+        fb = u;
+        fj = j;
       }
     }
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) {
-      const double ob = __shfl_xor(best, o, 64);
-      const int oj = __shfl_xor(bj, o, 64);
-      if (ob > best || (ob == best && oj < bj)) {
-        best = ob;
-        bj = oj;
+      const double ob = __shfl_xor(fb, o, 64);
+      const int oj = __shfl_xor(fj, o, 64);
+      if (ob > fb || (ob == fb && oj < fj)) {
+        fb = ob;
+        fj = oj;
       }
     }
+    if (lane == src) {
+      best = fb;
+      bj = fj;
+    }
   }
-  if (lane == 0 && valid) {
+  if (tc == 0 && valid) {
     ustar[bh * npad + erank] = best;
     tgt[bh * npad + erank] = bj;
   }
@@ -631,7 +661,8 @@ hipError_t launch_match(d2o_ctx* c, int layer, View K, int n, hipStream_t s) {
   const d2o_config& cf = c->cfg;
   const int me = max_evicted(c, layer, n);
   if (me == 0) return hipSuccess;
-  const dim3 gr((me + 3) / 4, cf.n_kv_heads, cf.batch);
+  const int refine_rows = 4 * 64 / ((cf.head_dim * c->esize) / 16);  // evicted rows per workgroup of match_refine
+  const dim3 gr((me + refine_rows - 1) / refine_rows, cf.n_kv_heads, cf.batch);
   if (cf.dtype == D2O_BF16) {
     const dim3 gf((me + 127) / 128, cf.n_kv_heads, cf.batch);
     invnorm_bf16<<<dim3((n + 15) / 16, cf.n_kv_heads, cf.batch), 256, 0, s>>>((const uint16_t*)K.ptr, K, c->invnorm, n,
