@@ -79,7 +79,7 @@ struct d2o_ctx {
   // ---- scratch workspace (device) ----
   // prefill attention
   float* lse = nullptr;          // [B][Hq][npad]   row log-sum-exp (natural log, scaled logits)
-  void* vt = nullptr;            // [B][Hkv][d][npad] transposed values as scaled fp16 (bf16 path)
+  void* vt = nullptr;            // [B][Hkv][npad/64][d][64] transposed values, tile by tile, as scaled fp16 (bf16 path)
   uint32_t* vmax_bits = nullptr; // [B][Hkv] bit pattern of max |v|
   float* vt_unscale = nullptr;   // [B][Hkv] power of two that undoes the fp16 scaling
   double* varpart = nullptr;     // [B][Hq][npad/128][2] partial sums of s and s^2

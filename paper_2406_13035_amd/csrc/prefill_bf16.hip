@@ -23,6 +23,7 @@
 //   A[m][8h .. 8h+7], B[8h .. 8h+7][m], D[(r/4)*8 + 4h + r%4][m] for r = 0..15.
 #include "d2o_internal.h"
 #include <algorithm>
+#include <type_traits>
 
 #include "device_utils.h"
 
@@ -71,7 +72,9 @@ __device__ __forceinline__ float v_scale_from_max(uint32_t maxbits) {
   return __uint_as_float(uint32_t(127 - k) << 23);  // 2^-k
 }
 
-// V [b][h][n][d] (bf16) -> VT [b][h][d][npad] (fp16, scaled), zero for keys >= n.
+// V [b][h][n][d] (bf16) -> VT [b][h][npad/64][d][64] (fp16, scaled), zero for keys >= n: the
+// transposed values of every 64-key tile are contiguous (a [d][npad] layout would put a tile's
+// rows a power-of-two stride apart, all on one memory channel).
 __global__ __launch_bounds__(256) void transpose_v(const uint16_t* __restrict__ V, View vv, uint16_t* __restrict__ VT,
                                                    const uint32_t* __restrict__ vmax, float* __restrict__ unscale,
                                                    int n, int npad) {
@@ -102,7 +105,7 @@ __global__ __launch_bounds__(256) void transpose_v(const uint16_t* __restrict__ 
     u32x4 v;
     v[0] = o[0] | (uint32_t(o[1]) << 16); v[1] = o[2] | (uint32_t(o[3]) << 16);
     v[2] = o[4] | (uint32_t(o[5]) << 16); v[3] = o[6] | (uint32_t(o[7]) << 16);
-    *reinterpret_cast<u32x4*>(dst + int64_t(dd) * npad + k0 + kc) = v;
+    *reinterpret_cast<u32x4*>(dst + (int64_t(blockIdx.x) * kD + dd) * 64 + kc) = v;
   }
 }
 
@@ -120,9 +123,10 @@ constexpr int kAttnBM = 32 * kAttnRW * kAttnNW;
 
 // NW wavefronts per workgroup, each owning RW 32-row MFMA column blocks (blocks of one
 // wavefront share every K / V^T operand read from LDS).  Built as 8 x 1: 256 query rows per
-// workgroup, two wavefronts per SIMD, which measured faster than 4 x 2.  K and V^T
-// tiles of 64 keys are double-buffered in LDS; the next tile's global loads are issued before
-// the current tile's MFMAs and written to the other buffer after them (one barrier per tile).
+// workgroup, two wavefronts per SIMD, which measured faster than 4 x 2.  K and V^T tiles of 64
+// keys are double-buffered in LDS.  A tile costs a wavefront about as many vector-ALU cycles
+// (32 exponentials per lane at a quarter of the ALU rate) as matrix-core cycles (32 MFMAs), so
+// the two wavefronts of a SIMD alternate between the two units (see the schedule below).
 template <int RW, int NW>
 __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_fwd_bf16(const uint16_t* __restrict__ Q, View qv,
                                                      const uint16_t* __restrict__ K, View kv,
@@ -170,20 +174,26 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, 2)))
   const int last_key = min(rb + BM - 1, n - 1);
   const int ntile = last_key / 64 + 1;
 
-  // staging: each thread moves 4 16-byte chunks of K and 4 of V^T per tile
+  // staging: each thread moves NCH 16-byte chunks of K and NCH of V^T per tile
   u32x4 kr[NCH], vr[NCH];
-  auto issue = [&](int t) {
+  auto issue_k = [&](int t) {
     const int k0 = t * 64;
 #pragma unroll
     for (int i = 0; i < NCH; ++i) {
       const int c = tid + NT * i;
       const int row = c >> 4, col = (c & 15) * 8;
       kr[i] = *reinterpret_cast<const u32x4*>(kbase + int64_t(min(k0 + row, n - 1)) * kv.sn + col);
-      const int dd = c >> 3, kc = (c & 7) * 8;
-      vr[i] = *reinterpret_cast<const u32x4*>(vtbase + int64_t(dd) * npad + k0 + kc);
     }
   };
-  auto stage = [&](int buf) {
+  auto issue_v = [&](int t) {
+#pragma unroll
+    for (int i = 0; i < NCH; ++i) {
+      const int c = tid + NT * i;
+      const int dd = c >> 3, kc = (c & 7) * 8;
+      vr[i] = *reinterpret_cast<const u32x4*>(vtbase + (int64_t(t) * kD + dd) * 64 + kc);
+    }
+  };
+  auto stage_k = [&](int t) {
 #pragma unroll
     for (int i = 0; i < NCH; ++i) {
       const int c = tid + NT * i;
@@ -192,93 +202,184 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, 2)))
       // MFMA row m, which must see key perm_key(m), reads LDS row m: consecutive rows, no
       // bank conflicts
       const int lrow = (row & 32) | perm_key(row & 31);
-      *reinterpret_cast<u32x4*>(&Ks[buf * kKsElems + lrow * kLdK + col]) = kr[i];
-      const int dd = c >> 3, kc = (c & 7) * 8;
-      *reinterpret_cast<u32x4*>(&Vs[buf * kVsElems + dd * kLdV + kc]) = vr[i];
+      *reinterpret_cast<u32x4*>(&Ks[(t & 1) * kKsElems + lrow * kLdK + col]) = kr[i];
     }
   };
-  issue(0);
-  stage(0);
-  __syncthreads();
-
-  for (int t = 0; t < ntile; ++t) {
-    const int k0 = t * 64, buf = t & 1;
-    const bool more = t + 1 < ntile;
-    if (more) issue(t + 1);
-    if (k0 <= wr0 + kWR - 1) {  // otherwise the whole tile is above this wavefront's diagonal
-      const uint16_t* ksb = Ks + buf * kKsElems;
-      const uint16_t* vsb = Vs + buf * kVsElems;
-      f32x16 s[RW][2];
+  auto stage_v = [&](int t) {
 #pragma unroll
-      for (int j = 0; j < RW; ++j)
+    for (int i = 0; i < NCH; ++i) {
+      const int c = tid + NT * i;
+      const int dd = c >> 3, kc = (c & 7) * 8;
+      *reinterpret_cast<u32x4*>(&Vs[(t & 1) * kVsElems + dd * kLdV + kc]) = vr[i];
+    }
+  };
+  // ---- the three stages of a tile, for this wavefront's rows
+  f32x16 s[RW][2];
+  f16x8 pb[RW][2][2];
+  auto active = [&](int t) { return t * 64 <= wr0 + kWR - 1; };  // else the tile is above the diagonal
+  auto qk = [&](int t) {  // S^T = K Q^T of tile t (K from its LDS buffer)
+    const uint16_t* ksb = Ks + (t & 1) * kKsElems;
 #pragma unroll
-        for (int st = 0; st < 2; ++st)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) s[j][st][r] = 0.f;
+    for (int j = 0; j < RW; ++j)
 #pragma unroll
       for (int st = 0; st < 2; ++st)
 #pragma unroll
-        for (int ks = 0; ks < 8; ++ks) {
-          const bf16x8 a = *reinterpret_cast<const bf16x8*>(&ksb[(st * 32 + m) * kLdK + ks * 16 + h * 8]);
+        for (int r = 0; r < 16; ++r) s[j][st][r] = 0.f;
 #pragma unroll
-          for (int j = 0; j < RW; ++j)
-            s[j][st] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bq[j][ks], s[j][st], 0, 0, 0);
-        }
-      // register r of sub-tile st holds key k0 + 32*st + 16*(r/8) + 8*h + r%8
-      f16x8 pb[RW][2][2];
-      const bool diag = k0 + 63 > wr0;
+    for (int st = 0; st < 2; ++st)
 #pragma unroll
-      for (int j = 0; j < RW; ++j) {
-        const int q_row = wr0 + j * 32 + m;
-        if (diag) {
+      for (int ks = 0; ks < 8; ++ks) {
+        const bf16x8 a = *reinterpret_cast<const bf16x8*>(&ksb[(st * 32 + m) * kLdK + ks * 16 + h * 8]);
 #pragma unroll
-          for (int st = 0; st < 2; ++st)
+        for (int j = 0; j < RW; ++j)
+          s[j][st] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, bq[j][ks], s[j][st], 0, 0, 0);
+      }
+  };
+  auto softmax = [&](int t) {  // s -> probabilities pb (fp16, scaled), running maximum and sum, rescale of o
+    const int k0 = t * 64;
+    // register r of sub-tile st holds key k0 + 32*st + 16*(r/8) + 8*h + r%8
+    const bool diag = k0 + 63 > wr0;
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-              const int key = k0 + st * 32 + (r >> 3) * 16 + h * 8 + (r & 7);
-              if (key > q_row) s[j][st][r] = -INFINITY;
-            }
-        }
-        float mx = s[j][0][0];
-#pragma unroll
-        for (int st = 0; st < 2; ++st)
-#pragma unroll
-          for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[j][st][r]);
-        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-        const float mnew = fmaxf(mrun[j], fmaf(mx, scale2, -kPShift));  // exponent reference, 2^12 headroom
-        const bool grew = mnew > mrun[j];
-        const float alpha = __builtin_amdgcn_exp2f(mrun[j] - mnew);
-        mrun[j] = mnew;
-        float psum = 0.f;
+    for (int j = 0; j < RW; ++j) {
+      const int q_row = wr0 + j * 32 + m;
+      if (diag) {
 #pragma unroll
         for (int st = 0; st < 2; ++st)
 #pragma unroll
           for (int r = 0; r < 16; ++r) {
-            const float p = __builtin_amdgcn_exp2f(fmaf(s[j][st][r], scale2, -mnew));
-            psum += p;
-            pb[j][st][r >> 3][r & 7] = (_Float16)p;
+            const int key = k0 + st * 32 + (r >> 3) * 16 + h * 8 + (r & 7);
+            if (key > q_row) s[j][st][r] = -INFINITY;
           }
-        lsum[j] = fmaf(lsum[j], alpha, psum);
-        if (__any(grew)) {  // wavefront-uniform: skip the rescale when no row's maximum moved
-#pragma unroll
-          for (int i = 0; i < 4; ++i)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) o[j][i][r] *= alpha;
-        }
       }
+      float mx = s[j][0][0];
 #pragma unroll
       for (int st = 0; st < 2; ++st)
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
+        for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[j][st][r]);
+      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+      const float mnew = fmaxf(mrun[j], fmaf(mx, scale2, -kPShift));  // exponent reference, 2^12 headroom
+      const bool grew = mnew > mrun[j];
+      const float alpha = __builtin_amdgcn_exp2f(mrun[j] - mnew);
+      mrun[j] = mnew;
+      float psum = 0.f;
 #pragma unroll
-          for (int dc = 0; dc < 4; ++dc) {
-            const f16x8 a = *reinterpret_cast<const f16x8*>(&vsb[(dc * 32 + m) * kLdV + st * 32 + kb * 16 + h * 8]);
+      for (int st = 0; st < 2; ++st)
 #pragma unroll
-            for (int j = 0; j < RW; ++j)
-              o[j][dc] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, pb[j][st][kb], o[j][dc], 0, 0, 0);
-          }
+        for (int r = 0; r < 16; ++r) {
+          const float p = __builtin_amdgcn_exp2f(fmaf(s[j][st][r], scale2, -mnew));
+          psum += p;
+          pb[j][st][r >> 3][r & 7] = (_Float16)p;
+        }
+      lsum[j] = fmaf(lsum[j], alpha, psum);
+      if (__any(grew)) {  // wavefront-uniform: skip the rescale when no row's maximum moved
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) o[j][i][r] *= alpha;
+      }
     }
-    if (more) stage(buf ^ 1);
+  };
+  // o += V^T P^T of tile t, then (WITH_QK) S^T = K Q^T of tile t + 1: 16 + 16 MFMAs whose LDS
+  // operands are fetched two batches of four ahead, so that the matrix core never waits for an
+  // LDS round trip (the compiler, left alone, keeps only two reads in flight).
+  auto mma_operand = [&](int t, int idx) -> u32x4 {
+    if (idx < 16) {  // P V: idx = (st, kb, dc)
+      const int st = idx >> 3, kb = (idx >> 2) & 1, dc = idx & 3;
+      return *reinterpret_cast<const u32x4*>(&Vs[(t & 1) * kVsElems + (dc * 32 + m) * kLdV + st * 32 + kb * 16 + h * 8]);
+    }
+    const int st = (idx - 16) & 1, ks = (idx - 16) >> 1;  // Q K^T of the next tile, the two sub-tiles alternating
+    return *reinterpret_cast<const u32x4*>(&Ks[((t + 1) & 1) * kKsElems + (st * 32 + m) * kLdK + ks * 16 + h * 8]);
+  };
+  auto mma_issue = [&](int idx, const u32x4& a) {
+    if (idx < 16) {
+      const int st = idx >> 3, kb = (idx >> 2) & 1, dc = idx & 3;
+#pragma unroll
+      for (int j = 0; j < RW; ++j)
+        o[j][dc] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a), pb[j][st][kb], o[j][dc], 0, 0, 0);
+    } else {
+      const int st = (idx - 16) & 1, ks = (idx - 16) >> 1;
+#pragma unroll
+      for (int j = 0; j < RW; ++j) {
+        if (ks == 0) {
+          const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+          s[j][st] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), bq[j][ks], zero, 0, 0, 0);
+        } else {
+          s[j][st] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), bq[j][ks], s[j][st], 0, 0, 0);
+        }
+      }
+    }
+  };
+  auto mma_phase = [&](int t, auto with_qk) {
+    constexpr int NB = decltype(with_qk)::value ? 8 : 4;  // batches of four MFMAs
+    u32x4 A[2][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) A[0][i] = mma_operand(t, i);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) A[1][i] = mma_operand(t, 4 + i);
+#pragma unroll
+    for (int bt = 0; bt < NB; ++bt) {
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) mma_issue(4 * bt + i, A[bt & 1][i]);
+      __builtin_amdgcn_sched_barrier(0);
+      if (bt + 2 < NB) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) A[bt & 1][i] = mma_operand(t, 4 * (bt + 2) + i);
+      }
+    }
+  };
+  auto pv_qk = [&](int t, bool with_qk) {
+    if (with_qk)
+      mma_phase(t, std::true_type{});
+    else
+      mma_phase(t, std::false_type{});
+  };
+
+  // ---- ping-pong schedule.  The two wavefronts that share a SIMD (w and w + NW/2) run half a
+  // tile apart: while one forms its probabilities on the vector ALU, the other runs its two
+  // matrix products (P V of the tile, then Q K^T of the next) on the matrix core, and they swap
+  // at a workgroup barrier.  K is staged two tiles ahead, V^T one tile ahead.
+  const bool late = w >= NW / 2;
+  // Pin the arrival of the Q operands here: otherwise the wait for them is placed inside the
+  // loop, behind the tile loads issued there, and stalls the matrix products on those.
+#pragma unroll
+  for (int j = 0; j < RW; ++j)
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) asm volatile("" ::"v"(bq[j][ks]));
+  issue_k(0);
+  issue_v(0);
+  stage_k(0);
+  stage_v(0);
+  if (ntile > 1) {
+    issue_k(1);
+    stage_k(1);
+  }
+  __syncthreads();
+  if (active(0)) {
+    qk(0);
+    if (!late) softmax(0);
+  }
+  __syncthreads();
+  for (int t = 0; t < ntile; ++t) {
+    const bool more = t + 1 < ntile, more2 = t + 2 < ntile;
+    if (more2) issue_k(t + 2);
+    if (more) issue_v(t + 1);
+    if (active(t)) {
+      if (late) {
+        softmax(t);
+      } else {
+        pv_qk(t, more && active(t + 1));
+      }
+    }
+    __syncthreads();
+    if (late) {
+      if (active(t)) pv_qk(t, more && active(t + 1));
+    } else if (more && active(t + 1)) {
+      softmax(t + 1);
+    }
+    // V(t-1) and K(t) were last read before this iteration: their buffers take V(t+1), K(t+2)
+    if (more) stage_v(t + 1);
+    if (more2) stage_k(t + 2);
     __syncthreads();
   }
 #pragma unroll
