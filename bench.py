@@ -127,6 +127,20 @@ def cpu_baseline(w, decode_steps_sample=8):
     }
 
 
+def measured_traffic(cfg: int, kernel: str):
+    """HBM bytes per launch (fetch + write) of a kernel from the committed rocprofv3 counter
+    summary of this configuration, or None when that summary has no complete entry."""
+    path = os.path.join(ROOT, "profiles", f"hbm_traffic_cfg{cfg}.txt")
+    try:
+        for line in open(path):
+            parts = line.split()
+            if len(parts) == 4 and parts[0] == "kernel" and parts[1] == kernel:
+                return float(int(parts[2]) + int(parts[3]))
+    except (OSError, ValueError):
+        pass
+    return None
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -137,6 +151,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--layers", type=int, default=None,
                     help="run only this many layers (profiling aid; the metric needs all)")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="profiling aid: also run three elementwise copies of 1 GiB (reads 1 GiB, "
+                         "writes 1 GiB each), the known traffic that scales the HBM byte counters")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (one GPU's share "
@@ -213,13 +230,23 @@ def main():
         "decode_step_hbm_frac": step_bytes / (decode_ms / dsteps * 1e-3) / 1e9 / PEAK_HBM_GBS,
         "roofline": {"kernel": "attn_fwd (prefill attention pass 1)", "bound": "mfma",
                      "achieved": attn_tflops, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": attn_tflops / PEAK_BF16_TFLOPS, "traffic": None,
+                     "frac": attn_tflops / PEAK_BF16_TFLOPS,
+                     "traffic": measured_traffic(w.cfg, "attn_fwd_bf16"),
+                     "algorithmic_flop_per_launch": flop_per_launch,
                      "avg_launch_ms": attn_ms / attn_n if attn_n else None},
         "roofline_decode": {"kernel": "decode_attend", "bound": "hbm", "achieved": dec_gbs,
                             "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": dec_gbs / PEAK_HBM_GBS,
-                            "traffic": None, "avg_launch_ms": da_ms / da_n if da_n else None},
+                            "traffic": measured_traffic(w.cfg, "decode_attend"),
+                            "algorithmic_bytes_per_launch": bytes_per_launch,
+                            "avg_launch_ms": da_ms / da_n if da_n else None},
         "kernel_ms_per_launch": {k: (v[0] / v[1] if v[1] else None) for k, v in kt.items()},
     }
+    if args.calibrate_copy:
+        src = torch.zeros(1 << 28, dtype=torch.int32, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            torch.add(src, 1, out=dst)
+        torch.cuda.synchronize()
     if not args.no_cpu_baseline:
         print("[bench] timing the CPU oracle on a bounded sample", file=sys.stderr, flush=True)
         out["cpu_baseline"] = cpu_baseline(w)
