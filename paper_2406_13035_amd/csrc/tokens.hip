@@ -194,8 +194,9 @@ __global__ __launch_bounds__(256) void invnorm_bf16(const uint16_t* __restrict__
 }
 
 // Candidate filter on the matrix cores.  A workgroup owns 128 evicted rows (4 wavefronts x 32,
-// the stationary B operand) and streams the retained keys in tiles of 128 through LDS (the A
-// operand), so each lane owns one evicted row and sees 16 retained keys per MFMA tile.
+// the stationary B operand) and streams the retained keys, read contiguously from the cache
+// region they were compacted into, in double-buffered tiles of 64 through LDS (the A operand),
+// so each lane owns one evicted row and sees 16 retained keys per MFMA tile.
 //   COLLECT = false: per row, track the best and second-best fp32 cosine and the best's
 //     retained rank.  A row whose two best values differ by less than kAmbiguous is flagged and
 //     its acceptance threshold (best - kAmbiguous, in the un-normalised domain) is stored.
@@ -211,6 +212,8 @@ constexpr int kLdM = 128 + 8;
 
 template <bool COLLECT>
 __global__ __launch_bounds__(256) void match_filter_bf16(const uint16_t* __restrict__ K, View kv,
+                                                         const uint16_t* __restrict__ cK,
+                                                         const int32_t* __restrict__ meta, int64_t slots,
                                                          const float* __restrict__ invn,
                                                          const int32_t* __restrict__ ret,
                                                          const int32_t* __restrict__ evi,
@@ -219,9 +222,11 @@ __global__ __launch_bounds__(256) void match_filter_bf16(const uint16_t* __restr
                                                          const int32_t* __restrict__ amb_cnt,
                                                          int32_t* __restrict__ ncand, int32_t* __restrict__ clist,
                                                          int npad) {
-  __shared__ __attribute__((aligned(16))) uint16_t Rs[128 * kLdM];
-  __shared__ float rin[128];   // 1/|k| of the staged retained keys
-  __shared__ float rbias[128];  // 0, or -inf for padding rows
+  constexpr int kTile = 64;     // retained keys per LDS tile
+  constexpr int NCH = kTile * 16 / 256;  // 16-byte chunks of a tile per thread
+  __shared__ __attribute__((aligned(16))) uint16_t Rs[2][kTile * kLdM];
+  __shared__ float rin[2][kTile];    // 1/|k| of the staged retained keys
+  __shared__ float rbias[2][kTile];  // 0, or -inf for padding rows
   const int hk = blockIdx.y, b = blockIdx.z, Hkv = gridDim.y;
   const int64_t bh = int64_t(b) * Hkv + hk;
   const int nret = cnt[bh * 2], nevi = cnt[bh * 2 + 1];
@@ -230,6 +235,9 @@ __global__ __launch_bounds__(256) void match_filter_bf16(const uint16_t* __restr
   if (e0 >= nrows) return;
   const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, m = lane & 31, h = lane >> 5;
   const uint16_t* kb = K + b * kv.sb + hk * kv.sh;
+  // the retained keys, in retained order, already sit contiguously in the layer's cache
+  // region (compaction runs first; merging, which changes them, runs after the matching)
+  const uint16_t* rk = cK + (bh * slots + meta[b * 4 + 0]) * 128;
   const int32_t* rl = ret + bh * npad;
   const int32_t* el = evi + bh * npad;
   const float* inl = invn + bh * npad;
@@ -244,48 +252,72 @@ __global__ __launch_bounds__(256) void match_filter_bf16(const uint16_t* __restr
   float m1 = -INFINITY, m2 = -INFINITY;
   int i1 = 0;
   const float mythr = COLLECT ? thr[bh * npad + erank] : 0.f;
-  for (int r0 = 0; r0 < nret; r0 += 128) {
-    __syncthreads();
-    for (int c = tid; c < 128 * 16; c += 256) {
-      const int rrow = c >> 4, col = (c & 15) * 8;
-      const int pos = rl[min(r0 + rrow, nret - 1)];
-      *reinterpret_cast<u32x4*>(&Rs[rrow * kLdM + col]) =
-          *reinterpret_cast<const u32x4*>(kb + int64_t(pos) * kv.sn + col);
+  // Tiles travel global -> registers -> LDS; two register sets keep two tiles in flight.
+  u32x4 rgA[NCH], rgB[NCH];
+  float rvA = 0.f, rvB = 0.f;
+  const int ntile = (nret + kTile - 1) / kTile;
+  auto issue = [&](int t, u32x4 (&rg)[NCH], float& rv) {
+    const int r0 = t * kTile;
+#pragma unroll
+    for (int i = 0; i < NCH; ++i) {
+      const int c = tid + 256 * i, rrow = c >> 4, col = (c & 15) * 8;
+      rg[i] = *reinterpret_cast<const u32x4*>(rk + int64_t(min(r0 + rrow, nret - 1)) * 128 + col);
     }
-    if (tid < 128) {
-      const bool ok = r0 + tid < nret;
-      rin[tid] = ok ? inl[rl[r0 + tid]] : 0.f;
-      rbias[tid] = ok ? 0.f : -INFINITY;
+    if (tid < kTile) rv = (r0 + tid < nret) ? inl[rl[r0 + tid]] : -1.f;  // -1 marks a padding row
+  };
+  auto stage = [&](int buf, const u32x4 (&rg)[NCH], float rv) {
+#pragma unroll
+    for (int i = 0; i < NCH; ++i) {
+      const int c = tid + 256 * i, rrow = c >> 4, col = (c & 15) * 8;
+      *reinterpret_cast<u32x4*>(&Rs[buf][rrow * kLdM + col]) = rg[i];
     }
-    __syncthreads();
-    const int nsub = min(4, (nret - r0 + 31) / 32);
+    if (tid < kTile) {
+      rin[buf][tid] = rv < 0.f ? 0.f : rv;
+      rbias[buf][tid] = rv < 0.f ? -INFINITY : 0.f;
+    }
+  };
+  auto one_tile = [&](int t, u32x4 (&far)[NCH], float& vfar, const u32x4 (&next)[NCH], const float& vnext) {
+    const int buf = t & 1, r0 = t * kTile;
+    if (t + 2 < ntile) issue(t + 2, far, vfar);
+    const int nsub = min(kTile / 32, (nret - r0 + 31) / 32);
     for (int st = 0; st < nsub; ++st) {
+      bf16x8 a[8];
+#pragma unroll
+      for (int ks = 0; ks < 8; ++ks)
+        a[ks] = *reinterpret_cast<const bf16x8*>(&Rs[buf][(st * 32 + m) * kLdM + ks * 16 + h * 8]);
       f32x16 s;
 #pragma unroll
       for (int r = 0; r < 16; ++r) s[r] = 0.f;
 #pragma unroll
-      for (int ks = 0; ks < 8; ++ks) {
-        const bf16x8 a = *reinterpret_cast<const bf16x8*>(&Rs[(st * 32 + m) * kLdM + ks * 16 + h * 8]);
-        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, be[ks], s, 0, 0, 0);
-      }
-      // register r: retained row st*32 + (r/4)*8 + 4h + r%4 of this stage, evicted row = lane's
+      for (int ks = 0; ks < 8; ++ks) s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks], be[ks], s, 0, 0, 0);
+      // register r: retained row st*32 + (r/4)*8 + 4h + r%4 of this tile, evicted row = lane's
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int rr = st * 32 + (r >> 2) * 8 + h * 4 + (r & 3);
-        const float t = fmaf(s[r], rin[rr], rbias[rr]);
+        const float tval = fmaf(s[r], rin[buf][rr], rbias[buf][rr]);
         if (COLLECT) {
-          if (live && t >= mythr) {
+          if (live && tval >= mythr) {
             const int k = atomicAdd(&ncand[bh * npad + erank], 1);
             if (k < kMaxCand) clist[(bh * npad + erank) * kMaxCand + k] = r0 + rr;
           }
         } else {
-          const bool gt = t > m1;
+          const bool gt = tval > m1;
           i1 = gt ? (r0 + rr) : i1;
-          m2 = __builtin_amdgcn_fmed3f(m1, m2, t);
-          m1 = fmaxf(m1, t);
+          m2 = __builtin_amdgcn_fmed3f(m1, m2, tval);
+          m1 = fmaxf(m1, tval);
         }
       }
     }
+    if (t + 1 < ntile) stage(buf ^ 1, next, vnext);
+    __syncthreads();
+  };
+  issue(0, rgA, rvA);
+  stage(0, rgA, rvA);
+  if (ntile > 1) issue(1, rgB, rvB);
+  __syncthreads();
+  for (int t = 0; t < ntile; t += 2) {
+    one_tile(t, rgA, rvA, rgB, rvB);
+    if (t + 1 < ntile) one_tile(t + 1, rgB, rvB, rgA, rvA);
   }
   if (COLLECT) return;
   // combine the two lane halves that share an evicted row
@@ -669,12 +701,16 @@ hipError_t launch_match(d2o_ctx* c, int layer, View K, int n, hipStream_t s) {
                                                                              c->npad);
     {
       KernelTimer kt(c, D2O_K_MATCH_FILTER, s);
-      match_filter_bf16<false><<<gf, 256, 0, s>>>((const uint16_t*)K.ptr, K, c->invnorm, c->sel_ret, c->sel_evi,
+      match_filter_bf16<false><<<gf, 256, 0, s>>>((const uint16_t*)K.ptr, K, (const uint16_t*)c->cacheK,
+                                                  c->meta + size_t(layer) * cf.batch * 4, cf.slots_per_seq,
+                                                  c->invnorm, c->sel_ret, c->sel_evi,
                                                   c->sel_cnt, c->m_cand, c->m_thr, c->amb_list, c->amb_cnt,
                                                   c->m_ncand, c->m_clist, c->npad);
       amb_compact_kernel<<<dim3(cf.n_kv_heads, cf.batch), 1024, 0, s>>>(c->m_cand, c->sel_cnt, c->amb_list,
                                                                         c->amb_cnt, c->m_ncand, c->npad);
-      match_filter_bf16<true><<<gf, 256, 0, s>>>((const uint16_t*)K.ptr, K, c->invnorm, c->sel_ret, c->sel_evi,
+      match_filter_bf16<true><<<gf, 256, 0, s>>>((const uint16_t*)K.ptr, K, (const uint16_t*)c->cacheK,
+                                                 c->meta + size_t(layer) * cf.batch * 4, cf.slots_per_seq,
+                                                 c->invnorm, c->sel_ret, c->sel_evi,
                                                  c->sel_cnt, c->m_cand, c->m_thr, c->amb_list, c->amb_cnt,
                                                  c->m_ncand, c->m_clist, c->npad);
     }
