@@ -205,7 +205,7 @@ def _run_decode_parity(w, n, B, layer, budget, recent, sink, steps, tau_force=fl
 
 
 @pytest.mark.parametrize("case", ["cfg1", "bf16-mha", "bf16-gqa-ragged-budgets", "bf16-grow",
-                                  "bf16-no-window", "bf16-never-merge"])
+                                  "bf16-no-window", "bf16-never-merge", "bf16-long"])
 def test_decode_from_oracle_state(case):
     print(f"case={case}", flush=True)
     if case == "cfg1":
@@ -218,8 +218,64 @@ def test_decode_from_oracle_state(case):
         _run_decode_parity(_small_bf16(True), 60, 1, 3, 66, 16, 0, 14)
     elif case == "bf16-no-window":  # M = 0: the new token itself may be evicted
         _run_decode_parity(_small_bf16(False), 300, 1, 31, 40, 0, 0, 12)
+    elif case == "bf16-long":      # many steps: the eviction candidates are carried from step to step
+        _run_decode_parity(_small_bf16(True), 400, 2, 17, [90, 130], [20, 30], 1, 96)
     else:
         _run_decode_parity(_small_bf16(False), 500, 1, 12, 100, 25, 0, 10, tau_force=float("inf"))
+
+
+def test_decode_evicted_token_outside_the_predicted_candidates():
+    """The library predicts the next evicted token (the lowest scores after a step) to compute
+    its similarities during the attention pass; when the prediction misses, a second pass must
+    give the same result.  State: three tokens with the lowest scores share one key u, a
+    fourth, slightly higher, has another key.  Step 1 evicts nothing special; the query of step
+    2 is a multiple of u, so the three predicted tokens receive almost all the attention and
+    the fourth becomes the lowest: it is evicted although it was not predicted."""
+    w = _small_bf16(False).scaled(n_q_heads=1, n_kv_heads=1)
+    d, n0, budget, recent = w.head_dim, 60, 40, 4
+    g = torch.Generator().manual_seed(11)
+    K = torch.randn(budget, d, generator=g).to(torch.bfloat16)
+    V = torch.randn(budget, d, generator=g).to(torch.bfloat16)
+    u = (3.0 * torch.randn(d, generator=g)).to(torch.bfloat16)
+    K[1] = u
+    K[2] = u
+    K[3] = u
+    K[4] = u
+    V[2] = V[1]                                           # equal values too: the mean of two different
+    V[3] = V[1]                                           # bf16 numbers can sit exactly on a rounding tie
+    V[4] = V[1]
+    score = 1.0 + torch.rand(budget, generator=g).double().numpy()
+    score[:6] = [0.05, 0.10, 0.11, 0.12, 0.13, 0.14]     # slot 0 goes first; 1-3 are then predicted; 5 has another key
+    pos = np.arange(budget, dtype=np.int32)               # prompt positions 0..39 of a 60-token prompt's survivors
+    ctx = H.new_ctx(w, 1, 1, n0, budget + 8, beta=0.7)
+    ctx.d2o_layer_reserve(0, n0, budget, recent)
+    Kd, Vd = binding.tensor_to_f64(K), binding.tensor_to_f64(V)
+    ctx.d2o_cache_import(0, 0, 0, Kd, Vd, score, pos, 0.5, n0)
+    cache = ref.HeadCache(Kd.copy(), Vd.copy(), score.copy(), pos.astype(np.int64), 0.5, "bf16")
+    steps = 4
+    q = (0.05 * torch.randn(steps, 1, 1, 1, d, generator=g)).to(torch.bfloat16)
+    q[1, 0, 0, 0] = (4.0 * u.float()).to(torch.bfloat16)
+    k = torch.randn(steps, 1, 1, 1, d, generator=g).to(torch.bfloat16)
+    v = torch.randn(steps, 1, 1, 1, d, generator=g).to(torch.bfloat16)
+    qg, kg, vg = q.cuda(), k.cuda(), v.cuda()
+    out = torch.empty(qg[0].shape, dtype=ctx.out_dtype, device="cuda")
+    evicted = []
+    for t in range(steps):
+        ctx.d2o_decode_step(0, 1, qg[t], kg[t], vg[t], out)
+        torch.cuda.synchronize()
+        ev, tg, us = ctx.d2o_last_events(0)
+        want, e = ref.decode_step_head(cache, binding.tensor_to_f64(q[t, 0, 0]), binding.tensor_to_f64(k[t, 0, 0, 0]),
+                                       binding.tensor_to_f64(v[t, 0, 0, 0]), n0 + t, budget, recent, 0, 0.7)
+        assert (ev[0, 0], tg[0, 0]) == (e.evicted_pos, e.target_pos), f"step {t}"
+        assert abs(us[0, 0] - e.u_star) < 1e-13
+        assert H.rownorm_err(binding.tensor_to_f64(out)[0, 0], want) <= H.FLOAT_TOL
+        evicted.append(e.evicted_pos)
+    assert evicted[0] == 0 and evicted[1] == 5, evicted   # the scenario really took the unpredicted token
+    gK, gV, gs, gp, gtau = ctx.d2o_cache_export(0, 0, 0, budget + 1)
+    assert np.array_equal(gp, cache.pos) and np.array_equal(gK, cache.K) and np.array_equal(gV, cache.V)
+    np.testing.assert_allclose(gs, cache.score, rtol=1e-12)
+    assert abs(gtau - cache.tau) < 1e-13
+    ctx.close()
 
 
 # ------------------------------------------------------------------ whole path, free running
