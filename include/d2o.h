@@ -201,8 +201,7 @@ typedef enum {
   D2O_K_MERGE = 5,
   D2O_K_DECODE_ATTEND = 6,  /* attention over the cache + score update + evict/merge         */
   D2O_K_DECODE_PREPARE = 7, /* append of the new token, operand set-up                      */
-  D2O_K_DECODE_FALLBACK = 8, /* second similarity pass for heads that need it (else exits)  */
-  D2O_K_COUNT = 9
+  D2O_K_COUNT = 8
 } d2o_kernel_id;
 int d2o_timing_enable(d2o_ctx* ctx, int32_t on);
 int d2o_timing_read(d2o_ctx* ctx, int32_t kernel_id, double* total_ms, int64_t* launches,

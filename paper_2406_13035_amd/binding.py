@@ -288,7 +288,7 @@ class D2O:
 
 
 KERNEL_IDS = {"attn_fwd": 0, "colsum": 1, "select": 2, "match_filter": 3, "match_refine": 4,
-              "merge": 5, "decode_attend": 6, "decode_prepare": 7, "decode_fallback": 8}
+              "merge": 5, "decode_attend": 6, "decode_prepare": 7}
 
 
 # ---- element conversions for host-side export / import (bit moves, no arithmetic) ----------

@@ -102,15 +102,11 @@ void layout(d2o_ctx* x, char* persistent, char* scratch, size_t* pbytes, size_t*
   s.take(x->g_src, bh * np);
   s.take(x->d_logit, B * Hq * slots);
   const size_t nsub = nch * 4;  // partial results are kept per 64 slots, a quarter of a chunk
-  s.take(x->d_pm, bh * nsub * G);
-  s.take(x->d_pf, bh * nsub * G);
-  s.take(x->d_pl, bh * nsub * G);
+  s.take(x->d_rec, bh * nsub * 32);
   s.take(x->d_pacc, bh * nsub * G * d);
   s.take(x->d_vecs, L * bh * (G + nc) * d);
   s.take(x->d_cnorm, L * bh * nc);
-  s.take(x->d_eslot, L * bh);
-  s.take(x->d_cu, bh * nsub * nc);
-  s.take(x->d_cslot, bh * nsub * nc);
+
   *sbytes = (s.off + 255) & ~size_t(255);
 }
 

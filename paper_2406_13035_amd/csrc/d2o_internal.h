@@ -103,15 +103,10 @@ struct d2o_ctx {
   int32_t* g_src = nullptr;      // evicted ranks grouped by target (unordered inside a group)
   // decode
   double* d_logit = nullptr;     // [B][Hq][slots]        exp(logit - chunk max)
-  double* d_pm = nullptr;        // [B][Hkv][4 nchunk][G]   maxima per 64 slots
-  double* d_pf = nullptr;        // [B][Hkv][4 nchunk][G]   rescale factors
-  double* d_pl = nullptr;        // [B][Hkv][4 nchunk][G]   exp-sums (relative to the maximum)
+  double* d_rec = nullptr;       // [B][Hkv][4 nchunk][32] per 64 slots: softmax maxima and sums, candidates' best cosine and slot
   float* d_pacc = nullptr;       // [B][Hkv][4 nchunk][G][d] partial outputs
   double* d_vecs = nullptr;      // [L][B][Hkv][G + candidates][d] queries and candidate keys, fp64
   double* d_cnorm = nullptr;     // [L][B][Hkv][candidates] norms of the candidate keys
-  int32_t* d_eslot = nullptr;    // [L][B][Hkv] evicted slot awaiting the fallback pass (-1 none)
-  double* d_cu = nullptr;        // [B][Hkv][4 nchunk][candidates] best cosine
-  int32_t* d_cslot = nullptr;    // [B][Hkv][4 nchunk][candidates] its slot
 };
 
 namespace d2o {

@@ -14,20 +14,17 @@
 //                   statistics of the 64 rows, the candidates' best cosine among them (Eq. 9),
 //                   and the partial P V in fp32.
 //                   The last workgroup of a head to finish (a ticket counter, no waiting)
-//                   combines the partial results: output rows, exact fp64 normaliser, score
-//                   update (Eq. 6, generation case), the token to evict (Eq. 7-8: lowest score
-//                   outside sinks and the recent window; equal scores evict the later
-//                   position) and the candidates of the next step (the lowest scores that
-//                   remain).  When the evicted token is one of this step's candidates, which
-//                   is the normal case, its similarities are already there and the same
-//                   workgroup finishes the step: arg-max (ties: earlier position), EMA
-//                   threshold (Eq. 10, update first, then test), merge or discard (Eq. 11-12
-//                   with one source), and the last slot moves into the freed one.
-//   decode_fallback for heads whose evicted token was not among the candidates (the first step
-//                   after prompt encoding, or a candidate overtaken by a token outside the
-//                   list): one workgroup per such head makes a second pass over the head's
-//                   keys and runs the same finishing code.  It exits at once for every other
-//                   head.
+//                   closes the head: output rows, exact fp64 normaliser, score update (Eq. 6,
+//                   generation case), the token to evict (Eq. 7-8: lowest score outside sinks
+//                   and the recent window; equal scores evict the later position) and the
+//                   candidates of the next step (the lowest scores that remain).  When the
+//                   evicted token is one of this step's candidates, which is the normal case,
+//                   its similarities are already there; otherwise (the first step after prompt
+//                   encoding, or a candidate overtaken by a token outside the list) the same
+//                   workgroup makes a second pass over the head's keys.  Then: arg-max (ties:
+//                   earlier position), EMA threshold (Eq. 10, update first, then test), merge
+//                   or discard (Eq. 11-12 with one source), and the last slot moves into the
+//                   freed one.
 //
 // All decision-bearing arithmetic - logits, softmax normaliser, score accumulation, eviction
 // arg-min, cosine arg-max, EMA threshold, merge - is fp64 in the operation order of the
@@ -43,6 +40,8 @@ namespace {
 
 constexpr int kCand = 3;                // eviction candidates whose similarities ride along with the attention pass
 constexpr int kMaxLayersPerCall = 64;
+constexpr int kRec = 32;                // doubles per sub-chunk record
+static_assert(kCand <= 4, "record layout holds four candidates");
 constexpr int kPiece = 128;             // bytes of a cache row staged per LDS round
 constexpr int kPitch = kPiece + 16;     // LDS pitch of a staged row piece: conflict-free b128 reads
 constexpr int kStageBytes = 4 * 64 * kPitch;
@@ -60,15 +59,12 @@ struct DecodeArgs {
   int32_t* cand;      // [L][B][Hkv][kCand] candidate slots for this step, -1 = none
   uint32_t* ticket;   // [L][B][Hkv] finished chunks of the running step
   double* elog;       // [B][Hq][slots] exp(logit - sub-chunk max)
-  double* pm;         // [B][Hkv][nsub][G] sub-chunk maxima
-  double* pf;         // [B][Hkv][nsub][G] rescale factors exp(sub-chunk max - head max)
-  double* pl;         // [B][Hkv][nsub][G] exp-sums relative to the sub-chunk maximum
+  double* rec;        // [B][Hkv][nsub][kRec] per sub-chunk record: [0..8) softmax maxima of the G
+                      // heads, [8..16) exp-sums relative to them, [16..16+kCand) the candidates' best
+                      // cosine, [20..20+kCand) its slot (-1 none); one 256-byte line, written at once
   float* pacc;        // [B][Hkv][nsub][G][d] partial outputs
   double* vecs;       // [L][B][Hkv][G + kCand][d] queries and candidate keys as fp64
   double* cnorm;      // [L][B][Hkv][kCand] |k| of the candidates
-  double* cu;         // [B][Hkv][nsub][kCand] best cosine per candidate
-  int32_t* cslot;     // [B][Hkv][nchunk][kCand] its slot (-1 none)
-  int32_t* eslot;     // [L][B][Hkv] slot awaiting the fallback pass (-1 none)
   int32_t* ev_evicted;
   int32_t* ev_target;
   double* ev_ustar;
@@ -152,14 +148,22 @@ __device__ __forceinline__ U ld_agent(const U* p) {
   return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
+__device__ __forceinline__ float4 ld_agent4(const float* p) {  // 16 bytes as two 8-byte loads
+  const uint64_t lo = ld_agent(reinterpret_cast<const uint64_t*>(p));
+  const uint64_t hi = ld_agent(reinterpret_cast<const uint64_t*>(p) + 1);
+  return make_float4(__uint_as_float(uint32_t(lo)), __uint_as_float(uint32_t(lo >> 32)),
+                     __uint_as_float(uint32_t(hi)), __uint_as_float(uint32_t(hi >> 32)));
+}
+
 // Which entry of the call's layer list a flat chunk index belongs to (block-uniform).  The
-// list is sorted by size, so the workgroups dispatched last belong to the smallest caches,
-// whose closing work is the shortest.
+// list is sorted by size, so the workgroups dispatched last belong to the smallest caches.
+// Unused entries of lay_off hold INT_MAX, so the search is a fixed chain of scalar compares on
+// kernel arguments: no memory round trip precedes the loads that depend on the layer.
 __device__ __forceinline__ int find_entry(const DecodeArgs& a, int x) {
-  // one lane per list entry (at most 64): the entry is the last one that starts at or before x
-  const int lane = threadIdx.x & 63;
-  const int start = lane < a.nl ? a.lay_off[lane] : 0x7FFFFFFF;
-  return __popcll(__ballot(start <= x)) - 1;
+  int entry = 0;
+#pragma unroll
+  for (int i = 1; i < kMaxLayersPerCall; ++i) entry += x >= a.lay_off[i] ? 1 : 0;
+  return entry;
 }
 
 // (u larger, then position smaller) wins; slot < 0 means "no entry".
@@ -170,17 +174,8 @@ struct Best {
 __device__ __forceinline__ bool better_match(double u, int p, int s, const Best& b) {
   return s >= 0 && (b.slot < 0 || u > b.u || (u == b.u && p < b.pos));
 }
-__device__ __forceinline__ Best wave_best_match(Best b) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) {
-    const double ou = __shfl_xor(b.u, o, 64);
-    const int op = __shfl_xor(b.pos, o, 64), os = __shfl_xor(b.slot, o, 64);
-    if (better_match(ou, op, os, b)) b = Best{ou, op, os};
-  }
-  return b;
-}
-// The same arg-max for one entry per lane whose positions are all different and whose u is
-// never below -1 (a cosine): largest u, then smallest position, then that lane's slot.
+// Wavefront arg-max of that order for one entry per lane whose positions are all different and
+// whose u is never below -1 (a cosine): largest u, then smallest position, then that lane's slot.
 __device__ __forceinline__ Best fast_wave_best_match(double u, int pos, int slot) {
   const bool live = slot >= 0;
   const double umax = fast_wave_max(live ? u : -INFINITY);
@@ -195,16 +190,17 @@ __device__ __forceinline__ Best fast_wave_best_match(double u, int pos, int slot
 __device__ __forceinline__ bool evicts_before(double s, int p, int sl, const Best& b) {
   return sl >= 0 && (b.slot < 0 || s < b.u || (s == b.u && p > b.pos));
 }
-__device__ __forceinline__ Best wave_first_evicted(Best b) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) {
-    const double ou = __shfl_xor(b.u, o, 64);
-    const int op = __shfl_xor(b.pos, o, 64), os = __shfl_xor(b.slot, o, 64);
-    if (evicts_before(ou, op, os, b)) b = Best{ou, op, os};
-  }
-  return b;
+// Wavefront-wide first of that order, for one entry per lane whose positions are all different.
+__device__ __forceinline__ Best fast_wave_first_evicted(const Best& b) {
+  const bool live = b.slot >= 0;
+  const double smin = -fast_wave_max(live ? -b.u : -INFINITY);
+  const bool top = live && b.u == smin;
+  const int pmax = -fast_wave_min(top ? -b.pos : 0x7FFFFFFF);
+  const unsigned long long who = __ballot(top && b.pos == pmax);
+  if (who == 0ull) return Best{0.0, 0, -1};
+  const int src = __ffsll((long long)who) - 1;
+  return Best{smin, pmax, __builtin_amdgcn_readlane(b.slot, src)};
 }
-
 template <typename T, typename OT, int D, int G>
 __global__ __launch_bounds__(128) void decode_prepare(DecodeArgs a, const T* __restrict__ q, View qv,
                                                       const T* __restrict__ kn, View kv, const T* __restrict__ vn,
@@ -241,140 +237,219 @@ __global__ __launch_bounds__(128) void decode_prepare(DecodeArgs a, const T* __r
 
 // Eq. 9 arg-max result -> Eq. 10 threshold, Eq. 11-12 merge with one source, slot bookkeeping.
 // Called by every thread of a workgroup (at least D threads) with block-uniform arguments.
+// told: the head's threshold before the step; (kl, vl): this thread's element of the last slot's
+// row as it was before the step; (sl, pl): that slot's updated score and its position.
 template <typename T, int D>
 __device__ __forceinline__ void finish_head(const DecodeArgs& a, int64_t lbh, int64_t slot0, int es, int total,
-                                            double best, int bp, int bs) {
+                                            double best, int bp, int bs, double told, T kl, T vl, double sl,
+                                            int pl) {
   T* Kc = static_cast<T*>(a.cK) + slot0 * D;
   T* Vc = static_cast<T*>(a.cV) + slot0 * D;
   const int tid = threadIdx.x, last = total - 1;
   bool do_merge;
   if (isnan(a.tau_force)) {
-    const double told = a.ctau[lbh];
     const double tnew = isnan(told) ? best : __dadd_rn(__dmul_rn(a.beta, best), __dmul_rn(1.0 - a.beta, told));
     do_merge = best >= tnew;
-    __syncthreads();  // every thread has read the old threshold
     if (tid == 0) a.ctau[lbh] = tnew;
   } else {
     do_merge = best >= a.tau_force;
   }
   if (tid == 0) {
-    a.ev_evicted[lbh] = a.cpos[slot0 + es];
+    a.ev_evicted[lbh] = es == last ? pl : a.cpos[slot0 + es];
     a.ev_target[lbh] = do_merge ? bp : -1;
     a.ev_ustar[lbh] = best;
     a.ccount[lbh] = last;
   }
-  if (do_merge && tid < D) {
-    const double e1 = 2.718281828459045;  // exp(1), the retained token's self-similarity weight
-    const double w = exp(best);
-    const double z = __dadd_rn(e1, w);
-    const double kk = __dadd_rn(__dmul_rn(e1, Elem<T>::to_f64(Kc[int64_t(bs) * D + tid])),
-                                __dmul_rn(w, Elem<T>::to_f64(Kc[int64_t(es) * D + tid])));
-    const double vv = __dadd_rn(__dmul_rn(e1, Elem<T>::to_f64(Vc[int64_t(bs) * D + tid])),
-                                __dmul_rn(w, Elem<T>::to_f64(Vc[int64_t(es) * D + tid])));
-    Kc[int64_t(bs) * D + tid] = Elem<T>::from_f64(kk / z);
-    Vc[int64_t(bs) * D + tid] = Elem<T>::from_f64(vv / z);
+  if (tid < D) {
+    if (do_merge) {
+      const double e1 = 2.718281828459045;  // exp(1), the retained token's self-similarity weight
+      const double w = exp(best);
+      const double z = __dadd_rn(e1, w);
+      const T ke = es == last ? kl : Kc[int64_t(es) * D + tid], ve = es == last ? vl : Vc[int64_t(es) * D + tid];
+      const T kt = bs == last ? kl : Kc[int64_t(bs) * D + tid], vt = bs == last ? vl : Vc[int64_t(bs) * D + tid];
+      const double kk = __dadd_rn(__dmul_rn(e1, Elem<T>::to_f64(kt)), __dmul_rn(w, Elem<T>::to_f64(ke)));
+      const double vv = __dadd_rn(__dmul_rn(e1, Elem<T>::to_f64(vt)), __dmul_rn(w, Elem<T>::to_f64(ve)));
+      const T km = Elem<T>::from_f64(kk / z), vm = Elem<T>::from_f64(vv / z);
+      if (bs == last) {  // the merged row is the one that moves into the hole
+        kl = km;
+        vl = vm;
+      } else {
+        Kc[int64_t(bs) * D + tid] = km;
+        Vc[int64_t(bs) * D + tid] = vm;
+      }
+    }
+    if (es != last) {  // the last slot fills the hole
+      Kc[int64_t(es) * D + tid] = kl;
+      Vc[int64_t(es) * D + tid] = vl;
+    }
   }
-  __syncthreads();  // the merge has read the evicted row (and tid 0 its position)
-  if (es != last) {  // the last slot fills the hole
-    if (tid < D) {
-      Kc[int64_t(es) * D + tid] = Kc[int64_t(last) * D + tid];
-      Vc[int64_t(es) * D + tid] = Vc[int64_t(last) * D + tid];
-    }
-    if (tid == 0) {
-      a.cscore[slot0 + es] = a.cscore[slot0 + last];
-      a.cpos[slot0 + es] = a.cpos[slot0 + last];
-    }
+  if (es != last && tid == 0) {
+    a.cscore[slot0 + es] = sl;
+    a.cpos[slot0 + es] = pl;
   }
 }
 
-// Work of the last workgroup of a head: combine the chunks, update the scores, choose the
-// evicted token and the next candidates, and finish the step when possible.
+// Cosine of the evicted key against every other row of the head (Eq. 9) by the whole workgroup;
+// returns the arg-max per wavefront-reduced lane (the caller reduces over the wavefronts).
+// ke: D doubles of shared memory, red: 4 doubles.
+template <typename T, int D>
+__device__ __forceinline__ Best scan_matches(const DecodeArgs& a, int64_t slot0, int es, int total, double* ke,
+                                             double* red) {
+  constexpr int kVec = 16 / sizeof(T);
+  constexpr int TPR = D / kVec;
+  constexpr int RPP = 256 / TPR;
+  const int tid = threadIdx.x;
+  const T* Kc = static_cast<const T*>(a.cK) + slot0 * D;
+  double part = 0.0;
+  __syncthreads();
+  if (tid < D) {
+    const double x = Elem<T>::to_f64(Kc[int64_t(es) * D + tid]);
+    ke[tid] = x;
+    part = x * x;
+  }
+  const double sne = sqrt(block_sum(part, red));
+  const int tr = tid / TPR, tc = (tid % TPR) * kVec;
+  Best m{0.0, 0, -1};
+  for (int r0 = 0; r0 < total; r0 += RPP) {
+    const int j = r0 + tr;
+    double dot = 0.0, nr = 0.0;
+    if (j < total) {
+      double x[kVec];
+      cvt16<T>(*reinterpret_cast<const u32x4*>(Kc + int64_t(j) * D + tc), x);
+#pragma unroll
+      for (int e = 0; e < kVec; ++e) {
+        dot = fma(x[e], ke[tc + e], dot);
+        nr = fma(x[e], x[e], nr);
+      }
+    }
+#pragma unroll
+    for (int o = TPR / 2; o > 0; o >>= 1) {
+      dot += __shfl_xor(dot, o, 64);
+      nr += __shfl_xor(nr, o, 64);
+    }
+    if (j < total && j != es && (tid % TPR) == 0) {
+      const double den = sne * sqrt(nr);
+      const double u = den > 0.0 ? dot / den : 0.0;
+      const int p = a.cpos[slot0 + j];
+      if (better_match(u, p, j, m)) m = Best{u, p, j};
+    }
+  }
+  return m;
+}
+
+// Closing work of a head, by one workgroup of 256 threads: combine the sub-chunks, update the
+// scores, choose the evicted token and the next candidates, find the merge target and finish the
+// step.  Every load whose address does not depend on a result of this function is issued before
+// the first of the workgroup-wide reductions, so the function costs a few memory round trips.
 template <typename T, typename OT, int D, int G>
 __device__ __forceinline__ void head_tail(const DecodeArgs& a, OT* __restrict__ out, const View& ov, int li, int b,
                                           int hk, int64_t lbh, int total, int nsub, double* sred, int* ired,
-                                          float* fred) {
+                                          float* fred, double* dred, unsigned char* park) {
+  constexpr int U = G >= 4 ? 1 : 4 / G;               // slots per thread and batch of the score pass
+  constexpr int C4 = D / 4;                           // threads across an output row (four columns each)
+  constexpr int RG = 256 / C4;                        // groups of threads that share the sub-chunks
+  constexpr int PB = 4;                               // partial rows in flight per thread
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
-  const int l = a.layer0 + li;
+  const int l = a.layer0 + li, last = total - 1;
   const int32_t* mt = a.meta + (l * a.B + b) * 4;
   const int64_t bh = int64_t(b) * a.Hkv + hk;
   const int64_t slot0 = bh * a.slots + mt[0];
-  const int64_t pbase = (bh * a.nsub_cap + int64_t(mt[3]) * (kChunk / kSub)) * G;
-  // pf and fred live in LDS space the chunk phase no longer needs
-  double Lg[G];
+  const int64_t sbase = bh * a.nsub_cap + int64_t(mt[3]) * (kChunk / kSub);
+  const int64_t pbase = sbase * G;
+  const T* Kc = static_cast<const T*>(a.cK) + slot0 * D;
+  const T* Vc = static_cast<const T*>(a.cV) + slot0 * D;
+  const double* elog = a.elog + (int64_t(b) * a.Hkv * G + hk * G) * a.slots + mt[0];
+  // ---- loads that depend on nothing: the threshold, this step's candidates, the last slot's row
+  const double told = a.ctau[lbh];
+  int cl[kCand];
+#pragma unroll
+  for (int i = 0; i < kCand; ++i) cl[i] = a.cand[lbh * kCand + i];
+  // Results that are needed only at the end wait in LDS, not in registers (`park`: 16 bytes per
+  // candidate and thread, then two elements per thread).
+  double* park_u = reinterpret_cast<double*>(park);
+  int2* park_ps = reinterpret_cast<int2*>(park + kCand * 256 * sizeof(double));
+  T* park_kv = reinterpret_cast<T*>(park + kCand * 256 * (sizeof(double) + sizeof(int2)));
+  if (tid < D) {
+    park_kv[tid] = Kc[int64_t(last) * D + tid];
+    park_kv[256 + tid] = Vc[int64_t(last) * D + tid];
+  }
+  // ---- head maximum and exact normaliser sum_j exp(s_j - max) of each query head (fixed tree)
+  double Mg[G], Lg[G];
 #pragma unroll
   for (int g = 0; g < G; ++g) {
     double mx = -INFINITY;
-    for (int c = tid; c < nsub; c += 256) mx = fmax(mx, ld_agent(&a.pm[pbase + int64_t(c) * G + g]));
+    for (int c = tid; c < nsub; c += 256) mx = fmax(mx, ld_agent(&a.rec[(sbase + c) * kRec + g]));
     mx = wave_max(mx);
     __syncthreads();
     if (lane == 0) sred[w] = mx;
     __syncthreads();
     mx = fmax(fmax(sred[0], sred[1]), fmax(sred[2], sred[3]));
     double part = 0.0;
-    for (int c = tid; c < nsub; c += 256) {
-      const int64_t pi = pbase + int64_t(c) * G + g;
-      const double m = ld_agent(&a.pm[pi]), pl = ld_agent(&a.pl[pi]);
-      const double f = exp(m - mx);
-      a.pf[pi] = f;  // the chunk's rescale factor (read back by this workgroup only)
-      part += pl * f;
-    }
-    Lg[g] = block_sum(part, sred);  // exact normaliser sum_j exp(s_j - max), fixed summation tree
-    // output row of query head g: NPART groups of threads take every NPART-th chunk, four
-    // loads in flight each, and the groups' sums are added in ascending order
-    constexpr int NPART = 256 / D;
-    const int dcol = tid % D, part_id = tid / D;
-    float num = 0.f;
-    for (int c0 = part_id; c0 < nsub; c0 += 4 * NPART) {
-      float v[4], f[4];
+    for (int c = tid; c < nsub; c += 256)
+      part += ld_agent(&a.rec[(sbase + c) * kRec + 8 + g]) * exp(ld_agent(&a.rec[(sbase + c) * kRec + g]) - mx);
+    Mg[g] = mx;
+    Lg[g] = block_sum(part, sred);
+  }
+  // ---- Eq. 9 arg-max over the sub-chunks' results, for every candidate of this step (which of
+  //      them is evicted is not known yet; ties: earlier position)
+  Best cm[kCand];
 #pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        const int c = c0 + u * NPART;
-        const int64_t pi = pbase + int64_t(min(c, nsub - 1)) * G + g;
-        v[u] = ld_agent(&a.pacc[pi * D + dcol]);
-        f[u] = c < nsub ? float(a.pf[pi]) : 0.f;
+  for (int i = 0; i < kCand; ++i) cm[i] = Best{0.0, 0, -1};
+  for (int c = tid; c < nsub; c += 256) {
+    const int64_t x = (sbase + c) * kRec;
+#pragma unroll
+    for (int i = 0; i < kCand; ++i) {
+      const int s = int(ld_agent(&a.rec[x + 20 + i]));
+      if (s >= 0) {
+        const double u = ld_agent(&a.rec[x + 16 + i]);
+        const int p = a.cpos[slot0 + s];
+        if (better_match(u, p, s, cm[i])) cm[i] = Best{u, p, s};
       }
-#pragma unroll
-      for (int u = 0; u < 4; ++u) num = fmaf(v[u], f[u], num);
-    }
-    __syncthreads();
-    fred[tid] = num;
-    __syncthreads();
-    if (tid < D) {
-      float t = fred[tid];
-#pragma unroll
-      for (int i = 1; i < NPART; ++i) t += fred[i * D + tid];
-      out[li * ov.sn + b * ov.sb + (hk * G + g) * ov.sh + tid] = Elem<OT>::from_f32(float(double(t) / Lg[g]));
     }
   }
-  // ---- scores (Eq. 6), the token to evict (Eq. 7-8 on count+1 entries) and the lowest scores
-  //      among the tokens evictable at the next step
+#pragma unroll
+  for (int i = 0; i < kCand; ++i) {
+    park_u[i * 256 + tid] = cm[i].u;
+    park_ps[i * 256 + tid] = make_int2(cm[i].pos, cm[i].slot);
+  }
+  // ---- score pass, set-up
   const bool evict = total > mt[1];
   const int recent = mt[2];
   Best ev{0.0, 0, -1};
   Best low[kCand + 1];
 #pragma unroll
   for (int i = 0; i <= kCand; ++i) low[i] = Best{0.0, 0, -1};
-  for (int j0 = tid; j0 < total; j0 += 4 * 256) {
-    double sc[4], e[4][G];
-    int ps[4];
+  double sc[U], e[U][G], ms[U][G];
+  int ps[U];
+  auto load_batch = [&](int j0) {
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {  // four slots' loads in flight
+    for (int u = 0; u < U; ++u) {
       const int j = min(j0 + u * 256, total - 1);
       sc[u] = a.cscore[slot0 + j];
       ps[u] = a.cpos[slot0 + j];
 #pragma unroll
-      for (int g = 0; g < G; ++g)
-        e[u][g] = ld_agent(&a.elog[(int64_t(b) * a.Hkv * G + hk * G + g) * a.slots + mt[0] + j]);
+      for (int g = 0; g < G; ++g) {
+        e[u][g] = ld_agent(&elog[int64_t(g) * a.slots + j]);
+        ms[u][g] = ld_agent(&a.rec[(sbase + j / kSub) * kRec + g]);
+      }
     }
+  };
+  // Eq. 6 for the batch's slots, the token to evict (Eq. 7-8 on count+1 entries) and the lowest
+  // scores among the tokens evictable at the next step
+  auto apply_batch = [&](int j0) {
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
+    for (int u = 0; u < U; ++u) {
       const int j = j0 + u * 256;
       if (j < total) {
         double s2 = sc[u];
 #pragma unroll
-        for (int g = 0; g < G; ++g) s2 += e[u][g] * a.pf[pbase + int64_t(j / kSub) * G + g] / Lg[g];
+        for (int g = 0; g < G; ++g) s2 += e[u][g] * exp(ms[u][g] - Mg[g]) / Lg[g];
         a.cscore[slot0 + j] = s2;
         const int p = ps[u];
+        if (j == last) {  // kept for the move into the freed slot
+          sred[4] = s2;
+          ired[8] = p;
+        }
         if (p >= a.n_sink && p <= a.new_pos - recent && evicts_before(s2, p, j, ev)) ev = Best{s2, p, j};
         if (p >= a.n_sink && p <= a.new_pos + 1 - recent && evicts_before(s2, p, j, low[kCand])) {
           low[kCand] = Best{s2, p, j};
@@ -387,17 +462,61 @@ __device__ __forceinline__ void head_tail(const DecodeArgs& a, OT* __restrict__ 
             }
         }
       }
+      __builtin_amdgcn_sched_barrier(0);  // one slot after the other: interleaving them costs registers
     }
+  };
+  // ---- output rows: thread (rg, c4) adds the sub-chunks rg, rg + RG, ... of four columns, PB
+  //      loads in flight; the groups' sums are added in ascending order
+  const int c4 = tid % C4, rg = tid / C4;
+#pragma unroll
+  for (int g = 0; g < G; ++g) {
+    float num[4] = {0.f, 0.f, 0.f, 0.f};
+    for (int c0 = rg; c0 < nsub; c0 += PB * RG) {
+      float4 v[PB];
+      float f[PB];
+#pragma unroll
+      for (int u = 0; u < PB; ++u) {
+        const int c = c0 + u * RG, cc = min(c, nsub - 1);
+        v[u] = ld_agent4(a.pacc + (pbase + int64_t(cc) * G + g) * D + c4 * 4);
+        f[u] = c < nsub ? float(exp(ld_agent(&a.rec[(sbase + cc) * kRec + g]) - Mg[g])) : 0.f;
+      }
+#pragma unroll
+      for (int u = 0; u < PB; ++u) {
+        num[0] = fmaf(v[u].x, f[u], num[0]);
+        num[1] = fmaf(v[u].y, f[u], num[1]);
+        num[2] = fmaf(v[u].z, f[u], num[2]);
+        num[3] = fmaf(v[u].w, f[u], num[3]);
+      }
+    }
+    lds_barrier();
+#pragma unroll
+    for (int e = 0; e < 4; ++e) fred[e * 256 + tid] = num[e];
+    lds_barrier();
+    if (tid < D) {  // column tid: element tid % 4 of the threads (rg, tid / 4)
+      const float* fr = fred + (tid % 4) * 256 + tid / 4;
+      float t = fr[0];
+#pragma unroll
+      for (int i = 1; i < RG; ++i) t += fr[i * C4];
+      out[li * ov.sn + b * ov.sb + (hk * G + g) * ov.sh + tid] = Elem<OT>::from_f32(float(double(t) / Lg[g]));
+    }
+    __builtin_amdgcn_sched_barrier(0);  // one query head after the other (registers)
+  }
+  // ---- score pass: batches of U slots per thread, their loads in flight together
+  for (int j0 = tid; j0 < total; j0 += U * 256) {
+    load_batch(j0);
+    apply_batch(j0);
   }
   // evicted token: block-wide
-  ev = wave_first_evicted(ev);
-  __syncthreads();
+  ev = fast_wave_first_evicted(ev);
+  lds_barrier();
   if (lane == 0) {
     sred[w] = ev.u;
     ired[w] = ev.pos;
     ired[4 + w] = ev.slot;
   }
-  __syncthreads();
+  lds_barrier();
+  const double s_last = sred[4];
+  const int p_last = ired[8];
   ev = Best{sred[0], ired[0], ired[4]};
 #pragma unroll
   for (int i = 1; i < 4; ++i)
@@ -407,14 +526,14 @@ __device__ __forceinline__ void head_tail(const DecodeArgs& a, OT* __restrict__ 
   int nxt[kCand + 1];
 #pragma unroll
   for (int r = 0; r <= kCand; ++r) {
-    Best h = wave_first_evicted(low[0]);
-    __syncthreads();
+    Best h = fast_wave_first_evicted(low[0]);
+    lds_barrier();
     if (lane == 0) {
       sred[w] = h.u;
       ired[w] = h.pos;
       ired[4 + w] = h.slot;
     }
-    __syncthreads();
+    lds_barrier();
     h = Best{sred[0], ired[0], ired[4]};
 #pragma unroll
     for (int i = 1; i < 4; ++i)
@@ -426,14 +545,11 @@ __device__ __forceinline__ void head_tail(const DecodeArgs& a, OT* __restrict__ 
       low[kCand].slot = -1;
     }
   }
-  // this step's candidate list, before it is replaced
   int ci = -1;
 #pragma unroll
   for (int i = kCand - 1; i >= 0; --i)
-    if (es >= 0 && a.cand[lbh * kCand + i] == es) ci = i;
-  __syncthreads();  // every thread has read the old list
-  if (tid == 0) {
-    const int last = total - 1;
+    if (es >= 0 && cl[i] == es) ci = i;
+  if (tid == 0) {  // the next step's candidates (every thread holds this step's list in registers)
     int k = 0;
     for (int r = 0; r <= kCand && k < kCand; ++r) {
       int s = nxt[r];
@@ -446,7 +562,6 @@ __device__ __forceinline__ void head_tail(const DecodeArgs& a, OT* __restrict__ 
   }
   if (!evict) {
     if (tid == 0) {
-      a.eslot[lbh] = -1;
       a.ccount[lbh] = total;
       a.ev_evicted[lbh] = -1;
       a.ev_target[lbh] = -1;
@@ -454,36 +569,33 @@ __device__ __forceinline__ void head_tail(const DecodeArgs& a, OT* __restrict__ 
     }
     return;
   }
-  if (ci < 0) {  // not foreseen: the fallback pass computes its similarities
-    if (tid == 0) a.eslot[lbh] = es;
-    return;
-  }
-  if (tid == 0) a.eslot[lbh] = -1;
-  // Eq. 9 arg-max over the chunks' results for candidate ci (ties: earlier position)
   Best m{0.0, 0, -1};
-  for (int c = tid; c < nsub; c += 256) {
-    const int64_t x = (pbase / G + c) * kCand + ci;
-    const int s = ld_agent(&a.cslot[x]);
-    if (s >= 0) {
-      const double u = ld_agent(&a.cu[x]);
-      const int p = a.cpos[slot0 + s];
-      if (better_match(u, p, s, m)) m = Best{u, p, s};
-    }
+  if (ci < 0) {
+    // Not foreseen (the first step after prompt encoding, or a candidate overtaken by a token
+    // outside the list): a second pass over the head's keys.
+    m = scan_matches<T, D>(a, slot0, es, total, dred, sred);
+  } else {
+    const int2 q = park_ps[ci * 256 + tid];  // written by this thread
+    m = Best{park_u[ci * 256 + tid], q.x, q.y};
   }
-  m = wave_best_match(m);
-  __syncthreads();
+  m = fast_wave_best_match(m.u, m.pos, m.slot);
+  lds_barrier();
   if (lane == 0) {
     sred[w] = m.u;
     ired[w] = m.pos;
     ired[4 + w] = m.slot;
   }
-  __syncthreads();
+  lds_barrier();
   m = Best{sred[0], ired[0], ired[4]};
 #pragma unroll
   for (int i = 1; i < 4; ++i)
     if (better_match(sred[i], ired[i], ired[4 + i], m)) m = Best{sred[i], ired[i], ired[4 + i]};
-  __syncthreads();
-  finish_head<T, D>(a, lbh, slot0, es, total, m.u, m.pos, m.slot);
+  T kl = T(), vl = T();
+  if (tid < D) {
+    kl = park_kv[tid];
+    vl = park_kv[256 + tid];
+  }
+  finish_head<T, D>(a, lbh, slot0, es, total, m.u, m.pos, m.slot, told, kl, vl, s_last, p_last);
 }
 
 template <typename T, typename OT, int D, int G>
@@ -501,39 +613,45 @@ __global__ __launch_bounds__(256) void decode_attend(DecodeArgs a, OT* __restric
   typedef typename RawBits<ES * sizeof(T)>::type Raw;
   __shared__ __attribute__((aligned(16))) unsigned char stage[kStageBytes];
   __shared__ float ps[4][G][kSub];
-  __shared__ double sred[4];
-  __shared__ int ired[8];
   __shared__ int sh_last;
 
+  // Grid: x = head (fastest), y = flat chunk group over the layers.  Workgroups go round-robin to
+  // the XCDs in index order, so with a head count that is a multiple of the XCD count every chunk
+  // of a head, and the workgroup that closes it, run on one XCD.
   const int entry = find_entry(a, blockIdx.y), grp = blockIdx.y - a.lay_off[entry];
   const int li = a.lay_id[entry];
   const int l = a.layer0 + li, b = blockIdx.x / a.Hkv, hk = blockIdx.x % a.Hkv;
   const int64_t lbh = (int64_t(l) * a.B + b) * a.Hkv + hk;
-  const int total = a.ccount[lbh] + 1;          // the new token has been appended
+  // Everything the workgroup needs to know about its head comes through the scalar cache in one
+  // round trip (the loads are independent of each other): the fill level, the layer's slot and
+  // sub-chunk offsets, the candidates.  The kernel that wrote them has completed.
+  typedef const int32_t __attribute__((address_space(4))) * ciptr;
+  typedef const double __attribute__((address_space(4))) * cptr;
+  const ciptr mt = (ciptr)a.meta + (l * a.B + b) * 4;
+  const int total = ((ciptr)a.ccount)[lbh] + 1;  // the new token has been appended
+  const int mt0 = mt[0], mt3 = mt[3];
+  int cs[kCand];
+  double cn[kCand];
+#pragma unroll
+  for (int c = 0; c < kCand; ++c) {
+    cs[c] = ((ciptr)a.cand)[lbh * kCand + c];
+    cn[c] = ((cptr)a.cnorm)[lbh * kCand + c];
+  }
+  asm volatile("" ::"s"(total), "s"(mt0), "s"(mt3));  // all of them are on their way before the first wait
   if (grp * kGroup * kChunk >= total) return;
-  const int ngroup = (total + kGroup * kChunk - 1) / (kGroup * kChunk);
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
-  const int32_t* mt = a.meta + (l * a.B + b) * 4;
   const int64_t bh = int64_t(b) * a.Hkv + hk;
-  const int64_t slot0 = bh * a.slots + mt[0];
+  const int64_t slot0 = bh * a.slots + mt0;
   const unsigned char* Kh = static_cast<const unsigned char*>(a.cK) + slot0 * RB;
   const unsigned char* Vh = static_cast<const unsigned char*>(a.cV) + slot0 * RB;
   // A workgroup owns kGroup consecutive chunks of 256 slots; each wavefront works alone on 64
   // rows ("sub-chunk") of each of them, in a software pipeline: while it computes on one
   // sub-chunk, the V rows of that sub-chunk and the K rows of its next one are in flight.
   // There is no workgroup barrier until the ticket.
-  typedef const double __attribute__((address_space(4))) * cptr;
   cptr S = (cptr)(a.vecs + lbh * NV * D);
   unsigned char* mine = stage + w * 64 * kPitch;
-  const int tr = lane / TPR, tc = lane % TPR;
+  int ln = lane;  // the lane number as the loop body sees it
   const double root_d = sqrt(double(D));
-  int cs[kCand];
-  double cn[kCand];
-#pragma unroll
-  for (int c = 0; c < kCand; ++c) {
-    cs[c] = a.cand[lbh * kCand + c];
-    cn[c] = a.cnorm[lbh * kCand + c];
-  }
   // K loads of a sub-chunk: per piece, 8 lanes cover 128 bytes of a row, 8 rows per load
   u32x4 kreg[NP][8];
   auto load_keys = [&](int sub, int rows) {
@@ -542,20 +660,21 @@ __global__ __launch_bounds__(256) void decode_attend(DecodeArgs a, OT* __restric
     for (int p = 0; p < NP; ++p)
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
-        const int r = min(i * 8 + (lane >> 3), rows - 1);  // rows past the end repeat the last one
-        kreg[p][i] = *reinterpret_cast<const u32x4*>(Kc + int64_t(r) * RB + p * kPiece + (lane & 7) * 16);
+        const int r = min(i * 8 + (ln >> 3), rows - 1);  // rows past the end repeat the last one
+        kreg[p][i] = *reinterpret_cast<const u32x4*>(Kc + int64_t(r) * RB + p * kPiece + (ln & 7) * 16);
       }
   };
   const int sub0 = grp * kGroup * (kChunk / kSub) + w;
-  {
-    const int rows0 = min(kSub, total - sub0 * kSub);
-    if (rows0 > 0) load_keys(sub0, rows0);
-  }
-#pragma unroll 1
+#pragma unroll
   for (int it = 0; it < kGroup; ++it) {
     const int sub = sub0 + it * (kChunk / kSub);
     const int rows = min(kSub, total - sub * kSub);  // <= 0: nothing (more) for this wavefront
     if (rows <= 0) break;
+    // With more than one pass, address arithmetic hoisted out of the loop would cost more
+    // registers than the occupancy allows; an opaque lane number keeps it inside.
+    if (kGroup > 1) asm volatile("" : "+v"(ln));
+    const int tr = ln / TPR, tc = ln % TPR;
+    load_keys(sub, rows);
     const unsigned char* Vc = Vh + int64_t(sub) * kSub * RB;
     // ---- K pass: lane = row.  The queries and candidate keys arrive through scalar loads.
     double acc[NV];
@@ -565,7 +684,7 @@ __global__ __launch_bounds__(256) void decode_attend(DecodeArgs a, OT* __restric
     Raw rawA, rawB;
     double sA[NV][ES], sB[NV][ES];
     auto fetch = [&](int e0, int st, Raw& raw, double (&sv)[NV][ES]) {  // e0: first element of the piece
-      raw = *reinterpret_cast<const Raw*>(mine + lane * kPitch + st * ES * int(sizeof(T)));
+      raw = *reinterpret_cast<const Raw*>(mine + ln * kPitch + st * ES * int(sizeof(T)));
 #pragma unroll
       for (int v = 0; v < NV; ++v)
 #pragma unroll
@@ -583,8 +702,8 @@ __global__ __launch_bounds__(256) void decode_attend(DecodeArgs a, OT* __restric
     };
     u32x4 vreg[NVL];
     // this lane's score-side loads ride along
-    const bool valid = lane < rows;
-    const int j = sub * kSub + lane;
+    const bool valid = ln < rows;
+    const int j = sub * kSub + ln;
     const int pos = valid ? a.cpos[slot0 + j] : 0;
 #pragma unroll
     for (int p = 0; p < NP; ++p) {
@@ -594,7 +713,7 @@ __global__ __launch_bounds__(256) void decode_attend(DecodeArgs a, OT* __restric
       __builtin_amdgcn_wave_barrier();
 #pragma unroll
       for (int i = 0; i < 8; ++i)
-        *reinterpret_cast<u32x4*>(mine + (i * 8 + (lane >> 3)) * kPitch + (lane & 7) * 16) = kreg[p][i];
+        *reinterpret_cast<u32x4*>(mine + (i * 8 + (ln >> 3)) * kPitch + (ln & 7) * 16) = kreg[p][i];
       __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
       __builtin_amdgcn_wave_barrier();
       if (p == NP - 1) {  // the key registers are free: this sub-chunk's V rows and the next one's K rows
@@ -603,8 +722,6 @@ __global__ __launch_bounds__(256) void decode_attend(DecodeArgs a, OT* __restric
           const int r = min(i * RPI + tr, rows - 1);  // repeated rows meet a zero probability
           vreg[i] = *reinterpret_cast<const u32x4*>(Vc + int64_t(r) * RB + tc * 16);
         }
-        const int nsub = sub + kChunk / kSub, nrows = min(kSub, total - nsub * kSub);
-        if (it + 1 < kGroup && nrows > 0) load_keys(nsub, nrows);
       }
       // ES elements per step.  The row's bits and the scalar operands of a step are fetched one
       // step ahead (two register sets), so their latency hides behind the previous step's FMAs.
@@ -616,26 +733,27 @@ __global__ __launch_bounds__(256) void decode_attend(DecodeArgs a, OT* __restric
         // return out of order, so a wait after them would cover them too)
         arrived(sA[0][0]);
         fetch(e0, st + 1, rawB, sB);
+        __builtin_amdgcn_sched_barrier(0);  // the fetches go out before the FMAs, not among them
         step(rawA, sA);
         arrived(sB[0][0]);
         fetch(e0, min(st + 2, NST - 1), rawA, sA);
+        __builtin_amdgcn_sched_barrier(0);
         step(rawB, sB);
       }
     }
     // ---- softmax statistics of the sub-chunk; the lane owns cache row sub*kSub + lane
-    const int64_t pidx = (bh * a.nsub_cap + int64_t(mt[3]) * (kChunk / kSub) + sub) * G;
+    const int64_t pidx = (bh * a.nsub_cap + int64_t(mt3) * (kChunk / kSub) + sub) * G;
+    double recv = 0.0;  // this lane's element of the sub-chunk record
 #pragma unroll
     for (int g = 0; g < G; ++g) {
       const double sg = acc[g] / root_d;
       const double mx = fast_wave_max(valid ? sg : -INFINITY);
       const double e = valid ? exp(sg - mx) : 0.0;
-      ps[w][g][lane] = float(e);
-      if (valid) st_agent(&a.elog[(int64_t(b) * a.Hkv * G + hk * G + g) * a.slots + mt[0] + j], e);
+      ps[w][g][ln] = float(e);
+      if (valid) st_agent(&a.elog[(int64_t(b) * a.Hkv * G + hk * G + g) * a.slots + mt0 + j], e);
       const double sm = fast_wave_sum(e);
-      if (lane == 0) {
-        st_agent(&a.pm[pidx + g], mx);
-        st_agent(&a.pl[pidx + g], sm);
-      }
+      if (ln == g) recv = mx;
+      if (ln == 8 + g) recv = sm;
     }
     // candidates: cosine of this row against each candidate key (Eq. 9), sub-chunk arg-max
     const double nrow = sqrt(nr);
@@ -644,12 +762,10 @@ __global__ __launch_bounds__(256) void decode_attend(DecodeArgs a, OT* __restric
       const double den = cn[c] * nrow;
       const double u = den > 0.0 ? acc[G + c] / den : 0.0;
       const Best m = fast_wave_best_match(u, pos, (valid && cs[c] >= 0 && j != cs[c]) ? j : -1);
-      if (lane == 0) {
-        const int64_t x = (pidx / G) * kCand + c;
-        st_agent(&a.cu[x], m.u);
-        st_agent(&a.cslot[x], m.slot);
-      }
+      if (ln == 16 + c) recv = m.u;
+      if (ln == 20 + c) recv = double(m.slot);
     }
+    if (ln < kRec) st_agent(&a.rec[(pidx / G) * kRec + ln], recv);  // the record in one store
     // ---- partial P V, fp32: TPR lanes per row, RPI rows per load, then a sum over the row groups
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
     __builtin_amdgcn_wave_barrier();
@@ -690,94 +806,33 @@ __global__ __launch_bounds__(256) void decode_attend(DecodeArgs a, OT* __restric
       }
       __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
       __builtin_amdgcn_wave_barrier();
-      for (int c = lane * 2; c < D; c += 128) {
+      for (int c = ln * 2; c < D; c += 128)
+      {
         const uint64_t two = uint64_t(__float_as_uint(xch[c])) | (uint64_t(__float_as_uint(xch[c + 1])) << 32);
         st_agent(reinterpret_cast<uint64_t*>(a.pacc + (pidx + g) * D + c), two);
       }
     }
   }
-  // ---- ticket: the last workgroup of the head to arrive combines the sub-chunks.  Every store
-  //      above that it will read is a write-through store; they have completed once the
-  //      memory counters are zero, before the barrier that precedes the ticket.
+  // ---- ticket: the last workgroup of the head to arrive closes the head.  Every store above
+  //      that it will read is a write-through store; they have completed once the memory
+  //      counters are zero, before the barrier that precedes the ticket.
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
   __builtin_amdgcn_s_waitcnt(0);
   __syncthreads();
-  if (tid == 0)
+  if (tid == 0) {
+    const int ngroup = (total + kGroup * kChunk - 1) / (kGroup * kChunk);
     sh_last = (__hip_atomic_fetch_add(&a.ticket[lbh], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) ==
                unsigned(ngroup - 1)) ? 1 : 0;
+  }
   __syncthreads();
   if (!sh_last) return;
-  head_tail<T, OT, D, G>(a, out, ov, li, b, hk, lbh, total, (total + kSub - 1) / kSub, sred, ired,
-                         reinterpret_cast<float*>(stage));
-}
-
-// Fallback for a head whose evicted token was not among the step's candidates: cosine of the
-// evicted key against every survivor (Eq. 9) by one workgroup, then the finishing code.
-template <typename T, int D>
-__global__ __launch_bounds__(256) void decode_fallback(DecodeArgs a) {
-  constexpr int kVec = 16 / sizeof(T);
-  constexpr int TPR = D / kVec;
-  constexpr int RPP = 256 / TPR;
-  __shared__ double ke[D];
-  __shared__ double red[4];
-  __shared__ double bu[4];
-  __shared__ int bpos[4], bslot[4];
-  const int li = blockIdx.y, l = a.layer0 + li, b = blockIdx.x / a.Hkv, hk = blockIdx.x % a.Hkv;
-  const int64_t lbh = (int64_t(l) * a.B + b) * a.Hkv + hk;
-  const int es = a.eslot[lbh];
-  if (es < 0) return;
-  const int total = a.ccount[lbh] + 1;
-  const int tid = threadIdx.x;
-  const int32_t* mt = a.meta + (l * a.B + b) * 4;
-  const int64_t bh = int64_t(b) * a.Hkv + hk;
-  const int64_t slot0 = bh * a.slots + mt[0];
-  const T* Kc = static_cast<const T*>(a.cK) + slot0 * D;
-  double part = 0.0;
-  if (tid < D) {
-    const double x = Elem<T>::to_f64(Kc[int64_t(es) * D + tid]);
-    ke[tid] = x;
-    part = x * x;
-  }
-  const double sne = sqrt(block_sum(part, red));
-  const int tr = tid / TPR, tc = (tid % TPR) * kVec;
-  Best m{0.0, 0, -1};
-  for (int r0 = 0; r0 < total; r0 += RPP) {
-    const int j = r0 + tr;
-    double dot = 0.0, nr = 0.0;
-    if (j < total) {
-      double x[kVec];
-      cvt16<T>(*reinterpret_cast<const u32x4*>(Kc + int64_t(j) * D + tc), x);
-#pragma unroll
-      for (int e = 0; e < kVec; ++e) {
-        dot = fma(x[e], ke[tc + e], dot);
-        nr = fma(x[e], x[e], nr);
-      }
-    }
-#pragma unroll
-    for (int o = TPR / 2; o > 0; o >>= 1) {
-      dot += __shfl_xor(dot, o, 64);
-      nr += __shfl_xor(nr, o, 64);
-    }
-    if (j < total && j != es && (tid % TPR) == 0) {
-      const double den = sne * sqrt(nr);
-      const double u = den > 0.0 ? dot / den : 0.0;
-      const int p = a.cpos[slot0 + j];
-      if (better_match(u, p, j, m)) m = Best{u, p, j};
-    }
-  }
-  m = wave_best_match(m);
-  if ((tid & 63) == 0) {
-    bu[tid >> 6] = m.u;
-    bpos[tid >> 6] = m.pos;
-    bslot[tid >> 6] = m.slot;
-  }
-  __syncthreads();
-  m = Best{bu[0], bpos[0], bslot[0]};
-#pragma unroll
-  for (int i = 1; i < 4; ++i)
-    if (better_match(bu[i], bpos[i], bslot[i], m)) m = Best{bu[i], bpos[i], bslot[i]};
-  __syncthreads();
-  finish_head<T, D>(a, lbh, slot0, es, total, m.u, m.pos, m.slot);
+  // the staging area is free: it holds the closing code's exchange buffers
+  float* fred = reinterpret_cast<float*>(stage);
+  double* dred = reinterpret_cast<double*>(stage + 4 * 256 * sizeof(float));
+  double* sred = dred + D;
+  int* ired = reinterpret_cast<int*>(sred + 8);
+  head_tail<T, OT, D, G>(a, out, ov, li, b, hk, lbh, total, (total + kSub - 1) / kSub, sred, ired, fred, dred,
+                         stage + 8192);
 }
 
 template <typename T, typename OT, int D, int G>
@@ -793,8 +848,6 @@ hipError_t run_decode_o(d2o_ctx* c, const DecodeArgs& a, int nl, int flat_chunks
     KernelTimer kt(c, D2O_K_DECODE_ATTEND, s);
     decode_attend<T, OT, D, G><<<dim3(bh, flat_chunks), 256, 0, s>>>(a, (OT*)out.ptr, out);
   }
-  KernelTimer kt(c, D2O_K_DECODE_FALLBACK, s);
-  decode_fallback<T, D><<<dim3(bh, nl), 256, 0, s>>>(a);
   return hipGetLastError();
 }
 
@@ -836,15 +889,10 @@ hipError_t launch_decode(d2o_ctx* c, int layer0, int nl_all, View q, View k, Vie
   a.cand = c->ccand;
   a.ticket = c->cticket;
   a.elog = c->d_logit;
-  a.pm = c->d_pm;
-  a.pf = c->d_pf;
-  a.pl = c->d_pl;
+  a.rec = c->d_rec;
   a.pacc = c->d_pacc;
   a.vecs = c->d_vecs;
   a.cnorm = c->d_cnorm;
-  a.cu = c->d_cu;
-  a.cslot = c->d_cslot;
-  a.eslot = c->d_eslot;
   a.ev_evicted = c->ev_evicted;
   a.ev_target = c->ev_target;
   a.ev_ustar = c->ev_ustar;
@@ -876,7 +924,7 @@ hipError_t launch_decode(d2o_ctx* c, int layer0, int nl_all, View q, View k, Vie
       a.lay_off[i] = flat;
       flat += mc[a.lay_id[i]];
     }
-    a.lay_off[nl] = flat;
+    for (int i = nl; i <= kMaxLayersPerCall; ++i) a.lay_off[i] = i == nl ? flat : 0x7FFFFFFF;
     auto shift = [&](View x, int elem_bytes) {  // first layer of this group
       x.ptr = static_cast<char*>(x.ptr) + size_t(g0) * x.sn * elem_bytes;
       return x;

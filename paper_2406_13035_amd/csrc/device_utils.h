@@ -124,6 +124,12 @@ __device__ __forceinline__ double row16_sum(double v) {
   return v;
 }
 
+// Workgroup barrier for exchanges through LDS only: it waits for the wavefront's LDS traffic,
+// not for its outstanding global loads and stores (which __syncthreads would drain first).
+__device__ __forceinline__ void lds_barrier() {
+  asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
 // Deterministic block-wide sum (fixed tree): every thread gets the total.
 // `buf` holds one double per wave; blockDim.x must be a multiple of 64 and <= 1024.
 __device__ __forceinline__ double block_sum(double v, double* buf) {
