@@ -35,6 +35,7 @@ constexpr int kD = 128;
 constexpr int kLdK = kD + 8;   // LDS row pitch (elements) of [token][d] tiles
 constexpr int kLdV = 64 + 8;   // LDS row pitch of the [d][key] tile
 constexpr float kPShift = 12.f;  // probabilities are formed as 2^12 * p before the fp16 rounding
+constexpr float kLazy = 3.f;     // log2 of the growth the exponent reference tolerates before it moves
 
 __global__ void zero_u32(uint32_t* p, int n) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
@@ -257,8 +258,12 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, 2)))
 #pragma unroll
         for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[j][st][r]);
       mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-      const float mnew = fmaxf(mrun[j], fmaf(mx, scale2, -kPShift));  // exponent reference, 2^12 headroom
-      const bool grew = mnew > mrun[j];
+      // Exponent reference with 2^12 headroom.  It follows the row maximum lazily: it moves only
+      // when the maximum has outgrown it by more than 2^kLazy, so the probabilities stay below
+      // 2^(12 + kLazy), inside fp16, and the rescale of the accumulators becomes rare.
+      const float mcand = fmaf(mx, scale2, -kPShift);
+      const bool grew = mcand > mrun[j] + kLazy;
+      const float mnew = grew ? mcand : mrun[j];
       const float alpha = __builtin_amdgcn_exp2f(mrun[j] - mnew);
       mrun[j] = mnew;
       float psum = 0.f;
@@ -421,7 +426,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, 2)))
 // workgroup of a head then reads the same query tiles at about the same time (all start at
 // the last tile), so the tiles are served from L2 instead of HBM.
 constexpr int kColNW = 8;
-__global__ __launch_bounds__(64 * kColNW) void colsum_bf16(const uint16_t* __restrict__ Q, View qv,
+__global__ __launch_bounds__(64 * kColNW) __attribute__((amdgpu_waves_per_eu(4, 4))) void colsum_bf16(const uint16_t* __restrict__ Q, View qv,
                                                            const uint16_t* __restrict__ K, View kv,
                                                            const float* __restrict__ lse2, float* __restrict__ score,
                                                            double* __restrict__ varpart, int n, int npad, int G,

@@ -588,63 +588,154 @@ __global__ __launch_bounds__(1024) void threshold_group_kernel(const double* __r
   (void)wb;
 }
 
-// Merge (Eq. 11-12).  One wavefront per retained slot that has sources.  fp64, operation order
-// of the definition: acc = e * k_c; for each source in ascending evicted order: w = exp(u),
-// Z += w, acc += w * k_e; result acc / Z rounded once to the cache dtype.  Products and sums
-// are kept unfused so the sequence is the one written in the formula.
+// PER consecutive elements of a row as one load / one store.
+template <typename T, int PER>
+__device__ __forceinline__ void load_elems(const T* p, double* out) {
+  static_assert(PER * sizeof(T) == 4 || PER * sizeof(T) == 8, "one 4- or 8-byte access");
+  T tmp[PER];
+  if constexpr (PER * sizeof(T) == 4)
+    *reinterpret_cast<uint32_t*>(tmp) = *reinterpret_cast<const uint32_t*>(p);
+  else
+    *reinterpret_cast<uint64_t*>(tmp) = *reinterpret_cast<const uint64_t*>(p);
+#pragma unroll
+  for (int i = 0; i < PER; ++i) out[i] = Elem<T>::to_f64(tmp[i]);
+}
+template <typename T, int PER>
+__device__ __forceinline__ void store_elems(T* p, const double* v, double z) {
+  T tmp[PER];
+#pragma unroll
+  for (int i = 0; i < PER; ++i) tmp[i] = Elem<T>::from_f64(v[i] / z);
+  if constexpr (PER * sizeof(T) == 4)
+    *reinterpret_cast<uint32_t*>(p) = *reinterpret_cast<const uint32_t*>(tmp);
+  else
+    *reinterpret_cast<uint64_t*>(p) = *reinterpret_cast<const uint64_t*>(tmp);
+}
+
+// Merge (Eq. 11-12).  One wavefront per retained slot that has sources; lane i owns elements
+// PER*i .. PER*i + PER - 1 of the row.  fp64, operation order of the definition: acc = e * k_c;
+// for each source in ascending evicted order: w = exp(u), Z += w, acc += w * k_e; result
+// acc / Z rounded once to the cache dtype.  Products and sums are kept unfused so the sequence
+// is the one written in the formula.
+// The source list of a slot is unordered, and its length varies widely (the keys nearest to a
+// cluster centre collect hundreds of sources; a small budget lengthens every list).
+//   up to 64 sources      one source per lane: the lanes rank their sources (count the smaller
+//                         ones), fetch weight and position in parallel;
+//   up to kMergeCap       the same ranking through LDS, weight and position stored at the rank;
+//   beyond                the next source is extracted by a scan per step.
+// The rows are then read kMergeBatch sources at a time in rank order.
+constexpr int kMergeCap = 512;
+constexpr int kMergeBatch = 8;
 template <typename T, int D>
 __global__ __launch_bounds__(256) void merge_kernel(const T* __restrict__ K, View kv, const T* __restrict__ V, View vv,
                                                     const int32_t* __restrict__ evi, const int32_t* __restrict__ cnt,
-                                                    const double* __restrict__ ustar, const int32_t* __restrict__ gcnt,
-                                                    const int32_t* __restrict__ goff, const int32_t* __restrict__ gsrc,
-                                                    const int32_t* __restrict__ meta, T* __restrict__ cK,
-                                                    T* __restrict__ cV, int npad, int64_t slots) {
+                                                    const double* __restrict__ ustar, const int32_t* __restrict__ goff,
+                                                    const int32_t* __restrict__ gsrc, const int32_t* __restrict__ meta,
+                                                    T* __restrict__ cK, T* __restrict__ cV, int npad, int64_t slots) {
+  __shared__ int s_src[4][kMergeCap];
+  __shared__ int s_pos[4][kMergeCap];
+  __shared__ double s_w[4][kMergeCap];
   const int hk = blockIdx.y, b = blockIdx.z, Hkv = gridDim.y;
   const int64_t bh = int64_t(b) * Hkv + hk;
-  const int nret = cnt[bh * 2];
   const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const int slot = blockIdx.x * 4 + w;
+  const int slot = blockIdx.x * 4 + w;  // < npad: both offsets below are inside the array
+  const int nret = cnt[bh * 2];
+  const int32_t* go = goff + bh * (npad + 1);  // exclusive prefix of the list sizes over [0, nret]
+  const int off0 = go[slot], off1 = go[slot + 1];
   if (slot >= nret) return;
-  const int ns = gcnt[bh * (npad + 1) + slot];
+  const int ns = off1 - off0;
   if (ns == 0) return;
-  const int32_t* src = gsrc + bh * npad + goff[bh * (npad + 1) + slot];
+  const int32_t* src = gsrc + bh * npad + off0;
   const int32_t* el = evi + bh * npad;
   const double* us = ustar + bh * npad;
   const T* kb = K + b * kv.sb + hk * kv.sh;
   const T* vb = V + b * vv.sb + hk * vv.sh;
   constexpr int PER = D / 64;
-  const int64_t dst = (bh * slots + meta[b * 4 + 0] + slot) * D;
+  const int64_t dst = (bh * slots + meta[b * 4 + 0] + slot) * D + lane * PER;
   const double e1 = 2.718281828459045;  // exp(1), the retained token's self-similarity weight
   double ak[PER], av[PER];
+  load_elems<T, PER>(cK + dst, ak);
+  load_elems<T, PER>(cV + dst, av);
 #pragma unroll
   for (int p = 0; p < PER; ++p) {
-    ak[p] = __dmul_rn(e1, Elem<T>::to_f64(cK[dst + lane + 64 * p]));
-    av[p] = __dmul_rn(e1, Elem<T>::to_f64(cV[dst + lane + 64 * p]));
+    ak[p] = __dmul_rn(e1, ak[p]);
+    av[p] = __dmul_rn(e1, av[p]);
   }
   double z = e1;
-  int prev = -1;
-  for (int s = 0; s < ns; ++s) {
-    int cur = 0x7FFFFFFF;
-    for (int t = lane; t < ns; t += 64) {
-      const int r = src[t];
-      if (r > prev && r < cur) cur = r;
-    }
-    cur = wave_min(cur);
-    const double wgt = exp(us[cur]);
+  auto add_source = [&](double wgt, const double* xk, const double* xv) {
     z = __dadd_rn(z, wgt);
-    const int64_t pos = el[cur];
 #pragma unroll
     for (int p = 0; p < PER; ++p) {
-      ak[p] = __dadd_rn(ak[p], __dmul_rn(wgt, Elem<T>::to_f64(kb[pos * kv.sn + lane + 64 * p])));
-      av[p] = __dadd_rn(av[p], __dmul_rn(wgt, Elem<T>::to_f64(vb[pos * vv.sn + lane + 64 * p])));
+      ak[p] = __dadd_rn(ak[p], __dmul_rn(wgt, xk[p]));
+      av[p] = __dadd_rn(av[p], __dmul_rn(wgt, xv[p]));
     }
-    prev = cur;
-  }
+  };
+  // rows of kMergeBatch sources in flight; weight and position of source s come from `at`
+  auto stream = [&](auto at) {
+    for (int s0 = 0; s0 < ns; s0 += kMergeBatch) {
+      double wq[kMergeBatch], xk[kMergeBatch][PER], xv[kMergeBatch][PER];
 #pragma unroll
-  for (int p = 0; p < PER; ++p) {
-    cK[dst + lane + 64 * p] = Elem<T>::from_f64(ak[p] / z);
-    cV[dst + lane + 64 * p] = Elem<T>::from_f64(av[p] / z);
+      for (int u = 0; u < kMergeBatch; ++u) {
+        int pos;
+        at(min(s0 + u, ns - 1), wq[u], pos);
+        load_elems<T, PER>(kb + int64_t(pos) * kv.sn + lane * PER, xk[u]);
+        load_elems<T, PER>(vb + int64_t(pos) * vv.sn + lane * PER, xv[u]);
+      }
+#pragma unroll
+      for (int u = 0; u < kMergeBatch; ++u)
+        if (s0 + u < ns) add_source(wq[u], xk[u], xv[u]);
+    }
+  };
+  if (ns <= 64) {
+    const bool have = lane < ns;
+    const int mine = have ? src[lane] : 0x7FFFFFFF;
+    const double wmine = have ? exp(us[mine]) : 0.0;
+    const int pmine = have ? el[mine] : 0;
+    int rank = 0;  // sources are distinct: the ranks are a permutation of 0 .. ns-1
+    for (int i = 0; i < ns; ++i) rank += __builtin_amdgcn_readlane(mine, i) < mine ? 1 : 0;
+    stream([&](int s, double& wgt, int& pos) {
+      const int owner = __ffsll((long long)__ballot(have && rank == s)) - 1;
+      wgt = lane_f64(wmine, owner);
+      pos = __builtin_amdgcn_readlane(pmine, owner);
+    });
+  } else if (ns <= kMergeCap) {
+    for (int t = lane; t < ns; t += 64) s_src[w][t] = src[t];
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    for (int t = lane; t < ns; t += 64) {
+      const int mine = s_src[w][t];
+      const double wm = exp(us[mine]);
+      const int pm = el[mine];
+      int rank = 0;
+      for (int i = 0; i < ns; ++i) rank += s_src[w][i] < mine ? 1 : 0;
+      s_w[w][rank] = wm;
+      s_pos[w][rank] = pm;
+    }
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    stream([&](int s, double& wgt, int& pos) {
+      wgt = s_w[w][s];
+      pos = s_pos[w][s];
+    });
+  } else {
+    int prev = -1;
+    for (int s = 0; s < ns; ++s) {
+      int cur = 0x7FFFFFFF;
+      for (int t = lane; t < ns; t += 64) {
+        const int r = src[t];
+        if (r > prev && r < cur) cur = r;
+      }
+      cur = wave_min(cur);
+      const double wgt = exp(us[cur]);
+      const int64_t pos = el[cur];
+      double xk[PER], xv[PER];
+      load_elems<T, PER>(kb + pos * kv.sn + lane * PER, xk);
+      load_elems<T, PER>(vb + pos * vv.sn + lane * PER, xv);
+      add_source(wgt, xk, xv);
+      prev = cur;
+    }
   }
+  store_elems<T, PER>(cK + dst, ak, z);
+  store_elems<T, PER>(cV + dst, av, z);
 }
 
 }  // namespace
@@ -738,28 +829,27 @@ hipError_t launch_threshold_group(d2o_ctx* c, int layer, int n, hipStream_t s) {
   return hipGetLastError();
 }
 
+template <typename T, int D>
+static void run_merge(d2o_ctx* c, const int32_t* meta, View K, View V, int max_budget, hipStream_t s) {
+  const d2o_config& cf = c->cfg;
+  merge_kernel<T, D><<<dim3((max_budget + 3) / 4, cf.n_kv_heads, cf.batch), 256, 0, s>>>(
+      (const T*)K.ptr, K, (const T*)V.ptr, V, c->sel_evi, c->sel_cnt, c->m_ustar, c->g_off, c->g_src, meta, (T*)c->cacheK,
+      (T*)c->cacheV, c->npad, cf.slots_per_seq);
+}
+
 hipError_t launch_merge(d2o_ctx* c, int layer, View K, View V, int n, hipStream_t s) {
   const d2o_config& cf = c->cfg;
   if (max_evicted(c, layer, n) == 0) return hipSuccess;
   int max_budget = 0;
   for (const auto& mt : c->layers[layer].meta) max_budget = std::max(max_budget, std::min(mt.budget, n));
   const int32_t* meta = c->meta + size_t(layer) * cf.batch * 4;
-  const dim3 gr((max_budget + 3) / 4, cf.n_kv_heads, cf.batch);
   KernelTimer kt(c, D2O_K_MERGE, s);
-  if (cf.dtype == D2O_BF16) {
-    merge_kernel<uint16_t, 128><<<gr, 256, 0, s>>>((const uint16_t*)K.ptr, K, (const uint16_t*)V.ptr, V, c->sel_evi,
-                                                   c->sel_cnt, c->m_ustar, c->g_cnt, c->g_off, c->g_src, meta,
-                                                   (uint16_t*)c->cacheK, (uint16_t*)c->cacheV, c->npad,
-                                                   cf.slots_per_seq);
-  } else if (cf.head_dim == 64) {
-    merge_kernel<float, 64><<<gr, 256, 0, s>>>((const float*)K.ptr, K, (const float*)V.ptr, V, c->sel_evi, c->sel_cnt,
-                                               c->m_ustar, c->g_cnt, c->g_off, c->g_src, meta, (float*)c->cacheK,
-                                               (float*)c->cacheV, c->npad, cf.slots_per_seq);
-  } else {
-    merge_kernel<float, 128><<<gr, 256, 0, s>>>((const float*)K.ptr, K, (const float*)V.ptr, V, c->sel_evi, c->sel_cnt,
-                                                c->m_ustar, c->g_cnt, c->g_off, c->g_src, meta, (float*)c->cacheK,
-                                                (float*)c->cacheV, c->npad, cf.slots_per_seq);
-  }
+  if (cf.dtype == D2O_BF16)
+    run_merge<uint16_t, 128>(c, meta, K, V, max_budget, s);
+  else if (cf.head_dim == 64)
+    run_merge<float, 64>(c, meta, K, V, max_budget, s);
+  else
+    run_merge<float, 128>(c, meta, K, V, max_budget, s);
   return hipGetLastError();
 }
 
