@@ -156,6 +156,34 @@ def test_matching_with_duplicate_keys_takes_first_maximum():
     ctx.close()
 
 
+def test_merge_with_long_source_lists():
+    """One retained key attracts about 700 evicted tokens, another about 200, the rest a few:
+    the merge visits a slot's sources in ascending order whatever their number (the library
+    ranks up to 64 of them in registers, up to 512 in LDS and scans beyond that)."""
+    w, n = _small_bf16(False), 2600
+    Q, K, V = H.make_inputs(w, 1, 3, n)
+    g = torch.Generator().manual_seed(77)
+    K = K.clone()
+    r1, r2 = 40, 900
+    for h in range(w.n_kv_heads):
+        c1, c2 = K[0, h, r1].float().cpu(), K[0, h, r2].float().cpu()
+        K[0, h, 100:800] = (c1[None] + 0.05 * torch.randn(700, w.head_dim, generator=g)).to(K.dtype).to(K.device)
+        K[0, h, 1000:1200] = (c2[None] + 0.05 * torch.randn(200, w.head_dim, generator=g)).to(K.dtype).to(K.device)
+    score32 = np.zeros((1, w.n_kv_heads, n), dtype=np.float32)
+    keep = np.concatenate([[r1, r2], np.arange(1300, 1330)])
+    score32[:, :, keep] = 3.0
+    ctx = H.new_ctx(w, 1, 1, n, 64, tau_force=float("-inf"))
+    ctx.d2o_scores_import(0, score32)
+    ctx.d2o_compress_layer(0, K, V, 40, 8)
+    torch.cuda.synchronize()
+    stats, _ = H.check_compress_against_oracle(ctx, 0, K, V, score32, 40, 8, 0, w.dtype, float("-inf"))
+    ret, evi, tgt, us, ps = ctx.d2o_prefill_events(0, 0, 0, n)
+    sizes = np.bincount(tgt[ps.astype(bool)], minlength=n)
+    print(f"  {stats}; largest source lists {np.sort(sizes)[-3:]}", flush=True)
+    assert sizes[r1] > 512 and 64 < sizes[r2] <= 512
+    ctx.close()
+
+
 # ------------------------------------------------------------------ a9-a12: decode from oracle state
 
 def _run_decode_parity(w, n, B, layer, budget, recent, sink, steps, tau_force=float("nan")):
