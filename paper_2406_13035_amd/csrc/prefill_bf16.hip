@@ -133,20 +133,26 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, 2)))
                                                      const uint16_t* __restrict__ K, View kv,
                                                      const uint16_t* __restrict__ VT, const float* __restrict__ unscale,
                                                      void* __restrict__ O, View ov, float* __restrict__ lse2, int n,
-                                                     int npad, int G, int out_f32) {
+                                                     int npad, int G, int out_f32, int nblk) {
   extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
   uint16_t* Ks = smem;                 // [2][kKsElems]
   uint16_t* Vs = smem + 2 * kKsElems;  // [2][kVsElems]
-  const int nblk = gridDim.x;
   const int hq = blockIdx.y, b = blockIdx.z, Hq = gridDim.y, hk = hq / G, Hkv = Hq / G;
   const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, m = lane & 31, h = lane >> 5;
   constexpr int kWR = 32 * RW;   // rows per wavefront
   constexpr int NT = 64 * NW;    // threads
   constexpr int NCH = 1024 / NT;  // 16-byte chunks of each tile per thread
   constexpr int BM = NW * kWR;   // query rows per workgroup
-  const int rb = (nblk - 1 - blockIdx.x) * BM;  // longest rows first
-  const int wr0 = rb + w * kWR;  // first row of this wavefront
   const float scale2 = kLog2e / sqrtf(float(kD));
+  // The work of a row block grows with its position (causal).  A workgroup takes row block
+  // nblk - 1 - x (the longer one first) and then row block x: every workgroup has the same
+  // amount of work and the launch fills the chip in whole rounds (with one row block per
+  // workgroup the longest ones ran on a nearly empty chip at the end: 80 % packing).
+  for (int pass = 0; pass < 2; ++pass) {
+  const int blk = pass == 0 ? nblk - 1 - int(blockIdx.x) : int(blockIdx.x);
+  if (pass == 1 && blk >= nblk - 1 - int(blockIdx.x)) break;
+  const int rb = blk * BM;
+  const int wr0 = rb + w * kWR;  // first row of this wavefront
 
   bf16x8 bq[RW][8];
 #pragma unroll
@@ -419,6 +425,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, 2)))
       }
     }
   }
+  }
 }
 
 // 256 keys per workgroup (8 wavefronts x 32 keys, the stationary A operand).  Query tiles of
@@ -430,17 +437,25 @@ __global__ __launch_bounds__(64 * kColNW) __attribute__((amdgpu_waves_per_eu(4, 
                                                            const uint16_t* __restrict__ K, View kv,
                                                            const float* __restrict__ lse2, float* __restrict__ score,
                                                            double* __restrict__ varpart, int n, int npad, int G,
-                                                           int Hq) {
+                                                           int Hq, int nblk) {
   __shared__ __attribute__((aligned(16))) uint16_t Qs[2][64 * kLdK];
   __shared__ float ls[2][64];
   __shared__ float cs[kColBN];
   __shared__ double red[kColNW];
   constexpr int NT = 64 * kColNW;
   constexpr int NCH = 1024 / NT;
-  const int tile = blockIdx.x, hk = blockIdx.y, b = blockIdx.z, Hkv = gridDim.y;
+  const int hk = blockIdx.y, b = blockIdx.z, Hkv = gridDim.y;
   const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, m = lane & 31, h = lane >> 5;
-  const int kb0 = tile * kColBN, kw0 = kb0 + w * 32;  // first key of the workgroup / wavefront
   const float scale2 = kLog2e / sqrtf(float(kD));
+  // The work of a key block grows with the number of queries behind it (causal), from one
+  // query tile for the last block to all of them for the first.  A workgroup takes block x and
+  // then block nblk - 1 - x: every workgroup then has the same amount of work and the launch
+  // fills the chip in whole rounds (with one block per workgroup the CUs held 1.3 of 2 possible
+  // workgroups on average, and the longest workgroup alone was a fifth of the kernel time).
+  for (int pass = 0; pass < 2; ++pass) {
+  const int tile = pass == 0 ? int(blockIdx.x) : nblk - 1 - int(blockIdx.x);
+  if (pass == 1 && tile <= int(blockIdx.x)) break;
+  const int kb0 = tile * kColBN, kw0 = kb0 + w * 32;  // first key of the workgroup / wavefront
 
   const uint16_t* kp = K + b * kv.sb + hk * kv.sh + int64_t(min(kw0 + m, n - 1)) * kv.sn;
   bf16x8 ak[8];
@@ -547,6 +562,7 @@ __global__ __launch_bounds__(64 * kColNW) __attribute__((amdgpu_waves_per_eu(4, 
     }
   }
   if (tid < kColBN && kb0 + tid < n) score[(int64_t(b) * Hkv + hk) * npad + kb0 + tid] = total;
+  }
 }
 
 }  // namespace
@@ -572,14 +588,14 @@ hipError_t launch_prefill_bf16(d2o_ctx* c, int layer, View Q, View K, View V, Vi
                                                                          c->vmax_bits, c->vt_unscale, n, c->npad);
   {
   KernelTimer kt(c, D2O_K_ATTN_FWD, s);
-  attn_fwd_bf16<kAttnRW, kAttnNW><<<dim3(nblk, cf.n_q_heads, cf.batch), 64 * kAttnNW, kAttnSmemBytes, s>>>((const uint16_t*)Q.ptr, Q, (const uint16_t*)K.ptr, K,
-                                                                  (const uint16_t*)c->vt, c->vt_unscale, O.ptr, O, c->lse,
-                                                                  n, c->npad, G, cf.out_f32);
+  attn_fwd_bf16<kAttnRW, kAttnNW><<<dim3((nblk + 1) / 2, cf.n_q_heads, cf.batch), 64 * kAttnNW, kAttnSmemBytes, s>>>(
+      (const uint16_t*)Q.ptr, Q, (const uint16_t*)K.ptr, K, (const uint16_t*)c->vt, c->vt_unscale, O.ptr, O, c->lse, n,
+      c->npad, G, cf.out_f32, nblk);
   }
   KernelTimer kt(c, D2O_K_COLSUM, s);
-  colsum_bf16<<<dim3(nblk_col, cf.n_kv_heads, cf.batch), 64 * kColNW, 0, s>>>((const uint16_t*)Q.ptr, Q, (const uint16_t*)K.ptr, K,
-                                                                 c->lse, score, c->varpart, n, c->npad, G,
-                                                                 cf.n_q_heads);
+  colsum_bf16<<<dim3((nblk_col + 1) / 2, cf.n_kv_heads, cf.batch), 64 * kColNW, 0, s>>>(
+      (const uint16_t*)Q.ptr, Q, (const uint16_t*)K.ptr, K, c->lse, score, c->varpart, n, c->npad, G, cf.n_q_heads,
+      nblk_col);
   return hipGetLastError();
 }
 
