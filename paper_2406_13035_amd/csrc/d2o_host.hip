@@ -148,6 +148,19 @@ int reserve_layer(d2o_ctx* x, int32_t layer, int32_t n, const int32_t* budget, c
   return D2O_OK;
 }
 
+// Fill of 32-bit words by a kernel: the state reset below may be part of a caller's captured
+// graph, where memset nodes are not reliable.
+__global__ void fill_words(uint32_t* p, uint32_t v, size_t n) {
+  for (size_t i = size_t(blockIdx.x) * blockDim.x + threadIdx.x; i < n; i += size_t(gridDim.x) * blockDim.x) p[i] = v;
+}
+hipError_t fill32(void* p, uint32_t v, size_t bytes, hipStream_t s) {
+  const size_t n = bytes / 4;
+  if (n == 0) return hipSuccess;
+  const unsigned blocks = unsigned(std::min<size_t>((n + 255) / 256, 1024));
+  fill_words<<<blocks, 256, 0, s>>>(static_cast<uint32_t*>(p), v, n);
+  return hipGetLastError();
+}
+
 }  // namespace
 }  // namespace d2o
 
@@ -211,16 +224,16 @@ int d2o_reset(d2o_ctx* x, void* stream) {
   const d2o_config& c = x->cfg;
   const size_t lbh = size_t(c.n_layers) * c.batch * c.n_kv_heads;
   // Only the small per-head state needs defined contents; 0xFF bytes read as NaN / -1.
-  D2O_HIP_CHECK(x, hipMemsetAsync(x->layer_F, 0xFF, sizeof(double) * c.n_layers * c.batch, s));
-  D2O_HIP_CHECK(x, hipMemsetAsync(x->head_var, 0xFF, sizeof(double) * c.n_layers * c.batch * c.n_q_heads, s));
-  D2O_HIP_CHECK(x, hipMemsetAsync(x->ccount, 0, sizeof(int32_t) * lbh, s));
-  D2O_HIP_CHECK(x, hipMemsetAsync(x->ctau, 0xFF, sizeof(double) * lbh, s));
-  D2O_HIP_CHECK(x, hipMemsetAsync(x->meta, 0, sizeof(int32_t) * 4 * c.n_layers * c.batch, s));
-  D2O_HIP_CHECK(x, hipMemsetAsync(x->ev_evicted, 0xFF, sizeof(int32_t) * lbh, s));
-  D2O_HIP_CHECK(x, hipMemsetAsync(x->ev_target, 0xFF, sizeof(int32_t) * lbh, s));
-  D2O_HIP_CHECK(x, hipMemsetAsync(x->ev_ustar, 0xFF, sizeof(double) * lbh, s));
-  D2O_HIP_CHECK(x, hipMemsetAsync(x->ccand, 0xFF, sizeof(int32_t) * lbh * decode_candidates(), s));
-  D2O_HIP_CHECK(x, hipMemsetAsync(x->cticket, 0, sizeof(uint32_t) * lbh, s));
+  D2O_HIP_CHECK(x, fill32(x->layer_F, 0xFFFFFFFFu, sizeof(double) * c.n_layers * c.batch, s));
+  D2O_HIP_CHECK(x, fill32(x->head_var, 0xFFFFFFFFu, sizeof(double) * c.n_layers * c.batch * c.n_q_heads, s));
+  D2O_HIP_CHECK(x, fill32(x->ccount, 0u, sizeof(int32_t) * lbh, s));
+  D2O_HIP_CHECK(x, fill32(x->ctau, 0xFFFFFFFFu, sizeof(double) * lbh, s));
+  D2O_HIP_CHECK(x, fill32(x->meta, 0u, sizeof(int32_t) * 4 * c.n_layers * c.batch, s));
+  D2O_HIP_CHECK(x, fill32(x->ev_evicted, 0xFFFFFFFFu, sizeof(int32_t) * lbh, s));
+  D2O_HIP_CHECK(x, fill32(x->ev_target, 0xFFFFFFFFu, sizeof(int32_t) * lbh, s));
+  D2O_HIP_CHECK(x, fill32(x->ev_ustar, 0xFFFFFFFFu, sizeof(double) * lbh, s));
+  D2O_HIP_CHECK(x, fill32(x->ccand, 0xFFFFFFFFu, sizeof(int32_t) * lbh * decode_candidates(), s));
+  D2O_HIP_CHECK(x, fill32(x->cticket, 0u, sizeof(uint32_t) * lbh, s));
   for (auto& l : x->layers) l = LayerState{};
   std::fill(x->used_slots.begin(), x->used_slots.end(), 0);
   std::fill(x->used_chunks.begin(), x->used_chunks.end(), 0);
@@ -523,8 +536,7 @@ int d2o_cache_import(d2o_ctx* x, int32_t layer, int32_t b, int32_t h, const void
   D2O_HIP_CHECK(x, hipMemcpyAsync(x->ccount + lbh, &count, sizeof(int32_t), hipMemcpyHostToDevice, s));
   D2O_HIP_CHECK(x, hipMemcpyAsync(x->ctau + lbh, &tau, sizeof(double), hipMemcpyHostToDevice, s));
   // the imported rows have no known eviction candidates yet
-  D2O_HIP_CHECK(x, hipMemsetAsync(x->ccand + lbh * decode_candidates(), 0xFF,
-                                  sizeof(int32_t) * decode_candidates(), s));
+  D2O_HIP_CHECK(x, fill32(x->ccand + lbh * decode_candidates(), 0xFFFFFFFFu, sizeof(int32_t) * decode_candidates(), s));
   D2O_HIP_CHECK(x, hipStreamSynchronize(s));
   st.next_pos = next_pos;
   return D2O_OK;
