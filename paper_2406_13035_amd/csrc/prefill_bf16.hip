@@ -349,7 +349,7 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, 2)))
   // ---- ping-pong schedule.  The two wavefronts that share a SIMD (w and w + NW/2) run half a
   // tile apart: while one forms its probabilities on the vector ALU, the other runs its two
   // matrix products (P V of the tile, then Q K^T of the next) on the matrix core, and they swap
-  // at a workgroup barrier.  K is staged two tiles ahead, V^T one tile ahead.
+  // in the middle of the iteration.  K is staged two tiles ahead, V^T one tile ahead.
   const bool late = w >= NW / 2;
   // Pin the arrival of the Q operands here: otherwise the wait for them is placed inside the
   // loop, behind the tile loads issued there, and stalls the matrix products on those.
@@ -382,7 +382,9 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, 2)))
         pv_qk(t, more && active(t + 1));
       }
     }
-    __syncthreads();
+    // no barrier between the two halves of an iteration: tiles are staged into buffers that
+    // nobody reads during this iteration, and the half-tile offset between the two wavefronts
+    // of a SIMD is re-established by the barrier at the end of every iteration
     if (late) {
       if (active(t)) pv_qk(t, more && active(t + 1));
     } else if (more && active(t + 1)) {
