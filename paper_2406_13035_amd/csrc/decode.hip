@@ -205,7 +205,7 @@ template <typename T, typename OT, int D, int G>
 __global__ __launch_bounds__(128) void decode_prepare(DecodeArgs a, const T* __restrict__ q, View qv,
                                                       const T* __restrict__ kn, View kv, const T* __restrict__ vn,
                                                       View vv) {
-  __shared__ double red[2];
+  __shared__ double red[2 * kCand];
   const int li = blockIdx.y, l = a.layer0 + li, b = blockIdx.x / a.Hkv, hk = blockIdx.x % a.Hkv;
   const int64_t lbh = (int64_t(l) * a.B + b) * a.Hkv + hk;
   const int count = a.ccount[lbh];
@@ -225,14 +225,25 @@ __global__ __launch_bounds__(128) void decode_prepare(DecodeArgs a, const T* __r
 #pragma unroll
   for (int g = 0; g < G; ++g)
     if (c < D) vec[g * D + c] = Elem<T>::to_f64(q[li * qv.sn + b * qv.sb + (hk * G + g) * qv.sh + c]);
+  // the candidates' keys: all slot numbers first, then all rows, then one exchange for the
+  // three norms (one memory round trip each instead of one per candidate)
+  int cs[kCand];
+#pragma unroll
+  for (int i = 0; i < kCand; ++i) cs[i] = a.cand[lbh * kCand + i];  // older slots: never the one just written
+  double x[kCand], part[kCand];
+#pragma unroll
+  for (int i = 0; i < kCand; ++i) x[i] = (cs[i] >= 0 && c < D) ? Elem<T>::to_f64(Kc[int64_t(cs[i]) * D + c]) : 0.0;
+#pragma unroll
   for (int i = 0; i < kCand; ++i) {
-    const int cs = a.cand[lbh * kCand + i];  // an older slot: never the one just written
-    double x = 0.0;
-    if (cs >= 0 && c < D) x = Elem<T>::to_f64(Kc[int64_t(cs) * D + c]);
-    if (c < D) vec[(G + i) * D + c] = x;
-    const double n2 = block_sum(x * x, red);
-    if (c == 0) a.cnorm[lbh * kCand + i] = sqrt(n2);
+    if (c < D) vec[(G + i) * D + c] = x[i];
+    part[i] = wave_sum(x[i] * x[i]);
   }
+  if ((c & 63) == 0) {
+#pragma unroll
+    for (int i = 0; i < kCand; ++i) red[(c >> 6) * kCand + i] = part[i];
+  }
+  __syncthreads();
+  if (c < kCand) a.cnorm[lbh * kCand + c] = sqrt(red[c] + red[kCand + c]);  // wavefront 0's sum first
 }
 
 // Eq. 9 arg-max result -> Eq. 10 threshold, Eq. 11-12 merge with one source, slot bookkeeping.
