@@ -100,7 +100,7 @@ void layout(d2o_ctx* x, char* persistent, char* scratch, size_t* pbytes, size_t*
   s.take(x->g_off, bh * (np + 1));
   s.take(x->g_cur, bh * (np + 1));
   s.take(x->g_src, bh * np);
-  s.take(x->d_logit, B * Hq * slots);
+  s.take(x->d_logit, nch * B * Hq * kChunk);
   const size_t nsub = nch * 4;  // partial results are kept per 64 slots, a quarter of a chunk
   s.take(x->d_rec, bh * nsub * 32);
   s.take(x->d_pacc, bh * nsub * G * d);

@@ -102,9 +102,9 @@ struct d2o_ctx {
   int32_t* g_cur = nullptr;      // [..][npad+1] fill cursors
   int32_t* g_src = nullptr;      // evicted ranks grouped by target (unordered inside a group)
   // decode
-  double* d_logit = nullptr;     // [B][Hq][slots]        exp(logit - chunk max)
-  double* d_rec = nullptr;       // [B][Hkv][4 nchunk][32] per 64 slots: softmax maxima and sums, candidates' best cosine and slot
-  float* d_pacc = nullptr;       // [B][Hkv][4 nchunk][G][d] partial outputs
+  double* d_logit = nullptr;     // [nchunk][B][Hkv][G][256] exp(logit - sub-chunk max), chunk-major
+  double* d_rec = nullptr;       // [nchunk][B][Hkv][4][32] per 64 slots: softmax maxima and sums, candidates' best cosine and slot
+  float* d_pacc = nullptr;       // [nchunk][B][Hkv][4][G][d] partial outputs
   double* d_vecs = nullptr;      // [L][B][Hkv][G + candidates][d] queries and candidate keys, fp64
   double* d_cnorm = nullptr;     // [L][B][Hkv][candidates] norms of the candidate keys
 };

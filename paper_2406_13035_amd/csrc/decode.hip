@@ -58,18 +58,17 @@ struct DecodeArgs {
   int32_t* cpos;
   int32_t* cand;      // [L][B][Hkv][kCand] candidate slots for this step, -1 = none
   uint32_t* ticket;   // [L][B][Hkv] finished chunks of the running step
-  double* elog;       // [B][Hq][slots] exp(logit - sub-chunk max)
-  double* rec;        // [B][Hkv][nsub][kRec] per sub-chunk record: [0..8) softmax maxima of the G
+  double* elog;       // [chunk][B][Hkv][G][256] exp(logit - sub-chunk max)
+  double* rec;        // [chunk][B][Hkv][4][kRec] per sub-chunk record: [0..8) softmax maxima of the G
                       // heads, [8..16) exp-sums relative to them, [16..16+kCand) the candidates' best
                       // cosine, [20..20+kCand) its slot (-1 none); one 256-byte line, written at once
-  float* pacc;        // [B][Hkv][nsub][G][d] partial outputs
+  float* pacc;        // [chunk][B][Hkv][G][d] partial outputs, relative to the chunk's softmax maximum
   double* vecs;       // [L][B][Hkv][G + kCand][d] queries and candidate keys as fp64
   double* cnorm;      // [L][B][Hkv][kCand] |k| of the candidates
   int32_t* ev_evicted;
   int32_t* ev_target;
   double* ev_ustar;
   int64_t slots;
-  int64_t nsub_cap;   // sub-chunk entries per (sequence, KV head) in the partial buffers
   int layer0, nl, B, Hkv, G, new_pos, n_sink, out_f32;
   double beta, tau_force;
   int32_t lay_off[kMaxLayersPerCall + 1];  // first flat chunk-group index of each entry of lay_id
@@ -127,6 +126,21 @@ __device__ __forceinline__ void raw_to_f64(const R& r, double* out) {
 #pragma unroll
     for (int i = 0; i < N; ++i) out[i] = double(__uint_as_float(raw_word(r, i)));
   }
+}
+
+// The partial results of a step are laid out chunk-major: [layer's chunk offset + chunk]
+// [sequence][KV head]...  Workgroups are dispatched head-fastest, so the results that are written
+// at about the same time are neighbours in memory (per-head contiguous arrays scatter them; a
+// streaming probe with this kernel's store pattern lost 6.2 -> 5.0 TB/s of read rate to the
+// scattered form and 6.2 -> 5.3 to this one).
+__device__ __forceinline__ int64_t sub_index(const DecodeArgs& a, int64_t bh, int chunk0, int c) {  // sub-chunk c of the head
+  return ((int64_t(chunk0) + (c >> 2)) * (a.B * a.Hkv) + bh) * 4 + (c & 3);
+}
+__device__ __forceinline__ int64_t chunk_index(const DecodeArgs& a, int64_t bh, int chunk0, int chunk) {  // chunk of the head
+  return (int64_t(chunk0) + chunk) * (a.B * a.Hkv) + bh;
+}
+__device__ __forceinline__ int64_t elog_index(const DecodeArgs& a, int64_t bh, int chunk0, int G, int g, int j) {  // slot j
+  return (((int64_t(chunk0) + (j >> 8)) * (a.B * a.Hkv) + bh) * G + g) * kChunk + (j & (kChunk - 1));
 }
 
 // Pins the point where a scalar-loaded value must have arrived; nothing is scheduled across it.
@@ -365,11 +379,9 @@ __device__ __forceinline__ void head_tail(const DecodeArgs& a, OT* __restrict__ 
   const int32_t* mt = a.meta + (l * a.B + b) * 4;
   const int64_t bh = int64_t(b) * a.Hkv + hk;
   const int64_t slot0 = bh * a.slots + mt[0];
-  const int64_t sbase = bh * a.nsub_cap + int64_t(mt[3]) * (kChunk / kSub);
-  const int64_t pbase = sbase * G;
+  const int ch0 = mt[3];  // the layer's first chunk in the partial-result arrays
   const T* Kc = static_cast<const T*>(a.cK) + slot0 * D;
   const T* Vc = static_cast<const T*>(a.cV) + slot0 * D;
-  const double* elog = a.elog + (int64_t(b) * a.Hkv * G + hk * G) * a.slots + mt[0];
   // ---- loads that depend on nothing: the threshold, this step's candidates, the last slot's row
   const double told = a.ctau[lbh];
   int cl[kCand];
@@ -389,7 +401,7 @@ __device__ __forceinline__ void head_tail(const DecodeArgs& a, OT* __restrict__ 
 #pragma unroll
   for (int g = 0; g < G; ++g) {
     double mx = -INFINITY;
-    for (int c = tid; c < nsub; c += 256) mx = fmax(mx, ld_agent(&a.rec[(sbase + c) * kRec + g]));
+    for (int c = tid; c < nsub; c += 256) mx = fmax(mx, ld_agent(&a.rec[sub_index(a, bh, ch0, c) * kRec + g]));
     mx = wave_max(mx);
     __syncthreads();
     if (lane == 0) sred[w] = mx;
@@ -397,7 +409,7 @@ __device__ __forceinline__ void head_tail(const DecodeArgs& a, OT* __restrict__ 
     mx = fmax(fmax(sred[0], sred[1]), fmax(sred[2], sred[3]));
     double part = 0.0;
     for (int c = tid; c < nsub; c += 256)
-      part += ld_agent(&a.rec[(sbase + c) * kRec + 8 + g]) * exp(ld_agent(&a.rec[(sbase + c) * kRec + g]) - mx);
+      part += ld_agent(&a.rec[sub_index(a, bh, ch0, c) * kRec + 8 + g]) * exp(ld_agent(&a.rec[sub_index(a, bh, ch0, c) * kRec + g]) - mx);
     Mg[g] = mx;
     Lg[g] = block_sum(part, sred);
   }
@@ -407,7 +419,7 @@ __device__ __forceinline__ void head_tail(const DecodeArgs& a, OT* __restrict__ 
 #pragma unroll
   for (int i = 0; i < kCand; ++i) cm[i] = Best{0.0, 0, -1};
   for (int c = tid; c < nsub; c += 256) {
-    const int64_t x = (sbase + c) * kRec;
+    const int64_t x = sub_index(a, bh, ch0, c) * kRec;
 #pragma unroll
     for (int i = 0; i < kCand; ++i) {
       const int s = int(ld_agent(&a.rec[x + 20 + i]));
@@ -440,8 +452,8 @@ __device__ __forceinline__ void head_tail(const DecodeArgs& a, OT* __restrict__ 
       ps[u] = a.cpos[slot0 + j];
 #pragma unroll
       for (int g = 0; g < G; ++g) {
-        e[u][g] = ld_agent(&elog[int64_t(g) * a.slots + j]);
-        ms[u][g] = ld_agent(&a.rec[(sbase + j / kSub) * kRec + g]);
+        e[u][g] = ld_agent(&a.elog[elog_index(a, bh, ch0, G, g, j)]);
+        ms[u][g] = ld_agent(&a.rec[sub_index(a, bh, ch0, j / kSub) * kRec + g]);
       }
     }
   };
@@ -476,27 +488,32 @@ __device__ __forceinline__ void head_tail(const DecodeArgs& a, OT* __restrict__ 
       __builtin_amdgcn_sched_barrier(0);  // one slot after the other: interleaving them costs registers
     }
   };
-  // ---- output rows: thread (rg, c4) adds the sub-chunks rg, rg + RG, ... of four columns, PB
+  // ---- output rows: thread (rg, c4) adds the chunks rg, rg + RG, ... of four columns, PB
   //      loads in flight; the groups' sums are added in ascending order
   const int c4 = tid % C4, rg = tid / C4;
+  const int nchunk = (nsub + 3) / 4;
 #pragma unroll
   for (int g = 0; g < G; ++g) {
     float num[4] = {0.f, 0.f, 0.f, 0.f};
-    for (int c0 = rg; c0 < nsub; c0 += PB * RG) {
+    for (int c0 = rg; c0 < nchunk; c0 += PB * RG) {
       float4 v[PB];
-      float f[PB];
+      double mc[PB];
 #pragma unroll
       for (int u = 0; u < PB; ++u) {
-        const int c = c0 + u * RG, cc = min(c, nsub - 1);
-        v[u] = ld_agent4(a.pacc + (pbase + int64_t(cc) * G + g) * D + c4 * 4);
-        f[u] = c < nsub ? float(exp(ld_agent(&a.rec[(sbase + cc) * kRec + g]) - Mg[g])) : 0.f;
+        const int cc = min(c0 + u * RG, nchunk - 1);
+        v[u] = ld_agent4(a.pacc + (chunk_index(a, bh, ch0, cc) * G + g) * D + c4 * 4);
+        mc[u] = -INFINITY;  // the chunk's maximum: that of its sub-chunks
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+          if (cc * 4 + i < nsub) mc[u] = fmax(mc[u], ld_agent(&a.rec[sub_index(a, bh, ch0, cc * 4 + i) * kRec + g]));
       }
 #pragma unroll
       for (int u = 0; u < PB; ++u) {
-        num[0] = fmaf(v[u].x, f[u], num[0]);
-        num[1] = fmaf(v[u].y, f[u], num[1]);
-        num[2] = fmaf(v[u].z, f[u], num[2]);
-        num[3] = fmaf(v[u].w, f[u], num[3]);
+        const float f = c0 + u * RG < nchunk ? float(exp(mc[u] - Mg[g])) : 0.f;
+        num[0] = fmaf(v[u].x, f, num[0]);
+        num[1] = fmaf(v[u].y, f, num[1]);
+        num[2] = fmaf(v[u].z, f, num[2]);
+        num[3] = fmaf(v[u].w, f, num[3]);
       }
     }
     lds_barrier();
@@ -624,6 +641,7 @@ __global__ __launch_bounds__(256) void decode_attend(DecodeArgs a, OT* __restric
   typedef typename RawBits<ES * sizeof(T)>::type Raw;
   __shared__ __attribute__((aligned(16))) unsigned char stage[kStageBytes];
   __shared__ float ps[4][G][kSub];
+  __shared__ double wmax[4][G];  // per wavefront: softmax maximum of its sub-chunk (-inf: no rows)
   __shared__ int sh_last;
 
   // Grid: x = head (fastest), y = flat chunk group over the layers.  Workgroups go round-robin to
@@ -680,7 +698,10 @@ __global__ __launch_bounds__(256) void decode_attend(DecodeArgs a, OT* __restric
   for (int it = 0; it < kGroup; ++it) {
     const int sub = sub0 + it * (kChunk / kSub);
     const int rows = min(kSub, total - sub * kSub);  // <= 0: nothing (more) for this wavefront
-    if (rows <= 0) break;
+    if (rows <= 0) {  // nothing (more) for this wavefront: it only takes part in the combination
+      if (ln < G) wmax[w][ln] = -INFINITY;
+      break;
+    }
     // With more than one pass, address arithmetic hoisted out of the loop would cost more
     // registers than the occupancy allows; an opaque lane number keeps it inside.
     if (kGroup > 1) asm volatile("" : "+v"(ln));
@@ -753,7 +774,7 @@ __global__ __launch_bounds__(256) void decode_attend(DecodeArgs a, OT* __restric
       }
     }
     // ---- softmax statistics of the sub-chunk; the lane owns cache row sub*kSub + lane
-    const int64_t pidx = (bh * a.nsub_cap + int64_t(mt3) * (kChunk / kSub) + sub) * G;
+    const int64_t pidx = sub_index(a, bh, mt3, sub) * G;
     double recv = 0.0;  // this lane's element of the sub-chunk record
 #pragma unroll
     for (int g = 0; g < G; ++g) {
@@ -761,9 +782,12 @@ __global__ __launch_bounds__(256) void decode_attend(DecodeArgs a, OT* __restric
       const double mx = fast_wave_max(valid ? sg : -INFINITY);
       const double e = valid ? exp(sg - mx) : 0.0;
       ps[w][g][ln] = float(e);
-      if (valid) st_agent(&a.elog[(int64_t(b) * a.Hkv * G + hk * G + g) * a.slots + mt0 + j], e);
+      if (valid) st_agent(&a.elog[elog_index(a, bh, mt3, G, g, j)], e);
       const double sm = fast_wave_sum(e);
-      if (ln == g) recv = mx;
+      if (ln == g) {
+        recv = mx;
+        wmax[w][g] = mx;
+      }
       if (ln == 8 + g) recv = sm;
     }
     // candidates: cosine of this row against each candidate key (Eq. 9), sub-chunk arg-max
@@ -797,9 +821,11 @@ __global__ __launch_bounds__(256) void decode_attend(DecodeArgs a, OT* __restric
         for (int e = 0; e < kVec; ++e) pv[g][e] = fmaf(p, x[e], pv[g][e]);
       }
     }
-    // sum over the row groups, then one full-width store per query head: lane i writes
-    // columns 2i, 2i+1 (the staging area is free again and serves as the exchange buffer)
+    // sum over the row groups; the wavefront's partial rows (one per query head) go to its
+    // staging area, which is free again, for the combination over the workgroup
     float* xch = reinterpret_cast<float*>(mine);
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
 #pragma unroll
     for (int g = 0; g < G; ++g) {
 #pragma unroll
@@ -809,19 +835,36 @@ __global__ __launch_bounds__(256) void decode_attend(DecodeArgs a, OT* __restric
         for (int o = TPR; o < 64; o <<= 1) t += __shfl_xor(t, o, 64);
         pv[g][e] = t;
       }
-      __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-      __builtin_amdgcn_wave_barrier();
       if (tr == 0) {
 #pragma unroll
-        for (int e = 0; e < kVec; ++e) xch[tc * kVec + e] = pv[g][e];
+        for (int e = 0; e < kVec; ++e) xch[g * D + tc * kVec + e] = pv[g][e];
       }
-      __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-      __builtin_amdgcn_wave_barrier();
-      for (int c = ln * 2; c < D; c += 128)
-      {
-        const uint64_t two = uint64_t(__float_as_uint(xch[c])) | (uint64_t(__float_as_uint(xch[c + 1])) << 32);
-        st_agent(reinterpret_cast<uint64_t*>(a.pacc + (pidx + g) * D + c), two);
+    }
+  }
+  // ---- one partial output row per chunk and query head: the four wavefronts' rows, each
+  //      rescaled from its sub-chunk's maximum to the chunk's (fp32, like the rows themselves).
+  //      A quarter of the partial-output bytes of a row per sub-chunk: on this chip a written
+  //      byte costs the stream of K and V rows several read bytes.
+  static_assert(kGroup == 1, "one chunk per workgroup");
+  lds_barrier();
+  for (int g = w; g < G; g += 4) {
+    double mc = wmax[0][g];
+#pragma unroll
+    for (int i = 1; i < 4; ++i) mc = fmax(mc, wmax[i][g]);
+    if (lane * 2 < D) {
+      float o0 = 0.f, o1 = 0.f;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const double mw = wmax[i][g];
+        if (mw != -INFINITY) {
+          const float f = expf(float(mw - mc));
+          const float* xr = reinterpret_cast<const float*>(stage + i * 64 * kPitch) + g * D + lane * 2;
+          o0 = fmaf(f, xr[0], o0);
+          o1 = fmaf(f, xr[1], o1);
+        }
       }
+      const uint64_t two = uint64_t(__float_as_uint(o0)) | (uint64_t(__float_as_uint(o1)) << 32);
+      st_agent(reinterpret_cast<uint64_t*>(a.pacc + (chunk_index(a, bh, mt3, grp) * G + g) * D + lane * 2), two);
     }
   }
   // ---- ticket: the last workgroup of the head to arrive closes the head.  Every store above
@@ -908,7 +951,6 @@ hipError_t launch_decode(d2o_ctx* c, int layer0, int nl_all, View q, View k, Vie
   a.ev_target = c->ev_target;
   a.ev_ustar = c->ev_ustar;
   a.slots = cf.slots_per_seq;
-  a.nsub_cap = c->nchunk_cap * (kChunk / kSub);
   a.B = cf.batch;
   a.Hkv = cf.n_kv_heads;
   a.G = cf.n_q_heads / cf.n_kv_heads;
