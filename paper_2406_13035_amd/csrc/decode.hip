@@ -40,8 +40,9 @@ namespace {
 
 constexpr int kCand = 3;                // eviction candidates whose similarities ride along with the attention pass
 constexpr int kMaxLayersPerCall = 64;
-constexpr int kRec = 32;                // doubles per sub-chunk record
-static_assert(kCand <= 4, "record layout holds four candidates");
+// Doubles per sub-chunk record: the G softmax maxima, the G exp-sums, then per candidate its
+// best cosine and that key's slot; rounded up to a multiple of eight (64 bytes).
+__host__ __device__ constexpr int rec_doubles(int G) { return (2 * G + 2 * kCand + 7) / 8 * 8; }
 constexpr int kPiece = 128;             // bytes of a cache row staged per LDS round
 constexpr int kPitch = kPiece + 16;     // LDS pitch of a staged row piece: conflict-free b128 reads
 constexpr int kStageBytes = 4 * 64 * kPitch;
@@ -59,9 +60,9 @@ struct DecodeArgs {
   int32_t* cand;      // [L][B][Hkv][kCand] candidate slots for this step, -1 = none
   uint32_t* ticket;   // [L][B][Hkv] finished chunks of the running step
   double* elog;       // [chunk][B][Hkv][G][256] exp(logit - sub-chunk max)
-  double* rec;        // [chunk][B][Hkv][4][kRec] per sub-chunk record: [0..8) softmax maxima of the G
-                      // heads, [8..16) exp-sums relative to them, [16..16+kCand) the candidates' best
-                      // cosine, [20..20+kCand) its slot (-1 none); one 256-byte line, written at once
+  double* rec;        // [chunk][B][Hkv][4][rec_doubles(G)] per sub-chunk record: [0..G) softmax maxima of the
+                      // query heads, [G..2G) exp-sums relative to them, [2G..2G+kCand) the candidates' best
+                      // cosine, [2G+kCand..2G+2kCand) its slot (-1 none); written with one store
   float* pacc;        // [chunk][B][Hkv][G][d] partial outputs, relative to the chunk's softmax maximum
   double* vecs;       // [L][B][Hkv][G + kCand][d] queries and candidate keys as fp64
   double* cnorm;      // [L][B][Hkv][kCand] |k| of the candidates
@@ -370,6 +371,7 @@ template <typename T, typename OT, int D, int G>
 __device__ __forceinline__ void head_tail(const DecodeArgs& a, OT* __restrict__ out, const View& ov, int li, int b,
                                           int hk, int64_t lbh, int total, int nsub, double* sred, int* ired,
                                           float* fred, double* dred, unsigned char* park) {
+  constexpr int kRec = rec_doubles(G);
   constexpr int U = G >= 4 ? 1 : 4 / G;               // slots per thread and batch of the score pass
   constexpr int C4 = D / 4;                           // threads across an output row (four columns each)
   constexpr int RG = 256 / C4;                        // groups of threads that share the sub-chunks
@@ -409,7 +411,7 @@ __device__ __forceinline__ void head_tail(const DecodeArgs& a, OT* __restrict__ 
     mx = fmax(fmax(sred[0], sred[1]), fmax(sred[2], sred[3]));
     double part = 0.0;
     for (int c = tid; c < nsub; c += 256)
-      part += ld_agent(&a.rec[sub_index(a, bh, ch0, c) * kRec + 8 + g]) * exp(ld_agent(&a.rec[sub_index(a, bh, ch0, c) * kRec + g]) - mx);
+      part += ld_agent(&a.rec[sub_index(a, bh, ch0, c) * kRec + G + g]) * exp(ld_agent(&a.rec[sub_index(a, bh, ch0, c) * kRec + g]) - mx);
     Mg[g] = mx;
     Lg[g] = block_sum(part, sred);
   }
@@ -422,9 +424,9 @@ __device__ __forceinline__ void head_tail(const DecodeArgs& a, OT* __restrict__ 
     const int64_t x = sub_index(a, bh, ch0, c) * kRec;
 #pragma unroll
     for (int i = 0; i < kCand; ++i) {
-      const int s = int(ld_agent(&a.rec[x + 20 + i]));
+      const int s = int(ld_agent(&a.rec[x + 2 * G + kCand + i]));
       if (s >= 0) {
-        const double u = ld_agent(&a.rec[x + 16 + i]);
+        const double u = ld_agent(&a.rec[x + 2 * G + i]);
         const int p = a.cpos[slot0 + s];
         if (better_match(u, p, s, cm[i])) cm[i] = Best{u, p, s};
       }
@@ -636,6 +638,7 @@ __global__ __launch_bounds__(256) void decode_attend(DecodeArgs a, OT* __restric
   constexpr int RPI = 64 / TPR;                 // V pass: rows per load instruction
   constexpr int NVL = kSub / RPI;               // V pass: loads per lane
   constexpr int NV = G + kCand;
+  constexpr int kRec = rec_doubles(G);
   constexpr int ES = NV <= 4 ? 4 : 2;           // elements per K-pass step (scalar register budget)
   constexpr int NST = EP / ES;                  // steps per piece (even)
   typedef typename RawBits<ES * sizeof(T)>::type Raw;
@@ -788,7 +791,7 @@ __global__ __launch_bounds__(256) void decode_attend(DecodeArgs a, OT* __restric
         recv = mx;
         wmax[w][g] = mx;
       }
-      if (ln == 8 + g) recv = sm;
+      if (ln == G + g) recv = sm;
     }
     // candidates: cosine of this row against each candidate key (Eq. 9), sub-chunk arg-max
     const double nrow = sqrt(nr);
@@ -797,8 +800,8 @@ __global__ __launch_bounds__(256) void decode_attend(DecodeArgs a, OT* __restric
       const double den = cn[c] * nrow;
       const double u = den > 0.0 ? acc[G + c] / den : 0.0;
       const Best m = fast_wave_best_match(u, pos, (valid && cs[c] >= 0 && j != cs[c]) ? j : -1);
-      if (ln == 16 + c) recv = m.u;
-      if (ln == 20 + c) recv = double(m.slot);
+      if (ln == 2 * G + c) recv = m.u;
+      if (ln == 2 * G + kCand + c) recv = double(m.slot);
     }
     if (ln < kRec) st_agent(&a.rec[(pidx / G) * kRec + ln], recv);  // the record in one store
     // ---- partial P V, fp32: TPR lanes per row, RPI rows per load, then a sum over the row groups
