@@ -154,6 +154,11 @@ def main():
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="profiling aid: also run three elementwise copies of 1 GiB (reads 1 GiB, "
                          "writes 1 GiB each), the known traffic that scales the HBM byte counters")
+    ap.add_argument("--zero-data-probe", action="store_true",
+                    help="profiling aid: after the measurement, time the two prompt-attention "
+                         "kernels of layer 0 on the workload's data and on all-zero Q, K, V (same "
+                         "instruction stream; the difference is what the chip's power management "
+                         "takes for operands that toggle)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (one GPU's share "
@@ -241,6 +246,24 @@ def main():
                             "avg_launch_ms": da_ms / da_n if da_n else None},
         "kernel_ms_per_launch": {k: (v[0] / v[1] if v[1] else None) for k, v in kt.items()},
     }
+    if args.zero_data_probe:
+        probe = {}
+        for tag, (q, k, v) in (("workload_data", (Q[0], K[0], V[0])),
+                               ("zero_data", tuple(torch.zeros_like(t) for t in (Q[0], K[0], V[0])))):
+            ctx.d2o_reset()
+            ctx.d2o_timing_enable(False)
+            ctx.d2o_prefill_attend(0, q, k, v, O)
+            ctx.d2o_timing_enable(True)
+            for kk in ("attn_fwd", "colsum"):
+                ctx.d2o_timing_read(kk)
+            for _ in range(5):
+                ctx.d2o_prefill_attend(0, q, k, v, O)
+            torch.cuda.synchronize()
+            for kk in ("attn_fwd", "colsum"):
+                ms, cnt = ctx.d2o_timing_read(kk)
+                probe[f"{kk}_ms_{tag}"] = ms / cnt
+            ctx.d2o_timing_enable(False)
+        out["zero_data_probe"] = probe
     if args.calibrate_copy:
         src = torch.zeros(1 << 28, dtype=torch.int32, device=dev)
         dst = torch.empty_like(src)
