@@ -202,6 +202,17 @@ def main():
     wall = time.perf_counter() - t0
     kt = {k: ctx.d2o_timing_read(k) for k in binding.KERNEL_IDS}
     ctx.d2o_timing_enable(False)
+    # the same decode steps issued as one call per layer (a caller that interleaves the layers
+    # with its own work), continuing on the caches of the last step; outside the timed region
+    per_layer_steps = 0 if args.layers else min(32, dsteps)  # not in the counter-profiling runs
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    ev[0].record()
+    for t in range(per_layer_steps):
+        for l in range(w.n_layers):
+            ctx.d2o_decode_step(l, 1, dq[t][l:l + 1], dk[t][l:l + 1], dv[t][l:l + 1], dout[l:l + 1])
+    ev[1].record()
+    torch.cuda.synchronize()
+    per_layer_ms = ev[0].elapsed_time(ev[1]) / per_layer_steps if per_layer_steps else None
 
     n, d, L = w.prompt_len, w.head_dim, w.n_layers
     decode_ms = float(np.mean(dec))
@@ -232,6 +243,7 @@ def main():
                    "density_F_seq0_min_max": [float(F[0].min()), float(F[0].max())]},
         "prefill_compress_ms_per_layer": prefill_ms / L,
         "decode_ms_per_step": decode_ms / dsteps,
+        "decode_ms_per_step_one_call_per_layer": per_layer_ms,
         "decode_step_hbm_frac": step_bytes / (decode_ms / dsteps * 1e-3) / 1e9 / PEAK_HBM_GBS,
         "roofline": {"kernel": "attn_fwd (prefill attention pass 1)", "bound": "mfma",
                      "achieved": attn_tflops, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
