@@ -354,6 +354,41 @@ def test_cfg1_end_to_end_free_running():
     ctx.close()
 
 
+def test_decode_all_layers_in_one_call_equals_one_call_per_layer():
+    """The layers of a decode call are independent (Sec. 4: every stage lives inside one layer's
+    KV group), so one call over three layers of very different budgets and three calls of one
+    layer each must leave bit-identical outputs, events and caches.  Covers the layer table of
+    the multi-layer launch (layers sorted by size, chunk -> layer search, per-layer strides)."""
+    w, n, L, B, steps = _small_bf16(True), 700, 3, 2, 6
+    budgets = [np.array([520, 300], np.int32), np.array([40, 64], np.int32), np.array([260, 130], np.int32)]
+    ctxs = [H.new_ctx(w, B, L, n, sum(int(b.max()) for b in budgets) + 3 * 8) for _ in range(2)]
+    for l in range(L):
+        Q, K, V = H.make_inputs(w, B, l, n)
+        for ctx in ctxs:
+            ctx.d2o_prefill_compress(l, Q, K, V, budgets[l], budgets[l] // 4)
+    q, k, v = H.decode_inputs(w, B, list(range(L)), steps)
+    outs = [torch.zeros(q[0].shape, dtype=ctxs[0].out_dtype, device=q.device) for _ in range(2)]
+    for t in range(steps):
+        ctxs[0].d2o_decode_step(0, L, q[t], k[t], v[t], outs[0])
+        for l in (2, 0, 1):  # any order
+            ctxs[1].d2o_decode_step(l, 1, q[t][l:l + 1], k[t][l:l + 1], v[t][l:l + 1], outs[1][l:l + 1])
+        torch.cuda.synchronize()
+        assert torch.equal(outs[0], outs[1]), f"outputs differ at step {t}"
+        for l in range(L):
+            ea, eb = ctxs[0].d2o_last_events(l), ctxs[1].d2o_last_events(l)
+            for x, y in zip(ea, eb):
+                assert np.array_equal(x, y, equal_nan=True), f"events differ at step {t}, layer {l}"
+    for l in range(L):
+        for b in range(B):
+            for h in range(w.n_kv_heads):
+                ca = ctxs[0].d2o_cache_export(l, b, h, int(budgets[l][b]) + 1)
+                cb = ctxs[1].d2o_cache_export(l, b, h, int(budgets[l][b]) + 1)
+                for x, y in zip(ca, cb):
+                    assert np.array_equal(np.asarray(x), np.asarray(y)), f"cache differs: layer {l}, b {b}, head {h}"
+    for ctx in ctxs:
+        ctx.close()
+
+
 def test_error_paths_return_codes():
     w, n = _small_bf16(False), 256
     Q, K, V = H.make_inputs(w, 1, 0, n)
