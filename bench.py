@@ -154,6 +154,9 @@ def main():
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="profiling aid: also run three elementwise copies of 1 GiB (reads 1 GiB, "
                          "writes 1 GiB each), the known traffic that scales the HBM byte counters")
+    ap.add_argument("--skip-per-layer-decode", action="store_true",
+                    help="profiling aid: leave out the extra decode steps issued as one call per "
+                         "layer, so that a kernel trace holds the all-layers launches only")
     ap.add_argument("--zero-data-probe", action="store_true",
                     help="profiling aid: after the measurement, time the two prompt-attention "
                          "kernels of layer 0 on the workload's data and on all-zero Q, K, V (same "
@@ -204,7 +207,7 @@ def main():
     ctx.d2o_timing_enable(False)
     # the same decode steps issued as one call per layer (a caller that interleaves the layers
     # with its own work), continuing on the caches of the last step; outside the timed region
-    per_layer_steps = 0 if args.layers else min(32, dsteps)  # not in the counter-profiling runs
+    per_layer_steps = 0 if (args.layers or args.skip_per_layer_decode) else min(32, dsteps)
     ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
     ev[0].record()
     for t in range(per_layer_steps):

@@ -203,7 +203,9 @@ __global__ __launch_bounds__(256) void invnorm_bf16(const uint16_t* __restrict__
 //   COLLECT = true: second sweep over the flagged rows only (compacted list): every retained
 //     key whose fp32 cosine reaches the row's threshold is appended to the row's candidate
 //     list (up to kMaxCand; more than that falls back to the exhaustive search).  The sweep
-//     repeats the first one's arithmetic exactly, so the best value is found again.
+//     repeats the first one's arithmetic exactly, so the best value is found again.  Few rows are
+//     flagged (a workgroup or two per head), so the retained keys are split over `ksplit`
+//     workgroups per row block: the lists are appended with atomics and read order-free.
 // kAmbiguous bounds twice the fp32 error of one cosine: at most one rounding per accumulated
 // product (128 * 2^-24 of |k_i||k_j|) plus the two fp32 inverse norms, 1.6e-5 in total.
 constexpr float kAmbiguous = 2.0e-5f;
@@ -221,7 +223,7 @@ __global__ __launch_bounds__(256) void match_filter_bf16(const uint16_t* __restr
                                                          float* __restrict__ thr, const int32_t* __restrict__ amb_list,
                                                          const int32_t* __restrict__ amb_cnt,
                                                          int32_t* __restrict__ ncand, int32_t* __restrict__ clist,
-                                                         int npad) {
+                                                         int npad, int ksplit) {
   constexpr int kTile = 64;     // retained keys per LDS tile
   constexpr int NCH = kTile * 16 / 256;  // 16-byte chunks of a tile per thread
   __shared__ __attribute__((aligned(16))) uint16_t Rs[2][kTile * kLdM];
@@ -231,7 +233,7 @@ __global__ __launch_bounds__(256) void match_filter_bf16(const uint16_t* __restr
   const int64_t bh = int64_t(b) * Hkv + hk;
   const int nret = cnt[bh * 2], nevi = cnt[bh * 2 + 1];
   const int nrows = COLLECT ? amb_cnt[bh] : nevi;
-  const int e0 = blockIdx.x * 128;
+  const int e0 = (int(blockIdx.x) / ksplit) * 128, part = int(blockIdx.x) % ksplit;
   if (e0 >= nrows) return;
   const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, m = lane & 31, h = lane >> 5;
   const uint16_t* kb = K + b * kv.sb + hk * kv.sh;
@@ -256,6 +258,9 @@ __global__ __launch_bounds__(256) void match_filter_bf16(const uint16_t* __restr
   u32x4 rgA[NCH], rgB[NCH];
   float rvA = 0.f, rvB = 0.f;
   const int ntile = (nret + kTile - 1) / kTile;
+  const int tper = (ntile + ksplit - 1) / ksplit;
+  const int tbeg = part * tper, tend = min(ntile, tbeg + tper);  // this workgroup's tiles
+  if (tbeg >= tend) return;
   auto issue = [&](int t, u32x4 (&rg)[NCH], float& rv) {
     const int r0 = t * kTile;
 #pragma unroll
@@ -278,7 +283,7 @@ __global__ __launch_bounds__(256) void match_filter_bf16(const uint16_t* __restr
   };
   auto one_tile = [&](int t, u32x4 (&far)[NCH], float& vfar, const u32x4 (&next)[NCH], const float& vnext) {
     const int buf = t & 1, r0 = t * kTile;
-    if (t + 2 < ntile) issue(t + 2, far, vfar);
+    if (t + 2 < tend) issue(t + 2, far, vfar);
     const int nsub = min(kTile / 32, (nret - r0 + 31) / 32);
     for (int st = 0; st < nsub; ++st) {
       bf16x8 a[8];
@@ -308,16 +313,16 @@ __global__ __launch_bounds__(256) void match_filter_bf16(const uint16_t* __restr
         }
       }
     }
-    if (t + 1 < ntile) stage(buf ^ 1, next, vnext);
+    if (t + 1 < tend) stage(buf ^ 1, next, vnext);
     __syncthreads();
   };
-  issue(0, rgA, rvA);
-  stage(0, rgA, rvA);
-  if (ntile > 1) issue(1, rgB, rvB);
+  issue(tbeg, rgA, rvA);
+  stage(tbeg & 1, rgA, rvA);
+  if (tbeg + 1 < tend) issue(tbeg + 1, rgB, rvB);
   __syncthreads();
-  for (int t = 0; t < ntile; t += 2) {
+  for (int t = tbeg; t < tend; t += 2) {
     one_tile(t, rgA, rvA, rgB, rvB);
-    if (t + 1 < ntile) one_tile(t + 1, rgB, rvB, rgA, rvA);
+    if (t + 1 < tend) one_tile(t + 1, rgB, rvB, rgA, rvA);
   }
   if (COLLECT) return;
   // combine the two lane halves that share an evicted row
@@ -796,14 +801,15 @@ hipError_t launch_match(d2o_ctx* c, int layer, View K, int n, hipStream_t s) {
                                                   c->meta + size_t(layer) * cf.batch * 4, cf.slots_per_seq,
                                                   c->invnorm, c->sel_ret, c->sel_evi,
                                                   c->sel_cnt, c->m_cand, c->m_thr, c->amb_list, c->amb_cnt,
-                                                  c->m_ncand, c->m_clist, c->npad);
+                                                  c->m_ncand, c->m_clist, c->npad, 1);
       amb_compact_kernel<<<dim3(cf.n_kv_heads, cf.batch), 1024, 0, s>>>(c->m_cand, c->sel_cnt, c->amb_list,
                                                                         c->amb_cnt, c->m_ncand, c->npad);
-      match_filter_bf16<true><<<gf, 256, 0, s>>>((const uint16_t*)K.ptr, K, (const uint16_t*)c->cacheK,
+      constexpr int kSplit = 8;
+      match_filter_bf16<true><<<dim3(gf.x * kSplit, gf.y, gf.z), 256, 0, s>>>((const uint16_t*)K.ptr, K, (const uint16_t*)c->cacheK,
                                                  c->meta + size_t(layer) * cf.batch * 4, cf.slots_per_seq,
                                                  c->invnorm, c->sel_ret, c->sel_evi,
                                                  c->sel_cnt, c->m_cand, c->m_thr, c->amb_list, c->amb_cnt,
-                                                 c->m_ncand, c->m_clist, c->npad);
+                                                 c->m_ncand, c->m_clist, c->npad, kSplit);
     }
     KernelTimer kt(c, D2O_K_MATCH_REFINE, s);
     match_refine<uint16_t, 128><<<gr, 256, 0, s>>>((const uint16_t*)K.ptr, K, c->sel_ret, c->sel_evi, c->sel_cnt,
