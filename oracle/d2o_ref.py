@@ -109,9 +109,20 @@ def layer_density(colsums_per_q_head) -> float:
 
 # --------------------------------------------------------------------------- a3: budget allocation
 
-def allocate_budgets(F, seq_len: int, total_budget: int, min_budget: int = 64):
+ALLOCATION_POLICIES = ("softmax", "reciprocal", "exp_decay", "uniform")
+
+
+def allocate_budgets(F, seq_len: int, total_budget: int, min_budget: int = 64, policy: str = "softmax"):
     """Integer per-layer cache sizes S_l from the density statistics, Sec. 4.1 Eq. 5 and
     App. A.2: alpha_l proportional to exp(-F_l), sum_l S_l = total_budget (= round(rho*S*L)).
+
+    `policy` selects the design of alpha_l among the four that the allocation-policy analysis
+    of Sec. 5 compares: "softmax" (Eq. 5, the method's own, weight exp(-F_l)), "reciprocal"
+    (weight 1/F_l, needs F_l > 0), "uniform" (weight 1: alpha_l = rho for every layer) - these
+    three split the same total budget and differ only in the weight that enters step 1 below -
+    and "exp_decay" (alpha_l = exp(-F_l) taken as the layer's own compression ratio, not
+    normalised over the layers: S_l = floor(exp(-F_l) * seq_len) clipped to [min_budget,
+    seq_len]; the total budget is not used, as the definition has no sum constraint).
 
     The paper bounds neither S_l <= S nor S_l > 0, and gives no integer rule.  Reading:
       1. split the budget over the layers in proportion to exp(-F_l) (exponent shifted by
@@ -127,6 +138,15 @@ def allocate_budgets(F, seq_len: int, total_budget: int, min_budget: int = 64):
     Raises ValueError when n_layers*min_budget <= total_budget <= n_layers*seq_len fails."""
     F = np.asarray(F, dtype=np.float64)
     L = F.size
+    if policy not in ALLOCATION_POLICIES:
+        raise ValueError("unknown allocation policy")
+    if policy == "exp_decay":
+        if min_budget < 0 or min_budget > seq_len:
+            raise ValueError("infeasible bounds")
+        S = np.floor(np.exp(-F) * float(seq_len)).astype(np.int64)
+        return np.clip(S, min_budget, seq_len)
+    if policy == "reciprocal" and not np.all(F > 0.0):
+        raise ValueError("the reciprocal policy needs positive variances")
     if not (L * min_budget <= total_budget <= L * seq_len) or min_budget < 0:
         raise ValueError("infeasible total budget")
     S = np.zeros(L, dtype=np.int64)
@@ -135,7 +155,12 @@ def allocate_budgets(F, seq_len: int, total_budget: int, min_budget: int = 64):
     share = np.zeros(L)
     while free.any():
         idx = np.flatnonzero(free)
-        w = np.exp(-(F[idx] - F[idx].min()))
+        if policy == "softmax":
+            w = np.exp(-(F[idx] - F[idx].min()))
+        elif policy == "reciprocal":
+            w = 1.0 / F[idx]
+        else:
+            w = np.ones(idx.size)
         wsum = 0.0
         for x in w:                      # ascending layer order
             wsum += x

@@ -154,6 +154,37 @@ def test_allocation_integer_remainder_goes_to_largest_fractions():
     assert list(ref.allocate_budgets(np.zeros(3), 100, 11, 0)) == [4, 4, 3]
 
 
+def test_allocation_policies_of_the_policy_analysis():
+    """The four designs of alpha_l that Sec. 5 (dynamic allocation policy analysis) compares,
+    pinned to their closed forms on inputs whose shares are exact."""
+    # reciprocal of variance: weights 1 : 1/2 : 1/4 -> shares 4 : 2 : 1, exact for a multiple of 7
+    S = ref.allocate_budgets(np.array([1.0, 2.0, 4.0]), 10_000, 7 * 123, 1, policy="reciprocal")
+    assert list(S) == [4 * 123, 2 * 123, 123]
+    # uniform: every layer gets rho * S whatever its variance
+    S = ref.allocate_budgets(np.array([0.1, 9.0, 3.0, 50.0]), 4096, 4 * 819, 64, policy="uniform")
+    assert list(S) == [819] * 4
+    assert list(ref.allocate_budgets(np.array([5.0, 0.0, 1.0]), 100, 11, 0, policy="uniform")) == [4, 4, 3]
+    # exponential decay: alpha_l = exp(-F_l) is the layer's own ratio, no sum constraint
+    F = -np.log(np.array([0.3, 0.0625, 1.0, 1e-9]))
+    S = ref.allocate_budgets(F, 1005, 0, 8, policy="exp_decay")
+    assert list(S) == [301, 62, 1005, 8]               # 301.5, 62.8, all of it, clipped from 0
+    # the three normalised designs spend the same budget and are monotone in the variance;
+    # the softmax design is the one without a policy argument
+    F = rng.uniform(0.2, 3.0, size=12)
+    tot = 12 * 500
+    for pol in ("softmax", "reciprocal", "uniform"):
+        S = ref.allocate_budgets(F, 4000, tot, 16, policy=pol)
+        assert S.sum() == tot and S.min() >= 16 and S.max() <= 4000
+        assert np.all(np.diff(S[np.argsort(F)]) <= (1 if pol == "uniform" else 0))
+    assert np.array_equal(ref.allocate_budgets(F, 4000, tot, 16), ref.allocate_budgets(F, 4000, tot, 16, policy="softmax"))
+    want = (1.0 / F) / (1.0 / F).sum() * tot
+    assert np.all(np.abs(ref.allocate_budgets(F, 4000, tot, 1, policy="reciprocal") - want) < 1.0)
+    with pytest.raises(ValueError):
+        ref.allocate_budgets(np.array([1.0, 0.0]), 100, 50, 1, policy="reciprocal")
+    with pytest.raises(ValueError):
+        ref.allocate_budgets(np.array([1.0, 2.0]), 100, 50, 1, policy="softmin")
+
+
 # ------------------------------------------------------------------ selection (Eq. 7-8)
 
 @pytest.mark.parametrize("n,budget,recent,sink", [(30, 12, 3, 0), (30, 12, 4, 2), (17, 6, 6, 0),
