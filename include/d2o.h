@@ -118,6 +118,27 @@ int d2o_get_density(d2o_ctx* ctx, double* F_layers, double* F_heads, void* strea
 int d2o_allocate_budgets(const double* F, int32_t n_layers, int32_t seq_len,
                          int64_t total_budget, int32_t min_budget, int32_t* S_out);
 
+/* The designs of the layer allocation factor alpha_l that the allocation-policy analysis of
+ * Sec. 5 compares.  SOFTMAX is Eq. 5 (weight exp(-F_l)), RECIPROCAL weighs a layer by 1/F_l
+ * (every F_l must be positive), UNIFORM by 1 (alpha_l = rho): these three split total_budget
+ * exactly as d2o_allocate_budgets does (same clipping and integer rule) and differ only in
+ * the weight.  EXP_DECAY takes alpha_l = exp(-F_l) as the layer's own ratio: S_l =
+ * floor(exp(-F_l) * seq_len) clipped to [min_budget, seq_len]; it has no sum constraint and
+ * ignores total_budget. */
+typedef enum {
+  D2O_ALLOC_SOFTMAX = 0,
+  D2O_ALLOC_RECIPROCAL = 1,
+  D2O_ALLOC_EXP_DECAY = 2,
+  D2O_ALLOC_UNIFORM = 3
+} d2o_alloc_policy;
+
+/* d2o_allocate_budgets with the design of alpha_l chosen by `policy` (SOFTMAX gives the same
+ * result as d2o_allocate_budgets).  Pure host function on host arrays, fp64.
+ * Errors: INVALID_ARG (unknown policy, infeasible bounds or total, an F that is not finite,
+ * or not positive under RECIPROCAL). */
+int d2o_allocate_budgets_policy(int32_t policy, const double* F, int32_t n_layers, int32_t seq_len,
+                                int64_t total_budget, int32_t min_budget, int32_t* S_out);
+
 /* Replaces a layer's per-key scores by host values ([B][Hkv][n] floats) as if
  * d2o_prefill_attend had produced them (used to drive the token-level stages from given
  * scores).  Synchronises `stream`.  Errors: INVALID_ARG, STATE, HIP. */

@@ -18,7 +18,8 @@ LIB_PATH = os.environ.get("D2O_LIB", os.path.join(HERE, "libd2o.so"))
 D2O_F32, D2O_BF16 = 0, 1
 EXPORTS = [
     "d2o_workspace_bytes", "d2o_create", "d2o_destroy", "d2o_last_error", "d2o_reset",
-    "d2o_prefill_attend", "d2o_get_density", "d2o_allocate_budgets", "d2o_scores_import",
+    "d2o_prefill_attend", "d2o_get_density", "d2o_allocate_budgets", "d2o_allocate_budgets_policy",
+    "d2o_scores_import",
     "d2o_scores_export", "d2o_compress_layer", "d2o_prefill_compress", "d2o_decode_step",
     "d2o_layer_reserve", "d2o_cache_export", "d2o_cache_import", "d2o_last_events",
     "d2o_prefill_events", "d2o_timing_enable", "d2o_timing_read",
@@ -65,6 +66,7 @@ def load_library() -> C.CDLL:
     lib.d2o_prefill_attend.argtypes = [vp, i32, d2o_view, d2o_view, d2o_view, i32, d2o_view, vp]
     lib.d2o_get_density.argtypes = [vp, vp, vp, vp]
     lib.d2o_allocate_budgets.argtypes = [vp, i32, i32, i64, i32, vp]
+    lib.d2o_allocate_budgets_policy.argtypes = [i32, vp, i32, i32, i64, i32, vp]
     lib.d2o_scores_import.argtypes = [vp, i32, vp, i32, vp]
     lib.d2o_scores_export.argtypes = [vp, i32, vp, i32, vp]
     lib.d2o_compress_layer.argtypes = [vp, i32, d2o_view, d2o_view, i32, vp, vp, vp]
@@ -97,6 +99,21 @@ def d2o_allocate_budgets(F, seq_len: int, total_budget: int, min_budget: int = 6
     rc = lib.d2o_allocate_budgets(_np_ptr(F), F.size, seq_len, total_budget, min_budget, _np_ptr(S))
     if rc != 0:
         raise D2OError(f"d2o_allocate_budgets failed with {rc}")
+    return S
+
+
+ALLOC_POLICIES = {"softmax": 0, "reciprocal": 1, "exp_decay": 2, "uniform": 3}
+
+
+def d2o_allocate_budgets_policy(policy: str, F, seq_len: int, total_budget: int, min_budget: int = 64) -> np.ndarray:
+    """Layer budgets under one of the designs of alpha_l compared in Sec. 5 (host function)."""
+    lib = load_library()
+    F = np.ascontiguousarray(F, dtype=np.float64)
+    S = np.zeros(F.size, dtype=np.int32)
+    rc = lib.d2o_allocate_budgets_policy(ALLOC_POLICIES[policy], _np_ptr(F), F.size, seq_len, total_budget,
+                                         min_budget, _np_ptr(S))
+    if rc != 0:
+        raise D2OError(f"d2o_allocate_budgets_policy failed with {rc}")
     return S
 
 

@@ -287,10 +287,24 @@ int d2o_get_density(d2o_ctx* x, double* F_layers, double* F_heads, void* stream)
 // Sec. 4.1 Eq. 5 with the clipping and integer rules stated in d2o.h.
 int d2o_allocate_budgets(const double* F, int32_t L, int32_t seq_len, int64_t total, int32_t min_budget,
                          int32_t* S_out) {
+  return d2o_allocate_budgets_policy(D2O_ALLOC_SOFTMAX, F, L, seq_len, total, min_budget, S_out);
+}
+
+int d2o_allocate_budgets_policy(int32_t policy, const double* F, int32_t L, int32_t seq_len, int64_t total,
+                                int32_t min_budget, int32_t* S_out) {
   if (!F || !S_out || L < 1 || seq_len < 1 || min_budget < 0) return D2O_ERR_INVALID_ARG;
-  if (total < int64_t(L) * min_budget || total > int64_t(L) * seq_len) return D2O_ERR_INVALID_ARG;
+  if (policy < D2O_ALLOC_SOFTMAX || policy > D2O_ALLOC_UNIFORM) return D2O_ERR_INVALID_ARG;
   for (int l = 0; l < L; ++l)
-    if (!std::isfinite(F[l])) return D2O_ERR_INVALID_ARG;
+    if (!std::isfinite(F[l]) || (policy == D2O_ALLOC_RECIPROCAL && !(F[l] > 0.0))) return D2O_ERR_INVALID_ARG;
+  if (policy == D2O_ALLOC_EXP_DECAY) {  // the layer's own ratio, no sum constraint
+    if (min_budget > seq_len) return D2O_ERR_INVALID_ARG;
+    for (int l = 0; l < L; ++l) {
+      const double v = std::floor(std::exp(-F[l]) * double(seq_len));
+      S_out[l] = v < double(min_budget) ? min_budget : v > double(seq_len) ? seq_len : int32_t(v);
+    }
+    return D2O_OK;
+  }
+  if (total < int64_t(L) * min_budget || total > int64_t(L) * seq_len) return D2O_ERR_INVALID_ARG;
   std::vector<char> pinned(L, 0);
   std::vector<double> share(L, 0.0), w(L, 0.0);
   int64_t remaining = total;
@@ -307,7 +321,7 @@ int d2o_allocate_budgets(const double* F, int32_t L, int32_t seq_len, int64_t to
     double wsum = 0.0;
     for (int l = 0; l < L; ++l)
       if (!pinned[l]) {
-        w[l] = std::exp(-(F[l] - fmin));
+        w[l] = policy == D2O_ALLOC_SOFTMAX ? std::exp(-(F[l] - fmin)) : policy == D2O_ALLOC_RECIPROCAL ? 1.0 / F[l] : 1.0;
         wsum += w[l];
       }
     double excess = 0.0, deficit = 0.0;

@@ -67,6 +67,29 @@ def test_allocate_budgets_matches_oracle_bit_for_bit(lib):
         binding.d2o_allocate_budgets(np.array([0.0, np.nan]), 100, 50, 0)
 
 
+def test_allocation_policies_match_oracle_bit_for_bit(lib):
+    """The designs of alpha_l compared in Sec. 5 (allocation-policy analysis): the host function
+    against the oracle on random densities, bounds and totals."""
+    g = np.random.default_rng(77)
+    for trial in range(200):
+        L = int(g.integers(1, 40))
+        F = g.uniform(0.01, 1, size=L) * g.choice([0.3, 1.0, 10.0, 300.0])
+        if trial % 7 == 0:
+            F[:] = F[0]
+        n = int(g.choice([512, 4096, 32768]))
+        lo = int(g.choice([0, 1, 16, 64]))
+        tot = int(g.integers(L * lo, L * n + 1))
+        for pol in ref.ALLOCATION_POLICIES:
+            want = ref.allocate_budgets(F, n, tot, lo, policy=pol)
+            got = binding.d2o_allocate_budgets_policy(pol, F, n, tot, lo)
+            assert np.array_equal(got, want), (pol, F, n, tot, lo, got, want)
+        assert np.array_equal(binding.d2o_allocate_budgets_policy("softmax", F, n, tot, lo),
+                              binding.d2o_allocate_budgets(F, n, tot, lo))
+    with pytest.raises(binding.D2OError):
+        binding.d2o_allocate_budgets_policy("reciprocal", np.array([1.0, 0.0]), 100, 50, 0)
+    assert lib.d2o_allocate_budgets_policy(7, None, 1, 1, 1, 0, None) < 0
+
+
 def test_benchmark_allocations_have_the_stated_totals(lib):
     from paper_2406_13035_amd import synth
     for cfg in (2, 3, 4, 5):
