@@ -277,7 +277,7 @@ def ema_threshold(tau_prev: float, u_star: float, beta: float) -> float:
 
 # --------------------------------------------------------------------------- a8: merge
 
-def merge(Kc, Vc, Ke, Ve, u_star, target, passed, storage: str = "f64"):
+def merge(Kc, Vc, Ke, Ve, u_star, target, passed, storage: str = "f64", weighted: bool = True):
     """Similarity-weighted merge, Sec. 4.2.2 Eq. 11-12.
 
     Eq. 12 as printed gives every evicted token the same weight; the reading taken is the
@@ -286,7 +286,9 @@ def merge(Kc, Vc, Ke, Ve, u_star, target, passed, storage: str = "f64"):
     (e = exp(1) is the retained token's self-similarity term, so it keeps the largest weight).
     Keys and values share the weights.  All merges read pre-merge rows.  Sources are added
     in ascending evicted order.  Retained rows without sources are returned unchanged;
-    changed rows are rounded to `storage`.  Returns (K', V', group sizes)."""
+    changed rows are rounded to `storage`.  Returns (K', V', group sizes).
+    weighted=False is the "average merging" that the merge-policy ablation of Sec. 5 compares
+    against: the plain mean of the retained row and its sources (every weight 1, Z_j = 1 + n_j)."""
     Kc = np.array(Kc, dtype=np.float64)
     Vc = np.array(Vc, dtype=np.float64)
     Ke = np.asarray(Ke, dtype=np.float64)
@@ -298,11 +300,12 @@ def merge(Kc, Vc, Ke, Ve, u_star, target, passed, storage: str = "f64"):
         if passed[i]:
             groups.setdefault(int(target[i]), []).append(i)
     for j, src in groups.items():
-        z = E
-        ka = E * Kc[j]
-        va = E * Vc[j]
+        w_self = E if weighted else 1.0
+        z = w_self
+        ka = w_self * Kc[j]
+        va = w_self * Vc[j]
         for i in src:
-            w = math.exp(float(u_star[i]))
+            w = math.exp(float(u_star[i])) if weighted else 1.0
             z += w
             ka = ka + w * Ke[i]
             va = va + w * Ve[i]
@@ -336,11 +339,12 @@ class PrefillEvents:
 
 
 def compress_head(K, V, score, budget: int, recent: int, n_sink: int = 0,
-                  storage: str = "f64", tau_force: float = float("nan")):
+                  storage: str = "f64", tau_force: float = float("nan"), weighted: bool = True):
     """Token-level operation on one KV head after prompt encoding (Sec. 4.2): eviction
     (Eq. 7-8), matching on the pre-merge keys (Eq. 9), tau_0 (Eq. 10), merge (Eq. 11-12).
     The cumulative score of a slot that absorbs tokens is left unchanged (paper silent).
-    tau_force: NaN = Eq. 10; +inf = never merge (pure eviction); -inf = merge everything."""
+    tau_force: NaN = Eq. 10; +inf = never merge (pure eviction); -inf = merge everything.
+    weighted: Eq. 11-12 weights, or the ablation's average merging."""
     K = np.asarray(K, dtype=np.float64)
     V = np.asarray(V, dtype=np.float64)
     score = np.asarray(score, dtype=np.float64)
@@ -349,7 +353,7 @@ def compress_head(K, V, score, budget: int, recent: int, n_sink: int = 0,
     tau, passed = prefill_threshold(u_star)
     if not math.isnan(tau_force):
         passed = u_star >= tau_force
-    Kc, Vc, _ = merge(K[ret], V[ret], K[evi], V[evi], u_star, t, passed, storage)
+    Kc, Vc, _ = merge(K[ret], V[ret], K[evi], V[evi], u_star, t, passed, storage, weighted)
     cache = HeadCache(Kc, Vc, score[ret].copy(), ret.copy(), tau, storage)
     ev = PrefillEvents(ret, evi, ret[t] if len(evi) else np.zeros(0, dtype=np.int64),
                        u_star, passed, tau)
@@ -367,7 +371,7 @@ class DecodeEvent:
 
 
 def decode_step_head(cache: HeadCache, q, k_new, v_new, new_pos: int, budget: int, recent: int,
-                     n_sink: int, beta: float, tau_force: float = float("nan")):
+                     n_sink: int, beta: float, tau_force: float = float("nan"), weighted: bool = True):
     """One generation step on one KV head (Sec. 3 Eq. 2-3; Sec. 4.2 Eq. 6-12).
 
     q [G, d] are the queries of the G query heads sharing this KV head (their softmax rows
@@ -411,7 +415,7 @@ def decode_step_head(cache: HeadCache, q, k_new, v_new, new_pos: int, budget: in
     target_pos = -1
     if do_merge:
         Km, Vm, _ = merge(cache.K[[tj]], cache.V[[tj]], cache.K[[e]], cache.V[[e]],
-                          np.array([u]), np.array([0]), np.array([True]), cache.storage)
+                          np.array([u]), np.array([0]), np.array([True]), cache.storage, weighted)
         cache.K[tj] = Km[0]
         cache.V[tj] = Vm[0]
         target_pos = int(cache.pos[tj])

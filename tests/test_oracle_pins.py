@@ -287,6 +287,29 @@ def test_merge_copies_of_twin_average_the_values():
     assert np.array_equal(K2[[0, 2]], Kc[[0, 2]]) and list(n) == [0, m, 0]
 
 
+def test_average_merging_is_the_plain_mean_of_the_group():
+    """The merge-policy ablation's alternative (Sec. 5): every member of a group weighs the same,
+    whatever its similarity."""
+    Kc, Vc, Ke, Ve = _rand(4, 6, 60), _rand(4, 6, 61), _rand(9, 6, 62), _rand(9, 6, 63)
+    u = rng.uniform(-1, 1, size=9)
+    t = np.array([0, 2, 2, 3, 2, 0, 3, 3, 3])
+    passed = np.array([1, 1, 0, 1, 1, 1, 1, 0, 1], bool)
+    K2, V2, n = ref.merge(Kc, Vc, Ke, Ve, u, t, passed, weighted=False)
+    for j in range(4):
+        src = [i for i in range(9) if passed[i] and t[i] == j]
+        np.testing.assert_allclose(K2[j], np.vstack([Kc[j:j + 1], Ke[src]]).mean(0), rtol=1e-14)
+        np.testing.assert_allclose(V2[j], np.vstack([Vc[j:j + 1], Ve[src]]).mean(0), rtol=1e-14)
+        assert n[j] == len(src)
+    assert np.array_equal(K2[1], Kc[1])                  # no source: untouched
+    # two tokens: the midpoint, where Eq. 11-12 lean towards the kept token
+    Km, _, _ = ref.merge(np.array([[1.0, 0.0]]), np.zeros((1, 2)), np.array([[0.0, 1.0]]), np.zeros((1, 2)),
+                         np.array([0.3]), np.array([0]), np.array([True]), weighted=False)
+    assert list(Km[0]) == [0.5, 0.5]
+    Kw, _, _ = ref.merge(np.array([[1.0, 0.0]]), np.zeros((1, 2)), np.array([[0.0, 1.0]]), np.zeros((1, 2)),
+                         np.array([0.3]), np.array([0]), np.array([True]))
+    assert Kw[0][0] > 0.5 > Kw[0][1]
+
+
 def test_merge_convex_hull_mask_and_brute_force():
     Kc, Vc, Ke, Ve = _rand(6, 5, 50), _rand(6, 5, 51), _rand(14, 5, 52), _rand(14, 5, 53)
     u, t = ref.match(Ke, Kc)
