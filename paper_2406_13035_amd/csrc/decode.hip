@@ -372,7 +372,7 @@ __device__ __forceinline__ void head_tail(const DecodeArgs& a, OT* __restrict__ 
                                           int hk, int64_t lbh, int total, int nsub, double* sred, int* ired,
                                           float* fred, double* dred, unsigned char* park) {
   constexpr int kRec = rec_doubles(G);
-  constexpr int U = G >= 4 ? 1 : 4 / G;               // slots per thread and batch of the score pass
+  constexpr int U = G >= 8 ? 1 : G >= 2 ? 2 : 4;      // slots per thread and batch of the score pass
   constexpr int C4 = D / 4;                           // threads across an output row (four columns each)
   constexpr int RG = 256 / C4;                        // groups of threads that share the sub-chunks
   constexpr int PB = 4;                               // partial rows in flight per thread
@@ -398,22 +398,52 @@ __device__ __forceinline__ void head_tail(const DecodeArgs& a, OT* __restrict__ 
     park_kv[tid] = Kc[int64_t(last) * D + tid];
     park_kv[256 + tid] = Vc[int64_t(last) * D + tid];
   }
-  // ---- head maximum and exact normaliser sum_j exp(s_j - max) of each query head (fixed tree)
+  // ---- head maximum and exact normaliser sum_j exp(s_j - max) of each query head (fixed tree),
+  //      all query heads in one sweep over the sub-chunk records.  exp(m_sub - max) of every
+  //      sub-chunk and query head is kept in LDS (`em`, behind the parked values) for the output
+  //      and score passes; for a head with more sub-chunks than fit, the factors overwrite the
+  //      maxima in the records and the score pass brings them into LDS segment by segment.
+  constexpr int kParkBytes = kCand * 256 * int(sizeof(double) + sizeof(int2)) + 2 * 256 * int(sizeof(T));
+  constexpr int kEmCap = (kStageBytes - 8192 - kParkBytes) / int(sizeof(double));
+  double* em = reinterpret_cast<double*>(park + kParkBytes);  // [nsub][G]
+  const bool em_lds = nsub * G <= kEmCap;
   double Mg[G], Lg[G];
+  {
 #pragma unroll
-  for (int g = 0; g < G; ++g) {
-    double mx = -INFINITY;
-    for (int c = tid; c < nsub; c += 256) mx = fmax(mx, ld_agent(&a.rec[sub_index(a, bh, ch0, c) * kRec + g]));
-    mx = wave_max(mx);
+    for (int g = 0; g < G; ++g) Mg[g] = -INFINITY;
+    for (int c = tid; c < nsub; c += 256) {
+      const int64_t x = sub_index(a, bh, ch0, c) * kRec;
+#pragma unroll
+      for (int g = 0; g < G; ++g) Mg[g] = fmax(Mg[g], ld_agent(&a.rec[x + g]));
+    }
+#pragma unroll
+    for (int g = 0; g < G; ++g) Mg[g] = wave_max(Mg[g]);
     __syncthreads();
-    if (lane == 0) sred[w] = mx;
+    if (lane == 0) {
+#pragma unroll
+      for (int g = 0; g < G; ++g) dred[w * G + g] = Mg[g];
+    }
     __syncthreads();
-    mx = fmax(fmax(sred[0], sred[1]), fmax(sred[2], sred[3]));
-    double part = 0.0;
-    for (int c = tid; c < nsub; c += 256)
-      part += ld_agent(&a.rec[sub_index(a, bh, ch0, c) * kRec + G + g]) * exp(ld_agent(&a.rec[sub_index(a, bh, ch0, c) * kRec + g]) - mx);
-    Mg[g] = mx;
-    Lg[g] = block_sum(part, sred);
+#pragma unroll
+    for (int g = 0; g < G; ++g) Mg[g] = fmax(fmax(dred[g], dred[G + g]), fmax(dred[2 * G + g], dred[3 * G + g]));
+    double part[G];
+#pragma unroll
+    for (int g = 0; g < G; ++g) part[g] = 0.0;
+    for (int c = tid; c < nsub; c += 256) {
+      const int64_t x = sub_index(a, bh, ch0, c) * kRec;
+#pragma unroll
+      for (int g = 0; g < G; ++g) {
+        const double t = exp(ld_agent(&a.rec[x + g]) - Mg[g]);
+        part[g] += ld_agent(&a.rec[x + G + g]) * t;
+        if (em_lds)
+          em[c * G + g] = t;
+        else
+          st_agent(&a.rec[x + g], t);  // the factor replaces the maximum (nobody needs it again)
+      }
+    }
+#pragma unroll
+    for (int g = 0; g < G; ++g) Lg[g] = block_sum(part[g], sred);
+    __syncthreads();  // `em` is complete (in memory: the stores have been acknowledged)
   }
   // ---- Eq. 9 arg-max over the sub-chunks' results, for every candidate of this step (which of
   //      them is evicted is not known yet; ties: earlier position)
@@ -444,19 +474,17 @@ __device__ __forceinline__ void head_tail(const DecodeArgs& a, OT* __restrict__ 
   Best low[kCand + 1];
 #pragma unroll
   for (int i = 0; i <= kCand; ++i) low[i] = Best{0.0, 0, -1};
-  double sc[U], e[U][G], ms[U][G];
+  double sc[U], e[U][G];
   int ps[U];
+  int seg0 = 0, jend = total;  // the segment of sub-chunks whose factors `em` holds, and its last slot + 1
   auto load_batch = [&](int j0) {
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      const int j = min(j0 + u * 256, total - 1);
+      const int j = min(j0 + u * 256, jend - 1);
       sc[u] = a.cscore[slot0 + j];
       ps[u] = a.cpos[slot0 + j];
 #pragma unroll
-      for (int g = 0; g < G; ++g) {
-        e[u][g] = ld_agent(&a.elog[elog_index(a, bh, ch0, G, g, j)]);
-        ms[u][g] = ld_agent(&a.rec[sub_index(a, bh, ch0, j / kSub) * kRec + g]);
-      }
+      for (int g = 0; g < G; ++g) e[u][g] = ld_agent(&a.elog[elog_index(a, bh, ch0, G, g, j)]);
     }
   };
   // Eq. 6 for the batch's slots, the token to evict (Eq. 7-8 on count+1 entries) and the lowest
@@ -465,10 +493,10 @@ __device__ __forceinline__ void head_tail(const DecodeArgs& a, OT* __restrict__ 
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const int j = j0 + u * 256;
-      if (j < total) {
+      if (j < jend) {
         double s2 = sc[u];
 #pragma unroll
-        for (int g = 0; g < G; ++g) s2 += e[u][g] * exp(ms[u][g] - Mg[g]) / Lg[g];
+        for (int g = 0; g < G; ++g) s2 += e[u][g] * em[(j / kSub - seg0) * G + g] / Lg[g];
         a.cscore[slot0 + j] = s2;
         const int p = ps[u];
         if (j == last) {  // kept for the move into the freed slot
@@ -499,19 +527,21 @@ __device__ __forceinline__ void head_tail(const DecodeArgs& a, OT* __restrict__ 
     float num[4] = {0.f, 0.f, 0.f, 0.f};
     for (int c0 = rg; c0 < nchunk; c0 += PB * RG) {
       float4 v[PB];
-      double mc[PB];
+      double fc[PB];
 #pragma unroll
       for (int u = 0; u < PB; ++u) {
         const int cc = min(c0 + u * RG, nchunk - 1);
         v[u] = ld_agent4(a.pacc + (chunk_index(a, bh, ch0, cc) * G + g) * D + c4 * 4);
-        mc[u] = -INFINITY;  // the chunk's maximum: that of its sub-chunks
+        fc[u] = 0.0;  // exp(chunk maximum - max): the largest of its sub-chunks' factors
 #pragma unroll
         for (int i = 0; i < 4; ++i)
-          if (cc * 4 + i < nsub) mc[u] = fmax(mc[u], ld_agent(&a.rec[sub_index(a, bh, ch0, cc * 4 + i) * kRec + g]));
+          if (cc * 4 + i < nsub)
+            fc[u] = fmax(fc[u], em_lds ? em[(cc * 4 + i) * G + g]
+                                       : ld_agent(&a.rec[sub_index(a, bh, ch0, cc * 4 + i) * kRec + g]));
       }
 #pragma unroll
       for (int u = 0; u < PB; ++u) {
-        const float f = c0 + u * RG < nchunk ? float(exp(mc[u] - Mg[g])) : 0.f;
+        const float f = c0 + u * RG < nchunk ? float(fc[u]) : 0.f;
         num[0] = fmaf(v[u].x, f, num[0]);
         num[1] = fmaf(v[u].y, f, num[1]);
         num[2] = fmaf(v[u].z, f, num[2]);
@@ -532,9 +562,23 @@ __device__ __forceinline__ void head_tail(const DecodeArgs& a, OT* __restrict__ 
     __builtin_amdgcn_sched_barrier(0);  // one query head after the other (registers)
   }
   // ---- score pass: batches of U slots per thread, their loads in flight together
-  for (int j0 = tid; j0 < total; j0 += U * 256) {
-    load_batch(j0);
-    apply_batch(j0);
+  constexpr int kSegSubs = kEmCap / G;  // sub-chunks whose factors fit `em`
+#pragma unroll 1
+  for (seg0 = 0; seg0 < nsub; seg0 += kSegSubs) {
+    const int nseg = min(kSegSubs, nsub - seg0);
+    jend = min(total, (seg0 + nseg) * kSub);
+    if (!em_lds) {  // a head of several segments: (re)fill the table for this one
+      lds_barrier();
+#pragma unroll 1
+      for (int i = tid; i < nseg * G; i += 256)
+        em[i] = ld_agent(&a.rec[sub_index(a, bh, ch0, seg0 + i / G) * kRec + i % G]);
+      lds_barrier();
+    }
+#pragma unroll 1
+    for (int j0 = seg0 * kSub + tid; j0 < jend; j0 += U * 256) {
+      load_batch(j0);
+      apply_batch(j0);
+    }
   }
   // evicted token: block-wide
   ev = fast_wave_first_evicted(ev);

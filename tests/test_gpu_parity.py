@@ -186,10 +186,13 @@ def test_merge_with_long_source_lists():
 
 # ------------------------------------------------------------------ a9-a12: decode from oracle state
 
-def _run_decode_parity(w, n, B, layer, budget, recent, sink, steps, tau_force=float("nan")):
+def _run_decode_parity(w, n, B, layer, budget, recent, sink, steps, tau_force=float("nan"), random_scores=False):
     Q, K, V = H.make_inputs(w, B, layer, n)
-    _, score, _ = H.oracle_prefill_layer(Q, K, V, w.group)
-    score32 = score.astype(np.float32)
+    if random_scores:  # long prompts: the token-level stages and decode do not care where scores come from
+        score32 = np.random.default_rng(n).random((B, w.n_kv_heads, n), dtype=np.float32) * w.group
+    else:
+        _, score, _ = H.oracle_prefill_layer(Q, K, V, w.group)
+        score32 = score.astype(np.float32)
     cap = int(np.max(budget)) + 1
     ctx = H.new_ctx(w, B, 1, n, cap + 8, n_sink=sink, tau_force=tau_force)
     ctx.d2o_scores_import(0, score32)
@@ -250,6 +253,15 @@ def test_decode_from_oracle_state(case):
         _run_decode_parity(_small_bf16(True), 400, 2, 17, [90, 130], [20, 30], 1, 96)
     else:
         _run_decode_parity(_small_bf16(False), 500, 1, 12, 100, 25, 0, 10, tau_force=float("inf"))
+
+
+@pytest.mark.parametrize("budget", [12000, 15000])
+def test_decode_one_large_head_with_eight_query_heads(budget):
+    """A head of 188 / 235 sub-chunks of 64 slots with 8 query heads: the closing workgroup's
+    table of per-sub-chunk softmax factors fits its LDS region in the first case and does not
+    in the second (it then lives in the sub-chunk records)."""
+    w = W1.scaled(n_q_heads=8, n_kv_heads=1)
+    _run_decode_parity(w, 16000, 1, 0, budget, budget // 4, 0, 4, random_scores=True)
 
 
 def test_decode_evicted_token_outside_the_predicted_candidates():
