@@ -372,7 +372,7 @@ __device__ __forceinline__ void head_tail(const DecodeArgs& a, OT* __restrict__ 
                                           int hk, int64_t lbh, int total, int nsub, double* sred, int* ired,
                                           float* fred, double* dred, unsigned char* park) {
   constexpr int kRec = rec_doubles(G);
-  constexpr int U = G >= 8 ? 1 : G >= 2 ? 2 : 4;      // slots per thread and batch of the score pass
+  constexpr int U = G >= 8 ? 1 : G >= 4 ? 3 : G >= 2 ? 4 : 6;  // slots per thread and batch of the score pass
   constexpr int C4 = D / 4;                           // threads across an output row (four columns each)
   constexpr int RG = 256 / C4;                        // groups of threads that share the sub-chunks
   constexpr int PB = 4;                               // partial rows in flight per thread
@@ -444,6 +444,15 @@ __device__ __forceinline__ void head_tail(const DecodeArgs& a, OT* __restrict__ 
 #pragma unroll
     for (int g = 0; g < G; ++g) Lg[g] = block_sum(part[g], sred);
     __syncthreads();  // `em` is complete (in memory: the stores have been acknowledged)
+    // the table holds the factors already divided by the normaliser: a probability is then
+    // one product, exp(s_j - m_sub) * em
+    if (em_lds) {
+      for (int c = tid; c < nsub; c += 256) {
+#pragma unroll
+        for (int g = 0; g < G; ++g) em[c * G + g] /= Lg[g];
+      }
+      lds_barrier();
+    }
   }
   // ---- Eq. 9 arg-max over the sub-chunks' results, for every candidate of this step (which of
   //      them is evicted is not known yet; ties: earlier position)
@@ -496,7 +505,7 @@ __device__ __forceinline__ void head_tail(const DecodeArgs& a, OT* __restrict__ 
       if (j < jend) {
         double s2 = sc[u];
 #pragma unroll
-        for (int g = 0; g < G; ++g) s2 += e[u][g] * em[(j / kSub - seg0) * G + g] / Lg[g];
+        for (int g = 0; g < G; ++g) s2 = fma(e[u][g], em[(j / kSub - seg0) * G + g], s2);
         a.cscore[slot0 + j] = s2;
         const int p = ps[u];
         if (j == last) {  // kept for the move into the freed slot
@@ -537,7 +546,7 @@ __device__ __forceinline__ void head_tail(const DecodeArgs& a, OT* __restrict__ 
         for (int i = 0; i < 4; ++i)
           if (cc * 4 + i < nsub)
             fc[u] = fmax(fc[u], em_lds ? em[(cc * 4 + i) * G + g]
-                                       : ld_agent(&a.rec[sub_index(a, bh, ch0, cc * 4 + i) * kRec + g]));
+                                       : ld_agent(&a.rec[sub_index(a, bh, ch0, cc * 4 + i) * kRec + g]) / Lg[g]);
       }
 #pragma unroll
       for (int u = 0; u < PB; ++u) {
@@ -557,7 +566,7 @@ __device__ __forceinline__ void head_tail(const DecodeArgs& a, OT* __restrict__ 
       float t = fr[0];
 #pragma unroll
       for (int i = 1; i < RG; ++i) t += fr[i * C4];
-      out[li * ov.sn + b * ov.sb + (hk * G + g) * ov.sh + tid] = Elem<OT>::from_f32(float(double(t) / Lg[g]));
+      out[li * ov.sn + b * ov.sb + (hk * G + g) * ov.sh + tid] = Elem<OT>::from_f32(t);
     }
     __builtin_amdgcn_sched_barrier(0);  // one query head after the other (registers)
   }
@@ -570,8 +579,12 @@ __device__ __forceinline__ void head_tail(const DecodeArgs& a, OT* __restrict__ 
     if (!em_lds) {  // a head of several segments: (re)fill the table for this one
       lds_barrier();
 #pragma unroll 1
-      for (int i = tid; i < nseg * G; i += 256)
-        em[i] = ld_agent(&a.rec[sub_index(a, bh, ch0, seg0 + i / G) * kRec + i % G]);
+      for (int i = tid; i < nseg * G; i += 256) {
+        double lg = Lg[0];
+#pragma unroll
+        for (int g = 1; g < G; ++g) lg = (i % G == g) ? Lg[g] : lg;
+        em[i] = ld_agent(&a.rec[sub_index(a, bh, ch0, seg0 + i / G) * kRec + i % G]) / lg;
+      }
       lds_barrier();
     }
 #pragma unroll 1
