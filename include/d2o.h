@@ -58,6 +58,9 @@ typedef struct {
   int32_t out_f32;        /* 0: attention outputs (O, out) in `dtype`; 1: in fp32, which    */
                           /* keeps the fp32 accumulator's precision (bf16 storage alone     */
                           /* costs up to 2^-8 relative)                                     */
+  int32_t merge_average;  /* 0: similarity-weighted merge, Eq. 11-12.  1: average merging,  */
+                          /* the alternative of the merge-policy ablation (Sec. 5): the     */
+                          /* plain mean of the retained row and the tokens merged into it   */
 } d2o_config;
 
 /* A strided tensor whose last dimension (d) is contiguous.  Strides are in elements.

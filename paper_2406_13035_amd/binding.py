@@ -34,7 +34,8 @@ class d2o_config(C.Structure):
     _fields_ = [("batch", C.c_int32), ("n_layers", C.c_int32), ("n_q_heads", C.c_int32),
                 ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32), ("max_prompt_len", C.c_int32),
                 ("slots_per_seq", C.c_int64), ("dtype", C.c_int32), ("n_sink", C.c_int32),
-                ("beta", C.c_double), ("tau_force", C.c_double), ("out_f32", C.c_int32)]
+                ("beta", C.c_double), ("tau_force", C.c_double), ("out_f32", C.c_int32),
+                ("merge_average", C.c_int32)]
 
 
 class d2o_view(C.Structure):
@@ -141,14 +142,14 @@ class D2O:
 
     def __init__(self, batch, n_layers, n_q_heads, n_kv_heads, head_dim, max_prompt_len,
                  slots_per_seq, dtype="bf16", n_sink=0, beta=0.7, tau_force=float("nan"),
-                 out_f32=False, device="cuda:0"):
+                 out_f32=False, device="cuda:0", merge_average=False):
         self.lib = load_library()
         if not torch.cuda.is_available():
             raise D2OError("no GPU visible: the D2O library has no CPU path")
         self.device = torch.device(device)
         self.cfg = d2o_config(batch, n_layers, n_q_heads, n_kv_heads, head_dim, max_prompt_len,
                               slots_per_seq, D2O_BF16 if dtype == "bf16" else D2O_F32, n_sink,
-                              beta, tau_force, 1 if out_f32 else 0)
+                              beta, tau_force, 1 if out_f32 else 0, 1 if merge_average else 0)
         self.dtype = dtype
         self.out_dtype = torch.float32 if out_f32 else (torch.bfloat16 if dtype == "bf16" else torch.float32)
         self.torch_dtype = torch.bfloat16 if dtype == "bf16" else torch.float32

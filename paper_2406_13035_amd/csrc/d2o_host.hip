@@ -49,6 +49,7 @@ int check_config(const d2o_config* c) {
   }
   if (c->n_q_heads / c->n_kv_heads > 8 || c->n_q_heads > 256) return D2O_ERR_UNSUPPORTED;
   if (c->out_f32 != 0 && c->out_f32 != 1) return D2O_ERR_INVALID_ARG;
+  if (c->merge_average != 0 && c->merge_average != 1) return D2O_ERR_INVALID_ARG;
   return D2O_OK;
 }
 

@@ -70,7 +70,7 @@ struct DecodeArgs {
   int32_t* ev_target;
   double* ev_ustar;
   int64_t slots;
-  int layer0, nl, B, Hkv, G, new_pos, n_sink, out_f32;
+  int layer0, nl, B, Hkv, G, new_pos, n_sink, out_f32, merge_average;
   double beta, tau_force;
   int32_t lay_off[kMaxLayersPerCall + 1];  // first flat chunk-group index of each entry of lay_id
   int32_t lay_id[kMaxLayersPerCall];       // layers of the call (relative), most chunks first
@@ -288,8 +288,9 @@ __device__ __forceinline__ void finish_head(const DecodeArgs& a, int64_t lbh, in
   }
   if (tid < D) {
     if (do_merge) {
-      const double e1 = 2.718281828459045;  // exp(1), the retained token's self-similarity weight
-      const double w = exp(best);
+      // exp(1), the retained token's self-similarity weight; average merging weighs both rows 1
+      const double e1 = a.merge_average ? 1.0 : 2.718281828459045;
+      const double w = a.merge_average ? 1.0 : exp(best);
       const double z = __dadd_rn(e1, w);
       const T ke = es == last ? kl : Kc[int64_t(es) * D + tid], ve = es == last ? vl : Vc[int64_t(es) * D + tid];
       const T kt = bs == last ? kl : Kc[int64_t(bs) * D + tid], vt = bs == last ? vl : Vc[int64_t(bs) * D + tid];
@@ -1017,6 +1018,7 @@ hipError_t launch_decode(d2o_ctx* c, int layer0, int nl_all, View q, View k, Vie
   a.new_pos = new_pos;
   a.n_sink = cf.n_sink;
   a.out_f32 = cf.out_f32;
+  a.merge_average = cf.merge_average;
   a.beta = cf.beta;
   a.tau_force = cf.tau_force;
   // the per-layer tensors of one call are [layer][...]: groups of at most kMaxLayersPerCall

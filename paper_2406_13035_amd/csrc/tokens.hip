@@ -635,7 +635,8 @@ __global__ __launch_bounds__(256) void merge_kernel(const T* __restrict__ K, Vie
                                                     const int32_t* __restrict__ evi, const int32_t* __restrict__ cnt,
                                                     const double* __restrict__ ustar, const int32_t* __restrict__ goff,
                                                     const int32_t* __restrict__ gsrc, const int32_t* __restrict__ meta,
-                                                    T* __restrict__ cK, T* __restrict__ cV, int npad, int64_t slots) {
+                                                    T* __restrict__ cK, T* __restrict__ cV, int npad, int64_t slots,
+                                                    int average) {
   __shared__ int s_src[4][kMergeCap];
   __shared__ int s_pos[4][kMergeCap];
   __shared__ double s_w[4][kMergeCap];
@@ -656,7 +657,9 @@ __global__ __launch_bounds__(256) void merge_kernel(const T* __restrict__ K, Vie
   const T* vb = V + b * vv.sb + hk * vv.sh;
   constexpr int PER = D / 64;
   const int64_t dst = (bh * slots + meta[b * 4 + 0] + slot) * D + lane * PER;
-  const double e1 = 2.718281828459045;  // exp(1), the retained token's self-similarity weight
+  // exp(1), the retained token's self-similarity weight; average merging weighs every member 1
+  const double e1 = average ? 1.0 : 2.718281828459045;
+  auto weight = [&](double u) __attribute__((always_inline)) { return average ? 1.0 : exp(u); };
   double ak[PER], av[PER];
   load_elems<T, PER>(cK + dst, ak);
   load_elems<T, PER>(cV + dst, av);
@@ -693,7 +696,7 @@ __global__ __launch_bounds__(256) void merge_kernel(const T* __restrict__ K, Vie
   if (ns <= 64) {
     const bool have = lane < ns;
     const int mine = have ? src[lane] : 0x7FFFFFFF;
-    const double wmine = have ? exp(us[mine]) : 0.0;
+    const double wmine = have ? weight(us[mine]) : 0.0;
     const int pmine = have ? el[mine] : 0;
     int rank = 0;  // sources are distinct: the ranks are a permutation of 0 .. ns-1
     for (int i = 0; i < ns; ++i) rank += __builtin_amdgcn_readlane(mine, i) < mine ? 1 : 0;
@@ -708,7 +711,7 @@ __global__ __launch_bounds__(256) void merge_kernel(const T* __restrict__ K, Vie
     __builtin_amdgcn_wave_barrier();
     for (int t = lane; t < ns; t += 64) {
       const int mine = s_src[w][t];
-      const double wm = exp(us[mine]);
+      const double wm = weight(us[mine]);
       const int pm = el[mine];
       int rank = 0;
       for (int i = 0; i < ns; ++i) rank += s_src[w][i] < mine ? 1 : 0;
@@ -730,7 +733,7 @@ __global__ __launch_bounds__(256) void merge_kernel(const T* __restrict__ K, Vie
         if (r > prev && r < cur) cur = r;
       }
       cur = wave_min(cur);
-      const double wgt = exp(us[cur]);
+      const double wgt = weight(us[cur]);
       const int64_t pos = el[cur];
       double xk[PER], xv[PER];
       load_elems<T, PER>(kb + pos * kv.sn + lane * PER, xk);
@@ -840,7 +843,7 @@ static void run_merge(d2o_ctx* c, const int32_t* meta, View K, View V, int max_b
   const d2o_config& cf = c->cfg;
   merge_kernel<T, D><<<dim3((max_budget + 3) / 4, cf.n_kv_heads, cf.batch), 256, 0, s>>>(
       (const T*)K.ptr, K, (const T*)V.ptr, V, c->sel_evi, c->sel_cnt, c->m_ustar, c->g_off, c->g_src, meta, (T*)c->cacheK,
-      (T*)c->cacheV, c->npad, cf.slots_per_seq);
+      (T*)c->cacheV, c->npad, cf.slots_per_seq, cf.merge_average);
 }
 
 hipError_t launch_merge(d2o_ctx* c, int layer, View K, View V, int n, hipStream_t s) {

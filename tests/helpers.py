@@ -52,16 +52,16 @@ def oracle_prefill_layer(Q, K, V, G):
 
 
 def new_ctx(w: synth.Workload, batch, n_layers, max_n, slots, n_sink=0, beta=None,
-            tau_force=float("nan"), out_f32=True):
+            tau_force=float("nan"), out_f32=True, merge_average=False):
     """Contexts of the parity tests write attention outputs in fp32 unless asked otherwise, so
     that the float bar applies to the arithmetic and not to bf16 output storage."""
     return binding.D2O(batch, n_layers, w.n_q_heads, w.n_kv_heads, w.head_dim, max_n, slots,
                        dtype=w.dtype, n_sink=n_sink, beta=w.beta if beta is None else beta,
-                       tau_force=tau_force, out_f32=out_f32)
+                       tau_force=tau_force, out_f32=out_f32, merge_average=merge_average)
 
 
 def check_compress_against_oracle(ctx, layer, K, V, score32, budget, recent, n_sink, storage,
-                                  tau_force=float("nan")):
+                                  tau_force=float("nan"), weighted=True):
     """After ctx.d2o_compress_layer ran on given fp32 scores: compare every (b, kv head) with the
     oracle fed the same fp32 scores.  Index outputs must be identical; floats near-exact."""
     Kd, Vd = binding.tensor_to_f64(K), binding.tensor_to_f64(V)
@@ -73,7 +73,7 @@ def check_compress_against_oracle(ctx, layer, K, V, score32, budget, recent, n_s
             bud = int(np.broadcast_to(budget, (B,))[b])
             rec = int(np.broadcast_to(recent, (B,))[b])
             cache, ev = ref.compress_head(Kd[b, h], Vd[b, h], score32[b, h].astype(np.float64), bud,
-                                          rec, n_sink, storage, tau_force)
+                                          rec, n_sink, storage, tau_force, weighted)
             ret, evi, tgt, us, ps = ctx.d2o_prefill_events(layer, b, h, n)
             assert np.array_equal(ret, ev.retained), f"retained differ b={b} h={h}"
             assert np.array_equal(evi, ev.evicted), f"evicted differ b={b} h={h}"

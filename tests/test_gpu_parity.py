@@ -186,7 +186,8 @@ def test_merge_with_long_source_lists():
 
 # ------------------------------------------------------------------ a9-a12: decode from oracle state
 
-def _run_decode_parity(w, n, B, layer, budget, recent, sink, steps, tau_force=float("nan"), random_scores=False):
+def _run_decode_parity(w, n, B, layer, budget, recent, sink, steps, tau_force=float("nan"), random_scores=False,
+                       merge_average=False):
     Q, K, V = H.make_inputs(w, B, layer, n)
     if random_scores:  # long prompts: the token-level stages and decode do not care where scores come from
         score32 = np.random.default_rng(n).random((B, w.n_kv_heads, n), dtype=np.float32) * w.group
@@ -194,11 +195,11 @@ def _run_decode_parity(w, n, B, layer, budget, recent, sink, steps, tau_force=fl
         _, score, _ = H.oracle_prefill_layer(Q, K, V, w.group)
         score32 = score.astype(np.float32)
     cap = int(np.max(budget)) + 1
-    ctx = H.new_ctx(w, B, 1, n, cap + 8, n_sink=sink, tau_force=tau_force)
+    ctx = H.new_ctx(w, B, 1, n, cap + 8, n_sink=sink, tau_force=tau_force, merge_average=merge_average)
     ctx.d2o_scores_import(0, score32)
     ctx.d2o_compress_layer(0, K, V, budget, recent)
     _, caches = H.check_compress_against_oracle(ctx, 0, K, V, score32, budget, recent, sink, w.dtype,
-                                                tau_force)
+                                                tau_force, not merge_average)
     q, k, v = H.decode_inputs(w, B, [layer], steps)
     out = torch.empty(q[0].shape, dtype=ctx.out_dtype, device=q.device)
     qd, kd, vd = (binding.tensor_to_f64(t) for t in (q, k, v))
@@ -216,7 +217,7 @@ def _run_decode_parity(w, n, B, layer, budget, recent, sink, steps, tau_force=fl
             for h in range(w.n_kv_heads):
                 want, e = ref.decode_step_head(caches[(b, h)], qd[t, 0, b, h * G:(h + 1) * G],
                                                kd[t, 0, b, h], vd[t, 0, b, h], n + t, bud, rec, sink,
-                                               w.beta, tau_force)
+                                               w.beta, tau_force, not merge_average)
                 assert (ev[b, h], tg[b, h]) == (e.evicted_pos, e.target_pos), \
                     f"step {t} b={b} h={h}: gpu ({ev[b, h]}, {tg[b, h]}) oracle {e}"
                 if e.evicted_pos >= 0:
@@ -262,6 +263,21 @@ def test_decode_one_large_head_with_eight_query_heads(budget):
     in the second (it then lives in the sub-chunk records)."""
     w = W1.scaled(n_q_heads=8, n_kv_heads=1)
     _run_decode_parity(w, 16000, 1, 0, budget, budget // 4, 0, 4, random_scores=True)
+
+
+@pytest.mark.parametrize("case", ["bf16-gqa", "f32", "bf16-merge-everything"])
+def test_average_merging_prefill_and_decode(case):
+    """merge_average = 1, the alternative of the merge-policy ablation (Sec. 5): prompt-phase
+    merges (groups of many sources) and the one-token merges of the decode steps against the
+    oracle's plain mean."""
+    print(f"case={case}", flush=True)
+    if case == "bf16-gqa":
+        _run_decode_parity(_small_bf16(True), 777, 2, 9, [150, 333], [37, 83], 2, 20, merge_average=True)
+    elif case == "f32":
+        _run_decode_parity(W1, 512, 1, 0, 128, 64, 0, W1.decode_steps, merge_average=True)
+    else:
+        _run_decode_parity(_small_bf16(False), 1000, 1, 20, 200, 50, 1, 12, tau_force=float("-inf"),
+                           merge_average=True)
 
 
 def test_decode_evicted_token_outside_the_predicted_candidates():
