@@ -630,13 +630,12 @@ __device__ __forceinline__ void store_elems(T* p, const double* v, double z) {
 // The rows are then read kMergeBatch sources at a time in rank order.
 constexpr int kMergeCap = 512;
 constexpr int kMergeBatch = 8;
-template <typename T, int D>
+template <typename T, int D, bool AVERAGE>
 __global__ __launch_bounds__(256) void merge_kernel(const T* __restrict__ K, View kv, const T* __restrict__ V, View vv,
                                                     const int32_t* __restrict__ evi, const int32_t* __restrict__ cnt,
                                                     const double* __restrict__ ustar, const int32_t* __restrict__ goff,
                                                     const int32_t* __restrict__ gsrc, const int32_t* __restrict__ meta,
-                                                    T* __restrict__ cK, T* __restrict__ cV, int npad, int64_t slots,
-                                                    int average) {
+                                                    T* __restrict__ cK, T* __restrict__ cV, int npad, int64_t slots) {
   __shared__ int s_src[4][kMergeCap];
   __shared__ int s_pos[4][kMergeCap];
   __shared__ double s_w[4][kMergeCap];
@@ -658,8 +657,8 @@ __global__ __launch_bounds__(256) void merge_kernel(const T* __restrict__ K, Vie
   constexpr int PER = D / 64;
   const int64_t dst = (bh * slots + meta[b * 4 + 0] + slot) * D + lane * PER;
   // exp(1), the retained token's self-similarity weight; average merging weighs every member 1
-  const double e1 = average ? 1.0 : 2.718281828459045;
-  auto weight = [&](double u) __attribute__((always_inline)) { return average ? 1.0 : exp(u); };
+  const double e1 = AVERAGE ? 1.0 : 2.718281828459045;
+  auto weight = [&](double u) __attribute__((always_inline)) { return AVERAGE ? 1.0 : exp(u); };
   double ak[PER], av[PER];
   load_elems<T, PER>(cK + dst, ak);
   load_elems<T, PER>(cV + dst, av);
@@ -841,9 +840,15 @@ hipError_t launch_threshold_group(d2o_ctx* c, int layer, int n, hipStream_t s) {
 template <typename T, int D>
 static void run_merge(d2o_ctx* c, const int32_t* meta, View K, View V, int max_budget, hipStream_t s) {
   const d2o_config& cf = c->cfg;
-  merge_kernel<T, D><<<dim3((max_budget + 3) / 4, cf.n_kv_heads, cf.batch), 256, 0, s>>>(
-      (const T*)K.ptr, K, (const T*)V.ptr, V, c->sel_evi, c->sel_cnt, c->m_ustar, c->g_off, c->g_src, meta, (T*)c->cacheK,
-      (T*)c->cacheV, c->npad, cf.slots_per_seq, cf.merge_average);
+  const dim3 grid((max_budget + 3) / 4, cf.n_kv_heads, cf.batch);
+  if (cf.merge_average)
+    merge_kernel<T, D, true><<<grid, 256, 0, s>>>((const T*)K.ptr, K, (const T*)V.ptr, V, c->sel_evi, c->sel_cnt,
+                                                  c->m_ustar, c->g_off, c->g_src, meta, (T*)c->cacheK, (T*)c->cacheV,
+                                                  c->npad, cf.slots_per_seq);
+  else
+    merge_kernel<T, D, false><<<grid, 256, 0, s>>>((const T*)K.ptr, K, (const T*)V.ptr, V, c->sel_evi, c->sel_cnt,
+                                                   c->m_ustar, c->g_off, c->g_src, meta, (T*)c->cacheK, (T*)c->cacheV,
+                                                   c->npad, cf.slots_per_seq);
 }
 
 hipError_t launch_merge(d2o_ctx* c, int layer, View K, View V, int n, hipStream_t s) {
