@@ -212,10 +212,13 @@ int d2o_prefill_events(d2o_ctx* ctx, int32_t layer, int32_t b, int32_t kv_head,
                        int32_t* n_evi, int32_t* target_pos, double* u_star, uint8_t* passed,
                        void* stream);
 
-/* Kernel timing aid for benchmarks (not part of the method).  While enabled, every launch
- * of the kernels below is bracketed by two HIP events recorded on the launch stream.
- * d2o_timing_read synchronises `stream`, returns the summed duration in milliseconds and the
- * number of launches of one kernel since the last read of that kernel, and forgets them. */
+/* Kernel timing aid for benchmarks (not part of the method).  While enabled (on >= 1), launches
+ * of the kernels below are bracketed by two HIP events recorded on the launch stream: every
+ * launch of the prompt-phase kernels, and every on-th launch of the two decode kernels (the
+ * events of a decode step cost it about 3 % at the largest configuration; on = 1 times every
+ * step).  d2o_timing_read synchronises `stream`, returns the summed duration in milliseconds and
+ * the number of timed launches of one kernel since the last read of that kernel, and forgets
+ * them. */
 typedef enum {
   D2O_K_ATTN_FWD = 0,      /* prefill attention, pass 1 (O and row log-sum-exp)            */
   D2O_K_COLSUM = 1,        /* prefill attention, pass 2 (per-key column sums)              */

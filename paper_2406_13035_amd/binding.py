@@ -241,8 +241,9 @@ class D2O:
                                              view_decode(k_new), view_decode(v_new),
                                              view_decode(out), _stream_ptr()), "d2o_decode_step")
 
-    def d2o_timing_enable(self, on: bool):
-        self._check(self.lib.d2o_timing_enable(self.ctx, 1 if on else 0), "d2o_timing_enable")
+    def d2o_timing_enable(self, on):
+        """False / 0: off.  True / 1: every launch.  n > 1: decode kernels every n-th launch."""
+        self._check(self.lib.d2o_timing_enable(self.ctx, int(on)), "d2o_timing_enable")
 
     def d2o_timing_read(self, kernel: str):
         """(total milliseconds, launches) of one kernel since its last read."""

@@ -603,7 +603,9 @@ int d2o_prefill_events(d2o_ctx* x, int32_t layer, int32_t b, int32_t h, int32_t*
 
 int d2o_timing_enable(d2o_ctx* x, int32_t on) {
   if (!x) return D2O_ERR_INVALID_ARG;
-  x->timing = on != 0;
+  if (on < 0) return D2O_ERR_INVALID_ARG;
+  x->timing = on;
+  for (auto& v : x->launch_no) v = 0;
   return D2O_OK;
 }
 

@@ -49,7 +49,8 @@ struct d2o_timed_launch {
 struct d2o_ctx {
   d2o_config cfg;
   std::string err;
-  bool timing = false;
+  int timing = 0;                    // 0 off; n: time every launch, decode kernels every n-th
+  int64_t launch_no[D2O_K_COUNT] = {};
   std::vector<d2o_timed_launch> timed;
   std::vector<d2o::LayerState> layers;
   std::vector<int64_t> used_slots;   // [B]
@@ -126,7 +127,8 @@ struct KernelTimer {
   hipStream_t s;
   bool on;
   d2o_timed_launch t;
-  KernelTimer(d2o_ctx* ctx, int id, hipStream_t stream) : c(ctx), s(stream), on(ctx->timing) {
+  KernelTimer(d2o_ctx* ctx, int id, hipStream_t stream) : c(ctx), s(stream), on(ctx->timing > 0) {
+    if (on && (id == D2O_K_DECODE_ATTEND || id == D2O_K_DECODE_PREPARE)) on = ctx->launch_no[id]++ % ctx->timing == 0;
     if (!on) return;
     t.id = id;
     if (hipEventCreate(&t.start) != hipSuccess || hipEventCreate(&t.stop) != hipSuccess) {
