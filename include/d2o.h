@@ -215,8 +215,8 @@ int d2o_prefill_events(d2o_ctx* ctx, int32_t layer, int32_t b, int32_t kv_head,
 /* Kernel timing aid for benchmarks (not part of the method).  While enabled (on >= 1), launches
  * of the kernels below are bracketed by two HIP events recorded on the launch stream: every
  * launch of the prompt-phase kernels, and every on-th launch of the two decode kernels (the
- * events of a decode step cost it about 3 % at the largest configuration; on = 1 times every
- * step).  d2o_timing_read synchronises `stream`, returns the summed duration in milliseconds and
+ * on-th, 2 on-th, ... after enabling; the events of a decode step cost it about 3 % at the
+ * largest configuration; on = 1 times every step).  d2o_timing_read synchronises `stream`, returns the summed duration in milliseconds and
  * the number of timed launches of one kernel since the last read of that kernel, and forgets
  * them. */
 typedef enum {

@@ -128,7 +128,7 @@ struct KernelTimer {
   bool on;
   d2o_timed_launch t;
   KernelTimer(d2o_ctx* ctx, int id, hipStream_t stream) : c(ctx), s(stream), on(ctx->timing > 0) {
-    if (on && (id == D2O_K_DECODE_ATTEND || id == D2O_K_DECODE_PREPARE)) on = ctx->launch_no[id]++ % ctx->timing == 0;
+    if (on && (id == D2O_K_DECODE_ATTEND || id == D2O_K_DECODE_PREPARE)) on = ctx->launch_no[id]++ % ctx->timing == ctx->timing - 1;
     if (!on) return;
     t.id = id;
     if (hipEventCreate(&t.start) != hipSuccess || hipEventCreate(&t.stop) != hipSuccess) {
