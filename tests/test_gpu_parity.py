@@ -417,6 +417,28 @@ def test_decode_all_layers_in_one_call_equals_one_call_per_layer():
         ctx.close()
 
 
+def test_timing_aid_samples_decode_launches():
+    """d2o_timing_enable(n): every launch of the prompt-phase kernels is timed, the decode kernels
+    on every n-th launch (the n-th, 2n-th, ...); reading forgets what it returned."""
+    w, n = _small_bf16(False), 300
+    Q, K, V = H.make_inputs(w, 1, 0, n)
+    ctx = H.new_ctx(w, 1, 1, n, 64 + 8)
+    ctx.d2o_timing_enable(4)
+    ctx.d2o_prefill_compress(0, Q, K, V, 64, 16)
+    q, k, v = H.decode_inputs(w, 1, [0], 9)
+    out = torch.empty(q[0].shape, dtype=ctx.out_dtype, device=q.device)
+    for t in range(9):
+        ctx.d2o_decode_step(0, 1, q[t], k[t], v[t], out)
+    for name, want in (("attn_fwd", 1), ("colsum", 1), ("merge", 1), ("decode_attend", 2), ("decode_prepare", 2)):
+        ms, cnt = ctx.d2o_timing_read(name)
+        assert cnt == want and ms > 0.0, (name, cnt, ms)
+    assert ctx.d2o_timing_read("decode_attend") == (0.0, 0)
+    ctx.d2o_timing_enable(0)
+    ctx.d2o_decode_step(0, 1, q[0], k[0], v[0], out)
+    assert ctx.d2o_timing_read("decode_attend")[1] == 0
+    ctx.close()
+
+
 def test_error_paths_return_codes():
     w, n = _small_bf16(False), 256
     Q, K, V = H.make_inputs(w, 1, 0, n)
