@@ -452,6 +452,7 @@ int d2o_compress_layer(d2o_ctx* x, int32_t layer, d2o_view K, d2o_view V, int32_
   if ((e = launch_match(x, layer, to_view(K), n, s)) != hipSuccess) return fail(x, D2O_ERR_HIP, std::string("match: ") + hipGetErrorString(e));
   if ((e = launch_threshold_group(x, layer, n, s)) != hipSuccess) return fail(x, D2O_ERR_HIP, std::string("threshold: ") + hipGetErrorString(e));
   if ((e = launch_merge(x, layer, to_view(K), to_view(V), n, s)) != hipSuccess) return fail(x, D2O_ERR_HIP, std::string("merge: ") + hipGetErrorString(e));
+  if ((e = launch_init_candidates(x, layer, st.next_pos, s)) != hipSuccess) return fail(x, D2O_ERR_HIP, std::string("candidates: ") + hipGetErrorString(e));
   return D2O_OK;
 }
 

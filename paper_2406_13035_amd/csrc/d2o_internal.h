@@ -158,5 +158,6 @@ hipError_t launch_merge(d2o_ctx* c, int layer, View K, View V, int n, hipStream_
 hipError_t launch_decode(d2o_ctx* c, int layer0, int nl, View q, View k, View v, View out,
                          int new_pos, hipStream_t s);
 int decode_candidates();  // eviction candidates tracked per (layer, sequence, KV head)
+hipError_t launch_init_candidates(d2o_ctx* c, int layer, int new_pos, hipStream_t s);
 
 }  // namespace d2o

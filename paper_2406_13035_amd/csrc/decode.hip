@@ -19,8 +19,8 @@
 //                   and the recent window; equal scores evict the later position) and the
 //                   candidates of the next step (the lowest scores that remain).  When the
 //                   evicted token is one of this step's candidates, which is the normal case,
-//                   its similarities are already there; otherwise (the first step after prompt
-//                   encoding, or a candidate overtaken by a token outside the list) the same
+//                   its similarities are already there; otherwise (the first step after a cache
+//                   import, or a candidate overtaken by a token outside the list) the same
 //                   workgroup makes a second pass over the head's keys.  Then: arg-max (ties:
 //                   earlier position), EMA threshold (Eq. 10, update first, then test), merge
 //                   or discard (Eq. 11-12 with one source), and the last slot moves into the
@@ -659,7 +659,7 @@ __device__ __forceinline__ void head_tail(const DecodeArgs& a, OT* __restrict__ 
   }
   Best m{0.0, 0, -1};
   if (ci < 0) {
-    // Not foreseen (the first step after prompt encoding, or a candidate overtaken by a token
+    // Not foreseen (the first step after a cache import, or a candidate overtaken by a token
     // outside the list): a second pass over the head's keys.
     m = scan_matches<T, D>(a, slot0, es, total, dred, sred);
   } else {
@@ -989,6 +989,70 @@ hipError_t run_decode_g(d2o_ctx* c, const DecodeArgs& a, int nl, int fc, View q,
 
 int decode_candidates() { return kCand; }
 
+
+// The eviction candidates of the first generation step of one layer, chosen after prompt
+// compression: the kCand lowest scores among the cached tokens that are evictable when token
+// `new_pos` arrives (Eq. 7-8 on count + 1 entries: neither sink nor inside the recent window).
+// A prediction like the one every step makes for the next: a miss costs that step's closing
+// workgroup a second pass over the keys and nothing else.
+__global__ __launch_bounds__(256) void init_candidates(const int32_t* __restrict__ ccount,
+                                                       const int32_t* __restrict__ meta,  // the layer's [B][4]
+                                                       const double* __restrict__ cscore,
+                                                       const int32_t* __restrict__ cpos, int32_t* __restrict__ cand,
+                                                       int layer, int B, int Hkv, int64_t slots, int new_pos,
+                                                       int n_sink) {
+  __shared__ double sred[4];
+  __shared__ int ired[8];
+  const int hk = blockIdx.x, b = blockIdx.y, tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const int64_t lbh = (int64_t(layer) * B + b) * Hkv + hk;
+  const int total = ccount[lbh], recent = meta[b * 4 + 2];
+  const int64_t slot0 = (int64_t(b) * Hkv + hk) * slots + meta[b * 4 + 0];
+  Best low[kCand + 1];
+#pragma unroll
+  for (int i = 0; i <= kCand; ++i) low[i] = Best{0.0, 0, -1};
+  for (int j = tid; j < total; j += 256) {
+    const double sc = cscore[slot0 + j];
+    const int p = cpos[slot0 + j];
+    if (p >= n_sink && p <= new_pos - recent && evicts_before(sc, p, j, low[kCand - 1])) {
+      low[kCand - 1] = Best{sc, p, j};
+#pragma unroll
+      for (int i = kCand - 1; i > 0; --i)
+        if (evicts_before(low[i].u, low[i].pos, low[i].slot, low[i - 1])) {
+          const Best t = low[i - 1];
+          low[i - 1] = low[i];
+          low[i] = t;
+        }
+    }
+  }
+#pragma unroll
+  for (int r = 0; r < kCand; ++r) {  // repeated block-wide extraction of the first in eviction order
+    Best h = fast_wave_first_evicted(low[0]);
+    __syncthreads();
+    if (lane == 0) {
+      sred[w] = h.u;
+      ired[w] = h.pos;
+      ired[4 + w] = h.slot;
+    }
+    __syncthreads();
+    h = Best{sred[0], ired[0], ired[4]};
+#pragma unroll
+    for (int i = 1; i < 4; ++i)
+      if (evicts_before(sred[i], ired[i], ired[4 + i], h)) h = Best{sred[i], ired[i], ired[4 + i]};
+    if (tid == 0) cand[lbh * kCand + r] = h.slot;
+    if (h.slot >= 0 && low[0].slot == h.slot) {  // the owner pops its head
+#pragma unroll
+      for (int i = 0; i < kCand; ++i) low[i] = low[i + 1];
+    }
+  }
+}
+
+hipError_t launch_init_candidates(d2o_ctx* c, int layer, int new_pos, hipStream_t s) {
+  const d2o_config& cf = c->cfg;
+  init_candidates<<<dim3(cf.n_kv_heads, cf.batch), 256, 0, s>>>(c->ccount, c->meta + size_t(layer) * cf.batch * 4,
+                                                                c->cscore, c->cpos, c->ccand, layer, cf.batch,
+                                                                cf.n_kv_heads, cf.slots_per_seq, new_pos, cf.n_sink);
+  return hipGetLastError();
+}
 
 hipError_t launch_decode(d2o_ctx* c, int layer0, int nl_all, View q, View k, View v, View out, int new_pos,
                          hipStream_t s) {
