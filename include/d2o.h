@@ -6,7 +6,10 @@
  * whose sizes d2o_workspace_bytes() reports.  All device work is enqueued on the stream
  * the caller passes (a hipStream_t, typed void* here so the header needs no HIP include;
  * NULL = the default stream).  Unless stated otherwise a call returns without
- * synchronising.  Every function returns 0 on success or a negative d2o_status;
+ * synchronising: d2o_create, d2o_reset, d2o_prefill_attend, d2o_compress_layer,
+ * d2o_prefill_compress and d2o_decode_step only enqueue kernels and read no host memory after
+ * they return; the calls that move data to or from host buffers (density, scores, cache,
+ * events, timing) and d2o_layer_reserve wait for the stream and say so below.  Every function returns 0 on success or a negative d2o_status;
  * d2o_last_error() gives the message of the last failure on a context.
  *
  * Pointer kinds: "device" = device memory, "host" = ordinary host memory.
@@ -44,7 +47,7 @@ typedef enum {
 typedef struct {
   int32_t batch;          /* B                                                             */
   int32_t n_layers;       /* L                                                             */
-  int32_t n_q_heads;      /* Hq, a multiple of n_kv_heads                                  */
+  int32_t n_q_heads;      /* Hq, a multiple of n_kv_heads with G = Hq / Hkv in {1, 2, 4, 8}  */
   int32_t n_kv_heads;     /* Hkv                                                           */
   int32_t head_dim;       /* d: 64 or 128 for D2O_F32, 128 for D2O_BF16                    */
   int32_t max_prompt_len; /* largest n any prefill call will pass                          */
@@ -158,8 +161,9 @@ int d2o_scores_export(d2o_ctx* ctx, int32_t layer, float* scores, int32_t n, voi
  * weighted merge of passing tokens into their matches (Eq. 11-12, weights
  * e/Z and exp(u)/Z with Z = e + sum exp(u)).  Requires the layer's scores
  * (d2o_prefill_attend or d2o_scores_import) and the same K, V.
- * budget, recent: host [B], the layer's S_l and M per sequence; budget >= n keeps
- * everything.  Errors: INVALID_ARG (budget < T + M, ...), STATE, CAPACITY, HIP. */
+ * budget, recent: host [B], the layer's S_l and M per sequence (read before the call returns);
+ * budget >= n keeps everything.  Enqueues only.  Errors: INVALID_ARG (budget < T + M, ...),
+ * STATE, CAPACITY, HIP. */
 int d2o_compress_layer(d2o_ctx* ctx, int32_t layer, d2o_view K, d2o_view V, int32_t n,
                        const int32_t* budget, const int32_t* recent, void* stream);
 
@@ -180,7 +184,8 @@ int d2o_decode_step(d2o_ctx* ctx, int32_t layer, int32_t n_layers_in_call, d2o_v
 
 /* Reserves a layer's cache region for the given budgets without running the prefill
  * stages (so that d2o_cache_import can fill it).  n is the prompt length the positions
- * refer to.  Errors: INVALID_ARG, STATE (already reserved), CAPACITY. */
+ * refer to.  Writes the layer's geometry on the default stream and waits for it.
+ * Errors: INVALID_ARG, STATE (already reserved), CAPACITY, HIP. */
 int d2o_layer_reserve(d2o_ctx* ctx, int32_t layer, int32_t n, const int32_t* budget,
                       const int32_t* recent);
 

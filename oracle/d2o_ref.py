@@ -59,8 +59,7 @@ def prefill_attention_head(q, k, v, causal: bool = True, row_block: int = 2048,
 
     A = softmax(Q K^T / sqrt(d)) row-wise (causal: keys j <= i only; the paper's
     models are decoder-only), O = A V, and the column sums s[j] = sum_i A[i, j]
-    ("sum the elements of each column", Sec. 4.1), the initial cumulative
-    attention score (Eq. 6, prompt case).  d is the head dimension.
+    (Sec. 4.1), the initial cumulative attention score (Eq. 6, prompt case).  d is the head dimension.
     Returns (O [N, d], s [N]).
 
     row_range = (lo, hi) restricts the work to query rows lo <= i < hi (rows are independent
@@ -102,7 +101,7 @@ def head_variance(colsum) -> float:
 
 def layer_density(colsums_per_q_head) -> float:
     """F_v^l of one layer: mean over its query heads of the per-head variances
-    (Eq. 4 omits heads; the paper's figures use "the mean value of heads for each layer")."""
+    (Eq. 4 omits heads; the figures of Sec. 1 and App. A.6 plot the per-layer mean over heads)."""
     vs = [head_variance(s) for s in colsums_per_q_head]
     return float(sum(vs) / len(vs))
 

@@ -47,7 +47,8 @@ int check_config(const d2o_config* c) {
   } else {
     return D2O_ERR_UNSUPPORTED;
   }
-  if (c->n_q_heads / c->n_kv_heads > 8 || c->n_q_heads > 256) return D2O_ERR_UNSUPPORTED;
+  const int G = c->n_q_heads / c->n_kv_heads;  // the decode kernels are built for these group sizes
+  if ((G != 1 && G != 2 && G != 4 && G != 8) || c->n_q_heads > 256) return D2O_ERR_UNSUPPORTED;
   if (c->out_f32 != 0 && c->out_f32 != 1) return D2O_ERR_INVALID_ARG;
   if (c->merge_average != 0 && c->merge_average != 1) return D2O_ERR_INVALID_ARG;
   return D2O_OK;
@@ -67,6 +68,7 @@ void layout(d2o_ctx* x, char* persistent, char* scratch, size_t* pbytes, size_t*
   p.take(x->cscore, B * Hkv * slots);
   p.take(x->cpos, B * Hkv * slots);
   p.take(x->ccount, L * B * Hkv);
+  p.take(x->ctotal, L * B * Hkv);
   p.take(x->ctau, L * B * Hkv);
   p.take(x->meta, L * B * 4);
   p.take(x->ev_evicted, L * B * Hkv);
@@ -162,7 +164,40 @@ hipError_t fill32(void* p, uint32_t v, size_t bytes, hipStream_t s) {
   return hipGetLastError();
 }
 
+// The per-sequence geometry of one layer travels to the device as kernel arguments (up to
+// kMetaPerLaunch sequences per launch): no host buffer has to outlive the call, so the caller's
+// stream is neither synchronised nor fed from pageable memory.
+constexpr int kMetaPerLaunch = 16;
+struct MetaPack {
+  int32_t v[kMetaPerLaunch * 4];
+};
+__global__ void write_meta_kernel(int32_t* dst, MetaPack m, int n_words) {
+  const int i = threadIdx.x;
+  if (i < n_words) dst[i] = m.v[i];
+}
+
 }  // namespace
+
+hipError_t launch_write_meta(d2o_ctx* x, int layer, hipStream_t s) {
+  const LayerState& st = x->layers[layer];
+  const int B = x->cfg.batch;
+  for (int b0 = 0; b0 < B; b0 += kMetaPerLaunch) {
+    const int nb = std::min(kMetaPerLaunch, B - b0);
+    MetaPack m;
+    for (int i = 0; i < nb; ++i) {
+      const LayerMeta& t = st.meta[b0 + i];
+      m.v[4 * i + 0] = t.base;
+      m.v[4 * i + 1] = t.budget;
+      m.v[4 * i + 2] = t.recent;
+      m.v[4 * i + 3] = t.chunk_base;
+    }
+    write_meta_kernel<<<1, kMetaPerLaunch * 4, 0, s>>>(x->meta + (size_t(layer) * B + b0) * 4, m, nb * 4);
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+  }
+  return hipSuccess;
+}
+
 }  // namespace d2o
 
 using namespace d2o;
@@ -228,6 +263,7 @@ int d2o_reset(d2o_ctx* x, void* stream) {
   D2O_HIP_CHECK(x, fill32(x->layer_F, 0xFFFFFFFFu, sizeof(double) * c.n_layers * c.batch, s));
   D2O_HIP_CHECK(x, fill32(x->head_var, 0xFFFFFFFFu, sizeof(double) * c.n_layers * c.batch * c.n_q_heads, s));
   D2O_HIP_CHECK(x, fill32(x->ccount, 0u, sizeof(int32_t) * lbh, s));
+  D2O_HIP_CHECK(x, fill32(x->ctotal, 0u, sizeof(int32_t) * lbh, s));
   D2O_HIP_CHECK(x, fill32(x->ctau, 0xFFFFFFFFu, sizeof(double) * lbh, s));
   D2O_HIP_CHECK(x, fill32(x->meta, 0u, sizeof(int32_t) * 4 * c.n_layers * c.batch, s));
   D2O_HIP_CHECK(x, fill32(x->ev_evicted, 0xFFFFFFFFu, sizeof(int32_t) * lbh, s));
@@ -419,9 +455,9 @@ int d2o_layer_reserve(d2o_ctx* x, int32_t layer, int32_t n, const int32_t* budge
   if (st.phase == kReady) return fail(x, D2O_ERR_STATE, "layer already reserved");
   int rc = reserve_layer(x, layer, n, budget, recent);
   if (rc) return rc;
-  // Metadata is tiny; a blocking copy keeps the host vector's lifetime simple.
-  hipError_t e = hipMemcpy(x->meta + size_t(layer) * c.batch * 4, st.meta.data(),
-                           sizeof(LayerMeta) * c.batch, hipMemcpyHostToDevice);
+  // no stream argument: the metadata goes out on the default stream and the call waits for it
+  hipError_t e = launch_write_meta(x, layer, nullptr);
+  if (e == hipSuccess) e = hipStreamSynchronize(nullptr);
   if (e != hipSuccess) return fail(x, D2O_ERR_HIP, hipGetErrorString(e));
   st.phase = kReady;
   return D2O_OK;
@@ -441,18 +477,17 @@ int d2o_compress_layer(d2o_ctx* x, int32_t layer, d2o_view K, d2o_view V, int32_
   int rc = reserve_layer(x, layer, n, budget, recent);
   if (rc) return rc;
   hipStream_t s = static_cast<hipStream_t>(stream);
-  D2O_HIP_CHECK(x, hipMemcpyAsync(x->meta + size_t(layer) * c.batch * 4, st.meta.data(),
-                                  sizeof(LayerMeta) * c.batch, hipMemcpyHostToDevice, s));
-  D2O_HIP_CHECK(x, hipStreamSynchronize(s));  // st.meta may be reallocated later; keep it simple
-  st.phase = kReady;
-  x->last_compress_layer = layer;
   hipError_t e;
+  if ((e = launch_write_meta(x, layer, s)) != hipSuccess) return fail(x, D2O_ERR_HIP, std::string("meta: ") + hipGetErrorString(e));
   if ((e = launch_select(x, layer, n, s)) != hipSuccess) return fail(x, D2O_ERR_HIP, std::string("select: ") + hipGetErrorString(e));
   if ((e = launch_gather(x, layer, to_view(K), to_view(V), n, s)) != hipSuccess) return fail(x, D2O_ERR_HIP, std::string("gather: ") + hipGetErrorString(e));
   if ((e = launch_match(x, layer, to_view(K), n, s)) != hipSuccess) return fail(x, D2O_ERR_HIP, std::string("match: ") + hipGetErrorString(e));
   if ((e = launch_threshold_group(x, layer, n, s)) != hipSuccess) return fail(x, D2O_ERR_HIP, std::string("threshold: ") + hipGetErrorString(e));
   if ((e = launch_merge(x, layer, to_view(K), to_view(V), n, s)) != hipSuccess) return fail(x, D2O_ERR_HIP, std::string("merge: ") + hipGetErrorString(e));
   if ((e = launch_init_candidates(x, layer, st.next_pos, s)) != hipSuccess) return fail(x, D2O_ERR_HIP, std::string("candidates: ") + hipGetErrorString(e));
+  // (a failed launch leaves the layer's slots reserved but the layer not ready: d2o_reset recovers)
+  st.phase = kReady;
+  x->last_compress_layer = layer;
   return D2O_OK;
 }
 

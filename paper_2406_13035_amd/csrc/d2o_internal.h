@@ -69,6 +69,7 @@ struct d2o_ctx {
   double* cscore = nullptr;      // [B][Hkv][slots]
   int32_t* cpos = nullptr;       // [B][Hkv][slots]
   int32_t* ccount = nullptr;     // [L][B][Hkv]
+  int32_t* ctotal = nullptr;     // [L][B][Hkv] entries of the running decode step (count + 1), fixed for the whole step
   double* ctau = nullptr;        // [L][B][Hkv]
   int32_t* meta = nullptr;       // [L][B][4]
   int32_t* ev_evicted = nullptr; // [L][B][Hkv]
@@ -159,5 +160,6 @@ hipError_t launch_decode(d2o_ctx* c, int layer0, int nl, View q, View k, View v,
                          int new_pos, hipStream_t s);
 int decode_candidates();  // eviction candidates tracked per (layer, sequence, KV head)
 hipError_t launch_init_candidates(d2o_ctx* c, int layer, int new_pos, hipStream_t s);
+hipError_t launch_write_meta(d2o_ctx* c, int layer, hipStream_t s);  // the layer's host meta -> device, by a kernel
 
 }  // namespace d2o

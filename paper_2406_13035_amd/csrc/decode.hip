@@ -51,6 +51,7 @@ constexpr int kGroup = 1;               // chunks of 256 slots per workgroup
 
 struct DecodeArgs {
   int32_t* ccount;
+  int32_t* ctotal;    // [L][B][Hkv] entries of this step (count + 1): written by decode_prepare, never by decode_attend
   double* ctau;
   const int32_t* meta;
   void* cK;
@@ -235,6 +236,10 @@ __global__ __launch_bounds__(128) void decode_prepare(DecodeArgs a, const T* __r
   if (c == 0) {
     a.cscore[slot0 + count] = 0.0;
     a.cpos[slot0 + count] = a.new_pos;
+    // The step's entry count gets a word of its own: the head's closing workgroup overwrites
+    // ccount while other workgroups of the same launch may not have started yet, and those
+    // must still see the count the step began with.
+    a.ctotal[lbh] = count + 1;
   }
   double* vec = a.vecs + lbh * (G + kCand) * D;
 #pragma unroll
@@ -718,7 +723,7 @@ __global__ __launch_bounds__(256) void decode_attend(DecodeArgs a, OT* __restric
   typedef const int32_t __attribute__((address_space(4))) * ciptr;
   typedef const double __attribute__((address_space(4))) * cptr;
   const ciptr mt = (ciptr)a.meta + (l * a.B + b) * 4;
-  const int total = ((ciptr)a.ccount)[lbh] + 1;  // the new token has been appended
+  const int total = ((ciptr)a.ctotal)[lbh];  // the new token has been appended; constant during this launch
   const int mt0 = mt[0], mt3 = mt[3];
   int cs[kCand];
   double cn[kCand];
@@ -941,6 +946,12 @@ __global__ __launch_bounds__(256) void decode_attend(DecodeArgs a, OT* __restric
   }
   __syncthreads();
   if (!sh_last) return;
+  // Consumer side of the hand-over.  The other workgroups' results (rec, elog, pacc) are read
+  // below through ld_agent only, which goes around this XCD's L2 whatever the compiler does
+  // with plain loads; this fence keeps the compiler from moving any load of the closing code
+  // above the ticket.  Plain loads in the closing code are limited to data that no other
+  // workgroup of this launch writes: cscore, cpos, cK, cV, ctau, cand, meta of this head.
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
   // the staging area is free: it holds the closing code's exchange buffers
   float* fred = reinterpret_cast<float*>(stage);
   double* dred = reinterpret_cast<double*>(stage + 4 * 256 * sizeof(float));
@@ -1059,6 +1070,7 @@ hipError_t launch_decode(d2o_ctx* c, int layer0, int nl_all, View q, View k, Vie
   const d2o_config& cf = c->cfg;
   DecodeArgs a;
   a.ccount = c->ccount;
+  a.ctotal = c->ctotal;
   a.ctau = c->ctau;
   a.meta = c->meta;
   a.cK = c->cacheK;

@@ -4,7 +4,7 @@
 // (pass 2).  The bf16 path in prefill_bf16.hip uses the matrix cores instead.
 //
 // Pass 1 (Sec. 4.1 Eq. 4, Sec. 3 Eq. 3): O = softmax(Q K^T / sqrt(d)) V, causal, and the row
-//   log-sum-exp.  Pass 2 ("sum the elements of each column", Sec. 4.1; Eq. 6 prompt case):
+//   log-sum-exp.  Pass 2 (column sums of the attention matrix, Sec. 4.1; Eq. 6 prompt case):
 //   score[j] = sum_g sum_{i >= j} exp(s_ij - lse_i), plus per-query-head partial sums of the
 //   column sums and their squares for the variance of Eq. 4.
 #include "d2o_internal.h"

@@ -43,6 +43,11 @@ def test_workspace_query_and_config_validation(lib):
     assert lib.d2o_workspace_bytes(C.byref(bad), C.byref(p), C.byref(s)) == -2      # head_dim
     bad = binding.d2o_config(1, 32, 32, 32, 128, 4096, 30000, binding.D2O_BF16, 0, 1.0, float("nan"), 0)
     assert lib.d2o_workspace_bytes(C.byref(bad), C.byref(p), C.byref(s)) == -1      # beta = 1
+    for hkv in (8, 4, 2, 1, 3, 6):    # G = 24 / Hkv = 3, 6, 12, 24 have no decode kernel; 8 and 4 do
+        cfg = binding.d2o_config(1, 2, 24, hkv, 128, 512, 300, binding.D2O_BF16, 0, 0.7, float("nan"), 0)
+        g = 24 // hkv
+        want = 0 if g in (1, 2, 4, 8) else -2
+        assert lib.d2o_workspace_bytes(C.byref(cfg), C.byref(p), C.byref(s)) == want, (hkv, g)
 
 
 def test_allocate_budgets_matches_oracle_bit_for_bit(lib):

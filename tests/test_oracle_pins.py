@@ -85,6 +85,28 @@ def test_zero_query_noncausal_is_uniform():
     assert ref.layer_density([s, s]) < 1e-26
 
 
+def test_layer_density_is_the_mean_of_the_head_variances():
+    """Eq. 4 with the per-head form of App. A.8: three heads whose column sums have the exact
+    population variances 1, 8 and 0 (by hand: [1, 3] -> mean 2, deviations +-1; [0, 0, 6] ->
+    mean 2, squared deviations 4, 4, 16; a constant vector) give F = (1 + 8 + 0) / 3 = 3.
+    A sum over heads (9), a sample variance (2, 12, 0 -> 14 / 3) or a variance of the pooled
+    values would all miss 3."""
+    heads = [np.array([1.0, 3.0]), np.array([0.0, 0.0, 6.0]), np.full(5, 2.5)]
+    assert ref.head_variance(heads[0]) == 1.0 and ref.head_variance(heads[1]) == 8.0
+    assert ref.layer_density(heads) == 3.0
+    assert ref.layer_density(heads[:2]) == 4.5
+    # a harmonic head (Q = 0, causal) next to a uniform one: half the closed-form variance
+    n = 12
+    Hn = [Fraction(0)]
+    for i in range(1, n + 1):
+        Hn.append(Hn[-1] + Fraction(1, i))
+    s = [Hn[n] - Hn[j] for j in range(n)]
+    mu = sum(s) / n
+    var = sum((x - mu) ** 2 for x in s) / n
+    got = ref.layer_density([np.array([float(x) for x in s]), np.ones(n)])
+    assert abs(got - float(var) / 2) < 1e-14
+
+
 def test_constant_values_give_constant_output():
     v = np.tile(np.array([[1.5, -2.0, 0.25]]), (20, 1))
     o, _ = ref.prefill_attention_head(_rand(20, 3, 3) * 3, _rand(20, 3, 4), v)
