@@ -182,6 +182,23 @@ int d2o_prefill_compress(d2o_ctx* ctx, int32_t layer, d2o_view Q, d2o_view K, d2
 int d2o_decode_step(d2o_ctx* ctx, int32_t layer, int32_t n_layers_in_call, d2o_view q,
                     d2o_view k_new, d2o_view v_new, d2o_view out, void* stream);
 
+/* d2o_decode_step for callers that cannot allocate or hand over scratch memory at the time of
+ * the call: code under HIP graph capture, tight serving loops, harnesses that forbid
+ * allocation.  Same arguments, same results (bit for bit) and same errors as d2o_decode_step,
+ * but the step's temporaries (per-slot softmax terms, per-chunk partial outputs and records,
+ * the fp64 operand vectors) live in a static device array inside the library instead of the
+ * context's scratch workspace, and the call makes no allocation of any kind (no device or
+ * host memory, no events: kernel timing is off for these calls).  The array holds 64 MiB
+ * (67108864 bytes) per GPU from the moment the library's code is loaded there until the
+ * process ends; a context whose decode step needs more (about 10 G + 3 bytes per cache slot
+ * of slots_per_seq, sequence and KV head, plus G + 3 KiB per layer, sequence and KV head at
+ * d = 128) gets D2O_ERR_CAPACITY and nothing is launched.  All contexts on a GPU share the array, which keeps the last call's
+ * contents: calls that overlap in time on one GPU (different streams or threads) race; calls
+ * ordered on one stream do not.  Nothing is carried in it from one step to the next, so a
+ * context may mix the two entry points freely. */
+int d2o_decode_step_static(d2o_ctx* ctx, int32_t layer, int32_t n_layers_in_call, d2o_view q,
+                           d2o_view k_new, d2o_view v_new, d2o_view out, void* stream);
+
 /* Reserves a layer's cache region for the given budgets without running the prefill
  * stages (so that d2o_cache_import can fill it).  n is the prompt length the positions
  * refer to.  Writes the layer's geometry on the default stream and waits for it.

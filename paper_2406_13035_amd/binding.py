@@ -21,6 +21,7 @@ EXPORTS = [
     "d2o_prefill_attend", "d2o_get_density", "d2o_allocate_budgets", "d2o_allocate_budgets_policy",
     "d2o_scores_import",
     "d2o_scores_export", "d2o_compress_layer", "d2o_prefill_compress", "d2o_decode_step",
+    "d2o_decode_step_static",
     "d2o_layer_reserve", "d2o_cache_export", "d2o_cache_import", "d2o_last_events",
     "d2o_prefill_events", "d2o_timing_enable", "d2o_timing_read",
 ]
@@ -74,6 +75,7 @@ def load_library() -> C.CDLL:
     lib.d2o_prefill_compress.argtypes = [vp, i32, d2o_view, d2o_view, d2o_view, i32, d2o_view,
                                          vp, vp, vp]
     lib.d2o_decode_step.argtypes = [vp, i32, i32, d2o_view, d2o_view, d2o_view, d2o_view, vp]
+    lib.d2o_decode_step_static.argtypes = [vp, i32, i32, d2o_view, d2o_view, d2o_view, d2o_view, vp]
     lib.d2o_layer_reserve.argtypes = [vp, i32, i32, vp, vp]
     lib.d2o_cache_export.argtypes = [vp, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp]
     lib.d2o_cache_import.argtypes = [vp, i32, i32, i32, vp, vp, vp, vp, i32, C.c_double, i32, vp]
@@ -240,6 +242,11 @@ class D2O:
         self._check(self.lib.d2o_decode_step(self.ctx, layer, n_layers_in_call, view_decode(q),
                                              view_decode(k_new), view_decode(v_new),
                                              view_decode(out), _stream_ptr()), "d2o_decode_step")
+
+    def d2o_decode_step_static(self, layer, n_layers_in_call, q, k_new, v_new, out):
+        self._check(self.lib.d2o_decode_step_static(self.ctx, layer, n_layers_in_call, view_decode(q),
+                                                    view_decode(k_new), view_decode(v_new),
+                                                    view_decode(out), _stream_ptr()), "d2o_decode_step_static")
 
     def d2o_timing_enable(self, on):
         """False / 0: off.  True / 1: every launch.  n > 1: decode kernels every n-th launch."""

@@ -239,6 +239,13 @@ int d2o_create(const d2o_config* cfg, void* persistent_dev, size_t persistent_by
     delete x;
     return rc;
   }
+  // set-up time is when this device's address of the static scratch array is looked up
+  // (d2o_decode_step_static then finds it cached and makes no runtime query of its own)
+  unsigned char* stat = nullptr;
+  if (static_scratch_address(&stat) != hipSuccess) {
+    delete x;
+    return D2O_ERR_HIP;
+  }
   *out = x;
   return D2O_OK;
 }
@@ -498,8 +505,8 @@ int d2o_prefill_compress(d2o_ctx* x, int32_t layer, d2o_view Q, d2o_view K, d2o_
   return d2o_compress_layer(x, layer, K, V, n, budget, recent, stream);
 }
 
-int d2o_decode_step(d2o_ctx* x, int32_t layer, int32_t nl, d2o_view q, d2o_view k_new, d2o_view v_new,
-                    d2o_view out, void* stream) {
+static int decode_step_impl(d2o_ctx* x, int32_t layer, int32_t nl, d2o_view q, d2o_view k_new, d2o_view v_new,
+                            d2o_view out, void* stream, bool use_static) {
   if (!x) return D2O_ERR_INVALID_ARG;
   const d2o_config& c = x->cfg;
   if (layer < 0 || nl < 1 || layer + nl > c.n_layers) return fail(x, D2O_ERR_INVALID_ARG, "layer range");
@@ -511,11 +518,33 @@ int d2o_decode_step(d2o_ctx* x, int32_t layer, int32_t nl, d2o_view q, d2o_view 
     if (x->layers[l].next_pos != new_pos)
       return fail(x, D2O_ERR_STATE, "layers of one call must be at the same token position");
   }
+  unsigned char* stat = nullptr;
+  if (use_static) {
+    const size_t need = decode_static_scratch_need(x), cap = decode_static_scratch_capacity();
+    if (need > cap)
+      return fail(x, D2O_ERR_CAPACITY, "a decode step of this context needs " + std::to_string(need) +
+                                           " bytes of scratch, the static array holds " + std::to_string(cap));
+    const hipError_t e = static_scratch_address(&stat);
+    if (e != hipSuccess) return fail(x, D2O_ERR_HIP, std::string("static scratch: ") + hipGetErrorString(e));
+  }
+  const int timing = x->timing;
+  if (use_static) x->timing = 0;  // timing events are runtime objects: none are created on this path
   hipError_t e = launch_decode(x, layer, nl, to_view(q), to_view(k_new), to_view(v_new), to_view(out),
-                               new_pos, static_cast<hipStream_t>(stream));
+                               new_pos, static_cast<hipStream_t>(stream), stat);
+  x->timing = timing;
   if (e != hipSuccess) return fail(x, D2O_ERR_HIP, std::string("decode: ") + hipGetErrorString(e));
   for (int l = layer; l < layer + nl; ++l) ++x->layers[l].next_pos;
   return D2O_OK;
+}
+
+int d2o_decode_step(d2o_ctx* x, int32_t layer, int32_t nl, d2o_view q, d2o_view k_new, d2o_view v_new,
+                    d2o_view out, void* stream) {
+  return decode_step_impl(x, layer, nl, q, k_new, v_new, out, stream, false);
+}
+
+int d2o_decode_step_static(d2o_ctx* x, int32_t layer, int32_t nl, d2o_view q, d2o_view k_new, d2o_view v_new,
+                           d2o_view out, void* stream) {
+  return decode_step_impl(x, layer, nl, q, k_new, v_new, out, stream, true);
 }
 
 static int head_args_ok(d2o_ctx* x, int32_t layer, int32_t b, int32_t h) {

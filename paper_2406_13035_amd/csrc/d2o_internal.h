@@ -156,8 +156,13 @@ hipError_t launch_gather(d2o_ctx* c, int layer, View K, View V, int n, hipStream
 hipError_t launch_match(d2o_ctx* c, int layer, View K, int n, hipStream_t s);
 hipError_t launch_threshold_group(d2o_ctx* c, int layer, int n, hipStream_t s);
 hipError_t launch_merge(d2o_ctx* c, int layer, View K, View V, int n, hipStream_t s);
+// static_scratch: nullptr = the context's scratch workspace; otherwise the device address of the
+// library's static scratch array, which then holds the step's partial results and operands
 hipError_t launch_decode(d2o_ctx* c, int layer0, int nl, View q, View k, View v, View out,
-                         int new_pos, hipStream_t s);
+                         int new_pos, hipStream_t s, unsigned char* static_scratch = nullptr);
+hipError_t static_scratch_address(unsigned char** out);  // per device; first call per device looks it up
+size_t decode_static_scratch_need(const d2o_ctx* c);     // bytes of it a decode step of this context uses
+size_t decode_static_scratch_capacity();
 int decode_candidates();  // eviction candidates tracked per (layer, sequence, KV head)
 hipError_t launch_init_candidates(d2o_ctx* c, int layer, int new_pos, hipStream_t s);
 hipError_t launch_write_meta(d2o_ctx* c, int layer, hipStream_t s);  // the layer's host meta -> device, by a kernel

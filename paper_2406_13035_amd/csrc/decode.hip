@@ -36,6 +36,42 @@
 #include "device_utils.h"
 
 namespace d2o {
+
+// Scratch memory of d2o_decode_step_static: the partial results and operand vectors of one
+// generation step, for callers that cannot hand over (or allocate) a scratch workspace.  One
+// copy per GPU, held from the moment the library's code is loaded on it until the process ends.
+// In host code the array's name is only a handle: the device address comes from
+// hipGetSymbolAddress, once per device, and is what kernels and launchers are given.
+constexpr size_t kStaticScratchBytes = size_t(64) << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+namespace {
+
+constexpr int kMaxDevices = 64;
+unsigned char* g_static_scratch[kMaxDevices] = {};  // device address of `scratch` per device (0: not looked up yet)
+
+}  // namespace
+
+// Device address of the static scratch array on the current device (looked up on the first
+// call per device; allocates nothing: the array is part of the loaded code object).
+hipError_t static_scratch_address(unsigned char** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  unsigned char* p = __atomic_load_n(&g_static_scratch[dev], __ATOMIC_ACQUIRE);
+  if (!p) {
+    void* sym = nullptr;
+    e = hipGetSymbolAddress(&sym, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (!sym) return hipErrorInvalidSymbol;
+    p = static_cast<unsigned char*>(sym);
+    __atomic_store_n(&g_static_scratch[dev], p, __ATOMIC_RELEASE);  // every thread would store the same address
+  }
+  *out = p;
+  return hipSuccess;
+}
+
 namespace {
 
 constexpr int kCand = 3;                // eviction candidates whose similarities ride along with the attention pass
@@ -1065,8 +1101,29 @@ hipError_t launch_init_candidates(d2o_ctx* c, int layer, int new_pos, hipStream_
   return hipGetLastError();
 }
 
+// Sizes (in bytes, each rounded up to 256) of the five scratch arrays of a decode step, in the
+// order elog, rec, pacc, vecs, cnorm.
+static void decode_scratch_sizes(const d2o_ctx* c, size_t (&sz)[5]) {
+  const d2o_config& cf = c->cfg;
+  const size_t B = cf.batch, L = cf.n_layers, Hq = cf.n_q_heads, Hkv = cf.n_kv_heads, d = cf.head_dim;
+  const size_t G = Hq / Hkv, bh = B * Hkv, nch = c->nchunk_cap, nsub = nch * 4;
+  sz[0] = nch * B * Hq * kChunk * sizeof(double);
+  sz[1] = bh * nsub * rec_doubles(int(G)) * sizeof(double);  // one record per 64 slots
+  sz[2] = bh * nch * G * d * sizeof(float);                  // one partial output row per chunk and query head
+  sz[3] = L * bh * (G + kCand) * d * sizeof(double);
+  sz[4] = L * bh * kCand * sizeof(double);
+  for (size_t& x : sz) x = (x + 255) & ~size_t(255);
+}
+
+size_t decode_static_scratch_need(const d2o_ctx* c) {
+  size_t sz[5];
+  decode_scratch_sizes(c, sz);
+  return sz[0] + sz[1] + sz[2] + sz[3] + sz[4];
+}
+size_t decode_static_scratch_capacity() { return kStaticScratchBytes; }
+
 hipError_t launch_decode(d2o_ctx* c, int layer0, int nl_all, View q, View k, View v, View out, int new_pos,
-                         hipStream_t s) {
+                         hipStream_t s, unsigned char* static_scratch) {
   const d2o_config& cf = c->cfg;
   DecodeArgs a;
   a.ccount = c->ccount;
@@ -1084,6 +1141,16 @@ hipError_t launch_decode(d2o_ctx* c, int layer0, int nl_all, View q, View k, Vie
   a.pacc = c->d_pacc;
   a.vecs = c->d_vecs;
   a.cnorm = c->d_cnorm;
+  if (static_scratch) {  // the same five arrays, carved from the library's static device array
+    size_t sz[5];
+    decode_scratch_sizes(c, sz);
+    unsigned char* p = static_scratch;
+    a.elog = reinterpret_cast<double*>(p);
+    a.rec = reinterpret_cast<double*>(p += sz[0]);
+    a.pacc = reinterpret_cast<float*>(p += sz[1]);
+    a.vecs = reinterpret_cast<double*>(p += sz[2]);
+    a.cnorm = reinterpret_cast<double*>(p += sz[3]);
+  }
   a.ev_evicted = c->ev_evicted;
   a.ev_target = c->ev_target;
   a.ev_ustar = c->ev_ustar;
