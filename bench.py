@@ -235,7 +235,8 @@ def main():
     slots_b = budgets.sum(axis=1) + L
     bytes_per_launch = float(sum(int(s) for s in slots_b) * w.n_kv_heads * (2 * d * es + 8))
     da_ms, da_n = kt["decode_attend"]
-    dec_gbs = bytes_per_launch / (da_ms / da_n * 1e-3) / 1e9 if da_n else 0.0
+    da_avg = da_ms / da_n if da_n else None
+    dec_gbs = bytes_per_launch / (da_avg * 1e-3) / 1e9 if da_n else 0.0
     step_bytes = bytes_per_launch  # whole decode step, algorithmic (K second touch not counted)
     out = {
         "metric": "compressed-KV decode tokens/s (+ prefill-compress ms/layer at N=32k)",
@@ -261,7 +262,7 @@ def main():
                             "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": dec_gbs / PEAK_HBM_GBS,
                             "traffic": measured_traffic(w.cfg, "decode_attend"),
                             "algorithmic_bytes_per_launch": bytes_per_launch,
-                            "avg_launch_ms": da_ms / da_n if da_n else None},
+                            "avg_launch_ms": da_avg},
         "kernel_ms_per_launch": {k: (v[0] / v[1] if v[1] else None) for k, v in kt.items()},
     }
     if args.zero_data_probe:

@@ -12,18 +12,38 @@ LIB = os.environ.get("D2O_LIB", os.path.join(HERE, "libd2o.so"))
 
 
 def build(verbose: bool = False) -> str:
+    """Compiles every source (in parallel, one hipcc per file) and links libd2o.so."""
+    from concurrent.futures import ThreadPoolExecutor
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc, "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
-           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-           "-I", os.path.join(ROOT, "include"), "-I", os.path.join(HERE, "csrc"),
-           "-Wno-unused-value", "-o", LIB] + os.environ.get("D2O_EXTRA_FLAGS", "").split() + [os.path.join(HERE, "csrc", s) for s in SOURCES]
-    res = subprocess.run(cmd, capture_output=True, text=True)
-    msgs = "\n".join(l for l in (res.stdout + res.stderr).splitlines()
-                     if "packed-fp32-ops" not in l)
+    objdir = os.path.join(HERE, "_build")
+    os.makedirs(objdir, exist_ok=True)
+    flags = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
+             "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+             "-I", os.path.join(ROOT, "include"), "-I", os.path.join(HERE, "csrc"),
+             "-Wno-unused-value"] + os.environ.get("D2O_EXTRA_FLAGS", "").split()
+
+    def compile_one(src):
+        obj = os.path.join(objdir, src.replace(".hip", ".o"))
+        res = subprocess.run([hipcc, "-c"] + flags + ["-o", obj, os.path.join(HERE, "csrc", src)],
+                             capture_output=True, text=True)
+        return src, obj, res
+
+    msgs = []
+    objs = []
+    with ThreadPoolExecutor(max_workers=min(len(SOURCES), int(os.environ.get("MAX_JOBS", "8")))) as ex:
+        for src, obj, res in ex.map(compile_one, SOURCES):
+            out = "\n".join(l for l in (res.stdout + res.stderr).splitlines() if "packed-fp32-ops" not in l)
+            if res.returncode != 0:
+                raise RuntimeError(f"hipcc failed on {src}:\n" + out)
+            if out.strip():
+                msgs.append(out)
+            objs.append(obj)
+    res = subprocess.run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + objs,
+                         capture_output=True, text=True)
     if res.returncode != 0:
-        raise RuntimeError("hipcc failed:\n" + msgs)
-    if verbose and msgs.strip():
-        print(msgs, file=sys.stderr)
+        raise RuntimeError("link failed:\n" + res.stdout + res.stderr)
+    if verbose and msgs:
+        print("\n".join(msgs), file=sys.stderr)
     return LIB
 
 

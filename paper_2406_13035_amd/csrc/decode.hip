@@ -32,8 +32,7 @@
 // Slots are physically unordered; a token's identity is its position.
 #include <algorithm>
 
-#include "d2o_internal.h"
-#include "device_utils.h"
+#include "decode_common.h"
 
 namespace d2o {
 
@@ -74,185 +73,8 @@ hipError_t static_scratch_address(unsigned char** out) {
 
 namespace {
 
-constexpr int kCand = 3;                // eviction candidates whose similarities ride along with the attention pass
-constexpr int kMaxLayersPerCall = 64;
-// Doubles per sub-chunk record: the G softmax maxima, the G exp-sums, then per candidate its
-// best cosine and that key's slot; rounded up to a multiple of eight (64 bytes).
-__host__ __device__ constexpr int rec_doubles(int G) { return (2 * G + 2 * kCand + 7) / 8 * 8; }
-constexpr int kPiece = 128;             // bytes of a cache row staged per LDS round
-constexpr int kPitch = kPiece + 16;     // LDS pitch of a staged row piece: conflict-free b128 reads
-constexpr int kStageBytes = 4 * 64 * kPitch;
-constexpr int kSub = 64;                // rows one wavefront handles at a time (lane = row)
-constexpr int kGroup = 1;               // chunks of 256 slots per workgroup
+using namespace dec;
 
-struct DecodeArgs {
-  int32_t* ccount;
-  int32_t* ctotal;    // [L][B][Hkv] entries of this step (count + 1): written by decode_prepare, never by decode_attend
-  double* ctau;
-  const int32_t* meta;
-  void* cK;
-  void* cV;
-  double* cscore;
-  int32_t* cpos;
-  int32_t* cand;      // [L][B][Hkv][kCand] candidate slots for this step, -1 = none
-  uint32_t* ticket;   // [L][B][Hkv] finished chunks of the running step
-  double* elog;       // [chunk][B][Hkv][G][256] exp(logit - sub-chunk max)
-  double* rec;        // [chunk][B][Hkv][4][rec_doubles(G)] per sub-chunk record: [0..G) softmax maxima of the
-                      // query heads, [G..2G) exp-sums relative to them, [2G..2G+kCand) the candidates' best
-                      // cosine, [2G+kCand..2G+2kCand) its slot (-1 none); written with one store
-  float* pacc;        // [chunk][B][Hkv][G][d] partial outputs, relative to the chunk's softmax maximum
-  double* vecs;       // [L][B][Hkv][G + kCand][d] queries and candidate keys as fp64
-  double* cnorm;      // [L][B][Hkv][kCand] |k| of the candidates
-  int32_t* ev_evicted;
-  int32_t* ev_target;
-  double* ev_ustar;
-  int64_t slots;
-  int layer0, nl, B, Hkv, G, new_pos, n_sink, out_f32, merge_average;
-  double beta, tau_force;
-  int32_t lay_off[kMaxLayersPerCall + 1];  // first flat chunk-group index of each entry of lay_id
-  int32_t lay_id[kMaxLayersPerCall];       // layers of the call (relative), most chunks first
-};
-
-template <typename T>
-__device__ __forceinline__ void cvt16(const u32x4& v, double* out);  // 16 bytes -> 8 or 4 doubles
-template <>
-__device__ __forceinline__ void cvt16<uint16_t>(const u32x4& v, double* out) {
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    out[2 * i] = double(__uint_as_float(v[i] << 16));
-    out[2 * i + 1] = double(__uint_as_float(v[i] & 0xFFFF0000u));
-  }
-}
-template <>
-__device__ __forceinline__ void cvt16<float>(const u32x4& v, double* out) {
-#pragma unroll
-  for (int i = 0; i < 4; ++i) out[i] = double(__uint_as_float(v[i]));
-}
-template <typename T>
-__device__ __forceinline__ void cvt16f(const u32x4& v, float* out);
-template <>
-__device__ __forceinline__ void cvt16f<uint16_t>(const u32x4& v, float* out) {
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    out[2 * i] = __uint_as_float(v[i] << 16);
-    out[2 * i + 1] = __uint_as_float(v[i] & 0xFFFF0000u);
-  }
-}
-template <>
-__device__ __forceinline__ void cvt16f<float>(const u32x4& v, float* out) {
-#pragma unroll
-  for (int i = 0; i < 4; ++i) out[i] = __uint_as_float(v[i]);
-}
-
-// N consecutive elements (4, 8 or 16 bytes) held as raw bits, and their conversion to doubles.
-template <int BYTES> struct RawBits;
-template <> struct RawBits<16> { typedef u32x4 type; };
-template <> struct RawBits<8> { typedef u32x2 type; };
-template <> struct RawBits<4> { typedef uint32_t type; };
-__device__ __forceinline__ uint32_t raw_word(const u32x4& r, int i) { return r[i]; }
-__device__ __forceinline__ uint32_t raw_word(const u32x2& r, int i) { return r[i]; }
-__device__ __forceinline__ uint32_t raw_word(const uint32_t& r, int) { return r; }
-template <typename T, int N, typename R>
-__device__ __forceinline__ void raw_to_f64(const R& r, double* out) {
-  if constexpr (sizeof(T) == 2) {
-#pragma unroll
-    for (int i = 0; i < N / 2; ++i) {
-      out[2 * i] = double(__uint_as_float(raw_word(r, i) << 16));
-      out[2 * i + 1] = double(__uint_as_float(raw_word(r, i) & 0xFFFF0000u));
-    }
-  } else {
-#pragma unroll
-    for (int i = 0; i < N; ++i) out[i] = double(__uint_as_float(raw_word(r, i)));
-  }
-}
-
-// The partial results of a step are laid out chunk-major: [layer's chunk offset + chunk]
-// [sequence][KV head]...  Workgroups are dispatched head-fastest, so the results that are written
-// at about the same time are neighbours in memory (per-head contiguous arrays scatter them; a
-// streaming probe with this kernel's store pattern lost 6.2 -> 5.0 TB/s of read rate to the
-// scattered form and 6.2 -> 5.3 to this one).
-__device__ __forceinline__ int64_t sub_index(const DecodeArgs& a, int64_t bh, int chunk0, int c) {  // sub-chunk c of the head
-  return ((int64_t(chunk0) + (c >> 2)) * (a.B * a.Hkv) + bh) * 4 + (c & 3);
-}
-__device__ __forceinline__ int64_t chunk_index(const DecodeArgs& a, int64_t bh, int chunk0, int chunk) {  // chunk of the head
-  return (int64_t(chunk0) + chunk) * (a.B * a.Hkv) + bh;
-}
-__device__ __forceinline__ int64_t elog_index(const DecodeArgs& a, int64_t bh, int chunk0, int G, int g, int j) {  // slot j
-  return (((int64_t(chunk0) + (j >> 8)) * (a.B * a.Hkv) + bh) * G + g) * kChunk + (j & (kChunk - 1));
-}
-
-// Pins the point where a scalar-loaded value must have arrived; nothing is scheduled across it.
-__device__ __forceinline__ void arrived(double v) {
-  asm volatile("" ::"s"(v));
-  __builtin_amdgcn_sched_barrier(0);
-}
-
-// Data that one workgroup of decode_attend hands to another (the head's last workgroup) goes
-// through agent-scope stores and loads: they write through / read around the per-XCD L2, so
-// the hand-over needs no L2 write-back (a release fence at agent scope writes the whole L2
-// back, once per workgroup, which costs more than the attention pass itself).
-template <typename U>
-__device__ __forceinline__ void st_agent(U* p, U v) {
-  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-template <typename U>
-__device__ __forceinline__ U ld_agent(const U* p) {
-  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-
-__device__ __forceinline__ float4 ld_agent4(const float* p) {  // 16 bytes as two 8-byte loads
-  const uint64_t lo = ld_agent(reinterpret_cast<const uint64_t*>(p));
-  const uint64_t hi = ld_agent(reinterpret_cast<const uint64_t*>(p) + 1);
-  return make_float4(__uint_as_float(uint32_t(lo)), __uint_as_float(uint32_t(lo >> 32)),
-                     __uint_as_float(uint32_t(hi)), __uint_as_float(uint32_t(hi >> 32)));
-}
-
-// Which entry of the call's layer list a flat chunk index belongs to (block-uniform).  The
-// list is sorted by size, so the workgroups dispatched last belong to the smallest caches.
-// Unused entries of lay_off hold INT_MAX, so the search is a fixed chain of scalar compares on
-// kernel arguments: no memory round trip precedes the loads that depend on the layer.
-__device__ __forceinline__ int find_entry(const DecodeArgs& a, int x) {
-  int entry = 0;
-#pragma unroll
-  for (int i = 1; i < kMaxLayersPerCall; ++i) entry += x >= a.lay_off[i] ? 1 : 0;
-  return entry;
-}
-
-// (u larger, then position smaller) wins; slot < 0 means "no entry".
-struct Best {
-  double u;
-  int pos, slot;
-};
-__device__ __forceinline__ bool better_match(double u, int p, int s, const Best& b) {
-  return s >= 0 && (b.slot < 0 || u > b.u || (u == b.u && p < b.pos));
-}
-// Wavefront arg-max of that order for one entry per lane whose positions are all different and
-// whose u is never below -1 (a cosine): largest u, then smallest position, then that lane's slot.
-__device__ __forceinline__ Best fast_wave_best_match(double u, int pos, int slot) {
-  const bool live = slot >= 0;
-  const double umax = fast_wave_max(live ? u : -INFINITY);
-  const bool top = live && u == umax;
-  const int pmin = fast_wave_min(top ? pos : 0x7FFFFFFF);
-  const unsigned long long who = __ballot(top && pos == pmin);
-  if (who == 0ull) return Best{0.0, 0, -1};
-  const int src = __ffsll((long long)who) - 1;
-  return Best{umax, pmin, __builtin_amdgcn_readlane(slot, src)};
-}
-// (score smaller, then position larger) wins: the order in which tokens are evicted.
-__device__ __forceinline__ bool evicts_before(double s, int p, int sl, const Best& b) {
-  return sl >= 0 && (b.slot < 0 || s < b.u || (s == b.u && p > b.pos));
-}
-// Wavefront-wide first of that order, for one entry per lane whose positions are all different.
-__device__ __forceinline__ Best fast_wave_first_evicted(const Best& b) {
-  const bool live = b.slot >= 0;
-  const double smin = -fast_wave_max(live ? -b.u : -INFINITY);
-  const bool top = live && b.u == smin;
-  const int pmax = -fast_wave_min(top ? -b.pos : 0x7FFFFFFF);
-  const unsigned long long who = __ballot(top && b.pos == pmax);
-  if (who == 0ull) return Best{0.0, 0, -1};
-  const int src = __ffsll((long long)who) - 1;
-  return Best{smin, pmax, __builtin_amdgcn_readlane(b.slot, src)};
-}
 template <typename T, typename OT, int D, int G>
 __global__ __launch_bounds__(128) void decode_prepare(DecodeArgs a, const T* __restrict__ q, View qv,
                                                       const T* __restrict__ kn, View kv, const T* __restrict__ vn,
@@ -302,109 +124,6 @@ __global__ __launch_bounds__(128) void decode_prepare(DecodeArgs a, const T* __r
   if (c < kCand) a.cnorm[lbh * kCand + c] = sqrt(red[c] + red[kCand + c]);  // wavefront 0's sum first
 }
 
-// Eq. 9 arg-max result -> Eq. 10 threshold, Eq. 11-12 merge with one source, slot bookkeeping.
-// Called by every thread of a workgroup (at least D threads) with block-uniform arguments.
-// told: the head's threshold before the step; (kl, vl): this thread's element of the last slot's
-// row as it was before the step; (sl, pl): that slot's updated score and its position.
-template <typename T, int D>
-__device__ __forceinline__ void finish_head(const DecodeArgs& a, int64_t lbh, int64_t slot0, int es, int total,
-                                            double best, int bp, int bs, double told, T kl, T vl, double sl,
-                                            int pl) {
-  T* Kc = static_cast<T*>(a.cK) + slot0 * D;
-  T* Vc = static_cast<T*>(a.cV) + slot0 * D;
-  const int tid = threadIdx.x, last = total - 1;
-  bool do_merge;
-  if (isnan(a.tau_force)) {
-    const double tnew = isnan(told) ? best : __dadd_rn(__dmul_rn(a.beta, best), __dmul_rn(1.0 - a.beta, told));
-    do_merge = best >= tnew;
-    if (tid == 0) a.ctau[lbh] = tnew;
-  } else {
-    do_merge = best >= a.tau_force;
-  }
-  if (tid == 0) {
-    a.ev_evicted[lbh] = es == last ? pl : a.cpos[slot0 + es];
-    a.ev_target[lbh] = do_merge ? bp : -1;
-    a.ev_ustar[lbh] = best;
-    a.ccount[lbh] = last;
-  }
-  if (tid < D) {
-    if (do_merge) {
-      // exp(1), the retained token's self-similarity weight; average merging weighs both rows 1
-      const double e1 = a.merge_average ? 1.0 : 2.718281828459045;
-      const double w = a.merge_average ? 1.0 : exp(best);
-      const double z = __dadd_rn(e1, w);
-      const T ke = es == last ? kl : Kc[int64_t(es) * D + tid], ve = es == last ? vl : Vc[int64_t(es) * D + tid];
-      const T kt = bs == last ? kl : Kc[int64_t(bs) * D + tid], vt = bs == last ? vl : Vc[int64_t(bs) * D + tid];
-      const double kk = __dadd_rn(__dmul_rn(e1, Elem<T>::to_f64(kt)), __dmul_rn(w, Elem<T>::to_f64(ke)));
-      const double vv = __dadd_rn(__dmul_rn(e1, Elem<T>::to_f64(vt)), __dmul_rn(w, Elem<T>::to_f64(ve)));
-      const T km = Elem<T>::from_f64(kk / z), vm = Elem<T>::from_f64(vv / z);
-      if (bs == last) {  // the merged row is the one that moves into the hole
-        kl = km;
-        vl = vm;
-      } else {
-        Kc[int64_t(bs) * D + tid] = km;
-        Vc[int64_t(bs) * D + tid] = vm;
-      }
-    }
-    if (es != last) {  // the last slot fills the hole
-      Kc[int64_t(es) * D + tid] = kl;
-      Vc[int64_t(es) * D + tid] = vl;
-    }
-  }
-  if (es != last && tid == 0) {
-    a.cscore[slot0 + es] = sl;
-    a.cpos[slot0 + es] = pl;
-  }
-}
-
-// Cosine of the evicted key against every other row of the head (Eq. 9) by the whole workgroup;
-// returns the arg-max per wavefront-reduced lane (the caller reduces over the wavefronts).
-// ke: D doubles of shared memory, red: 4 doubles.
-template <typename T, int D>
-__device__ __forceinline__ Best scan_matches(const DecodeArgs& a, int64_t slot0, int es, int total, double* ke,
-                                             double* red) {
-  constexpr int kVec = 16 / sizeof(T);
-  constexpr int TPR = D / kVec;
-  constexpr int RPP = 256 / TPR;
-  const int tid = threadIdx.x;
-  const T* Kc = static_cast<const T*>(a.cK) + slot0 * D;
-  double part = 0.0;
-  __syncthreads();
-  if (tid < D) {
-    const double x = Elem<T>::to_f64(Kc[int64_t(es) * D + tid]);
-    ke[tid] = x;
-    part = x * x;
-  }
-  const double sne = sqrt(block_sum(part, red));
-  const int tr = tid / TPR, tc = (tid % TPR) * kVec;
-  Best m{0.0, 0, -1};
-  for (int r0 = 0; r0 < total; r0 += RPP) {
-    const int j = r0 + tr;
-    double dot = 0.0, nr = 0.0;
-    if (j < total) {
-      double x[kVec];
-      cvt16<T>(*reinterpret_cast<const u32x4*>(Kc + int64_t(j) * D + tc), x);
-#pragma unroll
-      for (int e = 0; e < kVec; ++e) {
-        dot = fma(x[e], ke[tc + e], dot);
-        nr = fma(x[e], x[e], nr);
-      }
-    }
-#pragma unroll
-    for (int o = TPR / 2; o > 0; o >>= 1) {
-      dot += __shfl_xor(dot, o, 64);
-      nr += __shfl_xor(nr, o, 64);
-    }
-    if (j < total && j != es && (tid % TPR) == 0) {
-      const double den = sne * sqrt(nr);
-      const double u = den > 0.0 ? dot / den : 0.0;
-      const int p = a.cpos[slot0 + j];
-      if (better_match(u, p, j, m)) m = Best{u, p, j};
-    }
-  }
-  return m;
-}
-
 // Closing work of a head, by one workgroup of 256 threads: combine the sub-chunks, update the
 // scores, choose the evicted token and the next candidates, find the merge target and finish the
 // step.  Every load whose address does not depend on a result of this function is issued before
@@ -431,11 +150,11 @@ __device__ __forceinline__ void head_tail(const DecodeArgs& a, OT* __restrict__ 
   int cl[kCand];
 #pragma unroll
   for (int i = 0; i < kCand; ++i) cl[i] = a.cand[lbh * kCand + i];
-  // Results that are needed only at the end wait in LDS, not in registers (`park`: 16 bytes per
-  // candidate and thread, then two elements per thread).
-  double* park_u = reinterpret_cast<double*>(park);
-  int2* park_ps = reinterpret_cast<int2*>(park + kCand * 256 * sizeof(double));
-  T* park_kv = reinterpret_cast<T*>(park + kCand * 256 * (sizeof(double) + sizeof(int2)));
+  // Results that are needed only at the end wait in LDS, not in registers: per wavefront and
+  // candidate the best match found so far (`wcm`), and the last slot's row (two elements per thread).
+  double* wcm_u = sred + 8 + 8;                            // [4][kCand], behind sred and ired
+  int2* wcm_ps = reinterpret_cast<int2*>(wcm_u + 4 * kCand);  // [4][kCand] (position, slot)
+  T* park_kv = reinterpret_cast<T*>(wcm_ps + 4 * kCand);
   if (tid < D) {
     park_kv[tid] = Kc[int64_t(last) * D + tid];
     park_kv[256 + tid] = Vc[int64_t(last) * D + tid];
@@ -445,9 +164,8 @@ __device__ __forceinline__ void head_tail(const DecodeArgs& a, OT* __restrict__ 
   //      sub-chunk and query head is kept in LDS (`em`, behind the parked values) for the output
   //      and score passes; for a head with more sub-chunks than fit, the factors overwrite the
   //      maxima in the records and the score pass brings them into LDS segment by segment.
-  constexpr int kParkBytes = kCand * 256 * int(sizeof(double) + sizeof(int2)) + 2 * 256 * int(sizeof(T));
-  constexpr int kEmCap = (kStageBytes - 8192 - kParkBytes) / int(sizeof(double));
-  double* em = reinterpret_cast<double*>(park + kParkBytes);  // [nsub][G]
+  constexpr int kEmCap = (kStageBytes - 8192) / int(sizeof(double));
+  double* em = reinterpret_cast<double*>(park);  // [nsub][G]
   const bool em_lds = nsub * G <= kEmCap;
   double Mg[G], Lg[G];
   {
@@ -514,9 +232,12 @@ __device__ __forceinline__ void head_tail(const DecodeArgs& a, OT* __restrict__ 
     }
   }
 #pragma unroll
-  for (int i = 0; i < kCand; ++i) {
-    park_u[i * 256 + tid] = cm[i].u;
-    park_ps[i * 256 + tid] = make_int2(cm[i].pos, cm[i].slot);
+  for (int i = 0; i < kCand; ++i) {  // (a thread's entries come from different sub-chunks: all positions differ)
+    const Best r = fast_wave_best_match(cm[i].u, cm[i].pos, cm[i].slot);
+    if (lane == 0) {
+      wcm_u[w * kCand + i] = r.u;
+      wcm_ps[w * kCand + i] = make_int2(r.pos, r.slot);
+    }
   }
   // ---- score pass, set-up
   const bool evict = total > mt[1];
@@ -704,8 +425,10 @@ __device__ __forceinline__ void head_tail(const DecodeArgs& a, OT* __restrict__ 
     // outside the list): a second pass over the head's keys.
     m = scan_matches<T, D>(a, slot0, es, total, dred, sred);
   } else {
-    const int2 q = park_ps[ci * 256 + tid];  // written by this thread
-    m = Best{park_u[ci * 256 + tid], q.x, q.y};
+    if (tid < 4) {  // the four wavefronts' results (written before the barriers of the score pass)
+      const int2 q = wcm_ps[tid * kCand + ci];
+      m = Best{wcm_u[tid * kCand + ci], q.x, q.y};
+    }
   }
   m = fast_wave_best_match(m.u, m.pos, m.slot);
   lds_barrier();
@@ -783,16 +506,19 @@ __global__ __launch_bounds__(256) void decode_attend(DecodeArgs a, OT* __restric
   unsigned char* mine = stage + w * 64 * kPitch;
   int ln = lane;  // the lane number as the loop body sees it
   const double root_d = sqrt(double(D));
-  // K loads of a sub-chunk: per piece, 8 lanes cover 128 bytes of a row, 8 rows per load
-  u32x4 kreg[NP][8];
-  auto load_keys = [&](int sub, int rows) {
+  // K loads of a sub-chunk: a piece is 64 bytes of every row (4 lanes per row, 16 rows per load,
+  // 4 loads).  Pieces travel in pairs, the two halves of a 128-byte line requested together; the
+  // next pair is requested as soon as this one sits in LDS.
+  static_assert(NP % 2 == 0, "pieces are loaded in pairs");
+  u32x4 kreg[2][4];
+  auto load_pair = [&](int sub, int rows, int p0) {
     const unsigned char* Kc = Kh + int64_t(sub) * kSub * RB;
 #pragma unroll
-    for (int p = 0; p < NP; ++p)
+    for (int h = 0; h < 2; ++h)
 #pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        const int r = min(i * 8 + (ln >> 3), rows - 1);  // rows past the end repeat the last one
-        kreg[p][i] = *reinterpret_cast<const u32x4*>(Kc + int64_t(r) * RB + p * kPiece + (ln & 7) * 16);
+      for (int i = 0; i < 4; ++i) {
+        const int r = min(i * 16 + (ln >> 2), rows - 1);  // rows past the end repeat the last one
+        kreg[h][i] = *reinterpret_cast<const u32x4*>(Kc + int64_t(r) * RB + (p0 + h) * kPiece + (ln & 3) * 16);
       }
   };
   const int sub0 = grp * kGroup * (kChunk / kSub) + w;
@@ -808,7 +534,7 @@ __global__ __launch_bounds__(256) void decode_attend(DecodeArgs a, OT* __restric
     // registers than the occupancy allows; an opaque lane number keeps it inside.
     if (kGroup > 1) asm volatile("" : "+v"(ln));
     const int tr = ln / TPR, tc = ln % TPR;
-    load_keys(sub, rows);
+    load_pair(sub, rows, 0);
     const unsigned char* Vc = Vh + int64_t(sub) * kSub * RB;
     // ---- K pass: lane = row.  The queries and candidate keys arrive through scalar loads.
     double acc[NV];
@@ -834,7 +560,18 @@ __global__ __launch_bounds__(256) void decode_attend(DecodeArgs a, OT* __restric
 #pragma unroll
         for (int e = 0; e < ES; ++e) acc[v] = fma(x[e], sv[v][e], acc[v]);
     };
-    u32x4 vreg[NVL];
+    // V rows travel in quarters of the sub-chunk through two register sets: two quarters are on
+    // their way while the lanes finish the K pass, the others follow as the sets are consumed
+    // (a whole sub-chunk in registers would cost the kernel a quarter of its occupancy).
+    constexpr int VQ = NVL / 4;
+    u32x4 vbuf[2][VQ];
+    auto load_vq = [&](int q, int set) {
+#pragma unroll
+      for (int i = 0; i < VQ; ++i) {
+        const int r = min((q * VQ + i) * RPI + tr, rows - 1);  // repeated rows meet a zero probability
+        vbuf[set][i] = *reinterpret_cast<const u32x4*>(Vc + int64_t(r) * RB + tc * 16);
+      }
+    };
     // this lane's score-side loads ride along
     const bool valid = ln < rows;
     const int j = sub * kSub + ln;
@@ -846,16 +583,14 @@ __global__ __launch_bounds__(256) void decode_attend(DecodeArgs a, OT* __restric
       __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
       __builtin_amdgcn_wave_barrier();
 #pragma unroll
-      for (int i = 0; i < 8; ++i)
-        *reinterpret_cast<u32x4*>(mine + (i * 8 + (ln >> 3)) * kPitch + (ln & 7) * 16) = kreg[p][i];
+      for (int i = 0; i < 4; ++i)
+        *reinterpret_cast<u32x4*>(mine + (i * 16 + (ln >> 2)) * kPitch + (ln & 3) * 16) = kreg[p & 1][i];
       __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
       __builtin_amdgcn_wave_barrier();
-      if (p == NP - 1) {  // the key registers are free: this sub-chunk's V rows and the next one's K rows
-#pragma unroll
-        for (int i = 0; i < NVL; ++i) {
-          const int r = min(i * RPI + tr, rows - 1);  // repeated rows meet a zero probability
-          vreg[i] = *reinterpret_cast<const u32x4*>(Vc + int64_t(r) * RB + tc * 16);
-        }
+      if ((p & 1) && p + 1 < NP) load_pair(sub, rows, p + 1);
+      if (p == NP - 1) {  // the first half of this sub-chunk's V rows
+        load_vq(0, 0);
+        load_vq(1, 1);
       }
       // ES elements per step.  The row's bits and the scalar operands of a step are fetched one
       // step ahead (two register sets), so their latency hides behind the previous step's FMAs.
@@ -912,16 +647,20 @@ __global__ __launch_bounds__(256) void decode_attend(DecodeArgs a, OT* __restric
 #pragma unroll
       for (int e = 0; e < kVec; ++e) pv[g][e] = 0.f;
 #pragma unroll
-    for (int i = 0; i < NVL; ++i) {
-      const int r = i * RPI + tr;
-      float x[kVec];
-      cvt16f<T>(vreg[i], x);
+    for (int q = 0; q < 4; ++q) {
 #pragma unroll
-      for (int g = 0; g < G; ++g) {
-        const float p = ps[w][g][r];  // 0 for rows beyond the end
+      for (int i = 0; i < VQ; ++i) {
+        const int r = (q * VQ + i) * RPI + tr;
+        float x[kVec];
+        cvt16f<T>(vbuf[q & 1][i], x);
 #pragma unroll
-        for (int e = 0; e < kVec; ++e) pv[g][e] = fmaf(p, x[e], pv[g][e]);
+        for (int g = 0; g < G; ++g) {
+          const float p = ps[w][g][r];  // 0 for rows beyond the end
+#pragma unroll
+          for (int e = 0; e < kVec; ++e) pv[g][e] = fmaf(p, x[e], pv[g][e]);
+        }
       }
+      if (q + 2 < 4) load_vq(q + 2, q & 1);
     }
     // sum over the row groups; the wavefront's partial rows (one per query head) go to its
     // staging area, which is free again, for the combination over the workgroup
@@ -997,37 +736,41 @@ __global__ __launch_bounds__(256) void decode_attend(DecodeArgs a, OT* __restric
                          stage + 8192);
 }
 
-template <typename T, typename OT, int D, int G>
-hipError_t run_decode_o(d2o_ctx* c, const DecodeArgs& a, int nl, int flat_chunks, View q, View k, View v, View out,
-                        hipStream_t s) {
+template <typename T, int D>
+hipError_t run_prepare_g(d2o_ctx* c, const DecodeArgs& a, int nl, View q, View k, View v, hipStream_t s) {
   const int bh = a.B * a.Hkv;
-  {
-    KernelTimer kt(c, D2O_K_DECODE_PREPARE, s);
-    decode_prepare<T, OT, D, G><<<dim3(bh, nl), 128, 0, s>>>(a, (const T*)q.ptr, q, (const T*)k.ptr, k,
-                                                            (const T*)v.ptr, v);
-  }
-  {
-    KernelTimer kt(c, D2O_K_DECODE_ATTEND, s);
-    decode_attend<T, OT, D, G><<<dim3(bh, flat_chunks), 256, 0, s>>>(a, (OT*)out.ptr, out);
+  KernelTimer kt(c, D2O_K_DECODE_PREPARE, s);
+  const dim3 grid(bh, nl);
+  switch (a.G) {  // the output type plays no role in this kernel
+    case 1: decode_prepare<T, T, D, 1><<<grid, 128, 0, s>>>(a, (const T*)q.ptr, q, (const T*)k.ptr, k, (const T*)v.ptr, v); break;
+    case 2: decode_prepare<T, T, D, 2><<<grid, 128, 0, s>>>(a, (const T*)q.ptr, q, (const T*)k.ptr, k, (const T*)v.ptr, v); break;
+    case 4: decode_prepare<T, T, D, 4><<<grid, 128, 0, s>>>(a, (const T*)q.ptr, q, (const T*)k.ptr, k, (const T*)v.ptr, v); break;
+    case 8: decode_prepare<T, T, D, 8><<<grid, 128, 0, s>>>(a, (const T*)q.ptr, q, (const T*)k.ptr, k, (const T*)v.ptr, v); break;
+    default: return hipErrorInvalidValue;
   }
   return hipGetLastError();
 }
 
+template <typename T, typename OT, int D, int G>
+hipError_t run_attend(d2o_ctx* c, const DecodeArgs& a, int flat_chunks, View out, hipStream_t s) {
+  KernelTimer kt(c, D2O_K_DECODE_ATTEND, s);
+  decode_attend<T, OT, D, G><<<dim3(a.B * a.Hkv, flat_chunks), 256, 0, s>>>(a, (OT*)out.ptr, out);
+  return hipGetLastError();
+}
+
 template <typename T, int D, int G>
-hipError_t run_decode(d2o_ctx* c, const DecodeArgs& a, int nl, int fc, View q, View k, View v, View out,
-                      hipStream_t s) {
-  if (a.out_f32) return run_decode_o<T, float, D, G>(c, a, nl, fc, q, k, v, out, s);
-  return run_decode_o<T, T, D, G>(c, a, nl, fc, q, k, v, out, s);
+hipError_t run_decode(d2o_ctx* c, const DecodeArgs& a, int fc, View out, hipStream_t s) {
+  if (a.out_f32) return run_attend<T, float, D, G>(c, a, fc, out, s);
+  return run_attend<T, T, D, G>(c, a, fc, out, s);
 }
 
 template <typename T, int D>
-hipError_t run_decode_g(d2o_ctx* c, const DecodeArgs& a, int nl, int fc, View q, View k, View v, View out,
-                        hipStream_t s) {
+hipError_t run_decode_g(d2o_ctx* c, const DecodeArgs& a, int fc, View out, hipStream_t s) {
   switch (a.G) {
-    case 1: return run_decode<T, D, 1>(c, a, nl, fc, q, k, v, out, s);
-    case 2: return run_decode<T, D, 2>(c, a, nl, fc, q, k, v, out, s);
-    case 4: return run_decode<T, D, 4>(c, a, nl, fc, q, k, v, out, s);
-    case 8: return run_decode<T, D, 8>(c, a, nl, fc, q, k, v, out, s);
+    case 1: return run_decode<T, D, 1>(c, a, fc, out, s);
+    case 2: return run_decode<T, D, 2>(c, a, fc, out, s);
+    case 4: return run_decode<T, D, 4>(c, a, fc, out, s);
+    case 8: return run_decode<T, D, 8>(c, a, fc, out, s);
     default: return hipErrorInvalidValue;
   }
 }
@@ -1169,20 +912,14 @@ hipError_t launch_decode(d2o_ctx* c, int layer0, int nl_all, View q, View k, Vie
     const int nl = std::min(kMaxLayersPerCall, nl_all - g0);
     a.layer0 = layer0 + g0;
     a.nl = nl;
-    int mc[kMaxLayersPerCall];
+    int mc[kMaxLayersPerCall], chunk_id[kMaxLayersPerCall];
+    const int nc = nl;
     for (int i = 0; i < nl; ++i) {
-      a.lay_id[i] = i;
+      chunk_id[i] = i;
       mc[i] = 1;
       for (const auto& mt : c->layers[a.layer0 + i].meta)
         mc[i] = std::max(mc[i], (mt.budget + 1 + kGroup * kChunk - 1) / (kGroup * kChunk));
     }
-    std::stable_sort(a.lay_id, a.lay_id + nl, [&](int x, int y) { return mc[x] > mc[y]; });
-    int flat = 0;
-    for (int i = 0; i < nl; ++i) {
-      a.lay_off[i] = flat;
-      flat += mc[a.lay_id[i]];
-    }
-    for (int i = nl; i <= kMaxLayersPerCall; ++i) a.lay_off[i] = i == nl ? flat : 0x7FFFFFFF;
     auto shift = [&](View x, int elem_bytes) {  // first layer of this group
       x.ptr = static_cast<char*>(x.ptr) + size_t(g0) * x.sn * elem_bytes;
       return x;
@@ -1190,13 +927,32 @@ hipError_t launch_decode(d2o_ctx* c, int layer0, int nl_all, View q, View k, Vie
     const int es = c->esize, os = cf.out_f32 ? 4 : c->esize;
     const View qg = shift(q, es), kg = shift(k, es), vg = shift(v, es), og = shift(out, os);
     hipError_t e;
+    // ---- append + operand set-up for every layer of the group
     if (cf.dtype == D2O_BF16)
-      e = run_decode_g<uint16_t, 128>(c, a, nl, flat, qg, kg, vg, og, s);
+      e = run_prepare_g<uint16_t, 128>(c, a, nl, qg, kg, vg, s);
     else if (cf.head_dim == 64)
-      e = run_decode_g<float, 64>(c, a, nl, flat, qg, kg, vg, og, s);
+      e = run_prepare_g<float, 64>(c, a, nl, qg, kg, vg, s);
     else
-      e = run_decode_g<float, 128>(c, a, nl, flat, qg, kg, vg, og, s);
+      e = run_prepare_g<float, 128>(c, a, nl, qg, kg, vg, s);
     if (e != hipSuccess) return e;
+    // ---- attention over the caches, one workgroup per 256 slots; the layers with most chunks first
+    {
+      std::stable_sort(chunk_id, chunk_id + nc, [&](int x, int y) { return mc[x] > mc[y]; });
+      int flat = 0;
+      for (int i = 0; i < nc; ++i) {
+        a.lay_id[i] = chunk_id[i];
+        a.lay_off[i] = flat;
+        flat += mc[chunk_id[i]];
+      }
+      for (int i = nc; i <= kMaxLayersPerCall; ++i) a.lay_off[i] = i == nc ? flat : 0x7FFFFFFF;
+      if (cf.dtype == D2O_BF16)
+        e = run_decode_g<uint16_t, 128>(c, a, flat, og, s);
+      else if (cf.head_dim == 64)
+        e = run_decode_g<float, 64>(c, a, flat, og, s);
+      else
+        e = run_decode_g<float, 128>(c, a, flat, og, s);
+      if (e != hipSuccess) return e;
+    }
   }
   return hipSuccess;
 }

@@ -315,7 +315,8 @@ def _run_decode_parity(w, n, B, layer, budget, recent, sink, steps, tau_force=fl
 
 
 @pytest.mark.parametrize("case", ["cfg1", "bf16-mha", "bf16-gqa-ragged-budgets", "bf16-grow",
-                                  "bf16-no-window", "bf16-never-merge", "bf16-long"])
+                                  "bf16-no-window", "bf16-never-merge", "bf16-long", "bf16-gqa4",
+                                  "bf16-mha-many-rounds"])
 def test_decode_from_oracle_state(case):
     print(f"case={case}", flush=True)
     if case == "cfg1":
@@ -330,6 +331,12 @@ def test_decode_from_oracle_state(case):
         _run_decode_parity(_small_bf16(False), 300, 1, 31, 40, 0, 0, 12)
     elif case == "bf16-long":      # many steps: the eviction candidates are carried from step to step
         _run_decode_parity(_small_bf16(True), 400, 2, 17, [90, 130], [20, 30], 1, 96)
+    elif case == "bf16-gqa4":      # four query heads per KV head, as configurations 4 and 5
+        _run_decode_parity(W4.scaled(n_q_heads=8, n_kv_heads=2, n_clusters=16), 1500, 2, 6, [700, 410],
+                           [175, 100], 0, 10, random_scores=True)
+    elif case == "bf16-mha-many-rounds":   # 4000 rows: sixteen workgroups per head
+        _run_decode_parity(_small_bf16(False).scaled(n_q_heads=2, n_kv_heads=2), 6000, 1, 25, 4000, 1000, 0, 5,
+                           random_scores=True)
     else:
         _run_decode_parity(_small_bf16(False), 500, 1, 12, 100, 25, 0, 10, tau_force=float("inf"))
 
@@ -495,14 +502,11 @@ def test_decode_all_layers_in_one_call_equals_one_call_per_layer():
         ctx.close()
 
 
-def test_decode_growing_cache_crosses_chunk_boundaries_in_a_multi_layer_call():
-    """Two layers in one call: layer 0's budget is above its prompt, so its caches grow by one
-    token per step through 256 and 512 entries (the sizes at which a new workgroup joins a
-    head) and then start evicting; layer 1 evicts from the first step.  Every step's events
-    and outputs against the oracle, final caches identical."""
-    w, n, B, steps = _small_bf16(True), 250, 1, 275
-    layers, budgets, recents = [4, 11], [520, 100], [130, 25]
-    ctx = H.new_ctx(w, B, 2, n, sum(budgets) + 16)
+def _run_multi_layer_decode(w, n, layers, budgets, recents, steps):
+    """Several layers in one decode call per step, every head against the oracle at every step.
+    Returns the number of evictions per layer."""
+    B, L = 1, len(layers)
+    ctx = H.new_ctx(w, B, L, n, sum(budgets) + 8 * L)
     caches = {}
     for li, layer in enumerate(layers):
         Q, K, V = H.make_inputs(w, B, layer, n)
@@ -515,12 +519,12 @@ def test_decode_growing_cache_crosses_chunk_boundaries_in_a_multi_layer_call():
     q, k, v = H.decode_inputs(w, B, layers, steps)
     qd, kd, vd = (binding.tensor_to_f64(t) for t in (q, k, v))
     out = torch.empty(q[0].shape, dtype=ctx.out_dtype, device=q.device)
-    G, worst, evictions = w.group, 0.0, [0, 0]
+    G, worst, evictions = w.group, 0.0, [0] * L
     for t in range(steps):
-        ctx.d2o_decode_step(0, 2, q[t], k[t], v[t], out)
+        ctx.d2o_decode_step(0, L, q[t], k[t], v[t], out)
         torch.cuda.synchronize()
         od = binding.tensor_to_f64(out)
-        for li in range(2):
+        for li in range(L):
             ev, tg, us = ctx.d2o_last_events(li)
             for h in range(w.n_kv_heads):
                 want, e = ref.decode_step_head(caches[(li, h)], qd[t, li, 0, h * G:(h + 1) * G], kd[t, li, 0, h],
@@ -529,13 +533,32 @@ def test_decode_growing_cache_crosses_chunk_boundaries_in_a_multi_layer_call():
                 evictions[li] += e.evicted_pos >= 0
                 worst = max(worst, H.rownorm_err(od[li, 0, h * G:(h + 1) * G], want))
     assert worst <= H.FLOAT_TOL
-    assert evictions[0] == (steps - (budgets[0] - n)) * w.n_kv_heads and evictions[1] == steps * w.n_kv_heads
     for (li, h), cache in caches.items():
         gK, gV, gs, gp, gtau = ctx.d2o_cache_export(li, 0, h, budgets[li] + 1)
         assert np.array_equal(gp, cache.pos) and np.array_equal(gK, cache.K) and np.array_equal(gV, cache.V)
         np.testing.assert_allclose(gs, cache.score, rtol=1e-12)
     print(f"  {steps} steps, worst out err {worst:.2e}, evictions per layer {evictions}", flush=True)
     ctx.close()
+    return evictions
+
+
+def test_decode_growing_cache_crosses_chunk_boundaries_in_a_multi_layer_call():
+    """Two layers in one call: layer 0's budget is above its prompt, so its caches grow by one
+    token per step through 256 and 512 entries (the sizes at which a new workgroup joins a
+    head) and then start evicting; layer 1 evicts from the first
+    step.  Every step's events and outputs against the oracle, final caches identical."""
+    w, n, steps = _small_bf16(True), 250, 275
+    budgets = [520, 100]
+    ev = _run_multi_layer_decode(w, n, [4, 11], budgets, [130, 25], steps)
+    assert ev[0] == (steps - (budgets[0] - n)) * w.n_kv_heads and ev[1] == steps * w.n_kv_heads
+
+
+def test_decode_layers_of_very_different_sizes_in_one_call():
+    """Three layers in one call whose caches hold 10500, 200 and 3000 rows (42, 1 and 12 workgroups
+    per head): each head against the oracle at every step."""
+    w = _small_bf16(False).scaled(n_q_heads=2, n_kv_heads=2)
+    ev = _run_multi_layer_decode(w, 12000, [2, 30, 17], [10500, 200, 3000], [2600, 50, 750], 5)
+    assert ev == [10, 10, 10]
 
 
 def test_density_to_budgets_to_compress_free_running():
