@@ -115,6 +115,20 @@ __global__ __launch_bounds__(256) void transpose_v(const uint16_t* __restrict__ 
 // B-operand slice the P V product needs, with no cross-lane movement.
 __device__ __forceinline__ int perm_key(int m) { return (m & ~0xC) | ((m & 4) << 1) | ((m & 8) >> 1); }
 
+// Workgroups are handed to the chip's eight XCDs (each with its own L2) round-robin in launch
+// order.  With the head as the slow grid index a head's workgroups land on all eight, and every
+// L2 fetches every head's K / V tiles from memory.  This remaps (block, head) so that all
+// workgroups of a head run on one XCD, heads that share a KV head on the same one, and an XCD
+// works through its heads one after the other: the workgroups of a head, which walk the same
+// tiles at about the same time, then share them in one L2.  hz = head + heads * sequence.
+__device__ __forceinline__ void xcd_remap(int nx, int nhz, int& bx, int& hz) {
+  constexpr int kXcd = 8;
+  if (nhz % kXcd) return;  // identity when the heads do not divide over the XCDs
+  const int lin = bx + nx * hz, xcd = lin % kXcd, s = lin / kXcd;
+  hz = xcd * (nhz / kXcd) + s / nx;
+  bx = s % nx;
+}
+
 constexpr int kKsElems = 64 * kLdK;   // one K tile in LDS
 constexpr int kVsElems = kD * kLdV;   // one V^T tile in LDS
 constexpr int kAttnSmemBytes = 2 * (kKsElems + kVsElems) * 2;
@@ -137,7 +151,10 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, 2)))
   extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
   uint16_t* Ks = smem;                 // [2][kKsElems]
   uint16_t* Vs = smem + 2 * kKsElems;  // [2][kVsElems]
-  const int hq = blockIdx.y, b = blockIdx.z, Hq = gridDim.y, hk = hq / G, Hkv = Hq / G;
+  const int Hq = gridDim.y, Hkv = Hq / G;
+  int bx = blockIdx.x, hz = blockIdx.y + Hq * blockIdx.z;
+  xcd_remap(gridDim.x, Hq * gridDim.z, bx, hz);
+  const int hq = hz % Hq, b = hz / Hq, hk = hq / G;
   const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, m = lane & 31, h = lane >> 5;
   constexpr int kWR = 32 * RW;   // rows per wavefront
   constexpr int NT = 64 * NW;    // threads
@@ -149,8 +166,8 @@ __global__ __launch_bounds__(64 * NW) __attribute__((amdgpu_waves_per_eu(2, 2)))
   // amount of work and the launch fills the chip in whole rounds (with one row block per
   // workgroup the longest ones ran on a nearly empty chip at the end: 80 % packing).
   for (int pass = 0; pass < 2; ++pass) {
-  const int blk = pass == 0 ? nblk - 1 - int(blockIdx.x) : int(blockIdx.x);
-  if (pass == 1 && blk >= nblk - 1 - int(blockIdx.x)) break;
+  const int blk = pass == 0 ? nblk - 1 - bx : bx;
+  if (pass == 1 && blk >= nblk - 1 - bx) break;
   const int rb = blk * BM;
   const int wr0 = rb + w * kWR;  // first row of this wavefront
 
@@ -446,7 +463,10 @@ __global__ __launch_bounds__(64 * kColNW) __attribute__((amdgpu_waves_per_eu(4, 
   __shared__ double red[kColNW];
   constexpr int NT = 64 * kColNW;
   constexpr int NCH = 1024 / NT;
-  const int hk = blockIdx.y, b = blockIdx.z, Hkv = gridDim.y;
+  const int Hkv = gridDim.y;
+  int bx = blockIdx.x, hz = blockIdx.y + Hkv * blockIdx.z;
+  xcd_remap(gridDim.x, Hkv * gridDim.z, bx, hz);
+  const int hk = hz % Hkv, b = hz / Hkv;
   const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, m = lane & 31, h = lane >> 5;
   const float scale2 = kLog2e / sqrtf(float(kD));
   // The work of a key block grows with the number of queries behind it (causal), from one
@@ -455,8 +475,8 @@ __global__ __launch_bounds__(64 * kColNW) __attribute__((amdgpu_waves_per_eu(4, 
   // fills the chip in whole rounds (with one block per workgroup the CUs held 1.3 of 2 possible
   // workgroups on average, and the longest workgroup alone was a fifth of the kernel time).
   for (int pass = 0; pass < 2; ++pass) {
-  const int tile = pass == 0 ? int(blockIdx.x) : nblk - 1 - int(blockIdx.x);
-  if (pass == 1 && tile <= int(blockIdx.x)) break;
+  const int tile = pass == 0 ? bx : nblk - 1 - bx;
+  if (pass == 1 && tile <= bx) break;
   const int kb0 = tile * kColBN, kw0 = kb0 + w * 32;  // first key of the workgroup / wavefront
 
   const uint16_t* kp = K + b * kv.sb + hk * kv.sh + int64_t(min(kw0 + m, n - 1)) * kv.sn;
