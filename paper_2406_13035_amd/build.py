@@ -9,6 +9,11 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 SOURCES = ["d2o_host.hip", "prefill_f32.hip", "prefill_bf16.hip", "tokens.hip", "decode.hip"]
 LIB = os.environ.get("D2O_LIB", os.path.join(HERE, "libd2o.so"))
+# Matrix-core results straight into vector registers: the kernels of these files post-process
+# every accumulator element on the vector ALU, and a copy out of the accumulation registers per
+# element is a sizeable part of their instruction count.
+VGPR_FORM = ["-mllvm", "-amdgpu-mfma-vgpr-form"]
+EXTRA_FLAGS = {"tokens.hip": VGPR_FORM}
 
 
 def build(verbose: bool = False) -> str:
@@ -24,7 +29,7 @@ def build(verbose: bool = False) -> str:
 
     def compile_one(src):
         obj = os.path.join(objdir, src.replace(".hip", ".o"))
-        res = subprocess.run([hipcc, "-c"] + flags + ["-o", obj, os.path.join(HERE, "csrc", src)],
+        res = subprocess.run([hipcc, "-c"] + flags + EXTRA_FLAGS.get(src, []) + ["-o", obj, os.path.join(HERE, "csrc", src)],
                              capture_output=True, text=True)
         return src, obj, res
 

@@ -206,9 +206,10 @@ __global__ __launch_bounds__(256) void invnorm_bf16(const uint16_t* __restrict__
 //     repeats the first one's arithmetic exactly, so the best value is found again.  Few rows are
 //     flagged (a workgroup or two per head), so the retained keys are split over `ksplit`
 //     workgroups per row block: the lists are appended with atomics and read order-free.
-// kAmbiguous bounds twice the fp32 error of one cosine: at most one rounding per accumulated
-// product (128 * 2^-24 of |k_i||k_j|) plus the two fp32 inverse norms, 1.6e-5 in total.
-constexpr float kAmbiguous = 2.0e-5f;
+// kAmbiguous bounds twice the error of one filtered cosine: at most one rounding per accumulated
+// product (128 * 2^-24 of |k_i||k_j|) plus the two fp32 inverse norms, 1.6e-5 in total, plus the
+// four mantissa bits that carry the register number (2 * 16 * 2^-24 = 1.9e-6).
+constexpr float kAmbiguous = 2.4e-5f;
 constexpr int kMaxCand = 8;
 constexpr int kLdM = 128 + 8;
 
@@ -227,8 +228,9 @@ __global__ __launch_bounds__(256) void match_filter_bf16(const uint16_t* __restr
   constexpr int kTile = 64;     // retained keys per LDS tile
   constexpr int NCH = kTile * 16 / 256;  // 16-byte chunks of a tile per thread
   __shared__ __attribute__((aligned(16))) uint16_t Rs[2][kTile * kLdM];
-  __shared__ float rin[2][kTile];    // 1/|k| of the staged retained keys
-  __shared__ float rbias[2][kTile];  // 0, or -inf for padding rows
+  __shared__ __attribute__((aligned(16))) float rin[2][kTile];    // 1/|k| of the staged retained keys
+  __shared__ __attribute__((aligned(16))) float rbias[2][kTile];  // 0, or -3e38 for padding rows (finite: the low
+                                                                  // mantissa bits of a value get overwritten below)
   const int hk = blockIdx.y, b = blockIdx.z, Hkv = gridDim.y;
   const int64_t bh = int64_t(b) * Hkv + hk;
   const int nret = cnt[bh * 2], nevi = cnt[bh * 2 + 1];
@@ -252,16 +254,17 @@ __global__ __launch_bounds__(256) void match_filter_bf16(const uint16_t* __restr
   for (int ks = 0; ks < 8; ++ks)
     be[ks] = *reinterpret_cast<const bf16x8*>(kb + int64_t(epos) * kv.sn + ks * 16 + h * 8);
   float m1 = -INFINITY, m2 = -INFINITY;
-  int i1 = 0;
+  int isub = 0;  // first retained rank of the sub-tile the running best came from
   const float mythr = COLLECT ? thr[bh * npad + erank] : 0.f;
-  // Tiles travel global -> registers -> LDS; two register sets keep two tiles in flight.
-  u32x4 rgA[NCH], rgB[NCH];
-  float rvA = 0.f, rvB = 0.f;
+  // Tiles travel global -> registers -> LDS: the next tile is requested when work on a tile
+  // starts and written to the other LDS buffer when it ends.
+  u32x4 rg[NCH];
+  float rv = 0.f;
   const int ntile = (nret + kTile - 1) / kTile;
   const int tper = (ntile + ksplit - 1) / ksplit;
   const int tbeg = part * tper, tend = min(ntile, tbeg + tper);  // this workgroup's tiles
   if (tbeg >= tend) return;
-  auto issue = [&](int t, u32x4 (&rg)[NCH], float& rv) {
+  auto issue = [&](int t) {
     const int r0 = t * kTile;
 #pragma unroll
     for (int i = 0; i < NCH; ++i) {
@@ -270,7 +273,7 @@ __global__ __launch_bounds__(256) void match_filter_bf16(const uint16_t* __restr
     }
     if (tid < kTile) rv = (r0 + tid < nret) ? inl[rl[r0 + tid]] : -1.f;  // -1 marks a padding row
   };
-  auto stage = [&](int buf, const u32x4 (&rg)[NCH], float rv) {
+  auto stage = [&](int buf) {
 #pragma unroll
     for (int i = 0; i < NCH; ++i) {
       const int c = tid + 256 * i, rrow = c >> 4, col = (c & 15) * 8;
@@ -278,53 +281,84 @@ __global__ __launch_bounds__(256) void match_filter_bf16(const uint16_t* __restr
     }
     if (tid < kTile) {
       rin[buf][tid] = rv < 0.f ? 0.f : rv;
-      rbias[buf][tid] = rv < 0.f ? -INFINITY : 0.f;
+      rbias[buf][tid] = rv < 0.f ? -3.0e38f : 0.f;
     }
   };
-  auto one_tile = [&](int t, u32x4 (&far)[NCH], float& vfar, const u32x4 (&next)[NCH], const float& vnext) {
+  auto one_tile = [&](int t) {
     const int buf = t & 1, r0 = t * kTile;
-    if (t + 2 < tend) issue(t + 2, far, vfar);
+    if (t + 1 < tend) issue(t + 1);
     const int nsub = min(kTile / 32, (nret - r0 + 31) / 32);
-    for (int st = 0; st < nsub; ++st) {
+    const bool padded = r0 + kTile > nret;  // only the last tile can hold rows past the end
+    auto mma = [&](int st) -> f32x16 {
       bf16x8 a[8];
 #pragma unroll
       for (int ks = 0; ks < 8; ++ks)
         a[ks] = *reinterpret_cast<const bf16x8*>(&Rs[buf][(st * 32 + m) * kLdM + ks * 16 + h * 8]);
-      f32x16 s;
+      const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+      f32x16 s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[0], be[0], zero, 0, 0, 0);
 #pragma unroll
-      for (int r = 0; r < 16; ++r) s[r] = 0.f;
+      for (int ks = 1; ks < 8; ++ks) s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks], be[ks], s, 0, 0, 0);
+      return s;
+    };
+    auto post = [&](const f32x16& s, int st) {
+      // register r: retained row st*32 + (r/4)*8 + 4h + r%4 of this tile, evicted row = lane's;
+      // the four rows of a register group are neighbours, so their 1/|k| come in one LDS read
+      float tv[16];
 #pragma unroll
-      for (int ks = 0; ks < 8; ++ks) s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks], be[ks], s, 0, 0, 0);
-      // register r: retained row st*32 + (r/4)*8 + 4h + r%4 of this tile, evicted row = lane's
+      for (int g4 = 0; g4 < 4; ++g4) {
+        const int rb = st * 32 + g4 * 8 + h * 4;
+        const f32x4 ri = *reinterpret_cast<const f32x4*>(&rin[buf][rb]);
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int rr = st * 32 + (r >> 2) * 8 + h * 4 + (r & 3);
-        const float tval = fmaf(s[r], rin[buf][rr], rbias[buf][rr]);
-        if (COLLECT) {
-          if (live && tval >= mythr) {
+        for (int i = 0; i < 4; ++i) tv[g4 * 4 + i] = s[g4 * 4 + i] * ri[i];
+        if (padded) {  // block-uniform
+          const f32x4 bi = *reinterpret_cast<const f32x4*>(&rbias[buf][rb]);
+#pragma unroll
+          for (int i = 0; i < 4; ++i) tv[g4 * 4 + i] += bi[i];
+        }
+      }
+      if (COLLECT) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int rr = st * 32 + (r >> 2) * 8 + h * 4 + (r & 3);
+          if (live && tv[r] >= mythr) {
             const int k = atomicAdd(&ncand[bh * npad + erank], 1);
             if (k < kMaxCand) clist[(bh * npad + erank) * kMaxCand + k] = r0 + rr;
           }
-        } else {
-          const bool gt = tval > m1;
-          i1 = gt ? (r0 + rr) : i1;
-          m2 = __builtin_amdgcn_fmed3f(m1, m2, tval);
-          m1 = fmaxf(m1, tval);
         }
+      } else {
+        // Running best and second best of the lane's row, two operations per value: the low four
+        // mantissa bits of a value are replaced by its register number (a change of at most 16
+        // units in the last place, which kAmbiguous covers), so that the maximum carries the
+        // position inside the sub-tile with it; which sub-tile it came from is noted once per
+        // sub-tile.  Values that are equal up to those bits end up flagged as ambiguous and are
+        // decided by the exact refinement.
+        const float before = m1;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const float key = __uint_as_float((__float_as_uint(tv[r]) & ~15u) | uint32_t(r));
+          m2 = __builtin_amdgcn_fmed3f(m1, m2, key);
+          // (the maximum as the instruction itself: fmaxf would first re-canonicalise a value
+          // that was put together from bits)
+          asm("v_max_f32 %0, %1, %2" : "=v"(m1) : "v"(m1), "v"(key));
+        }
+        isub = (m1 != before) ? (r0 + st * 32) : isub;
       }
-    }
-    if (t + 1 < tend) stage(buf ^ 1, next, vnext);
+    };
+    // (two sub-tiles as two independent accumulation chains need 160 registers and cost a
+    // wavefront per SIMD: slower)
+    for (int st = 0; st < nsub; ++st) post(mma(st), st);
+    if (t + 1 < tend) stage(buf ^ 1);
     __syncthreads();
   };
-  issue(tbeg, rgA, rvA);
-  stage(tbeg & 1, rgA, rvA);
-  if (tbeg + 1 < tend) issue(tbeg + 1, rgB, rvB);
+  issue(tbeg);
+  stage(tbeg & 1);
   __syncthreads();
-  for (int t = tbeg; t < tend; t += 2) {
-    one_tile(t, rgA, rvA, rgB, rvB);
-    if (t + 1 < tend) one_tile(t + 1, rgB, rvB, rgA, rvA);
-  }
+#pragma unroll 1
+  for (int t = tbeg; t < tend; ++t) one_tile(t);
   if (COLLECT) return;
+  // the best's retained rank: its sub-tile, and the register number carried in its low bits
+  const int rbest = int(__float_as_uint(m1) & 15u);
+  const int i1 = isub + (rbest >> 2) * 8 + h * 4 + (rbest & 3);
   // combine the two lane halves that share an evicted row
   const float om1 = __shfl_xor(m1, 32, 64), om2 = __shfl_xor(m2, 32, 64);
   const int oi1 = __shfl_xor(i1, 32, 64);
