@@ -426,6 +426,80 @@ def decode_step_head(cache: HeadCache, q, k_new, v_new, new_pos: int, budget: in
     return out, DecodeEvent(evicted_pos, target_pos, u, cache.tau)
 
 
+# --------------------------------------------------------------------------- multi-token append
+
+@dataclasses.dataclass
+class AppendEvents:
+    evicted: np.ndarray      # positions, ascending (empty when the cache stayed within its budget)
+    target: np.ndarray       # [Le] position of the matched retained token
+    u_star: np.ndarray       # [Le]
+    passed: np.ndarray       # [Le] bool
+    tau: float
+
+
+def append_chunk_head(cache: HeadCache, q, k_new, v_new, first_pos: int, budget: int, recent: int,
+                      n_sink: int, beta: float, tau_force: float = float("nan"), weighted: bool = True):
+    """A block of m new tokens on one KV head: the chunked / multi-turn form of a generation
+    step (Sec. 3 Eq. 2-3 and Sec. 4.2 Eq. 6-12 applied to m tokens at once; the multi-turn
+    experiment of the appendix feeds whole turns into a cache of fixed budget).
+
+    q [G, m, d], k_new, v_new [m, d]; the tokens get positions first_pos .. first_pos + m - 1.
+      1. Attention and scores, token by token in causal order: token i is appended (score 0),
+         attends to everything cached so far including itself, p = softmax(q K^T / sqrt(d)),
+         out = p V, and every visible entry's score grows by p, for each of the G query heads in
+         turn (Eq. 6, generation case, with no eviction between the tokens of the block; the
+         totals equal the column sums of the block's attention matrix, Eq. 6 prompt case).
+      2. If the cache now holds more than `budget` entries, Eq. 7-8 applied once to all of them
+         (ordered by position) keeps T sinks, the top scores of the middle and the last M, so
+         count - budget tokens are evicted together.
+      3. Each evicted token is matched to its nearest retained key on the pre-merge keys (Eq. 9).
+      4. Threshold (Eq. 10).  The paper gives the t = 0 form for many evicted tokens (their mean
+         best similarity) and the t > 0 form for one; for a step that evicts several, the reading
+         taken joins the two: the step's similarity is the mean of the evicted tokens' best
+         similarities, tau <- beta * mean + (1 - beta) * tau (tau <- mean while unset).  With one
+         evicted token this is the generation step, with an unset tau the prompt-phase formula.
+         A token is merged iff its best similarity is not lower than the updated threshold.
+      5. Merge (Eq. 11-12, many sources per retained token), rounded to the cache's storage.
+    Mutates `cache`; returns (out [G, m, d], AppendEvents)."""
+    q = np.asarray(q, dtype=np.float64)
+    k_new = np.asarray(k_new, dtype=np.float64)
+    v_new = np.asarray(v_new, dtype=np.float64)
+    G, m, d = q.shape
+    root_d = np.sqrt(float(d))
+    out = np.empty_like(q)
+    for i in range(m):
+        cache.K = np.vstack([cache.K.reshape(-1, d), k_new[i][None, :]])
+        cache.V = np.vstack([cache.V.reshape(-1, d), v_new[i][None, :]])
+        cache.score = np.append(cache.score, 0.0)
+        cache.pos = np.append(cache.pos, first_pos + i).astype(np.int64)
+        for g in range(G):
+            s = (cache.K @ q[g, i]) / root_d
+            s = s - s.max()
+            p = np.exp(s)
+            p = p / p.sum()
+            out[g, i] = p @ cache.V
+            cache.score = cache.score + p
+    count = cache.pos.size
+    none = np.zeros(0, dtype=np.int64)
+    if count <= budget:
+        return out, AppendEvents(none, none, np.zeros(0), np.zeros(0, dtype=bool), cache.tau)
+    assert np.all(np.diff(cache.pos) > 0)
+    ret, evi = select(cache.score, budget, recent, n_sink)
+    u_star, t = match(cache.K[evi], cache.K[ret])
+    if math.isnan(tau_force):
+        cache.tau = ema_threshold(cache.tau, float(u_star.sum() / u_star.size), beta)
+        passed = u_star >= cache.tau
+    else:
+        passed = u_star >= tau_force
+    Kc, Vc, _ = merge(cache.K[ret], cache.V[ret], cache.K[evi], cache.V[evi], u_star, t, passed,
+                      cache.storage, weighted)
+    events = AppendEvents(cache.pos[evi].copy(), cache.pos[ret][t].copy(), u_star, passed, cache.tau)
+    cache.K, cache.V = Kc, Vc
+    cache.score = cache.score[ret]
+    cache.pos = cache.pos[ret]
+    return out, events
+
+
 # --------------------------------------------------------------------------- whole layer / config
 
 def prefill_kv_head(Q, K, V, causal: bool = True):

@@ -147,3 +147,46 @@ def decode_step(state, q_heads, k_new, v_new, new_pos, budget, recent, n_sink, b
     for key in ("pos", "K", "V", "score"):
         del state[key][e]
     return outs, ev
+
+
+def append_chunk(state, q_heads_per_token, k_new, v_new, first_pos, budget, recent, n_sink, beta):
+    """m tokens at once: each attends causally (cache + earlier tokens of the block + itself) and
+    adds its softmax row to the scores; then one eviction down to the budget, matching on the
+    keys as they are, threshold from the mean best similarity (EMA with the previous one), and
+    a merge of every passing token into its match.  q_heads_per_token[i] = the G queries of token i."""
+    m, d = len(k_new), len(k_new[0])
+    outs = []
+    for i in range(m):
+        state["pos"].append(first_pos + i)
+        state["K"].append(list(k_new[i]))
+        state["V"].append(list(v_new[i]))
+        state["score"].append(0.0)
+        n = len(state["pos"])
+        row = []
+        for q in q_heads_per_token[i]:
+            logits = [dot(q, kk) / math.sqrt(d) for kk in state["K"]]
+            mx = max(logits)
+            ex = [math.exp(x - mx) for x in logits]
+            z = math.fsum(ex)
+            p = [x / z for x in ex]
+            row.append([math.fsum(p[j] * state["V"][j][c] for j in range(n)) for c in range(d)])
+            state["score"] = [s + pj for s, pj in zip(state["score"], p)]
+        outs.append(row)
+    n = len(state["pos"])
+    if n <= budget:
+        return outs, {"evi": [], "t": [], "u": [], "passed": []}
+    alive, dropped = choose_retained(state["score"], budget, recent, n_sink)
+    best_u, best_j = nearest(state["K"], alive, dropped)
+    mean_u = math.fsum(best_u) / len(best_u)
+    tau = state["tau"]
+    tau = mean_u if math.isnan(tau) else beta * mean_u + (1.0 - beta) * tau
+    state["tau"] = tau
+    passed = [u >= tau for u in best_u]
+    Kc, Vc = merged_rows(state["K"], state["V"], alive, dropped, best_u, best_j, passed)
+    ev = {"evi": [state["pos"][e] for e in dropped], "t": [state["pos"][j] for j in best_j],
+          "u": best_u, "passed": passed}
+    state["K"] = [Kc[j] for j in alive]
+    state["V"] = [Vc[j] for j in alive]
+    state["score"] = [state["score"][j] for j in alive]
+    state["pos"] = [state["pos"][j] for j in alive]
+    return outs, ev

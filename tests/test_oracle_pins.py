@@ -513,3 +513,135 @@ def test_allocation_is_the_clipped_proportional_solution():
         want = np.clip(b * w, lo, hi)
         assert S.sum() == tot and S.min() >= lo and S.max() <= hi
         assert np.all(np.abs(S - want) <= 1.0 + 1e-6), (F, tot, S, want)
+
+
+# ------------------------------------------------------------------ multi-token append
+
+def _random_head_state(n, d, budget, recent, sink, seed, G=2):
+    g = np.random.default_rng(seed)
+    K, V = g.standard_normal((n, d)), g.standard_normal((n, d))
+    Q = g.standard_normal((G, n, d)) * 1.5
+    _, score, _ = ref.prefill_kv_head(Q, K, V)
+    cache, _ = ref.compress_head(K, V, score, budget, recent, sink)
+    return cache, g
+
+
+def _copy_cache(c):
+    return ref.HeadCache(c.K.copy(), c.V.copy(), c.score.copy(), c.pos.copy(), c.tau, c.storage)
+
+
+def test_append_of_one_token_is_a_generation_step():
+    """m = 1: the block form must be the generation step of Eq. 6-12, bit for bit."""
+    d, G, budget, recent, sink, beta = 6, 2, 12, 3, 1, 0.6
+    cache, g = _random_head_state(30, d, budget, recent, sink, 3, G)
+    a, b = _copy_cache(cache), _copy_cache(cache)
+    for t in range(9):
+        q, k, v = g.standard_normal((G, d)) * 2, g.standard_normal(d), g.standard_normal(d)
+        out1, e1 = ref.decode_step_head(a, q, k, v, 30 + t, budget, recent, sink, beta)
+        out2, e2 = ref.append_chunk_head(b, q[:, None, :], k[None], v[None], 30 + t, budget, recent, sink, beta)
+        assert np.array_equal(out1, out2[:, 0])
+        assert list(e2.evicted) == ([e1.evicted_pos] if e1.evicted_pos >= 0 else [])
+        if e1.evicted_pos >= 0:
+            assert e2.u_star[0] == e1.u_star and e2.tau == e1.tau
+            assert (int(e2.target[0]) if e2.passed[0] else -1) == e1.target_pos
+        assert np.array_equal(a.K, b.K) and np.array_equal(a.V, b.V)
+        assert np.array_equal(a.score, b.score) and np.array_equal(a.pos, b.pos)
+
+
+def test_append_to_an_empty_cache_is_prompt_encoding():
+    """A block appended to an empty cache with no threshold yet is prompt encoding: causal
+    attention over the block, column sums as scores (Eq. 6, prompt case), and the token-level
+    operation with tau_0 = mean best similarity (Eq. 10, t = 0)."""
+    n, d, G, budget, recent, sink = 40, 5, 2, 14, 4, 2
+    g = np.random.default_rng(11)
+    K, V = g.standard_normal((n, d)), g.standard_normal((n, d))
+    Q = g.standard_normal((G, n, d)) * 2
+    O, score, _ = ref.prefill_kv_head(Q, K, V)
+    want, ev = ref.compress_head(K, V, score, budget, recent, sink)
+    empty = ref.HeadCache(np.zeros((0, d)), np.zeros((0, d)), np.zeros(0), np.zeros(0, dtype=np.int64),
+                          float("nan"))
+    out, ae = ref.append_chunk_head(empty, Q, K, V, 0, budget, recent, sink, 0.7)
+    np.testing.assert_allclose(out, O, rtol=1e-12, atol=1e-14)
+    assert np.array_equal(empty.pos, want.pos) and np.array_equal(ae.evicted, ev.evicted)
+    assert np.array_equal(ae.target, ev.target) and np.array_equal(ae.passed, ev.passed)
+    np.testing.assert_allclose(empty.score, want.score, rtol=1e-12)
+    np.testing.assert_allclose(ae.u_star, ev.u_star, rtol=0, atol=1e-15)
+    assert abs(ae.tau - ev.tau) < 1e-14
+    np.testing.assert_allclose(empty.K, want.K, rtol=1e-12, atol=1e-14)
+    np.testing.assert_allclose(empty.V, want.V, rtol=1e-12, atol=1e-14)
+
+
+def test_append_within_budget_is_full_causal_attention_over_cache_and_block():
+    """budget >= count: nothing is evicted, outputs equal the library's attention of the block's
+    queries over [cache; block] with a causal mask inside the block, and the scores grow by G per
+    token in total (every softmax row sums to 1)."""
+    d, G, m = 8, 3, 7
+    g = np.random.default_rng(5)
+    c0 = 20
+    Kc, Vc = g.standard_normal((c0, d)), g.standard_normal((c0, d))
+    cache = ref.HeadCache(Kc.copy(), Vc.copy(), g.random(c0), np.arange(c0, dtype=np.int64), 0.4)
+    q, k, v = g.standard_normal((G, m, d)) * 2, g.standard_normal((m, d)), g.standard_normal((m, d))
+    before = cache.score.sum()
+    out, ev = ref.append_chunk_head(cache, q, k, v, c0, 100, 5, 0, 0.7)
+    assert ev.evicted.size == 0 and cache.pos.size == c0 + m and cache.tau == 0.4
+    assert abs(cache.score.sum() - before - G * m) < 1e-10
+    Kall, Vall = np.vstack([Kc, k]), np.vstack([Vc, v])
+    mask = torch.ones(m, c0 + m, dtype=torch.bool)
+    for i in range(m):
+        mask[i, c0 + i + 1:] = False
+    for h in range(G):
+        want = torch.nn.functional.scaled_dot_product_attention(
+            torch.from_numpy(q[h])[None], torch.from_numpy(Kall)[None], torch.from_numpy(Vall)[None],
+            attn_mask=mask[None])[0].numpy()
+        np.testing.assert_allclose(out[h], want, rtol=1e-12, atol=1e-13)
+
+
+@pytest.mark.parametrize("n,d,G,budget,recent,sink,m,rounds", [
+    (24, 4, 1, 10, 3, 0, 5, 3),
+    (30, 3, 2, 9, 2, 1, 4, 4),
+    (16, 5, 2, 12, 0, 2, 9, 2),       # no recent window, a block almost as large as the budget
+    (20, 4, 1, 8, 8, 0, 3, 3),        # no heavy hitters: sinks + window only
+])
+def test_append_matches_brute_force(n, d, G, budget, recent, sink, m, rounds):
+    g = np.random.default_rng(n * 100 + m)
+    K, V = g.standard_normal((n, d)), g.standard_normal((n, d))
+    Q = g.standard_normal((G, n, d)) * 1.5
+    _, score, _ = ref.prefill_kv_head(Q, K, V)
+    cache, _ = ref.compress_head(K, V, score, budget, recent, sink)
+    A = [brute.attention_matrix(Q[h].tolist(), K.tolist()) for h in range(G)]
+    bscore = [math.fsum(brute.column_sums(A[h])[j] for h in range(G)) for j in range(n)]
+    state, _ = brute.compress(K.tolist(), V.tolist(), bscore, budget, recent, sink)
+    pos = n
+    for r in range(rounds):
+        q, k, v = g.standard_normal((G, m, d)) * 2, g.standard_normal((m, d)), g.standard_normal((m, d))
+        out, ev = ref.append_chunk_head(cache, q, k, v, pos, budget, recent, sink, 0.7)
+        bout, bev = brute.append_chunk(state, [[q[h, i].tolist() for h in range(G)] for i in range(m)],
+                                       k.tolist(), v.tolist(), pos, budget, recent, sink, 0.7)
+        pos += m
+        assert list(ev.evicted) == bev["evi"] and list(ev.target) == bev["t"]
+        assert list(ev.passed) == bev["passed"]
+        np.testing.assert_allclose(ev.u_star, bev["u"], rtol=0, atol=1e-14)
+        for i in range(m):
+            for h in range(G):
+                np.testing.assert_allclose(out[h, i], bout[i][h], rtol=1e-11, atol=1e-13)
+        assert list(cache.pos) == state["pos"] and abs(cache.tau - state["tau"]) < 1e-13
+        np.testing.assert_allclose(cache.K, np.array(state["K"]), rtol=1e-11, atol=1e-13)
+        np.testing.assert_allclose(cache.V, np.array(state["V"]), rtol=1e-11, atol=1e-13)
+        np.testing.assert_allclose(cache.score, np.array(state["score"]), rtol=1e-11)
+        assert cache.pos.size == budget
+
+
+def test_append_threshold_is_the_ema_of_the_mean_best_similarity():
+    """Eq. 10 for a step with several evicted tokens: tau <- beta * mean(u*) + (1 - beta) * tau, and
+    the flags test against the updated value; a forced threshold leaves tau alone."""
+    d, G, budget, recent, sink, beta, m = 6, 1, 10, 2, 0, 0.3, 6
+    cache, g = _random_head_state(25, d, budget, recent, sink, 8, G)
+    tau0 = cache.tau
+    q, k, v = g.standard_normal((G, m, d)), g.standard_normal((m, d)), g.standard_normal((m, d))
+    forced = _copy_cache(cache)
+    _, ev = ref.append_chunk_head(cache, q, k, v, 25, budget, recent, sink, beta)
+    assert ev.evicted.size == m
+    want = beta * float(np.mean(ev.u_star)) + (1 - beta) * tau0
+    assert abs(cache.tau - want) < 1e-15 and np.array_equal(ev.passed, ev.u_star >= cache.tau)
+    _, evf = ref.append_chunk_head(forced, q, k, v, 25, budget, recent, sink, beta, tau_force=float("inf"))
+    assert forced.tau == tau0 and not evf.passed.any() and np.array_equal(evf.evicted, ev.evicted)
