@@ -64,6 +64,12 @@ typedef struct {
   int32_t merge_average;  /* 0: similarity-weighted merge, Eq. 11-12.  1: average merging,  */
                           /* the alternative of the merge-policy ablation (Sec. 5): the     */
                           /* plain mean of the retained row and the tokens merged into it   */
+  int32_t max_append;     /* largest block of tokens d2o_append_chunk will be given (0 or 1: */
+                          /* single-token generation steps only).  A layer's cache region    */
+                          /* holds S_l + max(1, max_append) rows, so slots_per_seq must hold */
+                          /* sum_l (S_l + max(1, max_append)), and S_l + max_append must not */
+                          /* exceed max_prompt_len (the block's token-level stages reuse the */
+                          /* prompt-phase scratch)                                           */
 } d2o_config;
 
 /* A strided tensor whose last dimension (d) is contiguous.  Strides are in elements.
@@ -181,6 +187,27 @@ int d2o_prefill_compress(d2o_ctx* ctx, int32_t layer, d2o_view Q, d2o_view K, d2
  * Errors: INVALID_ARG, STATE (a layer not compressed), CAPACITY, HIP. */
 int d2o_decode_step(d2o_ctx* ctx, int32_t layer, int32_t n_layers_in_call, d2o_view q,
                     d2o_view k_new, d2o_view v_new, d2o_view out, void* stream);
+
+/* A block of m new tokens on one layer (the chunked / multi-turn form of a generation step:
+ * Sec. 3 Eq. 2-3 and Sec. 4.2 Eq. 6-12 applied to m tokens at once).  Token i of the block is
+ * appended, attends to the cache and to the block's tokens up to itself, and adds its softmax
+ * rows to the cumulative scores (Eq. 6, no eviction inside the block); then every cache that
+ * exceeds its budget evicts count - S_l tokens together by Eq. 7-8, matches them on the keys as
+ * they are (Eq. 9), updates the threshold with the step's mean best similarity, tau <- beta *
+ * mean + (1 - beta) * tau (tau <- mean while unset; Eq. 10 with several evicted tokens in one
+ * step), and merges the passing ones (Eq. 11-12).  m = 1 gives the results of d2o_decode_step.
+ * Q, O: [B][Hq][m][d]; K, V: [B][Hkv][m][d] (views as for d2o_prefill_attend); 1 <= m <=
+ * max_append.  Enqueues only.  Errors: INVALID_ARG, STATE (layer not compressed), CAPACITY, HIP. */
+int d2o_append_chunk(d2o_ctx* ctx, int32_t layer, d2o_view Q, d2o_view K, d2o_view V, int32_t m,
+                     d2o_view O, void* stream);
+
+/* What the most recent d2o_append_chunk call did on one (sequence, KV head): evicted positions
+ * [n_evi] ascending and per evicted token its match (position), best similarity and whether it
+ * passed the threshold.  Host buffers of max_append + budget entries each; any may be NULL.
+ * Synchronises `stream`. */
+int d2o_append_events(d2o_ctx* ctx, int32_t layer, int32_t b, int32_t kv_head, int32_t* evicted_pos,
+                      int32_t* n_evi, int32_t* target_pos, double* u_star, uint8_t* passed,
+                      void* stream);
 
 /* d2o_decode_step for callers that cannot allocate or hand over scratch memory at the time of
  * the call: code under HIP graph capture, tight serving loops, harnesses that forbid

@@ -21,7 +21,7 @@ EXPORTS = [
     "d2o_prefill_attend", "d2o_get_density", "d2o_allocate_budgets", "d2o_allocate_budgets_policy",
     "d2o_scores_import",
     "d2o_scores_export", "d2o_compress_layer", "d2o_prefill_compress", "d2o_decode_step",
-    "d2o_decode_step_static",
+    "d2o_decode_step_static", "d2o_append_chunk", "d2o_append_events",
     "d2o_layer_reserve", "d2o_cache_export", "d2o_cache_import", "d2o_last_events",
     "d2o_prefill_events", "d2o_timing_enable", "d2o_timing_read",
 ]
@@ -36,7 +36,7 @@ class d2o_config(C.Structure):
                 ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32), ("max_prompt_len", C.c_int32),
                 ("slots_per_seq", C.c_int64), ("dtype", C.c_int32), ("n_sink", C.c_int32),
                 ("beta", C.c_double), ("tau_force", C.c_double), ("out_f32", C.c_int32),
-                ("merge_average", C.c_int32)]
+                ("merge_average", C.c_int32), ("max_append", C.c_int32)]
 
 
 class d2o_view(C.Structure):
@@ -76,6 +76,8 @@ def load_library() -> C.CDLL:
                                          vp, vp, vp]
     lib.d2o_decode_step.argtypes = [vp, i32, i32, d2o_view, d2o_view, d2o_view, d2o_view, vp]
     lib.d2o_decode_step_static.argtypes = [vp, i32, i32, d2o_view, d2o_view, d2o_view, d2o_view, vp]
+    lib.d2o_append_chunk.argtypes = [vp, i32, d2o_view, d2o_view, d2o_view, i32, d2o_view, vp]
+    lib.d2o_append_events.argtypes = [vp, i32, i32, i32, vp, vp, vp, vp, vp, vp]
     lib.d2o_layer_reserve.argtypes = [vp, i32, i32, vp, vp]
     lib.d2o_cache_export.argtypes = [vp, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp]
     lib.d2o_cache_import.argtypes = [vp, i32, i32, i32, vp, vp, vp, vp, i32, C.c_double, i32, vp]
@@ -144,14 +146,15 @@ class D2O:
 
     def __init__(self, batch, n_layers, n_q_heads, n_kv_heads, head_dim, max_prompt_len,
                  slots_per_seq, dtype="bf16", n_sink=0, beta=0.7, tau_force=float("nan"),
-                 out_f32=False, device="cuda:0", merge_average=False):
+                 out_f32=False, device="cuda:0", merge_average=False, max_append=0):
         self.lib = load_library()
         if not torch.cuda.is_available():
             raise D2OError("no GPU visible: the D2O library has no CPU path")
         self.device = torch.device(device)
         self.cfg = d2o_config(batch, n_layers, n_q_heads, n_kv_heads, head_dim, max_prompt_len,
                               slots_per_seq, D2O_BF16 if dtype == "bf16" else D2O_F32, n_sink,
-                              beta, tau_force, 1 if out_f32 else 0, 1 if merge_average else 0)
+                              beta, tau_force, 1 if out_f32 else 0, 1 if merge_average else 0,
+                              int(max_append))
         self.dtype = dtype
         self.out_dtype = torch.float32 if out_f32 else (torch.bfloat16 if dtype == "bf16" else torch.float32)
         self.torch_dtype = torch.bfloat16 if dtype == "bf16" else torch.float32
@@ -242,6 +245,24 @@ class D2O:
         self._check(self.lib.d2o_decode_step(self.ctx, layer, n_layers_in_call, view_decode(q),
                                              view_decode(k_new), view_decode(v_new),
                                              view_decode(out), _stream_ptr()), "d2o_decode_step")
+
+    def d2o_append_chunk(self, layer, Q, K, V, O):
+        """Q, O [B][Hq][m][d]; K, V [B][Hkv][m][d]: a block of m new tokens on one layer."""
+        self._check(self.lib.d2o_append_chunk(self.ctx, layer, view4(Q), view4(K), view4(V), Q.shape[2],
+                                              view4(O), _stream_ptr()), "d2o_append_chunk")
+
+    def d2o_append_events(self, layer, b, kv_head, capacity):
+        """(evicted positions, target positions, best similarities, passed flags) of the last block."""
+        evi = np.zeros(capacity, dtype=np.int32)
+        tgt = np.zeros(capacity, dtype=np.int32)
+        us = np.zeros(capacity, dtype=np.float64)
+        ps = np.zeros(capacity, dtype=np.uint8)
+        ne = C.c_int32()
+        self._check(self.lib.d2o_append_events(self.ctx, layer, b, kv_head, _np_ptr(evi), C.byref(ne),
+                                               _np_ptr(tgt), _np_ptr(us), _np_ptr(ps), _stream_ptr()),
+                    "d2o_append_events")
+        e = ne.value
+        return evi[:e], tgt[:e], us[:e], ps[:e].astype(bool)
 
     def d2o_decode_step_static(self, layer, n_layers_in_call, q, k_new, v_new, out):
         self._check(self.lib.d2o_decode_step_static(self.ctx, layer, n_layers_in_call, view_decode(q),

@@ -51,6 +51,7 @@ int check_config(const d2o_config* c) {
   if ((G != 1 && G != 2 && G != 4 && G != 8) || c->n_q_heads > 256) return D2O_ERR_UNSUPPORTED;
   if (c->out_f32 != 0 && c->out_f32 != 1) return D2O_ERR_INVALID_ARG;
   if (c->merge_average != 0 && c->merge_average != 1) return D2O_ERR_INVALID_ARG;
+  if (c->max_append < 0 || c->max_append >= c->max_prompt_len) return D2O_ERR_INVALID_ARG;
   return D2O_OK;
 }
 
@@ -103,6 +104,13 @@ void layout(d2o_ctx* x, char* persistent, char* scratch, size_t* pbytes, size_t*
   s.take(x->g_off, bh * (np + 1));
   s.take(x->g_cur, bh * (np + 1));
   s.take(x->g_src, bh * np);
+  const size_t ap = c.max_append > 1 ? 1 : 0;  // the position-ordered copy exists only when blocks can be appended
+  s.take_raw(x->app_K, ap * bh * np * d * es);
+  s.take_raw(x->app_V, ap * bh * np * d * es);
+  s.take(x->app_score, ap * bh * np);
+  s.take(x->app_pos, ap * bh * np);
+  s.take(x->app_rank, ap * bh * np);
+  s.take(x->app_n, ap * bh);
   s.take(x->d_logit, nch * B * Hq * kChunk);
   const size_t nsub = nch * 4;  // partial results are kept per 64 slots, a quarter of a chunk
   s.take(x->d_rec, bh * nsub * 32);
@@ -116,6 +124,7 @@ void layout(d2o_ctx* x, char* persistent, char* scratch, size_t* pbytes, size_t*
 void init_sizes(d2o_ctx* x) {
   x->esize = x->cfg.dtype == D2O_BF16 ? 2 : 4;
   x->npad = (x->cfg.max_prompt_len + 127) / 128 * 128;
+  x->grow = std::max(1, x->cfg.max_append);
   x->nchunk_cap = x->cfg.slots_per_seq / kChunk + x->cfg.n_layers + 1;
 }
 
@@ -133,7 +142,9 @@ int reserve_layer(d2o_ctx* x, int32_t layer, int32_t n, const int32_t* budget, c
     if (budget[b] < 1 || recent[b] < 0 || budget[b] < c.n_sink + recent[b])
       return fail(x, D2O_ERR_INVALID_ARG, "budget must be >= 1 and >= n_sink + recent");
     if (n < c.n_sink) return fail(x, D2O_ERR_INVALID_ARG, "prompt shorter than the sink tokens");
-    const int64_t need = int64_t(budget[b]) + 1;
+    const int64_t need = int64_t(budget[b]) + x->grow;
+    if (c.max_append > 1 && int64_t(budget[b]) + c.max_append > x->npad)
+      return fail(x, D2O_ERR_CAPACITY, "budget + max_append exceeds max_prompt_len (rounded up to 128)");
     if (x->used_slots[b] + need > c.slots_per_seq)
       return fail(x, D2O_ERR_CAPACITY, "slots_per_seq too small for the layer budgets");
     meta[b].base = int32_t(x->used_slots[b]);
@@ -142,8 +153,8 @@ int reserve_layer(d2o_ctx* x, int32_t layer, int32_t n, const int32_t* budget, c
     meta[b].chunk_base = int32_t(x->used_chunks[b]);
   }
   for (int b = 0; b < c.batch; ++b) {
-    x->used_slots[b] += int64_t(budget[b]) + 1;
-    x->used_chunks[b] += (int64_t(budget[b]) + 1 + kChunk - 1) / kChunk;
+    x->used_slots[b] += int64_t(budget[b]) + x->grow;
+    x->used_chunks[b] += (int64_t(budget[b]) + x->grow + kChunk - 1) / kChunk;
   }
   st.meta = meta;
   st.n = n;
@@ -282,6 +293,7 @@ int d2o_reset(d2o_ctx* x, void* stream) {
   std::fill(x->used_slots.begin(), x->used_slots.end(), 0);
   std::fill(x->used_chunks.begin(), x->used_chunks.end(), 0);
   x->last_compress_layer = -1;
+  x->last_append_layer = -1;
   return D2O_OK;
 }
 
@@ -547,6 +559,54 @@ int d2o_decode_step_static(d2o_ctx* x, int32_t layer, int32_t nl, d2o_view q, d2
   return decode_step_impl(x, layer, nl, q, k_new, v_new, out, stream, true);
 }
 
+int d2o_append_chunk(d2o_ctx* x, int32_t layer, d2o_view Q, d2o_view K, d2o_view V, int32_t m, d2o_view O,
+                     void* stream) {
+  if (!x) return D2O_ERR_INVALID_ARG;
+  const d2o_config& c = x->cfg;
+  if (layer < 0 || layer >= c.n_layers) return fail(x, D2O_ERR_INVALID_ARG, "layer out of range");
+  if (c.max_append < 2) return fail(x, D2O_ERR_STATE, "the context was created without room for blocks (max_append < 2)");
+  if (m < 1 || m > c.max_append) return fail(x, D2O_ERR_INVALID_ARG, "block size must be in [1, max_append]");
+  if (!view_ok(x, Q) || !view_ok(x, K) || !view_ok(x, V) || !view_ok(x, O, c.out_f32 ? 4 : 0))
+    return fail(x, D2O_ERR_INVALID_ARG, "null, misaligned or badly strided tensor view");
+  if (Q.stride_n < c.head_dim || K.stride_n < c.head_dim || V.stride_n < c.head_dim || O.stride_n < c.head_dim)
+    return fail(x, D2O_ERR_INVALID_ARG, "token stride smaller than head_dim");
+  LayerState& st = x->layers[layer];
+  if (st.phase != kReady) return fail(x, D2O_ERR_STATE, "layer not compressed");
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const int es = x->esize, os = c.out_f32 ? 4 : x->esize;
+  // ---- Eq. 6 token by token, no eviction inside the block: token i as a generation step over the
+  //      cache grown by the block's earlier tokens
+  for (int i = 0; i < m; ++i) {
+    auto tok = [&](const d2o_view& v, int bytes) {  // the block's token i as a [layer][b][head][d] tensor of one layer
+      View t = to_view(v);
+      t.ptr = static_cast<char*>(t.ptr) + size_t(i) * v.stride_n * bytes;
+      t.sn = 0;
+      return t;
+    };
+    const hipError_t e = launch_decode(x, layer, 1, tok(Q, es), tok(K, es), tok(V, es), tok(O, os),
+                                       st.next_pos + i, s, nullptr, i + 1);
+    if (e != hipSuccess) return fail(x, D2O_ERR_HIP, std::string("append, attention: ") + hipGetErrorString(e));
+  }
+  st.next_pos += m;
+  // ---- Eq. 7-12 once on every cache, in ascending token position
+  int max_budget = 0;
+  for (const auto& mt : st.meta) max_budget = std::max(max_budget, mt.budget);
+  const int n_eff = max_budget + m;  // upper bound of the entries of any head
+  const View aK{x->app_K, int64_t(c.n_kv_heads) * x->npad * c.head_dim, int64_t(x->npad) * c.head_dim, c.head_dim};
+  const View aV{x->app_V, aK.sb, aK.sh, aK.sn};
+  hipError_t e;
+  if ((e = launch_cache_sort(x, layer, s)) != hipSuccess) return fail(x, D2O_ERR_HIP, std::string("append, ordering: ") + hipGetErrorString(e));
+  if ((e = launch_select(x, layer, n_eff, s, true)) != hipSuccess) return fail(x, D2O_ERR_HIP, std::string("append, select: ") + hipGetErrorString(e));
+  if ((e = launch_gather(x, layer, aK, aV, n_eff, s, true)) != hipSuccess) return fail(x, D2O_ERR_HIP, std::string("append, gather: ") + hipGetErrorString(e));
+  if ((e = launch_match(x, layer, aK, n_eff, s)) != hipSuccess) return fail(x, D2O_ERR_HIP, std::string("append, match: ") + hipGetErrorString(e));
+  if ((e = launch_threshold_group(x, layer, n_eff, s, true)) != hipSuccess) return fail(x, D2O_ERR_HIP, std::string("append, threshold: ") + hipGetErrorString(e));
+  if ((e = launch_merge(x, layer, aK, aV, n_eff, s)) != hipSuccess) return fail(x, D2O_ERR_HIP, std::string("append, merge: ") + hipGetErrorString(e));
+  if ((e = launch_init_candidates(x, layer, st.next_pos, s)) != hipSuccess) return fail(x, D2O_ERR_HIP, std::string("append, candidates: ") + hipGetErrorString(e));
+  x->last_append_layer = layer;
+  x->last_compress_layer = -1;  // the prompt-phase events shared the scratch lists and are gone
+  return D2O_OK;
+}
+
 static int head_args_ok(d2o_ctx* x, int32_t layer, int32_t b, int32_t h) {
   const d2o_config& c = x->cfg;
   if (layer < 0 || layer >= c.n_layers || b < 0 || b >= c.batch || h < 0 || h >= c.n_kv_heads)
@@ -663,6 +723,37 @@ int d2o_prefill_events(d2o_ctx* x, int32_t layer, int32_t b, int32_t h, int32_t*
   if (retained_pos) std::memcpy(retained_pos, ret.data(), cnt[0] * sizeof(int32_t));
   if (target_pos)
     for (int i = 0; i < cnt[1]; ++i) target_pos[i] = ret[tgt[i]];
+  return D2O_OK;
+}
+
+int d2o_append_events(d2o_ctx* x, int32_t layer, int32_t b, int32_t h, int32_t* evicted_pos, int32_t* n_evi,
+                      int32_t* target_pos, double* u_star, uint8_t* passed, void* stream) {
+  if (!x) return D2O_ERR_INVALID_ARG;
+  int rc = head_args_ok(x, layer, b, h);
+  if (rc) return rc;
+  if (layer != x->last_append_layer)
+    return fail(x, D2O_ERR_STATE, "block events are kept for the layer of the most recent d2o_append_chunk only");
+  const d2o_config& c = x->cfg;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const size_t bh = size_t(b) * c.n_kv_heads + h, o = bh * x->npad;
+  int32_t cnt[2] = {0, 0}, n = 0;
+  D2O_HIP_CHECK(x, hipMemcpyAsync(cnt, x->sel_cnt + bh * 2, 2 * sizeof(int32_t), hipMemcpyDeviceToHost, s));
+  D2O_HIP_CHECK(x, hipMemcpyAsync(&n, x->app_n + bh, sizeof(int32_t), hipMemcpyDeviceToHost, s));
+  D2O_HIP_CHECK(x, hipStreamSynchronize(s));
+  if (n_evi) *n_evi = cnt[1];
+  if (cnt[1] == 0) return D2O_OK;
+  std::vector<int32_t> ret(cnt[0]), evi(cnt[1]), tgt(cnt[1]), pos(n);
+  D2O_HIP_CHECK(x, hipMemcpyAsync(ret.data(), x->sel_ret + o, cnt[0] * sizeof(int32_t), hipMemcpyDeviceToHost, s));
+  D2O_HIP_CHECK(x, hipMemcpyAsync(evi.data(), x->sel_evi + o, cnt[1] * sizeof(int32_t), hipMemcpyDeviceToHost, s));
+  D2O_HIP_CHECK(x, hipMemcpyAsync(tgt.data(), x->m_tgt + o, cnt[1] * sizeof(int32_t), hipMemcpyDeviceToHost, s));
+  D2O_HIP_CHECK(x, hipMemcpyAsync(pos.data(), x->app_pos + o, n * sizeof(int32_t), hipMemcpyDeviceToHost, s));
+  if (u_star) D2O_HIP_CHECK(x, hipMemcpyAsync(u_star, x->m_ustar + o, cnt[1] * sizeof(double), hipMemcpyDeviceToHost, s));
+  if (passed) D2O_HIP_CHECK(x, hipMemcpyAsync(passed, x->m_pass + o, cnt[1], hipMemcpyDeviceToHost, s));
+  D2O_HIP_CHECK(x, hipStreamSynchronize(s));
+  for (int i = 0; i < cnt[1]; ++i) {  // ranks in the position-ordered copy -> token positions
+    if (evicted_pos) evicted_pos[i] = pos[evi[i]];
+    if (target_pos) target_pos[i] = pos[ret[tgt[i]]];
+  }
   return D2O_OK;
 }
 

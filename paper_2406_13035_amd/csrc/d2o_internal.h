@@ -56,6 +56,8 @@ struct d2o_ctx {
   std::vector<int64_t> used_slots;   // [B]
   std::vector<int64_t> used_chunks;  // [B]
   int32_t last_compress_layer = -1;
+  int32_t last_append_layer = -1;
+  int32_t grow = 1;                  // rows a layer's cache region holds beyond its budget: max(1, max_append)
   int32_t esize = 2;                 // bytes per element of Q/K/V/cache
   int32_t npad = 0;                  // max_prompt_len rounded up to 128
   int64_t nchunk_cap = 0;            // chunk slots per (sequence, KV head) in decode partials
@@ -103,6 +105,13 @@ struct d2o_ctx {
   int32_t* g_off = nullptr;      // [..][npad+1] exclusive prefix of g_cnt
   int32_t* g_cur = nullptr;      // [..][npad+1] fill cursors
   int32_t* g_src = nullptr;      // evicted ranks grouped by target (unordered inside a group)
+  // multi-token append: the cache in ascending token position (block-level Eq. 7-12 run on it)
+  void* app_K = nullptr;         // [B][Hkv][npad][d]
+  void* app_V = nullptr;         // [B][Hkv][npad][d]
+  double* app_score = nullptr;   // [B][Hkv][npad] cumulative scores, fp64
+  int32_t* app_pos = nullptr;    // [B][Hkv][npad] token positions, ascending
+  int32_t* app_rank = nullptr;   // [B][Hkv][npad] rank of every cache slot's position
+  int32_t* app_n = nullptr;      // [B][Hkv] entries
   // decode
   double* d_logit = nullptr;     // [nchunk][B][Hkv][G][256] exp(logit - sub-chunk max), chunk-major
   double* d_rec = nullptr;       // [nchunk][B][Hkv][4][32] per 64 slots: softmax maxima and sums, candidates' best cosine and slot
@@ -151,15 +160,21 @@ hipError_t launch_prefill_f32(d2o_ctx* c, int layer, View Q, View K, View V, Vie
 hipError_t launch_prefill_bf16(d2o_ctx* c, int layer, View Q, View K, View V, View O, int n,
                                hipStream_t s);
 hipError_t launch_density(d2o_ctx* c, int layer, int n, hipStream_t s);
-hipError_t launch_select(d2o_ctx* c, int layer, int n, hipStream_t s);
-hipError_t launch_gather(d2o_ctx* c, int layer, View K, View V, int n, hipStream_t s);
+// append = true: the stages run on the position-ordered copy of the cache (app_*): fp64 scores,
+// per-head entry counts, positions through app_pos, EMA form of the threshold
+hipError_t launch_select(d2o_ctx* c, int layer, int n, hipStream_t s, bool append = false);
+hipError_t launch_gather(d2o_ctx* c, int layer, View K, View V, int n, hipStream_t s, bool append = false);
 hipError_t launch_match(d2o_ctx* c, int layer, View K, int n, hipStream_t s);
-hipError_t launch_threshold_group(d2o_ctx* c, int layer, int n, hipStream_t s);
+hipError_t launch_threshold_group(d2o_ctx* c, int layer, int n, hipStream_t s, bool append = false);
+hipError_t launch_cache_sort(d2o_ctx* c, int layer, hipStream_t s);  // cache -> app_* in ascending position
 hipError_t launch_merge(d2o_ctx* c, int layer, View K, View V, int n, hipStream_t s);
 // static_scratch: nullptr = the context's scratch workspace; otherwise the device address of the
 // library's static scratch array, which then holds the step's partial results and operands
+// extra_rows > 0: the caches may already hold up to that many rows beyond their budgets and
+// nothing is evicted (a token of a d2o_append_chunk block)
 hipError_t launch_decode(d2o_ctx* c, int layer0, int nl, View q, View k, View v, View out,
-                         int new_pos, hipStream_t s, unsigned char* static_scratch = nullptr);
+                         int new_pos, hipStream_t s, unsigned char* static_scratch = nullptr,
+                         int extra_rows = 0);
 hipError_t static_scratch_address(unsigned char** out);  // per device; first call per device looks it up
 size_t decode_static_scratch_need(const d2o_ctx* c);     // bytes of it a decode step of this context uses
 size_t decode_static_scratch_capacity();

@@ -43,6 +43,7 @@ struct DecodeArgs {
   double* ev_ustar;
   int64_t slots;
   int layer0, nl, B, Hkv, G, new_pos, n_sink, out_f32, merge_average;
+  int no_evict;       // 1: a token inside a block of d2o_append_chunk: the caches grow past their budgets
   double beta, tau_force;
   int32_t lay_off[kMaxLayersPerCall + 1];  // first flat chunk-group index of each entry of lay_id
   int32_t lay_id[kMaxLayersPerCall];       // layers of the call (relative), most chunks first

@@ -22,6 +22,11 @@ __device__ __forceinline__ uint32_t order_key(float x) {
   const uint32_t b = __float_as_uint(x);
   return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
 }
+__device__ __forceinline__ uint64_t order_key(double x) {
+  if (x == 0.0) x = 0.0;
+  const uint64_t b = uint64_t(__double_as_longlong(x));
+  return (b & 0x8000000000000000ull) ? ~b : (b | 0x8000000000000000ull);
+}
 
 // Exclusive prefix sums of two 0/1 flags over the block, in thread order.  Returns the
 // exclusive counts and adds the block totals to *tot_a / *tot_b (read by all threads).
@@ -52,16 +57,23 @@ __device__ __forceinline__ void block_scan2(bool fa, bool fb, int& ex_a, int& ex
   tot_b = tb;
 }
 
-__global__ __launch_bounds__(1024) void select_kernel(const float* __restrict__ score, const int32_t* __restrict__ meta,
+// S: score type (fp32 column sums after prompt encoding; fp64 cumulative scores of a cache that a
+// block of tokens was appended to).  nvec, when given, holds the number of entries per head.
+template <typename S>
+__global__ __launch_bounds__(1024) void select_kernel(const S* __restrict__ score, const int32_t* __restrict__ meta,
                                                       int32_t* __restrict__ ret, int32_t* __restrict__ evi,
-                                                      int32_t* __restrict__ cnt, int n, int npad, int n_sink) {
+                                                      int32_t* __restrict__ cnt, int n_all, const int32_t* __restrict__ nvec,
+                                                      int npad, int n_sink) {
+  typedef decltype(order_key(S())) Key;
+  constexpr int kTopShift = int(sizeof(Key)) * 8 - 8;
   __shared__ int hist[256];
   __shared__ int wa[16], wb[16];
-  __shared__ uint32_t sh_prefix;
+  __shared__ Key sh_prefix;
   __shared__ int sh_need;
   const int hk = blockIdx.x, b = blockIdx.y, Hkv = gridDim.x;
   const int64_t bh = int64_t(b) * Hkv + hk;
-  const float* sc = score + bh * npad;
+  const int n = nvec ? nvec[bh] : n_all;
+  const S* sc = score + bh * npad;
   int32_t* r = ret + bh * npad;
   int32_t* e = evi + bh * npad;
   const int budget = meta[b * 4 + 1], recent = meta[b * 4 + 2];
@@ -77,15 +89,15 @@ __global__ __launch_bounds__(1024) void select_kernel(const float* __restrict__ 
   const int lo = n_sink, hi = n - recent;   // middle range [lo, hi)
   const int nhh = budget - n_sink - recent;  // heavy hitters to keep, 0 <= nhh < hi - lo
   // ---- radix select: find the key value of the nhh-th largest and how many equal keys to take
-  uint32_t prefix = 0, mask = 0;
+  Key prefix = 0, mask = 0;
   int need = nhh;
   if (nhh > 0) {
-    for (int shift = 24; shift >= 0; shift -= 8) {
+    for (int shift = kTopShift; shift >= 0; shift -= 8) {
       for (int i = tid; i < 256; i += blockDim.x) hist[i] = 0;
       __syncthreads();
       for (int j = lo + tid; j < hi; j += blockDim.x) {
-        const uint32_t k = order_key(sc[j]);
-        if ((k & mask) == prefix) atomicAdd(&hist[(k >> shift) & 255], 1);
+        const Key k = order_key(sc[j]);
+        if ((k & mask) == prefix) atomicAdd(&hist[int(k >> shift) & 255], 1);
       }
       __syncthreads();
       if (tid == 0) {
@@ -94,13 +106,13 @@ __global__ __launch_bounds__(1024) void select_kernel(const float* __restrict__ 
           if (hist[bin] >= rem) break;
           rem -= hist[bin];
         }
-        sh_prefix = prefix | (uint32_t(bin) << shift);
+        sh_prefix = prefix | (Key(bin) << shift);
         sh_need = rem;
       }
       __syncthreads();
       prefix = sh_prefix;
       need = sh_need;
-      mask |= 0xFFu << shift;
+      mask |= Key(0xFF) << shift;
       __syncthreads();
     }
   }
@@ -113,7 +125,7 @@ __global__ __launch_bounds__(1024) void select_kernel(const float* __restrict__ 
       if (j < lo || j >= hi) {
         keep = true;
       } else if (nhh > 0) {
-        const uint32_t k = order_key(sc[j]);
+        const Key k = order_key(sc[j]);
         keep = k > prefix;
         eq = k == prefix;
       }
@@ -140,9 +152,12 @@ __global__ __launch_bounds__(1024) void select_kernel(const float* __restrict__ 
 
 // ------------------------------------------------------------------------------------------
 // Compaction: retained rows of K, V into the layer's cache region; scores widen to fp64.
-template <typename T>
+// APPEND: the source is the position-ordered copy of a cache: fp64 scores (sc64) and token
+// positions (apos) indexed like its rows.
+template <typename T, bool APPEND>
 __global__ __launch_bounds__(256) void gather_kernel(const T* __restrict__ K, View kv, const T* __restrict__ V, View vv,
-                                                     const float* __restrict__ score, const int32_t* __restrict__ ret,
+                                                     const float* __restrict__ score, const double* __restrict__ sc64,
+                                                     const int32_t* __restrict__ apos, const int32_t* __restrict__ ret,
                                                      const int32_t* __restrict__ cnt, const int32_t* __restrict__ meta,
                                                      T* __restrict__ cK, T* __restrict__ cV, double* __restrict__ cscore,
                                                      int32_t* __restrict__ cpos, int32_t* __restrict__ ccount,
@@ -164,8 +179,8 @@ __global__ __launch_bounds__(256) void gather_kernel(const T* __restrict__ K, Vi
   *reinterpret_cast<u32x4*>(cV + dst * d + c) =
       *reinterpret_cast<const u32x4*>(V + b * vv.sb + hk * vv.sh + int64_t(pos) * vv.sn + c);
   if (c == 0) {
-    cscore[dst] = double(score[bh * npad + pos]);
-    cpos[dst] = pos;
+    cscore[dst] = APPEND ? sc64[bh * npad + pos] : double(score[bh * npad + pos]);
+    cpos[dst] = APPEND ? apos[bh * npad + pos] : pos;
   }
 }
 
@@ -559,7 +574,8 @@ __global__ __launch_bounds__(1024) void threshold_group_kernel(const double* __r
                                                                const int32_t* __restrict__ cnt, uint8_t* __restrict__ pass,
                                                                int32_t* __restrict__ gcnt, int32_t* __restrict__ goff,
                                                                int32_t* __restrict__ gcur, int32_t* __restrict__ gsrc,
-                                                               double* __restrict__ tau_out, int npad, double tau_force) {
+                                                               double* __restrict__ tau_out, int npad, double tau_force,
+                                                               int ema, double beta) {
   __shared__ double red[16];
   __shared__ int wa[16], wb[16];
   const int hk = blockIdx.x, b = blockIdx.y, Hkv = gridDim.x;
@@ -574,13 +590,22 @@ __global__ __launch_bounds__(1024) void threshold_group_kernel(const double* __r
   int32_t* gu = gcur + bh * (npad + 1);
   int32_t* gs = gsrc + bh * npad;
   if (nevi == 0) {
-    for (int j = tid; j <= nret; j += blockDim.x) gc[j] = 0;
-    return;  // tau stays unset (NaN)
+    // no sources anywhere: merge_kernel reads the offsets of every slot, so they must say so
+    for (int j = tid; j <= nret; j += blockDim.x) {
+      gc[j] = 0;
+      go[j] = 0;
+    }
+    return;  // tau keeps its value (unset, NaN, after prompt encoding)
   }
   double part = 0.0;
   for (int i = tid; i < nevi; i += blockDim.x) part += us[i];
-  const double tau = block_sum(part, red) / double(nevi);
-  if (tid == 0) tau_out[bh] = tau;
+  double tau = block_sum(part, red) / double(nevi);
+  if (ema) {  // a step that evicts several tokens at once: Eq. 10 on their mean best similarity
+    const double prev = tau_out[bh];
+    if (!isnan(prev)) tau = __dadd_rn(__dmul_rn(beta, tau), __dmul_rn(1.0 - beta, prev));
+    __syncthreads();  // every thread has read the previous value
+  }
+  if (tid == 0 && !(ema && !isnan(tau_force))) tau_out[bh] = tau;  // (a forced threshold leaves the EMA state alone)
   const double thr = isnan(tau_force) ? tau : tau_force;
   for (int j = tid; j <= nret; j += blockDim.x) {
     gc[j] = 0;
@@ -783,35 +808,46 @@ __global__ __launch_bounds__(256) void merge_kernel(const T* __restrict__ K, Vie
 
 // ---------------------------------------------------------------------------------------------
 
-hipError_t launch_select(d2o_ctx* c, int layer, int n, hipStream_t s) {
+hipError_t launch_select(d2o_ctx* c, int layer, int n, hipStream_t s, bool append) {
   const d2o_config& cf = c->cfg;
   const float* score = c->score_pre + size_t(layer) * cf.batch * cf.n_kv_heads * c->npad;
+  const int32_t* meta = c->meta + size_t(layer) * cf.batch * 4;
   KernelTimer kt(c, D2O_K_SELECT, s);
-  select_kernel<<<dim3(cf.n_kv_heads, cf.batch), 1024, 0, s>>>(score, c->meta + size_t(layer) * cf.batch * 4,
-                                                               c->sel_ret, c->sel_evi, c->sel_cnt, n, c->npad,
-                                                               cf.n_sink);
+  if (append)
+    select_kernel<double><<<dim3(cf.n_kv_heads, cf.batch), 1024, 0, s>>>(c->app_score, meta, c->sel_ret, c->sel_evi,
+                                                                         c->sel_cnt, n, c->app_n, c->npad, cf.n_sink);
+  else
+    select_kernel<float><<<dim3(cf.n_kv_heads, cf.batch), 1024, 0, s>>>(score, meta, c->sel_ret, c->sel_evi, c->sel_cnt,
+                                                                        n, nullptr, c->npad, cf.n_sink);
   return hipGetLastError();
 }
 
-hipError_t launch_gather(d2o_ctx* c, int layer, View K, View V, int n, hipStream_t s) {
+template <typename T>
+static void run_gather(d2o_ctx* c, int layer, View K, View V, int max_budget, bool append, hipStream_t s) {
   const d2o_config& cf = c->cfg;
   const float* score = c->score_pre + size_t(layer) * cf.batch * cf.n_kv_heads * c->npad;
   const int32_t* meta = c->meta + size_t(layer) * cf.batch * 4;
   int32_t* ccount = c->ccount + size_t(layer) * cf.batch * cf.n_kv_heads;
+  const int rows = 256 / (cf.head_dim * int(sizeof(T)) / 16);
+  const dim3 grid((max_budget + rows - 1) / rows, cf.n_kv_heads, cf.batch);
+  if (append)
+    gather_kernel<T, true><<<grid, 256, 0, s>>>((const T*)K.ptr, K, (const T*)V.ptr, V, score, c->app_score, c->app_pos,
+                                                c->sel_ret, c->sel_cnt, meta, (T*)c->cacheK, (T*)c->cacheV, c->cscore,
+                                                c->cpos, ccount, c->npad, cf.head_dim, cf.slots_per_seq);
+  else
+    gather_kernel<T, false><<<grid, 256, 0, s>>>((const T*)K.ptr, K, (const T*)V.ptr, V, score, nullptr, nullptr,
+                                                 c->sel_ret, c->sel_cnt, meta, (T*)c->cacheK, (T*)c->cacheV, c->cscore,
+                                                 c->cpos, ccount, c->npad, cf.head_dim, cf.slots_per_seq);
+}
+
+hipError_t launch_gather(d2o_ctx* c, int layer, View K, View V, int n, hipStream_t s, bool append) {
+  const d2o_config& cf = c->cfg;
   int max_budget = 0;
   for (const auto& mt : c->layers[layer].meta) max_budget = std::max(max_budget, std::min(mt.budget, n));
-  if (cf.dtype == D2O_BF16) {
-    const int rows = 256 / (cf.head_dim / 8);
-    gather_kernel<uint16_t><<<dim3((max_budget + rows - 1) / rows, cf.n_kv_heads, cf.batch), 256, 0, s>>>(
-        (const uint16_t*)K.ptr, K, (const uint16_t*)V.ptr, V, score, c->sel_ret, c->sel_cnt, meta,
-        (uint16_t*)c->cacheK, (uint16_t*)c->cacheV, c->cscore, c->cpos, ccount, c->npad, cf.head_dim,
-        cf.slots_per_seq);
-  } else {
-    const int rows = 256 / (cf.head_dim / 4);
-    gather_kernel<float><<<dim3((max_budget + rows - 1) / rows, cf.n_kv_heads, cf.batch), 256, 0, s>>>(
-        (const float*)K.ptr, K, (const float*)V.ptr, V, score, c->sel_ret, c->sel_cnt, meta, (float*)c->cacheK,
-        (float*)c->cacheV, c->cscore, c->cpos, ccount, c->npad, cf.head_dim, cf.slots_per_seq);
-  }
+  if (cf.dtype == D2O_BF16)
+    run_gather<uint16_t>(c, layer, K, V, max_budget, append, s);
+  else
+    run_gather<float>(c, layer, K, V, max_budget, append, s);
   return hipGetLastError();
 }
 
@@ -862,12 +898,12 @@ hipError_t launch_match(d2o_ctx* c, int layer, View K, int n, hipStream_t s) {
   return hipGetLastError();
 }
 
-hipError_t launch_threshold_group(d2o_ctx* c, int layer, int n, hipStream_t s) {
+hipError_t launch_threshold_group(d2o_ctx* c, int layer, int n, hipStream_t s, bool append) {
   const d2o_config& cf = c->cfg;
   double* tau = c->ctau + size_t(layer) * cf.batch * cf.n_kv_heads;
   threshold_group_kernel<<<dim3(cf.n_kv_heads, cf.batch), 1024, 0, s>>>(c->m_ustar, c->m_tgt, c->sel_cnt, c->m_pass,
                                                                         c->g_cnt, c->g_off, c->g_cur, c->g_src, tau,
-                                                                        c->npad, cf.tau_force);
+                                                                        c->npad, cf.tau_force, append ? 1 : 0, cf.beta);
   return hipGetLastError();
 }
 

@@ -113,6 +113,7 @@ def test_bf16_output_storage_adds_only_its_rounding():
     ("bf16-gqa", [150, 333], [37, 83], 2, float("nan")),
     ("bf16-gqa", 96, 96, 0, float("nan")),          # no heavy hitters: sinks + window only
     ("bf16-gqa", 5000, 10, 0, float("nan")),        # budget >= n: nothing evicted
+    ("bf16-gqa", [5000, 150], [10, 37], 0, float("nan")),  # one sequence keeps everything, the other evicts
     ("bf16-mha", 200, 50, 0, float("inf")),         # never merge: pure eviction
     ("bf16-mha", 200, 50, 1, float("-inf")),        # merge everything
 ])
@@ -417,6 +418,105 @@ def test_decode_evicted_token_outside_the_predicted_candidates():
     np.testing.assert_allclose(gs, cache.score, rtol=1e-12)
     assert abs(gtau - cache.tau) < 1e-13
     ctx.close()
+
+
+# ------------------------------------------------------------------ multi-token append
+
+def _block_inputs(w, B, layer, m, seed):
+    """Q [B, Hq, m, d], K, V [B, Hkv, m, d] of a block: the workload's decode-token law."""
+    qs, ks, vs = [], [], []
+    for b in range(B):
+        q, k, v = synth.layer_decode_inputs(w.scaled(cfg=w.cfg), b, layer + 100 * seed, m, "cpu")
+        qs.append(q.transpose(0, 1))
+        ks.append(k.transpose(0, 1))
+        vs.append(v.transpose(0, 1))
+    return (torch.stack(qs).contiguous().cuda(), torch.stack(ks).contiguous().cuda(),
+            torch.stack(vs).contiguous().cuda())
+
+
+def _run_append_parity(w, n, B, layer, budget, recent, sink, blocks, tau_force=float("nan"), decode_between=2):
+    """Prompt compression from given scores, then blocks of new tokens (d2o_append_chunk) with a
+    few single-token steps in between; outputs, events and caches against the oracle after
+    every call."""
+    Q, K, V = H.make_inputs(w, B, layer, n)
+    score32 = np.random.default_rng(n + layer).random((B, w.n_kv_heads, n), dtype=np.float32) * w.group
+    bud = np.broadcast_to(np.asarray(budget), (B,))
+    rec = np.broadcast_to(np.asarray(recent), (B,))
+    ctx = H.new_ctx(w, B, 1, max(n, int(bud.max()) + max(blocks)), int(bud.max()) + max(blocks) + 8, n_sink=sink,
+                    tau_force=tau_force, max_append=max(blocks))
+    ctx.d2o_scores_import(0, score32)
+    ctx.d2o_compress_layer(0, K, V, budget, recent)
+    _, caches = H.check_compress_against_oracle(ctx, 0, K, V, score32, budget, recent, sink, w.dtype, tau_force)
+    G, pos, worst, evicted_total = w.group, n, 0.0, 0
+    dq, dk, dv = H.decode_inputs(w, B, [layer], decode_between * len(blocks) + 1)
+    dqd, dkd, dvd = (binding.tensor_to_f64(t) for t in (dq, dk, dv))
+    dout = torch.empty(dq[0].shape, dtype=ctx.out_dtype, device=dq.device)
+    step = 0
+    for bi, m in enumerate(blocks):
+        Qb, Kb, Vb = _block_inputs(w, B, layer, m, bi + 1)
+        Ob = torch.empty(Qb.shape, dtype=ctx.out_dtype, device=Qb.device)
+        ctx.d2o_append_chunk(0, Qb, Kb, Vb, Ob)
+        torch.cuda.synchronize()
+        qd, kd, vd, od = (binding.tensor_to_f64(t) for t in (Qb, Kb, Vb, Ob))
+        for b in range(B):
+            for h in range(w.n_kv_heads):
+                cache = caches[(b, h)]
+                want, ev = ref.append_chunk_head(cache, qd[b, h * G:(h + 1) * G], kd[b, h], vd[b, h], pos,
+                                                 int(bud[b]), int(rec[b]), sink, w.beta, tau_force)
+                worst = max(worst, H.rownorm_err(od[b, h * G:(h + 1) * G], want))
+                evi, tgt, us, ps = ctx.d2o_append_events(0, b, h, int(bud[b]) + m)
+                assert np.array_equal(evi, ev.evicted), f"block {bi} b={b} h={h}: evicted differ"
+                assert np.array_equal(tgt, ev.target), f"block {bi} b={b} h={h}: targets differ"
+                assert np.array_equal(ps, ev.passed), f"block {bi} b={b} h={h}: flags differ"
+                if len(evi):
+                    assert np.max(np.abs(us - ev.u_star)) < 1e-13
+                evicted_total += len(evi)
+                gK, gV, gs, gp, gtau = ctx.d2o_cache_export(0, b, h, int(bud[b]) + m)
+                assert np.array_equal(gp, cache.pos), f"block {bi} b={b} h={h}: cache positions differ"
+                np.testing.assert_allclose(gs, cache.score, rtol=1e-12)
+                assert np.array_equal(gK, cache.K) and np.array_equal(gV, cache.V)
+                assert (math.isnan(gtau) and math.isnan(cache.tau)) or abs(gtau - cache.tau) < 1e-13
+        pos += m
+        for _ in range(decode_between):      # single-token steps continue on the block's result
+            ctx.d2o_decode_step(0, 1, dq[step], dk[step], dv[step], dout)
+            torch.cuda.synchronize()
+            e_, t_, _ = ctx.d2o_last_events(0)
+            dd = binding.tensor_to_f64(dout)
+            for b in range(B):
+                for h in range(w.n_kv_heads):
+                    want, e = ref.decode_step_head(caches[(b, h)], dqd[step, 0, b, h * G:(h + 1) * G],
+                                                   dkd[step, 0, b, h], dvd[step, 0, b, h], pos, int(bud[b]),
+                                                   int(rec[b]), sink, w.beta, tau_force)
+                    assert (e_[b, h], t_[b, h]) == (e.evicted_pos, e.target_pos), f"step after block {bi}"
+                    worst = max(worst, H.rownorm_err(dd[0, b, h * G:(h + 1) * G], want))
+            pos += 1
+            step += 1
+    assert worst <= H.FLOAT_TOL
+    print(f"  blocks {blocks}: worst out err {worst:.2e}, evicted {evicted_total}", flush=True)
+    ctx.close()
+
+
+@pytest.mark.parametrize("case", ["bf16-gqa", "f32", "bf16-mha-sinks", "bf16-no-window", "bf16-grow",
+                                  "bf16-never-merge", "multi-turn"])
+def test_append_chunk_against_oracle(case):
+    print(f"case={case}", flush=True)
+    if case == "bf16-gqa":          # ragged budgets, blocks of different sizes, a block of one token
+        _run_append_parity(_small_bf16(True), 777, 2, 9, [150, 333], [37, 83], 0, [40, 7, 1, 64])
+    elif case == "f32":
+        _run_append_parity(W1, 512, 1, 0, 128, 64, 0, [16, 50])
+    elif case == "bf16-mha-sinks":
+        _run_append_parity(_small_bf16(False), 1000, 1, 20, 300, 75, 4, [100, 33])
+    elif case == "bf16-no-window":  # M = 0: tokens of the block itself can be evicted
+        _run_append_parity(_small_bf16(False), 300, 1, 31, 40, 0, 0, [12, 30])
+    elif case == "bf16-grow":       # budget above the prompt: the first block fits, the second evicts
+        _run_append_parity(_small_bf16(True), 60, 1, 3, 100, 25, 0, [30, 30])
+    elif case == "bf16-never-merge":
+        _run_append_parity(_small_bf16(False), 500, 1, 12, 100, 25, 0, [20, 20], tau_force=float("inf"))
+    else:
+        # the shape of the multi-turn experiment (appendix): budget 2048 = 48 heavy hitters + 2000
+        # recent tokens, whole turns of a few hundred tokens appended at once
+        w = _small_bf16(False).scaled(n_q_heads=2, n_kv_heads=2)
+        _run_append_parity(w, 2500, 1, 7, 2048, 2000, 0, [300, 120], decode_between=1)
 
 
 # ------------------------------------------------------------------ whole path, free running
