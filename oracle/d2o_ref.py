@@ -200,6 +200,31 @@ def allocate_budgets(F, seq_len: int, total_budget: int, min_budget: int = 64, p
     return S
 
 
+def allocate_budgets_heads(F_heads, group: int, seq_len: int, total_budget: int, min_budget: int = 64):
+    """Per-head allocation of App. A.8: alpha_l^h proportional to exp(-F^{l,h}) with the sum taken
+    over ALL layers and heads, S_l^h = alpha_l^h * S_total (S_total = rho * L * H * S), the
+    layer's proportion being alpha_l = sum_h alpha_l^h.  That is Eq. 5 with one entry per (layer,
+    head) instead of one per layer, so it takes the same bounds and integer rule (the reading
+    documented at allocate_budgets).  F_heads [L, Hq] holds the per-query-head variances; caches
+    are kept per KV head, and under grouped-query attention a KV head's statistic is read as
+    the mean of the variances of the `group` query heads it serves (the paper names the
+    attention types but not this case).  total_budget counts rows over all layers and KV heads.
+    Returns S [L, Hkv]; S.sum(axis=1) are the layer totals."""
+    F = np.asarray(F_heads, dtype=np.float64)
+    L, Hq = F.shape
+    if Hq % group:
+        raise ValueError("query heads must be a multiple of the group size")
+    Hkv = Hq // group
+    Fkv = np.zeros((L, Hkv))
+    for l in range(L):
+        for h in range(Hkv):
+            acc = 0.0
+            for g in range(group):               # ascending head order
+                acc += F[l, h * group + g]
+            Fkv[l, h] = acc / float(group)
+    return allocate_budgets(Fkv.reshape(-1), seq_len, total_budget, min_budget).reshape(L, Hkv)
+
+
 # --------------------------------------------------------------------------- a4: selection
 
 def select(score, budget: int, recent: int, n_sink: int = 0):

@@ -515,6 +515,35 @@ def test_allocation_is_the_clipped_proportional_solution():
         assert np.all(np.abs(S - want) <= 1.0 + 1e-6), (F, tot, S, want)
 
 
+def test_per_head_allocation_is_the_softmax_over_all_layers_and_heads():
+    """App. A.8: S_l^h = S_total * exp(-F^{l,h}) / sum over all (l, h); the layer proportions are the
+    sums over heads and add up to 1; with every head of a layer alike and one KV head per query
+    head the layer totals are those of Eq. 5 scaled by the head count."""
+    from scipy.special import softmax
+    g = np.random.default_rng(31)
+    L, H = 6, 4
+    F = g.uniform(0.0, 2.0, size=(L, H))
+    total = L * H * 300
+    S = ref.allocate_budgets_heads(F, 1, 5000, total, 1)
+    want = softmax(-F.reshape(-1)).reshape(L, H) * total
+    assert S.sum() == total and np.all(np.abs(S - want) < 1.0)
+    alpha_l = softmax(-F.reshape(-1)).reshape(L, H).sum(axis=1)
+    assert abs(alpha_l.sum() - 1.0) < 1e-12 and np.all(np.abs(S.sum(axis=1) - alpha_l * total) < H)
+    # heads of a layer alike: the per-layer form of Eq. 5, H times over
+    Fl = g.uniform(0.0, 2.0, size=L)
+    Sh = ref.allocate_budgets_heads(np.repeat(Fl[:, None], H, axis=1), 1, 5000, total, 1)
+    Sl = ref.allocate_budgets(Fl, 5000, total // H, 1)
+    assert np.all(np.abs(Sh - Sl[:, None]) <= 1)
+    # grouped-query: a KV head's statistic is the mean of its query heads' variances
+    Fq = g.uniform(0.0, 2.0, size=(L, 8))
+    Sg = ref.allocate_budgets_heads(Fq, 4, 5000, L * 2 * 300, 1)
+    assert Sg.shape == (L, 2)
+    assert np.array_equal(Sg, ref.allocate_budgets_heads(Fq.reshape(L, 2, 4).mean(axis=2), 1, 5000, L * 2 * 300, 1))
+    # lower variance, larger cache - across layers AND heads
+    order = np.argsort(Fq.reshape(L, 2, 4).mean(axis=2).reshape(-1))
+    assert np.all(np.diff(Sg.reshape(-1)[order]) <= 0)
+
+
 # ------------------------------------------------------------------ multi-token append
 
 def _random_head_state(n, d, budget, recent, sink, seed, G=2):
