@@ -173,6 +173,22 @@ int d2o_scores_export(d2o_ctx* ctx, int32_t layer, float* scores, int32_t n, voi
 int d2o_compress_layer(d2o_ctx* ctx, int32_t layer, d2o_view K, d2o_view V, int32_t n,
                        const int32_t* budget, const int32_t* recent, void* stream);
 
+/* d2o_compress_layer with a budget and a recent window of its own for every KV head: budget,
+ * recent are host [B][Hkv] (per-head allocation, App. A.8).  Everything else as above. */
+int d2o_compress_layer_heads(d2o_ctx* ctx, int32_t layer, d2o_view K, d2o_view V, int32_t n,
+                             const int32_t* budget, const int32_t* recent, void* stream);
+
+/* Per-head dynamic allocation (App. A.8): alpha_l^h proportional to exp(-F^{l,h}) over ALL
+ * (layer, head) pairs, S_l^h = alpha_l^h * total_budget, the layer's share being the sum over
+ * its heads.  F_heads: host [L][Hq] per-query-head variances (one sequence's slice of what
+ * d2o_get_density returns); a KV head's statistic is the mean over the G query heads it serves;
+ * total_budget counts cache rows per sequence over all layers and KV heads (rho * N * L * Hkv).
+ * Bounds and integer rule as in d2o_allocate_budgets.  S_out: host [L][Hkv].  Pure host
+ * function, fp64.  Errors: INVALID_ARG. */
+int d2o_allocate_budgets_heads(const double* F_heads, int32_t n_layers, int32_t n_q_heads,
+                               int32_t n_kv_heads, int32_t seq_len, int64_t total_budget,
+                               int32_t min_budget, int32_t* S_out);
+
 /* d2o_prefill_attend followed by d2o_compress_layer with caller-chosen budgets. */
 int d2o_prefill_compress(d2o_ctx* ctx, int32_t layer, d2o_view Q, d2o_view K, d2o_view V,
                          int32_t n, d2o_view O, const int32_t* budget, const int32_t* recent,

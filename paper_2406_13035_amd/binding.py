@@ -20,7 +20,7 @@ EXPORTS = [
     "d2o_workspace_bytes", "d2o_create", "d2o_destroy", "d2o_last_error", "d2o_reset",
     "d2o_prefill_attend", "d2o_get_density", "d2o_allocate_budgets", "d2o_allocate_budgets_policy",
     "d2o_scores_import",
-    "d2o_scores_export", "d2o_compress_layer", "d2o_prefill_compress", "d2o_decode_step",
+    "d2o_scores_export", "d2o_compress_layer", "d2o_compress_layer_heads", "d2o_allocate_budgets_heads", "d2o_prefill_compress", "d2o_decode_step",
     "d2o_decode_step_static", "d2o_append_chunk", "d2o_append_events",
     "d2o_layer_reserve", "d2o_cache_export", "d2o_cache_import", "d2o_last_events",
     "d2o_prefill_events", "d2o_timing_enable", "d2o_timing_read",
@@ -72,6 +72,8 @@ def load_library() -> C.CDLL:
     lib.d2o_scores_import.argtypes = [vp, i32, vp, i32, vp]
     lib.d2o_scores_export.argtypes = [vp, i32, vp, i32, vp]
     lib.d2o_compress_layer.argtypes = [vp, i32, d2o_view, d2o_view, i32, vp, vp, vp]
+    lib.d2o_compress_layer_heads.argtypes = [vp, i32, d2o_view, d2o_view, i32, vp, vp, vp]
+    lib.d2o_allocate_budgets_heads.argtypes = [vp, i32, i32, i32, i32, i64, i32, vp]
     lib.d2o_prefill_compress.argtypes = [vp, i32, d2o_view, d2o_view, d2o_view, i32, d2o_view,
                                          vp, vp, vp]
     lib.d2o_decode_step.argtypes = [vp, i32, i32, d2o_view, d2o_view, d2o_view, d2o_view, vp]
@@ -104,6 +106,19 @@ def d2o_allocate_budgets(F, seq_len: int, total_budget: int, min_budget: int = 6
     rc = lib.d2o_allocate_budgets(_np_ptr(F), F.size, seq_len, total_budget, min_budget, _np_ptr(S))
     if rc != 0:
         raise D2OError(f"d2o_allocate_budgets failed with {rc}")
+    return S
+
+
+def d2o_allocate_budgets_heads(F_heads, n_kv_heads: int, seq_len: int, total_budget: int,
+                               min_budget: int = 64) -> np.ndarray:
+    """App. A.8: per-(layer, KV head) budgets from the per-query-head variances [L][Hq] (host function)."""
+    lib = load_library()
+    F = np.ascontiguousarray(F_heads, dtype=np.float64)
+    L, Hq = F.shape
+    S = np.zeros((L, n_kv_heads), dtype=np.int32)
+    rc = lib.d2o_allocate_budgets_heads(_np_ptr(F), L, Hq, n_kv_heads, seq_len, total_budget, min_budget, _np_ptr(S))
+    if rc != 0:
+        raise D2OError(f"d2o_allocate_budgets_heads failed with {rc}")
     return S
 
 
@@ -233,6 +248,15 @@ class D2O:
         self._check(self.lib.d2o_compress_layer(self.ctx, layer, view4(K), view4(V), K.shape[2],
                                                 _np_ptr(b), _np_ptr(r), _stream_ptr()),
                     "d2o_compress_layer")
+
+    def d2o_compress_layer_heads(self, layer, K, V, budget, recent):
+        """budget, recent: [B][Hkv] integer arrays (a cache size and a recent window per KV head)."""
+        shape = (self.cfg.batch, self.cfg.n_kv_heads)
+        b = np.ascontiguousarray(np.broadcast_to(np.asarray(budget, dtype=np.int32), shape))
+        r = np.ascontiguousarray(np.broadcast_to(np.asarray(recent, dtype=np.int32), shape))
+        self._check(self.lib.d2o_compress_layer_heads(self.ctx, layer, view4(K), view4(V), K.shape[2],
+                                                      _np_ptr(b), _np_ptr(r), _stream_ptr()),
+                    "d2o_compress_layer_heads")
 
     def d2o_prefill_compress(self, layer, Q, K, V, budget, recent, O=None):
         b, r = self._budget_arrays(budget, recent)

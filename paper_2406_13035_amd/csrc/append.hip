@@ -17,7 +17,7 @@ namespace {
 constexpr int kRankTile = 4096;  // positions held in LDS at a time
 
 __global__ __launch_bounds__(1024) void rank_by_position(const int32_t* __restrict__ ccount,   // the layer's [B][Hkv]
-                                                         const int32_t* __restrict__ meta,     // the layer's [B][4]
+                                                         const int32_t* __restrict__ meta,     // the layer's [B][Hkv][4]
                                                          const double* __restrict__ cscore,
                                                          const int32_t* __restrict__ cpos, int32_t* __restrict__ rank,
                                                          int32_t* __restrict__ opos, double* __restrict__ oscore,
@@ -26,7 +26,7 @@ __global__ __launch_bounds__(1024) void rank_by_position(const int32_t* __restri
   const int hk = blockIdx.x, b = blockIdx.y, Hkv = gridDim.x, tid = threadIdx.x;
   const int64_t bh = int64_t(b) * Hkv + hk;
   const int n = ccount[bh];
-  const int64_t slot0 = bh * slots + meta[b * 4 + 0];
+  const int64_t slot0 = bh * slots + meta[bh * 4 + 0];
   if (tid == 0) on[bh] = n;
   // every thread owns the slots tid, tid + 1024, ...; the positions pass through LDS tile by tile
   // and each owned slot counts the smaller ones (all threads read the same LDS word at a time)
@@ -73,7 +73,7 @@ __global__ __launch_bounds__(256) void permute_rows(const int32_t* __restrict__ 
   const int j = blockIdx.x * rows_per_blk + threadIdx.x / tpr;
   if (j >= on[bh]) return;
   const int c = (threadIdx.x % tpr) * kVec;
-  const int64_t src = (bh * slots + meta[b * 4 + 0] + j) * d + c;
+  const int64_t src = (bh * slots + meta[bh * 4 + 0] + j) * d + c;
   const int64_t dst = (bh * npad + rank[bh * npad + j]) * d + c;
   *reinterpret_cast<u32x4*>(oK + dst) = *reinterpret_cast<const u32x4*>(cK + src);
   *reinterpret_cast<u32x4*>(oV + dst) = *reinterpret_cast<const u32x4*>(cV + src);
@@ -83,7 +83,7 @@ __global__ __launch_bounds__(256) void permute_rows(const int32_t* __restrict__ 
 
 hipError_t launch_cache_sort(d2o_ctx* c, int layer, hipStream_t s) {
   const d2o_config& cf = c->cfg;
-  const int32_t* meta = c->meta + size_t(layer) * cf.batch * 4;
+  const int32_t* meta = c->meta + size_t(layer) * cf.batch * cf.n_kv_heads * 4;
   const int32_t* ccount = c->ccount + size_t(layer) * cf.batch * cf.n_kv_heads;
   int max_rows = 0;
   for (const auto& mt : c->layers[layer].meta) max_rows = std::max(max_rows, mt.budget + c->grow);

@@ -71,7 +71,7 @@ void layout(d2o_ctx* x, char* persistent, char* scratch, size_t* pbytes, size_t*
   p.take(x->ccount, L * B * Hkv);
   p.take(x->ctotal, L * B * Hkv);
   p.take(x->ctau, L * B * Hkv);
-  p.take(x->meta, L * B * 4);
+  p.take(x->meta, L * B * Hkv * 4);
   p.take(x->ev_evicted, L * B * Hkv);
   p.take(x->ev_target, L * B * Hkv);
   p.take(x->ev_ustar, L * B * Hkv);
@@ -134,11 +134,19 @@ bool view_ok(const d2o_ctx* x, const d2o_view& v, int esize = 0) {
   return v.stride_b % al == 0 && v.stride_h % al == 0 && v.stride_n % al == 0 && v.stride_n >= 0;
 }
 
-int reserve_layer(d2o_ctx* x, int32_t layer, int32_t n, const int32_t* budget, const int32_t* recent) {
+// budget, recent: [B][Hkv] when per_head, else [B] (every KV head of a sequence alike)
+int reserve_layer(d2o_ctx* x, int32_t layer, int32_t n, const int32_t* budget_in, const int32_t* recent_in,
+                  bool per_head = false) {
   const d2o_config& c = x->cfg;
   LayerState& st = x->layers[layer];
-  std::vector<LayerMeta> meta(c.batch);
-  for (int b = 0; b < c.batch; ++b) {
+  const int nbh = c.batch * c.n_kv_heads;
+  std::vector<LayerMeta> meta(nbh);
+  std::vector<int32_t> budget(nbh), recent(nbh);
+  for (int i = 0; i < nbh; ++i) {
+    budget[i] = budget_in[per_head ? i : i / c.n_kv_heads];
+    recent[i] = recent_in[per_head ? i : i / c.n_kv_heads];
+  }
+  for (int b = 0; b < nbh; ++b) {
     if (budget[b] < 1 || recent[b] < 0 || budget[b] < c.n_sink + recent[b])
       return fail(x, D2O_ERR_INVALID_ARG, "budget must be >= 1 and >= n_sink + recent");
     if (n < c.n_sink) return fail(x, D2O_ERR_INVALID_ARG, "prompt shorter than the sink tokens");
@@ -152,7 +160,7 @@ int reserve_layer(d2o_ctx* x, int32_t layer, int32_t n, const int32_t* budget, c
     meta[b].recent = recent[b];
     meta[b].chunk_base = int32_t(x->used_chunks[b]);
   }
-  for (int b = 0; b < c.batch; ++b) {
+  for (int b = 0; b < nbh; ++b) {
     x->used_slots[b] += int64_t(budget[b]) + x->grow;
     x->used_chunks[b] += (int64_t(budget[b]) + x->grow + kChunk - 1) / kChunk;
   }
@@ -191,7 +199,7 @@ __global__ void write_meta_kernel(int32_t* dst, MetaPack m, int n_words) {
 
 hipError_t launch_write_meta(d2o_ctx* x, int layer, hipStream_t s) {
   const LayerState& st = x->layers[layer];
-  const int B = x->cfg.batch;
+  const int B = x->cfg.batch * x->cfg.n_kv_heads;  // one entry per (sequence, KV head)
   for (int b0 = 0; b0 < B; b0 += kMetaPerLaunch) {
     const int nb = std::min(kMetaPerLaunch, B - b0);
     MetaPack m;
@@ -243,8 +251,8 @@ int d2o_create(const d2o_config* cfg, void* persistent_dev, size_t persistent_by
     return D2O_ERR_CAPACITY;
   }
   x->layers.assign(cfg->n_layers, LayerState{});
-  x->used_slots.assign(cfg->batch, 0);
-  x->used_chunks.assign(cfg->batch, 0);
+  x->used_slots.assign(size_t(cfg->batch) * cfg->n_kv_heads, 0);
+  x->used_chunks.assign(size_t(cfg->batch) * cfg->n_kv_heads, 0);
   rc = d2o_reset(x, stream);
   if (rc) {
     delete x;
@@ -283,7 +291,7 @@ int d2o_reset(d2o_ctx* x, void* stream) {
   D2O_HIP_CHECK(x, fill32(x->ccount, 0u, sizeof(int32_t) * lbh, s));
   D2O_HIP_CHECK(x, fill32(x->ctotal, 0u, sizeof(int32_t) * lbh, s));
   D2O_HIP_CHECK(x, fill32(x->ctau, 0xFFFFFFFFu, sizeof(double) * lbh, s));
-  D2O_HIP_CHECK(x, fill32(x->meta, 0u, sizeof(int32_t) * 4 * c.n_layers * c.batch, s));
+  D2O_HIP_CHECK(x, fill32(x->meta, 0u, sizeof(int32_t) * 4 * lbh, s));
   D2O_HIP_CHECK(x, fill32(x->ev_evicted, 0xFFFFFFFFu, sizeof(int32_t) * lbh, s));
   D2O_HIP_CHECK(x, fill32(x->ev_target, 0xFFFFFFFFu, sizeof(int32_t) * lbh, s));
   D2O_HIP_CHECK(x, fill32(x->ev_ustar, 0xFFFFFFFFu, sizeof(double) * lbh, s));
@@ -482,8 +490,8 @@ int d2o_layer_reserve(d2o_ctx* x, int32_t layer, int32_t n, const int32_t* budge
   return D2O_OK;
 }
 
-int d2o_compress_layer(d2o_ctx* x, int32_t layer, d2o_view K, d2o_view V, int32_t n,
-                       const int32_t* budget, const int32_t* recent, void* stream) {
+static int compress_layer_impl(d2o_ctx* x, int32_t layer, d2o_view K, d2o_view V, int32_t n,
+                               const int32_t* budget, const int32_t* recent, bool per_head, void* stream) {
   if (!x || !budget || !recent) return D2O_ERR_INVALID_ARG;
   const d2o_config& c = x->cfg;
   if (layer < 0 || layer >= c.n_layers) return fail(x, D2O_ERR_INVALID_ARG, "layer out of range");
@@ -493,7 +501,7 @@ int d2o_compress_layer(d2o_ctx* x, int32_t layer, d2o_view K, d2o_view V, int32_
   if (n != st.n) return fail(x, D2O_ERR_INVALID_ARG, "n differs from the attention call");
   if (!view_ok(x, K) || !view_ok(x, V) || K.stride_n < c.head_dim || V.stride_n < c.head_dim)
     return fail(x, D2O_ERR_INVALID_ARG, "null, misaligned or badly strided tensor view");
-  int rc = reserve_layer(x, layer, n, budget, recent);
+  int rc = reserve_layer(x, layer, n, budget, recent, per_head);
   if (rc) return rc;
   hipStream_t s = static_cast<hipStream_t>(stream);
   hipError_t e;
@@ -508,6 +516,32 @@ int d2o_compress_layer(d2o_ctx* x, int32_t layer, d2o_view K, d2o_view V, int32_
   st.phase = kReady;
   x->last_compress_layer = layer;
   return D2O_OK;
+}
+
+int d2o_compress_layer(d2o_ctx* x, int32_t layer, d2o_view K, d2o_view V, int32_t n, const int32_t* budget,
+                       const int32_t* recent, void* stream) {
+  return compress_layer_impl(x, layer, K, V, n, budget, recent, false, stream);
+}
+
+int d2o_compress_layer_heads(d2o_ctx* x, int32_t layer, d2o_view K, d2o_view V, int32_t n, const int32_t* budget,
+                             const int32_t* recent, void* stream) {
+  return compress_layer_impl(x, layer, K, V, n, budget, recent, true, stream);
+}
+
+// App. A.8: Eq. 5 over all (layer, KV head) pairs; a KV head's statistic is the mean of the
+// variances of the query heads it serves.
+int d2o_allocate_budgets_heads(const double* F_heads, int32_t L, int32_t Hq, int32_t Hkv, int32_t seq_len,
+                               int64_t total, int32_t min_budget, int32_t* S_out) {
+  if (!F_heads || !S_out || L < 1 || Hq < 1 || Hkv < 1 || Hq % Hkv) return D2O_ERR_INVALID_ARG;
+  const int G = Hq / Hkv;
+  std::vector<double> F(size_t(L) * Hkv);
+  for (int l = 0; l < L; ++l)
+    for (int h = 0; h < Hkv; ++h) {
+      double sum = 0.0;
+      for (int g = 0; g < G; ++g) sum += F_heads[size_t(l) * Hq + h * G + g];  // ascending head order
+      F[size_t(l) * Hkv + h] = sum / double(G);
+    }
+  return d2o_allocate_budgets_policy(D2O_ALLOC_SOFTMAX, F.data(), L * Hkv, seq_len, total, min_budget, S_out);
 }
 
 int d2o_prefill_compress(d2o_ctx* x, int32_t layer, d2o_view Q, d2o_view K, d2o_view V, int32_t n,
@@ -632,7 +666,7 @@ int d2o_cache_export(d2o_ctx* x, int32_t layer, int32_t b, int32_t h, void* K, v
   if (count) *count = cnt;
   if (tau) *tau = t;
   if (cnt <= 0) return D2O_OK;
-  const size_t slot0 = (size_t(b) * c.n_kv_heads + h) * c.slots_per_seq + st.meta[b].base;
+  const size_t slot0 = (size_t(b) * c.n_kv_heads + h) * c.slots_per_seq + st.meta[size_t(b) * c.n_kv_heads + h].base;
   const size_t row = size_t(c.head_dim) * x->esize;
   std::vector<char> k(cnt * row), v(cnt * row);
   std::vector<double> sc(cnt);
@@ -664,10 +698,10 @@ int d2o_cache_import(d2o_ctx* x, int32_t layer, int32_t b, int32_t h, const void
   const d2o_config& c = x->cfg;
   LayerState& st = x->layers[layer];
   if (st.phase != kReady) return fail(x, D2O_ERR_STATE, "layer not reserved");
-  if (count < 0 || count > st.meta[b].budget) return fail(x, D2O_ERR_INVALID_ARG, "count exceeds the budget");
+  if (count < 0 || count > st.meta[size_t(b) * c.n_kv_heads + h].budget) return fail(x, D2O_ERR_INVALID_ARG, "count exceeds the budget");
   hipStream_t s = static_cast<hipStream_t>(stream);
   const size_t lbh = (size_t(layer) * c.batch + b) * c.n_kv_heads + h;
-  const size_t slot0 = (size_t(b) * c.n_kv_heads + h) * c.slots_per_seq + st.meta[b].base;
+  const size_t slot0 = (size_t(b) * c.n_kv_heads + h) * c.slots_per_seq + st.meta[size_t(b) * c.n_kv_heads + h].base;
   const size_t row = size_t(c.head_dim) * x->esize;
   D2O_HIP_CHECK(x, hipMemcpyAsync(static_cast<char*>(x->cacheK) + slot0 * row, K, count * row, hipMemcpyHostToDevice, s));
   D2O_HIP_CHECK(x, hipMemcpyAsync(static_cast<char*>(x->cacheV) + slot0 * row, V, count * row, hipMemcpyHostToDevice, s));

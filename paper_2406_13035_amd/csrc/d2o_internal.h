@@ -22,7 +22,7 @@ struct View {
 
 inline View to_view(const d2o_view& v) { return View{v.ptr, v.stride_b, v.stride_h, v.stride_n}; }
 
-// Per-(layer, sequence) cache geometry, mirrored on the device as int32[4].
+// Per-(layer, sequence, KV head) cache geometry, mirrored on the device as int32[4].
 struct LayerMeta {
   int32_t base;        // first slot of this layer's region inside a (sequence, KV head) cache
   int32_t budget;      // S_l
@@ -36,7 +36,7 @@ struct LayerState {
   int phase = kEmpty;
   int32_t n = 0;          // prompt length seen by the prefill calls
   int32_t next_pos = 0;   // position of the next generated token
-  std::vector<LayerMeta> meta;  // [B]
+  std::vector<LayerMeta> meta;  // [B][Hkv]
 };
 
 }  // namespace d2o
@@ -53,8 +53,8 @@ struct d2o_ctx {
   int64_t launch_no[D2O_K_COUNT] = {};
   std::vector<d2o_timed_launch> timed;
   std::vector<d2o::LayerState> layers;
-  std::vector<int64_t> used_slots;   // [B]
-  std::vector<int64_t> used_chunks;  // [B]
+  std::vector<int64_t> used_slots;   // [B][Hkv]
+  std::vector<int64_t> used_chunks;  // [B][Hkv]
   int32_t last_compress_layer = -1;
   int32_t last_append_layer = -1;
   int32_t grow = 1;                  // rows a layer's cache region holds beyond its budget: max(1, max_append)
@@ -73,7 +73,7 @@ struct d2o_ctx {
   int32_t* ccount = nullptr;     // [L][B][Hkv]
   int32_t* ctotal = nullptr;     // [L][B][Hkv] entries of the running decode step (count + 1), fixed for the whole step
   double* ctau = nullptr;        // [L][B][Hkv]
-  int32_t* meta = nullptr;       // [L][B][4]
+  int32_t* meta = nullptr;       // [L][B][Hkv][4]
   int32_t* ev_evicted = nullptr; // [L][B][Hkv]
   int32_t* ev_target = nullptr;  // [L][B][Hkv]
   double* ev_ustar = nullptr;    // [L][B][Hkv]

@@ -83,7 +83,7 @@ __global__ __launch_bounds__(128) void decode_prepare(DecodeArgs a, const T* __r
   const int li = blockIdx.y, l = a.layer0 + li, b = blockIdx.x / a.Hkv, hk = blockIdx.x % a.Hkv;
   const int64_t lbh = (int64_t(l) * a.B + b) * a.Hkv + hk;
   const int count = a.ccount[lbh];
-  const int64_t slot0 = (int64_t(b) * a.Hkv + hk) * a.slots + a.meta[(l * a.B + b) * 4 + 0];
+  const int64_t slot0 = (int64_t(b) * a.Hkv + hk) * a.slots + a.meta[lbh * 4 + 0];
   const int c = threadIdx.x;
   T* Kc = static_cast<T*>(a.cK) + slot0 * D;
   T* Vc = static_cast<T*>(a.cV) + slot0 * D;
@@ -139,7 +139,7 @@ __device__ __forceinline__ void head_tail(const DecodeArgs& a, OT* __restrict__ 
   constexpr int PB = 4;                               // partial rows in flight per thread
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const int l = a.layer0 + li, last = total - 1;
-  const int32_t* mt = a.meta + (l * a.B + b) * 4;
+  const int32_t* mt = a.meta + lbh * 4;
   const int64_t bh = int64_t(b) * a.Hkv + hk;
   const int64_t slot0 = bh * a.slots + mt[0];
   const int ch0 = mt[3];  // the layer's first chunk in the partial-result arrays
@@ -481,7 +481,7 @@ __global__ __launch_bounds__(256) void decode_attend(DecodeArgs a, OT* __restric
   // sub-chunk offsets, the candidates.  The kernel that wrote them has completed.
   typedef const int32_t __attribute__((address_space(4))) * ciptr;
   typedef const double __attribute__((address_space(4))) * cptr;
-  const ciptr mt = (ciptr)a.meta + (l * a.B + b) * 4;
+  const ciptr mt = (ciptr)a.meta + lbh * 4;
   const int total = ((ciptr)a.ctotal)[lbh];  // the new token has been appended; constant during this launch
   const int mt0 = mt[0], mt3 = mt[3];
   int cs[kCand];
@@ -786,7 +786,7 @@ int decode_candidates() { return kCand; }
 // A prediction like the one every step makes for the next: a miss costs that step's closing
 // workgroup a second pass over the keys and nothing else.
 __global__ __launch_bounds__(256) void init_candidates(const int32_t* __restrict__ ccount,
-                                                       const int32_t* __restrict__ meta,  // the layer's [B][4]
+                                                       const int32_t* __restrict__ meta,  // the layer's [B][Hkv][4]
                                                        const double* __restrict__ cscore,
                                                        const int32_t* __restrict__ cpos, int32_t* __restrict__ cand,
                                                        int layer, int B, int Hkv, int64_t slots, int new_pos,
@@ -795,8 +795,8 @@ __global__ __launch_bounds__(256) void init_candidates(const int32_t* __restrict
   __shared__ int ired[8];
   const int hk = blockIdx.x, b = blockIdx.y, tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const int64_t lbh = (int64_t(layer) * B + b) * Hkv + hk;
-  const int total = ccount[lbh], recent = meta[b * 4 + 2];
-  const int64_t slot0 = (int64_t(b) * Hkv + hk) * slots + meta[b * 4 + 0];
+  const int total = ccount[lbh], recent = meta[(b * Hkv + hk) * 4 + 2];
+  const int64_t slot0 = (int64_t(b) * Hkv + hk) * slots + meta[(b * Hkv + hk) * 4 + 0];
   Best low[kCand + 1];
 #pragma unroll
   for (int i = 0; i <= kCand; ++i) low[i] = Best{0.0, 0, -1};
@@ -838,7 +838,7 @@ __global__ __launch_bounds__(256) void init_candidates(const int32_t* __restrict
 
 hipError_t launch_init_candidates(d2o_ctx* c, int layer, int new_pos, hipStream_t s) {
   const d2o_config& cf = c->cfg;
-  init_candidates<<<dim3(cf.n_kv_heads, cf.batch), 256, 0, s>>>(c->ccount, c->meta + size_t(layer) * cf.batch * 4,
+  init_candidates<<<dim3(cf.n_kv_heads, cf.batch), 256, 0, s>>>(c->ccount, c->meta + size_t(layer) * cf.batch * cf.n_kv_heads * 4,
                                                                 c->cscore, c->cpos, c->ccand, layer, cf.batch,
                                                                 cf.n_kv_heads, cf.slots_per_seq, new_pos, cf.n_sink);
   return hipGetLastError();

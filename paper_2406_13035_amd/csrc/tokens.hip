@@ -76,7 +76,7 @@ __global__ __launch_bounds__(1024) void select_kernel(const S* __restrict__ scor
   const S* sc = score + bh * npad;
   int32_t* r = ret + bh * npad;
   int32_t* e = evi + bh * npad;
-  const int budget = meta[b * 4 + 1], recent = meta[b * 4 + 2];
+  const int budget = meta[bh * 4 + 1], recent = meta[bh * 4 + 2];
   const int tid = threadIdx.x;
   if (budget >= n) {
     for (int j = tid; j < n; j += blockDim.x) r[j] = j;
@@ -173,7 +173,7 @@ __global__ __launch_bounds__(256) void gather_kernel(const T* __restrict__ K, Vi
   if (slot >= nret) return;
   const int c = (threadIdx.x % tpr) * kVec;
   const int pos = ret[bh * npad + slot];
-  const int64_t dst = (bh * slots + meta[b * 4 + 0] + slot);
+  const int64_t dst = (bh * slots + meta[bh * 4 + 0] + slot);
   *reinterpret_cast<u32x4*>(cK + dst * d + c) =
       *reinterpret_cast<const u32x4*>(K + b * kv.sb + hk * kv.sh + int64_t(pos) * kv.sn + c);
   *reinterpret_cast<u32x4*>(cV + dst * d + c) =
@@ -256,7 +256,7 @@ __global__ __launch_bounds__(256) void match_filter_bf16(const uint16_t* __restr
   const uint16_t* kb = K + b * kv.sb + hk * kv.sh;
   // the retained keys, in retained order, already sit contiguously in the layer's cache
   // region (compaction runs first; merging, which changes them, runs after the matching)
-  const uint16_t* rk = cK + (bh * slots + meta[b * 4 + 0]) * 128;
+  const uint16_t* rk = cK + (bh * slots + meta[bh * 4 + 0]) * 128;
   const int32_t* rl = ret + bh * npad;
   const int32_t* el = evi + bh * npad;
   const float* inl = invn + bh * npad;
@@ -714,7 +714,7 @@ __global__ __launch_bounds__(256) void merge_kernel(const T* __restrict__ K, Vie
   const T* kb = K + b * kv.sb + hk * kv.sh;
   const T* vb = V + b * vv.sb + hk * vv.sh;
   constexpr int PER = D / 64;
-  const int64_t dst = (bh * slots + meta[b * 4 + 0] + slot) * D + lane * PER;
+  const int64_t dst = (bh * slots + meta[bh * 4 + 0] + slot) * D + lane * PER;
   // exp(1), the retained token's self-similarity weight; average merging weighs every member 1
   const double e1 = AVERAGE ? 1.0 : 2.718281828459045;
   auto weight = [&](double u) __attribute__((always_inline)) { return AVERAGE ? 1.0 : exp(u); };
@@ -811,7 +811,7 @@ __global__ __launch_bounds__(256) void merge_kernel(const T* __restrict__ K, Vie
 hipError_t launch_select(d2o_ctx* c, int layer, int n, hipStream_t s, bool append) {
   const d2o_config& cf = c->cfg;
   const float* score = c->score_pre + size_t(layer) * cf.batch * cf.n_kv_heads * c->npad;
-  const int32_t* meta = c->meta + size_t(layer) * cf.batch * 4;
+  const int32_t* meta = c->meta + size_t(layer) * cf.batch * cf.n_kv_heads * 4;
   KernelTimer kt(c, D2O_K_SELECT, s);
   if (append)
     select_kernel<double><<<dim3(cf.n_kv_heads, cf.batch), 1024, 0, s>>>(c->app_score, meta, c->sel_ret, c->sel_evi,
@@ -826,7 +826,7 @@ template <typename T>
 static void run_gather(d2o_ctx* c, int layer, View K, View V, int max_budget, bool append, hipStream_t s) {
   const d2o_config& cf = c->cfg;
   const float* score = c->score_pre + size_t(layer) * cf.batch * cf.n_kv_heads * c->npad;
-  const int32_t* meta = c->meta + size_t(layer) * cf.batch * 4;
+  const int32_t* meta = c->meta + size_t(layer) * cf.batch * cf.n_kv_heads * 4;
   int32_t* ccount = c->ccount + size_t(layer) * cf.batch * cf.n_kv_heads;
   const int rows = 256 / (cf.head_dim * int(sizeof(T)) / 16);
   const dim3 grid((max_budget + rows - 1) / rows, cf.n_kv_heads, cf.batch);
@@ -870,7 +870,7 @@ hipError_t launch_match(d2o_ctx* c, int layer, View K, int n, hipStream_t s) {
     {
       KernelTimer kt(c, D2O_K_MATCH_FILTER, s);
       match_filter_bf16<false><<<gf, 256, 0, s>>>((const uint16_t*)K.ptr, K, (const uint16_t*)c->cacheK,
-                                                  c->meta + size_t(layer) * cf.batch * 4, cf.slots_per_seq,
+                                                  c->meta + size_t(layer) * cf.batch * cf.n_kv_heads * 4, cf.slots_per_seq,
                                                   c->invnorm, c->sel_ret, c->sel_evi,
                                                   c->sel_cnt, c->m_cand, c->m_thr, c->amb_list, c->amb_cnt,
                                                   c->m_ncand, c->m_clist, c->npad, 1);
@@ -878,7 +878,7 @@ hipError_t launch_match(d2o_ctx* c, int layer, View K, int n, hipStream_t s) {
                                                                         c->amb_cnt, c->m_ncand, c->npad);
       constexpr int kSplit = 8;
       match_filter_bf16<true><<<dim3(gf.x * kSplit, gf.y, gf.z), 256, 0, s>>>((const uint16_t*)K.ptr, K, (const uint16_t*)c->cacheK,
-                                                 c->meta + size_t(layer) * cf.batch * 4, cf.slots_per_seq,
+                                                 c->meta + size_t(layer) * cf.batch * cf.n_kv_heads * 4, cf.slots_per_seq,
                                                  c->invnorm, c->sel_ret, c->sel_evi,
                                                  c->sel_cnt, c->m_cand, c->m_thr, c->amb_list, c->amb_cnt,
                                                  c->m_ncand, c->m_clist, c->npad, kSplit);
@@ -926,7 +926,7 @@ hipError_t launch_merge(d2o_ctx* c, int layer, View K, View V, int n, hipStream_
   if (max_evicted(c, layer, n) == 0) return hipSuccess;
   int max_budget = 0;
   for (const auto& mt : c->layers[layer].meta) max_budget = std::max(max_budget, std::min(mt.budget, n));
-  const int32_t* meta = c->meta + size_t(layer) * cf.batch * 4;
+  const int32_t* meta = c->meta + size_t(layer) * cf.batch * cf.n_kv_heads * 4;
   KernelTimer kt(c, D2O_K_MERGE, s);
   if (cf.dtype == D2O_BF16)
     run_merge<uint16_t, 128>(c, meta, K, V, max_budget, s);

@@ -103,3 +103,18 @@ def test_benchmark_allocations_have_the_stated_totals(lib):
         S = binding.d2o_allocate_budgets(F, w.prompt_len, w.total_budget(), 64)
         assert S.sum() == w.total_budget() and S.min() >= 64 and S.max() <= w.prompt_len
         assert np.all(np.diff(S) <= 0)
+
+
+def test_allocate_budgets_heads_matches_oracle_bit_for_bit(lib):
+    g = np.random.default_rng(77)
+    for trial in range(100):
+        L, Hkv = int(g.integers(1, 12)), int(g.choice([1, 2, 4, 8]))
+        G = int(g.choice([1, 2, 4]))
+        F = g.uniform(0, 1, size=(L, Hkv * G)) * g.choice([0.1, 1.0, 30.0, 2000.0])
+        n = int(g.choice([512, 4096, 32768]))
+        lo = int(g.choice([0, 1, 64]))
+        tot = int(g.integers(L * Hkv * lo, L * Hkv * n + 1))
+        want = ref.allocate_budgets_heads(F, G, n, tot, lo)
+        got = binding.d2o_allocate_budgets_heads(F, Hkv, n, tot, lo)
+        assert np.array_equal(got, want), (trial, L, Hkv, G)
+        assert int(got.sum()) == tot

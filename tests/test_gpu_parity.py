@@ -519,6 +519,92 @@ def test_append_chunk_against_oracle(case):
         _run_append_parity(w, 2500, 1, 7, 2048, 2000, 0, [300, 120], decode_between=1)
 
 
+# ------------------------------------------------------------------ per-head allocation, ragged per-head caches
+
+def test_per_head_budgets_ragged_caches_prefill_decode_and_append():
+    """App. A.8 end to end on two layers: per-head variances from the library's attention pass,
+    per-(layer, KV head) budgets from d2o_allocate_budgets_heads (equal to the oracle's on the
+    same variances), d2o_compress_layer_heads with those budgets (every KV head its own cache
+    size and recent window), then generation steps over both layers in one call and a block of
+    tokens on each layer: every head against the oracle run with that head's budget."""
+    w = _small_bf16(True).scaled(n_layers=2)            # 4 query heads, 2 KV heads
+    n, B, L, G = 900, 2, 2, 2
+    total = int(0.2 * n * L * w.n_kv_heads)
+    data = [H.make_inputs(w, B, l, n) for l in range(L)]
+    probe = H.new_ctx(w, B, L, n, 8)                      # a first context only measures the densities
+    for l in range(L):
+        probe.d2o_prefill_attend(l, *data[l], None)
+    _, Fh = probe.d2o_get_density(heads=True)            # [B, L, Hq]
+    probe.close()
+    S = np.stack([binding.d2o_allocate_budgets_heads(Fh[b], w.n_kv_heads, n, total, 32) for b in range(B)])
+    for b in range(B):
+        assert np.array_equal(S[b], ref.allocate_budgets_heads(Fh[b], G, n, total, 32)) and int(S[b].sum()) == total
+    assert len(set(S.reshape(-1).tolist())) > 4, S      # really ragged
+    print(f"  per-head budgets [b][layer][kv head]: {S.tolist()}", flush=True)
+    m = 24
+    ctx = H.new_ctx(w, B, L, n, int(S.sum(axis=1).max()) + L * (m + 8), max_append=m)
+    caches = {}
+    for l in range(L):
+        Q, K, V = data[l]
+        bud = S[:, l, :]                                 # [B, Hkv]
+        rec = bud // 4
+        score32 = np.random.default_rng(l).random((B, w.n_kv_heads, n), dtype=np.float32) * G
+        ctx.d2o_scores_import(l, score32)
+        ctx.d2o_compress_layer_heads(l, K, V, bud, rec)
+        torch.cuda.synchronize()
+        Kd, Vd = binding.tensor_to_f64(K), binding.tensor_to_f64(V)
+        for b in range(B):
+            for h in range(w.n_kv_heads):
+                cache, ev = ref.compress_head(Kd[b, h], Vd[b, h], score32[b, h].astype(np.float64), int(bud[b, h]),
+                                              int(rec[b, h]), 0, w.dtype)
+                ret, evi, tgt, us, ps = ctx.d2o_prefill_events(l, b, h, n)
+                assert np.array_equal(ret, ev.retained) and np.array_equal(tgt, ev.target)
+                assert np.array_equal(ps, ev.passed) and len(ret) == int(bud[b, h])
+                gK, gV, gs, gp, gtau = ctx.d2o_cache_export(l, b, h, int(bud[b, h]) + 1)
+                assert np.array_equal(gp, cache.pos) and np.array_equal(gK, cache.K) and np.array_equal(gV, cache.V)
+                caches[(l, b, h)] = cache
+    steps = 5
+    q, k, v = H.decode_inputs(w, B, list(range(L)), steps)
+    qd, kd, vd = (binding.tensor_to_f64(t) for t in (q, k, v))
+    out = torch.empty(q[0].shape, dtype=ctx.out_dtype, device=q.device)
+    worst, pos = 0.0, n
+    for t in range(steps):
+        ctx.d2o_decode_step(0, L, q[t], k[t], v[t], out)
+        torch.cuda.synchronize()
+        od = binding.tensor_to_f64(out)
+        for l in range(L):
+            e_, t_, _ = ctx.d2o_last_events(l)
+            for b in range(B):
+                for h in range(w.n_kv_heads):
+                    bud = int(S[b, l, h])
+                    want, e = ref.decode_step_head(caches[(l, b, h)], qd[t, l, b, h * G:(h + 1) * G], kd[t, l, b, h],
+                                                   vd[t, l, b, h], pos, bud, bud // 4, 0, w.beta)
+                    assert (e_[b, h], t_[b, h]) == (e.evicted_pos, e.target_pos), f"step {t} l={l} b={b} h={h}"
+                    worst = max(worst, H.rownorm_err(od[l, b, h * G:(h + 1) * G], want))
+        pos += 1
+    for l in range(L):
+        Qb, Kb, Vb = _block_inputs(w, B, l, m, 3)
+        Ob = torch.empty(Qb.shape, dtype=ctx.out_dtype, device=Qb.device)
+        ctx.d2o_append_chunk(l, Qb, Kb, Vb, Ob)
+        torch.cuda.synchronize()
+        bq, bk, bv, bo = (binding.tensor_to_f64(x) for x in (Qb, Kb, Vb, Ob))
+        for b in range(B):
+            for h in range(w.n_kv_heads):
+                bud = int(S[b, l, h])
+                want, ev = ref.append_chunk_head(caches[(l, b, h)], bq[b, h * G:(h + 1) * G], bk[b, h], bv[b, h], pos,
+                                                 bud, bud // 4, 0, w.beta)
+                worst = max(worst, H.rownorm_err(bo[b, h * G:(h + 1) * G], want))
+                evi, tgt, us, ps = ctx.d2o_append_events(l, b, h, bud + m)
+                assert np.array_equal(evi, ev.evicted) and np.array_equal(tgt, ev.target) and np.array_equal(ps, ev.passed)
+                gK, gV, gs, gp, gtau = ctx.d2o_cache_export(l, b, h, bud + m)
+                cache = caches[(l, b, h)]
+                assert np.array_equal(gp, cache.pos) and np.array_equal(gK, cache.K) and np.array_equal(gV, cache.V)
+                np.testing.assert_allclose(gs, cache.score, rtol=1e-12)
+    assert worst <= H.FLOAT_TOL
+    print(f"  worst output err {worst:.2e}", flush=True)
+    ctx.close()
+
+
 # ------------------------------------------------------------------ whole path, free running
 
 def test_cfg1_end_to_end_free_running():
