@@ -51,6 +51,46 @@ def round_storage(x: np.ndarray, dtype: str) -> np.ndarray:
     raise ValueError(dtype)
 
 
+# --------------------------------------------------------------------------- upstream: Q, K, V from the hidden states
+
+def rope_rotate(x, positions, base: float = 10000.0):
+    """Rotary position embedding on vectors x [..., n, d] at integer positions [n] (the models the
+    paper evaluates - Llama, Mistral - apply it to queries and keys before Eq. 3; the paper
+    itself does not print it).  Half-split convention of those models: element i < d/2 is paired
+    with element i + d/2, and the pair is rotated by the angle pos * base^(-2i/d):
+      y_i = x_i cos - x_{i+d/2} sin,   y_{i+d/2} = x_{i+d/2} cos + x_i sin."""
+    x = np.asarray(x, dtype=np.float64)
+    d = x.shape[-1]
+    half = d // 2
+    inv_freq = base ** (-(2.0 * np.arange(half)) / float(d))
+    ang = np.asarray(positions, dtype=np.float64)[:, None] * inv_freq[None, :]      # [n, d/2]
+    c, s_ = np.cos(ang), np.sin(ang)
+    a, b = x[..., :half], x[..., half:]
+    return np.concatenate([a * c - b * s_, b * c + a * s_], axis=-1)
+
+
+def qkv_project(X, W, n_q_heads: int, n_kv_heads: int, head_dim: int, pos0: int = 0, base: float = 10000.0,
+                storage: str = "f64"):
+    """Sec. 3 Eq. 1 for one layer: Q = X W_Q, K = X W_K, V = X W_V from the hidden states X
+    [n, hidden], with the three weight matrices stacked as the rows of W [(Hq + 2 Hkv) d, hidden]
+    (queries first, then keys, then values; a row of W is one output feature), rotary embedding
+    (rope_rotate) on queries and keys at positions pos0 .. pos0 + n - 1, values left as they are.
+    Results are rounded to `storage` once, at the end (the tensors handed to the attention of
+    Eq. 3 are stored in the model's dtype).  Returns Q [Hq, n, d], K [Hkv, n, d], V [Hkv, n, d]."""
+    X = np.asarray(X, dtype=np.float64)
+    W = np.asarray(W, dtype=np.float64)
+    n = X.shape[0]
+    Y = X @ W.T                                                   # [n, (Hq + 2 Hkv) d]
+    nq, nk = n_q_heads * head_dim, n_kv_heads * head_dim
+    pos = np.arange(pos0, pos0 + n)
+    Q = Y[:, :nq].reshape(n, n_q_heads, head_dim).transpose(1, 0, 2)
+    K = Y[:, nq:nq + nk].reshape(n, n_kv_heads, head_dim).transpose(1, 0, 2)
+    V = Y[:, nq + nk:].reshape(n, n_kv_heads, head_dim).transpose(1, 0, 2)
+    Q = rope_rotate(Q, pos, base)
+    K = rope_rotate(K, pos, base)
+    return round_storage(Q, storage), round_storage(K, storage), round_storage(V, storage)
+
+
 # --------------------------------------------------------------------------- a1: prefill attention
 
 def prefill_attention_head(q, k, v, causal: bool = True, row_block: int = 2048,

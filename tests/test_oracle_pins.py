@@ -674,3 +674,44 @@ def test_append_threshold_is_the_ema_of_the_mean_best_similarity():
     assert abs(cache.tau - want) < 1e-15 and np.array_equal(ev.passed, ev.u_star >= cache.tau)
     _, evf = ref.append_chunk_head(forced, q, k, v, 25, budget, recent, sink, beta, tau_force=float("inf"))
     assert forced.tau == tau0 and not evf.passed.any() and np.array_equal(evf.evicted, ev.evicted)
+
+
+# ------------------------------------------------------------------ upstream: projection and rotary embedding
+
+def test_rope_is_a_complex_rotation_and_depends_on_relative_position_only():
+    g = np.random.default_rng(4)
+    d, n = 16, 9
+    x = g.standard_normal((3, n, d))
+    pos = np.array([0, 1, 2, 5, 17, 100, 1000, 4095, 131071])
+    y = ref.rope_rotate(x, pos, 10000.0)
+    # independent formulation: the pair (x_i, x_{i+d/2}) as a complex number times exp(i * angle)
+    z = (x[..., :d // 2] + 1j * x[..., d // 2:]) * np.exp(1j * pos[:, None] * 10000.0 ** (-2.0 * np.arange(d // 2) / d))
+    np.testing.assert_allclose(y, np.concatenate([z.real, z.imag], axis=-1), rtol=1e-12, atol=1e-12)
+    np.testing.assert_allclose(y[:, 0], x[:, 0], rtol=0, atol=0)                    # position 0: identity
+    np.testing.assert_allclose(np.linalg.norm(y, axis=-1), np.linalg.norm(x, axis=-1), rtol=1e-12)
+    # <rope(q, p), rope(k, p')> depends on p - p' only
+    q, k = g.standard_normal(d), g.standard_normal(d)
+    def dot_at(p, pp):
+        return float(ref.rope_rotate(q[None], [p], 500000.0)[0] @ ref.rope_rotate(k[None], [pp], 500000.0)[0])
+    assert abs(dot_at(7, 3) - dot_at(1007, 1003)) < 1e-9 and abs(dot_at(7, 3) - dot_at(4, 0)) < 1e-10
+    assert abs(dot_at(7, 3) - dot_at(3, 7)) > 1e-3                                  # but on its sign
+
+
+def test_qkv_projection_layout_and_library_matmul():
+    g = np.random.default_rng(9)
+    n, hidden, Hq, Hkv, d = 7, 12, 4, 2, 6
+    X, W = g.standard_normal((n, hidden)), g.standard_normal(((Hq + 2 * Hkv) * d, hidden))
+    Q, K, V = ref.qkv_project(X, W, Hq, Hkv, d, pos0=0, base=10000.0)
+    assert Q.shape == (Hq, n, d) and K.shape == (Hkv, n, d) and V.shape == (Hkv, n, d)
+    lin = torch.nn.functional.linear(torch.from_numpy(X), torch.from_numpy(W)).numpy()     # library routine
+    np.testing.assert_allclose(V[1], lin[:, (Hq + Hkv + 1) * d:(Hq + Hkv + 2) * d], rtol=1e-12, atol=1e-13)
+    np.testing.assert_allclose(Q[2, 0], lin[0, 2 * d:3 * d], rtol=1e-12, atol=1e-13)       # position 0: no rotation
+    np.testing.assert_allclose(K[1], ref.rope_rotate(lin[:, (Hq + 1) * d:(Hq + 2) * d], np.arange(n)), rtol=1e-12, atol=1e-13)
+    # a position offset shifts the rotation, not the projection
+    Q5, K5, V5 = ref.qkv_project(X, W, Hq, Hkv, d, pos0=5)
+    np.testing.assert_array_equal(V5, V)
+    np.testing.assert_allclose(Q5[3], ref.rope_rotate(lin[:, 3 * d:4 * d], np.arange(5, 5 + n)), rtol=1e-12, atol=1e-13)
+    # one hot hidden state picks a column of W: X = e_j gives feature f the value W[f, j]
+    E = np.zeros((1, hidden)); E[0, 3] = 1.0
+    Qe, Ke, Ve = ref.qkv_project(E, W, Hq, Hkv, d)
+    np.testing.assert_allclose(Ve[0, 0], W[(Hq + Hkv) * d:(Hq + Hkv + 1) * d, 3], rtol=0, atol=0)
