@@ -265,6 +265,27 @@ def main():
                             "avg_launch_ms": da_avg},
         "kernel_ms_per_launch": {k: (v[0] / v[1] if v[1] else None) for k, v in kt.items()},
     }
+    # ---- outside the timed region: the upstream step (Sec. 3 Eq. 1 + rotary embedding) at the
+    #      workload's shape with the hidden size of the model the shape comes from (heads * d)
+    if w.dtype == "bf16" and w.head_dim == 128 and not args.layers:
+        hidden = w.n_q_heads * w.head_dim
+        gx = torch.Generator(device=dev)
+        gx.manual_seed(synth.BASE_SEED + 17)
+        X = torch.randn(w.batch, n, hidden, generator=gx, device=dev, dtype=torch.float32).to(torch.bfloat16)
+        Wm = (torch.randn((w.n_q_heads + 2 * w.n_kv_heads) * d, hidden, generator=gx, device=dev,
+                          dtype=torch.float32) / hidden ** 0.5).to(torch.bfloat16)
+        binding.d2o_qkv_project(X, Wm, w.n_q_heads, w.n_kv_heads, d)
+        evq = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+        evq[0].record()
+        for _ in range(5):
+            binding.d2o_qkv_project(X, Wm, w.n_q_heads, w.n_kv_heads, d)
+        evq[1].record()
+        torch.cuda.synchronize()
+        q_ms = evq[0].elapsed_time(evq[1]) / 5
+        q_flop = 2.0 * w.batch * n * hidden * (w.n_q_heads + 2 * w.n_kv_heads) * d
+        out["qkv_project"] = {"ms_per_layer": q_ms, "hidden": hidden, "tflops": q_flop / (q_ms * 1e-3) / 1e12,
+                              "frac_of_bf16_peak": q_flop / (q_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS}
+        del X, Wm
     if args.zero_data_probe:
         probe = {}
         for tag, (q, k, v) in (("workload_data", (Q[0], K[0], V[0])),

@@ -105,6 +105,20 @@ const char* d2o_last_error(const d2o_ctx* ctx);
 /* Forgets all layers' caches, scores and thresholds (the workspaces are reused). */
 int d2o_reset(d2o_ctx* ctx, void* stream);
 
+/* Upstream step (Sec. 3 Eq. 1): Q = X W_Q, K = X W_K, V = X W_V of one layer as one matrix
+ * product, with the rotary position embedding of the evaluated models applied to queries and
+ * keys (feature i < d/2 pairs with i + d/2; angle = position * rope_base^(-2i/d); positions pos0,
+ * pos0 + 1, ... along the tokens of every sequence), results rounded once to `dtype` and written
+ * in the layout the attention calls read.  No context is needed.
+ * X: device [batch * n][hidden]; W: device [(Hq + 2 Hkv) * d][hidden] (a row = one output
+ * feature; queries first, then keys, then values), both contiguous and 16-byte aligned;
+ * Q: [B][Hq][n][d], K, V: [B][Hkv][n][d] views.  Built for D2O_BF16, d = 128, hidden a multiple
+ * of 32 (fp32 accumulation on the matrix cores).  Enqueues only.
+ * Errors: INVALID_ARG, UNSUPPORTED (other dtype / head_dim / hidden), HIP. */
+int d2o_qkv_project(int32_t batch, int32_t n, int32_t hidden, int32_t n_q_heads, int32_t n_kv_heads,
+                    int32_t head_dim, int32_t dtype, const void* X, const void* W, d2o_view Q,
+                    d2o_view K, d2o_view V, int32_t pos0, double rope_base, void* stream);
+
 /* Prompt encoding, attention part (Sec. 4.1 Eq. 4; Sec. 4.2.1 Eq. 6, prompt case).
  * For one layer computes, per query head, O = softmax(Q K^T / sqrt(d)) V with a causal
  * mask; per KV head the cumulative attention score of every key (column sums of the

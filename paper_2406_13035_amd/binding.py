@@ -17,7 +17,7 @@ LIB_PATH = os.environ.get("D2O_LIB", os.path.join(HERE, "libd2o.so"))
 
 D2O_F32, D2O_BF16 = 0, 1
 EXPORTS = [
-    "d2o_workspace_bytes", "d2o_create", "d2o_destroy", "d2o_last_error", "d2o_reset",
+    "d2o_workspace_bytes", "d2o_qkv_project", "d2o_create", "d2o_destroy", "d2o_last_error", "d2o_reset",
     "d2o_prefill_attend", "d2o_get_density", "d2o_allocate_budgets", "d2o_allocate_budgets_policy",
     "d2o_scores_import",
     "d2o_scores_export", "d2o_compress_layer", "d2o_compress_layer_heads", "d2o_allocate_budgets_heads", "d2o_prefill_compress", "d2o_decode_step",
@@ -59,6 +59,8 @@ def load_library() -> C.CDLL:
     vp, i32, i64 = C.c_void_p, C.c_int32, C.c_int64
     P = C.POINTER
     lib.d2o_workspace_bytes.argtypes = [P(d2o_config), P(C.c_size_t), P(C.c_size_t)]
+    lib.d2o_qkv_project.argtypes = [i32, i32, i32, i32, i32, i32, i32, vp, vp, d2o_view, d2o_view, d2o_view, i32,
+                                    C.c_double, vp]
     lib.d2o_create.argtypes = [P(d2o_config), vp, C.c_size_t, vp, C.c_size_t, vp, P(vp)]
     lib.d2o_destroy.argtypes = [vp]
     lib.d2o_destroy.restype = None
@@ -120,6 +122,25 @@ def d2o_allocate_budgets_heads(F_heads, n_kv_heads: int, seq_len: int, total_bud
     if rc != 0:
         raise D2OError(f"d2o_allocate_budgets_heads failed with {rc}")
     return S
+
+
+def d2o_qkv_project(X: torch.Tensor, W: torch.Tensor, n_q_heads: int, n_kv_heads: int, head_dim: int,
+                    pos0: int = 0, rope_base: float = 10000.0):
+    """Sec. 3 Eq. 1 with rotary embedding: X [B, n, hidden], W [(Hq + 2 Hkv) d, hidden] (bf16, on the
+    device) -> Q [B, Hq, n, d], K, V [B, Hkv, n, d]."""
+    lib = load_library()
+    assert X.is_cuda and W.is_cuda and X.dtype == torch.bfloat16 and W.dtype == torch.bfloat16
+    assert X.is_contiguous() and W.is_contiguous()
+    B, n, hidden = X.shape
+    Q = torch.empty((B, n_q_heads, n, head_dim), dtype=X.dtype, device=X.device)
+    K = torch.empty((B, n_kv_heads, n, head_dim), dtype=X.dtype, device=X.device)
+    V = torch.empty_like(K)
+    with torch.cuda.device(X.device):
+        rc = lib.d2o_qkv_project(B, n, hidden, n_q_heads, n_kv_heads, head_dim, D2O_BF16, X.data_ptr(), W.data_ptr(),
+                                 view4(Q), view4(K), view4(V), pos0, rope_base, _stream_ptr())
+    if rc != 0:
+        raise D2OError(f"d2o_qkv_project failed with {rc}")
+    return Q, K, V
 
 
 ALLOC_POLICIES = {"softmax": 0, "reciprocal": 1, "exp_decay": 2, "uniform": 3}

@@ -1,0 +1,228 @@
+// Upstream step of the hot path (Sec. 3 Eq. 1): Q = X W_Q, K = X W_K, V = X W_V for one layer as
+// ONE matrix product on the CDNA4 matrix cores, with the rotary position embedding of queries
+// and keys applied to the fp32 accumulators before they are stored, and the three results
+// written directly in the [sequence][head][token][d] layout that the prompt attention reads.
+//
+// bf16 operands, fp32 accumulation, head_dim 128.  X [B * n][hidden] and the stacked weights
+// W [(Hq + 2 Hkv) * 128][hidden] are both contiguous along `hidden`, which is the layout both
+// operands of v_mfma_f32_32x32x16_bf16 want (lane l: row l % 32, eight consecutive k from
+// 8 * (l / 32)).
+//
+// A workgroup (4 wavefronts) computes 256 tokens x 128 features = one head; a wavefront owns 64
+// tokens x 128 features (2 x 4 accumulator blocks: six LDS operand reads feed eight matrix
+// instructions).  The feature pair (c, c + 64) that the rotary embedding mixes lives in the same
+// lane and register of accumulator blocks j and j + 2, so the rotation needs no exchange.  The
+// rotated tile goes through LDS once so that every lane stores 16 contiguous bytes of a token's
+// head vector.
+#include <algorithm>
+
+#include "d2o_internal.h"
+#include "device_utils.h"
+
+namespace d2o {
+namespace {
+
+constexpr int kBM = 256, kBN = 128, kBK = 32;
+constexpr int kLd = kBK + 8;                 // LDS pitch (elements) of the operand tiles
+constexpr int kLdC = kBN + 8;                // LDS pitch of the result tile
+constexpr int kOperandElems = 2 * (kBM + kBN) * kLd;  // two stages
+constexpr int kResultElems = kBM / 2 * kLdC;          // the result tile passes through LDS in two halves
+constexpr int kSmemElems = kOperandElems > kResultElems ? kOperandElems : kResultElems;
+
+struct QkvArgs {
+  const uint16_t* X;
+  const uint16_t* W;
+  View q, k, v;        // [b][head][token][d]
+  int M, n, hidden, Hq, Hkv, pos0;
+  double log2_base;
+};
+
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void qkv_rope_bf16(QkvArgs a) {
+  __shared__ __attribute__((aligned(16))) uint16_t smem[kSmemElems];
+  const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, m = lane & 31, h = lane >> 5;
+  // Workgroups go to the eight XCDs round-robin in launch order.  Each XCD takes one eighth of
+  // the heads (its slice of W stays close to it) and walks the token tiles with its heads as
+  // the fast index, so the workgroups that run together share a few token tiles and that slice.
+  int ft = blockIdx.x;  // feature tile = head index over [Q heads | K heads | V heads]
+  int rt = blockIdx.y;  // token tile
+  if (gridDim.x % 8 == 0) {
+    const int lin = blockIdx.x + gridDim.x * blockIdx.y, xcd = lin & 7, s_ = lin >> 3, fpx = gridDim.x / 8;
+    ft = xcd * fpx + s_ % fpx;
+    rt = s_ / fpx;
+  }
+  const int row0 = rt * kBM;  // first token (flattened over sequences) of the tile
+  const uint16_t* Xb = a.X;
+  const uint16_t* Wb = a.W + int64_t(ft) * kBN * a.hidden;
+  auto As = [&](int st) { return smem + st * (kBM + kBN) * kLd; };
+  auto Bs = [&](int st) { return smem + st * (kBM + kBN) * kLd + kBM * kLd; };
+
+  f32x16 acc[2][4];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  // staging: a tile row holds 64 bytes = four 16-byte chunks; 1024 chunks of X and 512 of W
+  u32x4 ra[4], rb[2];
+  auto issue = [&](int kt) {
+    const int k0 = kt * kBK;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int c = tid + 256 * i, row = c >> 2, col = (c & 3) * 8;
+      ra[i] = *reinterpret_cast<const u32x4*>(Xb + int64_t(min(row0 + row, a.M - 1)) * a.hidden + k0 + col);
+    }
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const int c = tid + 256 * i, row = c >> 2, col = (c & 3) * 8;
+      rb[i] = *reinterpret_cast<const u32x4*>(Wb + int64_t(row) * a.hidden + k0 + col);
+    }
+  };
+  auto stage = [&](int st) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int c = tid + 256 * i, row = c >> 2, col = (c & 3) * 8;
+      *reinterpret_cast<u32x4*>(As(st) + row * kLd + col) = ra[i];
+    }
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const int c = tid + 256 * i, row = c >> 2, col = (c & 3) * 8;
+      *reinterpret_cast<u32x4*>(Bs(st) + row * kLd + col) = rb[i];
+    }
+  };
+  const int nk = a.hidden / kBK;
+  issue(0);
+  stage(0);
+  __syncthreads();
+  for (int kt = 0; kt < nk; ++kt) {
+    const int st = kt & 1;
+    if (kt + 1 < nk) issue(kt + 1);
+    // all operand reads of the stage first, then its sixteen matrix instructions back to back
+    bf16x8 av[kBK / 16][2], bv[kBK / 16][4];
+#pragma unroll
+    for (int ks = 0; ks < kBK / 16; ++ks) {
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+        av[ks][i] = *reinterpret_cast<const bf16x8*>(As(st) + (w * 64 + i * 32 + m) * kLd + ks * 16 + h * 8);
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+        bv[ks][j] = *reinterpret_cast<const bf16x8*>(Bs(st) + (j * 32 + m) * kLd + ks * 16 + h * 8);
+    }
+#pragma unroll
+    for (int ks = 0; ks < kBK / 16; ++ks)
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[ks][i], bv[ks][j], acc[i][j], 0, 0, 0);
+    if (kt + 1 < nk) stage(st ^ 1);
+    __syncthreads();
+  }
+  // ---- rotary embedding on queries and keys.  Accumulator layout: acc[i][j][r] is token
+  //      w*64 + i*32 + (r/4)*8 + 4h + r%4 of the tile, feature j*32 + m.  Features c < 64 pair with
+  //      c + 64: blocks (0, 2) and (1, 3) of the same lane and register.
+  const bool rotate = ft < a.Hq + a.Hkv;
+  if (rotate) {
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      const int c = j * 32 + m;
+      // turns (angle / 2 pi) per position step of this feature pair
+      const double turns_per_pos = exp2(-(2.0 * double(c) / double(kBN)) * a.log2_base) * 0.15915494309189535;
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int t = row0 + w * 64 + i * 32 + (r >> 2) * 8 + h * 4 + (r & 3);
+          const int pos = a.pos0 + (t % a.n);
+          // the angle in fp64, reduced to a fraction of a turn before the fp32 sine and cosine
+          // (positions reach 10^5: an fp32 product would be off by a hundredth of a radian); the
+          // hardware sine and cosine take their argument in turns
+          const double turns = double(pos) * turns_per_pos;
+          const float frac = float(turns - rint(turns));
+          const float sn = __builtin_amdgcn_sinf(frac), cs = __builtin_amdgcn_cosf(frac);
+          const float x0 = acc[i][j][r], x1 = acc[i][j + 2][r];
+          acc[i][j][r] = x0 * cs - x1 * sn;
+          acc[i][j + 2][r] = x1 * cs + x0 * sn;
+        }
+    }
+  }
+  // which tensor and head this tile is
+  View dst = a.q;
+  int head = ft;
+  if (ft >= a.Hq + a.Hkv) {
+    dst = a.v;
+    head = ft - a.Hq - a.Hkv;
+  } else if (ft >= a.Hq) {
+    dst = a.k;
+    head = ft - a.Hq;
+  }
+  uint16_t* out = static_cast<uint16_t*>(dst.ptr);
+  // ---- through LDS (the operand tiles are no longer needed; the loop's last barrier has passed),
+  //      128 tokens at a time: [token][feature] in bf16, then 16 contiguous bytes per lane
+  uint16_t* Cs = smem;
+#pragma unroll
+  for (int half = 0; half < 2; ++half) {
+    if ((w >> 1) == half) {
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const int row = (w & 1) * 64 + i * 32 + (r >> 2) * 8 + h * 4 + (r & 3);
+            Cs[row * kLdC + j * 32 + m] = Elem<uint16_t>::from_f32(acc[i][j][r]);
+          }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < kBM / 2 * kBN / 8 / 256; ++i) {
+      const int c = tid + 256 * i, row = c >> 4, col = (c & 15) * 8;
+      const int t = row0 + half * (kBM / 2) + row;
+      if (t < a.M) {
+        const int b = t / a.n, tok = t % a.n;
+        *reinterpret_cast<u32x4*>(out + b * dst.sb + head * dst.sh + int64_t(tok) * dst.sn + col) =
+            *reinterpret_cast<const u32x4*>(Cs + row * kLdC + col);
+      }
+    }
+    __syncthreads();
+  }
+}
+
+}  // namespace
+}  // namespace d2o
+
+using namespace d2o;
+
+extern "C" int d2o_qkv_project(int32_t batch, int32_t n, int32_t hidden, int32_t n_q_heads, int32_t n_kv_heads,
+                               int32_t head_dim, int32_t dtype, const void* X, const void* W, d2o_view Q,
+                               d2o_view K, d2o_view V, int32_t pos0, double rope_base, void* stream) {
+  if (batch < 1 || n < 1 || hidden < 1 || n_q_heads < 1 || n_kv_heads < 1 || !X || !W || pos0 < 0 ||
+      !(rope_base > 1.0))
+    return D2O_ERR_INVALID_ARG;
+  if (dtype != D2O_BF16 || head_dim != kBN) return D2O_ERR_UNSUPPORTED;
+  if (hidden % kBK) return D2O_ERR_UNSUPPORTED;
+  if (int64_t(batch) * n > 0x7FFFFFFF) return D2O_ERR_INVALID_ARG;
+  for (const d2o_view* v : {&Q, &K, &V}) {
+    if (!v->ptr || (reinterpret_cast<uintptr_t>(v->ptr) & 15) || v->stride_b % 8 || v->stride_h % 8 ||
+        v->stride_n % 8 || v->stride_n < head_dim)
+      return D2O_ERR_INVALID_ARG;
+  }
+  if ((reinterpret_cast<uintptr_t>(X) | reinterpret_cast<uintptr_t>(W)) & 15) return D2O_ERR_INVALID_ARG;
+  QkvArgs a;
+  a.X = static_cast<const uint16_t*>(X);
+  a.W = static_cast<const uint16_t*>(W);
+  a.q = to_view(Q);
+  a.k = to_view(K);
+  a.v = to_view(V);
+  a.M = batch * n;
+  a.n = n;
+  a.hidden = hidden;
+  a.Hq = n_q_heads;
+  a.Hkv = n_kv_heads;
+  a.pos0 = pos0;
+  a.log2_base = std::log2(rope_base);
+  const dim3 grid(n_q_heads + 2 * n_kv_heads, (a.M + kBM - 1) / kBM);
+  qkv_rope_bf16<<<grid, 256, 0, static_cast<hipStream_t>(stream)>>>(a);
+  return hipGetLastError() == hipSuccess ? D2O_OK : D2O_ERR_HIP;
+}

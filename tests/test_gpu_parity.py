@@ -888,3 +888,32 @@ def test_error_paths_return_codes():
     ctx.d2o_decode_step(0, 1, q[0][:1], k[0][:1], v[0][:1], out[:1])
     torch.cuda.synchronize()
     ctx.close()
+
+
+# ------------------------------------------------------------------ upstream: Q, K, V from the hidden states
+
+@pytest.mark.parametrize("B,n,hidden,Hq,Hkv,pos0,base", [
+    (1, 300, 256, 4, 2, 0, 10000.0),          # ragged against the 256-token tile, grouped-query
+    (2, 513, 128, 2, 2, 4000, 500000.0),      # two sequences, a position offset, a large rotary base
+    (1, 64, 1024, 3, 1, 131000, 10000.0),     # positions beyond 10^5
+])
+def test_qkv_projection_with_rotary_embedding(B, n, hidden, Hq, Hkv, pos0, base):
+    """Sec. 3 Eq. 1 on the matrix cores (bf16 operands, fp32 accumulation, bf16 results) against
+    the oracle's fp64 product and rotation: |got - want| <= 2e-3 * |row|_inf + 2^-8 * |want|
+    (the second term is the result's own bf16 rounding)."""
+    d = 128
+    g = torch.Generator().manual_seed(B * 1000 + n)
+    X = torch.randn(B, n, hidden, generator=g).to(torch.bfloat16)
+    W = (torch.randn((Hq + 2 * Hkv) * d, hidden, generator=g) / hidden ** 0.5).to(torch.bfloat16)
+    Q, K, V = binding.d2o_qkv_project(X.cuda(), W.cuda(), Hq, Hkv, d, pos0, base)
+    torch.cuda.synchronize()
+    Xd, Wd = binding.tensor_to_f64(X), binding.tensor_to_f64(W)
+    worst = 0.0
+    for b in range(B):
+        wq, wk, wv = ref.qkv_project(Xd[b], Wd, Hq, Hkv, d, pos0, base)
+        for got, want in ((Q[b], wq), (K[b], wk), (V[b], wv)):
+            got = binding.tensor_to_f64(got)
+            bound = H.FLOAT_TOL * np.abs(want).max(axis=-1, keepdims=True) + 2.0 ** -8 * np.abs(want)
+            assert np.all(np.abs(got - want) <= bound)
+            worst = max(worst, float((np.abs(got - want) / bound).max()))
+    print(f"  worst element error / bound = {worst:.3f}", flush=True)
