@@ -163,6 +163,9 @@ def main():
                          "kernels of layer 0 on the workload's data and on all-zero Q, K, V (same "
                          "instruction stream; the difference is what the chip's power management "
                          "takes for operands that toggle)")
+    ap.add_argument("--split-rows", type=int, default=0,
+                    help="tuning aid: the context's split_rows (entries above which a head's closing "
+                         "work in a generation step is split over workgroups); 0 = the library's default")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (one GPU's share "
@@ -183,7 +186,7 @@ def main():
     dq, dk, dv = generate_decode(w, dsteps, dev)
     slots = w.total_budget() + w.n_layers + 8
     ctx = binding.D2O(w.batch, w.n_layers, w.n_q_heads, w.n_kv_heads, w.head_dim, w.prompt_len,
-                      slots, dtype=w.dtype, n_sink=0, beta=w.beta)
+                      slots, dtype=w.dtype, n_sink=0, beta=w.beta, split_rows=args.split_rows)
     O = torch.empty_like(Q[0])
     dout = torch.empty_like(dq[0])
     torch.cuda.synchronize()

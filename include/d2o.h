@@ -70,6 +70,13 @@ typedef struct {
                           /* sum_l (S_l + max(1, max_append)), and S_l + max_append must not */
                           /* exceed max_prompt_len (the block's token-level stages reuse the */
                           /* prompt-phase scratch)                                           */
+  int32_t split_rows;     /* generation steps: a head whose cache holds more entries than    */
+                          /* this has its closing work (normaliser, score update, eviction   */
+                          /* choice) split over several workgroups in two extra launches     */
+                          /* instead of done by one.  0: chosen per launch (half a percent   */
+                          /* of the rows the launch streams, within [8192, 16384]).          */
+                          /* Otherwise at least 256.  A tuning knob: events and scores do    */
+                          /* not depend on it, outputs only in fp32 summation order.         */
 } d2o_config;
 
 /* A strided tensor whose last dimension (d) is contiguous.  Strides are in elements.
@@ -271,7 +278,11 @@ int d2o_cache_export(d2o_ctx* ctx, int32_t layer, int32_t b, int32_t kv_head, vo
 
 /* Host buffers into the cache of one (layer, sequence, KV head) of a reserved layer;
  * count <= budget, `next_pos` = position the next generated token will get (same for every
- * head of the layer).  Synchronises `stream`. */
+ * head of the layer).  The generation steps protect the recent window by position (the
+ * last M positions before the new token), which equals the last M cache entries of Eq. 7
+ * only while those positions are all present: an imported cache must hold every position
+ * of [next_pos - M, next_pos), as every cache this library produces does.
+ * Synchronises `stream`. */
 int d2o_cache_import(d2o_ctx* ctx, int32_t layer, int32_t b, int32_t kv_head, const void* K,
                      const void* V, const double* score, const int32_t* pos, int32_t count,
                      double tau, int32_t next_pos, void* stream);
@@ -307,7 +318,8 @@ typedef enum {
   D2O_K_MERGE = 5,
   D2O_K_DECODE_ATTEND = 6,  /* attention over the cache + score update + evict/merge         */
   D2O_K_DECODE_PREPARE = 7, /* append of the new token, operand set-up                      */
-  D2O_K_COUNT = 8
+  D2O_K_DECODE_CLOSE = 8,   /* closing work of very large heads, split over workgroups        */
+  D2O_K_COUNT = 9
 } d2o_kernel_id;
 int d2o_timing_enable(d2o_ctx* ctx, int32_t on);
 int d2o_timing_read(d2o_ctx* ctx, int32_t kernel_id, double* total_ms, int64_t* launches,

@@ -36,7 +36,8 @@ class d2o_config(C.Structure):
                 ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32), ("max_prompt_len", C.c_int32),
                 ("slots_per_seq", C.c_int64), ("dtype", C.c_int32), ("n_sink", C.c_int32),
                 ("beta", C.c_double), ("tau_force", C.c_double), ("out_f32", C.c_int32),
-                ("merge_average", C.c_int32), ("max_append", C.c_int32)]
+                ("merge_average", C.c_int32), ("max_append", C.c_int32),
+                ("split_rows", C.c_int32)]
 
 
 class d2o_view(C.Structure):
@@ -182,7 +183,7 @@ class D2O:
 
     def __init__(self, batch, n_layers, n_q_heads, n_kv_heads, head_dim, max_prompt_len,
                  slots_per_seq, dtype="bf16", n_sink=0, beta=0.7, tau_force=float("nan"),
-                 out_f32=False, device="cuda:0", merge_average=False, max_append=0):
+                 out_f32=False, device="cuda:0", merge_average=False, max_append=0, split_rows=0):
         self.lib = load_library()
         if not torch.cuda.is_available():
             raise D2OError("no GPU visible: the D2O library has no CPU path")
@@ -190,7 +191,7 @@ class D2O:
         self.cfg = d2o_config(batch, n_layers, n_q_heads, n_kv_heads, head_dim, max_prompt_len,
                               slots_per_seq, D2O_BF16 if dtype == "bf16" else D2O_F32, n_sink,
                               beta, tau_force, 1 if out_f32 else 0, 1 if merge_average else 0,
-                              int(max_append))
+                              int(max_append), int(split_rows))
         self.dtype = dtype
         self.out_dtype = torch.float32 if out_f32 else (torch.bfloat16 if dtype == "bf16" else torch.float32)
         self.torch_dtype = torch.bfloat16 if dtype == "bf16" else torch.float32
@@ -380,7 +381,7 @@ class D2O:
 
 
 KERNEL_IDS = {"attn_fwd": 0, "colsum": 1, "select": 2, "match_filter": 3, "match_refine": 4,
-              "merge": 5, "decode_attend": 6, "decode_prepare": 7}
+              "merge": 5, "decode_attend": 6, "decode_prepare": 7, "decode_close": 8}
 
 
 # ---- element conversions for host-side export / import (bit moves, no arithmetic) ----------

@@ -52,6 +52,7 @@ int check_config(const d2o_config* c) {
   if (c->out_f32 != 0 && c->out_f32 != 1) return D2O_ERR_INVALID_ARG;
   if (c->merge_average != 0 && c->merge_average != 1) return D2O_ERR_INVALID_ARG;
   if (c->max_append < 0 || c->max_append >= c->max_prompt_len) return D2O_ERR_INVALID_ARG;
+  if (c->split_rows != 0 && c->split_rows < 256) return D2O_ERR_INVALID_ARG;
   return D2O_OK;
 }
 
@@ -115,6 +116,7 @@ void layout(d2o_ctx* x, char* persistent, char* scratch, size_t* pbytes, size_t*
   const size_t nsub = nch * 4;  // partial results are kept per 64 slots, a quarter of a chunk
   s.take(x->d_rec, bh * nsub * 32);
   s.take(x->d_pacc, bh * nsub * G * d);
+  s.take(x->d_part, bh * nch * kPartRecDoubles);
   s.take(x->d_vecs, L * bh * (G + nc) * d);
   s.take(x->d_cnorm, L * bh * nc);
 

@@ -11,6 +11,8 @@
 
 namespace d2o {
 
+constexpr int kPartRecDoubles = 32;  // doubles of a part record of the split closing kernels
+constexpr int kMinAutoSplitRows = 8192, kMaxAutoSplitRows = 16384;  // bounds of the automatic split_rows
 constexpr int kChunk = 256;        // cache slots handled by one workgroup in the decode kernels
 constexpr int kColBN = 256;        // keys per workgroup, column-sum pass (bf16)
 
@@ -115,6 +117,7 @@ struct d2o_ctx {
   // decode
   double* d_logit = nullptr;     // [nchunk][B][Hkv][G][256] exp(logit - sub-chunk max), chunk-major
   double* d_rec = nullptr;       // [nchunk][B][Hkv][4][32] per 64 slots: softmax maxima and sums, candidates' best cosine and slot
+  double* d_part = nullptr;      // [nchunk][B][Hkv][kPartRecDoubles] records of the split closing kernels (one per part, at its first chunk)
   float* d_pacc = nullptr;       // [nchunk][B][Hkv][4][G][d] partial outputs
   double* d_vecs = nullptr;      // [L][B][Hkv][G + candidates][d] queries and candidate keys, fp64
   double* d_cnorm = nullptr;     // [L][B][Hkv][candidates] norms of the candidate keys

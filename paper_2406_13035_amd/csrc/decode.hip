@@ -356,98 +356,7 @@ __device__ __forceinline__ void head_tail(const DecodeArgs& a, OT* __restrict__ 
       apply_batch(j0);
     }
   }
-  // evicted token: block-wide
-  ev = fast_wave_first_evicted(ev);
-  lds_barrier();
-  if (lane == 0) {
-    sred[w] = ev.u;
-    ired[w] = ev.pos;
-    ired[4 + w] = ev.slot;
-  }
-  lds_barrier();
-  const double s_last = sred[4];
-  const int p_last = ired[8];
-  ev = Best{sred[0], ired[0], ired[4]};
-#pragma unroll
-  for (int i = 1; i < 4; ++i)
-    if (evicts_before(sred[i], ired[i], ired[4 + i], ev)) ev = Best{sred[i], ired[i], ired[4 + i]};
-  const int es = evict ? ev.slot : -1;  // a candidate always exists: total > budget >= T + M
-  // the kCand + 1 lowest of the next step's evictable tokens: repeated block-wide extraction
-  int nxt[kCand + 1];
-#pragma unroll
-  for (int r = 0; r <= kCand; ++r) {
-    Best h = fast_wave_first_evicted(low[0]);
-    lds_barrier();
-    if (lane == 0) {
-      sred[w] = h.u;
-      ired[w] = h.pos;
-      ired[4 + w] = h.slot;
-    }
-    lds_barrier();
-    h = Best{sred[0], ired[0], ired[4]};
-#pragma unroll
-    for (int i = 1; i < 4; ++i)
-      if (evicts_before(sred[i], ired[i], ired[4 + i], h)) h = Best{sred[i], ired[i], ired[4 + i]};
-    nxt[r] = h.slot;
-    if (h.slot >= 0 && low[0].slot == h.slot) {  // the owner pops its head
-#pragma unroll
-      for (int i = 0; i < kCand; ++i) low[i] = low[i + 1];
-      low[kCand].slot = -1;
-    }
-  }
-  int ci = -1;
-#pragma unroll
-  for (int i = kCand - 1; i >= 0; --i)
-    if (es >= 0 && cl[i] == es) ci = i;
-  if (tid == 0) {  // the next step's candidates (every thread holds this step's list in registers)
-    int k = 0;
-    for (int r = 0; r <= kCand && k < kCand; ++r) {
-      int s = nxt[r];
-      if (s < 0 || s == es) continue;
-      if (es >= 0 && s == last) s = es;  // the last slot is about to move into the freed one
-      a.cand[lbh * kCand + k++] = s;
-    }
-    for (; k < kCand; ++k) a.cand[lbh * kCand + k] = -1;
-    st_agent(&a.ticket[lbh], 0u);
-  }
-  if (!evict) {
-    if (tid == 0) {
-      a.ccount[lbh] = total;
-      a.ev_evicted[lbh] = -1;
-      a.ev_target[lbh] = -1;
-      a.ev_ustar[lbh] = __longlong_as_double(0x7FF8000000000000ll);
-    }
-    return;
-  }
-  Best m{0.0, 0, -1};
-  if (ci < 0) {
-    // Not foreseen (the first step after a cache import, or a candidate overtaken by a token
-    // outside the list): a second pass over the head's keys.
-    m = scan_matches<T, D>(a, slot0, es, total, dred, sred);
-  } else {
-    if (tid < 4) {  // the four wavefronts' results (written before the barriers of the score pass)
-      const int2 q = wcm_ps[tid * kCand + ci];
-      m = Best{wcm_u[tid * kCand + ci], q.x, q.y};
-    }
-  }
-  m = fast_wave_best_match(m.u, m.pos, m.slot);
-  lds_barrier();
-  if (lane == 0) {
-    sred[w] = m.u;
-    ired[w] = m.pos;
-    ired[4 + w] = m.slot;
-  }
-  lds_barrier();
-  m = Best{sred[0], ired[0], ired[4]};
-#pragma unroll
-  for (int i = 1; i < 4; ++i)
-    if (better_match(sred[i], ired[i], ired[4 + i], m)) m = Best{sred[i], ired[i], ired[4 + i]};
-  T kl = T(), vl = T();
-  if (tid < D) {
-    kl = park_kv[tid];
-    vl = park_kv[256 + tid];
-  }
-  finish_head<T, D>(a, lbh, slot0, es, total, m.u, m.pos, m.slot, told, kl, vl, s_last, p_last);
+  close_head<T, D>(a, lbh, slot0, total, evict, ev, low, cl, told, sred, ired, dred, wcm_u, wcm_ps, park_kv);
 }
 
 template <typename T, typename OT, int D, int G>
@@ -721,6 +630,7 @@ __global__ __launch_bounds__(256) void decode_attend(DecodeArgs a, OT* __restric
   }
   __syncthreads();
   if (!sh_last) return;
+  if (total > a.big_rows) return;  // a very large head: two more launches close it (decode_close_part / _final)
   // Consumer side of the hand-over.  The other workgroups' results (rec, elog, pacc) are read
   // below through ld_agent only, which goes around this XCD's L2 whatever the compiler does
   // with plain loads; this fence keeps the compiler from moving any load of the closing code
@@ -844,9 +754,9 @@ hipError_t launch_init_candidates(d2o_ctx* c, int layer, int new_pos, hipStream_
   return hipGetLastError();
 }
 
-// Sizes (in bytes, each rounded up to 256) of the five scratch arrays of a decode step, in the
-// order elog, rec, pacc, vecs, cnorm.
-static void decode_scratch_sizes(const d2o_ctx* c, size_t (&sz)[5]) {
+// Sizes (in bytes, each rounded up to 256) of the six scratch arrays of a decode step, in the
+// order elog, rec, pacc, vecs, cnorm, part.
+static void decode_scratch_sizes(const d2o_ctx* c, size_t (&sz)[6]) {
   const d2o_config& cf = c->cfg;
   const size_t B = cf.batch, L = cf.n_layers, Hq = cf.n_q_heads, Hkv = cf.n_kv_heads, d = cf.head_dim;
   const size_t G = Hq / Hkv, bh = B * Hkv, nch = c->nchunk_cap, nsub = nch * 4;
@@ -855,13 +765,14 @@ static void decode_scratch_sizes(const d2o_ctx* c, size_t (&sz)[5]) {
   sz[2] = bh * nch * G * d * sizeof(float);                  // one partial output row per chunk and query head
   sz[3] = L * bh * (G + kCand) * d * sizeof(double);
   sz[4] = L * bh * kCand * sizeof(double);
+  sz[5] = bh * nch * kPartRecDoubles * sizeof(double);
   for (size_t& x : sz) x = (x + 255) & ~size_t(255);
 }
 
 size_t decode_static_scratch_need(const d2o_ctx* c) {
-  size_t sz[5];
+  size_t sz[6];
   decode_scratch_sizes(c, sz);
-  return sz[0] + sz[1] + sz[2] + sz[3] + sz[4];
+  return sz[0] + sz[1] + sz[2] + sz[3] + sz[4] + sz[5];
 }
 size_t decode_static_scratch_capacity() { return kStaticScratchBytes; }
 
@@ -884,8 +795,9 @@ hipError_t launch_decode(d2o_ctx* c, int layer0, int nl_all, View q, View k, Vie
   a.pacc = c->d_pacc;
   a.vecs = c->d_vecs;
   a.cnorm = c->d_cnorm;
-  if (static_scratch) {  // the same five arrays, carved from the library's static device array
-    size_t sz[5];
+  a.part = c->d_part;
+  if (static_scratch) {  // the same six arrays, carved from the library's static device array
+    size_t sz[6];
     decode_scratch_sizes(c, sz);
     unsigned char* p = static_scratch;
     a.elog = reinterpret_cast<double*>(p);
@@ -893,6 +805,7 @@ hipError_t launch_decode(d2o_ctx* c, int layer0, int nl_all, View q, View k, Vie
     a.pacc = reinterpret_cast<float*>(p += sz[1]);
     a.vecs = reinterpret_cast<double*>(p += sz[2]);
     a.cnorm = reinterpret_cast<double*>(p += sz[3]);
+    a.part = reinterpret_cast<double*>(p += sz[4]);
   }
   a.ev_evicted = c->ev_evicted;
   a.ev_target = c->ev_target;
@@ -906,6 +819,7 @@ hipError_t launch_decode(d2o_ctx* c, int layer0, int nl_all, View q, View k, Vie
   a.out_f32 = cf.out_f32;
   a.merge_average = cf.merge_average;
   a.no_evict = extra_rows > 0 ? 1 : 0;
+  a.part_chunks = cf.split_rows > 0 ? std::min(8, std::max(1, cf.split_rows / (4 * kChunk))) : 8;
   a.beta = cf.beta;
   a.tau_force = cf.tau_force;
   // the per-layer tensors of one call are [layer][...]: groups of at most kMaxLayersPerCall
@@ -915,12 +829,22 @@ hipError_t launch_decode(d2o_ctx* c, int layer0, int nl_all, View q, View k, Vie
     a.nl = nl;
     int mc[kMaxLayersPerCall], chunk_id[kMaxLayersPerCall];
     const int nc = nl;
+    int64_t rows = 0;  // cache rows this launch streams
     for (int i = 0; i < nl; ++i) {
       chunk_id[i] = i;
       mc[i] = 1;
-      for (const auto& mt : c->layers[a.layer0 + i].meta)
+      for (const auto& mt : c->layers[a.layer0 + i].meta) {
         mc[i] = std::max(mc[i], (mt.budget + std::max(1, extra_rows) + kGroup * kChunk - 1) / (kGroup * kChunk));
+        rows += mt.budget + std::max(1, extra_rows);
+      }
     }
+    // Which heads are too large for one closing workgroup.  A head's last workgroup closes it
+    // while the other heads' chunks still stream, which costs nothing as long as the head is a
+    // small part of the launch; a head that holds more than about half a percent of the
+    // launch's rows (a few giant layers after Eq. 5, or a launch of one layer) would leave the
+    // chip waiting for its closing workgroup, and is finished by the split kernels instead.
+    a.big_rows = cf.split_rows > 0 ? cf.split_rows
+                                   : int(std::min<int64_t>(kMaxAutoSplitRows, std::max<int64_t>(kMinAutoSplitRows, rows / 200)));
     auto shift = [&](View x, int elem_bytes) {  // first layer of this group
       x.ptr = static_cast<char*>(x.ptr) + size_t(g0) * x.sn * elem_bytes;
       return x;
@@ -953,6 +877,14 @@ hipError_t launch_decode(d2o_ctx* c, int layer0, int nl_all, View q, View k, Vie
       else
         e = run_decode_g<float, 128>(c, a, flat, og, s);
       if (e != hipSuccess) return e;
+      // ---- heads too large for one closing workgroup (their entry count can reach budget + rows
+      //      appended since): the same grid finishes them in parts
+      bool big = false;
+      for (int i = 0; i < nl; ++i) big = big || int64_t(mc[i]) * kChunk > a.big_rows;
+      if (big) {
+        e = launch_decode_split(c, a, mc, nl, og, s);
+        if (e != hipSuccess) return e;
+      }
     }
   }
   return hipSuccess;

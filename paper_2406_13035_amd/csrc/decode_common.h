@@ -43,6 +43,9 @@ struct DecodeArgs {
   double* ev_ustar;
   int64_t slots;
   int layer0, nl, B, Hkv, G, new_pos, n_sink, out_f32, merge_average;
+  int big_rows;       // heads with more entries are closed by the split kernels, not by their last workgroup
+  int part_chunks;    // chunks per workgroup of decode_close_part
+  double* part;       // [chunk][B][Hkv][kPartRecDoubles] part records (at a part's first chunk)
   int no_evict;       // 1: a token inside a block of d2o_append_chunk: the caches grow past their budgets
   double beta, tau_force;
   int32_t lay_off[kMaxLayersPerCall + 1];  // first flat chunk-group index of each entry of lay_id
@@ -292,6 +295,120 @@ __device__ __forceinline__ Best scan_matches(const DecodeArgs& a, int64_t slot0,
   return m;
 }
 
+
+// The end of a head's closing work, by a workgroup of 256 threads.  On entry every thread holds
+// its own first-evicted entry `ev` and its sorted list `low` of the next step's lowest evictable
+// entries (a thread's entries belong to slots no other thread holds); LDS holds, per wavefront
+// and candidate, the best match found (`wcm_u`, `wcm_ps` = (position, slot)), the last slot's
+// updated score and position (sred[4], ired[8]) and its row as it was before the step
+// (`park_kv`: K at [0, D), V at [256, 256 + D)).  The function reduces them over the workgroup,
+// writes the next step's candidates, resets the head's ticket, finds the merge target (from the
+// candidates' results, else by a pass over the head's keys) and finishes the step.
+template <typename T, int D>
+__device__ __forceinline__ void close_head(const DecodeArgs& a, int64_t lbh, int64_t slot0, int total, bool evict,
+                                           Best ev, Best (&low)[kCand + 1], const int (&cl)[kCand], double told,
+                                           double* sred, int* ired, double* dred, const double* wcm_u,
+                                           const int2* wcm_ps, const T* park_kv) {
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const int last = total - 1;
+  // evicted token: block-wide
+  ev = fast_wave_first_evicted(ev);
+  lds_barrier();
+  if (lane == 0) {
+    sred[w] = ev.u;
+    ired[w] = ev.pos;
+    ired[4 + w] = ev.slot;
+  }
+  lds_barrier();
+  const double s_last = sred[4];
+  const int p_last = ired[8];
+  ev = Best{sred[0], ired[0], ired[4]};
+#pragma unroll
+  for (int i = 1; i < 4; ++i)
+    if (evicts_before(sred[i], ired[i], ired[4 + i], ev)) ev = Best{sred[i], ired[i], ired[4 + i]};
+  const int es = evict ? ev.slot : -1;  // a candidate always exists: total > budget >= T + M
+  // the kCand + 1 lowest of the next step's evictable tokens: repeated block-wide extraction
+  int nxt[kCand + 1];
+#pragma unroll
+  for (int r = 0; r <= kCand; ++r) {
+    Best h = fast_wave_first_evicted(low[0]);
+    lds_barrier();
+    if (lane == 0) {
+      sred[w] = h.u;
+      ired[w] = h.pos;
+      ired[4 + w] = h.slot;
+    }
+    lds_barrier();
+    h = Best{sred[0], ired[0], ired[4]};
+#pragma unroll
+    for (int i = 1; i < 4; ++i)
+      if (evicts_before(sred[i], ired[i], ired[4 + i], h)) h = Best{sred[i], ired[i], ired[4 + i]};
+    nxt[r] = h.slot;
+    if (h.slot >= 0 && low[0].slot == h.slot) {  // the owner pops its head
+#pragma unroll
+      for (int i = 0; i < kCand; ++i) low[i] = low[i + 1];
+      low[kCand].slot = -1;
+    }
+  }
+  int ci = -1;
+#pragma unroll
+  for (int i = kCand - 1; i >= 0; --i)
+    if (es >= 0 && cl[i] == es) ci = i;
+  if (tid == 0) {  // the next step's candidates (every thread holds this step's list in registers)
+    int k = 0;
+    for (int r = 0; r <= kCand && k < kCand; ++r) {
+      int s = nxt[r];
+      if (s < 0 || s == es) continue;
+      if (es >= 0 && s == last) s = es;  // the last slot is about to move into the freed one
+      a.cand[lbh * kCand + k++] = s;
+    }
+    for (; k < kCand; ++k) a.cand[lbh * kCand + k] = -1;
+    st_agent(&a.ticket[lbh], 0u);
+  }
+  if (!evict) {
+    if (tid == 0) {
+      a.ccount[lbh] = total;
+      a.ev_evicted[lbh] = -1;
+      a.ev_target[lbh] = -1;
+      a.ev_ustar[lbh] = __longlong_as_double(0x7FF8000000000000ll);
+    }
+    return;
+  }
+  Best m{0.0, 0, -1};
+  if (ci < 0) {
+    // Not foreseen (the first step after a cache import, or a candidate overtaken by a token
+    // outside the list): a second pass over the head's keys.
+    m = scan_matches<T, D>(a, slot0, es, total, dred, sred);
+  } else {
+    if (tid < 4) {  // the four wavefronts' results (written before the barriers of the score pass)
+      const int2 q = wcm_ps[tid * kCand + ci];
+      m = Best{wcm_u[tid * kCand + ci], q.x, q.y};
+    }
+  }
+  m = fast_wave_best_match(m.u, m.pos, m.slot);
+  lds_barrier();
+  if (lane == 0) {
+    sred[w] = m.u;
+    ired[w] = m.pos;
+    ired[4 + w] = m.slot;
+  }
+  lds_barrier();
+  m = Best{sred[0], ired[0], ired[4]};
+#pragma unroll
+  for (int i = 1; i < 4; ++i)
+    if (better_match(sred[i], ired[i], ired[4 + i], m)) m = Best{sred[i], ired[i], ired[4 + i]};
+  T kl = T(), vl = T();
+  if (tid < D) {
+    kl = park_kv[tid];
+    vl = park_kv[256 + tid];
+  }
+  finish_head<T, D>(a, lbh, slot0, es, total, m.u, m.pos, m.slot, told, kl, vl, s_last, p_last);
+}
+
+// The two launches that close the heads with more than a.big_rows entries (decode_split.hip).
+// `max_chunks[i]`: the chunks the largest head of the call's layer i can occupy in this step.
+hipError_t launch_decode_split(d2o_ctx* c, const DecodeArgs& attend, const int* max_chunks, int nl, View out,
+                               hipStream_t s);
 
 }  // namespace dec
 

@@ -266,7 +266,7 @@ def test_merge_with_long_source_lists():
 # ------------------------------------------------------------------ a9-a12: decode from oracle state
 
 def _run_decode_parity(w, n, B, layer, budget, recent, sink, steps, tau_force=float("nan"), random_scores=False,
-                       merge_average=False):
+                       merge_average=False, split_rows=0):
     Q, K, V = H.make_inputs(w, B, layer, n)
     if random_scores:  # long prompts: the token-level stages and decode do not care where scores come from
         score32 = np.random.default_rng(n).random((B, w.n_kv_heads, n), dtype=np.float32) * w.group
@@ -274,7 +274,8 @@ def _run_decode_parity(w, n, B, layer, budget, recent, sink, steps, tau_force=fl
         _, score, _ = H.oracle_prefill_layer(Q, K, V, w.group)
         score32 = score.astype(np.float32)
     cap = int(np.max(budget)) + 1
-    ctx = H.new_ctx(w, B, 1, n, cap + 8, n_sink=sink, tau_force=tau_force, merge_average=merge_average)
+    ctx = H.new_ctx(w, B, 1, n, cap + 8, n_sink=sink, tau_force=tau_force, merge_average=merge_average,
+                    split_rows=split_rows)
     ctx.d2o_scores_import(0, score32)
     ctx.d2o_compress_layer(0, K, V, budget, recent)
     _, caches = H.check_compress_against_oracle(ctx, 0, K, V, score32, budget, recent, sink, w.dtype,
@@ -346,9 +347,77 @@ def test_decode_from_oracle_state(case):
 def test_decode_one_large_head_with_eight_query_heads(budget):
     """A head of 188 / 235 sub-chunks of 64 slots with 8 query heads: the closing workgroup's
     table of per-sub-chunk softmax factors fits its LDS region in the first case and does not
-    in the second (it then lives in the sub-chunk records)."""
+    in the second (it then lives in the sub-chunk records).  split_rows is set out of reach so
+    that one workgroup closes the head, whatever the library would choose for this launch."""
     w = W1.scaled(n_q_heads=8, n_kv_heads=1)
-    _run_decode_parity(w, 16000, 1, 0, budget, budget // 4, 0, 4, random_scores=True)
+    _run_decode_parity(w, 16000, 1, 0, budget, budget // 4, 0, 4, random_scores=True, split_rows=1 << 30)
+
+
+@pytest.mark.parametrize("case", ["bf16-mha-16-parts", "bf16-gqa4-ragged", "bf16-gqa8-12-parts", "f32-d64",
+                                  "bf16-never-merge", "bf16-average"])
+def test_decode_large_heads_closed_in_parts(case):
+    """split_rows lowered so that the heads of these small caches take the path of very large
+    ones: their closing work is done by one workgroup per part (1, 2 or 4 chunks here) and a
+    final workgroup per head.  Events, caches and scores against the oracle as in the
+    single-workgroup form."""
+    print(f"case={case}", flush=True)
+    if case == "bf16-mha-16-parts":
+        _run_decode_parity(_small_bf16(False).scaled(n_q_heads=2, n_kv_heads=2), 6000, 1, 25, 4000, 1000, 0, 5,
+                           random_scores=True, split_rows=1024)
+    elif case == "bf16-gqa4-ragged":   # 3 parts and 2 parts of one chunk; the smaller sequence's last part is ragged
+        _run_decode_parity(W4.scaled(n_q_heads=8, n_kv_heads=2, n_clusters=16), 1500, 2, 6, [700, 410],
+                           [175, 100], 0, 10, random_scores=True, split_rows=256)
+    elif case == "bf16-gqa8-12-parts":
+        _run_decode_parity(W1.scaled(n_q_heads=8, n_kv_heads=1), 16000, 1, 0, 12000, 3000, 0, 4,
+                           random_scores=True, split_rows=4096)
+    elif case == "f32-d64":
+        _run_decode_parity(W1, 2000, 1, 0, 600, 150, 2, 12, random_scores=True, split_rows=256)
+    elif case == "bf16-never-merge":
+        _run_decode_parity(_small_bf16(False), 1500, 1, 12, 900, 225, 0, 8, tau_force=float("inf"),
+                           random_scores=True, split_rows=2048)   # one part of two chunks + a ragged one
+    else:
+        _run_decode_parity(_small_bf16(True), 1777, 2, 9, [650, 333], [37, 83], 2, 12, merge_average=True,
+                           random_scores=True, split_rows=512)    # only the first sequence's heads are large
+
+
+def test_decode_large_head_after_cache_import_scans_for_the_match():
+    """The first step after a cache import has no predicted candidates, so the evicted token's
+    match comes from a pass over the head's keys: here in the final workgroup of the split
+    form (700 entries, split_rows 256)."""
+    w = _small_bf16(False).scaled(n_q_heads=1, n_kv_heads=1)
+    d, n0, budget, recent, steps = w.head_dim, 900, 700, 100, 3
+    g = torch.Generator().manual_seed(5)
+    K = torch.randn(budget, d, generator=g).to(torch.bfloat16)
+    V = torch.randn(budget, d, generator=g).to(torch.bfloat16)
+    score = 1.0 + torch.rand(budget, generator=g).double().numpy()
+    # survivors of a 900-token prompt: the recent window complete (Eq. 7 keeps it), the rest a random subset
+    pos = np.concatenate([np.sort(np.random.default_rng(5).choice(n0 - recent, budget - recent, replace=False)),
+                          np.arange(n0 - recent, n0)]).astype(np.int32)
+    ctx = H.new_ctx(w, 1, 1, n0, budget + 8, beta=0.7, split_rows=256)
+    ctx.d2o_layer_reserve(0, n0, budget, recent)
+    Kd, Vd = binding.tensor_to_f64(K), binding.tensor_to_f64(V)
+    ctx.d2o_cache_import(0, 0, 0, Kd, Vd, score, pos, 0.5, n0)
+    cache = ref.HeadCache(Kd.copy(), Vd.copy(), score.copy(), pos.astype(np.int64), 0.5, "bf16")
+    q = torch.randn(steps, 1, 1, 1, d, generator=g).to(torch.bfloat16)
+    k = torch.randn(steps, 1, 1, 1, d, generator=g).to(torch.bfloat16)
+    v = torch.randn(steps, 1, 1, 1, d, generator=g).to(torch.bfloat16)
+    qg, kg, vg = q.cuda(), k.cuda(), v.cuda()
+    out = torch.empty(qg[0].shape, dtype=ctx.out_dtype, device="cuda")
+    for t in range(steps):
+        ctx.d2o_decode_step(0, 1, qg[t], kg[t], vg[t], out)
+        torch.cuda.synchronize()
+        ev, tg, us = ctx.d2o_last_events(0)
+        want, e = ref.decode_step_head(cache, binding.tensor_to_f64(q[t, 0, 0]), binding.tensor_to_f64(k[t, 0, 0, 0]),
+                                       binding.tensor_to_f64(v[t, 0, 0, 0]), n0 + t, budget, recent, 0, 0.7)
+        assert e.evicted_pos >= 0
+        assert (ev[0, 0], tg[0, 0]) == (e.evicted_pos, e.target_pos), f"step {t}"
+        assert abs(us[0, 0] - e.u_star) < 1e-13
+        assert H.rownorm_err(binding.tensor_to_f64(out)[0, 0], want) <= H.FLOAT_TOL
+    gK, gV, gs, gp, gtau = ctx.d2o_cache_export(0, 0, 0, budget + 1)
+    assert np.array_equal(gp, cache.pos) and np.array_equal(gK, cache.K) and np.array_equal(gV, cache.V)
+    np.testing.assert_allclose(gs, cache.score, rtol=1e-12)
+    assert abs(gtau - cache.tau) < 1e-13
+    ctx.close()
 
 
 @pytest.mark.parametrize("case", ["bf16-gqa", "f32", "bf16-merge-everything"])
@@ -688,11 +757,11 @@ def test_decode_all_layers_in_one_call_equals_one_call_per_layer():
         ctx.close()
 
 
-def _run_multi_layer_decode(w, n, layers, budgets, recents, steps):
+def _run_multi_layer_decode(w, n, layers, budgets, recents, steps, split_rows=0):
     """Several layers in one decode call per step, every head against the oracle at every step.
     Returns the number of evictions per layer."""
     B, L = 1, len(layers)
-    ctx = H.new_ctx(w, B, L, n, sum(budgets) + 8 * L)
+    ctx = H.new_ctx(w, B, L, n, sum(budgets) + 8 * L, split_rows=split_rows)
     caches = {}
     for li, layer in enumerate(layers):
         Q, K, V = H.make_inputs(w, B, layer, n)
@@ -736,6 +805,16 @@ def test_decode_growing_cache_crosses_chunk_boundaries_in_a_multi_layer_call():
     w, n, steps = _small_bf16(True), 250, 275
     budgets = [520, 100]
     ev = _run_multi_layer_decode(w, n, [4, 11], budgets, [130, 25], steps)
+    assert ev[0] == (steps - (budgets[0] - n)) * w.n_kv_heads and ev[1] == steps * w.n_kv_heads
+
+
+def test_decode_growing_cache_becomes_large_in_a_multi_layer_call():
+    """The same two layers with split_rows = 256: layer 0's heads pass from the single-workgroup
+    closing form to the split form while they grow (and gain a second and a third part);
+    layer 1's heads stay small, so both forms run in every launch."""
+    w, n, steps = _small_bf16(True), 250, 275
+    budgets = [520, 100]
+    ev = _run_multi_layer_decode(w, n, [4, 11], budgets, [130, 25], steps, split_rows=256)
     assert ev[0] == (steps - (budgets[0] - n)) * w.n_kv_heads and ev[1] == steps * w.n_kv_heads
 
 

@@ -12,11 +12,11 @@ from tests import helpers as H
 pytestmark = pytest.mark.gpu
 
 
-def _pair_run(w, n, B, L, budgets, steps):
+def _pair_run(w, n, B, L, budgets, steps, split_rows=0):
     """Two contexts with identical state; one steps through d2o_decode_step, the other through
     d2o_decode_step_static.  Returns nothing; asserts bit-identical results at every step."""
     slots = sum(int(np.max(b)) for b in budgets) + 8 * L
-    ctxs = [H.new_ctx(w, B, L, n, slots, out_f32=False) for _ in range(2)]
+    ctxs = [H.new_ctx(w, B, L, n, slots, out_f32=False, split_rows=split_rows) for _ in range(2)]
     for l in range(L):
         Q, K, V = H.make_inputs(w, B, l, n)
         for ctx in ctxs:
@@ -49,6 +49,9 @@ def test_static_scratch_decode_equals_decode_step_then_again_on_a_smaller_input(
                              np.array([260, 130], np.int32)], 6)
     print("call 2: smaller input (one layer, one sequence, budget 48) on the array the first call used", flush=True)
     _pair_run(w, 200, 1, 1, [np.array([48], np.int32)], 5)
+    print("call 3: the first input with the large-head closing form (its part records live in the array too)", flush=True)
+    _pair_run(w, 700, 2, 3, [np.array([520, 300], np.int32), np.array([40, 64], np.int32),
+                             np.array([260, 130], np.int32)], 6, split_rows=256)
 
 
 def test_static_scratch_rejects_a_context_that_does_not_fit():
