@@ -241,6 +241,13 @@ def main():
     da_avg = da_ms / da_n if da_n else None
     dec_gbs = bytes_per_launch / (da_avg * 1e-3) / 1e9 if da_n else 0.0
     step_bytes = bytes_per_launch  # whole decode step, algorithmic (K second touch not counted)
+    # the whole prompt phase of a layer: the attention product above plus the evicted-by-retained
+    # similarity product of Eq. 9 (2 * Le * Lr * d per (sequence, KV head), mean over the layers);
+    # the column sums' second QK^T is overhead of this implementation, not algorithmic work
+    match_flop_layer = float(sum(2.0 * (n - int(s)) * int(s) * d for s in budgets.reshape(-1)) * w.n_kv_heads / L)
+    layer_flop = flop_per_launch + match_flop_layer
+    cs_ms, cs_n = kt["colsum"]
+    passes_ms = (attn_ms / attn_n + cs_ms / cs_n) if attn_n and cs_n else None
     out = {
         "metric": "compressed-KV decode tokens/s (+ prefill-compress ms/layer at N=32k)",
         "value": tokens_per_s, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
@@ -261,6 +268,14 @@ def main():
                      "traffic": measured_traffic(w.cfg, "attn_fwd_bf16"),
                      "algorithmic_flop_per_launch": flop_per_launch,
                      "avg_launch_ms": attn_ms / attn_n if attn_n else None},
+        "roofline_prefill_compress": {
+            "what": "one layer's whole prompt phase (attention, column sums, selection, matching, merge)",
+            "bound": "mfma", "algorithmic_flop_per_layer": layer_flop,
+            "achieved": layer_flop / (prefill_ms / L * 1e-3) / 1e12, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+            "frac": layer_flop / (prefill_ms / L * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+            "attention_and_column_sums_ms": passes_ms,
+            "attention_and_column_sums_frac": (flop_per_launch / (passes_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS
+                                               if passes_ms else None)},
         "roofline_decode": {"kernel": "decode_attend", "bound": "hbm", "achieved": dec_gbs,
                             "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": dec_gbs / PEAK_HBM_GBS,
                             "traffic": measured_traffic(w.cfg, "decode_attend"),
