@@ -176,3 +176,92 @@ def test_full_size_sampled_heads(cfg):
     print(f"  decode: {DECODE_STEPS} steps, worst output err {worst:.2e}, events and cache rows "
           f"identical", flush=True)
     ctx.close()
+
+
+def test_config3_as_benchmarked_allocated_budgets_bf16_outputs_and_32_decode_steps():
+    """Configuration 3 in the shape bench.py times it: all 32 layers in one context, budgets from
+    d2o_allocate_budgets on the library's own densities (they span two orders of magnitude),
+    bf16 attention outputs, every decode step one call over all layers.  The oracle follows
+    the layers with the largest and the smallest budget and one in between, two heads each:
+    token-level stages from its own fp32 scores, then 32 teacher-forced decode steps - events
+    identical at every step, outputs within the bf16 storage bound, final caches identical."""
+    w = synth.WORKLOADS[3]
+    n, G, d, B, L = w.prompt_len, w.group, w.head_dim, w.batch, w.n_layers
+    steps = 32
+    dev = torch.device("cuda:0")
+    slots = w.total_budget() + L + 8
+    ctx = binding.D2O(B, L, w.n_q_heads, w.n_kv_heads, d, n, slots, dtype=w.dtype, beta=w.beta)
+    O = torch.empty((B, w.n_q_heads, n, d), dtype=torch.bfloat16, device=dev)
+    print("prompt attention of all 32 layers", flush=True)
+    for l in range(L):
+        Q, K, V = _layer_on_device(w, l, dev)
+        ctx.d2o_prefill_attend(l, Q, K, V, O)
+    torch.cuda.synchronize()
+    F = ctx.d2o_get_density()
+    budgets = binding.d2o_allocate_budgets(F[0], n, w.total_budget(), 64)
+    want_b = ref.allocate_budgets(F[0], n, w.total_budget(), 64)
+    assert np.array_equal(budgets, want_b) and int(budgets.sum()) == w.total_budget()
+    order = np.argsort(budgets)
+    followed = sorted({int(order[0]), int(order[L // 2]), int(order[-1])})
+    heads = [(0, 5), (0, 26)]
+    print(f"budgets {budgets.min()}..{budgets.max()}; oracle follows layers {followed} "
+          f"(budgets {[int(budgets[l]) for l in followed]}), heads {heads}", flush=True)
+    caches = {}
+    for l in range(L):
+        Q, K, V = _layer_on_device(w, l, dev)
+        bud, rec = int(budgets[l]), int(budgets[l]) // 4
+        if l in followed:
+            drive = ctx.d2o_scores_export(l, n)
+            for (b, h) in heads:
+                Qd = binding.tensor_to_f64(Q[b, h * G:(h + 1) * G])
+                Kd, Vd = binding.tensor_to_f64(K[b, h]), binding.tensor_to_f64(V[b, h])
+                score = np.zeros(n)
+                for g in range(G):
+                    _, s = ref.prefill_attention_head(Qd[g], Kd, Vd)
+                    score += s
+                assert np.abs(drive[b, h] - score).max() <= H.FLOAT_TOL * np.abs(score).max()
+                drive[b, h] = score.astype(np.float32)
+                caches[(l, b, h)] = (Kd, Vd, drive[b, h].astype(np.float64))
+            ctx.d2o_scores_import(l, drive)
+        ctx.d2o_compress_layer(l, K, V, bud, rec)
+        if l in followed:
+            torch.cuda.synchronize()
+            for (b, h) in heads:
+                Kd, Vd, sc = caches[(l, b, h)]
+                cache, ev = ref.compress_head(Kd, Vd, sc, bud, rec, 0, w.dtype)
+                ret, evi, tgt, us, ps = ctx.d2o_prefill_events(l, b, h, n)
+                assert np.array_equal(ret, ev.retained) and np.array_equal(evi, ev.evicted)
+                assert np.array_equal(tgt, ev.target) and np.array_equal(ps, ev.passed)
+                gK, gV, gsc, gp, gtau = ctx.d2o_cache_export(l, b, h, bud + 1)
+                assert np.array_equal(gp, cache.pos) and np.array_equal(gK, cache.K) and np.array_equal(gV, cache.V)
+                caches[(l, b, h)] = cache
+                print(f"  layer {l} head {h}: budget {bud}, evicted {len(evi)}, merged {int(ps.sum())}: identical",
+                      flush=True)
+        del Q, K, V
+    q, k, v = _decode_on_device(w, list(range(L)), steps, dev)
+    out = torch.empty(q[0].shape, dtype=torch.bfloat16, device=dev)
+    worst = 0.0
+    for t in range(steps):
+        ctx.d2o_decode_step(0, L, q[t], k[t], v[t], out)
+        torch.cuda.synchronize()
+        for l in followed:
+            ev_, tg_, us_ = ctx.d2o_last_events(l)
+            bud, rec = int(budgets[l]), int(budgets[l]) // 4
+            for (b, h) in heads:
+                qd = binding.tensor_to_f64(q[t, l, b, h * G:(h + 1) * G])
+                kd, vd = binding.tensor_to_f64(k[t, l, b, h]), binding.tensor_to_f64(v[t, l, b, h])
+                want, e = ref.decode_step_head(caches[(l, b, h)], qd, kd, vd, n + t, bud, rec, 0, w.beta)
+                assert (ev_[b, h], tg_[b, h]) == (e.evicted_pos, e.target_pos), f"step {t} layer {l} head {h}"
+                assert abs(us_[b, h] - e.u_star) < 1e-13
+                got = binding.tensor_to_f64(out[l, b, h * G:(h + 1) * G])
+                bound = H.FLOAT_TOL * np.abs(want).max(axis=-1, keepdims=True) + 2.0 ** -8 * np.abs(want)
+                assert np.all(np.abs(got - want) <= bound), f"step {t} layer {l} head {h}: bf16 output"
+                worst = max(worst, float(np.max(np.abs(got - want) / np.abs(want).max(axis=-1, keepdims=True))))
+    for (l, b, h), cache in caches.items():
+        gK, gV, gsc, gp, gtau = ctx.d2o_cache_export(l, b, h, int(budgets[l]) + 1)
+        assert np.array_equal(gp, cache.pos) and np.array_equal(gK, cache.K) and np.array_equal(gV, cache.V)
+        np.testing.assert_allclose(gsc, cache.score, rtol=1e-12)
+        assert abs(gtau - cache.tau) < 1e-13
+    print(f"  {steps} decode steps over all {L} layers: events and caches identical, worst bf16 output "
+          f"error {worst:.2e} of the row maximum", flush=True)
+    ctx.close()
