@@ -116,7 +116,7 @@ void layout(d2o_ctx* x, char* persistent, char* scratch, size_t* pbytes, size_t*
   const size_t nsub = nch * 4;  // partial results are kept per 64 slots, a quarter of a chunk
   s.take(x->d_rec, bh * nsub * 32);
   s.take(x->d_pacc, bh * nsub * G * d);
-  s.take(x->d_part, bh * nch * kPartRecDoubles);
+  s.take(x->d_part, bh * nch * kPartRecDoubles + L * bh * 16);  // part records, then 16 doubles per head
   s.take(x->d_vecs, L * bh * (G + nc) * d);
   s.take(x->d_cnorm, L * bh * nc);
 

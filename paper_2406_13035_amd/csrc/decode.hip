@@ -124,6 +124,50 @@ __global__ __launch_bounds__(128) void decode_prepare(DecodeArgs a, const T* __r
   if (c < kCand) a.cnorm[lbh * kCand + c] = sqrt(red[c] + red[kCand + c]);  // wavefront 0's sum first
 }
 
+// Softmax maximum and exact normaliser sum_j exp(s_j - max) of each query head of one head, from
+// its sub-chunk records (fixed summation tree), by one workgroup of 256 threads of the launch
+// that wrote the records; result: hn[g] = maximum, hn[G + g] = normaliser.
+template <int G>
+__device__ __forceinline__ void head_normaliser(const DecodeArgs& a, int64_t bh, int ch0, int nsub, double* hn,
+                                                double* dred, double* sred) {
+  constexpr int kRec = rec_doubles(G);
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  double Mg[G], part[G];
+#pragma unroll
+  for (int g = 0; g < G; ++g) Mg[g] = -INFINITY;
+  for (int c = tid; c < nsub; c += 256) {
+    const int64_t x = sub_index(a, bh, ch0, c) * kRec;
+#pragma unroll
+    for (int g = 0; g < G; ++g) Mg[g] = fmax(Mg[g], ld_agent(&a.rec[x + g]));
+  }
+#pragma unroll
+  for (int g = 0; g < G; ++g) Mg[g] = wave_max(Mg[g]);
+  __syncthreads();
+  if (lane == 0) {
+#pragma unroll
+    for (int g = 0; g < G; ++g) dred[w * G + g] = Mg[g];
+  }
+  __syncthreads();
+#pragma unroll
+  for (int g = 0; g < G; ++g) {
+    Mg[g] = fmax(fmax(dred[g], dred[G + g]), fmax(dred[2 * G + g], dred[3 * G + g]));
+    part[g] = 0.0;
+  }
+  for (int c = tid; c < nsub; c += 256) {
+    const int64_t x = sub_index(a, bh, ch0, c) * kRec;
+#pragma unroll
+    for (int g = 0; g < G; ++g) part[g] += ld_agent(&a.rec[x + G + g]) * exp(ld_agent(&a.rec[x + g]) - Mg[g]);
+  }
+#pragma unroll
+  for (int g = 0; g < G; ++g) {
+    const double lg = block_sum(part[g], sred);
+    if (tid == 0) {
+      hn[g] = Mg[g];
+      hn[G + g] = lg;
+    }
+  }
+}
+
 // Closing work of a head, by one workgroup of 256 threads: combine the sub-chunks, update the
 // scores, choose the evicted token and the next candidates, find the merge target and finish the
 // step.  Every load whose address does not depend on a result of this function is issued before
@@ -630,7 +674,6 @@ __global__ __launch_bounds__(256) void decode_attend(DecodeArgs a, OT* __restric
   }
   __syncthreads();
   if (!sh_last) return;
-  if (total > a.big_rows) return;  // a very large head: two more launches close it (decode_close_part / _final)
   // Consumer side of the hand-over.  The other workgroups' results (rec, elog, pacc) are read
   // below through ld_agent only, which goes around this XCD's L2 whatever the compiler does
   // with plain loads; this fence keeps the compiler from moving any load of the closing code
@@ -642,6 +685,14 @@ __global__ __launch_bounds__(256) void decode_attend(DecodeArgs a, OT* __restric
   double* dred = reinterpret_cast<double*>(stage + 4 * 256 * sizeof(float));
   double* sred = dred + D;
   int* ired = reinterpret_cast<int*>(sred + 8);
+  if (total > a.big_rows) {
+    // A very large head: two more launches close it (decode_close_part / _final).  All its
+    // sub-chunk records are there now, so this workgroup leaves them the head's softmax
+    // maxima and exact normalisers (the sweep and summation tree of the single-workgroup form),
+    // while other heads' chunks still stream.
+    head_normaliser<G>(a, int64_t(b) * a.Hkv + hk, mt3, (total + kSub - 1) / kSub, a.hnorm + lbh * 16, dred, sred);
+    return;
+  }
   head_tail<T, OT, D, G>(a, out, ov, li, b, hk, lbh, total, (total + kSub - 1) / kSub, sred, ired, fred, dred,
                          stage + 8192);
 }
@@ -765,7 +816,7 @@ static void decode_scratch_sizes(const d2o_ctx* c, size_t (&sz)[6]) {
   sz[2] = bh * nch * G * d * sizeof(float);                  // one partial output row per chunk and query head
   sz[3] = L * bh * (G + kCand) * d * sizeof(double);
   sz[4] = L * bh * kCand * sizeof(double);
-  sz[5] = bh * nch * kPartRecDoubles * sizeof(double);
+  sz[5] = (bh * nch * kPartRecDoubles + L * bh * 16) * sizeof(double);  // part records, then 16 doubles per head
   for (size_t& x : sz) x = (x + 255) & ~size_t(255);
 }
 
@@ -843,7 +894,8 @@ hipError_t launch_decode(d2o_ctx* c, int layer0, int nl_all, View q, View k, Vie
     // small part of the launch; a head that holds more than about half a percent of the
     // launch's rows (a few giant layers after Eq. 5, or a launch of one layer) would leave the
     // chip waiting for its closing workgroup, and is finished by the split kernels instead.
-    a.big_rows = cf.split_rows > 0 ? cf.split_rows
+    a.hnorm = a.part + size_t(cf.batch) * cf.n_kv_heads * c->nchunk_cap * kPartRecDoubles;
+  a.big_rows = cf.split_rows > 0 ? cf.split_rows
                                    : int(std::min<int64_t>(kMaxAutoSplitRows, std::max<int64_t>(kMinAutoSplitRows, rows / 200)));
     auto shift = [&](View x, int elem_bytes) {  // first layer of this group
       x.ptr = static_cast<char*>(x.ptr) + size_t(g0) * x.sn * elem_bytes;

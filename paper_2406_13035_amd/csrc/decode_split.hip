@@ -7,9 +7,10 @@
 // `big_rows` entries decode_attend therefore stops after its partial results, and two more
 // launches finish the head:
 //
-//   decode_close_part   one workgroup per `part_chunks` chunks of the head: the head's exact
-//                       normaliser (every part recomputes it from the sub-chunk records: a few
-//                       KB per thousand slots), then, for its own chunks only, the partial
+//   decode_close_part   one workgroup per `part_chunks` chunks of the head.  The head's softmax
+//                       maxima and exact normalisers are there already (the head's last
+//                       attention workgroup computed them from the sub-chunk records while
+//                       other heads still streamed); for its own chunks the part does the partial
 //                       output rows, the score update (Eq. 6), its first-evicted entry (Eq. 7-8),
 //                       its four lowest entries for the next step and the candidates' best
 //                       matches (Eq. 9).  Results: one record of kPartRec doubles per part, and
@@ -57,7 +58,6 @@ __global__ __launch_bounds__(256) void decode_close_part(DecodeArgs a) {
   static_assert(kGroup == 1, "a flat index is one chunk");
   __shared__ double em[kMaxPartChunks * 4 * G];  // exp(m_sub - max) / normaliser of the part's sub-chunks
   __shared__ float fred[4 * 256];
-  __shared__ double dred[4 * G];
   __shared__ double sred[8];
   __shared__ int ired[8];
   // grid: x = head, y = flat part index over the layers that can hold large heads (lay_off counts parts here)
@@ -77,36 +77,16 @@ __global__ __launch_bounds__(256) void decode_close_part(DecodeArgs a) {
   const int s_lo = c_lo * 4, s_hi = min(c_hi * 4, nsub);          // its sub-chunks
   const int j_lo = c_lo * kChunk, j_hi = min(c_hi * kChunk, total);  // its slots
   double* prec = a.part + chunk_index(a, bh, ch0, c_lo) * kPartRec;
-  // ---- head maximum and exact normaliser of each query head: the sweep and the summation tree
-  //      of the single-workgroup form
+  // ---- head maximum and exact normaliser of each query head, left by the head's last attention
+  //      workgroup; exp(m_sub - max) / normaliser of the part's sub-chunks goes to LDS
   double Mg[G], Lg[G];
   {
+    const double* hn = a.hnorm + lbh * 16;
 #pragma unroll
-    for (int g = 0; g < G; ++g) Mg[g] = -INFINITY;
-    for (int c = tid; c < nsub; c += 256) {
-      const int64_t x = sub_index(a, bh, ch0, c) * kRec;
-#pragma unroll
-      for (int g = 0; g < G; ++g) Mg[g] = fmax(Mg[g], a.rec[x + g]);
+    for (int g = 0; g < G; ++g) {
+      Mg[g] = hn[g];
+      Lg[g] = hn[G + g];
     }
-#pragma unroll
-    for (int g = 0; g < G; ++g) Mg[g] = wave_max(Mg[g]);
-    if (lane == 0) {
-#pragma unroll
-      for (int g = 0; g < G; ++g) dred[w * G + g] = Mg[g];
-    }
-    __syncthreads();
-#pragma unroll
-    for (int g = 0; g < G; ++g) Mg[g] = fmax(fmax(dred[g], dred[G + g]), fmax(dred[2 * G + g], dred[3 * G + g]));
-    double part[G];
-#pragma unroll
-    for (int g = 0; g < G; ++g) part[g] = 0.0;
-    for (int c = tid; c < nsub; c += 256) {
-      const int64_t x = sub_index(a, bh, ch0, c) * kRec;
-#pragma unroll
-      for (int g = 0; g < G; ++g) part[g] += a.rec[x + G + g] * exp(a.rec[x + g] - Mg[g]);
-    }
-#pragma unroll
-    for (int g = 0; g < G; ++g) Lg[g] = block_sum(part[g], sred);
     for (int i = tid; i < (s_hi - s_lo) * G; i += 256) {
       const int c = s_lo + i / G, g = i % G;
       double mg = Mg[0], lg = Lg[0];
