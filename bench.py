@@ -304,6 +304,33 @@ def main():
         out["qkv_project"] = {"ms_per_layer": q_ms, "hidden": hidden, "tflops": q_flop / (q_ms * 1e-3) / 1e12,
                               "frac_of_bf16_peak": q_flop / (q_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS}
         del X, Wm
+    # ---- outside the timed region: a block of new tokens on one layer's compressed cache
+    #      (d2o_append_chunk) in the shape of the multi-turn experiment of the appendix: budget
+    #      2048 = 48 heavy hitters + 2000 recent, turns of 256 tokens, the workload's heads
+    if w.dtype == "bf16" and not args.layers:
+        m, a_budget, a_recent, a_n = 256, 2048, 2000, 4096
+        actx = binding.D2O(w.batch, 1, w.n_q_heads, w.n_kv_heads, d, a_n, a_budget + m + 8, dtype=w.dtype,
+                           beta=w.beta, max_append=m)
+        ga = torch.Generator(device=dev)
+        ga.manual_seed(synth.BASE_SEED + 23)
+        mk = lambda *shape: torch.randn(*shape, generator=ga, device=dev, dtype=torch.float32).to(torch.bfloat16)
+        Qa, Ka, Va = mk(w.batch, w.n_q_heads, a_n, d), mk(w.batch, w.n_kv_heads, a_n, d), mk(w.batch, w.n_kv_heads, a_n, d)
+        actx.d2o_prefill_compress(0, Qa, Ka, Va, a_budget, a_recent)
+        Qb, Kb, Vb = mk(w.batch, w.n_q_heads, m, d), mk(w.batch, w.n_kv_heads, m, d), mk(w.batch, w.n_kv_heads, m, d)
+        Ob = torch.empty_like(Qb)
+        actx.d2o_append_chunk(0, Qb, Kb, Vb, Ob)          # warm-up turn
+        eva = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+        eva[0].record()
+        turns = 3
+        for _ in range(turns):
+            actx.d2o_append_chunk(0, Qb, Kb, Vb, Ob)
+        eva[1].record()
+        torch.cuda.synchronize()
+        a_ms = eva[0].elapsed_time(eva[1]) / turns
+        out["append_chunk"] = {"ms_per_layer_and_block": a_ms, "block_tokens": m, "budget": a_budget,
+                               "recent": a_recent, "tokens_per_s_one_layer": w.batch * m / (a_ms * 1e-3)}
+        actx.close()
+        del Qa, Ka, Va, Qb, Kb, Vb, Ob
     if args.zero_data_probe:
         probe = {}
         for tag, (q, k, v) in (("workload_data", (Q[0], K[0], V[0])),

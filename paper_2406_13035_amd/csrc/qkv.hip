@@ -23,7 +23,11 @@ namespace d2o {
 namespace {
 
 constexpr int kBM = 256, kBN = 128, kBK = 32;
-constexpr int kLd = kBK + 8;                 // LDS pitch (elements) of the operand tiles
+constexpr int kLd = kBK;                     // LDS pitch (elements) of the operand tiles: 64 bytes = four 16-byte chunks,
+                                             // chunk k of row r stored at position k ^ ((r >> 2) & 3): the 16 lanes of a
+                                             // 128-bit access phase then cover all 64 banks once, for the staging stores
+                                             // (four consecutive rows x four chunks) and for the operand reads (sixteen
+                                             // consecutive rows, one chunk)
 constexpr int kLdC = kBN + 8;                // LDS pitch of the result tile
 constexpr int kOperandElems = 2 * (kBM + kBN) * kLd;  // two stages
 constexpr int kResultElems = kBM / 2 * kLdC;          // the result tile passes through LDS in two halves
@@ -64,50 +68,51 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-  // staging: a tile row holds 64 bytes = four 16-byte chunks; 1024 chunks of X and 512 of W
-  u32x4 ra[4], rb[2];
-  auto issue = [&](int kt) {
+  // staging: a tile row holds 64 bytes = four 16-byte chunks; 1024 chunks of X and 512 of W.
+  // Two register sets: the loads of k-tile t + 2 are issued while tile t is multiplied, and a
+  // tile moves from its registers to LDS one iteration after that, so a load has two
+  // iterations (and the other resident workgroup's) to arrive; one iteration is shorter than
+  // an L2 round trip under load.
+  auto swz = [](int row, int col) { return col ^ (((row >> 2) & 3) << 3); };  // col: element offset of a 16-byte chunk
+  struct Regs {
+    u32x4 a[4], b[2];
+  } R0, R1;
+  auto issue = [&](int kt, Regs& R) {
     const int k0 = kt * kBK;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const int c = tid + 256 * i, row = c >> 2, col = (c & 3) * 8;
-      ra[i] = *reinterpret_cast<const u32x4*>(Xb + int64_t(min(row0 + row, a.M - 1)) * a.hidden + k0 + col);
+      R.a[i] = *reinterpret_cast<const u32x4*>(Xb + int64_t(min(row0 + row, a.M - 1)) * a.hidden + k0 + col);
     }
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
       const int c = tid + 256 * i, row = c >> 2, col = (c & 3) * 8;
-      rb[i] = *reinterpret_cast<const u32x4*>(Wb + int64_t(row) * a.hidden + k0 + col);
+      R.b[i] = *reinterpret_cast<const u32x4*>(Wb + int64_t(row) * a.hidden + k0 + col);
     }
   };
-  auto stage = [&](int st) {
+  auto stage = [&](int st, const Regs& R) {
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const int c = tid + 256 * i, row = c >> 2, col = (c & 3) * 8;
-      *reinterpret_cast<u32x4*>(As(st) + row * kLd + col) = ra[i];
+      *reinterpret_cast<u32x4*>(As(st) + row * kLd + swz(row, col)) = R.a[i];
     }
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
       const int c = tid + 256 * i, row = c >> 2, col = (c & 3) * 8;
-      *reinterpret_cast<u32x4*>(Bs(st) + row * kLd + col) = rb[i];
+      *reinterpret_cast<u32x4*>(Bs(st) + row * kLd + swz(row, col)) = R.b[i];
     }
   };
-  const int nk = a.hidden / kBK;
-  issue(0);
-  stage(0);
-  __syncthreads();
-  for (int kt = 0; kt < nk; ++kt) {
-    const int st = kt & 1;
-    if (kt + 1 < nk) issue(kt + 1);
-    // all operand reads of the stage first, then its sixteen matrix instructions back to back
+  // all operand reads of a stage first, then its sixteen matrix instructions back to back
+  auto multiply = [&](int st) {
     bf16x8 av[kBK / 16][2], bv[kBK / 16][4];
 #pragma unroll
     for (int ks = 0; ks < kBK / 16; ++ks) {
 #pragma unroll
       for (int i = 0; i < 2; ++i)
-        av[ks][i] = *reinterpret_cast<const bf16x8*>(As(st) + (w * 64 + i * 32 + m) * kLd + ks * 16 + h * 8);
+        av[ks][i] = *reinterpret_cast<const bf16x8*>(As(st) + (w * 64 + i * 32 + m) * kLd + swz(m, ks * 16 + h * 8));
 #pragma unroll
       for (int j = 0; j < 4; ++j)
-        bv[ks][j] = *reinterpret_cast<const bf16x8*>(Bs(st) + (j * 32 + m) * kLd + ks * 16 + h * 8);
+        bv[ks][j] = *reinterpret_cast<const bf16x8*>(Bs(st) + (j * 32 + m) * kLd + swz(m, ks * 16 + h * 8));
     }
 #pragma unroll
     for (int ks = 0; ks < kBK / 16; ++ks)
@@ -116,7 +121,23 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 #pragma unroll
         for (int j = 0; j < 4; ++j)
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[ks][i], bv[ks][j], acc[i][j], 0, 0, 0);
-    if (kt + 1 < nk) stage(st ^ 1);
+  };
+  const int nk = a.hidden / kBK;
+  issue(0, R0);
+  if (nk > 1) issue(1, R1);
+  stage(0, R0);
+  __syncthreads();
+  for (int kt = 0; kt < nk; kt += 2) {
+    // LDS stage 0 holds tile kt, R1 tile kt + 1
+    if (kt + 2 < nk) issue(kt + 2, R0);
+    multiply(0);
+    if (kt + 1 < nk) stage(1, R1);
+    __syncthreads();
+    if (kt + 1 >= nk) break;
+    // LDS stage 1 holds tile kt + 1, R0 tile kt + 2
+    if (kt + 3 < nk) issue(kt + 3, R1);
+    multiply(1);
+    if (kt + 2 < nk) stage(0, R0);
     __syncthreads();
   }
   // ---- rotary embedding on queries and keys.  Accumulator layout: acc[i][j][r] is token
