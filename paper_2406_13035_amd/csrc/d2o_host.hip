@@ -112,6 +112,13 @@ void layout(d2o_ctx* x, char* persistent, char* scratch, size_t* pbytes, size_t*
   s.take(x->app_pos, ap * bh * np);
   s.take(x->app_rank, ap * bh * np);
   s.take(x->app_n, ap * bh);
+  x->ap_maxq = ap ? int((size_t(c.max_append) * G + 7) / 8 * 8) : 0;
+  x->ap_nch = ap ? int(std::min<int64_t>(np, c.slots_per_seq) / kChunk + 2) : 0;
+  s.take(x->ap_q, ap * bh * x->ap_maxq * d);
+  s.take(x->ap_stat, ap * x->ap_nch * bh * x->ap_maxq * 2);
+  s.take(x->ap_norm, ap * bh * x->ap_maxq * 2);
+  s.take(x->ap_out, ap * x->ap_nch * bh * x->ap_maxq * d);
+  s.take(x->ap_spart, ap * 16 * bh * x->ap_nch * kChunk);
   s.take(x->d_logit, nch * B * Hq * kChunk);
   const size_t nsub = nch * 4;  // partial results are kept per 64 slots, a quarter of a chunk
   s.take(x->d_rec, bh * nsub * 32);
@@ -610,17 +617,10 @@ int d2o_append_chunk(d2o_ctx* x, int32_t layer, d2o_view Q, d2o_view K, d2o_view
   if (st.phase != kReady) return fail(x, D2O_ERR_STATE, "layer not compressed");
   hipStream_t s = static_cast<hipStream_t>(stream);
   const int es = x->esize, os = c.out_f32 ? 4 : x->esize;
-  // ---- Eq. 6 token by token, no eviction inside the block: token i as a generation step over the
-  //      cache grown by the block's earlier tokens
-  for (int i = 0; i < m; ++i) {
-    auto tok = [&](const d2o_view& v, int bytes) {  // the block's token i as a [layer][b][head][d] tensor of one layer
-      View t = to_view(v);
-      t.ptr = static_cast<char*>(t.ptr) + size_t(i) * v.stride_n * bytes;
-      t.sn = 0;
-      return t;
-    };
-    const hipError_t e = launch_decode(x, layer, 1, tok(Q, es), tok(K, es), tok(V, es), tok(O, os),
-                                       st.next_pos + i, s, nullptr, i + 1);
+  // ---- the block's rows appended, every token's attention over the cache and the block's earlier
+  //      tokens, Eq. 6 for every token; no eviction inside the block
+  {
+    const hipError_t e = launch_block_attend(x, layer, to_view(Q), to_view(K), to_view(V), to_view(O), m, st.next_pos, s);
     if (e != hipSuccess) return fail(x, D2O_ERR_HIP, std::string("append, attention: ") + hipGetErrorString(e));
   }
   st.next_pos += m;

@@ -114,6 +114,13 @@ struct d2o_ctx {
   int32_t* app_pos = nullptr;    // [B][Hkv][npad] token positions, ascending
   int32_t* app_rank = nullptr;   // [B][Hkv][npad] rank of every cache slot's position
   int32_t* app_n = nullptr;      // [B][Hkv] entries
+  // block attention of d2o_append_chunk (contexts with max_append > 1)
+  int32_t ap_maxq = 0, ap_nch = 0;  // queries per head (max_append * G, rounded up to 8) and chunks per head the arrays hold
+  double* ap_q = nullptr;        // [B][Hkv][ap_maxq][d] the block's queries as fp64
+  double* ap_stat = nullptr;     // [ap_nch][B][Hkv][ap_maxq][2] per chunk: softmax maximum and exp-sum of every query
+  double* ap_norm = nullptr;     // [B][Hkv][ap_maxq][2] maximum and normaliser of every query
+  float* ap_out = nullptr;       // [ap_nch][B][Hkv][ap_maxq][d] partial outputs per chunk
+  double* ap_spart = nullptr;    // [16 query slices][B][Hkv][ap_nch * 256] per row: sum of the slice's probabilities
   // decode
   double* d_logit = nullptr;     // [nchunk][B][Hkv][G][256] exp(logit - sub-chunk max), chunk-major
   double* d_rec = nullptr;       // [nchunk][B][Hkv][4][32] per 64 slots: softmax maxima and sums, candidates' best cosine and slot
@@ -170,14 +177,14 @@ hipError_t launch_gather(d2o_ctx* c, int layer, View K, View V, int n, hipStream
 hipError_t launch_match(d2o_ctx* c, int layer, View K, int n, hipStream_t s);
 hipError_t launch_threshold_group(d2o_ctx* c, int layer, int n, hipStream_t s, bool append = false);
 hipError_t launch_cache_sort(d2o_ctx* c, int layer, hipStream_t s);  // cache -> app_* in ascending position
+// A block of m tokens: rows appended, attention and Eq. 6 for every token of the block, nothing evicted.
+hipError_t launch_block_attend(d2o_ctx* c, int layer, View q, View k, View v, View out, int m, int first_pos,
+                               hipStream_t s);
 hipError_t launch_merge(d2o_ctx* c, int layer, View K, View V, int n, hipStream_t s);
 // static_scratch: nullptr = the context's scratch workspace; otherwise the device address of the
 // library's static scratch array, which then holds the step's partial results and operands
-// extra_rows > 0: the caches may already hold up to that many rows beyond their budgets and
-// nothing is evicted (a token of a d2o_append_chunk block)
 hipError_t launch_decode(d2o_ctx* c, int layer0, int nl, View q, View k, View v, View out,
-                         int new_pos, hipStream_t s, unsigned char* static_scratch = nullptr,
-                         int extra_rows = 0);
+                         int new_pos, hipStream_t s, unsigned char* static_scratch = nullptr);
 hipError_t static_scratch_address(unsigned char** out);  // per device; first call per device looks it up
 size_t decode_static_scratch_need(const d2o_ctx* c);     // bytes of it a decode step of this context uses
 size_t decode_static_scratch_capacity();

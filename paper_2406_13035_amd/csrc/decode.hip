@@ -284,7 +284,7 @@ __device__ __forceinline__ void head_tail(const DecodeArgs& a, OT* __restrict__ 
     }
   }
   // ---- score pass, set-up
-  const bool evict = !a.no_evict && total > mt[1];
+  const bool evict = total > mt[1];
   const int recent = mt[2];
   Best ev{0.0, 0, -1};
   Best low[kCand + 1];
@@ -828,7 +828,7 @@ size_t decode_static_scratch_need(const d2o_ctx* c) {
 size_t decode_static_scratch_capacity() { return kStaticScratchBytes; }
 
 hipError_t launch_decode(d2o_ctx* c, int layer0, int nl_all, View q, View k, View v, View out, int new_pos,
-                         hipStream_t s, unsigned char* static_scratch, int extra_rows) {
+                         hipStream_t s, unsigned char* static_scratch) {
   const d2o_config& cf = c->cfg;
   DecodeArgs a;
   a.ccount = c->ccount;
@@ -869,7 +869,6 @@ hipError_t launch_decode(d2o_ctx* c, int layer0, int nl_all, View q, View k, Vie
   a.n_sink = cf.n_sink;
   a.out_f32 = cf.out_f32;
   a.merge_average = cf.merge_average;
-  a.no_evict = extra_rows > 0 ? 1 : 0;
   a.part_chunks = cf.split_rows > 0 ? std::min(8, std::max(1, cf.split_rows / (4 * kChunk))) : 8;
   a.beta = cf.beta;
   a.tau_force = cf.tau_force;
@@ -885,8 +884,8 @@ hipError_t launch_decode(d2o_ctx* c, int layer0, int nl_all, View q, View k, Vie
       chunk_id[i] = i;
       mc[i] = 1;
       for (const auto& mt : c->layers[a.layer0 + i].meta) {
-        mc[i] = std::max(mc[i], (mt.budget + std::max(1, extra_rows) + kGroup * kChunk - 1) / (kGroup * kChunk));
-        rows += mt.budget + std::max(1, extra_rows);
+        mc[i] = std::max(mc[i], (mt.budget + 1 + kGroup * kChunk - 1) / (kGroup * kChunk));
+        rows += mt.budget + 1;
       }
     }
     // Which heads are too large for one closing workgroup.  A head's last workgroup closes it

@@ -47,7 +47,6 @@ struct DecodeArgs {
   int part_chunks;    // chunks per workgroup of decode_close_part
   double* part;       // [chunk][B][Hkv][kPartRecDoubles] part records (at a part's first chunk)
   double* hnorm;      // [L][B][Hkv][16] of a head closed in parts: [0..G) softmax maxima, [G..2G) exact normalisers
-  int no_evict;       // 1: a token inside a block of d2o_append_chunk: the caches grow past their budgets
   double beta, tau_force;
   int32_t lay_off[kMaxLayersPerCall + 1];  // first flat chunk-group index of each entry of lay_id
   int32_t lay_id[kMaxLayersPerCall];       // layers of the call (relative), most chunks first

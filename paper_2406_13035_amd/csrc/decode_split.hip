@@ -343,7 +343,7 @@ __global__ __launch_bounds__(256) void decode_close_final(DecodeArgs a, OT* __re
       }
     }
   }
-  const bool evict = !a.no_evict && total > mt[1];
+  const bool evict = total > mt[1];
   close_head<T, D>(a, lbh, slot0, total, evict, ev, low, cl, told, sred, ired, dred, wcm_u, wcm_ps, park_kv);
 }
 
