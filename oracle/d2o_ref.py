@@ -48,7 +48,35 @@ def round_storage(x: np.ndarray, dtype: str) -> np.ndarray:
         lsb = (b >> np.uint64(45)) & np.uint64(1)
         r = (b + np.uint64((1 << 44) - 1) + lsb) & ~np.uint64((1 << 45) - 1)
         return r.view(np.float64).copy()
+    if dtype == "fp8":
+        return quantise_fp8_rows(round_storage(x, "bf16"))
     raise ValueError(dtype)
+
+
+def quantise_fp8_rows(x: np.ndarray) -> np.ndarray:
+    """The fp8 cache encoding (the conclusion of the paper names the combination with KV-cache
+    quantisation as future work and defines no format; this is the reading taken).  A cache row
+    (last axis) is stored as d codes of the 8-bit floating-point format E4M3 (1 sign, 4 exponent
+    bits with bias 7, 3 fraction bits, subnormals down to 2^-9, largest magnitude 448, no
+    infinities) and one power of two per row:
+      e   = the smallest integer with max|x| * 2^-e <= 448 (0 for an all-zero row),
+      q_i = x_i * 2^-e rounded to the nearest E4M3 value, ties to the even fraction,
+    and the row then holds the values q_i * 2^e, which is what this function returns (fp64).
+    The cache's logical type stays the input type: "fp8" storage rounds a row to bf16 first and
+    encodes that (round_storage), so prompt-phase rows, new tokens and merged rows all enter the
+    cache the same way."""
+    x = np.ascontiguousarray(x, dtype=np.float64)
+    if x.ndim == 1:
+        return quantise_fp8_rows(x[None, :])[0]
+    amax = np.abs(x).max(axis=-1, keepdims=True)
+    frac, ex = np.frexp(amax)                      # amax = frac * 2^ex, 0.5 <= frac < 1; 448 = 0.875 * 2^9
+    e = np.where(frac <= 0.875, ex - 9, ex - 8)
+    e = np.where(amax > 0.0, e, 0)
+    y = np.ldexp(x, -e)                            # exact; |y| <= 448
+    _, ey = np.frexp(y)                            # |y| in [2^(ey-1), 2^ey)
+    E = np.maximum(ey - 1, -6)                     # binade of y, the subnormal range counts as binade -6
+    q = np.ldexp(np.rint(np.ldexp(y, 3 - E)), E - 3)   # spacing 2^(E-3); rint rounds ties to even
+    return np.ldexp(q, e) + 0.0                    # (+ 0.0: a negative zero becomes zero)
 
 
 # --------------------------------------------------------------------------- upstream: Q, K, V from the hidden states
@@ -418,6 +446,8 @@ def compress_head(K, V, score, budget: int, recent: int, n_sink: int = 0,
     if not math.isnan(tau_force):
         passed = u_star >= tau_force
     Kc, Vc, _ = merge(K[ret], V[ret], K[evi], V[evi], u_star, t, passed, storage, weighted)
+    if storage == "fp8":    # every row that enters the cache is encoded, the unmerged ones too
+        Kc, Vc = round_storage(Kc, storage), round_storage(Vc, storage)
     cache = HeadCache(Kc, Vc, score[ret].copy(), ret.copy(), tau, storage)
     ev = PrefillEvents(ret, evi, ret[t] if len(evi) else np.zeros(0, dtype=np.int64),
                        u_star, passed, tau)
@@ -448,8 +478,12 @@ def decode_step_head(cache: HeadCache, q, k_new, v_new, new_pos: int, budget: in
     Mutates `cache`; returns (out [G, d], DecodeEvent)."""
     q = np.asarray(q, dtype=np.float64)
     d = q.shape[1]
-    cache.K = np.vstack([cache.K, np.asarray(k_new, dtype=np.float64)[None, :]])
-    cache.V = np.vstack([cache.V, np.asarray(v_new, dtype=np.float64)[None, :]])
+    k_new = np.asarray(k_new, dtype=np.float64)
+    v_new = np.asarray(v_new, dtype=np.float64)
+    if cache.storage == "fp8":   # the new row is encoded when it enters the cache, before it is attended to
+        k_new, v_new = round_storage(k_new, "fp8"), round_storage(v_new, "fp8")
+    cache.K = np.vstack([cache.K, k_new[None, :]])
+    cache.V = np.vstack([cache.V, v_new[None, :]])
     cache.score = np.append(cache.score, 0.0)
     cache.pos = np.append(cache.pos, new_pos)
     root_d = np.sqrt(float(d))
@@ -532,6 +566,8 @@ def append_chunk_head(cache: HeadCache, q, k_new, v_new, first_pos: int, budget:
     G, m, d = q.shape
     root_d = np.sqrt(float(d))
     out = np.empty_like(q)
+    if cache.storage == "fp8":   # rows are encoded when they enter the cache
+        k_new, v_new = round_storage(k_new, "fp8"), round_storage(v_new, "fp8")
     for i in range(m):
         cache.K = np.vstack([cache.K.reshape(-1, d), k_new[i][None, :]])
         cache.V = np.vstack([cache.V.reshape(-1, d), v_new[i][None, :]])

@@ -715,3 +715,103 @@ def test_qkv_projection_layout_and_library_matmul():
     E = np.zeros((1, hidden)); E[0, 3] = 1.0
     Qe, Ke, Ve = ref.qkv_project(E, W, Hq, Hkv, d)
     np.testing.assert_allclose(Ve[0, 0], W[(Hq + Hkv) * d:(Hq + Hkv + 1) * d, 3], rtol=0, atol=0)
+
+
+# ------------------------------------------------------------------ fp8 cache encoding
+
+def _e4m3_values():
+    """Every finite value of the 8-bit format E4M3 (sign, 4 exponent bits with bias 7, 3 fraction
+    bits; exponent field 0 = subnormal; the all-ones code with fraction 7 is NaN), built from the
+    format's definition, not from the oracle."""
+    vals = []
+    for code in range(256):
+        sign, ef, fr = code >> 7, (code >> 3) & 15, code & 7
+        if ef == 15 and fr == 7:
+            continue
+        mag = fr / 8.0 * 2.0 ** -6 if ef == 0 else (1.0 + fr / 8.0) * 2.0 ** (ef - 7)
+        vals.append(-mag if sign else mag)
+    return np.array(sorted(set(vals)))
+
+
+def test_fp8_rows_grid_values_are_fixed_points_and_midpoints_round_to_even():
+    grid = _e4m3_values()
+    assert grid.size == 253 and grid.max() == 448.0 and grid[grid > 0].min() == 2.0 ** -9
+    # a row whose largest magnitude is 448 gets the scale 2^0: every grid value must come back unchanged
+    for v in grid:
+        assert ref.quantise_fp8_rows(np.array([v, 448.0]))[0] == v
+    pos = grid[grid >= 0]
+    for a, b in zip(pos[:-1], pos[1:]):
+        got = ref.quantise_fp8_rows(np.array([(a + b) / 2, 448.0]))[0]
+        # ties go to the value with the even fraction: of two neighbours exactly one is an even multiple of the spacing
+        even = a if round(a / (b - a)) % 2 == 0 else b
+        assert got == even, (a, b, got)
+        assert ref.quantise_fp8_rows(np.array([a + 0.49 * (b - a), 448.0]))[0] == a
+        assert ref.quantise_fp8_rows(np.array([a + 0.51 * (b - a), 448.0]))[0] == b
+        assert ref.quantise_fp8_rows(np.array([-(a + 0.51 * (b - a)), 448.0]))[0] == -b
+
+
+def test_fp8_rows_match_the_library_cast_scale_is_minimal_and_commutes_with_powers_of_two():
+    rng = np.random.default_rng(11)
+    x = rng.standard_normal((500, 128)) * np.exp(3 * rng.standard_normal((500, 1)))
+    x = ref.round_storage(x, "bf16")                       # what enters the cache: bf16 rows
+    x[7] = 0.0                                             # an all-zero row stays zero
+    x[8, :] = 0.0
+    x[8, 5] = -3.0                                         # a row with one element
+    q = ref.quantise_fp8_rows(x)
+    assert np.array_equal(q[7], np.zeros(128)) and q[8, 5] == -3.0
+    amax = np.abs(x).max(-1)
+    nz = amax > 0
+    # the scale: the smallest power of two that brings the row's largest magnitude to 448 or below
+    # (found here by search), and every encoded element is a grid value times that power
+    grid = set(_e4m3_values().tolist())
+    for r, qr, a in zip(x[nz][:100], q[nz][:100], amax[nz][:100]):
+        e = next(k for k in range(-80, 80) if a * 2.0 ** -k <= 448.0)
+        assert a * 2.0 ** -(e - 1) > 448.0
+        assert all(v in grid for v in (qr * 2.0 ** -e).tolist())
+    # against torch's float8_e4m3fn cast of the scaled row (bf16 inputs: the scaled values are exact in fp32)
+    for r in x[nz][:200]:
+        a = np.abs(r).max()
+        fr, ex = np.frexp(a)
+        e = int(ex - 9 if fr <= 0.875 else ex - 8)
+        y = torch.tensor(np.ldexp(r, -e), dtype=torch.float32)
+        assert float(y.abs().max()) <= 448.0 and float(y.abs().max()) > 224.0
+        want = np.ldexp(y.to(torch.float8_e4m3fn).to(torch.float64).numpy(), e)
+        assert np.array_equal(ref.quantise_fp8_rows(r), want)
+    # error bound: half a spacing, i.e. 2^-4 relative for normal results, 2^-10 of the scale below
+    err = np.abs(q - x)
+    assert np.all(err <= np.maximum(2.0 ** -4 * np.abs(x), 2.0 ** -10 * (np.abs(q).max(-1, keepdims=True) / 224.0)))
+    # idempotent, odd, and commuting with powers of two
+    assert np.array_equal(ref.quantise_fp8_rows(q), q)
+    assert np.array_equal(ref.quantise_fp8_rows(-x), -q)
+    assert np.array_equal(ref.quantise_fp8_rows(x * 2.0 ** -7), q * 2.0 ** -7)
+    assert np.array_equal(ref.round_storage(x, "fp8"), q)
+
+
+def test_fp8_cache_every_row_is_encoded_and_decode_reads_the_encoded_rows():
+    """storage = "fp8": after prompt compression every cache row (merged or not) is a fixed point
+    of the encoding; a generation step encodes the new row before attending to it, so its
+    output is full attention over the encoded rows (the library's SDPA on them); with the
+    threshold at +inf (pure eviction) the surviving rows are never rewritten."""
+    rng = np.random.default_rng(5)
+    n, d, budget, recent = 90, 16, 30, 8
+    K = ref.round_storage(rng.standard_normal((n, d)) * 2, "bf16")
+    V = ref.round_storage(rng.standard_normal((n, d)), "bf16")
+    score = rng.random(n)
+    cache, ev = ref.compress_head(K, V, score, budget, recent, 0, "fp8")
+    assert np.array_equal(ref.quantise_fp8_rows(cache.K), cache.K) and np.array_equal(ref.quantise_fp8_rows(cache.V), cache.V)
+    same, _ = ref.compress_head(K, V, score, budget, recent, 0, "bf16")
+    assert np.array_equal(cache.pos, same.pos)                                  # selection does not depend on storage
+    assert np.array_equal(cache.K, ref.round_storage(same.K, "fp8"))            # the encoded bf16 rows
+    pure, _ = ref.compress_head(K, V, score, budget, recent, 0, "fp8", tau_force=float("inf"))
+    assert np.array_equal(pure.K, ref.quantise_fp8_rows(K[pure.pos]))
+    q = ref.round_storage(rng.standard_normal((1, d)), "bf16")
+    k_new = ref.round_storage(rng.standard_normal(d) * 2, "bf16")
+    v_new = ref.round_storage(rng.standard_normal(d), "bf16")
+    rows_K = np.vstack([pure.K, ref.quantise_fp8_rows(k_new)[None]])
+    rows_V = np.vstack([pure.V, ref.quantise_fp8_rows(v_new)[None]])
+    out, e = ref.decode_step_head(pure, q, k_new, v_new, n, budget, recent, 0, 0.5, tau_force=float("inf"))
+    want = torch.nn.functional.scaled_dot_product_attention(
+        torch.tensor(q)[None], torch.tensor(rows_K)[None], torch.tensor(rows_V)[None]).numpy()[0]
+    np.testing.assert_allclose(out, want, rtol=1e-12, atol=1e-14)
+    assert e.evicted_pos >= 0 and e.target_pos == -1
+    assert np.array_equal(ref.quantise_fp8_rows(pure.K), pure.K) and pure.K.shape[0] == budget
