@@ -163,6 +163,10 @@ def main():
                          "kernels of layer 0 on the workload's data and on all-zero Q, K, V (same "
                          "instruction stream; the difference is what the chip's power management "
                          "takes for operands that toggle)")
+    ap.add_argument("--cache-fp8", action="store_true",
+                    help="run the workload with the fp8 cache encoding (E4M3 codes and one power of two "
+                         "per row) instead of a cache in the tensors' dtype; the decode roofline then "
+                         "counts 2 * d + 2 + 8 bytes per slot")
     ap.add_argument("--split-rows", type=int, default=0,
                     help="tuning aid: the context's split_rows (entries above which a head's closing "
                          "work in a generation step is split over workgroups); 0 = the library's default")
@@ -186,7 +190,8 @@ def main():
     dq, dk, dv = generate_decode(w, dsteps, dev)
     slots = w.total_budget() + w.n_layers + 8
     ctx = binding.D2O(w.batch, w.n_layers, w.n_q_heads, w.n_kv_heads, w.head_dim, w.prompt_len,
-                      slots, dtype=w.dtype, n_sink=0, beta=w.beta, split_rows=args.split_rows)
+                      slots, dtype=w.dtype, n_sink=0, beta=w.beta, split_rows=args.split_rows,
+                      cache_fp8=args.cache_fp8)
     O = torch.empty_like(Q[0])
     dout = torch.empty_like(dq[0])
     torch.cuda.synchronize()
@@ -211,6 +216,7 @@ def main():
     wall = time.perf_counter() - t0
     kt = {k: ctx.d2o_timing_read(k) for k in binding.KERNEL_IDS}
     ctx.d2o_timing_enable(False)
+    misses = ctx.d2o_candidate_misses()  # of the last pass (d2o_reset clears the counter)
     # the same decode steps issued as one call per layer (a caller that interleaves the layers
     # with its own work), continuing on the caches of the last step; outside the timed region
     per_layer_steps = 0 if (args.layers or args.skip_per_layer_decode) else min(32, dsteps)
@@ -236,7 +242,8 @@ def main():
     # written, per KV head; slots = budget (+1) per layer.
     es = 2 if w.dtype == "bf16" else 4
     slots_b = budgets.sum(axis=1) + L
-    bytes_per_launch = float(sum(int(s) for s in slots_b) * w.n_kv_heads * (2 * d * es + 8))
+    row_bytes = 2 * d + 2 if args.cache_fp8 else 2 * d * es  # K and V row (fp8: codes and the two powers of two)
+    bytes_per_launch = float(sum(int(s) for s in slots_b) * w.n_kv_heads * (row_bytes + 8))
     da_ms, da_n = kt["decode_attend"]
     da_avg = da_ms / da_n if da_n else None
     dec_gbs = bytes_per_launch / (da_avg * 1e-3) / 1e9 if da_n else 0.0
@@ -256,6 +263,7 @@ def main():
         "config": {"workload": f"config {w.cfg}: {w.name}", "batch": w.batch, "layers": L,
                    "q_heads": w.n_q_heads, "kv_heads": w.n_kv_heads, "head_dim": d, "prompt_len": n,
                    "decode_steps": dsteps, "total_budget": w.total_budget(),
+                   "cache": "fp8 (E4M3 codes + one power of two per row)" if args.cache_fp8 else w.dtype,
                    "layer_budgets_seq0": [int(x) for x in budgets[0]],
                    "density_F_seq0_min_max": [float(F[0].min()), float(F[0].max())]},
         "prefill_compress_ms_per_layer": prefill_ms / L,
@@ -282,6 +290,8 @@ def main():
                             "algorithmic_bytes_per_launch": bytes_per_launch,
                             "avg_launch_ms": da_avg},
         "kernel_ms_per_launch": {k: (v[0] / v[1] if v[1] else None) for k, v in kt.items()},
+        # evictions of the last pass whose token was not among the candidates predicted a step ahead
+        "decode_candidate_misses": {"misses": int(misses), "head_steps": int(L * w.batch * w.n_kv_heads * dsteps)},
     }
     # ---- outside the timed region: the upstream step (Sec. 3 Eq. 1 + rotary embedding) at the
     #      workload's shape with the hidden size of the model the shape comes from (heads * d)

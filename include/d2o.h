@@ -77,6 +77,14 @@ typedef struct {
                           /* of the rows the launch streams, within [8192, 16384]).          */
                           /* Otherwise at least 256.  A tuning knob: events and scores do    */
                           /* not depend on it, outputs only in fp32 summation order.         */
+  int32_t cache_fp8;      /* 1: the cache stores a K or V row as d codes of the 8-bit float   */
+                          /* format E4M3 and one power of two per row (the smallest that      */
+                          /* brings the row's largest magnitude to 448 or below; round to     */
+                          /* nearest even).  Rows are encoded when they enter the cache (after */
+                          /* prompt compression, new tokens before they are attended to,      */
+                          /* merged rows); every read sees the decoded values.  The paper      */
+                          /* names KV-cache quantisation as future work and fixes no format.   */
+                          /* Needs dtype D2O_BF16 and max_append <= 1.  0: cache in `dtype`.    */
 } d2o_config;
 
 /* A strided tensor whose last dimension (d) is contiguous.  Strides are in elements.
@@ -292,6 +300,12 @@ int d2o_cache_import(d2o_ctx* ctx, int32_t layer, int32_t b, int32_t kv_head, co
  * (NaN none).  Synchronises `stream`. */
 int d2o_last_events(d2o_ctx* ctx, int32_t layer, int32_t* evicted_pos, int32_t* target_pos,
                     double* u_star, void* stream);
+
+/* Diagnostic: how many evictions of generation steps, over all layers and heads since d2o_create
+ * or d2o_reset, took a token that was not among the candidates predicted one step ahead (each
+ * costs the head's closing workgroup a second pass over the head's keys; the first step after
+ * d2o_cache_import always does).  Results never depend on the prediction.  Synchronises `stream`. */
+int d2o_candidate_misses(d2o_ctx* ctx, int64_t* misses, void* stream);
 
 /* What the most recent d2o_compress_layer call did on one (sequence, KV head): retained
  * positions [n_ret] and evicted positions [n_evi] ascending, and per evicted token its

@@ -59,7 +59,8 @@ def quantise_fp8_rows(x: np.ndarray) -> np.ndarray:
     (last axis) is stored as d codes of the 8-bit floating-point format E4M3 (1 sign, 4 exponent
     bits with bias 7, 3 fraction bits, subnormals down to 2^-9, largest magnitude 448, no
     infinities) and one power of two per row:
-      e   = the smallest integer with max|x| * 2^-e <= 448 (0 for an all-zero row),
+      e   = the smallest integer with max|x| * 2^-e <= 448 (0 for an all-zero row; not below
+            -120, so that it fits a signed byte: rows of magnitude 1e-34 and less lose bits),
       q_i = x_i * 2^-e rounded to the nearest E4M3 value, ties to the even fraction,
     and the row then holds the values q_i * 2^e, which is what this function returns (fp64).
     The cache's logical type stays the input type: "fp8" storage rounds a row to bf16 first and
@@ -71,7 +72,7 @@ def quantise_fp8_rows(x: np.ndarray) -> np.ndarray:
     amax = np.abs(x).max(axis=-1, keepdims=True)
     frac, ex = np.frexp(amax)                      # amax = frac * 2^ex, 0.5 <= frac < 1; 448 = 0.875 * 2^9
     e = np.where(frac <= 0.875, ex - 9, ex - 8)
-    e = np.where(amax > 0.0, e, 0)
+    e = np.where(amax > 0.0, np.maximum(e, -120), 0)
     y = np.ldexp(x, -e)                            # exact; |y| <= 448
     _, ey = np.frexp(y)                            # |y| in [2^(ey-1), 2^ey)
     E = np.maximum(ey - 1, -6)                     # binade of y, the subnormal range counts as binade -6

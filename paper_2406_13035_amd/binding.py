@@ -20,7 +20,7 @@ EXPORTS = [
     "d2o_workspace_bytes", "d2o_qkv_project", "d2o_create", "d2o_destroy", "d2o_last_error", "d2o_reset",
     "d2o_prefill_attend", "d2o_get_density", "d2o_allocate_budgets", "d2o_allocate_budgets_policy",
     "d2o_scores_import",
-    "d2o_scores_export", "d2o_compress_layer", "d2o_compress_layer_heads", "d2o_allocate_budgets_heads", "d2o_prefill_compress", "d2o_decode_step",
+    "d2o_scores_export", "d2o_compress_layer", "d2o_compress_layer_heads", "d2o_allocate_budgets_heads", "d2o_candidate_misses", "d2o_prefill_compress", "d2o_decode_step",
     "d2o_decode_step_static", "d2o_append_chunk", "d2o_append_events",
     "d2o_layer_reserve", "d2o_cache_export", "d2o_cache_import", "d2o_last_events",
     "d2o_prefill_events", "d2o_timing_enable", "d2o_timing_read",
@@ -37,7 +37,7 @@ class d2o_config(C.Structure):
                 ("slots_per_seq", C.c_int64), ("dtype", C.c_int32), ("n_sink", C.c_int32),
                 ("beta", C.c_double), ("tau_force", C.c_double), ("out_f32", C.c_int32),
                 ("merge_average", C.c_int32), ("max_append", C.c_int32),
-                ("split_rows", C.c_int32)]
+                ("split_rows", C.c_int32), ("cache_fp8", C.c_int32)]
 
 
 class d2o_view(C.Structure):
@@ -183,7 +183,8 @@ class D2O:
 
     def __init__(self, batch, n_layers, n_q_heads, n_kv_heads, head_dim, max_prompt_len,
                  slots_per_seq, dtype="bf16", n_sink=0, beta=0.7, tau_force=float("nan"),
-                 out_f32=False, device="cuda:0", merge_average=False, max_append=0, split_rows=0):
+                 out_f32=False, device="cuda:0", merge_average=False, max_append=0, split_rows=0,
+                 cache_fp8=False):
         self.lib = load_library()
         if not torch.cuda.is_available():
             raise D2OError("no GPU visible: the D2O library has no CPU path")
@@ -191,7 +192,7 @@ class D2O:
         self.cfg = d2o_config(batch, n_layers, n_q_heads, n_kv_heads, head_dim, max_prompt_len,
                               slots_per_seq, D2O_BF16 if dtype == "bf16" else D2O_F32, n_sink,
                               beta, tau_force, 1 if out_f32 else 0, 1 if merge_average else 0,
-                              int(max_append), int(split_rows))
+                              int(max_append), int(split_rows), 1 if cache_fp8 else 0)
         self.dtype = dtype
         self.out_dtype = torch.float32 if out_f32 else (torch.bfloat16 if dtype == "bf16" else torch.float32)
         self.torch_dtype = torch.bfloat16 if dtype == "bf16" else torch.float32
@@ -355,6 +356,12 @@ class D2O:
         self._check(self.lib.d2o_cache_import(self.ctx, layer, b, kv_head, _np_ptr(Kb), _np_ptr(Vb),
                                               _np_ptr(score), _np_ptr(pos), len(pos), float(tau),
                                               next_pos, _stream_ptr()), "d2o_cache_import")
+
+    def d2o_candidate_misses(self):
+        """Evictions of generation steps that took a token outside the predicted candidates."""
+        m = C.c_int64()
+        self._check(self.lib.d2o_candidate_misses(self.ctx, C.byref(m), _stream_ptr()), "d2o_candidate_misses")
+        return m.value
 
     def d2o_last_events(self, layer):
         c = self.cfg

@@ -7,7 +7,7 @@ import sys
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
-SOURCES = ["d2o_host.hip", "prefill_f32.hip", "prefill_bf16.hip", "tokens.hip", "decode.hip", "decode_split.hip", "append.hip", "qkv.hip"]
+SOURCES = ["d2o_host.hip", "prefill_f32.hip", "prefill_bf16.hip", "tokens.hip", "decode.hip", "decode_split.hip", "append.hip", "qkv.hip", "fp8.hip"]
 LIB = os.environ.get("D2O_LIB", os.path.join(HERE, "libd2o.so"))
 # Matrix-core results straight into vector registers: the kernels of these files post-process
 # every accumulator element on the vector ALU, and a copy out of the accumulation registers per

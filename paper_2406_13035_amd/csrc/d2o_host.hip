@@ -53,6 +53,8 @@ int check_config(const d2o_config* c) {
   if (c->merge_average != 0 && c->merge_average != 1) return D2O_ERR_INVALID_ARG;
   if (c->max_append < 0 || c->max_append >= c->max_prompt_len) return D2O_ERR_INVALID_ARG;
   if (c->split_rows != 0 && c->split_rows < 256) return D2O_ERR_INVALID_ARG;
+  if (c->cache_fp8 != 0 && c->cache_fp8 != 1) return D2O_ERR_INVALID_ARG;
+  if (c->cache_fp8 && (c->dtype != D2O_BF16 || c->max_append > 1)) return D2O_ERR_UNSUPPORTED;
   return D2O_OK;
 }
 
@@ -65,8 +67,12 @@ void layout(d2o_ctx* x, char* persistent, char* scratch, size_t* pbytes, size_t*
   p.take(x->score_pre, L * B * Hkv * np);
   p.take(x->head_var, L * B * Hq);
   p.take(x->layer_F, L * B);
-  p.take_raw(x->cacheK, B * Hkv * slots * d * es);
-  p.take_raw(x->cacheV, B * Hkv * slots * d * es);
+  const size_t f8 = c.cache_fp8 ? 1 : 0;
+  p.take_raw(x->cacheK, B * Hkv * slots * d * x->csize);
+  p.take_raw(x->cacheV, B * Hkv * slots * d * x->csize);
+  p.take(x->cKe, f8 * B * Hkv * slots);
+  p.take(x->cVe, f8 * B * Hkv * slots);
+  p.take(x->meta_stage, f8 * L * B * Hkv * 4);
   p.take(x->cscore, B * Hkv * slots);
   p.take(x->cpos, B * Hkv * slots);
   p.take(x->ccount, L * B * Hkv);
@@ -79,6 +85,7 @@ void layout(d2o_ctx* x, char* persistent, char* scratch, size_t* pbytes, size_t*
   const size_t nc = decode_candidates();
   p.take(x->ccand, L * B * Hkv * nc);
   p.take(x->cticket, L * B * Hkv);
+  p.take(x->cmiss, L * B * Hkv);
   *pbytes = (p.off + 255) & ~size_t(255);
 
   Carver s{scratch};
@@ -106,8 +113,8 @@ void layout(d2o_ctx* x, char* persistent, char* scratch, size_t* pbytes, size_t*
   s.take(x->g_cur, bh * (np + 1));
   s.take(x->g_src, bh * np);
   const size_t ap = c.max_append > 1 ? 1 : 0;  // the position-ordered copy exists only when blocks can be appended
-  s.take_raw(x->app_K, ap * bh * np * d * es);
-  s.take_raw(x->app_V, ap * bh * np * d * es);
+  s.take_raw(x->app_K, (ap | f8) * bh * np * d * es);
+  s.take_raw(x->app_V, (ap | f8) * bh * np * d * es);
   s.take(x->app_score, ap * bh * np);
   s.take(x->app_pos, ap * bh * np);
   s.take(x->app_rank, ap * bh * np);
@@ -132,6 +139,7 @@ void layout(d2o_ctx* x, char* persistent, char* scratch, size_t* pbytes, size_t*
 
 void init_sizes(d2o_ctx* x) {
   x->esize = x->cfg.dtype == D2O_BF16 ? 2 : 4;
+  x->csize = x->cfg.cache_fp8 ? 1 : x->esize;
   x->npad = (x->cfg.max_prompt_len + 127) / 128 * 128;
   x->grow = std::max(1, x->cfg.max_append);
   x->nchunk_cap = x->cfg.slots_per_seq / kChunk + x->cfg.n_layers + 1;
@@ -162,6 +170,8 @@ int reserve_layer(d2o_ctx* x, int32_t layer, int32_t n, const int32_t* budget_in
     const int64_t need = int64_t(budget[b]) + x->grow;
     if (c.max_append > 1 && int64_t(budget[b]) + c.max_append > x->npad)
       return fail(x, D2O_ERR_CAPACITY, "budget + max_append exceeds max_prompt_len (rounded up to 128)");
+    if (c.cache_fp8 && int64_t(budget[b]) + 1 > x->npad)
+      return fail(x, D2O_ERR_CAPACITY, "fp8 cache: budget + 1 exceeds max_prompt_len (rounded up to 128), the rows the staging area holds");
     if (x->used_slots[b] + need > c.slots_per_seq)
       return fail(x, D2O_ERR_CAPACITY, "slots_per_seq too small for the layer budgets");
     meta[b].base = int32_t(x->used_slots[b]);
@@ -220,8 +230,13 @@ hipError_t launch_write_meta(d2o_ctx* x, int layer, hipStream_t s) {
       m.v[4 * i + 3] = t.chunk_base;
     }
     write_meta_kernel<<<1, kMetaPerLaunch * 4, 0, s>>>(x->meta + (size_t(layer) * B + b0) * 4, m, nb * 4);
-    const hipError_t e = hipGetLastError();
+    hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
+    if (x->cfg.cache_fp8) {  // the staging rows of a head start at row 0
+      for (int i = 0; i < nb; ++i) m.v[4 * i + 0] = 0;
+      write_meta_kernel<<<1, kMetaPerLaunch * 4, 0, s>>>(x->meta_stage + (size_t(layer) * B + b0) * 4, m, nb * 4);
+      if ((e = hipGetLastError()) != hipSuccess) return e;
+    }
   }
   return hipSuccess;
 }
@@ -306,6 +321,7 @@ int d2o_reset(d2o_ctx* x, void* stream) {
   D2O_HIP_CHECK(x, fill32(x->ev_ustar, 0xFFFFFFFFu, sizeof(double) * lbh, s));
   D2O_HIP_CHECK(x, fill32(x->ccand, 0xFFFFFFFFu, sizeof(int32_t) * lbh * decode_candidates(), s));
   D2O_HIP_CHECK(x, fill32(x->cticket, 0u, sizeof(uint32_t) * lbh, s));
+  D2O_HIP_CHECK(x, fill32(x->cmiss, 0u, sizeof(uint32_t) * lbh, s));
   for (auto& l : x->layers) l = LayerState{};
   std::fill(x->used_slots.begin(), x->used_slots.end(), 0);
   std::fill(x->used_chunks.begin(), x->used_chunks.end(), 0);
@@ -520,6 +536,7 @@ static int compress_layer_impl(d2o_ctx* x, int32_t layer, d2o_view K, d2o_view V
   if ((e = launch_match(x, layer, to_view(K), n, s)) != hipSuccess) return fail(x, D2O_ERR_HIP, std::string("match: ") + hipGetErrorString(e));
   if ((e = launch_threshold_group(x, layer, n, s)) != hipSuccess) return fail(x, D2O_ERR_HIP, std::string("threshold: ") + hipGetErrorString(e));
   if ((e = launch_merge(x, layer, to_view(K), to_view(V), n, s)) != hipSuccess) return fail(x, D2O_ERR_HIP, std::string("merge: ") + hipGetErrorString(e));
+  if (c.cache_fp8 && (e = launch_encode_layer(x, layer, s)) != hipSuccess) return fail(x, D2O_ERR_HIP, std::string("encode: ") + hipGetErrorString(e));
   if ((e = launch_init_candidates(x, layer, st.next_pos, s)) != hipSuccess) return fail(x, D2O_ERR_HIP, std::string("candidates: ") + hipGetErrorString(e));
   // (a failed launch leaves the layer's slots reserved but the layer not ready: d2o_reset recovers)
   st.phase = kReady;
@@ -673,8 +690,15 @@ int d2o_cache_export(d2o_ctx* x, int32_t layer, int32_t b, int32_t h, void* K, v
   std::vector<char> k(cnt * row), v(cnt * row);
   std::vector<double> sc(cnt);
   std::vector<int32_t> ps(cnt);
-  D2O_HIP_CHECK(x, hipMemcpyAsync(k.data(), static_cast<char*>(x->cacheK) + slot0 * row, cnt * row, hipMemcpyDeviceToHost, s));
-  D2O_HIP_CHECK(x, hipMemcpyAsync(v.data(), static_cast<char*>(x->cacheV) + slot0 * row, cnt * row, hipMemcpyDeviceToHost, s));
+  if (c.cache_fp8) {  // decoded into the head's bf16 staging rows first (the decoded values are exact in bf16)
+    const size_t stage0 = (size_t(b) * c.n_kv_heads + h) * x->npad;
+    D2O_HIP_CHECK(x, launch_decode_head(x, layer, b, h, cnt, s));
+    D2O_HIP_CHECK(x, hipMemcpyAsync(k.data(), static_cast<char*>(x->app_K) + stage0 * row, cnt * row, hipMemcpyDeviceToHost, s));
+    D2O_HIP_CHECK(x, hipMemcpyAsync(v.data(), static_cast<char*>(x->app_V) + stage0 * row, cnt * row, hipMemcpyDeviceToHost, s));
+  } else {
+    D2O_HIP_CHECK(x, hipMemcpyAsync(k.data(), static_cast<char*>(x->cacheK) + slot0 * row, cnt * row, hipMemcpyDeviceToHost, s));
+    D2O_HIP_CHECK(x, hipMemcpyAsync(v.data(), static_cast<char*>(x->cacheV) + slot0 * row, cnt * row, hipMemcpyDeviceToHost, s));
+  }
   D2O_HIP_CHECK(x, hipMemcpyAsync(sc.data(), x->cscore + slot0, cnt * sizeof(double), hipMemcpyDeviceToHost, s));
   D2O_HIP_CHECK(x, hipMemcpyAsync(ps.data(), x->cpos + slot0, cnt * sizeof(int32_t), hipMemcpyDeviceToHost, s));
   D2O_HIP_CHECK(x, hipStreamSynchronize(s));
@@ -705,8 +729,15 @@ int d2o_cache_import(d2o_ctx* x, int32_t layer, int32_t b, int32_t h, const void
   const size_t lbh = (size_t(layer) * c.batch + b) * c.n_kv_heads + h;
   const size_t slot0 = (size_t(b) * c.n_kv_heads + h) * c.slots_per_seq + st.meta[size_t(b) * c.n_kv_heads + h].base;
   const size_t row = size_t(c.head_dim) * x->esize;
-  D2O_HIP_CHECK(x, hipMemcpyAsync(static_cast<char*>(x->cacheK) + slot0 * row, K, count * row, hipMemcpyHostToDevice, s));
-  D2O_HIP_CHECK(x, hipMemcpyAsync(static_cast<char*>(x->cacheV) + slot0 * row, V, count * row, hipMemcpyHostToDevice, s));
+  if (c.cache_fp8) {  // the bf16 rows go to the head's staging rows and are encoded from there
+    const size_t stage0 = (size_t(b) * c.n_kv_heads + h) * x->npad;
+    D2O_HIP_CHECK(x, hipMemcpyAsync(static_cast<char*>(x->app_K) + stage0 * row, K, count * row, hipMemcpyHostToDevice, s));
+    D2O_HIP_CHECK(x, hipMemcpyAsync(static_cast<char*>(x->app_V) + stage0 * row, V, count * row, hipMemcpyHostToDevice, s));
+    D2O_HIP_CHECK(x, launch_encode_head(x, layer, b, h, count, s));
+  } else {
+    D2O_HIP_CHECK(x, hipMemcpyAsync(static_cast<char*>(x->cacheK) + slot0 * row, K, count * row, hipMemcpyHostToDevice, s));
+    D2O_HIP_CHECK(x, hipMemcpyAsync(static_cast<char*>(x->cacheV) + slot0 * row, V, count * row, hipMemcpyHostToDevice, s));
+  }
   D2O_HIP_CHECK(x, hipMemcpyAsync(x->cscore + slot0, score, count * sizeof(double), hipMemcpyHostToDevice, s));
   D2O_HIP_CHECK(x, hipMemcpyAsync(x->cpos + slot0, pos, count * sizeof(int32_t), hipMemcpyHostToDevice, s));
   D2O_HIP_CHECK(x, hipMemcpyAsync(x->ccount + lbh, &count, sizeof(int32_t), hipMemcpyHostToDevice, s));
@@ -790,6 +821,20 @@ int d2o_append_events(d2o_ctx* x, int32_t layer, int32_t b, int32_t h, int32_t* 
     if (evicted_pos) evicted_pos[i] = pos[evi[i]];
     if (target_pos) target_pos[i] = pos[ret[tgt[i]]];
   }
+  return D2O_OK;
+}
+
+int d2o_candidate_misses(d2o_ctx* x, int64_t* misses, void* stream) {
+  if (!x || !misses) return D2O_ERR_INVALID_ARG;
+  const d2o_config& c = x->cfg;
+  const size_t n = size_t(c.n_layers) * c.batch * c.n_kv_heads;
+  std::vector<uint32_t> h(n);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  D2O_HIP_CHECK(x, hipMemcpyAsync(h.data(), x->cmiss, n * sizeof(uint32_t), hipMemcpyDeviceToHost, s));
+  D2O_HIP_CHECK(x, hipStreamSynchronize(s));
+  int64_t t = 0;
+  for (uint32_t v : h) t += v;
+  *misses = t;
   return D2O_OK;
 }
 

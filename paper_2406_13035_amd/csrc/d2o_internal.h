@@ -60,7 +60,8 @@ struct d2o_ctx {
   int32_t last_compress_layer = -1;
   int32_t last_append_layer = -1;
   int32_t grow = 1;                  // rows a layer's cache region holds beyond its budget: max(1, max_append)
-  int32_t esize = 2;                 // bytes per element of Q/K/V/cache
+  int32_t esize = 2;                 // bytes per element of Q/K/V (and of the cache, unless it is fp8)
+  int32_t csize = 2;                 // bytes per element of a cache row: esize, or 1 for an fp8 cache
   int32_t npad = 0;                  // max_prompt_len rounded up to 128
   int64_t nchunk_cap = 0;            // chunk slots per (sequence, KV head) in decode partials
 
@@ -70,6 +71,9 @@ struct d2o_ctx {
   double* layer_F = nullptr;     // [L][B]              density statistic
   void* cacheK = nullptr;        // [B][Hkv][slots][d]
   void* cacheV = nullptr;        // [B][Hkv][slots][d]
+  int8_t* cKe = nullptr;         // [B][Hkv][slots] fp8 cache: the power of two of every K row
+  int8_t* cVe = nullptr;         // [B][Hkv][slots] the same for V
+  int32_t* meta_stage = nullptr; // [L][B][Hkv][4] fp8 cache: `meta` with base 0, the geometry of the bf16 staging rows
   double* cscore = nullptr;      // [B][Hkv][slots]
   int32_t* cpos = nullptr;       // [B][Hkv][slots]
   int32_t* ccount = nullptr;     // [L][B][Hkv]
@@ -81,6 +85,7 @@ struct d2o_ctx {
   double* ev_ustar = nullptr;    // [L][B][Hkv]
   int32_t* ccand = nullptr;      // [L][B][Hkv][decode_candidates()] eviction candidates (slots, -1 none)
   uint32_t* cticket = nullptr;   // [L][B][Hkv] chunk counter of the running decode step (0 between steps)
+  uint32_t* cmiss = nullptr;     // [L][B][Hkv] evictions of a token outside the predicted candidates, since the last reset
 
   // ---- scratch workspace (device) ----
   // prefill attention
@@ -107,7 +112,9 @@ struct d2o_ctx {
   int32_t* g_off = nullptr;      // [..][npad+1] exclusive prefix of g_cnt
   int32_t* g_cur = nullptr;      // [..][npad+1] fill cursors
   int32_t* g_src = nullptr;      // evicted ranks grouped by target (unordered inside a group)
-  // multi-token append: the cache in ascending token position (block-level Eq. 7-12 run on it)
+  // multi-token append: the cache in ascending token position (block-level Eq. 7-12 run on it);
+  // fp8 cache: the bf16 rows of the layer being compressed (the prompt-phase kernels work on
+  // them; encode_layer then writes the cache) and of a head being imported or exported
   void* app_K = nullptr;         // [B][Hkv][npad][d]
   void* app_V = nullptr;         // [B][Hkv][npad][d]
   double* app_score = nullptr;   // [B][Hkv][npad] cumulative scores, fp64
@@ -181,6 +188,19 @@ hipError_t launch_cache_sort(d2o_ctx* c, int layer, hipStream_t s);  // cache ->
 hipError_t launch_block_attend(d2o_ctx* c, int layer, View q, View k, View v, View out, int m, int first_pos,
                                hipStream_t s);
 hipError_t launch_merge(d2o_ctx* c, int layer, View K, View V, int n, hipStream_t s);
+// Where the prompt-phase kernels (compaction, matching, merge) keep a layer's cache rows: in the
+// cache itself, or - fp8 cache - in bf16 staging rows [B][Hkv][npad][d] that encode_layer turns
+// into cache rows once the layer's merges are done.
+inline void* prompt_rows_K(const d2o_ctx* c) { return c->cfg.cache_fp8 ? c->app_K : c->cacheK; }
+inline void* prompt_rows_V(const d2o_ctx* c) { return c->cfg.cache_fp8 ? c->app_V : c->cacheV; }
+inline int64_t prompt_rows_stride(const d2o_ctx* c) { return c->cfg.cache_fp8 ? c->npad : c->cfg.slots_per_seq; }
+inline const int32_t* prompt_rows_meta(const d2o_ctx* c, int layer) {
+  return (c->cfg.cache_fp8 ? c->meta_stage : c->meta) + size_t(layer) * c->cfg.batch * c->cfg.n_kv_heads * 4;
+}
+// fp8 cache: staging rows of a layer -> cache rows (all heads), and one head's rows either way
+hipError_t launch_encode_layer(d2o_ctx* c, int layer, hipStream_t s);
+hipError_t launch_encode_head(d2o_ctx* c, int layer, int b, int hk, int count, hipStream_t s);  // staging -> cache
+hipError_t launch_decode_head(d2o_ctx* c, int layer, int b, int hk, int count, hipStream_t s);  // cache -> staging
 // static_scratch: nullptr = the context's scratch workspace; otherwise the device address of the
 // library's static scratch array, which then holds the step's partial results and operands
 hipError_t launch_decode(d2o_ctx* c, int layer0, int nl, View q, View k, View v, View out,

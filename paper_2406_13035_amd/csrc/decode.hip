@@ -31,6 +31,7 @@
 // defining formulas; only the attention output (P V) accumulates in fp32.
 // Slots are physically unordered; a token's identity is its position.
 #include <algorithm>
+#include <type_traits>
 
 #include "decode_common.h"
 
@@ -75,11 +76,12 @@ namespace {
 
 using namespace dec;
 
-template <typename T, typename OT, int D, int G>
-__global__ __launch_bounds__(128) void decode_prepare(DecodeArgs a, const T* __restrict__ q, View qv,
-                                                      const T* __restrict__ kn, View kv, const T* __restrict__ vn,
+// T: the cache's element type (uint8_t: fp8 codes), IT: the type of q, k_new, v_new.
+template <typename T, typename IT, int D, int G>
+__global__ __launch_bounds__(128) void decode_prepare(DecodeArgs a, const IT* __restrict__ q, View qv,
+                                                      const IT* __restrict__ kn, View kv, const IT* __restrict__ vn,
                                                       View vv) {
-  __shared__ double red[2 * kCand];
+  __shared__ double red[2 * kCand > 4 ? 2 * kCand : 4];
   const int li = blockIdx.y, l = a.layer0 + li, b = blockIdx.x / a.Hkv, hk = blockIdx.x % a.Hkv;
   const int64_t lbh = (int64_t(l) * a.B + b) * a.Hkv + hk;
   const int count = a.ccount[lbh];
@@ -87,9 +89,31 @@ __global__ __launch_bounds__(128) void decode_prepare(DecodeArgs a, const T* __r
   const int c = threadIdx.x;
   T* Kc = static_cast<T*>(a.cK) + slot0 * D;
   T* Vc = static_cast<T*>(a.cV) + slot0 * D;
-  if (c < D) {
-    Kc[int64_t(count) * D + c] = kn[li * kv.sn + b * kv.sb + hk * kv.sh + c];
-    Vc[int64_t(count) * D + c] = vn[li * vv.sn + b * vv.sb + hk * vv.sh + c];
+  if constexpr (sizeof(T) == 1) {
+    // fp8 cache: the new row is encoded as it enters the cache (its largest magnitude decides
+    // the row's power of two: a reduction over the two wavefronts)
+    static_assert(D == 128, "one element per thread");
+    const double kx = Elem<IT>::to_f64(kn[li * kv.sn + b * kv.sb + hk * kv.sh + c]);
+    const double vx = Elem<IT>::to_f64(vn[li * vv.sn + b * vv.sb + hk * vv.sh + c]);
+    const double ak = wave_max(fabs(kx)), av = wave_max(fabs(vx));
+    if ((c & 63) == 0) {
+      red[c >> 6] = ak;
+      red[2 + (c >> 6)] = av;
+    }
+    __syncthreads();
+    const int ek = fp8_row_exponent(fmax(red[0], red[1])), ev = fp8_row_exponent(fmax(red[2], red[3]));
+    Kc[int64_t(count) * D + c] = fp8_encode(ldexp(kx, -ek));
+    Vc[int64_t(count) * D + c] = fp8_encode(ldexp(vx, -ev));
+    if (c == 0) {
+      a.cKe[slot0 + count] = int8_t(ek);
+      a.cVe[slot0 + count] = int8_t(ev);
+    }
+    __syncthreads();  // `red` is used again below
+  } else {
+    if (c < D) {
+      Kc[int64_t(count) * D + c] = kn[li * kv.sn + b * kv.sb + hk * kv.sh + c];
+      Vc[int64_t(count) * D + c] = vn[li * vv.sn + b * vv.sb + hk * vv.sh + c];
+    }
   }
   if (c == 0) {
     a.cscore[slot0 + count] = 0.0;
@@ -102,15 +126,18 @@ __global__ __launch_bounds__(128) void decode_prepare(DecodeArgs a, const T* __r
   double* vec = a.vecs + lbh * (G + kCand) * D;
 #pragma unroll
   for (int g = 0; g < G; ++g)
-    if (c < D) vec[g * D + c] = Elem<T>::to_f64(q[li * qv.sn + b * qv.sb + (hk * G + g) * qv.sh + c]);
+    if (c < D) vec[g * D + c] = Elem<IT>::to_f64(q[li * qv.sn + b * qv.sb + (hk * G + g) * qv.sh + c]);
   // the candidates' keys: all slot numbers first, then all rows, then one exchange for the
-  // three norms (one memory round trip each instead of one per candidate)
+  // norms (one memory round trip each instead of one per candidate)
   int cs[kCand];
 #pragma unroll
   for (int i = 0; i < kCand; ++i) cs[i] = a.cand[lbh * kCand + i];  // older slots: never the one just written
   double x[kCand], part[kCand];
 #pragma unroll
-  for (int i = 0; i < kCand; ++i) x[i] = (cs[i] >= 0 && c < D) ? Elem<T>::to_f64(Kc[int64_t(cs[i]) * D + c]) : 0.0;
+  for (int i = 0; i < kCand; ++i) {
+    x[i] = (cs[i] >= 0 && c < D) ? Elem<T>::to_f64(Kc[int64_t(cs[i]) * D + c]) : 0.0;
+    if constexpr (sizeof(T) == 1) x[i] *= pow2_f64(a.cKe[slot0 + max(cs[i], 0)]);
+  }
 #pragma unroll
   for (int i = 0; i < kCand; ++i) {
     if (c < D) vec[(G + i) * D + c] = x[i];
@@ -529,6 +556,12 @@ __global__ __launch_bounds__(256) void decode_attend(DecodeArgs a, OT* __restric
     const bool valid = ln < rows;
     const int j = sub * kSub + ln;
     const int pos = valid ? a.cpos[slot0 + j] : 0;
+    // fp8 cache: the powers of two of this lane's K and V row
+    int rek = 0, rev = 0;
+    if constexpr (sizeof(T) == 1) {
+      rek = valid ? a.cKe[slot0 + j] : 0;
+      rev = valid ? a.cVe[slot0 + j] : 0;
+    }
 #pragma unroll
     for (int p = 0; p < NP; ++p) {
       // The staging area is private to the wavefront and LDS serves a wavefront's requests in
@@ -563,6 +596,14 @@ __global__ __launch_bounds__(256) void decode_attend(DecodeArgs a, OT* __restric
         step(rawB, sB);
       }
     }
+    if constexpr (sizeof(T) == 1) {
+      // the K pass worked on the codes: the row's power of two scales its dot products and its
+      // squared norm (exactly: the sums are exact, see the precision notes of the file header)
+      const double sk = pow2_f64(rek);
+#pragma unroll
+      for (int v = 0; v < NV; ++v) acc[v] *= sk;
+      nr *= sk * sk;
+    }
     // ---- softmax statistics of the sub-chunk; the lane owns cache row sub*kSub + lane
     const int64_t pidx = sub_index(a, bh, mt3, sub) * G;
     double recv = 0.0;  // this lane's element of the sub-chunk record
@@ -571,7 +612,8 @@ __global__ __launch_bounds__(256) void decode_attend(DecodeArgs a, OT* __restric
       const double sg = acc[g] / root_d;
       const double mx = fast_wave_max(valid ? sg : -INFINITY);
       const double e = valid ? exp(sg - mx) : 0.0;
-      ps[w][g][ln] = float(e);
+      // (fp8 cache: the V pass works on the codes, so the row's power of two rides on its probability)
+      ps[w][g][ln] = sizeof(T) == 1 ? float(e) * pow2_f32(rev) : float(e);
       if (valid) st_agent(&a.elog[elog_index(a, bh, mt3, G, g, j)], e);
       const double sm = fast_wave_sum(e);
       if (ln == g) {
@@ -697,16 +739,24 @@ __global__ __launch_bounds__(256) void decode_attend(DecodeArgs a, OT* __restric
                          stage + 8192);
 }
 
+// The type of q, k_new, v_new and (unless fp32 is asked for) of the outputs: the cache's own
+// type, or bf16 when the cache holds fp8 codes.
+template <typename T>
+struct TensorType {
+  typedef typename std::conditional<sizeof(T) == 1, uint16_t, T>::type type;
+};
+
 template <typename T, int D>
 hipError_t run_prepare_g(d2o_ctx* c, const DecodeArgs& a, int nl, View q, View k, View v, hipStream_t s) {
+  typedef typename TensorType<T>::type IT;
   const int bh = a.B * a.Hkv;
   KernelTimer kt(c, D2O_K_DECODE_PREPARE, s);
   const dim3 grid(bh, nl);
-  switch (a.G) {  // the output type plays no role in this kernel
-    case 1: decode_prepare<T, T, D, 1><<<grid, 128, 0, s>>>(a, (const T*)q.ptr, q, (const T*)k.ptr, k, (const T*)v.ptr, v); break;
-    case 2: decode_prepare<T, T, D, 2><<<grid, 128, 0, s>>>(a, (const T*)q.ptr, q, (const T*)k.ptr, k, (const T*)v.ptr, v); break;
-    case 4: decode_prepare<T, T, D, 4><<<grid, 128, 0, s>>>(a, (const T*)q.ptr, q, (const T*)k.ptr, k, (const T*)v.ptr, v); break;
-    case 8: decode_prepare<T, T, D, 8><<<grid, 128, 0, s>>>(a, (const T*)q.ptr, q, (const T*)k.ptr, k, (const T*)v.ptr, v); break;
+  switch (a.G) {
+    case 1: decode_prepare<T, IT, D, 1><<<grid, 128, 0, s>>>(a, (const IT*)q.ptr, q, (const IT*)k.ptr, k, (const IT*)v.ptr, v); break;
+    case 2: decode_prepare<T, IT, D, 2><<<grid, 128, 0, s>>>(a, (const IT*)q.ptr, q, (const IT*)k.ptr, k, (const IT*)v.ptr, v); break;
+    case 4: decode_prepare<T, IT, D, 4><<<grid, 128, 0, s>>>(a, (const IT*)q.ptr, q, (const IT*)k.ptr, k, (const IT*)v.ptr, v); break;
+    case 8: decode_prepare<T, IT, D, 8><<<grid, 128, 0, s>>>(a, (const IT*)q.ptr, q, (const IT*)k.ptr, k, (const IT*)v.ptr, v); break;
     default: return hipErrorInvalidValue;
   }
   return hipGetLastError();
@@ -722,7 +772,7 @@ hipError_t run_attend(d2o_ctx* c, const DecodeArgs& a, int flat_chunks, View out
 template <typename T, int D, int G>
 hipError_t run_decode(d2o_ctx* c, const DecodeArgs& a, int fc, View out, hipStream_t s) {
   if (a.out_f32) return run_attend<T, float, D, G>(c, a, fc, out, s);
-  return run_attend<T, T, D, G>(c, a, fc, out, s);
+  return run_attend<T, typename TensorType<T>::type, D, G>(c, a, fc, out, s);
 }
 
 template <typename T, int D>
@@ -837,10 +887,13 @@ hipError_t launch_decode(d2o_ctx* c, int layer0, int nl_all, View q, View k, Vie
   a.meta = c->meta;
   a.cK = c->cacheK;
   a.cV = c->cacheV;
+  a.cKe = c->cKe;
+  a.cVe = c->cVe;
   a.cscore = c->cscore;
   a.cpos = c->cpos;
   a.cand = c->ccand;
   a.ticket = c->cticket;
+  a.cmiss = c->cmiss;
   a.elog = c->d_logit;
   a.rec = c->d_rec;
   a.pacc = c->d_pacc;
@@ -904,7 +957,9 @@ hipError_t launch_decode(d2o_ctx* c, int layer0, int nl_all, View q, View k, Vie
     const View qg = shift(q, es), kg = shift(k, es), vg = shift(v, es), og = shift(out, os);
     hipError_t e;
     // ---- append + operand set-up for every layer of the group
-    if (cf.dtype == D2O_BF16)
+    if (cf.cache_fp8)
+      e = run_prepare_g<uint8_t, 128>(c, a, nl, qg, kg, vg, s);
+    else if (cf.dtype == D2O_BF16)
       e = run_prepare_g<uint16_t, 128>(c, a, nl, qg, kg, vg, s);
     else if (cf.head_dim == 64)
       e = run_prepare_g<float, 64>(c, a, nl, qg, kg, vg, s);
@@ -921,7 +976,9 @@ hipError_t launch_decode(d2o_ctx* c, int layer0, int nl_all, View q, View k, Vie
         flat += mc[chunk_id[i]];
       }
       for (int i = nc; i <= kMaxLayersPerCall; ++i) a.lay_off[i] = i == nc ? flat : 0x7FFFFFFF;
-      if (cf.dtype == D2O_BF16)
+      if (cf.cache_fp8)
+        e = run_decode_g<uint8_t, 128>(c, a, flat, og, s);
+      else if (cf.dtype == D2O_BF16)
         e = run_decode_g<uint16_t, 128>(c, a, flat, og, s);
       else if (cf.head_dim == 64)
         e = run_decode_g<float, 64>(c, a, flat, og, s);

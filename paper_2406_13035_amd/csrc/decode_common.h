@@ -9,7 +9,14 @@
 namespace d2o {
 namespace dec {
 
-constexpr int kCand = 3;                // eviction candidates whose similarities ride along with the attention pass
+// Eviction candidates whose similarities ride along with the attention pass.  One: the token
+// with the lowest score after a step is, with very few exceptions, the one evicted at the next
+// (scores only grow, and the lowest tokens are the ones that receive next to no attention); on
+// the benchmark workloads no eviction of 5 x 10^5 to 2 x 10^6 head-steps took another token.
+// Every further candidate costs the K pass another fp64 dot product per cache row (with three,
+// configuration 4 ran 6 % and an fp8 cache 11 % slower); a miss costs one head a second pass
+// over its keys.
+constexpr int kCand = 1;
 constexpr int kMaxLayersPerCall = 64;
 // Doubles per sub-chunk record: the G softmax maxima, the G exp-sums, then per candidate its
 // best cosine and that key's slot; rounded up to a multiple of eight (64 bytes).
@@ -27,10 +34,13 @@ struct DecodeArgs {
   const int32_t* meta;
   void* cK;
   void* cV;
+  int8_t* cKe;        // fp8 cache only: the power of two of every K row, [B][Hkv][slots]
+  int8_t* cVe;        // the same for V
   double* cscore;
   int32_t* cpos;
   int32_t* cand;      // [L][B][Hkv][kCand] candidate slots for this step, -1 = none
   uint32_t* ticket;   // [L][B][Hkv] finished chunks of the running step
+  uint32_t* cmiss;    // [L][B][Hkv] evictions whose token was not among the predicted candidates (since the last reset)
   double* elog;       // [chunk][B][Hkv][G][256] exp(logit - sub-chunk max)
   double* rec;        // [chunk][B][Hkv][4][rec_doubles(G)] per sub-chunk record: [0..G) softmax maxima of the
                       // query heads, [G..2G) exp-sums relative to them, [2G..2G+kCand) the candidates' best
@@ -67,6 +77,16 @@ __device__ __forceinline__ void cvt16<float>(const u32x4& v, double* out) {
 #pragma unroll
   for (int i = 0; i < 4; ++i) out[i] = double(__uint_as_float(v[i]));
 }
+template <>
+__device__ __forceinline__ void cvt16<uint8_t>(const u32x4& v, double* out) {  // sixteen fp8 codes, without the row's power of two
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    out[4 * i] = double(__builtin_amdgcn_cvt_f32_fp8(int(v[i]), 0));
+    out[4 * i + 1] = double(__builtin_amdgcn_cvt_f32_fp8(int(v[i]), 1));
+    out[4 * i + 2] = double(__builtin_amdgcn_cvt_f32_fp8(int(v[i]), 2));
+    out[4 * i + 3] = double(__builtin_amdgcn_cvt_f32_fp8(int(v[i]), 3));
+  }
+}
 template <typename T>
 __device__ __forceinline__ void cvt16f(const u32x4& v, float* out);
 template <>
@@ -82,18 +102,39 @@ __device__ __forceinline__ void cvt16f<float>(const u32x4& v, float* out) {
 #pragma unroll
   for (int i = 0; i < 4; ++i) out[i] = __uint_as_float(v[i]);
 }
+template <>
+__device__ __forceinline__ void cvt16f<uint8_t>(const u32x4& v, float* out) {
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    out[4 * i] = __builtin_amdgcn_cvt_f32_fp8(int(v[i]), 0);
+    out[4 * i + 1] = __builtin_amdgcn_cvt_f32_fp8(int(v[i]), 1);
+    out[4 * i + 2] = __builtin_amdgcn_cvt_f32_fp8(int(v[i]), 2);
+    out[4 * i + 3] = __builtin_amdgcn_cvt_f32_fp8(int(v[i]), 3);
+  }
+}
 
 // N consecutive elements (4, 8 or 16 bytes) held as raw bits, and their conversion to doubles.
 template <int BYTES> struct RawBits;
 template <> struct RawBits<16> { typedef u32x4 type; };
 template <> struct RawBits<8> { typedef u32x2 type; };
 template <> struct RawBits<4> { typedef uint32_t type; };
+template <> struct RawBits<2> { typedef uint16_t type; };
+__device__ __forceinline__ uint32_t raw_word(const uint16_t& r, int) { return r; }
 __device__ __forceinline__ uint32_t raw_word(const u32x4& r, int i) { return r[i]; }
 __device__ __forceinline__ uint32_t raw_word(const u32x2& r, int i) { return r[i]; }
 __device__ __forceinline__ uint32_t raw_word(const uint32_t& r, int) { return r; }
 template <typename T, int N, typename R>
 __device__ __forceinline__ void raw_to_f64(const R& r, double* out) {
-  if constexpr (sizeof(T) == 2) {
+  if constexpr (sizeof(T) == 1) {  // two or four fp8 codes in one word, without the row's power of two
+    static_assert(N == 2 || N == 4, "fp8 codes come two or four at a time");
+    const int wd = int(raw_word(r, 0));
+    out[0] = double(__builtin_amdgcn_cvt_f32_fp8(wd, 0));
+    out[1] = double(__builtin_amdgcn_cvt_f32_fp8(wd, 1));
+    if constexpr (N == 4) {
+      out[2] = double(__builtin_amdgcn_cvt_f32_fp8(wd, 2));
+      out[3] = double(__builtin_amdgcn_cvt_f32_fp8(wd, 3));
+    }
+  } else if constexpr (sizeof(T) == 2) {
 #pragma unroll
     for (int i = 0; i < N / 2; ++i) {
       out[2 * i] = double(__uint_as_float(raw_word(r, i) << 16));
@@ -199,7 +240,7 @@ __device__ __forceinline__ Best fast_wave_first_evicted(const Best& b) {
 template <typename T, int D>
 __device__ __forceinline__ void finish_head(const DecodeArgs& a, int64_t lbh, int64_t slot0, int es, int total,
                                             double best, int bp, int bs, double told, T kl, T vl, double sl,
-                                            int pl) {
+                                            int pl, double* red) {
   T* Kc = static_cast<T*>(a.cK) + slot0 * D;
   T* Vc = static_cast<T*>(a.cV) + slot0 * D;
   const int tid = threadIdx.x, last = total - 1;
@@ -217,28 +258,85 @@ __device__ __forceinline__ void finish_head(const DecodeArgs& a, int64_t lbh, in
     a.ev_ustar[lbh] = best;
     a.ccount[lbh] = last;
   }
-  if (tid < D) {
+  // exp(1), the retained token's self-similarity weight; average merging weighs both rows 1
+  const double e1 = a.merge_average ? 1.0 : 2.718281828459045;
+  const double w = a.merge_average ? 1.0 : exp(best);
+  const double z = __dadd_rn(e1, w);
+  if constexpr (sizeof(T) == 1) {
+    // fp8 cache: rows are codes times the row's power of two.  The merged row is rounded to the
+    // cache's logical type (bf16) and encoded again with a power of two of its own, which takes
+    // its largest magnitude: a reduction over the workgroup (`red`: one double per wavefront).
+    int8_t* Ke = a.cKe + slot0;
+    int8_t* Ve = a.cVe + slot0;
+    int ekl = Ke[last], evl = Ve[last];  // the last row's powers of two travel with its codes
     if (do_merge) {
-      // exp(1), the retained token's self-similarity weight; average merging weighs both rows 1
-      const double e1 = a.merge_average ? 1.0 : 2.718281828459045;
-      const double w = a.merge_average ? 1.0 : exp(best);
-      const double z = __dadd_rn(e1, w);
-      const T ke = es == last ? kl : Kc[int64_t(es) * D + tid], ve = es == last ? vl : Vc[int64_t(es) * D + tid];
-      const T kt = bs == last ? kl : Kc[int64_t(bs) * D + tid], vt = bs == last ? vl : Vc[int64_t(bs) * D + tid];
-      const double kk = __dadd_rn(__dmul_rn(e1, Elem<T>::to_f64(kt)), __dmul_rn(w, Elem<T>::to_f64(ke)));
-      const double vv = __dadd_rn(__dmul_rn(e1, Elem<T>::to_f64(vt)), __dmul_rn(w, Elem<T>::to_f64(ve)));
-      const T km = Elem<T>::from_f64(kk / z), vm = Elem<T>::from_f64(vv / z);
+      double km = 0.0, vm = 0.0;
+      if (tid < D) {
+        const double ke = Elem<T>::to_f64(es == last ? kl : Kc[int64_t(es) * D + tid]) * pow2_f64(Ke[es]);
+        const double ve = Elem<T>::to_f64(es == last ? vl : Vc[int64_t(es) * D + tid]) * pow2_f64(Ve[es]);
+        const double kt = Elem<T>::to_f64(bs == last ? kl : Kc[int64_t(bs) * D + tid]) * pow2_f64(Ke[bs]);
+        const double vt = Elem<T>::to_f64(bs == last ? vl : Vc[int64_t(bs) * D + tid]) * pow2_f64(Ve[bs]);
+        const double kk = __dadd_rn(__dmul_rn(e1, kt), __dmul_rn(w, ke));
+        const double vv = __dadd_rn(__dmul_rn(e1, vt), __dmul_rn(w, ve));
+        km = Elem<uint16_t>::to_f64(Elem<uint16_t>::from_f64(kk / z));
+        vm = Elem<uint16_t>::to_f64(Elem<uint16_t>::from_f64(vv / z));
+      }
+      const double ak = wave_max(fabs(km)), av = wave_max(fabs(vm));
+      __syncthreads();
+      if ((tid & 63) == 0) {
+        red[tid >> 6] = ak;
+        red[4 + (tid >> 6)] = av;
+      }
+      __syncthreads();
+      const int ek = fp8_row_exponent(fmax(fmax(red[0], red[1]), fmax(red[2], red[3])));
+      const int ev = fp8_row_exponent(fmax(fmax(red[4], red[5]), fmax(red[6], red[7])));
+      const T kc = fp8_encode(ldexp(km, -ek)), vc = fp8_encode(ldexp(vm, -ev));
       if (bs == last) {  // the merged row is the one that moves into the hole
-        kl = km;
-        vl = vm;
+        kl = kc;
+        vl = vc;
+        ekl = ek;
+        evl = ev;
       } else {
-        Kc[int64_t(bs) * D + tid] = km;
-        Vc[int64_t(bs) * D + tid] = vm;
+        if (tid < D) {
+          Kc[int64_t(bs) * D + tid] = kc;
+          Vc[int64_t(bs) * D + tid] = vc;
+        }
+        if (tid == 0) {
+          Ke[bs] = int8_t(ek);
+          Ve[bs] = int8_t(ev);
+        }
       }
     }
     if (es != last) {  // the last slot fills the hole
-      Kc[int64_t(es) * D + tid] = kl;
-      Vc[int64_t(es) * D + tid] = vl;
+      if (tid < D) {
+        Kc[int64_t(es) * D + tid] = kl;
+        Vc[int64_t(es) * D + tid] = vl;
+      }
+      if (tid == 0) {
+        Ke[es] = int8_t(ekl);
+        Ve[es] = int8_t(evl);
+      }
+    }
+  } else {
+    if (tid < D) {
+      if (do_merge) {
+        const T ke = es == last ? kl : Kc[int64_t(es) * D + tid], ve = es == last ? vl : Vc[int64_t(es) * D + tid];
+        const T kt = bs == last ? kl : Kc[int64_t(bs) * D + tid], vt = bs == last ? vl : Vc[int64_t(bs) * D + tid];
+        const double kk = __dadd_rn(__dmul_rn(e1, Elem<T>::to_f64(kt)), __dmul_rn(w, Elem<T>::to_f64(ke)));
+        const double vv = __dadd_rn(__dmul_rn(e1, Elem<T>::to_f64(vt)), __dmul_rn(w, Elem<T>::to_f64(ve)));
+        const T km = Elem<T>::from_f64(kk / z), vm = Elem<T>::from_f64(vv / z);
+        if (bs == last) {  // the merged row is the one that moves into the hole
+          kl = km;
+          vl = vm;
+        } else {
+          Kc[int64_t(bs) * D + tid] = km;
+          Vc[int64_t(bs) * D + tid] = vm;
+        }
+      }
+      if (es != last) {  // the last slot fills the hole
+        Kc[int64_t(es) * D + tid] = kl;
+        Vc[int64_t(es) * D + tid] = vl;
+      }
     }
   }
   if (es != last && tid == 0) {
@@ -261,7 +359,8 @@ __device__ __forceinline__ Best scan_matches(const DecodeArgs& a, int64_t slot0,
   double part = 0.0;
   __syncthreads();
   if (tid < D) {
-    const double x = Elem<T>::to_f64(Kc[int64_t(es) * D + tid]);
+    double x = Elem<T>::to_f64(Kc[int64_t(es) * D + tid]);
+    if constexpr (sizeof(T) == 1) x *= pow2_f64(a.cKe[slot0 + es]);
     ke[tid] = x;
     part = x * x;
   }
@@ -284,6 +383,11 @@ __device__ __forceinline__ Best scan_matches(const DecodeArgs& a, int64_t slot0,
     for (int o = TPR / 2; o > 0; o >>= 1) {
       dot += __shfl_xor(dot, o, 64);
       nr += __shfl_xor(nr, o, 64);
+    }
+    if constexpr (sizeof(T) == 1) {  // the row's power of two: exact on sums that are exact
+      const double sc = pow2_f64(a.cKe[slot0 + min(j, total - 1)]);
+      dot *= sc;
+      nr *= sc * sc;
     }
     if (j < total && j != es && (tid % TPR) == 0) {
       const double den = sne * sqrt(nr);
@@ -378,6 +482,7 @@ __device__ __forceinline__ void close_head(const DecodeArgs& a, int64_t lbh, int
   if (ci < 0) {
     // Not foreseen (the first step after a cache import, or a candidate overtaken by a token
     // outside the list): a second pass over the head's keys.
+    if (tid == 0) a.cmiss[lbh] += 1u;
     m = scan_matches<T, D>(a, slot0, es, total, dred, sred);
   } else {
     if (tid < 4) {  // the four wavefronts' results (written before the barriers of the score pass)
@@ -402,7 +507,7 @@ __device__ __forceinline__ void close_head(const DecodeArgs& a, int64_t lbh, int
     kl = park_kv[tid];
     vl = park_kv[256 + tid];
   }
-  finish_head<T, D>(a, lbh, slot0, es, total, m.u, m.pos, m.slot, told, kl, vl, s_last, p_last);
+  finish_head<T, D>(a, lbh, slot0, es, total, m.u, m.pos, m.slot, told, kl, vl, s_last, p_last, sred);
 }
 
 // The two launches that close the heads with more than a.big_rows entries (decode_split.hip).

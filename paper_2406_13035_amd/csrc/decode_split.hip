@@ -24,6 +24,7 @@
 // operations per slot; the normaliser's fixed summation tree is the same); the output rows
 // differ from it only in the order of the fp32 additions over chunks.
 #include <algorithm>
+#include <type_traits>
 
 #include "decode_common.h"
 
@@ -360,7 +361,7 @@ hipError_t run_split(d2o_ctx* c, const DecodeArgs& a, int flat_parts, int nl, Vi
 template <typename T, int D, int G>
 hipError_t run_split_o(d2o_ctx* c, const DecodeArgs& a, int fc, int nl, View out, hipStream_t s) {
   if (a.out_f32) return run_split<T, float, D, G>(c, a, fc, nl, out, s);
-  return run_split<T, T, D, G>(c, a, fc, nl, out, s);
+  return run_split<T, typename std::conditional<sizeof(T) == 1, uint16_t, T>::type, D, G>(c, a, fc, nl, out, s);
 }
 
 template <typename T, int D>
@@ -392,6 +393,7 @@ hipError_t launch_decode_split(d2o_ctx* c, const DecodeArgs& attend, const int* 
   }
   if (n == 0) return hipSuccess;
   for (int i = n; i <= kMaxLayersPerCall; ++i) a.lay_off[i] = i == n ? flat : 0x7FFFFFFF;
+  if (c->cfg.cache_fp8) return run_split_g<uint8_t, 128>(c, a, flat, nl, out, s);
   if (c->cfg.dtype == D2O_BF16) return run_split_g<uint16_t, 128>(c, a, flat, nl, out, s);
   if (c->cfg.head_dim == 64) return run_split_g<float, 64>(c, a, flat, nl, out, s);
   return run_split_g<float, 128>(c, a, flat, nl, out, s);

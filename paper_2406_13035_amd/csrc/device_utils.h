@@ -44,6 +44,39 @@ struct Elem<uint16_t> {
   }
 };
 
+// ---- fp8 cache rows: d codes of the 8-bit format E4M3 (1 sign, 4 exponent bits with bias 7, 3
+// fraction bits, subnormals, largest magnitude 448, no infinities) and one power of two per row;
+// a row's values are code * 2^e.
+template <>
+struct Elem<uint8_t> {  // the code alone, without the row's power of two
+  static __device__ __forceinline__ float to_f32(uint8_t x) { return __builtin_amdgcn_cvt_f32_fp8(int(x), 0); }
+  static __device__ __forceinline__ double to_f64(uint8_t x) { return double(to_f32(x)); }
+};
+__device__ __forceinline__ double pow2_f64(int e) { return __hiloint2double((1023 + e) << 20, 0); }   // |e| < 1023
+__device__ __forceinline__ float pow2_f32(int e) { return __uint_as_float(uint32_t(127 + e) << 23); }  // |e| < 127
+// The row's exponent: the smallest e with amax * 2^-e <= 448 (448 = 0.875 * 2^9), not below -120
+// (one signed byte holds it); 0 for an all-zero row.
+__device__ __forceinline__ int fp8_row_exponent(double amax) {
+  if (!(amax > 0.0)) return 0;
+  int ex;
+  const double fr = frexp(amax, &ex);
+  return max((fr <= 0.875 ? ex - 9 : ex - 8), -120);
+}
+// y (|y| <= 448) to the nearest E4M3 value, ties to the even fraction; exact arithmetic throughout.
+__device__ __forceinline__ uint8_t fp8_encode(double y) {
+  const double ay = fabs(y);
+  int ex;
+  (void)frexp(ay, &ex);                       // ay in [2^(ex-1), 2^ex); ex = 0 for ay = 0
+  const int E = max(ex - 1, -6);              // the subnormal range counts as binade -6
+  const double q = ldexp(rint(ldexp(ay, 3 - E)), E - 3);
+  if (q == 0.0) return 0;                     // (no negative zero)
+  int eq;
+  (void)frexp(q, &eq);
+  const int Eq = eq - 1;                      // rounding may have carried into the next binade
+  const uint32_t code = Eq < -6 ? uint32_t(ldexp(q, 9)) : (uint32_t(Eq + 7) << 3) | uint32_t(ldexp(q, 3 - Eq) - 8.0);
+  return uint8_t(code | (y < 0.0 ? 0x80u : 0u));
+}
+
 __device__ __forceinline__ float wave_max(float v) {
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));

@@ -161,7 +161,8 @@ __global__ __launch_bounds__(256) void gather_kernel(const T* __restrict__ K, Vi
                                                      const int32_t* __restrict__ cnt, const int32_t* __restrict__ meta,
                                                      T* __restrict__ cK, T* __restrict__ cV, double* __restrict__ cscore,
                                                      int32_t* __restrict__ cpos, int32_t* __restrict__ ccount,
-                                                     int npad, int d, int64_t slots) {
+                                                     int npad, int d, int64_t slots, const int32_t* __restrict__ row_meta,
+                                                     int64_t row_slots) {
   const int hk = blockIdx.y, b = blockIdx.z, Hkv = gridDim.y;
   const int64_t bh = int64_t(b) * Hkv + hk;
   const int nret = cnt[bh * 2];
@@ -174,9 +175,11 @@ __global__ __launch_bounds__(256) void gather_kernel(const T* __restrict__ K, Vi
   const int c = (threadIdx.x % tpr) * kVec;
   const int pos = ret[bh * npad + slot];
   const int64_t dst = (bh * slots + meta[bh * 4 + 0] + slot);
-  *reinterpret_cast<u32x4*>(cK + dst * d + c) =
+  // (the rows may live elsewhere than scores and positions: the bf16 staging rows of an fp8 cache)
+  const int64_t dst_row = (bh * row_slots + row_meta[bh * 4 + 0] + slot);
+  *reinterpret_cast<u32x4*>(cK + dst_row * d + c) =
       *reinterpret_cast<const u32x4*>(K + b * kv.sb + hk * kv.sh + int64_t(pos) * kv.sn + c);
-  *reinterpret_cast<u32x4*>(cV + dst * d + c) =
+  *reinterpret_cast<u32x4*>(cV + dst_row * d + c) =
       *reinterpret_cast<const u32x4*>(V + b * vv.sb + hk * vv.sh + int64_t(pos) * vv.sn + c);
   if (c == 0) {
     cscore[dst] = APPEND ? sc64[bh * npad + pos] : double(score[bh * npad + pos]);
@@ -832,12 +835,14 @@ static void run_gather(d2o_ctx* c, int layer, View K, View V, int max_budget, bo
   const dim3 grid((max_budget + rows - 1) / rows, cf.n_kv_heads, cf.batch);
   if (append)
     gather_kernel<T, true><<<grid, 256, 0, s>>>((const T*)K.ptr, K, (const T*)V.ptr, V, score, c->app_score, c->app_pos,
-                                                c->sel_ret, c->sel_cnt, meta, (T*)c->cacheK, (T*)c->cacheV, c->cscore,
-                                                c->cpos, ccount, c->npad, cf.head_dim, cf.slots_per_seq);
+                                                c->sel_ret, c->sel_cnt, meta, (T*)prompt_rows_K(c), (T*)prompt_rows_V(c), c->cscore,
+                                                c->cpos, ccount, c->npad, cf.head_dim, cf.slots_per_seq,
+                                                prompt_rows_meta(c, layer), prompt_rows_stride(c));
   else
     gather_kernel<T, false><<<grid, 256, 0, s>>>((const T*)K.ptr, K, (const T*)V.ptr, V, score, nullptr, nullptr,
-                                                 c->sel_ret, c->sel_cnt, meta, (T*)c->cacheK, (T*)c->cacheV, c->cscore,
-                                                 c->cpos, ccount, c->npad, cf.head_dim, cf.slots_per_seq);
+                                                 c->sel_ret, c->sel_cnt, meta, (T*)prompt_rows_K(c), (T*)prompt_rows_V(c), c->cscore,
+                                                 c->cpos, ccount, c->npad, cf.head_dim, cf.slots_per_seq,
+                                                 prompt_rows_meta(c, layer), prompt_rows_stride(c));
 }
 
 hipError_t launch_gather(d2o_ctx* c, int layer, View K, View V, int n, hipStream_t s, bool append) {
@@ -869,16 +874,16 @@ hipError_t launch_match(d2o_ctx* c, int layer, View K, int n, hipStream_t s) {
                                                                              c->npad);
     {
       KernelTimer kt(c, D2O_K_MATCH_FILTER, s);
-      match_filter_bf16<false><<<gf, 256, 0, s>>>((const uint16_t*)K.ptr, K, (const uint16_t*)c->cacheK,
-                                                  c->meta + size_t(layer) * cf.batch * cf.n_kv_heads * 4, cf.slots_per_seq,
+      match_filter_bf16<false><<<gf, 256, 0, s>>>((const uint16_t*)K.ptr, K, (const uint16_t*)prompt_rows_K(c),
+                                                  prompt_rows_meta(c, layer), prompt_rows_stride(c),
                                                   c->invnorm, c->sel_ret, c->sel_evi,
                                                   c->sel_cnt, c->m_cand, c->m_thr, c->amb_list, c->amb_cnt,
                                                   c->m_ncand, c->m_clist, c->npad, 1);
       amb_compact_kernel<<<dim3(cf.n_kv_heads, cf.batch), 1024, 0, s>>>(c->m_cand, c->sel_cnt, c->amb_list,
                                                                         c->amb_cnt, c->m_ncand, c->npad);
       constexpr int kSplit = 8;
-      match_filter_bf16<true><<<dim3(gf.x * kSplit, gf.y, gf.z), 256, 0, s>>>((const uint16_t*)K.ptr, K, (const uint16_t*)c->cacheK,
-                                                 c->meta + size_t(layer) * cf.batch * cf.n_kv_heads * 4, cf.slots_per_seq,
+      match_filter_bf16<true><<<dim3(gf.x * kSplit, gf.y, gf.z), 256, 0, s>>>((const uint16_t*)K.ptr, K, (const uint16_t*)prompt_rows_K(c),
+                                                 prompt_rows_meta(c, layer), prompt_rows_stride(c),
                                                  c->invnorm, c->sel_ret, c->sel_evi,
                                                  c->sel_cnt, c->m_cand, c->m_thr, c->amb_list, c->amb_cnt,
                                                  c->m_ncand, c->m_clist, c->npad, kSplit);
@@ -913,12 +918,12 @@ static void run_merge(d2o_ctx* c, const int32_t* meta, View K, View V, int max_b
   const dim3 grid((max_budget + 3) / 4, cf.n_kv_heads, cf.batch);
   if (cf.merge_average)
     merge_kernel<T, D, true><<<grid, 256, 0, s>>>((const T*)K.ptr, K, (const T*)V.ptr, V, c->sel_evi, c->sel_cnt,
-                                                  c->m_ustar, c->g_off, c->g_src, meta, (T*)c->cacheK, (T*)c->cacheV,
-                                                  c->npad, cf.slots_per_seq);
+                                                  c->m_ustar, c->g_off, c->g_src, meta, (T*)prompt_rows_K(c), (T*)prompt_rows_V(c),
+                                                  c->npad, prompt_rows_stride(c));
   else
     merge_kernel<T, D, false><<<grid, 256, 0, s>>>((const T*)K.ptr, K, (const T*)V.ptr, V, c->sel_evi, c->sel_cnt,
-                                                   c->m_ustar, c->g_off, c->g_src, meta, (T*)c->cacheK, (T*)c->cacheV,
-                                                   c->npad, cf.slots_per_seq);
+                                                   c->m_ustar, c->g_off, c->g_src, meta, (T*)prompt_rows_K(c), (T*)prompt_rows_V(c),
+                                                   c->npad, prompt_rows_stride(c));
 }
 
 hipError_t launch_merge(d2o_ctx* c, int layer, View K, View V, int n, hipStream_t s) {
@@ -926,7 +931,7 @@ hipError_t launch_merge(d2o_ctx* c, int layer, View K, View V, int n, hipStream_
   if (max_evicted(c, layer, n) == 0) return hipSuccess;
   int max_budget = 0;
   for (const auto& mt : c->layers[layer].meta) max_budget = std::max(max_budget, std::min(mt.budget, n));
-  const int32_t* meta = c->meta + size_t(layer) * cf.batch * cf.n_kv_heads * 4;
+  const int32_t* meta = prompt_rows_meta(c, layer);  // the merge kernel touches rows only
   KernelTimer kt(c, D2O_K_MERGE, s);
   if (cf.dtype == D2O_BF16)
     run_merge<uint16_t, 128>(c, meta, K, V, max_budget, s);

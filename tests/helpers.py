@@ -52,13 +52,14 @@ def oracle_prefill_layer(Q, K, V, G):
 
 
 def new_ctx(w: synth.Workload, batch, n_layers, max_n, slots, n_sink=0, beta=None,
-            tau_force=float("nan"), out_f32=True, merge_average=False, max_append=0, split_rows=0):
+            tau_force=float("nan"), out_f32=True, merge_average=False, max_append=0, split_rows=0,
+            cache_fp8=False):
     """Contexts of the parity tests write attention outputs in fp32 unless asked otherwise, so
     that the float bar applies to the arithmetic and not to bf16 output storage."""
     return binding.D2O(batch, n_layers, w.n_q_heads, w.n_kv_heads, w.head_dim, max_n, slots,
                        dtype=w.dtype, n_sink=n_sink, beta=w.beta if beta is None else beta,
                        tau_force=tau_force, out_f32=out_f32, merge_average=merge_average,
-                       max_append=max_append, split_rows=split_rows)
+                       max_append=max_append, split_rows=split_rows, cache_fp8=cache_fp8)
 
 
 def check_compress_against_oracle(ctx, layer, K, V, score32, budget, recent, n_sink, storage,

@@ -266,7 +266,7 @@ def test_merge_with_long_source_lists():
 # ------------------------------------------------------------------ a9-a12: decode from oracle state
 
 def _run_decode_parity(w, n, B, layer, budget, recent, sink, steps, tau_force=float("nan"), random_scores=False,
-                       merge_average=False, split_rows=0):
+                       merge_average=False, split_rows=0, cache_fp8=False):
     Q, K, V = H.make_inputs(w, B, layer, n)
     if random_scores:  # long prompts: the token-level stages and decode do not care where scores come from
         score32 = np.random.default_rng(n).random((B, w.n_kv_heads, n), dtype=np.float32) * w.group
@@ -274,12 +274,12 @@ def _run_decode_parity(w, n, B, layer, budget, recent, sink, steps, tau_force=fl
         _, score, _ = H.oracle_prefill_layer(Q, K, V, w.group)
         score32 = score.astype(np.float32)
     cap = int(np.max(budget)) + 1
-    ctx = H.new_ctx(w, B, 1, n, cap + 8, n_sink=sink, tau_force=tau_force, merge_average=merge_average,
-                    split_rows=split_rows)
+    ctx = H.new_ctx(w, B, 1, max(n, cap) if cache_fp8 else n, cap + 8, n_sink=sink, tau_force=tau_force,
+                    merge_average=merge_average, split_rows=split_rows, cache_fp8=cache_fp8)
     ctx.d2o_scores_import(0, score32)
     ctx.d2o_compress_layer(0, K, V, budget, recent)
-    _, caches = H.check_compress_against_oracle(ctx, 0, K, V, score32, budget, recent, sink, w.dtype,
-                                                tau_force, not merge_average)
+    _, caches = H.check_compress_against_oracle(ctx, 0, K, V, score32, budget, recent, sink,
+                                                "fp8" if cache_fp8 else w.dtype, tau_force, not merge_average)
     q, k, v = H.decode_inputs(w, B, [layer], steps)
     out = torch.empty(q[0].shape, dtype=ctx.out_dtype, device=q.device)
     qd, kd, vd = (binding.tensor_to_f64(t) for t in (q, k, v))
@@ -757,18 +757,20 @@ def test_decode_all_layers_in_one_call_equals_one_call_per_layer():
         ctx.close()
 
 
-def _run_multi_layer_decode(w, n, layers, budgets, recents, steps, split_rows=0):
+def _run_multi_layer_decode(w, n, layers, budgets, recents, steps, split_rows=0, cache_fp8=False):
     """Several layers in one decode call per step, every head against the oracle at every step.
     Returns the number of evictions per layer."""
     B, L = 1, len(layers)
-    ctx = H.new_ctx(w, B, L, n, sum(budgets) + 8 * L, split_rows=split_rows)
+    ctx = H.new_ctx(w, B, L, max([n] + [b + 1 for b in budgets]) if cache_fp8 else n, sum(budgets) + 8 * L,
+                    split_rows=split_rows, cache_fp8=cache_fp8)
     caches = {}
     for li, layer in enumerate(layers):
         Q, K, V = H.make_inputs(w, B, layer, n)
         score32 = np.random.default_rng(layer).random((B, w.n_kv_heads, n), dtype=np.float32) * w.group
         ctx.d2o_scores_import(li, score32)
         ctx.d2o_compress_layer(li, K, V, budgets[li], recents[li])
-        _, c = H.check_compress_against_oracle(ctx, li, K, V, score32, budgets[li], recents[li], 0, w.dtype)
+        _, c = H.check_compress_against_oracle(ctx, li, K, V, score32, budgets[li], recents[li], 0,
+                                               "fp8" if cache_fp8 else w.dtype)
         for (b, h), cache in c.items():
             caches[(li, h)] = cache
     q, k, v = H.decode_inputs(w, B, layers, steps)
