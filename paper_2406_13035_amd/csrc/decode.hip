@@ -432,11 +432,14 @@ __device__ __forceinline__ void head_tail(const DecodeArgs& a, OT* __restrict__ 
 
 template <typename T, typename OT, int D, int G>
 __global__ __launch_bounds__(256) void decode_attend(DecodeArgs a, OT* __restrict__ out, View ov) {
-  constexpr int kVec = 16 / sizeof(T);          // elements per 16-byte load
+  constexpr int VB = sizeof(T) == 1 ? 8 : 16;   // V pass: bytes per lane and load (fp8: 8, which keeps the
+                                                // partial sums at eight per lane and query head)
+  constexpr int kVec = VB / sizeof(T);          // elements per load
+  typedef typename RawBits<VB>::type VRaw;
   constexpr int RB = D * sizeof(T);             // bytes of a cache row
   constexpr int NP = RB / kPiece;               // row pieces staged through LDS
   constexpr int EP = kPiece / sizeof(T);        // elements of a piece
-  constexpr int TPR = RB / 16;                  // V pass: lanes per row
+  constexpr int TPR = RB / VB;                  // V pass: lanes per row
   constexpr int RPI = 64 / TPR;                 // V pass: rows per load instruction
   constexpr int NVL = kSub / RPI;               // V pass: loads per lane
   constexpr int NV = G + kCand;
@@ -544,12 +547,12 @@ __global__ __launch_bounds__(256) void decode_attend(DecodeArgs a, OT* __restric
     // their way while the lanes finish the K pass, the others follow as the sets are consumed
     // (a whole sub-chunk in registers would cost the kernel a quarter of its occupancy).
     constexpr int VQ = NVL / 4;
-    u32x4 vbuf[2][VQ];
+    VRaw vbuf[2][VQ];
     auto load_vq = [&](int q, int set) {
 #pragma unroll
       for (int i = 0; i < VQ; ++i) {
         const int r = min((q * VQ + i) * RPI + tr, rows - 1);  // repeated rows meet a zero probability
-        vbuf[set][i] = *reinterpret_cast<const u32x4*>(Vc + int64_t(r) * RB + tc * 16);
+        vbuf[set][i] = *reinterpret_cast<const VRaw*>(Vc + int64_t(r) * RB + tc * VB);
       }
     };
     // this lane's score-side loads ride along
@@ -647,7 +650,19 @@ __global__ __launch_bounds__(256) void decode_attend(DecodeArgs a, OT* __restric
       for (int i = 0; i < VQ; ++i) {
         const int r = (q * VQ + i) * RPI + tr;
         float x[kVec];
-        cvt16f<T>(vbuf[q & 1][i], x);
+        if constexpr (sizeof(T) == 1) {  // eight codes in two words (the byte selector is an immediate)
+          static_assert(sizeof(T) != 1 || kVec == 8, "two words of codes");
+#pragma unroll
+          for (int wd = 0; wd < 2; ++wd) {
+            const int bits = int(raw_word(vbuf[q & 1][i], wd));
+            x[4 * wd] = __builtin_amdgcn_cvt_f32_fp8(bits, 0);
+            x[4 * wd + 1] = __builtin_amdgcn_cvt_f32_fp8(bits, 1);
+            x[4 * wd + 2] = __builtin_amdgcn_cvt_f32_fp8(bits, 2);
+            x[4 * wd + 3] = __builtin_amdgcn_cvt_f32_fp8(bits, 3);
+          }
+        } else {
+          cvt16f<T>(vbuf[q & 1][i], x);
+        }
 #pragma unroll
         for (int g = 0; g < G; ++g) {
           const float p = ps[w][g][r];  // 0 for rows beyond the end
