@@ -128,3 +128,56 @@ def test_unsupported_combinations_are_refused():
         H.new_ctx(w, 1, 1, 256, 300, cache_fp8=True, max_append=16)     # no block append on an fp8 cache
     with pytest.raises(binding.D2OError):
         H.new_ctx(synth.WORKLOADS[1], 1, 1, 256, 300, cache_fp8=True)   # fp32 tensors
+
+
+def test_fp8_cache_with_per_head_budgets_and_the_static_scratch_entry_point():
+    """Ragged per-head cache sizes (d2o_compress_layer_heads) on an fp8 cache, two layers in one
+    decode call, stepped through d2o_decode_step_static: every head against the oracle."""
+    w = _small(True).scaled(n_layers=2)            # 4 query heads, 2 KV heads
+    n, B, L, G = 700, 2, 2, 2
+    S = np.array([[[150, 333], [64, 210]], [[500, 90], [280, 281]]], dtype=np.int32)   # [b][layer][kv head]
+    ctx = H.new_ctx(w, B, L, n, int(S.sum(axis=1).max()) + 8 * L, cache_fp8=True)
+    caches = {}
+    for l in range(L):
+        Q, K, V = H.make_inputs(w, B, l, n)
+        bud = S[:, l, :]
+        rec = bud // 4
+        score32 = np.random.default_rng(l).random((B, w.n_kv_heads, n), dtype=np.float32) * G
+        ctx.d2o_scores_import(l, score32)
+        ctx.d2o_compress_layer_heads(l, K, V, bud, rec)
+        torch.cuda.synchronize()
+        Kd, Vd = binding.tensor_to_f64(K), binding.tensor_to_f64(V)
+        for b in range(B):
+            for h in range(w.n_kv_heads):
+                cache, ev = ref.compress_head(Kd[b, h], Vd[b, h], score32[b, h].astype(np.float64), int(bud[b, h]),
+                                              int(rec[b, h]), 0, "fp8")
+                ret, evi, tgt, us, ps = ctx.d2o_prefill_events(l, b, h, n)
+                assert np.array_equal(ret, ev.retained) and np.array_equal(tgt, ev.target) and np.array_equal(ps, ev.passed)
+                gK, gV, gs, gp, gtau = ctx.d2o_cache_export(l, b, h, int(bud[b, h]) + 1)
+                assert np.array_equal(gp, cache.pos) and np.array_equal(gK, cache.K) and np.array_equal(gV, cache.V)
+                caches[(l, b, h)] = cache
+    steps = 6
+    q, k, v = H.decode_inputs(w, B, list(range(L)), steps)
+    qd, kd, vd = (binding.tensor_to_f64(t) for t in (q, k, v))
+    out = torch.empty(q[0].shape, dtype=ctx.out_dtype, device=q.device)
+    worst = 0.0
+    for t in range(steps):
+        ctx.d2o_decode_step_static(0, L, q[t], k[t], v[t], out)
+        torch.cuda.synchronize()
+        od = binding.tensor_to_f64(out)
+        for l in range(L):
+            e_, t_, u_ = ctx.d2o_last_events(l)
+            for b in range(B):
+                for h in range(w.n_kv_heads):
+                    bud = int(S[b, l, h])
+                    want, e = ref.decode_step_head(caches[(l, b, h)], qd[t, l, b, h * G:(h + 1) * G], kd[t, l, b, h],
+                                                   vd[t, l, b, h], n + t, bud, bud // 4, 0, w.beta)
+                    assert (e_[b, h], t_[b, h]) == (e.evicted_pos, e.target_pos), f"step {t} l={l} b={b} h={h}"
+                    assert abs(u_[b, h] - e.u_star) < 1e-13
+                    worst = max(worst, H.rownorm_err(od[l, b, h * G:(h + 1) * G], want))
+    assert worst <= H.FLOAT_TOL
+    for (l, b, h), cache in caches.items():
+        gK, gV, gs, gp, gtau = ctx.d2o_cache_export(l, b, h, int(S[b, l, h]) + 1)
+        assert np.array_equal(gp, cache.pos) and np.array_equal(gK, cache.K) and np.array_equal(gV, cache.V)
+        np.testing.assert_allclose(gs, cache.score, rtol=1e-12)
+    ctx.close()
