@@ -341,6 +341,18 @@ def main():
                                "recent": a_recent, "tokens_per_s_one_layer": w.batch * m / (a_ms * 1e-3)}
         actx.close()
         del Qa, Ka, Va, Qb, Kb, Vb, Ob
+    # ---- outside the timed region: the same workload's decode steps on the fp8 cache encoding
+    if w.dtype == "bf16" and not args.layers and not args.cache_fp8:
+        fctx = binding.D2O(w.batch, w.n_layers, w.n_q_heads, w.n_kv_heads, w.head_dim, w.prompt_len,
+                           slots, dtype=w.dtype, n_sink=0, beta=w.beta, split_rows=args.split_rows, cache_fp8=True)
+        run_step(fctx, w, Q, K, V, O, dq, dk, dv, dout, dsteps)
+        _, fdec, _, _ = run_step(fctx, w, Q, K, V, O, dq, dk, dv, dout, dsteps)
+        f_bytes = float(sum(int(s) for s in slots_b) * w.n_kv_heads * (2 * d + 2 + 8))
+        out["fp8_cache"] = {"decode_ms_per_step": fdec / dsteps, "tokens_per_s": w.batch * dsteps / (fdec * 1e-3),
+                            "algorithmic_bytes_per_step": f_bytes,
+                            "decode_step_hbm_frac": f_bytes / (fdec / dsteps * 1e-3) / 1e9 / PEAK_HBM_GBS,
+                            "candidate_misses": int(fctx.d2o_candidate_misses())}
+        fctx.close()
     if args.zero_data_probe:
         probe = {}
         for tag, (q, k, v) in (("workload_data", (Q[0], K[0], V[0])),

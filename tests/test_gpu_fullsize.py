@@ -178,8 +178,10 @@ def test_full_size_sampled_heads(cfg):
     ctx.close()
 
 
-def test_config3_as_benchmarked_allocated_budgets_bf16_outputs_and_32_decode_steps():
-    """Configuration 3 in the shape bench.py times it: all 32 layers in one context, budgets from
+@pytest.mark.parametrize("cache_fp8", [False, True])
+def test_config3_as_benchmarked_allocated_budgets_bf16_outputs_and_32_decode_steps(cache_fp8):
+    """(Once with the cache in bf16, once with the fp8 cache encoding.)
+    Configuration 3 in the shape bench.py times it: all 32 layers in one context, budgets from
     d2o_allocate_budgets on the library's own densities (they span two orders of magnitude),
     bf16 attention outputs, every decode step one call over all layers.  The oracle follows
     the layers with the largest and the smallest budget and one in between, two heads each:
@@ -190,7 +192,8 @@ def test_config3_as_benchmarked_allocated_budgets_bf16_outputs_and_32_decode_ste
     steps = 32
     dev = torch.device("cuda:0")
     slots = w.total_budget() + L + 8
-    ctx = binding.D2O(B, L, w.n_q_heads, w.n_kv_heads, d, n, slots, dtype=w.dtype, beta=w.beta)
+    ctx = binding.D2O(B, L, w.n_q_heads, w.n_kv_heads, d, n, slots, dtype=w.dtype, beta=w.beta, cache_fp8=cache_fp8)
+    storage = "fp8" if cache_fp8 else w.dtype
     O = torch.empty((B, w.n_q_heads, n, d), dtype=torch.bfloat16, device=dev)
     print("prompt attention of all 32 layers", flush=True)
     for l in range(L):
@@ -228,7 +231,7 @@ def test_config3_as_benchmarked_allocated_budgets_bf16_outputs_and_32_decode_ste
             torch.cuda.synchronize()
             for (b, h) in heads:
                 Kd, Vd, sc = caches[(l, b, h)]
-                cache, ev = ref.compress_head(Kd, Vd, sc, bud, rec, 0, w.dtype)
+                cache, ev = ref.compress_head(Kd, Vd, sc, bud, rec, 0, storage)
                 ret, evi, tgt, us, ps = ctx.d2o_prefill_events(l, b, h, n)
                 assert np.array_equal(ret, ev.retained) and np.array_equal(evi, ev.evicted)
                 assert np.array_equal(tgt, ev.target) and np.array_equal(ps, ev.passed)
