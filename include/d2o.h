@@ -84,7 +84,7 @@ typedef struct {
                           /* prompt compression, new tokens before they are attended to,      */
                           /* merged rows); every read sees the decoded values.  The paper      */
                           /* names KV-cache quantisation as future work and fixes no format.   */
-                          /* Needs dtype D2O_BF16 and max_append <= 1.  0: cache in `dtype`.    */
+                          /* Needs dtype D2O_BF16.  0: cache in `dtype`.                       */
 } d2o_config;
 
 /* A strided tensor whose last dimension (d) is contiguous.  Strides are in elements.

@@ -111,12 +111,12 @@ __global__ __launch_bounds__(256) void permute_rows(const int32_t* __restrict__ 
 constexpr int kQG = 8;             // queries per pass over a row
 constexpr int kMaxQuerySlices = 16;  // workgroups that share the queries of a (head, chunk)
 
-template <typename T, int D>
+template <typename T, typename IT, int D>
 __global__ __launch_bounds__(256) void block_begin(const int32_t* __restrict__ ccount, int32_t* __restrict__ ctotal,
                                                    const int32_t* __restrict__ meta, T* __restrict__ cK,
                                                    T* __restrict__ cV, double* __restrict__ cscore,
-                                                   int32_t* __restrict__ cpos, const T* __restrict__ q, View qv,
-                                                   const T* __restrict__ kn, View kv, const T* __restrict__ vn, View vv,
+                                                   int32_t* __restrict__ cpos, const IT* __restrict__ q, View qv,
+                                                   const IT* __restrict__ kn, View kv, const IT* __restrict__ vn, View vv,
                                                    double* __restrict__ aq, int m, int G, int maxq, int first_pos,
                                                    int64_t slots) {
   const int hk = blockIdx.x, b = blockIdx.y, Hkv = gridDim.x;
@@ -124,10 +124,12 @@ __global__ __launch_bounds__(256) void block_begin(const int32_t* __restrict__ c
   const int64_t bh = int64_t(b) * Hkv + hk;
   const int count = ccount[bh];  // the entry count moves to N in block_norm, when no workgroup of this launch reads it any more
   const int64_t slot0 = bh * slots + meta[bh * 4 + 0];
-  for (int x = tid; x < m * D; x += nt) {
-    const int i = x / D, c = x % D;
-    cK[(slot0 + count + i) * D + c] = kn[b * kv.sb + hk * kv.sh + int64_t(i) * kv.sn + c];
-    cV[(slot0 + count + i) * D + c] = vn[b * vv.sb + hk * vv.sh + int64_t(i) * vv.sn + c];
+  if constexpr (sizeof(T) == sizeof(IT)) {  // (an fp8 cache gets its rows from block_rows_fp8)
+    for (int x = tid; x < m * D; x += nt) {
+      const int i = x / D, c = x % D;
+      cK[(slot0 + count + i) * D + c] = kn[b * kv.sb + hk * kv.sh + int64_t(i) * kv.sn + c];
+      cV[(slot0 + count + i) * D + c] = vn[b * vv.sb + hk * vv.sh + int64_t(i) * vv.sn + c];
+    }
   }
   for (int i = tid; i < m; i += nt) {
     cscore[slot0 + count + i] = 0.0;
@@ -137,7 +139,7 @@ __global__ __launch_bounds__(256) void block_begin(const int32_t* __restrict__ c
   for (int x = tid; x < nq_pad * D; x += nt) {
     const int qi = x / D, c = x % D;
     double v = 0.0;
-    if (qi < nq) v = Elem<T>::to_f64(q[b * qv.sb + (hk * G + qi % G) * qv.sh + int64_t(qi / G) * qv.sn + c]);
+    if (qi < nq) v = Elem<IT>::to_f64(q[b * qv.sb + (hk * G + qi % G) * qv.sh + int64_t(qi / G) * qv.sn + c]);
     aq[(bh * maxq + qi) * D + c] = v;
   }
   if (tid == 0) ctotal[bh] = count + m;
@@ -175,10 +177,12 @@ struct BlockRows {
 // set is pinned before the other set's loads are issued, because scalar loads return out of
 // order).
 template <typename T, int D>
-__device__ __forceinline__ void block_logits(const unsigned char* myrow, const double* aq_head, int q0, double* s) {
+__device__ __forceinline__ void block_logits(const unsigned char* myrow, const double* aq_head, int q0, double* s,
+                                             double row_scale) {
   typedef const double __attribute__((address_space(4))) * cptr;
   constexpr int ES = 2, NST = D / ES;
-  typedef typename std::conditional<sizeof(T) == 2, uint32_t, u32x2>::type Raw;
+  typedef typename std::conditional<sizeof(T) == 1, uint16_t,
+                                    typename std::conditional<sizeof(T) == 2, uint32_t, u32x2>::type>::type Raw;
   const cptr Qv = (cptr)(aq_head + int64_t(q0) * D);
 #pragma unroll
   for (int u = 0; u < kQG; ++u) s[u] = 0.0;
@@ -193,7 +197,10 @@ __device__ __forceinline__ void block_logits(const unsigned char* myrow, const d
   };
   auto step = [&](const Raw& raw, const double (&sv)[kQG][ES]) {
     double k[ES];
-    if constexpr (sizeof(T) == 2) {
+    if constexpr (sizeof(T) == 1) {  // fp8 codes, without the row's power of two (the caller applies it)
+      k[0] = double(__builtin_amdgcn_cvt_f32_fp8(int(raw), 0));
+      k[1] = double(__builtin_amdgcn_cvt_f32_fp8(int(raw), 1));
+    } else if constexpr (sizeof(T) == 2) {
       k[0] = double(__uint_as_float(raw << 16));
       k[1] = double(__uint_as_float(raw & 0xFFFF0000u));
     } else {
@@ -219,13 +226,14 @@ __device__ __forceinline__ void block_logits(const unsigned char* myrow, const d
   }
   const double root_d = sqrt(double(D));
 #pragma unroll
-  for (int u = 0; u < kQG; ++u) s[u] = s[u] / root_d;
+  for (int u = 0; u < kQG; ++u) s[u] = (sizeof(T) == 1 ? s[u] * row_scale : s[u]) / root_d;  // exact scaling of exact sums
 }
 
 template <typename T, int D>
 __global__ __launch_bounds__(256) void block_stats(const int32_t* __restrict__ ctotal, const int32_t* __restrict__ meta,
-                                                   const T* __restrict__ cK, const double* __restrict__ aq,
-                                                   double* __restrict__ stat, int m, int G, int maxq, int64_t slots) {
+                                                   const T* __restrict__ cK, const int8_t* __restrict__ cKe,
+                                                   const double* __restrict__ aq, double* __restrict__ stat, int m, int G,
+                                                   int maxq, int64_t slots) {
   typedef BlockRows<T, D> BR;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];  // [4][64 rows] staged keys
   __shared__ double wm[4][kQG], wl[4][kQG];
@@ -239,11 +247,13 @@ __global__ __launch_bounds__(256) void block_stats(const int32_t* __restrict__ c
   unsigned char* mine = smem + w * BR::kWaveBytes;
   BR::stage(cK, slot0, chunk * kChunk + w * 64, N - 1, mine, lane);
   const unsigned char* myrow = mine + lane * BR::kPitch;
+  double ksc = 1.0;
+  if constexpr (sizeof(T) == 1) ksc = pow2_f64(cKe[slot0 + min(j, N - 1)]);
   const int nq = m * G, ngrp = (nq + kQG - 1) / kQG, gper = (ngrp + gridDim.z - 1) / gridDim.z;
   const int q_lo = blockIdx.z * gper * kQG, q_hi = min(nq, q_lo + gper * kQG);  // this workgroup's slice of the queries
   for (int q0 = q_lo; q0 < q_hi; q0 += kQG) {
     double s[kQG];
-    block_logits<T, D>(myrow, aq + int64_t(bh) * maxq * D, q0, s);
+    block_logits<T, D>(myrow, aq + int64_t(bh) * maxq * D, q0, s, ksc);
 #pragma unroll
     for (int u = 0; u < kQG; ++u) {
       const bool vis = valid && j <= nc + (q0 + u) / G;
@@ -291,6 +301,7 @@ __global__ __launch_bounds__(256) void block_norm(const int32_t* __restrict__ ct
 template <typename T, int D>
 __global__ __launch_bounds__(256) void block_apply(const int32_t* __restrict__ ctotal, const int32_t* __restrict__ meta,
                                                    const T* __restrict__ cK, const T* __restrict__ cV,
+                                                   const int8_t* __restrict__ cKe, const int8_t* __restrict__ cVe,
                                                    double* __restrict__ spart, const double* __restrict__ aq,
                                                    const double* __restrict__ norm, float* __restrict__ pout, int m,
                                                    int G, int maxq, int64_t slots, int rows_cap) {
@@ -309,14 +320,26 @@ __global__ __launch_bounds__(256) void block_apply(const int32_t* __restrict__ c
   unsigned char* mine = smem + w * BR::kWaveBytes;
   BR::stage(cK, slot0, r0, N - 1, mine, lane);
   const unsigned char* myrow = mine + lane * BR::kPitch;
-  // the wavefront's 64 value rows, this lane's CPL columns of each, as raw words
-  constexpr int VW = CPL * sizeof(T) / 4;
+  // the wavefront's 64 value rows, this lane's CPL columns of each, as raw words (fp8: two codes
+  // in half a word; the row's power of two rides on the row's probability)
+  constexpr int VW = sizeof(T) == 1 ? 1 : CPL * sizeof(T) / 4;
   uint32_t vraw[64][VW];
 #pragma unroll
   for (int r = 0; r < 64; ++r) {
-    const uint32_t* vr = reinterpret_cast<const uint32_t*>(cV + (slot0 + min(r0 + r, N - 1)) * D + lane * CPL);
+    if constexpr (sizeof(T) == 1) {
+      static_assert(sizeof(T) != 1 || CPL == 2, "two codes per lane");
+      vraw[r][0] = reinterpret_cast<const uint16_t*>(cV + (slot0 + min(r0 + r, N - 1)) * D)[lane];
+    } else {
+      const uint32_t* vr = reinterpret_cast<const uint32_t*>(cV + (slot0 + min(r0 + r, N - 1)) * D + lane * CPL);
 #pragma unroll
-    for (int c = 0; c < VW; ++c) vraw[r][c] = vr[c];
+      for (int c = 0; c < VW; ++c) vraw[r][c] = vr[c];
+    }
+  }
+  double ksc = 1.0;
+  float vsc = 1.f;
+  if constexpr (sizeof(T) == 1) {
+    ksc = pow2_f64(cKe[slot0 + min(j, N - 1)]);
+    vsc = pow2_f32(cVe[slot0 + min(j, N - 1)]);
   }
   double sc = 0.0;
   const int nq = m * G, ngrp = (nq + kQG - 1) / kQG, gper = (ngrp + gridDim.z - 1) / gridDim.z;
@@ -324,7 +347,7 @@ __global__ __launch_bounds__(256) void block_apply(const int32_t* __restrict__ c
   typedef const double __attribute__((address_space(4))) * cptr;
   for (int q0 = q_lo; q0 < q_hi; q0 += kQG) {
     double s[kQG];
-    block_logits<T, D>(myrow, aq + int64_t(bh) * maxq * D, q0, s);
+    block_logits<T, D>(myrow, aq + int64_t(bh) * maxq * D, q0, s, ksc);
     const cptr nm = (cptr)(norm + (int64_t(bh) * maxq + q0) * 2);
     float p32[kQG];
 #pragma unroll
@@ -332,7 +355,7 @@ __global__ __launch_bounds__(256) void block_apply(const int32_t* __restrict__ c
       const bool vis = valid && q0 + u < nq && j <= nc + (q0 + u) / G;
       const double p = vis ? exp(s[u] - nm[2 * u]) / nm[2 * u + 1] : 0.0;
       sc += p;  // Eq. 6: the slice's probabilities, in (token, query head) order
-      p32[u] = float(p);
+      p32[u] = sizeof(T) == 1 ? float(p) * vsc : float(p);
     }
     float acc[kQG][CPL];
 #pragma unroll
@@ -344,7 +367,10 @@ __global__ __launch_bounds__(256) void block_apply(const int32_t* __restrict__ c
 #pragma unroll
       for (int u = 0; u < kQG; ++u) {
         const float pr = __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(p32[u]), r));
-        if constexpr (sizeof(T) == 2) {
+        if constexpr (sizeof(T) == 1) {
+          acc[u][0] = fmaf(pr, __builtin_amdgcn_cvt_f32_fp8(int(vraw[r][0]), 0), acc[u][0]);
+          acc[u][1] = fmaf(pr, __builtin_amdgcn_cvt_f32_fp8(int(vraw[r][0]), 1), acc[u][1]);
+        } else if constexpr (sizeof(T) == 2) {
           static_assert(sizeof(T) != 2 || CPL == 2, "two bf16 columns per lane");
           acc[u][0] = fmaf(pr, __uint_as_float(vraw[r][0] << 16), acc[u][0]);
           acc[u][1] = fmaf(pr, __uint_as_float(vraw[r][0] & 0xFFFF0000u), acc[u][1]);
@@ -393,8 +419,56 @@ __global__ __launch_bounds__(D) void block_finish(const int32_t* __restrict__ ct
   out[b * ov.sb + (hk * G + q % G) * ov.sh + int64_t(q / G) * ov.sn + c] = Elem<OT>::from_f32(t);
 }
 
+// fp8 cache: the same permutation, decoding every row into the bf16 copy on the way (a code times
+// a power of two has four significant bits: exact in bf16).  One wavefront per row, D = 128.
+__global__ __launch_bounds__(256) void permute_decode_rows(const int32_t* __restrict__ on, const int32_t* __restrict__ meta,
+                                                           const int32_t* __restrict__ rank, const uint8_t* __restrict__ cK,
+                                                           const uint8_t* __restrict__ cV, const int8_t* __restrict__ cKe,
+                                                           const int8_t* __restrict__ cVe, uint16_t* __restrict__ oK,
+                                                           uint16_t* __restrict__ oV, int npad, int64_t slots) {
+  constexpr int D = 128;
+  const int hk = blockIdx.y, b = blockIdx.z, Hkv = gridDim.y, lane = threadIdx.x & 63;
+  const int64_t bh = int64_t(b) * Hkv + hk;
+  const int j = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (j >= on[bh]) return;
+  const int64_t src = bh * slots + meta[bh * 4 + 0] + j;
+  const int64_t dst = (bh * npad + rank[bh * npad + j]) * D;
+#pragma unroll
+  for (int which = 0; which < 2; ++which) {
+    const uint16_t codes = reinterpret_cast<const uint16_t*>((which ? cV : cK) + src * D)[lane];
+    const float sc = pow2_f32((which ? cVe : cKe)[src]);
+    const float v0 = Elem<uint8_t>::to_f32(uint8_t(codes & 0xFF)) * sc, v1 = Elem<uint8_t>::to_f32(uint8_t(codes >> 8)) * sc;
+    reinterpret_cast<uint32_t*>((which ? oV : oK) + dst)[lane] = (__float_as_uint(v0) >> 16) | (__float_as_uint(v1) & 0xFFFF0000u);
+  }
+}
+
+// fp8 cache: the block's K and V rows encoded into the cache (one wavefront per new row).
+__global__ __launch_bounds__(256) void block_rows_fp8(const int32_t* __restrict__ ccount, const int32_t* __restrict__ meta,
+                                                      uint8_t* __restrict__ cK, uint8_t* __restrict__ cV,
+                                                      int8_t* __restrict__ cKe, int8_t* __restrict__ cVe,
+                                                      const uint16_t* __restrict__ kn, View kv,
+                                                      const uint16_t* __restrict__ vn, View vv, int m, int64_t slots) {
+  constexpr int D = 128;
+  const int hk = blockIdx.y, b = blockIdx.z, Hkv = gridDim.y, lane = threadIdx.x & 63;
+  const int64_t bh = int64_t(b) * Hkv + hk;
+  const int i = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (i >= m) return;
+  const int64_t dst = bh * slots + meta[bh * 4 + 0] + ccount[bh] + i;  // (the entry count moves later, in block_norm)
+#pragma unroll
+  for (int which = 0; which < 2; ++which) {
+    const uint16_t* src = which ? vn + b * vv.sb + hk * vv.sh + int64_t(i) * vv.sn : kn + b * kv.sb + hk * kv.sh + int64_t(i) * kv.sn;
+    const uint32_t two = reinterpret_cast<const uint32_t*>(src)[lane];
+    const double x0 = double(__uint_as_float(two << 16)), x1 = double(__uint_as_float(two & 0xFFFF0000u));
+    const int e = fp8_row_exponent(wave_max(fmax(fabs(x0), fabs(x1))));
+    reinterpret_cast<uint16_t*>((which ? cV : cK) + dst * D)[lane] =
+        uint16_t(fp8_encode(ldexp(x0, -e))) | uint16_t(uint16_t(fp8_encode(ldexp(x1, -e))) << 8);
+    if (lane == 0) (which ? cVe : cKe)[dst] = int8_t(e);
+  }
+}
+
 template <typename T, int D>
 hipError_t run_block_attend(d2o_ctx* c, int layer, View q, View k, View v, View out, int m, int first_pos, hipStream_t s) {
+  typedef typename std::conditional<sizeof(T) == 1, uint16_t, T>::type IT;  // the tensors' type (an fp8 cache takes bf16 tensors)
   const d2o_config& cf = c->cfg;
   const int G = cf.n_q_heads / cf.n_kv_heads, bh = cf.batch * cf.n_kv_heads, maxq = c->ap_maxq;
   const size_t lo = size_t(layer) * bh;
@@ -409,25 +483,30 @@ hipError_t run_block_attend(d2o_ctx* c, int layer, View q, View k, View v, View 
   // as workgroups of their own, enough of them to fill the chip a few times over
   const int ngrp = (m * G + kQG - 1) / kQG;
   const int nslice = std::max(1, std::min({kMaxQuerySlices, ngrp, 4096 / std::max(1, bh * nch)}));
-  block_begin<T, D><<<dim3(cf.n_kv_heads, cf.batch, 8), 256, 0, s>>>(ccount, ctotal, meta, (T*)c->cacheK, (T*)c->cacheV, c->cscore,
-                                                                     c->cpos, (const T*)q.ptr, q, (const T*)k.ptr, k,
-                                                                     (const T*)v.ptr, v, c->ap_q, m, G, maxq, first_pos,
-                                                                     cf.slots_per_seq);
+  block_begin<T, IT, D><<<dim3(cf.n_kv_heads, cf.batch, 8), 256, 0, s>>>(ccount, ctotal, meta, (T*)c->cacheK, (T*)c->cacheV, c->cscore,
+                                                                         c->cpos, (const IT*)q.ptr, q, (const IT*)k.ptr, k,
+                                                                         (const IT*)v.ptr, v, c->ap_q, m, G, maxq, first_pos,
+                                                                         cf.slots_per_seq);
+  if constexpr (sizeof(T) == 1)
+    block_rows_fp8<<<dim3((m + 3) / 4, cf.n_kv_heads, cf.batch), 256, 0, s>>>(ccount, meta, (uint8_t*)c->cacheK, (uint8_t*)c->cacheV,
+                                                                               c->cKe, c->cVe, (const uint16_t*)k.ptr, k,
+                                                                               (const uint16_t*)v.ptr, v, m, cf.slots_per_seq);
   constexpr int kRowsLds = 4 * BlockRows<T, D>::kWaveBytes;
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(block_stats<T, D>), hipFuncAttributeMaxDynamicSharedMemorySize, kRowsLds);
   if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(block_apply<T, D>), hipFuncAttributeMaxDynamicSharedMemorySize, kRowsLds);
   if (e != hipSuccess) return e;
-  block_stats<T, D><<<dim3(bh, nch, nslice), 256, kRowsLds, s>>>(ctotal, meta, (const T*)c->cacheK, c->ap_q, c->ap_stat, m, G, maxq,
-                                                              cf.slots_per_seq);
+  block_stats<T, D><<<dim3(bh, nch, nslice), 256, kRowsLds, s>>>(ctotal, meta, (const T*)c->cacheK, c->cKe, c->ap_q, c->ap_stat, m, G,
+                                                              maxq, cf.slots_per_seq);
   block_norm<<<dim3(bh), 256, 0, s>>>(ctotal, ccount, c->ap_stat, c->ap_norm, m, G, maxq);
   const int rows_cap = c->ap_nch * kChunk;
-  block_apply<T, D><<<dim3(bh, nch, nslice), 256, kRowsLds, s>>>(ctotal, meta, (const T*)c->cacheK, (const T*)c->cacheV, c->ap_spart,
-                                                              c->ap_q, c->ap_norm, c->ap_out, m, G, maxq, cf.slots_per_seq, rows_cap);
+  block_apply<T, D><<<dim3(bh, nch, nslice), 256, kRowsLds, s>>>(ctotal, meta, (const T*)c->cacheK, (const T*)c->cacheV, c->cKe, c->cVe,
+                                                              c->ap_spart, c->ap_q, c->ap_norm, c->ap_out, m, G, maxq,
+                                                              cf.slots_per_seq, rows_cap);
   block_scores<<<dim3(bh, nch), 256, 0, s>>>(ctotal, meta, c->cscore, c->ap_spart, nslice, cf.slots_per_seq, rows_cap);
   if (cf.out_f32)
     block_finish<float, D><<<dim3(bh, m * G), D, 0, s>>>(ctotal, c->ap_out, (float*)out.ptr, out, G, maxq, cf.n_kv_heads);
   else
-    block_finish<T, D><<<dim3(bh, m * G), D, 0, s>>>(ctotal, c->ap_out, (T*)out.ptr, out, G, maxq, cf.n_kv_heads);
+    block_finish<IT, D><<<dim3(bh, m * G), D, 0, s>>>(ctotal, c->ap_out, (IT*)out.ptr, out, G, maxq, cf.n_kv_heads);
   return hipGetLastError();
 }
 
@@ -442,7 +521,11 @@ hipError_t launch_cache_sort(d2o_ctx* c, int layer, hipStream_t s) {
   rank_by_position<<<dim3(cf.n_kv_heads, cf.batch, (max_rows + 1023) / 1024), 256, 0, s>>>(ccount, meta, c->cscore, c->cpos, c->app_rank,
                                                                   c->app_pos, c->app_score, c->app_n, c->npad,
                                                                   cf.slots_per_seq);
-  if (cf.dtype == D2O_BF16) {
+  if (cf.cache_fp8) {
+    permute_decode_rows<<<dim3((max_rows + 3) / 4, cf.n_kv_heads, cf.batch), 256, 0, s>>>(
+        c->app_n, meta, c->app_rank, (const uint8_t*)c->cacheK, (const uint8_t*)c->cacheV, c->cKe, c->cVe,
+        (uint16_t*)c->app_K, (uint16_t*)c->app_V, c->npad, cf.slots_per_seq);
+  } else if (cf.dtype == D2O_BF16) {
     const int rows = 256 / (cf.head_dim / 8);
     permute_rows<uint16_t><<<dim3((max_rows + rows - 1) / rows, cf.n_kv_heads, cf.batch), 256, 0, s>>>(
         c->app_n, meta, c->app_rank, (const uint16_t*)c->cacheK, (const uint16_t*)c->cacheV, (uint16_t*)c->app_K,
@@ -459,6 +542,7 @@ hipError_t launch_cache_sort(d2o_ctx* c, int layer, hipStream_t s) {
 hipError_t launch_block_attend(d2o_ctx* c, int layer, View q, View k, View v, View out, int m, int first_pos,
                                hipStream_t s) {
   const d2o_config& cf = c->cfg;
+  if (cf.cache_fp8) return run_block_attend<uint8_t, 128>(c, layer, q, k, v, out, m, first_pos, s);
   if (cf.dtype == D2O_BF16) return run_block_attend<uint16_t, 128>(c, layer, q, k, v, out, m, first_pos, s);
   if (cf.head_dim == 64) return run_block_attend<float, 64>(c, layer, q, k, v, out, m, first_pos, s);
   return run_block_attend<float, 128>(c, layer, q, k, v, out, m, first_pos, s);

@@ -54,7 +54,7 @@ int check_config(const d2o_config* c) {
   if (c->max_append < 0 || c->max_append >= c->max_prompt_len) return D2O_ERR_INVALID_ARG;
   if (c->split_rows != 0 && c->split_rows < 256) return D2O_ERR_INVALID_ARG;
   if (c->cache_fp8 != 0 && c->cache_fp8 != 1) return D2O_ERR_INVALID_ARG;
-  if (c->cache_fp8 && (c->dtype != D2O_BF16 || c->max_append > 1)) return D2O_ERR_UNSUPPORTED;
+  if (c->cache_fp8 && c->dtype != D2O_BF16) return D2O_ERR_UNSUPPORTED;
   return D2O_OK;
 }
 
@@ -113,8 +113,10 @@ void layout(d2o_ctx* x, char* persistent, char* scratch, size_t* pbytes, size_t*
   s.take(x->g_cur, bh * (np + 1));
   s.take(x->g_src, bh * np);
   const size_t ap = c.max_append > 1 ? 1 : 0;  // the position-ordered copy exists only when blocks can be appended
-  s.take_raw(x->app_K, (ap | f8) * bh * np * d * es);
-  s.take_raw(x->app_V, (ap | f8) * bh * np * d * es);
+  s.take_raw(x->st_K, f8 * bh * np * d * es);
+  s.take_raw(x->st_V, f8 * bh * np * d * es);
+  s.take_raw(x->app_K, ap * bh * np * d * es);
+  s.take_raw(x->app_V, ap * bh * np * d * es);
   s.take(x->app_score, ap * bh * np);
   s.take(x->app_pos, ap * bh * np);
   s.take(x->app_rank, ap * bh * np);
@@ -654,6 +656,7 @@ int d2o_append_chunk(d2o_ctx* x, int32_t layer, d2o_view Q, d2o_view K, d2o_view
   if ((e = launch_match(x, layer, aK, n_eff, s)) != hipSuccess) return fail(x, D2O_ERR_HIP, std::string("append, match: ") + hipGetErrorString(e));
   if ((e = launch_threshold_group(x, layer, n_eff, s, true)) != hipSuccess) return fail(x, D2O_ERR_HIP, std::string("append, threshold: ") + hipGetErrorString(e));
   if ((e = launch_merge(x, layer, aK, aV, n_eff, s)) != hipSuccess) return fail(x, D2O_ERR_HIP, std::string("append, merge: ") + hipGetErrorString(e));
+  if (c.cache_fp8 && (e = launch_encode_layer(x, layer, s)) != hipSuccess) return fail(x, D2O_ERR_HIP, std::string("append, encode: ") + hipGetErrorString(e));
   if ((e = launch_init_candidates(x, layer, st.next_pos, s)) != hipSuccess) return fail(x, D2O_ERR_HIP, std::string("append, candidates: ") + hipGetErrorString(e));
   x->last_append_layer = layer;
   x->last_compress_layer = -1;  // the prompt-phase events shared the scratch lists and are gone
@@ -693,8 +696,8 @@ int d2o_cache_export(d2o_ctx* x, int32_t layer, int32_t b, int32_t h, void* K, v
   if (c.cache_fp8) {  // decoded into the head's bf16 staging rows first (the decoded values are exact in bf16)
     const size_t stage0 = (size_t(b) * c.n_kv_heads + h) * x->npad;
     D2O_HIP_CHECK(x, launch_decode_head(x, layer, b, h, cnt, s));
-    D2O_HIP_CHECK(x, hipMemcpyAsync(k.data(), static_cast<char*>(x->app_K) + stage0 * row, cnt * row, hipMemcpyDeviceToHost, s));
-    D2O_HIP_CHECK(x, hipMemcpyAsync(v.data(), static_cast<char*>(x->app_V) + stage0 * row, cnt * row, hipMemcpyDeviceToHost, s));
+    D2O_HIP_CHECK(x, hipMemcpyAsync(k.data(), static_cast<char*>(x->st_K) + stage0 * row, cnt * row, hipMemcpyDeviceToHost, s));
+    D2O_HIP_CHECK(x, hipMemcpyAsync(v.data(), static_cast<char*>(x->st_V) + stage0 * row, cnt * row, hipMemcpyDeviceToHost, s));
   } else {
     D2O_HIP_CHECK(x, hipMemcpyAsync(k.data(), static_cast<char*>(x->cacheK) + slot0 * row, cnt * row, hipMemcpyDeviceToHost, s));
     D2O_HIP_CHECK(x, hipMemcpyAsync(v.data(), static_cast<char*>(x->cacheV) + slot0 * row, cnt * row, hipMemcpyDeviceToHost, s));
@@ -731,8 +734,8 @@ int d2o_cache_import(d2o_ctx* x, int32_t layer, int32_t b, int32_t h, const void
   const size_t row = size_t(c.head_dim) * x->esize;
   if (c.cache_fp8) {  // the bf16 rows go to the head's staging rows and are encoded from there
     const size_t stage0 = (size_t(b) * c.n_kv_heads + h) * x->npad;
-    D2O_HIP_CHECK(x, hipMemcpyAsync(static_cast<char*>(x->app_K) + stage0 * row, K, count * row, hipMemcpyHostToDevice, s));
-    D2O_HIP_CHECK(x, hipMemcpyAsync(static_cast<char*>(x->app_V) + stage0 * row, V, count * row, hipMemcpyHostToDevice, s));
+    D2O_HIP_CHECK(x, hipMemcpyAsync(static_cast<char*>(x->st_K) + stage0 * row, K, count * row, hipMemcpyHostToDevice, s));
+    D2O_HIP_CHECK(x, hipMemcpyAsync(static_cast<char*>(x->st_V) + stage0 * row, V, count * row, hipMemcpyHostToDevice, s));
     D2O_HIP_CHECK(x, launch_encode_head(x, layer, b, h, count, s));
   } else {
     D2O_HIP_CHECK(x, hipMemcpyAsync(static_cast<char*>(x->cacheK) + slot0 * row, K, count * row, hipMemcpyHostToDevice, s));

@@ -112,9 +112,11 @@ struct d2o_ctx {
   int32_t* g_off = nullptr;      // [..][npad+1] exclusive prefix of g_cnt
   int32_t* g_cur = nullptr;      // [..][npad+1] fill cursors
   int32_t* g_src = nullptr;      // evicted ranks grouped by target (unordered inside a group)
-  // multi-token append: the cache in ascending token position (block-level Eq. 7-12 run on it);
   // fp8 cache: the bf16 rows of the layer being compressed (the prompt-phase kernels work on
   // them; encode_layer then writes the cache) and of a head being imported or exported
+  void* st_K = nullptr;          // [B][Hkv][npad][d]
+  void* st_V = nullptr;          // [B][Hkv][npad][d]
+  // multi-token append: the cache in ascending token position (block-level Eq. 7-12 run on it)
   void* app_K = nullptr;         // [B][Hkv][npad][d]
   void* app_V = nullptr;         // [B][Hkv][npad][d]
   double* app_score = nullptr;   // [B][Hkv][npad] cumulative scores, fp64
@@ -191,8 +193,8 @@ hipError_t launch_merge(d2o_ctx* c, int layer, View K, View V, int n, hipStream_
 // Where the prompt-phase kernels (compaction, matching, merge) keep a layer's cache rows: in the
 // cache itself, or - fp8 cache - in bf16 staging rows [B][Hkv][npad][d] that encode_layer turns
 // into cache rows once the layer's merges are done.
-inline void* prompt_rows_K(const d2o_ctx* c) { return c->cfg.cache_fp8 ? c->app_K : c->cacheK; }
-inline void* prompt_rows_V(const d2o_ctx* c) { return c->cfg.cache_fp8 ? c->app_V : c->cacheV; }
+inline void* prompt_rows_K(const d2o_ctx* c) { return c->cfg.cache_fp8 ? c->st_K : c->cacheK; }
+inline void* prompt_rows_V(const d2o_ctx* c) { return c->cfg.cache_fp8 ? c->st_V : c->cacheV; }
 inline int64_t prompt_rows_stride(const d2o_ctx* c) { return c->cfg.cache_fp8 ? c->npad : c->cfg.slots_per_seq; }
 inline const int32_t* prompt_rows_meta(const d2o_ctx* c, int layer) {
   return (c->cfg.cache_fp8 ? c->meta_stage : c->meta) + size_t(layer) * c->cfg.batch * c->cfg.n_kv_heads * 4;

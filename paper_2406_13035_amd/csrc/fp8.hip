@@ -65,7 +65,7 @@ hipError_t launch_encode_layer(d2o_ctx* c, int layer, hipStream_t s) {
   int max_rows = 1;
   for (const auto& mt : c->layers[layer].meta) max_rows = std::max(max_rows, mt.budget);
   encode_rows<<<dim3((max_rows + 3) / 4, bh), 256, 0, s>>>(
-      c->ccount + size_t(layer) * bh, c->meta + size_t(layer) * bh * 4, (const uint16_t*)c->app_K, (const uint16_t*)c->app_V,
+      c->ccount + size_t(layer) * bh, c->meta + size_t(layer) * bh * 4, (const uint16_t*)c->st_K, (const uint16_t*)c->st_V,
       (uint8_t*)c->cacheK, (uint8_t*)c->cacheV, c->cKe, c->cVe, c->npad, cf.slots_per_seq, 0, -1);
   return hipGetLastError();
 }
@@ -75,7 +75,7 @@ hipError_t launch_encode_head(d2o_ctx* c, int layer, int b, int hk, int count, h
   const int bh = cf.batch * cf.n_kv_heads;
   if (count < 1) return hipSuccess;
   encode_rows<<<dim3((count + 3) / 4, 1), 256, 0, s>>>(
-      c->ccount + size_t(layer) * bh, c->meta + size_t(layer) * bh * 4, (const uint16_t*)c->app_K, (const uint16_t*)c->app_V,
+      c->ccount + size_t(layer) * bh, c->meta + size_t(layer) * bh * 4, (const uint16_t*)c->st_K, (const uint16_t*)c->st_V,
       (uint8_t*)c->cacheK, (uint8_t*)c->cacheV, c->cKe, c->cVe, c->npad, cf.slots_per_seq, b * cf.n_kv_heads + hk, count);
   return hipGetLastError();
 }
@@ -85,8 +85,8 @@ hipError_t launch_decode_head(d2o_ctx* c, int layer, int b, int hk, int count, h
   const int bh = cf.batch * cf.n_kv_heads;
   if (count < 1) return hipSuccess;
   decode_rows<<<dim3((count + 3) / 4), 256, 0, s>>>(c->meta + size_t(layer) * bh * 4, (const uint8_t*)c->cacheK,
-                                                    (const uint8_t*)c->cacheV, c->cKe, c->cVe, (uint16_t*)c->app_K,
-                                                    (uint16_t*)c->app_V, c->npad, cf.slots_per_seq,
+                                                    (const uint8_t*)c->cacheV, c->cKe, c->cVe, (uint16_t*)c->st_K,
+                                                    (uint16_t*)c->st_V, c->npad, cf.slots_per_seq,
                                                     b * cf.n_kv_heads + hk, count);
   return hipGetLastError();
 }

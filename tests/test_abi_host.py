@@ -48,6 +48,21 @@ def test_workspace_query_and_config_validation(lib):
         g = 24 // hkv
         want = 0 if g in (1, 2, 4, 8) else -2
         assert lib.d2o_workspace_bytes(C.byref(cfg), C.byref(p), C.byref(s)) == want, (hkv, g)
+    # the fields this build added: split_rows (0 or >= 256), cache_fp8 (bf16 tensors only)
+    def cfg_with(**kw):
+        c = binding.d2o_config(1, 32, 32, 32, 128, 4096, 30000, binding.D2O_BF16, 0, 0.7, float("nan"), 0)
+        for k, v in kw.items():
+            setattr(c, k, v)
+        return c
+    assert lib.d2o_workspace_bytes(C.byref(cfg_with(split_rows=100)), C.byref(p), C.byref(s)) == -1
+    assert lib.d2o_workspace_bytes(C.byref(cfg_with(split_rows=256)), C.byref(p), C.byref(s)) == 0
+    assert lib.d2o_workspace_bytes(C.byref(cfg_with(cache_fp8=2)), C.byref(p), C.byref(s)) == -1
+    assert lib.d2o_workspace_bytes(C.byref(cfg_with(cache_fp8=1, dtype=binding.D2O_F32)), C.byref(p), C.byref(s)) == -2
+    assert lib.d2o_workspace_bytes(C.byref(cfg_with()), C.byref(p), C.byref(s)) == 0
+    bf16_bytes = p.value
+    assert lib.d2o_workspace_bytes(C.byref(cfg_with(cache_fp8=1)), C.byref(p), C.byref(s)) == 0
+    # K and V rows shrink from 256 to 128 bytes (+ 1 byte per row for the power of two)
+    assert bf16_bytes - p.value > 0.9 * 32 * 30000 * 128 * 2
 
 
 def test_allocate_budgets_matches_oracle_bit_for_bit(lib):

@@ -122,10 +122,27 @@ def test_decode_growing_fp8_caches_in_a_multi_layer_call():
     assert ev[0] == (steps - (budgets[0] - n)) * w.n_kv_heads and ev[1] == steps * w.n_kv_heads
 
 
+@pytest.mark.parametrize("case", ["gqa", "mha-sinks", "no-window", "grow", "multi-turn"])
+def test_blocks_of_tokens_on_an_fp8_cache(case):
+    """d2o_append_chunk on an fp8 cache: the block's rows are encoded as they enter the cache, the
+    block-level Eq. 7-12 run on the decoded rows and the survivors are encoded again; single-token
+    steps continue on the result."""
+    from tests.test_gpu_parity import _run_append_parity
+    print(f"case={case}", flush=True)
+    if case == "gqa":
+        _run_append_parity(_small(True), 700, 2, 3, [150, 333], [37, 83], 0, [24, 7, 1, 40], cache_fp8=True)
+    elif case == "mha-sinks":
+        _run_append_parity(_small(False), 500, 1, 8, 120, 30, 3, [16, 50], cache_fp8=True)
+    elif case == "no-window":
+        _run_append_parity(_small(False), 300, 1, 30, 40, 0, 0, [12, 12], cache_fp8=True)
+    elif case == "grow":           # budget above the prompt: blocks are absorbed until the cache is full
+        _run_append_parity(_small(True), 60, 1, 3, 100, 25, 0, [30, 30, 30], cache_fp8=True)
+    else:                          # budget 2048 = 48 heavy hitters + 2000 recent, turns of 300 and 120 tokens
+        _run_append_parity(_small(False).scaled(n_q_heads=2, n_kv_heads=2), 3000, 1, 14, 2048, 2000, 0, [300, 120],
+                           decode_between=1, cache_fp8=True)
+
+
 def test_unsupported_combinations_are_refused():
-    w = _small(False)
-    with pytest.raises(binding.D2OError):
-        H.new_ctx(w, 1, 1, 256, 300, cache_fp8=True, max_append=16)     # no block append on an fp8 cache
     with pytest.raises(binding.D2OError):
         H.new_ctx(synth.WORKLOADS[1], 1, 1, 256, 300, cache_fp8=True)   # fp32 tensors
 

@@ -503,7 +503,8 @@ def _block_inputs(w, B, layer, m, seed):
             torch.stack(vs).contiguous().cuda())
 
 
-def _run_append_parity(w, n, B, layer, budget, recent, sink, blocks, tau_force=float("nan"), decode_between=2):
+def _run_append_parity(w, n, B, layer, budget, recent, sink, blocks, tau_force=float("nan"), decode_between=2,
+                       cache_fp8=False):
     """Prompt compression from given scores, then blocks of new tokens (d2o_append_chunk) with a
     few single-token steps in between; outputs, events and caches against the oracle after
     every call."""
@@ -512,10 +513,11 @@ def _run_append_parity(w, n, B, layer, budget, recent, sink, blocks, tau_force=f
     bud = np.broadcast_to(np.asarray(budget), (B,))
     rec = np.broadcast_to(np.asarray(recent), (B,))
     ctx = H.new_ctx(w, B, 1, max(n, int(bud.max()) + max(blocks)), int(bud.max()) + max(blocks) + 8, n_sink=sink,
-                    tau_force=tau_force, max_append=max(blocks))
+                    tau_force=tau_force, max_append=max(blocks), cache_fp8=cache_fp8)
     ctx.d2o_scores_import(0, score32)
     ctx.d2o_compress_layer(0, K, V, budget, recent)
-    _, caches = H.check_compress_against_oracle(ctx, 0, K, V, score32, budget, recent, sink, w.dtype, tau_force)
+    _, caches = H.check_compress_against_oracle(ctx, 0, K, V, score32, budget, recent, sink,
+                                                "fp8" if cache_fp8 else w.dtype, tau_force)
     G, pos, worst, evicted_total = w.group, n, 0.0, 0
     dq, dk, dv = H.decode_inputs(w, B, [layer], decode_between * len(blocks) + 1)
     dqd, dkd, dvd = (binding.tensor_to_f64(t) for t in (dq, dk, dv))
