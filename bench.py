@@ -163,6 +163,9 @@ def main():
                          "kernels of layer 0 on the workload's data and on all-zero Q, K, V (same "
                          "instruction stream; the difference is what the chip's power management "
                          "takes for operands that toggle)")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="profiling aid: leave out what runs outside the timed region (upstream projection, "
+                         "block append, the fp8-cache pass), so that a kernel trace holds the timed path only")
     ap.add_argument("--cache-fp8", action="store_true",
                     help="run the workload with the fp8 cache encoding (E4M3 codes and one power of two "
                          "per row) instead of a cache in the tensors' dtype; the decode roofline then "
@@ -295,7 +298,7 @@ def main():
     }
     # ---- outside the timed region: the upstream step (Sec. 3 Eq. 1 + rotary embedding) at the
     #      workload's shape with the hidden size of the model the shape comes from (heads * d)
-    if w.dtype == "bf16" and w.head_dim == 128 and not args.layers:
+    if w.dtype == "bf16" and w.head_dim == 128 and not args.layers and not args.no_extras:
         hidden = w.n_q_heads * w.head_dim
         gx = torch.Generator(device=dev)
         gx.manual_seed(synth.BASE_SEED + 17)
@@ -317,7 +320,7 @@ def main():
     # ---- outside the timed region: a block of new tokens on one layer's compressed cache
     #      (d2o_append_chunk) in the shape of the multi-turn experiment of the appendix: budget
     #      2048 = 48 heavy hitters + 2000 recent, turns of 256 tokens, the workload's heads
-    if w.dtype == "bf16" and not args.layers:
+    if w.dtype == "bf16" and not args.layers and not args.no_extras:
         m, a_budget, a_recent, a_n = 256, 2048, 2000, 4096
         actx = binding.D2O(w.batch, 1, w.n_q_heads, w.n_kv_heads, d, a_n, a_budget + m + 8, dtype=w.dtype,
                            beta=w.beta, max_append=m)
@@ -342,7 +345,7 @@ def main():
         actx.close()
         del Qa, Ka, Va, Qb, Kb, Vb, Ob
     # ---- outside the timed region: the same workload's decode steps on the fp8 cache encoding
-    if w.dtype == "bf16" and not args.layers and not args.cache_fp8:
+    if w.dtype == "bf16" and not args.layers and not args.cache_fp8 and not args.no_extras:
         fctx = binding.D2O(w.batch, w.n_layers, w.n_q_heads, w.n_kv_heads, w.head_dim, w.prompt_len,
                            slots, dtype=w.dtype, n_sink=0, beta=w.beta, split_rows=args.split_rows, cache_fp8=True)
         run_step(fctx, w, Q, K, V, O, dq, dk, dv, dout, dsteps)
