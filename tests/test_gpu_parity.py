@@ -1000,3 +1000,21 @@ def test_qkv_projection_with_rotary_embedding(B, n, hidden, Hq, Hkv, pos0, base)
             assert np.all(np.abs(got - want) <= bound)
             worst = max(worst, float((np.abs(got - want) / bound).max()))
     print(f"  worst element error / bound = {worst:.3f}", flush=True)
+
+
+def test_fp32_tensors_with_head_dim_128():
+    """The fp32 kernels at head_dim 128 (the benchmark's fp32 configuration has 64): attention,
+    scores and densities, compression, generation steps and blocks of tokens."""
+    w = W1.scaled(head_dim=128, n_q_heads=4, n_kv_heads=2)
+    n, B = 300, 1
+    Q, K, V = H.make_inputs(w, B, 0, n)
+    ctx = H.new_ctx(w, B, 1, n, 200)
+    O = torch.empty(Q.shape, dtype=ctx.out_dtype, device=Q.device)
+    ctx.d2o_prefill_attend(0, Q, K, V, O)
+    want_O, want_score, want_var = H.oracle_prefill_layer(Q, K, V, w.group)
+    assert H.rownorm_err(binding.tensor_to_f64(O), want_O) <= H.FLOAT_TOL
+    got_score = ctx.d2o_scores_export(0, n)
+    assert np.abs(got_score - want_score).max() <= H.FLOAT_TOL * np.abs(want_score).max()
+    ctx.close()
+    _run_decode_parity(w, n, B, 0, 96, 24, 1, 10)
+    _run_append_parity(w, n, B, 0, 96, 24, 0, [20, 33])

@@ -815,3 +815,27 @@ def test_fp8_cache_every_row_is_encoded_and_decode_reads_the_encoded_rows():
     np.testing.assert_allclose(out, want, rtol=1e-12, atol=1e-14)
     assert e.evicted_pos >= 0 and e.target_pos == -1
     assert np.array_equal(ref.quantise_fp8_rows(pure.K), pure.K) and pure.K.shape[0] == budget
+
+
+def test_append_of_one_token_on_an_fp8_cache_is_a_generation_step_on_it():
+    """storage = "fp8": the block form with m = 1 and the generation step must agree bit for bit,
+    and both leave a cache whose every row is a fixed point of the encoding."""
+    d, G, budget, recent, sink, beta = 16, 2, 12, 3, 1, 0.6
+    g = np.random.default_rng(9)
+    n = 40
+    K = ref.round_storage(g.standard_normal((n, d)) * 2, "bf16")
+    V = ref.round_storage(g.standard_normal((n, d)), "bf16")
+    cache, _ = ref.compress_head(K, V, g.random(n) * 3, budget, recent, sink, "fp8")
+    a, b = _copy_cache(cache), _copy_cache(cache)
+    merged = 0
+    for t in range(12):
+        q = ref.round_storage(g.standard_normal((G, d)) * 2, "bf16")
+        k, v = ref.round_storage(g.standard_normal(d) * 2, "bf16"), ref.round_storage(g.standard_normal(d), "bf16")
+        out1, e1 = ref.decode_step_head(a, q, k, v, n + t, budget, recent, sink, beta)
+        out2, e2 = ref.append_chunk_head(b, q[:, None, :], k[None], v[None], n + t, budget, recent, sink, beta)
+        assert np.array_equal(out1, out2[:, 0]) and list(e2.evicted) == [e1.evicted_pos]
+        assert (int(e2.target[0]) if e2.passed[0] else -1) == e1.target_pos
+        merged += e1.target_pos >= 0
+        assert np.array_equal(a.K, b.K) and np.array_equal(a.V, b.V) and np.array_equal(a.score, b.score)
+        assert np.array_equal(ref.quantise_fp8_rows(a.K), a.K) and np.array_equal(ref.quantise_fp8_rows(a.V), a.V)
+    assert 0 < merged < 12   # both branches (merge and discard) were taken
