@@ -268,3 +268,112 @@ def test_config3_as_benchmarked_allocated_budgets_bf16_outputs_and_32_decode_ste
     print(f"  {steps} decode steps over all {L} layers: events and caches identical, worst bf16 output "
           f"error {worst:.2e} of the row maximum", flush=True)
     ctx.close()
+
+
+def test_qkv_projection_as_benchmarked_sampled_tokens():
+    """Sec. 3 Eq. 1 with rotary embedding in the shape bench.py times it (configuration 3 with the
+    hidden size of the model the shape comes from: 32768 tokens x 4096 -> 96 heads x 128).  The
+    oracle computes sampled tokens - the first and last rows of the first, a middle and the last
+    256-token tile, and tokens drawn at random - with all 12288 outputs of each."""
+    w = synth.WORKLOADS[3]
+    n, d, Hq, Hkv = w.prompt_len, w.head_dim, w.n_q_heads, w.n_kv_heads
+    hidden = Hq * d
+    dev = torch.device("cuda:0")
+    g = torch.Generator(device=dev)
+    g.manual_seed(synth.BASE_SEED + 17)
+    X = torch.randn(1, n, hidden, generator=g, device=dev, dtype=torch.float32).to(torch.bfloat16)
+    W = (torch.randn((Hq + 2 * Hkv) * d, hidden, generator=g, device=dev, dtype=torch.float32)
+         / hidden ** 0.5).to(torch.bfloat16)
+    print("projection of 32768 tokens", flush=True)
+    Q, K, V = binding.d2o_qkv_project(X, W, Hq, Hkv, d)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(3)
+    tokens = sorted({0, 1, 255, 256, n // 2 - 1, n // 2, n - 256, n - 2, n - 1}
+                    | {int(t) for t in rng.integers(0, n, 24)})
+    Wd = binding.tensor_to_f64(W)
+    worst = 0.0
+    for t in tokens:
+        wq, wk, wv = ref.qkv_project(binding.tensor_to_f64(X[0, t:t + 1]), Wd, Hq, Hkv, d, pos0=t)
+        for got, want in ((Q[0, :, t], wq[:, 0]), (K[0, :, t], wk[:, 0]), (V[0, :, t], wv[:, 0])):
+            got = binding.tensor_to_f64(got)
+            bound = H.FLOAT_TOL * np.abs(want).max(axis=-1, keepdims=True) + 2.0 ** -8 * np.abs(want)
+            assert np.all(np.abs(got - want) <= bound), f"token {t}"
+            worst = max(worst, float((np.abs(got - want) / bound).max()))
+    print(f"  {len(tokens)} tokens x {(Hq + 2 * Hkv) * d} outputs: worst element error / bound = {worst:.3f}",
+          flush=True)
+
+
+def test_append_block_as_benchmarked_sampled_heads():
+    """d2o_append_chunk in the shape bench.py times it: one layer of configuration 3's heads
+    (32 x 128, bf16 outputs), a prompt of 4096 tokens compressed to the budget of the multi-turn
+    experiment of the appendix (2048 = 48 heavy hitters + 2000 recent), then turns of 256 tokens.
+    The oracle follows three heads: token-level stages from its own fp32 scores, then every
+    turn's evicted positions, merge targets and flags identical, outputs within the bf16 storage
+    bound, caches identical."""
+    w = synth.WORKLOADS[3]
+    G, d, B = w.group, w.head_dim, w.batch
+    n, budget, recent, m, turns = 4096, 2048, 2000, 256, 3
+    dev = torch.device("cuda:0")
+    ctx = binding.D2O(B, 1, w.n_q_heads, w.n_kv_heads, d, n, budget + m + 8, dtype=w.dtype, beta=w.beta,
+                      max_append=m)
+    g = torch.Generator(device=dev)
+    g.manual_seed(synth.BASE_SEED + 23)
+    mk = lambda *shape: torch.randn(*shape, generator=g, device=dev, dtype=torch.float32).to(torch.bfloat16)
+    Q, K, V = mk(B, w.n_q_heads, n, d), mk(B, w.n_kv_heads, n, d), mk(B, w.n_kv_heads, n, d)
+    O = torch.empty_like(Q)
+    print("prompt attention", flush=True)
+    ctx.d2o_prefill_attend(0, Q, K, V, O)
+    torch.cuda.synchronize()
+    heads = [(0, 0), (0, 13), (0, 31)]
+    drive = ctx.d2o_scores_export(0, n)
+    kv = {}
+    for (b, h) in heads:
+        Kd, Vd = binding.tensor_to_f64(K[b, h]), binding.tensor_to_f64(V[b, h])
+        score = np.zeros(n)
+        for gi in range(G):
+            _, s = ref.prefill_attention_head(binding.tensor_to_f64(Q[b, h * G + gi]), Kd, Vd)
+            score += s
+        assert np.abs(drive[b, h] - score).max() <= H.FLOAT_TOL * np.abs(score).max()
+        drive[b, h] = score.astype(np.float32)
+        kv[(b, h)] = (Kd, Vd)
+    ctx.d2o_scores_import(0, drive)
+    ctx.d2o_compress_layer(0, K, V, budget, recent)
+    torch.cuda.synchronize()
+    caches = {}
+    for (b, h) in heads:
+        Kd, Vd = kv[(b, h)]
+        cache, ev = ref.compress_head(Kd, Vd, drive[b, h].astype(np.float64), budget, recent, 0, w.dtype)
+        ret, evi, tgt, us, ps = ctx.d2o_prefill_events(0, b, h, n)
+        assert np.array_equal(ret, ev.retained) and np.array_equal(evi, ev.evicted)
+        assert np.array_equal(tgt, ev.target) and np.array_equal(ps, ev.passed)
+        caches[(b, h)] = cache
+    pos, worst, evicted_total = n, 0.0, 0
+    for turn in range(turns):
+        print(f"turn {turn}", flush=True)
+        Qb, Kb, Vb = mk(B, w.n_q_heads, m, d), mk(B, w.n_kv_heads, m, d), mk(B, w.n_kv_heads, m, d)
+        Ob = torch.empty_like(Qb)
+        ctx.d2o_append_chunk(0, Qb, Kb, Vb, Ob)
+        torch.cuda.synchronize()
+        for (b, h) in heads:
+            cache = caches[(b, h)]
+            want, ev = ref.append_chunk_head(cache, binding.tensor_to_f64(Qb[b, h * G:(h + 1) * G]),
+                                             binding.tensor_to_f64(Kb[b, h]), binding.tensor_to_f64(Vb[b, h]),
+                                             pos, budget, recent, 0, w.beta)
+            evi, tgt, us, ps = ctx.d2o_append_events(0, b, h, budget + m)
+            assert np.array_equal(evi, ev.evicted) and np.array_equal(tgt, ev.target), f"turn {turn} head {h}"
+            assert np.array_equal(ps, ev.passed), f"turn {turn} head {h}"
+            if len(evi):
+                assert np.max(np.abs(us - ev.u_star)) < 1e-13
+            evicted_total += len(evi)
+            got = binding.tensor_to_f64(Ob[b, h * G:(h + 1) * G])
+            bound = H.FLOAT_TOL * np.abs(want).max(axis=-1, keepdims=True) + 2.0 ** -8 * np.abs(want)
+            assert np.all(np.abs(got - want) <= bound), f"turn {turn} head {h}: bf16 output"
+            worst = max(worst, float(np.max(np.abs(got - want) / np.abs(want).max(axis=-1, keepdims=True))))
+            gK, gV, gs, gp, gtau = ctx.d2o_cache_export(0, b, h, budget + m)
+            assert np.array_equal(gp, cache.pos) and np.array_equal(gK, cache.K) and np.array_equal(gV, cache.V)
+            np.testing.assert_allclose(gs, cache.score, rtol=1e-12)
+            assert abs(gtau - cache.tau) < 1e-13
+        pos += m
+    print(f"  {turns} turns of {m} tokens, {len(heads)} heads followed: {evicted_total} evictions identical, "
+          f"worst bf16 output error {worst:.2e} of the row maximum", flush=True)
+    ctx.close()
