@@ -109,7 +109,6 @@ __global__ __launch_bounds__(256) void permute_rows(const int32_t* __restrict__ 
 // workgroups of their own (a block on a cache of a few thousand rows is too little work per head
 // to fill the chip otherwise); a row's score then grows by the slices' sums in slice order.
 constexpr int kQG = 8;             // queries per pass over a row
-constexpr int kMaxQuerySlices = 16;  // workgroups that share the queries of a (head, chunk)
 
 template <typename T, typename IT, int D>
 __global__ __launch_bounds__(256) void block_begin(const int32_t* __restrict__ ccount, int32_t* __restrict__ ctotal,

@@ -127,7 +127,7 @@ void layout(d2o_ctx* x, char* persistent, char* scratch, size_t* pbytes, size_t*
   s.take(x->ap_stat, ap * x->ap_nch * bh * x->ap_maxq * 2);
   s.take(x->ap_norm, ap * bh * x->ap_maxq * 2);
   s.take(x->ap_out, ap * x->ap_nch * bh * x->ap_maxq * d);
-  s.take(x->ap_spart, ap * 16 * bh * x->ap_nch * kChunk);
+  s.take(x->ap_spart, ap * kMaxQuerySlices * bh * x->ap_nch * kChunk);
   s.take(x->d_logit, nch * B * Hq * kChunk);
   const size_t nsub = nch * 4;  // partial results are kept per 64 slots, a quarter of a chunk
   s.take(x->d_rec, bh * nsub * 32);

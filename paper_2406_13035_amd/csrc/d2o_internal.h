@@ -12,6 +12,7 @@
 namespace d2o {
 
 constexpr int kPartRecDoubles = 32;  // doubles of a part record of the split closing kernels
+constexpr int kMaxQuerySlices = 16;  // block append: workgroups that share the queries of a (head, chunk)
 constexpr int kMinAutoSplitRows = 8192, kMaxAutoSplitRows = 16384;  // bounds of the automatic split_rows
 constexpr int kChunk = 256;        // cache slots handled by one workgroup in the decode kernels
 constexpr int kColBN = 256;        // keys per workgroup, column-sum pass (bf16)
@@ -129,7 +130,7 @@ struct d2o_ctx {
   double* ap_stat = nullptr;     // [ap_nch][B][Hkv][ap_maxq][2] per chunk: softmax maximum and exp-sum of every query
   double* ap_norm = nullptr;     // [B][Hkv][ap_maxq][2] maximum and normaliser of every query
   float* ap_out = nullptr;       // [ap_nch][B][Hkv][ap_maxq][d] partial outputs per chunk
-  double* ap_spart = nullptr;    // [16 query slices][B][Hkv][ap_nch * 256] per row: sum of the slice's probabilities
+  double* ap_spart = nullptr;    // [kMaxQuerySlices][B][Hkv][ap_nch * 256] per row: sum of the slice's probabilities
   // decode
   double* d_logit = nullptr;     // [nchunk][B][Hkv][G][256] exp(logit - sub-chunk max), chunk-major
   double* d_rec = nullptr;       // [nchunk][B][Hkv][4][32] per 64 slots: softmax maxima and sums, candidates' best cosine and slot

@@ -962,7 +962,7 @@ hipError_t launch_decode(d2o_ctx* c, int layer0, int nl_all, View q, View k, Vie
     // launch's rows (a few giant layers after Eq. 5, or a launch of one layer) would leave the
     // chip waiting for its closing workgroup, and is finished by the split kernels instead.
     a.hnorm = a.part + size_t(cf.batch) * cf.n_kv_heads * c->nchunk_cap * kPartRecDoubles;
-  a.big_rows = cf.split_rows > 0 ? cf.split_rows
+    a.big_rows = cf.split_rows > 0 ? cf.split_rows
                                    : int(std::min<int64_t>(kMaxAutoSplitRows, std::max<int64_t>(kMinAutoSplitRows, rows / 200)));
     auto shift = [&](View x, int elem_bytes) {  // first layer of this group
       x.ptr = static_cast<char*>(x.ptr) + size_t(g0) * x.sn * elem_bytes;

@@ -12,7 +12,7 @@
 //                       attention workgroup computed them from the sub-chunk records while
 //                       other heads still streamed); for its own chunks the part does the partial
 //                       output rows, the score update (Eq. 6), its first-evicted entry (Eq. 7-8),
-//                       its four lowest entries for the next step and the candidates' best
+//                       its kCand + 1 lowest entries for the next step and the candidates' best
 //                       matches (Eq. 9).  Results: one record of kPartRec doubles per part, and
 //                       the part's output row in place of its first chunk's partial row.
 //   decode_close_final  one workgroup per head: adds the parts' output rows in ascending
@@ -37,11 +37,11 @@ constexpr int kMaxPartChunks = 8;
 
 // Record of one part (doubles; integers are stored as doubles, exactly):
 //   [0..3)   first-evicted entry (score, position, slot; slot -1: none)
-//   [3..15)  the four lowest entries evictable at the next step, in eviction order
+//   [3..15)  the kCand + 1 lowest entries evictable at the next step, in eviction order (room for four)
 //   [15..24) best match of each candidate (cosine, position, slot)
 //   [24..26) the head's last slot: updated score, position (written by the part that owns it)
 constexpr int kPartRec = kPartRecDoubles;
-static_assert(kPartRec >= 26, "record too small");
+static_assert(kPartRec >= 26 && 3 + 3 * (kCand + 1) <= 15 && 15 + 3 * kCand <= 24, "record too small");
 
 __device__ __forceinline__ void put(double* r, const Best& b) {
   r[0] = b.u;
@@ -206,7 +206,7 @@ __global__ __launch_bounds__(256) void decode_close_part(DecodeArgs a) {
       }
     }
   }
-  // block-wide: the first evicted, then the four lowest by repeated extraction
+  // block-wide: the first evicted, then the kCand + 1 lowest by repeated extraction
 #pragma unroll
   for (int r = -1; r <= kCand; ++r) {
     Best h = fast_wave_first_evicted(r < 0 ? ev : low[0]);
