@@ -973,6 +973,37 @@ def test_error_paths_return_codes():
     ctx.close()
 
 
+# ------------------------------------------------------------------ degenerate sizes
+
+@pytest.mark.parametrize("n,budget,recent", [
+    (1, 1, 0),      # a prompt of one token, a cache of one entry: every step evicts one of two and merges
+    (1, 1, 1),      # ... with the window covering the whole cache: the oldest of the two leaves
+    (2, 1, 0),      # the prompt phase itself evicts: one token merged into the only retained one
+    (5, 2, 1),
+    (33, 3, 0),     # one row past a 32-row tile
+    (3, 8, 2),      # budget above the prompt: nothing to evict until the cache has grown to it
+])
+def test_tiny_prompts_and_budgets_through_every_call(n, budget, recent):
+    """The smallest shapes the calls accept: attention and scores of the prompt, compression,
+    single-token steps and blocks (one token, then more tokens than the cache holds), bf16 and
+    fp32, all against the oracle."""
+    for w in (_small_bf16(True), W1):
+        print(f"n={n} budget={budget} recent={recent} dtype={w.dtype}", flush=True)
+        Q, K, V = H.make_inputs(w, 1, 2, n)
+        ctx = H.new_ctx(w, 1, 1, n, n + 8)
+        O = torch.empty(Q.shape, dtype=ctx.out_dtype, device=Q.device)
+        ctx.d2o_prefill_attend(0, Q, K, V, O)
+        torch.cuda.synchronize()
+        wantO, want_score, want_var = H.oracle_prefill_layer(Q, K, V, w.group)
+        assert H.rownorm_err(binding.tensor_to_f64(O), wantO) <= H.FLOAT_TOL
+        assert H.rownorm_err(ctx.d2o_scores_export(0, n).astype(np.float64), want_score) <= H.FLOAT_TOL
+        _, Fh = ctx.d2o_get_density(heads=True)
+        assert np.max(np.abs(Fh[:, 0] - want_var)) <= H.FLOAT_TOL * max(1.0, float(np.abs(want_var).max()))
+        ctx.close()
+        _run_decode_parity(w, n, 1, 2, budget, recent, 0, 6)
+        _run_append_parity(w, n, 1, 2, budget, recent, 0, [1, budget + 3, 2], decode_between=1)
+
+
 # ------------------------------------------------------------------ upstream: Q, K, V from the hidden states
 
 @pytest.mark.parametrize("B,n,hidden,Hq,Hkv,pos0,base", [
