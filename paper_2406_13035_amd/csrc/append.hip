@@ -91,24 +91,37 @@ __global__ __launch_bounds__(256) void permute_rows(const int32_t* __restrict__ 
 // the block, nothing evicted): the block's rows are appended first; query i*G + g (token i, query
 // head g of the group) then attends to the cache's N - m old entries and to the block's tokens
 // 0..i.  Logits, softmax and score accumulation in fp64 as in the generation step; P V in fp32.
+// Both products are dense contractions (rows x queries x d, queries x d x rows) and run on the
+// matrix cores: the fp64 16x16x4 instruction for the logits (its sums of products of bf16 or
+// fp8 values are exact, so they do not depend on the order of the contraction), the fp32
+// 16x16x4 instruction for P V.
 //
 //   block_begin   per head: appends the block's K, V rows (score 0, positions first_pos + i),
 //                 lays the queries out as fp64 vectors, sets the entry count to N.
-//   block_stats   per (head, 256 rows): a lane owns a cache row and multiplies it with eight
-//                 queries at a time, which reach the FMAs as scalar operands; per query the
-//                 maximum and exp-sum over the chunk's visible rows.
+//   block_stats   per (head, 256 rows, slice of the queries): the rows are staged in LDS once; a
+//                 wavefront takes tiles of 16 queries and forms their logits against the 256
+//                 rows, 64 rows at a time; per query the maximum and exp-sum over the chunk's
+//                 visible rows.
 //   block_norm    per head and query: maximum and exact normaliser over the chunks.
-//   block_apply   per (head, 256 rows): logits again, p = exp(s - max) / normaliser; per row the
-//                 sum of the p of every query that sees it, in the order (token, query head) of
-//                 the defining formula; partial P V per chunk (the probabilities travel from
-//                 the row's lane to all lanes through scalar registers, a lane owns D / 64
-//                 output columns).
+//   block_apply   the same tiling: logits again, p = exp(s - max) / normaliser; per row the sum
+//                 of the p of every query that sees it; the wavefront's 16 x d partial output
+//                 tile over the 256 rows, accumulated by the fp32 matrix instruction whose A
+//                 operand is the probability tile as the logits' instruction left it.
 //   block_scores  per row: score += the sums (Eq. 6).
 //   block_finish  per head and query: the chunks' partial output rows added in ascending order.
-// block_stats and block_apply cut a head's queries into up to kMaxQuerySlices slices that run as
-// workgroups of their own (a block on a cache of a few thousand rows is too little work per head
-// to fill the chip otherwise); a row's score then grows by the slices' sums in slice order.
-constexpr int kQG = 8;             // queries per pass over a row
+// A head's queries are cut into up to kMaxQuerySlices slices that run as workgroups of their own
+// (a block on a cache of a few thousand rows is too little work per head to fill the chip
+// otherwise); a row's score then grows by the slices' sums in slice order.
+//
+// Register layouts of the two instructions (lane l, c = l % 16, kq = l / 16):
+//   operands   A[i = c][k = kq], B[k = kq][j = c]
+//   fp64 result register r: D[i = 4 r + kq][j = c]
+//   fp32 result register r: D[i = 4 kq + r][j = c]
+// so with rows as i and queries as j, lane l holds the logits of query c against the rows
+// 16 t + 4 r + kq of a 64-row group (t = 0..3), and for fixed (t, r) these values, taken as the A
+// operand of the fp32 instruction (i = query c, k = kq), meet the four consecutive rows
+// 16 t + 4 r + kq of V as B.
+constexpr int kQT = 16;  // queries per tile
 
 template <typename T, typename IT, int D>
 __global__ __launch_bounds__(256) void block_begin(const int32_t* __restrict__ ccount, int32_t* __restrict__ ctotal,
@@ -134,7 +147,7 @@ __global__ __launch_bounds__(256) void block_begin(const int32_t* __restrict__ c
     cscore[slot0 + count + i] = 0.0;
     cpos[slot0 + count + i] = first_pos + i;
   }
-  const int nq = m * G, nq_pad = (nq + kQG - 1) / kQG * kQG;  // the queries of a last, partial group are zero
+  const int nq = m * G, nq_pad = (nq + kQT - 1) / kQT * kQT;  // the queries of a last, partial tile are zero
   for (int x = tid; x < nq_pad * D; x += nt) {
     const int qi = x / D, c = x % D;
     double v = 0.0;
@@ -144,137 +157,135 @@ __global__ __launch_bounds__(256) void block_begin(const int32_t* __restrict__ c
   if (tid == 0) ctotal[bh] = count + m;
 }
 
-// Pins the point where a scalar-loaded value must have arrived; nothing is scheduled across it.
-__device__ __forceinline__ void scalar_arrived(double v) {
-  asm volatile("" ::"s"(v));
-  __builtin_amdgcn_sched_barrier(0);
-}
-
 template <typename T, int D>
 struct BlockRows {
   static constexpr int RB = D * sizeof(T);   // bytes of a cache row
-  static constexpr int kPitch = RB + 16;     // LDS pitch of a staged row
+  static constexpr int kPitch = RB + 16;     // LDS pitch of a staged row (conflict-free for the operand reads below)
   static constexpr int kWaveBytes = 64 * kPitch;
-  // The wavefront's 64 rows [r0, r0 + 64) of `src` (rows past `last` repeat it) into its staging
-  // area, coalesced; afterwards every lane reads its own row from there.
-  static __device__ __forceinline__ void stage(const T* src, int64_t slot0, int r0, int last, unsigned char* mine,
-                                               int lane) {
+  static constexpr int kRowsBytes = 4 * kWaveBytes;                 // the chunk's 256 rows
+  static constexpr int kScaleBytes = sizeof(T) == 1 ? 256 * 12 : 0;  // fp8: the rows' powers of two (K as fp64, V as fp32)
+  static constexpr int KS = D / 4;           // contraction steps of the logits
+  static constexpr int CT = D / 16;          // output column tiles of P V (lane c holds columns CT c .. CT c + CT - 1)
+  // The chunk's rows [r0, r0 + 256) of `src` (rows past `last` repeat it) into LDS, each
+  // wavefront 64 of them, coalesced; fp8: the rows' powers of two behind them.
+  static __device__ __forceinline__ void stage(const T* src, const int8_t* ke, const int8_t* ve, int64_t slot0, int r0,
+                                               int last, unsigned char* smem, int tid) {
+    const int lane = tid & 63, w = tid >> 6;
+    unsigned char* mine = smem + w * kWaveBytes;
 #pragma unroll
     for (int i = 0; i < RB / 16; ++i) {
       const int ch = i * 64 + lane, row = ch / (RB / 16), col = ch % (RB / 16);
       *reinterpret_cast<u32x4*>(mine + row * kPitch + col * 16) =
-          *reinterpret_cast<const u32x4*>(src + (slot0 + min(r0 + row, last)) * D + col * (16 / sizeof(T)));
+          *reinterpret_cast<const u32x4*>(src + (slot0 + min(r0 + w * 64 + row, last)) * D + col * (16 / sizeof(T)));
     }
-    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-    __builtin_amdgcn_wave_barrier();
+    if constexpr (sizeof(T) == 1) {
+      reinterpret_cast<double*>(smem + kRowsBytes)[tid] = pow2_f64(ke[slot0 + min(r0 + tid, last)]);
+      reinterpret_cast<float*>(smem + kRowsBytes + 256 * 8)[tid] = pow2_f32(ve[slot0 + min(r0 + tid, last)]);
+    }
+    __syncthreads();
+  }
+  // element k of staged row `row` (0..255) as fp64 (fp8: the code, without the row's power of two)
+  static __device__ __forceinline__ double elem(const unsigned char* smem, int row, int k) {
+    const unsigned char* p = smem + row * kPitch + k * int(sizeof(T));
+    if constexpr (sizeof(T) == 1) return double(__builtin_amdgcn_cvt_f32_fp8(int(*p), 0));
+    else if constexpr (sizeof(T) == 2) return double(__uint_as_float(uint32_t(*reinterpret_cast<const uint16_t*>(p)) << 16));
+    else return double(*reinterpret_cast<const float*>(p));
+  }
+  // The query tile's B operands: bq[s] = element 4 s + kq of query q0 + c.
+  static __device__ __forceinline__ void load_queries(const double* aq_head, int q0, int lane, double (&bq)[KS]) {
+    const double* qp = aq_head + int64_t(q0 + (lane & 15)) * D + (lane >> 4);
+#pragma unroll
+    for (int s = 0; s < KS; ++s) bq[s] = qp[4 * s];
+  }
+  // Logits of the tile's 16 queries against the rows [64 g, 64 g + 64) of the chunk:
+  // S[t][r] = (row 64 g + 16 t + 4 r + kq) . (query c) / sqrt(d), exactly scaled (fp8: times the row's power of two).
+  static __device__ __forceinline__ void logits(const unsigned char* smem, int g, int lane, const double (&bq)[KS],
+                                                f64x4 (&S)[4]) {
+    const int c = lane & 15, kq = lane >> 4;
+#pragma unroll
+    for (int t = 0; t < 4; ++t) S[t] = f64x4{0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+    for (int s = 0; s < KS; ++s)
+#pragma unroll
+      for (int t = 0; t < 4; ++t)
+        S[t] = __builtin_amdgcn_mfma_f64_16x16x4f64(elem(smem, g * 64 + t * 16 + c, 4 * s + kq), bq[s], S[t], 0, 0, 0);
+    const double root_d = sqrt(double(D));
+#pragma unroll
+    for (int t = 0; t < 4; ++t)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        double v = S[t][r];
+        if constexpr (sizeof(T) == 1) v *= reinterpret_cast<const double*>(smem + kRowsBytes)[g * 64 + t * 16 + 4 * r + kq];
+        S[t][r] = v / root_d;
+      }
   }
 };
 
-// Logits of the lane's row (staged in LDS at `myrow`) against the kQG queries from q0 on (fp64,
-// exact for bf16 inputs).  Two elements per step: the row's bits come from LDS, the queries'
-// elements through scalar loads, both fetched one step ahead (two register sets; the wait for a
-// set is pinned before the other set's loads are issued, because scalar loads return out of
-// order).
-template <typename T, int D>
-__device__ __forceinline__ void block_logits(const unsigned char* myrow, const double* aq_head, int q0, double* s,
-                                             double row_scale) {
-  typedef const double __attribute__((address_space(4))) * cptr;
-  constexpr int ES = 2, NST = D / ES;
-  typedef typename std::conditional<sizeof(T) == 1, uint16_t,
-                                    typename std::conditional<sizeof(T) == 2, uint32_t, u32x2>::type>::type Raw;
-  const cptr Qv = (cptr)(aq_head + int64_t(q0) * D);
-#pragma unroll
-  for (int u = 0; u < kQG; ++u) s[u] = 0.0;
-  Raw rawA, rawB;
-  double sA[kQG][ES], sB[kQG][ES];
-  auto fetch = [&](int st, Raw& raw, double (&sv)[kQG][ES]) {
-    raw = *reinterpret_cast<const Raw*>(myrow + st * ES * int(sizeof(T)));
-#pragma unroll
-    for (int u = 0; u < kQG; ++u)
-#pragma unroll
-      for (int e = 0; e < ES; ++e) sv[u][e] = Qv[u * D + st * ES + e];
-  };
-  auto step = [&](const Raw& raw, const double (&sv)[kQG][ES]) {
-    double k[ES];
-    if constexpr (sizeof(T) == 1) {  // fp8 codes, without the row's power of two (the caller applies it)
-      k[0] = double(__builtin_amdgcn_cvt_f32_fp8(int(raw), 0));
-      k[1] = double(__builtin_amdgcn_cvt_f32_fp8(int(raw), 1));
-    } else if constexpr (sizeof(T) == 2) {
-      k[0] = double(__uint_as_float(raw << 16));
-      k[1] = double(__uint_as_float(raw & 0xFFFF0000u));
-    } else {
-      k[0] = double(__uint_as_float(raw[0]));
-      k[1] = double(__uint_as_float(raw[1]));
-    }
-#pragma unroll
-    for (int e = 0; e < ES; ++e)
-#pragma unroll
-      for (int u = 0; u < kQG; ++u) s[u] = fma(k[e], sv[u][e], s[u]);
-  };
-  fetch(0, rawA, sA);
-#pragma unroll 1
-  for (int st = 0; st < NST; st += 2) {
-    scalar_arrived(sA[0][0]);
-    fetch(st + 1, rawB, sB);
-    __builtin_amdgcn_sched_barrier(0);  // the fetches go out before the FMAs, not among them
-    step(rawA, sA);
-    scalar_arrived(sB[0][0]);
-    fetch(min(st + 2, NST - 1), rawA, sA);
-    __builtin_amdgcn_sched_barrier(0);
-    step(rawB, sB);
-  }
-  const double root_d = sqrt(double(D));
-#pragma unroll
-  for (int u = 0; u < kQG; ++u) s[u] = (sizeof(T) == 1 ? s[u] * row_scale : s[u]) / root_d;  // exact scaling of exact sums
+// sum / maximum over the four lanes that hold the same query column (kq = 0..3)
+__device__ __forceinline__ double kq_max(double v) {
+  v = fmax(v, __shfl_xor(v, 16, 64));
+  return fmax(v, __shfl_xor(v, 32, 64));
+}
+__device__ __forceinline__ double kq_sum(double v) {
+  v += __shfl_xor(v, 16, 64);
+  return v + __shfl_xor(v, 32, 64);
 }
 
 template <typename T, int D>
 __global__ __launch_bounds__(256) void block_stats(const int32_t* __restrict__ ctotal, const int32_t* __restrict__ meta,
                                                    const T* __restrict__ cK, const int8_t* __restrict__ cKe,
                                                    const double* __restrict__ aq, double* __restrict__ stat, int m, int G,
-                                                   int maxq, int64_t slots) {
+                                                   int maxq, int64_t slots, int tiles_per_slice) {
   typedef BlockRows<T, D> BR;
-  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];  // [4][64 rows] staged keys
-  __shared__ double wm[4][kQG], wl[4][kQG];
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   const int bhN = gridDim.x, bh = blockIdx.x, chunk = blockIdx.y;
   const int N = ctotal[bh];
   if (chunk * kChunk >= N) return;
-  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, c = lane & 15, kq = lane >> 4;
   const int64_t slot0 = int64_t(bh) * slots + meta[bh * 4 + 0];
-  const int j = chunk * kChunk + tid, nc = N - m;
-  const bool valid = j < N;
-  unsigned char* mine = smem + w * BR::kWaveBytes;
-  BR::stage(cK, slot0, chunk * kChunk + w * 64, N - 1, mine, lane);
-  const unsigned char* myrow = mine + lane * BR::kPitch;
-  double ksc = 1.0;
-  if constexpr (sizeof(T) == 1) ksc = pow2_f64(cKe[slot0 + min(j, N - 1)]);
-  const int nq = m * G, ngrp = (nq + kQG - 1) / kQG, gper = (ngrp + gridDim.z - 1) / gridDim.z;
-  const int q_lo = blockIdx.z * gper * kQG, q_hi = min(nq, q_lo + gper * kQG);  // this workgroup's slice of the queries
-  for (int q0 = q_lo; q0 < q_hi; q0 += kQG) {
-    double s[kQG];
-    block_logits<T, D>(myrow, aq + int64_t(bh) * maxq * D, q0, s, ksc);
+  const int nc = N - m, nq = m * G, ntile = (nq + kQT - 1) / kQT;
+  BR::stage(cK, cKe, cKe, slot0, chunk * kChunk, N - 1, smem, tid);
+  const int ngroup = min(4, (N - chunk * kChunk + 63) / 64);  // 64-row groups of the chunk that hold rows
+  const int t_hi = min(ntile, (blockIdx.z + 1) * tiles_per_slice);
+  for (int qt = blockIdx.z * tiles_per_slice + w; qt < t_hi; qt += 4) {  // this wavefront's query tiles
+    const int q0 = qt * kQT, query = q0 + c;
+    double bq[BR::KS];
+    BR::load_queries(aq + int64_t(bh) * maxq * D, q0, lane, bq);
+    const int seen = nc + query / G;  // the last row this query attends to
+    double M = -INFINITY, L = 0.0;
+#pragma unroll 1
+    for (int g = 0; g < ngroup; ++g) {
+      f64x4 S[4];
+      BR::logits(smem, g, lane, bq, S);
+      const int j0 = chunk * kChunk + g * 64 + kq;
+      double mg = -INFINITY;
 #pragma unroll
-    for (int u = 0; u < kQG; ++u) {
-      const bool vis = valid && j <= nc + (q0 + u) / G;
-      const double mw = wave_max(vis ? s[u] : -INFINITY);
-      const double lw = wave_sum(vis ? exp(s[u] - mw) : 0.0);
-      if (lane == 0) {
-        wm[w][u] = mw;
-        wl[w][u] = lw;
-      }
+      for (int t = 0; t < 4; ++t)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const int j = j0 + t * 16 + 4 * r;
+          if (j < N && j <= seen) mg = fmax(mg, S[t][r]);
+        }
+      mg = kq_max(mg);
+      if (mg == -INFINITY) continue;  // (the same for the four lanes of a query)
+      double lg = 0.0;
+#pragma unroll
+      for (int t = 0; t < 4; ++t)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const int j = j0 + t * 16 + 4 * r;
+          if (j < N && j <= seen) lg += exp(S[t][r] - mg);
+        }
+      lg = kq_sum(lg);
+      const double Mn = fmax(M, mg);
+      L = (M == -INFINITY ? 0.0 : L * exp(M - Mn)) + lg * exp(mg - Mn);
+      M = Mn;
     }
-    __syncthreads();
-    if (tid < kQG && q0 + tid < nq) {
-      double M = fmax(fmax(wm[0][tid], wm[1][tid]), fmax(wm[2][tid], wm[3][tid]));
-      double L = 0.0;
-#pragma unroll
-      for (int i = 0; i < 4; ++i)
-        if (wm[i][tid] != -INFINITY) L += wl[i][tid] * exp(wm[i][tid] - M);
-      double* st = stat + ((int64_t(chunk) * bhN + bh) * maxq + q0 + tid) * 2;
+    if (kq == 0 && query < nq) {
+      double* st = stat + ((int64_t(chunk) * bhN + bh) * maxq + query) * 2;
       st[0] = M;
       st[1] = L;
     }
-    __syncthreads();
   }
 }
 
@@ -303,95 +314,101 @@ __global__ __launch_bounds__(256) void block_apply(const int32_t* __restrict__ c
                                                    const int8_t* __restrict__ cKe, const int8_t* __restrict__ cVe,
                                                    double* __restrict__ spart, const double* __restrict__ aq,
                                                    const double* __restrict__ norm, float* __restrict__ pout, int m,
-                                                   int G, int maxq, int64_t slots, int rows_cap) {
+                                                   int G, int maxq, int64_t slots, int rows_cap, int tiles_per_slice) {
   typedef BlockRows<T, D> BR;
-  constexpr int CPL = D / 64;  // output columns per lane
-  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];  // [4][64 rows] staged keys
-  __shared__ float xch[4][kQG][D];
+  constexpr int CT = BR::CT;
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  // behind the rows (and the fp8 scales): per wavefront and row, the sum of its queries' probabilities
+  double* rs = reinterpret_cast<double*>(smem + BR::kRowsBytes + BR::kScaleBytes);
   const int bhN = gridDim.x, bh = blockIdx.x, chunk = blockIdx.y;
   const int N = ctotal[bh];
   if (chunk * kChunk >= N) return;
-  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, c = lane & 15, kq = lane >> 4;
   const int64_t slot0 = int64_t(bh) * slots + meta[bh * 4 + 0];
-  const int r0 = chunk * kChunk + w * 64;  // the wavefront's first row
-  const int j = r0 + lane, nc = N - m;
-  const bool valid = j < N;
-  unsigned char* mine = smem + w * BR::kWaveBytes;
-  BR::stage(cK, slot0, r0, N - 1, mine, lane);
-  const unsigned char* myrow = mine + lane * BR::kPitch;
-  // the wavefront's 64 value rows, this lane's CPL columns of each, as raw words (fp8: two codes
-  // in half a word; the row's power of two rides on the row's probability)
-  constexpr int VW = sizeof(T) == 1 ? 1 : CPL * sizeof(T) / 4;
-  uint32_t vraw[64][VW];
+  const int nc = N - m, nq = m * G, ntile = (nq + kQT - 1) / kQT;
 #pragma unroll
-  for (int r = 0; r < 64; ++r) {
-    if constexpr (sizeof(T) == 1) {
-      static_assert(sizeof(T) != 1 || CPL == 2, "two codes per lane");
-      vraw[r][0] = reinterpret_cast<const uint16_t*>(cV + (slot0 + min(r0 + r, N - 1)) * D)[lane];
-    } else {
-      const uint32_t* vr = reinterpret_cast<const uint32_t*>(cV + (slot0 + min(r0 + r, N - 1)) * D + lane * CPL);
+  for (int i = 0; i < 4; ++i) rs[i * 256 + tid] = 0.0;
+  BR::stage(cK, cKe, cVe, slot0, chunk * kChunk, N - 1, smem, tid);
+  const int ngroup = min(4, (N - chunk * kChunk + 63) / 64);
+  const int t_hi = min(ntile, (blockIdx.z + 1) * tiles_per_slice);
+  for (int qt = blockIdx.z * tiles_per_slice + w; qt < t_hi; qt += 4) {
+    const int q0 = qt * kQT, query = q0 + c;
+    double bq[BR::KS];
+    BR::load_queries(aq + int64_t(bh) * maxq * D, q0, lane, bq);
+    const int seen = query < nq ? nc + query / G : -1;  // a padding query sees nothing
+    const double M = norm[(int64_t(bh) * maxq + query) * 2], Linv = 1.0 / norm[(int64_t(bh) * maxq + query) * 2 + 1];
+    f32x4 O[CT];
 #pragma unroll
-      for (int c = 0; c < VW; ++c) vraw[r][c] = vr[c];
-    }
-  }
-  double ksc = 1.0;
-  float vsc = 1.f;
-  if constexpr (sizeof(T) == 1) {
-    ksc = pow2_f64(cKe[slot0 + min(j, N - 1)]);
-    vsc = pow2_f32(cVe[slot0 + min(j, N - 1)]);
-  }
-  double sc = 0.0;
-  const int nq = m * G, ngrp = (nq + kQG - 1) / kQG, gper = (ngrp + gridDim.z - 1) / gridDim.z;
-  const int q_lo = blockIdx.z * gper * kQG, q_hi = min(nq, q_lo + gper * kQG);  // this workgroup's slice of the queries
-  typedef const double __attribute__((address_space(4))) * cptr;
-  for (int q0 = q_lo; q0 < q_hi; q0 += kQG) {
-    double s[kQG];
-    block_logits<T, D>(myrow, aq + int64_t(bh) * maxq * D, q0, s, ksc);
-    const cptr nm = (cptr)(norm + (int64_t(bh) * maxq + q0) * 2);
-    float p32[kQG];
+    for (int ct = 0; ct < CT; ++ct) O[ct] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll 1
+    for (int g = 0; g < ngroup; ++g) {
+      f64x4 S[4];
+      BR::logits(smem, g, lane, bq, S);
+      const int j0 = chunk * kChunk + g * 64 + kq;
 #pragma unroll
-    for (int u = 0; u < kQG; ++u) {
-      const bool vis = valid && q0 + u < nq && j <= nc + (q0 + u) / G;
-      const double p = vis ? exp(s[u] - nm[2 * u]) / nm[2 * u + 1] : 0.0;
-      sc += p;  // Eq. 6: the slice's probabilities, in (token, query head) order
-      p32[u] = sizeof(T) == 1 ? float(p) * vsc : float(p);
-    }
-    float acc[kQG][CPL];
+      for (int t = 0; t < 4; ++t)
 #pragma unroll
-    for (int u = 0; u < kQG; ++u)
+        for (int r = 0; r < 4; ++r) {
+          const int row = g * 64 + t * 16 + 4 * r + kq, j = j0 + t * 16 + 4 * r;
+          // (the division by the normaliser is a multiplication by its reciprocal here: the
+          // probabilities are compared within the float tolerance, never bit for bit)
+          const double p = (j < N && j <= seen) ? exp(S[t][r] - M) * Linv : 0.0;
+          // Eq. 6: the row's sum over the tile's queries, then over the wavefront's tiles
+          double ps = p;
+          ps += __shfl_xor(ps, 1, 64);
+          ps += __shfl_xor(ps, 2, 64);
+          ps += __shfl_xor(ps, 4, 64);
+          ps += __shfl_xor(ps, 8, 64);
+          if (c == 0) rs[w * 256 + row] += ps;
+          // P V: this (t, r) is one contraction step over the rows 16 t + 4 r + kq
+          float pa = float(p);
+          if constexpr (sizeof(T) == 1) pa *= reinterpret_cast<const float*>(smem + BR::kRowsBytes + 256 * 8)[row];
+          const T* vrow = cV + (slot0 + min(j, N - 1)) * D + c * CT;
+          float vb[CT];
+          if constexpr (sizeof(T) == 1) {
+            static_assert(sizeof(T) != 1 || CT == 8, "eight codes per lane");
+            const u32x2 raw = *reinterpret_cast<const u32x2*>(vrow);
 #pragma unroll
-      for (int c = 0; c < CPL; ++c) acc[u][c] = 0.f;
+            for (int wd = 0; wd < 2; ++wd) {
+              vb[4 * wd] = __builtin_amdgcn_cvt_f32_fp8(int(raw[wd]), 0);
+              vb[4 * wd + 1] = __builtin_amdgcn_cvt_f32_fp8(int(raw[wd]), 1);
+              vb[4 * wd + 2] = __builtin_amdgcn_cvt_f32_fp8(int(raw[wd]), 2);
+              vb[4 * wd + 3] = __builtin_amdgcn_cvt_f32_fp8(int(raw[wd]), 3);
+            }
+          } else if constexpr (sizeof(T) == 2) {
+            static_assert(sizeof(T) != 2 || CT == 8, "eight bf16 columns per lane");
+            const u32x4 raw = *reinterpret_cast<const u32x4*>(vrow);
 #pragma unroll
-    for (int r = 0; r < 64; ++r) {
+            for (int wd = 0; wd < 4; ++wd) {
+              vb[2 * wd] = __uint_as_float(raw[wd] << 16);
+              vb[2 * wd + 1] = __uint_as_float(raw[wd] & 0xFFFF0000u);
+            }
+          } else {
 #pragma unroll
-      for (int u = 0; u < kQG; ++u) {
-        const float pr = __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(p32[u]), r));
-        if constexpr (sizeof(T) == 1) {
-          acc[u][0] = fmaf(pr, __builtin_amdgcn_cvt_f32_fp8(int(vraw[r][0]), 0), acc[u][0]);
-          acc[u][1] = fmaf(pr, __builtin_amdgcn_cvt_f32_fp8(int(vraw[r][0]), 1), acc[u][1]);
-        } else if constexpr (sizeof(T) == 2) {
-          static_assert(sizeof(T) != 2 || CPL == 2, "two bf16 columns per lane");
-          acc[u][0] = fmaf(pr, __uint_as_float(vraw[r][0] << 16), acc[u][0]);
-          acc[u][1] = fmaf(pr, __uint_as_float(vraw[r][0] & 0xFFFF0000u), acc[u][1]);
-        } else {
+            for (int x = 0; x < CT; x += 4) {
+              const u32x4 raw = *reinterpret_cast<const u32x4*>(vrow + x);
 #pragma unroll
-          for (int c = 0; c < CPL; ++c) acc[u][c] = fmaf(pr, __uint_as_float(vraw[r][c]), acc[u][c]);
+              for (int e = 0; e < 4; ++e) vb[x + e] = __uint_as_float(raw[e]);
+            }
+          }
+#pragma unroll
+          for (int ct = 0; ct < CT; ++ct) O[ct] = __builtin_amdgcn_mfma_f32_16x16x4f32(pa, vb[ct], O[ct], 0, 0, 0);
         }
+    }
+    // O[ct][r]: query q0 + 4 kq + r, column CT c + ct
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const int qo = q0 + 4 * kq + r;
+      if (qo < nq) {
+        float* dst = pout + ((int64_t(chunk) * bhN + bh) * maxq + qo) * D + c * CT;
+#pragma unroll
+        for (int x = 0; x < CT; x += 4) *reinterpret_cast<f32x4*>(dst + x) = f32x4{O[x][r], O[x + 1][r], O[x + 2][r], O[x + 3][r]};
       }
     }
-#pragma unroll
-    for (int u = 0; u < kQG; ++u)
-#pragma unroll
-      for (int c = 0; c < CPL; ++c) xch[w][u][lane * CPL + c] = acc[u][c];
-    __syncthreads();
-    for (int x = tid; x < kQG * D; x += 256) {
-      const int u = x / D, c = x % D;
-      if (q0 + u < nq)
-        pout[((int64_t(chunk) * bhN + bh) * maxq + q0 + u) * D + c] = (xch[0][u][c] + xch[1][u][c]) + (xch[2][u][c] + xch[3][u][c]);
-    }
-    __syncthreads();
   }
-  if (valid) spart[(int64_t(blockIdx.z) * bhN + bh) * rows_cap + j] = sc;
+  __syncthreads();
+  const int j = chunk * kChunk + tid;
+  if (j < N) spart[(int64_t(blockIdx.z) * bhN + bh) * rows_cap + j] = (rs[tid] + rs[256 + tid]) + (rs[512 + tid] + rs[768 + tid]);
 }
 
 // Eq. 6 for the block: a row's score grows by the slices' sums, added in slice order (slices hold
@@ -478,10 +495,13 @@ hipError_t run_block_attend(d2o_ctx* c, int layer, View q, View k, View v, View 
   for (const auto& mt : c->layers[layer].meta) max_rows = std::max(max_rows, mt.budget + m);
   const int nch = (max_rows + kChunk - 1) / kChunk;
   if (nch > c->ap_nch || m * G > maxq) return hipErrorInvalidValue;
-  // few heads and chunks give few workgroups: the queries of a head are cut into slices that run
-  // as workgroups of their own, enough of them to fill the chip a few times over
-  const int ngrp = (m * G + kQG - 1) / kQG;
-  const int nslice = std::max(1, std::min({kMaxQuerySlices, ngrp, 4096 / std::max(1, bh * nch)}));
+  // few heads and chunks give few workgroups: the query tiles of a head are cut into slices that
+  // run as workgroups of their own (whole rounds of the four wavefronts), enough of them to fill
+  // the chip a few times over
+  const int ntile = (m * G + kQT - 1) / kQT;
+  const int want = std::max(1, std::min(kMaxQuerySlices, 2048 / std::max(1, bh * nch)));
+  const int tiles_per_slice = 4 * ((ntile + 4 * want - 1) / (4 * want));
+  const int nslice = (ntile + tiles_per_slice - 1) / tiles_per_slice;
   block_begin<T, IT, D><<<dim3(cf.n_kv_heads, cf.batch, 8), 256, 0, s>>>(ccount, ctotal, meta, (T*)c->cacheK, (T*)c->cacheV, c->cscore,
                                                                          c->cpos, (const IT*)q.ptr, q, (const IT*)k.ptr, k,
                                                                          (const IT*)v.ptr, v, c->ap_q, m, G, maxq, first_pos,
@@ -490,17 +510,18 @@ hipError_t run_block_attend(d2o_ctx* c, int layer, View q, View k, View v, View 
     block_rows_fp8<<<dim3((m + 3) / 4, cf.n_kv_heads, cf.batch), 256, 0, s>>>(ccount, meta, (uint8_t*)c->cacheK, (uint8_t*)c->cacheV,
                                                                                c->cKe, c->cVe, (const uint16_t*)k.ptr, k,
                                                                                (const uint16_t*)v.ptr, v, m, cf.slots_per_seq);
-  constexpr int kRowsLds = 4 * BlockRows<T, D>::kWaveBytes;
-  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(block_stats<T, D>), hipFuncAttributeMaxDynamicSharedMemorySize, kRowsLds);
-  if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(block_apply<T, D>), hipFuncAttributeMaxDynamicSharedMemorySize, kRowsLds);
+  typedef BlockRows<T, D> BR;
+  constexpr int kStatsLds = BR::kRowsBytes + BR::kScaleBytes, kApplyLds = kStatsLds + 4 * 256 * int(sizeof(double));
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(block_stats<T, D>), hipFuncAttributeMaxDynamicSharedMemorySize, kStatsLds);
+  if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(block_apply<T, D>), hipFuncAttributeMaxDynamicSharedMemorySize, kApplyLds);
   if (e != hipSuccess) return e;
-  block_stats<T, D><<<dim3(bh, nch, nslice), 256, kRowsLds, s>>>(ctotal, meta, (const T*)c->cacheK, c->cKe, c->ap_q, c->ap_stat, m, G,
-                                                              maxq, cf.slots_per_seq);
+  block_stats<T, D><<<dim3(bh, nch, nslice), 256, kStatsLds, s>>>(ctotal, meta, (const T*)c->cacheK, c->cKe, c->ap_q, c->ap_stat, m, G,
+                                                               maxq, cf.slots_per_seq, tiles_per_slice);
   block_norm<<<dim3(bh), 256, 0, s>>>(ctotal, ccount, c->ap_stat, c->ap_norm, m, G, maxq);
   const int rows_cap = c->ap_nch * kChunk;
-  block_apply<T, D><<<dim3(bh, nch, nslice), 256, kRowsLds, s>>>(ctotal, meta, (const T*)c->cacheK, (const T*)c->cacheV, c->cKe, c->cVe,
-                                                              c->ap_spart, c->ap_q, c->ap_norm, c->ap_out, m, G, maxq,
-                                                              cf.slots_per_seq, rows_cap);
+  block_apply<T, D><<<dim3(bh, nch, nslice), 256, kApplyLds, s>>>(ctotal, meta, (const T*)c->cacheK, (const T*)c->cacheV, c->cKe, c->cVe,
+                                                               c->ap_spart, c->ap_q, c->ap_norm, c->ap_out, m, G, maxq,
+                                                               cf.slots_per_seq, rows_cap, tiles_per_slice);
   block_scores<<<dim3(bh, nch), 256, 0, s>>>(ctotal, meta, c->cscore, c->ap_spart, nslice, cf.slots_per_seq, rows_cap);
   if (cf.out_f32)
     block_finish<float, D><<<dim3(bh, m * G), D, 0, s>>>(ctotal, c->ap_out, (float*)out.ptr, out, G, maxq, cf.n_kv_heads);

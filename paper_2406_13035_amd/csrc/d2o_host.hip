@@ -121,7 +121,7 @@ void layout(d2o_ctx* x, char* persistent, char* scratch, size_t* pbytes, size_t*
   s.take(x->app_pos, ap * bh * np);
   s.take(x->app_rank, ap * bh * np);
   s.take(x->app_n, ap * bh);
-  x->ap_maxq = ap ? int((size_t(c.max_append) * G + 7) / 8 * 8) : 0;
+  x->ap_maxq = ap ? int((size_t(c.max_append) * G + 15) / 16 * 16) : 0;
   x->ap_nch = ap ? int(std::min<int64_t>(np, c.slots_per_seq) / kChunk + 2) : 0;
   s.take(x->ap_q, ap * bh * x->ap_maxq * d);
   s.take(x->ap_stat, ap * x->ap_nch * bh * x->ap_maxq * 2);

@@ -125,7 +125,7 @@ struct d2o_ctx {
   int32_t* app_rank = nullptr;   // [B][Hkv][npad] rank of every cache slot's position
   int32_t* app_n = nullptr;      // [B][Hkv] entries
   // block attention of d2o_append_chunk (contexts with max_append > 1)
-  int32_t ap_maxq = 0, ap_nch = 0;  // queries per head (max_append * G, rounded up to 8) and chunks per head the arrays hold
+  int32_t ap_maxq = 0, ap_nch = 0;  // queries per head (max_append * G, rounded up to 16) and chunks per head the arrays hold
   double* ap_q = nullptr;        // [B][Hkv][ap_maxq][d] the block's queries as fp64
   double* ap_stat = nullptr;     // [ap_nch][B][Hkv][ap_maxq][2] per chunk: softmax maximum and exp-sum of every query
   double* ap_norm = nullptr;     // [B][Hkv][ap_maxq][2] maximum and normaliser of every query
