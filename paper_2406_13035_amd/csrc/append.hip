@@ -19,6 +19,7 @@ namespace {
 
 constexpr int kRankTile = 4096;  // positions held in LDS at a time
 
+template <int U>  // slots per thread: 4 amortises the LDS reads on large caches, 1 gives small ones more workgroups
 __global__ __launch_bounds__(256) void rank_by_position(const int32_t* __restrict__ ccount,   // the layer's [B][Hkv]
                                                         const int32_t* __restrict__ meta,     // the layer's [B][Hkv][4]
                                                         const double* __restrict__ cscore,
@@ -31,32 +32,32 @@ __global__ __launch_bounds__(256) void rank_by_position(const int32_t* __restric
   const int n = ccount[bh];
   const int64_t slot0 = bh * slots + meta[bh * 4 + 0];
   if (tid == 0 && blockIdx.z == 0) on[bh] = n;
-  // A workgroup owns 1024 slots at a time (a thread four of them; the workgroups of a head stride
+  // A workgroup owns 256 U slots at a time (a thread U of them; the workgroups of a head stride
   // over its slots); all positions of the head pass through LDS tile by tile, and each owned
   // slot counts the smaller ones (all threads read the same LDS words, eight at a time).
-  for (int j0 = blockIdx.z * 1024; j0 < n; j0 += gridDim.z * 1024) {
-    int mine[4], cnt[4];
+  for (int j0 = blockIdx.z * 256 * U; j0 < n; j0 += gridDim.z * 256 * U) {
+    int mine[U], cnt[U];
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
+    for (int u = 0; u < U; ++u) {
       const int j = j0 + u * 256 + tid;
       mine[u] = j < n ? cpos[slot0 + j] : 0x7FFFFFFF;
       cnt[u] = 0;
     }
     for (int t0 = 0; t0 < n; t0 += kRankTile) {
       __syncthreads();
-      for (int i = tid; i < kRankTile; i += 256) tile[i] = t0 + i < n ? cpos[slot0 + t0 + i] : 0x7FFFFFFF;
-      __syncthreads();
       const int lim = min(kRankTile, (n - t0 + 7) & ~7);  // the padding compares as "not smaller"
+      for (int i = tid; i < lim; i += 256) tile[i] = t0 + i < n ? cpos[slot0 + t0 + i] : 0x7FFFFFFF;
+      __syncthreads();
       for (int i = 0; i < lim; i += 8) {
         const int4 pa = *reinterpret_cast<const int4*>(&tile[i]), pb = *reinterpret_cast<const int4*>(&tile[i + 4]);
 #pragma unroll
-        for (int u = 0; u < 4; ++u)
+        for (int u = 0; u < U; ++u)
           cnt[u] += (pa.x < mine[u]) + (pa.y < mine[u]) + (pa.z < mine[u]) + (pa.w < mine[u]) + (pb.x < mine[u]) +
                     (pb.y < mine[u]) + (pb.z < mine[u]) + (pb.w < mine[u]);
       }
     }
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
+    for (int u = 0; u < U; ++u) {
       const int j = j0 + u * 256 + tid;
       if (j < n) {
         rank[bh * npad + j] = cnt[u];
@@ -538,9 +539,12 @@ hipError_t launch_cache_sort(d2o_ctx* c, int layer, hipStream_t s) {
   const int32_t* ccount = c->ccount + size_t(layer) * cf.batch * cf.n_kv_heads;
   int max_rows = 0;
   for (const auto& mt : c->layers[layer].meta) max_rows = std::max(max_rows, mt.budget + c->grow);
-  rank_by_position<<<dim3(cf.n_kv_heads, cf.batch, (max_rows + 1023) / 1024), 256, 0, s>>>(ccount, meta, c->cscore, c->cpos, c->app_rank,
-                                                                  c->app_pos, c->app_score, c->app_n, c->npad,
-                                                                  cf.slots_per_seq);
+  if (max_rows <= 8192)
+    rank_by_position<1><<<dim3(cf.n_kv_heads, cf.batch, (max_rows + 255) / 256), 256, 0, s>>>(
+        ccount, meta, c->cscore, c->cpos, c->app_rank, c->app_pos, c->app_score, c->app_n, c->npad, cf.slots_per_seq);
+  else
+    rank_by_position<4><<<dim3(cf.n_kv_heads, cf.batch, (max_rows + 1023) / 1024), 256, 0, s>>>(
+        ccount, meta, c->cscore, c->cpos, c->app_rank, c->app_pos, c->app_score, c->app_n, c->npad, cf.slots_per_seq);
   if (cf.cache_fp8) {
     permute_decode_rows<<<dim3((max_rows + 3) / 4, cf.n_kv_heads, cf.batch), 256, 0, s>>>(
         c->app_n, meta, c->app_rank, (const uint8_t*)c->cacheK, (const uint8_t*)c->cacheV, c->cKe, c->cVe,

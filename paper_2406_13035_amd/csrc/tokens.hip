@@ -100,14 +100,37 @@ __global__ __launch_bounds__(1024) void select_kernel(const S* __restrict__ scor
         if ((k & mask) == prefix) atomicAdd(&hist[int(k >> shift) & 255], 1);
       }
       __syncthreads();
-      if (tid == 0) {
-        int rem = need, bin = 255;
-        for (; bin > 0; --bin) {
-          if (hist[bin] >= rem) break;
-          rem -= hist[bin];
+      if (tid < 64) {
+        // the highest bin at which the count of keys in this and all higher bins reaches `need`
+        // (it exists: the candidates number at least `need`): lane i holds the bins 255 - 4 i
+        // down to 252 - 4 i, and a scan over the lanes counts the keys above them
+        const int b0 = 255 - 4 * tid;
+        const int h0 = hist[b0], h1 = hist[b0 - 1], h2 = hist[b0 - 2], h3 = hist[b0 - 3];
+        const int tot = h0 + h1 + h2 + h3;
+        int inc = tot;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+          const int v = __shfl_up(inc, o, 64);
+          if (tid >= o) inc += v;
         }
-        sh_prefix = prefix | (Key(bin) << shift);
-        sh_need = rem;
+        const int above = inc - tot;
+        if (above < need && need <= inc) {
+          int rem = need - above, bin = b0;
+          if (h0 < rem) {
+            rem -= h0;
+            bin = b0 - 1;
+            if (h1 < rem) {
+              rem -= h1;
+              bin = b0 - 2;
+              if (h2 < rem) {
+                rem -= h2;
+                bin = b0 - 3;
+              }
+            }
+          }
+          sh_prefix = prefix | (Key(bin) << shift);
+          sh_need = rem;
+        }
       }
       __syncthreads();
       prefix = sh_prefix;
