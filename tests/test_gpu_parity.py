@@ -973,6 +973,68 @@ def test_error_paths_return_codes():
     ctx.close()
 
 
+# ------------------------------------------------------------------ repeatability, non-finite inputs
+
+def _whole_path_once(w, n, budget, recent, steps, m, cache_fp8=False):
+    """Prompt phase on the library's own scores, generation steps, a block: every result as bytes."""
+    Q, K, V = H.make_inputs(w, 2, 5, n)
+    ctx = H.new_ctx(w, 2, 1, max(n, budget + m), budget + m + 8, max_append=m, cache_fp8=cache_fp8)
+    O = torch.empty(Q.shape, dtype=ctx.out_dtype, device=Q.device)
+    ctx.d2o_prefill_compress(0, Q, K, V, budget, recent, O)
+    got = [O.cpu().numpy().tobytes(), ctx.d2o_scores_export(0, n).tobytes()]
+    got += [a.tobytes() for a in ctx.d2o_get_density(heads=True)]
+    q, k, v = H.decode_inputs(w, 2, [5], steps)
+    out = torch.empty(q[0].shape, dtype=ctx.out_dtype, device=q.device)
+    for t in range(steps):
+        ctx.d2o_decode_step(0, 1, q[t], k[t], v[t], out)
+        got.append(out.cpu().numpy().tobytes())
+        got += [a.tobytes() for a in ctx.d2o_last_events(0)]
+    Qb, Kb, Vb = _block_inputs(w, 2, 5, m, 1)
+    Ob = torch.empty(Qb.shape, dtype=ctx.out_dtype, device=Qb.device)
+    ctx.d2o_append_chunk(0, Qb, Kb, Vb, Ob)
+    got.append(Ob.cpu().numpy().tobytes())
+    for b in range(2):
+        for h in range(w.n_kv_heads):
+            gK, gV, gs, gp, gtau = ctx.d2o_cache_export(0, b, h, budget + m)
+            got += [gK.tobytes(), gV.tobytes(), gs.tobytes(), gp.tobytes(), np.float64(gtau).tobytes()]
+    ctx.close()
+    return got
+
+
+@pytest.mark.parametrize("cache_fp8", [False, True])
+def test_two_runs_give_the_same_bits(cache_fp8):
+    """No result depends on the order in which workgroups run (no floating-point atomics, fixed
+    summation trees, ordered merge sources): the whole path - attention outputs, scores,
+    densities, every generation step's outputs and events, a block append, the final caches -
+    run twice in fresh contexts gives identical bytes."""
+    w = _small_bf16(True)
+    first = _whole_path_once(w, 1500, 300, 60, 12, 40, cache_fp8)
+    second = _whole_path_once(w, 1500, 300, 60, 12, 40, cache_fp8)
+    assert len(first) == len(second)
+    for i, (a, b) in enumerate(zip(first, second)):
+        assert a == b, f"result {i} differs between the two runs"
+
+
+def test_non_finite_inputs_reach_the_density_and_the_budget_call_rejects_them():
+    """The kernels do not scan their inputs.  A NaN in a query or a key row spreads through the
+    softmax normaliser into that head's column sums, variance and the layer's density, and
+    d2o_allocate_budgets answers a non-finite density with an error; the other layer's density
+    stays finite."""
+    w, n = _small_bf16(False), 600
+    ctx = H.new_ctx(w, 1, 2, n, n + 8)
+    for layer, poison in ((0, None), (1, "q")):
+        Q, K, V = H.make_inputs(w, 1, layer, n)
+        if poison:
+            Q[0, 2, 17, 5] = float("nan")
+        ctx.d2o_prefill_attend(layer, Q, K, V, None)
+    torch.cuda.synchronize()
+    F = ctx.d2o_get_density()
+    assert np.isfinite(F[0, 0]) and not np.isfinite(F[0, 1])
+    with pytest.raises(binding.D2OError):
+        binding.d2o_allocate_budgets(F[0], n, 300, 16)
+    ctx.close()
+
+
 # ------------------------------------------------------------------ degenerate sizes
 
 @pytest.mark.parametrize("n,budget,recent", [
