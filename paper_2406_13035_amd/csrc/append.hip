@@ -199,7 +199,7 @@ struct BlockRows {
     for (int s = 0; s < KS; ++s) bq[s] = qp[4 * s];
   }
   // Logits of the tile's 16 queries against the rows [64 g, 64 g + 64) of the chunk:
-  // S[t][r] = (row 64 g + 16 t + 4 r + kq) . (query c) / sqrt(d), exactly scaled (fp8: times the row's power of two).
+  // S[t][r] = (row 64 g + 16 t + 4 r + kq) . (query c) / sqrt(d) (fp8: times the row's power of two, exactly).
   static __device__ __forceinline__ void logits(const unsigned char* smem, int g, int lane, const double (&bq)[KS],
                                                 f64x4 (&S)[4]) {
     const int c = lane & 15, kq = lane >> 4;
@@ -210,14 +210,16 @@ struct BlockRows {
 #pragma unroll
       for (int t = 0; t < 4; ++t)
         S[t] = __builtin_amdgcn_mfma_f64_16x16x4f64(elem(smem, g * 64 + t * 16 + c, 4 * s + kq), bq[s], S[t], 0, 0, 0);
-    const double root_d = sqrt(double(D));
+    // (times the rounded reciprocal of sqrt(d), exact for d = 64: a block's logits are compared
+    // within the float tolerance, and a division per element would cost a tenth of the pass)
+    const double inv_root_d = 1.0 / sqrt(double(D));
 #pragma unroll
     for (int t = 0; t < 4; ++t)
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
         double v = S[t][r];
         if constexpr (sizeof(T) == 1) v *= reinterpret_cast<const double*>(smem + kRowsBytes)[g * 64 + t * 16 + 4 * r + kq];
-        S[t][r] = v / root_d;
+        S[t][r] = v * inv_root_d;
       }
   }
 };
