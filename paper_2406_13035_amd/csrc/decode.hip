@@ -489,20 +489,23 @@ __global__ __launch_bounds__(256) void decode_attend(DecodeArgs a, OT* __restric
   unsigned char* mine = stage + w * 64 * kPitch;
   int ln = lane;  // the lane number as the loop body sees it
   const double root_d = sqrt(double(D));
-  // K loads of a sub-chunk: a piece is 64 bytes of every row (4 lanes per row, 16 rows per load,
-  // 4 loads).  Pieces travel in pairs, the two halves of a 128-byte line requested together; the
-  // next pair is requested as soon as this one sits in LDS.
+  // K loads of a sub-chunk.  The K pass takes a row's bytes in pieces of 64 (one LDS staging round
+  // each); the loads fetch two pieces at a time as whole 128-byte lines: 8 lanes per row, 8 rows
+  // per load, 8 loads.  They are non-temporal like the V loads below: every K and V byte is
+  // needed once per step, and a stream that does not settle in the caches leaves them to the
+  // step's small read-write arrays (measured on a streaming probe with this access pattern:
+  // 6.25 -> 6.7 TB/s; in 64-byte half lines the hint costs bandwidth instead, the second half
+  // of a line then comes from memory again).  The next pair is requested as soon as this one
+  // sits in LDS.
   static_assert(NP % 2 == 0, "pieces are loaded in pairs");
-  u32x4 kreg[2][4];
+  u32x4 kreg[8];
   auto load_pair = [&](int sub, int rows, int p0) {
     const unsigned char* Kc = Kh + int64_t(sub) * kSub * RB;
 #pragma unroll
-    for (int h = 0; h < 2; ++h)
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const int r = min(i * 16 + (ln >> 2), rows - 1);  // rows past the end repeat the last one
-        kreg[h][i] = *reinterpret_cast<const u32x4*>(Kc + int64_t(r) * RB + (p0 + h) * kPiece + (ln & 3) * 16);
-      }
+    for (int i = 0; i < 8; ++i) {
+      const int r = min(i * 8 + (ln >> 3), rows - 1);  // rows past the end repeat the last one
+      kreg[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(Kc + int64_t(r) * RB + p0 * kPiece + (ln & 7) * 16));
+    }
   };
   const int sub0 = grp * kGroup * (kChunk / kSub) + w;
 #pragma unroll
@@ -552,7 +555,7 @@ __global__ __launch_bounds__(256) void decode_attend(DecodeArgs a, OT* __restric
 #pragma unroll
       for (int i = 0; i < VQ; ++i) {
         const int r = min((q * VQ + i) * RPI + tr, rows - 1);  // repeated rows meet a zero probability
-        vbuf[set][i] = *reinterpret_cast<const VRaw*>(Vc + int64_t(r) * RB + tc * VB);
+        vbuf[set][i] = __builtin_nontemporal_load(reinterpret_cast<const VRaw*>(Vc + int64_t(r) * RB + tc * VB));
       }
     };
     // this lane's score-side loads ride along
@@ -571,9 +574,11 @@ __global__ __launch_bounds__(256) void decode_attend(DecodeArgs a, OT* __restric
       // order, so the piece hand-over needs compiler ordering only.
       __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
       __builtin_amdgcn_wave_barrier();
+      if (((ln >> 2) & 1) == (p & 1)) {  // the lanes that hold this piece's half of the lines
 #pragma unroll
-      for (int i = 0; i < 4; ++i)
-        *reinterpret_cast<u32x4*>(mine + (i * 16 + (ln >> 2)) * kPitch + (ln & 3) * 16) = kreg[p & 1][i];
+        for (int i = 0; i < 8; ++i)
+          *reinterpret_cast<u32x4*>(mine + (i * 8 + (ln >> 3)) * kPitch + (ln & 3) * 16) = kreg[i];
+      }
       __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
       __builtin_amdgcn_wave_barrier();
       if ((p & 1) && p + 1 < NP) load_pair(sub, rows, p + 1);
