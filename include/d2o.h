@@ -74,7 +74,7 @@ typedef struct {
                           /* this has its closing work (normaliser, score update, eviction   */
                           /* choice) split over several workgroups in two extra launches     */
                           /* instead of done by one.  0: chosen per launch (half a percent   */
-                          /* of the rows the launch streams, within [8192, 16384]).          */
+                          /* of the rows the launch streams, within [6144, 16384]).          */
                           /* Otherwise at least 256.  A tuning knob: events and scores do    */
                           /* not depend on it, outputs only in fp32 summation order.         */
   int32_t cache_fp8;      /* 1: the cache stores a K or V row as d codes of the 8-bit float   */

@@ -13,7 +13,7 @@ namespace d2o {
 
 constexpr int kPartRecDoubles = 32;  // doubles of a part record of the split closing kernels
 constexpr int kMaxQuerySlices = 16;  // block append: workgroups that share the queries of a (head, chunk)
-constexpr int kMinAutoSplitRows = 8192, kMaxAutoSplitRows = 16384;  // bounds of the automatic split_rows
+constexpr int kMinAutoSplitRows = 6144, kMaxAutoSplitRows = 16384;  // bounds of the automatic split_rows (below the lower one the two extra launches cost more than a single closing workgroup)
 constexpr int kChunk = 256;        // cache slots handled by one workgroup in the decode kernels
 constexpr int kColBN = 256;        // keys per workgroup, column-sum pass (bf16)
 
