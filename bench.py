@@ -88,10 +88,11 @@ def run_step(ctx, w, Q, K, V, O, dq, dk, dv, dout, decode_steps):
     return ev[0].elapsed_time(ev[1]), ev[1].elapsed_time(ev[2]), budgets, F
 
 
-def cpu_baseline(w, decode_steps_sample=8):
-    """The fp64 oracle, as it stands, on a bounded sample of the same workload: one query
-    head of layer 0 (prefill attention + scores), the token-level stages of its KV head at the
-    mean budget, and a few decode steps on that head."""
+def cpu_baseline(w, heads_sample=3, decode_steps_sample=32):
+    """The fp64 oracle, as it stands, on a bounded sample of the same workload (about 10-15 s of
+    CPU work at configuration 3): for the first KV heads of layer 0, the prompt attention and
+    scores of one of their query heads, the token-level stages at the mean budget, and a few
+    decode steps; the mean times are scaled to the whole workload."""
     from oracle import d2o_ref as ref
     try:
         from threadpoolctl import threadpool_info
@@ -99,31 +100,37 @@ def cpu_baseline(w, decode_steps_sample=8):
     except Exception:
         cores = os.cpu_count() or 1
     n = w.prompt_len
-    Qh, Kh, Vh = synth.kv_head_inputs(w, 0, 0, 0, "cpu")
-    Qd, Kd, Vd = (binding.tensor_to_f64(t) for t in (Qh, Kh, Vh))
-    t0 = time.perf_counter()
-    o, s = ref.prefill_attention_head(Qd[0], Kd, Vd)
-    var = ref.head_variance(s)
-    t1 = time.perf_counter()
-    score = s * w.group
     budget = w.total_budget() // w.n_layers
-    cache, _ = ref.compress_head(Kd, Vd, score, budget, budget // 4, 0, w.dtype)
-    t2 = time.perf_counter()
-    q, k, v = synth.kv_head_decode_inputs(w, 0, 0, 0, decode_steps_sample, "cpu")
-    qd, kd, vd = (binding.tensor_to_f64(t) for t in (q, k, v))
-    for t in range(decode_steps_sample):
-        ref.decode_step_head(cache, qd[t], kd[t], vd[t], n + t, budget, budget // 4, 0, w.beta)
-    t3 = time.perf_counter()
-    attn_s, comp_s, dec_s = t1 - t0, t2 - t1, (t3 - t2) / decode_steps_sample
+    heads = list(range(min(heads_sample, w.n_kv_heads)))
+    attn_s = comp_s = dec_s = 0.0
+    for h in heads:
+        Qh, Kh, Vh = synth.kv_head_inputs(w, 0, 0, h, "cpu")
+        Qd, Kd, Vd = (binding.tensor_to_f64(t) for t in (Qh, Kh, Vh))
+        t0 = time.perf_counter()
+        o, s = ref.prefill_attention_head(Qd[0], Kd, Vd)
+        var = ref.head_variance(s)
+        t1 = time.perf_counter()
+        score = s * w.group
+        cache, _ = ref.compress_head(Kd, Vd, score, budget, budget // 4, 0, w.dtype)
+        t2 = time.perf_counter()
+        q, k, v = synth.kv_head_decode_inputs(w, 0, 0, h, decode_steps_sample, "cpu")
+        qd, kd, vd = (binding.tensor_to_f64(t) for t in (q, k, v))
+        t3 = time.perf_counter()
+        for t in range(decode_steps_sample):
+            ref.decode_step_head(cache, qd[t], kd[t], vd[t], n + t, budget, budget // 4, 0, w.beta)
+        t4 = time.perf_counter()
+        attn_s += (t1 - t0) / len(heads)
+        comp_s += (t2 - t1) / len(heads)
+        dec_s += (t4 - t3) / decode_steps_sample / len(heads)
     heads_q, heads_kv = w.n_q_heads * w.batch, w.n_kv_heads * w.batch
     prefill_ms_layer = (attn_s * heads_q + comp_s * heads_kv) * 1e3
     step_s = dec_s * heads_kv * w.n_layers
     return {
         "value": w.batch / step_s, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
         "prefill_compress_ms_per_layer": prefill_ms_layer,
-        "sample": (f"layer 0: attention+scores of 1 query head ({attn_s:.1f} s), token-level "
-                   f"stages of 1 KV head at budget {budget} ({comp_s:.1f} s), {decode_steps_sample} "
-                   f"decode steps of 1 KV head ({dec_s * 1e3:.1f} ms each); scaled by "
+        "sample": (f"layer 0, {len(heads)} KV heads: attention+scores of one query head each ({attn_s:.1f} s per "
+                   f"head), token-level stages at budget {budget} ({comp_s:.1f} s per head), {decode_steps_sample} "
+                   f"decode steps per head ({dec_s * 1e3:.1f} ms each); mean times scaled by "
                    f"{heads_q} query heads / {heads_kv} KV heads per layer and {w.n_layers} layers"),
     }
 
