@@ -6,7 +6,6 @@ missing or a call fails, an exception is raised."""
 from __future__ import annotations
 
 import ctypes as C
-import math
 import os
 
 import numpy as np

@@ -635,7 +635,6 @@ int d2o_append_chunk(d2o_ctx* x, int32_t layer, d2o_view Q, d2o_view K, d2o_view
   LayerState& st = x->layers[layer];
   if (st.phase != kReady) return fail(x, D2O_ERR_STATE, "layer not compressed");
   hipStream_t s = static_cast<hipStream_t>(stream);
-  const int es = x->esize, os = c.out_f32 ? 4 : x->esize;
   // ---- the block's rows appended, every token's attention over the cache and the block's earlier
   //      tokens, Eq. 6 for every token; no eviction inside the block
   {

@@ -209,7 +209,7 @@ __device__ __forceinline__ void head_tail(const DecodeArgs& a, OT* __restrict__ 
   constexpr int RG = 256 / C4;                        // groups of threads that share the sub-chunks
   constexpr int PB = 4;                               // partial rows in flight per thread
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
-  const int l = a.layer0 + li, last = total - 1;
+  const int last = total - 1;
   const int32_t* mt = a.meta + lbh * 4;
   const int64_t bh = int64_t(b) * a.Hkv + hk;
   const int64_t slot0 = bh * a.slots + mt[0];

@@ -2,7 +2,6 @@
 E4M3 codes with one power of two per row when they enter the cache and every read sees the
 decoded values.  Same bar as everywhere: positions, flags and cache rows identical, outputs
 within 2e-3."""
-import math
 
 import numpy as np
 import pytest

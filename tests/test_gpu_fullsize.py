@@ -14,7 +14,6 @@ three row ranges of the attention matrix per query head instead of all rows: the
 rows, the complete scores of the last columns, and - as the score vector that drives the
 token-level stages there - the column sums over the last row range; the invariant that a
 head's scores add up to G * N covers the rest."""
-import math
 
 import numpy as np
 import pytest
