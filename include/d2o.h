@@ -9,8 +9,9 @@
  * synchronising: d2o_create, d2o_reset, d2o_prefill_attend, d2o_compress_layer,
  * d2o_prefill_compress and d2o_decode_step only enqueue kernels and read no host memory after
  * they return; the calls that move data to or from host buffers (density, scores, cache,
- * events, timing) and d2o_layer_reserve wait for the stream and say so below.  Every function returns 0 on success or a negative d2o_status;
- * d2o_last_error() gives the message of the last failure on a context.
+ * events, timing) and d2o_layer_reserve wait for the stream and say so below.  Every
+ * function returns 0 on success or a negative d2o_status; d2o_last_error() gives the
+ * message of the last failure on a context.
  *
  * Pointer kinds: "device" = device memory, "host" = ordinary host memory.
  * Token identity across the ABI is the ORIGINAL TOKEN POSITION (prompt tokens 0..n-1,
