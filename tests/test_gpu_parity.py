@@ -977,10 +977,9 @@ def test_error_paths_return_codes():
 
 # ------------------------------------------------------------------ repeatability, non-finite inputs
 
-def _whole_path_once(w, n, budget, recent, steps, m, cache_fp8=False):
+def _whole_path_in(ctx, w, n, budget, recent, steps, m):
     """Prompt phase on the library's own scores, generation steps, a block: every result as bytes."""
     Q, K, V = H.make_inputs(w, 2, 5, n)
-    ctx = H.new_ctx(w, 2, 1, max(n, budget + m), budget + m + 8, max_append=m, cache_fp8=cache_fp8)
     O = torch.empty(Q.shape, dtype=ctx.out_dtype, device=Q.device)
     ctx.d2o_prefill_compress(0, Q, K, V, budget, recent, O)
     got = [O.cpu().numpy().tobytes(), ctx.d2o_scores_export(0, n).tobytes()]
@@ -999,7 +998,6 @@ def _whole_path_once(w, n, budget, recent, steps, m, cache_fp8=False):
         for h in range(w.n_kv_heads):
             gK, gV, gs, gp, gtau = ctx.d2o_cache_export(0, b, h, budget + m)
             got += [gK.tobytes(), gV.tobytes(), gs.tobytes(), gp.tobytes(), np.float64(gtau).tobytes()]
-    ctx.close()
     return got
 
 
@@ -1008,13 +1006,23 @@ def test_two_runs_give_the_same_bits(cache_fp8):
     """No result depends on the order in which workgroups run (no floating-point atomics, fixed
     summation trees, ordered merge sources): the whole path - attention outputs, scores,
     densities, every generation step's outputs and events, a block append, the final caches -
-    run twice in fresh contexts gives identical bytes."""
+    gives identical bytes when it is run again in a fresh context, and again in the first
+    context after d2o_reset (which therefore leaves nothing of the first run behind)."""
     w = _small_bf16(True)
-    first = _whole_path_once(w, 1500, 300, 60, 12, 40, cache_fp8)
-    second = _whole_path_once(w, 1500, 300, 60, 12, 40, cache_fp8)
-    assert len(first) == len(second)
-    for i, (a, b) in enumerate(zip(first, second)):
-        assert a == b, f"result {i} differs between the two runs"
+    n, budget, recent, steps, m = 1500, 300, 60, 12, 40
+    mk = lambda: H.new_ctx(w, 2, 1, max(n, budget + m), budget + m + 8, max_append=m, cache_fp8=cache_fp8)
+    ctx = mk()
+    first = _whole_path_in(ctx, w, n, budget, recent, steps, m)
+    ctx.d2o_reset()
+    again = _whole_path_in(ctx, w, n, budget, recent, steps, m)
+    ctx.close()
+    ctx = mk()
+    fresh = _whole_path_in(ctx, w, n, budget, recent, steps, m)
+    ctx.close()
+    assert len(first) == len(again) == len(fresh)
+    for i, (a, b, c) in enumerate(zip(first, again, fresh)):
+        assert a == b, f"result {i} differs after d2o_reset"
+        assert a == c, f"result {i} differs between two contexts"
 
 
 def test_non_finite_inputs_reach_the_density_and_the_budget_call_rejects_them():
