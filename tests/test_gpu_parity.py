@@ -484,6 +484,7 @@ def test_decode_evicted_token_outside_the_predicted_candidates():
         assert H.rownorm_err(binding.tensor_to_f64(out)[0, 0], want) <= H.FLOAT_TOL
         evicted.append(e.evicted_pos)
     assert evicted[0] == 0 and evicted[1] == 5, evicted   # the scenario really took the unpredicted token
+    assert ctx.d2o_candidate_misses() >= 1                # ... and the library counted the second pass over the keys
     gK, gV, gs, gp, gtau = ctx.d2o_cache_export(0, 0, 0, budget + 1)
     assert np.array_equal(gp, cache.pos) and np.array_equal(gK, cache.K) and np.array_equal(gV, cache.V)
     np.testing.assert_allclose(gs, cache.score, rtol=1e-12)
