@@ -32,7 +32,7 @@ SAMPLES = {
     4: ([5], [(0, 2), (15, 7), (9, 0)], None),
     5: ([30], [(0, 1), (0, 6)], "ranges"),
 }
-DECODE_STEPS = 3
+DECODE_STEPS = 16
 
 
 def _layer_on_device(w, layer, dev):
