@@ -762,9 +762,10 @@ def test_decode_all_layers_in_one_call_equals_one_call_per_layer():
         ctx.close()
 
 
-def _run_multi_layer_decode(w, n, layers, budgets, recents, steps, split_rows=0, cache_fp8=False):
-    """Several layers in one decode call per step, every head against the oracle at every step.
-    Returns the number of evictions per layer."""
+def _run_multi_layer_decode(w, n, layers, budgets, recents, steps, split_rows=0, cache_fp8=False, ranges=None):
+    """Several layers in one decode call per step (or in one call per range of layers, `ranges` =
+    [(first, count), ...]), every head against the oracle at every step.  Returns the number of
+    evictions per layer."""
     B, L = 1, len(layers)
     ctx = H.new_ctx(w, B, L, max([n] + [b + 1 for b in budgets]) if cache_fp8 else n, sum(budgets) + 8 * L,
                     split_rows=split_rows, cache_fp8=cache_fp8)
@@ -783,7 +784,8 @@ def _run_multi_layer_decode(w, n, layers, budgets, recents, steps, split_rows=0,
     out = torch.empty(q[0].shape, dtype=ctx.out_dtype, device=q.device)
     G, worst, evictions = w.group, 0.0, [0] * L
     for t in range(steps):
-        ctx.d2o_decode_step(0, L, q[t], k[t], v[t], out)
+        for (l0, nl) in (ranges or [(0, L)]):
+            ctx.d2o_decode_step(l0, nl, q[t][l0:l0 + nl], k[t][l0:l0 + nl], v[t][l0:l0 + nl], out[l0:l0 + nl])
         torch.cuda.synchronize()
         od = binding.tensor_to_f64(out)
         for li in range(L):
@@ -831,6 +833,15 @@ def test_decode_layers_of_very_different_sizes_in_one_call():
     w = _small_bf16(False).scaled(n_q_heads=2, n_kv_heads=2)
     ev = _run_multi_layer_decode(w, 12000, [2, 30, 17], [10500, 200, 3000], [2600, 50, 750], 5)
     assert ev == [10, 10, 10]
+
+
+def test_decode_in_calls_over_layer_ranges():
+    """A step issued as two calls, layers [0, 1) and [1, 4): the second range starts above layer 0
+    and holds layers of different sizes; every head against the oracle at every step."""
+    w = _small_bf16(True)
+    ev = _run_multi_layer_decode(w, 900, [7, 1, 19, 28], [300, 520, 64, 700], [75, 130, 16, 175], 6,
+                                 ranges=[(0, 1), (1, 3)])
+    assert ev == [6 * w.n_kv_heads] * 4
 
 
 def test_density_to_budgets_to_compress_free_running():
