@@ -989,23 +989,44 @@ def test_error_paths_return_codes():
 
 # ------------------------------------------------------------------ repeatability, non-finite inputs
 
-def _whole_path_in(ctx, w, n, budget, recent, steps, m):
-    """Prompt phase on the library's own scores, generation steps, a block: every result as bytes."""
-    Q, K, V = H.make_inputs(w, 2, 5, n)
-    O = torch.empty(Q.shape, dtype=ctx.out_dtype, device=Q.device)
+def _token_major(t):
+    """The same [b][head][token][d] values as a strided view of a [b][token][head][d + 8] buffer
+    (the layout a model's projection leaves them in, with padded rows)."""
+    B, Hh, n, d = t.shape
+    buf = torch.zeros((B, n, Hh, d + 8), dtype=t.dtype, device=t.device)
+    buf[..., :d] = t.permute(0, 2, 1, 3)
+    return buf[..., :d].permute(0, 2, 1, 3)
+
+
+def _padded_heads(t):
+    """[layers][b][head][d] values as a view with padded head and sequence strides."""
+    L, B, Hh, d = t.shape
+    buf = torch.zeros((L, B + 1, Hh + 1, d + 16), dtype=t.dtype, device=t.device)
+    buf[:, :B, :Hh, :d] = t
+    return buf[:, :B, :Hh, :d]
+
+
+def _whole_path_in(ctx, w, n, budget, recent, steps, m, strided=False):
+    """Prompt phase on the library's own scores, generation steps, a block: every result as bytes.
+    strided: every tensor handed to the library is a non-contiguous view."""
+    lay4 = _token_major if strided else (lambda x: x)
+    layd = _padded_heads if strided else (lambda x: x)
+    Q, K, V = (lay4(x) for x in H.make_inputs(w, 2, 5, n))
+    O = lay4(torch.empty(Q.shape, dtype=ctx.out_dtype, device=Q.device))
     ctx.d2o_prefill_compress(0, Q, K, V, budget, recent, O)
-    got = [O.cpu().numpy().tobytes(), ctx.d2o_scores_export(0, n).tobytes()]
+    raw = lambda x: x.contiguous().view(torch.uint8).cpu().numpy().tobytes()  # the values in logical order
+    got = [raw(O), ctx.d2o_scores_export(0, n).tobytes()]
     got += [a.tobytes() for a in ctx.d2o_get_density(heads=True)]
     q, k, v = H.decode_inputs(w, 2, [5], steps)
-    out = torch.empty(q[0].shape, dtype=ctx.out_dtype, device=q.device)
+    out = layd(torch.empty(q[0].shape, dtype=ctx.out_dtype, device=q.device))
     for t in range(steps):
-        ctx.d2o_decode_step(0, 1, q[t], k[t], v[t], out)
-        got.append(out.cpu().numpy().tobytes())
+        ctx.d2o_decode_step(0, 1, layd(q[t]), layd(k[t]), layd(v[t]), out)
+        got.append(raw(out))
         got += [a.tobytes() for a in ctx.d2o_last_events(0)]
-    Qb, Kb, Vb = _block_inputs(w, 2, 5, m, 1)
-    Ob = torch.empty(Qb.shape, dtype=ctx.out_dtype, device=Qb.device)
+    Qb, Kb, Vb = (lay4(x) for x in _block_inputs(w, 2, 5, m, 1))
+    Ob = lay4(torch.empty(Qb.shape, dtype=ctx.out_dtype, device=Qb.device))
     ctx.d2o_append_chunk(0, Qb, Kb, Vb, Ob)
-    got.append(Ob.cpu().numpy().tobytes())
+    got.append(raw(Ob))
     for b in range(2):
         for h in range(w.n_kv_heads):
             gK, gV, gs, gp, gtau = ctx.d2o_cache_export(0, b, h, budget + m)
@@ -1035,6 +1056,23 @@ def test_two_runs_give_the_same_bits(cache_fp8):
     for i, (a, b, c) in enumerate(zip(first, again, fresh)):
         assert a == b, f"result {i} differs after d2o_reset"
         assert a == c, f"result {i} differs between two contexts"
+
+
+def test_strided_views_give_the_same_bits_as_contiguous_tensors():
+    """Every tensor argument is a view with its own strides (d contiguous).  Prompt tensors as
+    views of token-major buffers with padded rows, generation-step tensors with padded head and
+    sequence strides, outputs written through such views: the whole path gives the bytes it
+    gives on contiguous tensors."""
+    w = _small_bf16(True)
+    n, budget, recent, steps, m = 700, 200, 40, 6, 24
+    results = []
+    for strided in (False, True):
+        ctx = H.new_ctx(w, 2, 1, max(n, budget + m), budget + m + 8, max_append=m, out_f32=False)
+        results.append(_whole_path_in(ctx, w, n, budget, recent, steps, m, strided=strided))
+        ctx.close()
+    assert len(results[0]) == len(results[1])
+    for i, (a, b) in enumerate(zip(*results)):
+        assert a == b, f"result {i} differs between contiguous and strided tensors"
 
 
 def test_non_finite_inputs_reach_the_density_and_the_budget_call_rejects_them():
