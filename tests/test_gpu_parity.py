@@ -318,7 +318,7 @@ def _run_decode_parity(w, n, B, layer, budget, recent, sink, steps, tau_force=fl
 
 @pytest.mark.parametrize("case", ["cfg1", "bf16-mha", "bf16-gqa-ragged-budgets", "bf16-grow",
                                   "bf16-no-window", "bf16-never-merge", "bf16-long", "bf16-gqa4",
-                                  "bf16-mha-many-rounds", "bf16-mha-256-steps"])
+                                  "bf16-mha-many-rounds", "bf16-mha-256-steps", "bf16-beta-0", "bf16-beta-0.95"])
 def test_decode_from_oracle_state(case):
     print(f"case={case}", flush=True)
     if case == "cfg1":
@@ -339,6 +339,8 @@ def test_decode_from_oracle_state(case):
     elif case == "bf16-mha-many-rounds":   # 4000 rows: sixteen workgroups per head
         _run_decode_parity(_small_bf16(False).scaled(n_q_heads=2, n_kv_heads=2), 6000, 1, 25, 4000, 1000, 0, 5,
                            random_scores=True)
+    elif case.startswith("bf16-beta-"):    # the ends of the range of the EMA constant of Eq. 10
+        _run_decode_parity(_small_bf16(True).scaled(beta=float(case[len("bf16-beta-"):])), 600, 1, 8, 150, 40, 0, 30)
     elif case == "bf16-mha-256-steps":     # three chunks per head, as many steps as configuration 1 generates
         _run_decode_parity(_small_bf16(False), 3000, 1, 11, 700, 150, 0, 256, random_scores=True)
     else:
