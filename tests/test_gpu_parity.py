@@ -32,7 +32,7 @@ def _small_bf16(gqa: bool):
 
 # ------------------------------------------------------------------ a1-a2: attention, scores, density
 
-@pytest.mark.parametrize("case", ["cfg1-f32", "bf16-mha-ragged", "bf16-gqa-ragged", "bf16-short"])
+@pytest.mark.parametrize("case", ["cfg1-f32", "bf16-mha-ragged", "bf16-gqa-ragged", "bf16-short", "bf16-gqa8", "f32-gqa4-d128"])
 def test_prefill_attention_scores_density(case):
     if case == "cfg1-f32":
         w, n, B, layer = W1, W1.prompt_len, 1, 0
@@ -40,6 +40,10 @@ def test_prefill_attention_scores_density(case):
         w, n, B, layer = _small_bf16(False), 1000, 1, 20
     elif case == "bf16-gqa-ragged":
         w, n, B, layer = _small_bf16(True), 777, 2, 9
+    elif case == "bf16-gqa8":       # the largest group size: eight query heads on one KV head
+        w, n, B, layer = W4.scaled(n_q_heads=16, n_kv_heads=2, n_clusters=16), 600, 1, 14
+    elif case == "f32-gqa4-d128":   # the fp32 kernels with grouped queries and head_dim 128
+        w, n, B, layer = W1.scaled(n_q_heads=8, n_kv_heads=2, head_dim=128), 333, 2, 1
     else:
         w, n, B, layer = _small_bf16(True), 50, 1, 3
     print(f"case={case} n={n} B={B}", flush=True)
