@@ -841,6 +841,16 @@ def test_decode_layers_of_very_different_sizes_in_one_call():
     assert ev == [10, 10, 10]
 
 
+def test_decode_more_layers_than_one_launch_takes():
+    """70 layers in one call (a launch's layer table holds 64: the call becomes two groups of
+    launches), budgets cycling through four sizes: every head against the oracle at every step."""
+    w = _small_bf16(True)
+    L = 70
+    budgets = [[48, 300, 64, 130][i % 4] for i in range(L)]
+    ev = _run_multi_layer_decode(w, 350, list(range(L)), budgets, [b // 4 for b in budgets], 3)
+    assert ev == [3 * w.n_kv_heads] * L
+
+
 def test_decode_in_calls_over_layer_ranges():
     """A step issued as two calls, layers [0, 1) and [1, 4): the second range starts above layer 0
     and holds layers of different sizes; every head against the oracle at every step."""
