@@ -8,9 +8,9 @@
 // operands of v_mfma_f32_32x32x16_bf16 want (lane l: row l % 32, eight consecutive k from
 // 8 * (l / 32)).
 //
-// A workgroup (4 wavefronts) computes 256 tokens x 128 features = one head; a wavefront owns 64
-// tokens x 128 features (2 x 4 accumulator blocks: six LDS operand reads feed eight matrix
-// instructions).  The feature pair (c, c + 64) that the rotary embedding mixes lives in the same
+// A workgroup (8 wavefronts) computes 256 tokens x 256 features = two heads; a wavefront owns 64
+// tokens x one head's 128 features (2 x 4 accumulator blocks: six LDS operand reads feed eight
+// matrix instructions).  The feature pair (c, c + 64) that the rotary embedding mixes lives in the same
 // lane and register of accumulator blocks j and j + 2, so the rotation needs no exchange.  The
 // rotated tile goes through LDS once so that every lane stores 16 contiguous bytes of a token's
 // head vector.
@@ -22,14 +22,15 @@
 namespace d2o {
 namespace {
 
-constexpr int kBM = 256, kBN = 128, kBK = 32;
+constexpr int kBM = 256, kBN = 128, kBK = 32;  // kBN: one head; a workgroup's tile holds kHeadsPerWg of them
+constexpr int kHeadsPerWg = 2, kThreads = 512;
 constexpr int kLd = kBK;                     // LDS pitch (elements) of the operand tiles: 64 bytes = four 16-byte chunks,
                                              // chunk k of row r stored at position k ^ ((r >> 2) & 3): the 16 lanes of a
                                              // 128-bit access phase then cover all 64 banks once, for the staging stores
                                              // (four consecutive rows x four chunks) and for the operand reads (sixteen
                                              // consecutive rows, one chunk)
 constexpr int kLdC = kBN + 8;                // LDS pitch of the result tile
-constexpr int kOperandElems = 2 * (kBM + kBN) * kLd;  // two stages
+constexpr int kOperandElems = 2 * (kBM + kHeadsPerWg * kBN) * kLd;  // two stages
 constexpr int kResultElems = kBM / 2 * kLdC;          // the result tile passes through LDS in two halves
 constexpr int kSmemElems = kOperandElems > kResultElems ? kOperandElems : kResultElems;
 
@@ -41,24 +42,30 @@ struct QkvArgs {
   double log2_base;
 };
 
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void qkv_rope_bf16(QkvArgs a) {
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(2, 2))) void qkv_rope_bf16(QkvArgs a) {
   __shared__ __attribute__((aligned(16))) uint16_t smem[kSmemElems];
   const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, m = lane & 31, h = lane >> 5;
   // Workgroups go to the eight XCDs round-robin in launch order.  Each XCD takes one eighth of
   // the heads (its slice of W stays close to it) and walks the token tiles with its heads as
   // the fast index, so the workgroups that run together share a few token tiles and that slice.
-  int ft = blockIdx.x;  // feature tile = head index over [Q heads | K heads | V heads]
-  int rt = blockIdx.y;  // token tile
+  int ftile = blockIdx.x;  // feature tile = a pair of heads out of [Q heads | K heads | V heads]
+  int rt = blockIdx.y;     // token tile
   if (gridDim.x % 8 == 0) {
     const int lin = blockIdx.x + gridDim.x * blockIdx.y, xcd = lin & 7, s_ = lin >> 3, fpx = gridDim.x / 8;
-    ft = xcd * fpx + s_ % fpx;
+    ftile = xcd * fpx + s_ % fpx;
     rt = s_ / fpx;
   }
+  const int nheads = a.Hq + 2 * a.Hkv;
+  const int wm = w & 3, wn = w >> 2;      // the wavefront's 64 tokens, and which head of the pair
+  const int ft = ftile * kHeadsPerWg + wn;  // this wavefront's head (an odd head count leaves the last tile's second half idle)
+  const bool live = ft < nheads;
   const int row0 = rt * kBM;  // first token (flattened over sequences) of the tile
   const uint16_t* Xb = a.X;
-  const uint16_t* Wb = a.W + int64_t(ft) * kBN * a.hidden;
-  auto As = [&](int st) { return smem + st * (kBM + kBN) * kLd; };
-  auto Bs = [&](int st) { return smem + st * (kBM + kBN) * kLd + kBM * kLd; };
+  const uint16_t* Wb = a.W + int64_t(ftile) * kHeadsPerWg * kBN * a.hidden;
+  const int wrows = min(kHeadsPerWg * kBN, (nheads - ftile * kHeadsPerWg) * kBN);  // weight rows this tile has
+  constexpr int kStageElems = (kBM + kHeadsPerWg * kBN) * kLd;
+  auto As = [&](int st) { return smem + st * kStageElems; };
+  auto Bs = [&](int st) { return smem + st * kStageElems + kBM * kLd; };
 
   f32x16 acc[2][4];
 #pragma unroll
@@ -74,31 +81,32 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
   // iterations (and the other resident workgroup's) to arrive; one iteration is shorter than
   // an L2 round trip under load.
   auto swz = [](int row, int col) { return col ^ (((row >> 2) & 3) << 3); };  // col: element offset of a 16-byte chunk
+  constexpr int NA = kBM * 4 / kThreads, NB = kHeadsPerWg * kBN * 4 / kThreads;  // 16-byte chunks per thread
   struct Regs {
-    u32x4 a[4], b[2];
+    u32x4 a[NA], b[NB];
   } R0, R1;
   auto issue = [&](int kt, Regs& R) {
     const int k0 = kt * kBK;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int c = tid + 256 * i, row = c >> 2, col = (c & 3) * 8;
+    for (int i = 0; i < NA; ++i) {
+      const int c = tid + kThreads * i, row = c >> 2, col = (c & 3) * 8;
       R.a[i] = *reinterpret_cast<const u32x4*>(Xb + int64_t(min(row0 + row, a.M - 1)) * a.hidden + k0 + col);
     }
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
-      const int c = tid + 256 * i, row = c >> 2, col = (c & 3) * 8;
-      R.b[i] = *reinterpret_cast<const u32x4*>(Wb + int64_t(row) * a.hidden + k0 + col);
+    for (int i = 0; i < NB; ++i) {
+      const int c = tid + kThreads * i, row = c >> 2, col = (c & 3) * 8;
+      R.b[i] = *reinterpret_cast<const u32x4*>(Wb + int64_t(min(row, wrows - 1)) * a.hidden + k0 + col);
     }
   };
   auto stage = [&](int st, const Regs& R) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int c = tid + 256 * i, row = c >> 2, col = (c & 3) * 8;
+    for (int i = 0; i < NA; ++i) {
+      const int c = tid + kThreads * i, row = c >> 2, col = (c & 3) * 8;
       *reinterpret_cast<u32x4*>(As(st) + row * kLd + swz(row, col)) = R.a[i];
     }
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
-      const int c = tid + 256 * i, row = c >> 2, col = (c & 3) * 8;
+    for (int i = 0; i < NB; ++i) {
+      const int c = tid + kThreads * i, row = c >> 2, col = (c & 3) * 8;
       *reinterpret_cast<u32x4*>(Bs(st) + row * kLd + swz(row, col)) = R.b[i];
     }
   };
@@ -109,10 +117,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     for (int ks = 0; ks < kBK / 16; ++ks) {
 #pragma unroll
       for (int i = 0; i < 2; ++i)
-        av[ks][i] = *reinterpret_cast<const bf16x8*>(As(st) + (w * 64 + i * 32 + m) * kLd + swz(m, ks * 16 + h * 8));
+        av[ks][i] = *reinterpret_cast<const bf16x8*>(As(st) + (wm * 64 + i * 32 + m) * kLd + swz(m, ks * 16 + h * 8));
 #pragma unroll
       for (int j = 0; j < 4; ++j)
-        bv[ks][j] = *reinterpret_cast<const bf16x8*>(Bs(st) + (j * 32 + m) * kLd + swz(m, ks * 16 + h * 8));
+        bv[ks][j] = *reinterpret_cast<const bf16x8*>(Bs(st) + (wn * kBN + j * 32 + m) * kLd + swz(m, ks * 16 + h * 8));
     }
 #pragma unroll
     for (int ks = 0; ks < kBK / 16; ++ks)
@@ -141,9 +149,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     __syncthreads();
   }
   // ---- rotary embedding on queries and keys.  Accumulator layout: acc[i][j][r] is token
-  //      w*64 + i*32 + (r/4)*8 + 4h + r%4 of the tile, feature j*32 + m.  Features c < 64 pair with
+  //      wm*64 + i*32 + (r/4)*8 + 4h + r%4 of the tile, feature j*32 + m of the wavefront's head.  Features c < 64 pair with
   //      c + 64: blocks (0, 2) and (1, 3) of the same lane and register.
-  const bool rotate = ft < a.Hq + a.Hkv;
+  const bool rotate = live && ft < a.Hq + a.Hkv;
   if (rotate) {
 #pragma unroll
     for (int j = 0; j < 2; ++j) {
@@ -154,7 +162,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
       for (int i = 0; i < 2; ++i)
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-          const int t = row0 + w * 64 + i * 32 + (r >> 2) * 8 + h * 4 + (r & 3);
+          const int t = row0 + wm * 64 + i * 32 + (r >> 2) * 8 + h * 4 + (r & 3);
           const int pos = a.pos0 + (t % a.n);
           // the angle in fp64, reduced to a fraction of a turn before the fp32 sine and cosine
           // (positions reach 10^5: an fp32 product would be off by a hundredth of a radian); the
@@ -168,42 +176,46 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
         }
     }
   }
-  // which tensor and head this tile is
-  View dst = a.q;
-  int head = ft;
-  if (ft >= a.Hq + a.Hkv) {
-    dst = a.v;
-    head = ft - a.Hq - a.Hkv;
-  } else if (ft >= a.Hq) {
-    dst = a.k;
-    head = ft - a.Hq;
-  }
-  uint16_t* out = static_cast<uint16_t*>(dst.ptr);
   // ---- through LDS (the operand tiles are no longer needed; the loop's last barrier has passed),
-  //      128 tokens at a time: [token][feature] in bf16, then 16 contiguous bytes per lane
+  //      one head and 128 tokens at a time: [token][feature] in bf16, then 16 contiguous bytes per lane
   uint16_t* Cs = smem;
-#pragma unroll
-  for (int half = 0; half < 2; ++half) {
-    if ((w >> 1) == half) {
+#pragma unroll 1
+  for (int pass = 0; pass < 2 * kHeadsPerWg; ++pass) {
+    const int half = pass & 1, hsel = pass >> 1;
+    if (wn == hsel && (wm >> 1) == half) {
 #pragma unroll
       for (int i = 0; i < 2; ++i)
 #pragma unroll
         for (int j = 0; j < 4; ++j)
 #pragma unroll
           for (int r = 0; r < 16; ++r) {
-            const int row = (w & 1) * 64 + i * 32 + (r >> 2) * 8 + h * 4 + (r & 3);
+            const int row = (wm & 1) * 64 + i * 32 + (r >> 2) * 8 + h * 4 + (r & 3);
             Cs[row * kLdC + j * 32 + m] = Elem<uint16_t>::from_f32(acc[i][j][r]);
           }
     }
     __syncthreads();
+    // which tensor and head this pass writes
+    const int fh = ftile * kHeadsPerWg + hsel;
+    if (fh < nheads) {
+      View dst = a.q;
+      int head = fh;
+      if (fh >= a.Hq + a.Hkv) {
+        dst = a.v;
+        head = fh - a.Hq - a.Hkv;
+      } else if (fh >= a.Hq) {
+        dst = a.k;
+        head = fh - a.Hq;
+      }
+      uint16_t* out = static_cast<uint16_t*>(dst.ptr);
 #pragma unroll
-    for (int i = 0; i < kBM / 2 * kBN / 8 / 256; ++i) {
-      const int c = tid + 256 * i, row = c >> 4, col = (c & 15) * 8;
-      const int t = row0 + half * (kBM / 2) + row;
-      if (t < a.M) {
-        const int b = t / a.n, tok = t % a.n;
-        *reinterpret_cast<u32x4*>(out + b * dst.sb + head * dst.sh + int64_t(tok) * dst.sn + col) =
-            *reinterpret_cast<const u32x4*>(Cs + row * kLdC + col);
+      for (int i = 0; i < kBM / 2 * kBN / 8 / kThreads; ++i) {
+        const int c = tid + kThreads * i, row = c >> 4, col = (c & 15) * 8;
+        const int t = row0 + half * (kBM / 2) + row;
+        if (t < a.M) {
+          const int b = t / a.n, tok = t % a.n;
+          *reinterpret_cast<u32x4*>(out + b * dst.sb + head * dst.sh + int64_t(tok) * dst.sn + col) =
+              *reinterpret_cast<const u32x4*>(Cs + row * kLdC + col);
+        }
       }
     }
     __syncthreads();
@@ -243,7 +255,7 @@ extern "C" int d2o_qkv_project(int32_t batch, int32_t n, int32_t hidden, int32_t
   a.Hkv = n_kv_heads;
   a.pos0 = pos0;
   a.log2_base = std::log2(rope_base);
-  const dim3 grid(n_q_heads + 2 * n_kv_heads, (a.M + kBM - 1) / kBM);
-  qkv_rope_bf16<<<grid, 256, 0, static_cast<hipStream_t>(stream)>>>(a);
+  const dim3 grid((n_q_heads + 2 * n_kv_heads + kHeadsPerWg - 1) / kHeadsPerWg, (a.M + kBM - 1) / kBM);
+  qkv_rope_bf16<<<grid, kThreads, 0, static_cast<hipStream_t>(stream)>>>(a);
   return hipGetLastError() == hipSuccess ? D2O_OK : D2O_ERR_HIP;
 }
