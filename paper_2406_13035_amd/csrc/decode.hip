@@ -239,13 +239,33 @@ __device__ __forceinline__ void head_tail(const DecodeArgs& a, OT* __restrict__ 
   double* em = reinterpret_cast<double*>(park);  // [nsub][G]
   const bool em_lds = nsub * G <= kEmCap;
   double Mg[G], Lg[G];
+  // The record of sub-chunk `tid` (the only one of this thread unless the head has more than 256
+  // sub-chunks) is read once, whole, and kept: the sweeps below then cost one memory round trip
+  // instead of three.
+  double own_m[G], own_l[G], own_u[kCand];
+  int own_s[kCand];
   {
 #pragma unroll
     for (int g = 0; g < G; ++g) Mg[g] = -INFINITY;
     for (int c = tid; c < nsub; c += 256) {
       const int64_t x = sub_index(a, bh, ch0, c) * kRec;
+      if (c == tid) {
 #pragma unroll
-      for (int g = 0; g < G; ++g) Mg[g] = fmax(Mg[g], ld_agent(&a.rec[x + g]));
+        for (int g = 0; g < G; ++g) {
+          own_m[g] = ld_agent(&a.rec[x + g]);
+          own_l[g] = ld_agent(&a.rec[x + G + g]);
+        }
+#pragma unroll
+        for (int i = 0; i < kCand; ++i) {
+          own_u[i] = ld_agent(&a.rec[x + 2 * G + i]);
+          own_s[i] = int(ld_agent(&a.rec[x + 2 * G + kCand + i]));
+        }
+#pragma unroll
+        for (int g = 0; g < G; ++g) Mg[g] = fmax(Mg[g], own_m[g]);
+      } else {
+#pragma unroll
+        for (int g = 0; g < G; ++g) Mg[g] = fmax(Mg[g], ld_agent(&a.rec[x + g]));
+      }
     }
 #pragma unroll
     for (int g = 0; g < G; ++g) Mg[g] = wave_max(Mg[g]);
@@ -264,8 +284,8 @@ __device__ __forceinline__ void head_tail(const DecodeArgs& a, OT* __restrict__ 
       const int64_t x = sub_index(a, bh, ch0, c) * kRec;
 #pragma unroll
       for (int g = 0; g < G; ++g) {
-        const double t = exp(ld_agent(&a.rec[x + g]) - Mg[g]);
-        part[g] += ld_agent(&a.rec[x + G + g]) * t;
+        const double t = exp((c == tid ? own_m[g] : ld_agent(&a.rec[x + g])) - Mg[g]);
+        part[g] += (c == tid ? own_l[g] : ld_agent(&a.rec[x + G + g])) * t;
         if (em_lds)
           em[c * G + g] = t;
         else
@@ -294,9 +314,9 @@ __device__ __forceinline__ void head_tail(const DecodeArgs& a, OT* __restrict__ 
     const int64_t x = sub_index(a, bh, ch0, c) * kRec;
 #pragma unroll
     for (int i = 0; i < kCand; ++i) {
-      const int s = int(ld_agent(&a.rec[x + 2 * G + kCand + i]));
+      const int s = c == tid ? own_s[i] : int(ld_agent(&a.rec[x + 2 * G + kCand + i]));
       if (s >= 0) {
-        const double u = ld_agent(&a.rec[x + 2 * G + i]);
+        const double u = c == tid ? own_u[i] : ld_agent(&a.rec[x + 2 * G + i]);
         const int p = a.cpos[slot0 + s];
         if (better_match(u, p, s, cm[i])) cm[i] = Best{u, p, s};
       }
