@@ -57,6 +57,28 @@ __device__ __forceinline__ void block_scan2(bool fa, bool fb, int& ex_a, int& ex
   tot_b = tb;
 }
 
+// Exclusive prefix sums of one integer per thread over the block, in thread order, and the
+// block total (read by all threads).
+__device__ __forceinline__ void block_scan_int(int v, int& ex, int& tot, int* wa) {
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, nw = blockDim.x >> 6;
+  int inc = v;
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const int t = __shfl_up(inc, o, 64);
+    if (lane >= o) inc += t;
+  }
+  __syncthreads();
+  if (lane == 63) wa[w] = inc;
+  __syncthreads();
+  int off = 0, total = 0;
+  for (int i = 0; i < nw; ++i) {
+    if (i < w) off += wa[i];
+    total += wa[i];
+  }
+  ex = off + inc - v;
+  tot = total;
+}
+
 // S: score type (fp32 column sums after prompt encoding; fp64 cumulative scores of a cache that a
 // block of tokens was appended to).  nvec, when given, holds the number of entries per head.
 template <typename S>
@@ -67,7 +89,7 @@ __global__ __launch_bounds__(1024) void select_kernel(const S* __restrict__ scor
   typedef decltype(order_key(S())) Key;
   constexpr int kTopShift = int(sizeof(Key)) * 8 - 8;
   __shared__ int hist[256];
-  __shared__ int wa[16], wb[16];
+  __shared__ int wa[16];
   __shared__ Key sh_prefix;
   __shared__ int sh_need;
   const int hk = blockIdx.x, b = blockIdx.y, Hkv = gridDim.x;
@@ -139,30 +161,55 @@ __global__ __launch_bounds__(1024) void select_kernel(const S* __restrict__ scor
       __syncthreads();
     }
   }
-  // prefix = threshold key; `need` of the keys equal to it are kept, lowest positions first
+  // prefix = threshold key; `need` of the keys equal to it are kept, lowest positions first.
+  // Ordered compaction, four consecutive positions per thread and round: two block-wide scans
+  // (ties, then kept entries) per 4096 positions.
+  constexpr int PT = 4;
   int base_keep = 0, base_eq = 0;
-  for (int j0 = 0; j0 < n; j0 += blockDim.x) {
-    const int j = j0 + tid;
-    bool keep = false, eq = false;
-    if (j < n) {
-      if (j < lo || j >= hi) {
-        keep = true;
-      } else if (nhh > 0) {
-        const Key k = order_key(sc[j]);
-        keep = k > prefix;
-        eq = k == prefix;
+  for (int j0 = 0; j0 < n; j0 += PT * blockDim.x) {
+    const int jt = j0 + PT * tid;
+    bool keep[PT], eq[PT];
+    int neq = 0;
+#pragma unroll
+    for (int u = 0; u < PT; ++u) {
+      const int j = jt + u;
+      keep[u] = false;
+      eq[u] = false;
+      if (j < n) {
+        if (j < lo || j >= hi) {
+          keep[u] = true;
+        } else if (nhh > 0) {
+          const Key k = order_key(sc[j]);
+          keep[u] = k > prefix;
+          eq[u] = k == prefix;
+        }
       }
+      neq += eq[u] ? 1 : 0;
     }
-    int ex_eq, ex_dummy, tot_eq, tot_dummy;
-    block_scan2(eq, false, ex_eq, ex_dummy, tot_eq, tot_dummy, wa, wb);
-    if (eq && base_eq + ex_eq < need) keep = true;
+    int ex_eq, tot_eq;
+    block_scan_int(neq, ex_eq, tot_eq, wa);
+    int nkeep = 0, seen_eq = base_eq + ex_eq;
+#pragma unroll
+    for (int u = 0; u < PT; ++u) {
+      if (eq[u]) {
+        if (seen_eq < need) keep[u] = true;
+        ++seen_eq;
+      }
+      nkeep += keep[u] ? 1 : 0;
+    }
     int ex_keep, tot_keep;
-    block_scan2(keep, false, ex_keep, ex_dummy, tot_keep, tot_dummy, wa, wb);
-    if (j < n) {
-      if (keep)
-        r[base_keep + ex_keep] = j;
-      else
-        e[j - (base_keep + ex_keep)] = j;
+    block_scan_int(nkeep, ex_keep, tot_keep, wa);
+    int kept = base_keep + ex_keep;  // kept entries before position jt + u
+#pragma unroll
+    for (int u = 0; u < PT; ++u) {
+      const int j = jt + u;
+      if (j < n) {
+        if (keep[u])
+          r[kept] = j;
+        else
+          e[j - kept] = j;
+      }
+      kept += keep[u] ? 1 : 0;
     }
     base_keep += tot_keep;
     base_eq += tot_eq;
